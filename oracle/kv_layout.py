@@ -1,0 +1,80 @@
+"""Where a token's K row and V row live in a layer's KV pool (oracle side).
+
+TEST INFRASTRUCTURE ONLY; shares no code with the HIP library.
+
+The KV cache holds, per layer, one key row and one value row of `d` fp16
+numbers per sequence, per token, per KV head (paper §II-A: keys and values of
+every processed token are kept for reuse by the decode stage).  The library
+fixes two pool layouts, both row-major, written here from their description:
+
+  contiguous  pool[b][kv][g][tok][d]     b < B, tok < C (capacity in tokens)
+  paged       pool[blk][kv][g][slot][d]  blk < n_blocks, slot < T
+              token i of sequence b lives in block block_table[b][i // T],
+              slot i % T
+
+kv = 0 selects keys, kv = 1 selects values.  Offsets are in ELEMENTS (fp16),
+not bytes.
+"""
+import numpy as np
+
+
+def contiguous_row_offset(b, kv, g, tok, G, C, d):
+    """Element offset of row (b, kv, g, tok) in a contiguous pool."""
+    assert 0 <= kv < 2 and 0 <= g < G and 0 <= tok < C
+    return (((b * 2 + kv) * G + g) * C + tok) * d
+
+
+def paged_row_offset(blk, kv, g, slot, G, T, d):
+    """Element offset of row (blk, kv, g, slot) in a paged pool."""
+    assert blk >= 0, "token maps to an unallocated block"
+    assert 0 <= kv < 2 and 0 <= g < G and 0 <= slot < T
+    return (((blk * 2 + kv) * G + g) * T + slot) * d
+
+
+def token_row_offset(layout, b, kv, g, tok):
+    """Element offset of token `tok` of sequence `b` under `layout`.
+
+    layout: dict with keys G, d and either
+      {"kind": "contiguous", "C": capacity}
+      {"kind": "paged", "T": block tokens, "block_table": int array [B][max_blocks]}
+    """
+    G, d = layout["G"], layout["d"]
+    if layout["kind"] == "contiguous":
+        return contiguous_row_offset(b, kv, g, tok, G, layout["C"], d)
+    T = layout["T"]
+    blk = int(layout["block_table"][b][tok // T])
+    return paged_row_offset(blk, kv, g, tok % T, G, T, d)
+
+
+def gather_rows(pool_flat, layout, b, kv, g, n):
+    """Rows 0..n-1 of (b, kv, g) as an [n, d] array of the pool's dtype.
+
+    pool_flat is the layer's pool viewed as a flat 1-D array of fp16 (or of
+    raw uint16 bit patterns); one row is copied per token, no arithmetic.
+    """
+    d = layout["d"]
+    out = np.empty((n, d), dtype=pool_flat.dtype)
+    for i in range(n):
+        off = token_row_offset(layout, b, kv, g, i)
+        out[i] = pool_flat[off:off + d]
+    return out
+
+
+def append_scatter(pool_flat, layout, ctx_lens_after, k_new, v_new):
+    """What one append does to a layer's pool, in place.
+
+    ctx_lens_after[b] is the number of tokens sequence b holds once this
+    step's token is stored, so the new rows go to position ctx_lens_after[b]-1.
+    k_new, v_new: [B][G][d] arrays of the pool's dtype (bit copy, no rounding).
+    """
+    G, d = layout["G"], layout["d"]
+    B = len(ctx_lens_after)
+    for b in range(B):
+        pos = int(ctx_lens_after[b]) - 1
+        assert pos >= 0
+        for g in range(G):
+            ok = token_row_offset(layout, b, 0, g, pos)
+            ov = token_row_offset(layout, b, 1, g, pos)
+            pool_flat[ok:ok + d] = k_new[b, g]
+            pool_flat[ov:ov + d] = v_new[b, g]
+    return pool_flat

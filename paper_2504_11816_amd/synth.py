@@ -1,0 +1,123 @@
+"""Seeded synthetic inputs: shapes and value distributions of the workloads.
+
+This module holds none of the method's arithmetic.  It only draws numbers:
+fp16 N(0,1) tensors for q / K / V, a shuffled block table, ragged context
+lengths, and the table of workload shapes.  Both the tests' CPU oracle and
+the GPU path are fed from here, so they see the same bytes.
+
+The paper's workloads are fixed token-length patterns (online: 128 prompt /
+512 generated; offline: 1024 prompt / 128 generated, §VI-A) run on OPT
+models; the shapes below keep the OPT-6.7B-like stack (32 layers, 32 heads of
+128) and scale batch and context to a 288 GB GPU.
+"""
+import numpy as np
+
+_MASK64 = (1 << 64) - 1
+
+
+def stream_seed(seed, tensor_id, layer=0, step=0):
+    """A distinct 63-bit seed per (run seed, tensor, layer, step).
+
+    splitmix64-style mixing of the four integers; any fixed bijective mixing
+    would do, the point is that no two tensors share a random stream.
+    """
+    x = (seed * 0x9E3779B97F4A7C15 + tensor_id * 0xBF58476D1CE4E5B9
+         + layer * 0x94D049BB133111EB + step * 0xD6E8FEB86659FD93 + 0x2545F4914F6CDD1D) & _MASK64
+    x ^= x >> 30
+    x = (x * 0xBF58476D1CE4E5B9) & _MASK64
+    x ^= x >> 27
+    x = (x * 0x94D049BB133111EB) & _MASK64
+    x ^= x >> 31
+    return x & ((1 << 63) - 1)
+
+
+TENSOR_K, TENSOR_V, TENSOR_Q, TENSOR_KNEW, TENSOR_VNEW, TENSOR_POOL = 1, 2, 3, 4, 5, 6
+
+
+def randn_f16_numpy(shape, seed):
+    """N(0,1) rounded to fp16, on the host (numpy Generator, PCG64)."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    return rng.standard_normal(size=shape, dtype=np.float32).astype(np.float16)
+
+
+def randn_f16_torch(shape, seed, device):
+    """N(0,1) rounded to fp16 as a torch tensor on `device` (its own generator)."""
+    import torch
+    gen = torch.Generator(device=device)
+    gen.manual_seed(seed)
+    return torch.randn(shape, generator=gen, device=device, dtype=torch.float32).to(torch.float16)
+
+
+def fill_randn_f16_(tensor, seed, chunk_elems=1 << 28):
+    """Fill an existing fp16 torch tensor (device or pinned host) with N(0,1),
+    chunk by chunk so that no fp32 copy of the whole tensor is ever alive."""
+    import torch
+    flat = tensor.view(-1)
+    dev = flat.device
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(seed)
+    n = flat.numel()
+    for lo in range(0, n, chunk_elems):
+        hi = min(n, lo + chunk_elems)
+        flat[lo:hi] = torch.randn(hi - lo, generator=gen, device=dev, dtype=torch.float32).to(torch.float16)
+    return tensor
+
+
+def ragged_ctx_lens(B, lo, hi, seed):
+    """B integers uniform in [lo, hi], both ends included."""
+    rng = np.random.Generator(np.random.PCG64(seed))
+    return rng.integers(lo, hi + 1, size=B, dtype=np.int64).astype(np.int32)
+
+
+def blocks_needed(ctx_cap, T):
+    return (int(ctx_cap) + T - 1) // T
+
+
+def shuffled_block_table(ctx_caps, T, blocks_per_layer, seed, max_blocks_per_seq=None):
+    """A seeded random permutation of [0, blocks_per_layer) dealt to the
+    sequences in order (sequence 0 first), enough blocks for each sequence's
+    capacity ctx_caps[b]; unused entries are -1.  Returns int32 [B][max_blocks].
+    """
+    need = [blocks_needed(c, T) for c in ctx_caps]
+    if max_blocks_per_seq is None:
+        max_blocks_per_seq = max(need)
+    if sum(need) > blocks_per_layer:
+        raise ValueError("pool too small for the requested capacities")
+    rng = np.random.Generator(np.random.PCG64(seed))
+    perm = rng.permutation(blocks_per_layer).astype(np.int32)
+    table = np.full((len(ctx_caps), max_blocks_per_seq), -1, dtype=np.int32)
+    at = 0
+    for b, k in enumerate(need):
+        table[b, :k] = perm[at:at + k]
+        at += k
+    return table
+
+
+def identity_block_table(ctx_caps, T, max_blocks_per_seq=None):
+    """Blocks handed out in order, no shuffle (block b*k+i for sequence b)."""
+    need = [blocks_needed(c, T) for c in ctx_caps]
+    if max_blocks_per_seq is None:
+        max_blocks_per_seq = max(need)
+    table = np.full((len(ctx_caps), max_blocks_per_seq), -1, dtype=np.int32)
+    at = 0
+    for b, k in enumerate(need):
+        table[b, :k] = np.arange(at, at + k, dtype=np.int32)
+        at += k
+    return table
+
+
+# The five workload shapes.  "ctx" is the number of keys attended at the
+# first timed step (after that step's append); "steps" how many decode steps
+# the full workload runs; c_off as an exact fraction (numerator, denominator).
+WORKLOADS = {
+    "cfg1": dict(L=1, H=8, G=8, d=64, B=4, ctx=256, steps=1, T=0, c_off=(0, 1), ragged=None,
+                 note="single layer, all resident, latency only"),
+    "cfg2": dict(L=32, H=32, G=32, d=128, B=32, ctx=513, steps=512, T=0, c_off=(0, 1), ragged=None,
+                 note="6.7B-shaped MHA, prompt 512 + 512 generated, contiguous, resident"),
+    "cfg3": dict(L=32, H=32, G=32, d=128, B=64, ctx=2048, steps=8, T=16, c_off=(1, 2), ragged=None,
+                 note="paged, shuffled table, 50% of layers on host"),
+    "cfg4": dict(L=32, H=32, G=8, d=128, B=128, ctx=None, steps=20, T=16, c_off=(0, 1),
+                 ragged=(512, 4096), note="GQA 32/8, ragged contexts, paged, resident"),
+    "cfg5": dict(L=32, H=32, G=32, d=128, B=192, ctx=4096, steps=3, T=16, c_off=(3, 5), ragged=None,
+                 note="offline large batch, 60% of layers on host"),
+}
