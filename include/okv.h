@@ -1,0 +1,240 @@
+/*
+ * okv -- decode attention over a partly offloaded KV cache, for one MI355X (gfx950).
+ *
+ * The workload (paper §II-A, §II-B, §IV-C, §IV-D): in the decode stage every new
+ * token attends over the keys and values of all earlier tokens of its sequence,
+ * which are kept per layer in a KV cache.  When that cache does not fit in GPU
+ * memory a share C_off of it lives in host memory and is brought back to the
+ * GPU layer by layer, because attention runs on the GPU and therefore needs the
+ * layer's KV in GPU memory.  This library is that hot loop and nothing else:
+ *
+ *   kv_offload_plan   which layers live on the host for a given C_off
+ *   kv_append         store this step's K/V rows of one layer
+ *   decode_attn       softmax(q K^T / sqrt(d)) V of one layer for a batch
+ *
+ * plus the small amount of state around them (batch description, step
+ * bookkeeping, the copy pipeline for host layers).
+ *
+ * General conventions
+ *   - C ABI, no C++ or framework types.  Every pointer is labelled HOST or DEVICE.
+ *   - The caller owns every large buffer (KV pools, staging buffers, workspace,
+ *     q / k / v / out) and keeps it alive until okv_destroy; the library never
+ *     frees or reallocates them.  The library itself allocates only small
+ *     bookkeeping arrays (O(max_batch * max_blocks_per_seq) integers, a few events).
+ *   - Work is enqueued on the two streams given at creation and the calls return
+ *     without waiting for the GPU unless stated otherwise.  q / k_new / v_new / out
+ *     may be reused once the work enqueued on the compute stream has finished.
+ *   - Every function returns OKV_OK (0) or a negative OKV_E* code and never aborts
+ *     or throws.  okv_last_error gives a readable message for the last failure.
+ *   - A context is not thread-safe: one host thread drives it.
+ *
+ * KV pool layouts (fp16, row-major; kv = 0 keys, kv = 1 values; G = n_kv_heads,
+ * d = head_dim):
+ *   contiguous (block_tokens == 0):  pool[b][kv][g][tok][d]    b < max_batch, tok < max_ctx
+ *   paged      (block_tokens == T):  pool[blk][kv][g][slot][d] blk < blocks_per_layer, slot < T
+ *     token i of sequence b is in block block_table[b][i / T], slot i % T.
+ * In both, the K rows (and the V rows) of 16 consecutive tokens of one KV head
+ * are one contiguous run of 16 * d * 2 bytes.
+ */
+#ifndef OKV_H
+#define OKV_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define OKV_OK       0
+#define OKV_EINVAL  (-1)  /* bad argument: NULL, shape, range, empty context        */
+#define OKV_ENOSPC  (-2)  /* no room: block table / capacity / workspace / staging  */
+#define OKV_ESTATE  (-3)  /* call out of order                                      */
+#define OKV_EHIP    (-4)  /* a HIP runtime call failed; see okv_last_error          */
+
+typedef struct okv_ctx okv_ctx;   /* opaque */
+
+typedef struct okv_config {
+  int32_t n_layers;            /* L >= 1                                                     */
+  int32_t n_q_heads;           /* H; H % G == 0 and H / G in {1, 2, 4, 8}                    */
+  int32_t n_kv_heads;          /* G                                                          */
+  int32_t head_dim;            /* d in {64, 128}                                             */
+  int32_t block_tokens;        /* T: 0 = contiguous pools, else a power of two in [16, 1024] */
+  int32_t max_batch;           /* largest B okv_set_batch will see                           */
+  int32_t max_blocks_per_seq;  /* paged: columns of the block table; contiguous: ignored     */
+  int32_t max_ctx;             /* contiguous: capacity in tokens per sequence, multiple of 16;
+                                  paged: ignored (capacity is max_blocks_per_seq * T)        */
+  int64_t blocks_per_layer;    /* paged: blocks in each layer's pool; contiguous: ignored    */
+  int32_t out_dtype;           /* 0 = fp16 (round to nearest even), 1 = fp32                 */
+  int32_t split_tokens;        /* keys per split-K work item; 0 lets the library choose      */
+  void  **dev_pool;            /* HOST array [L] of DEVICE pointers: the pool of each layer
+                                  that stays in HBM, NULL for a layer kept on the host       */
+  void  **host_pool;           /* HOST array [L] of HOST pointers to PINNED, device-mapped
+                                  memory (hipHostMalloc): the pool of each host layer, NULL
+                                  for a resident layer.  Exactly one of dev_pool[l],
+                                  host_pool[l] is non-NULL.  May be NULL if no layer is on
+                                  the host.                                                   */
+  void   *staging[2];          /* DEVICE: buffers host layers are copied into, each at least
+                                  okv_layer_pool_bytes; staging[1] may be NULL (no overlap of
+                                  copy and compute then); both NULL if no layer is on the host */
+  int64_t staging_bytes;       /* size of each staging buffer                                */
+  void   *workspace;           /* DEVICE: split-K partial results                            */
+  int64_t workspace_bytes;     /* at least okv_workspace_bytes(cfg)                          */
+  void   *compute_stream;      /* hipStream_t for kernels (NULL = the default stream)        */
+  void   *h2d_stream;          /* hipStream_t for host-to-device copies; must differ from
+                                  compute_stream when any layer is on the host               */
+} okv_config;
+
+/* ---- sizes ------------------------------------------------------------------ */
+
+/* Bytes of one layer's pool under cfg (both layouts); < 0 on a bad cfg.  Only the
+ * shape fields of cfg are read.  This is the paper's Mem_KVcache,per_layer
+ * (Table II) for the pool's capacity. */
+int64_t okv_layer_pool_bytes(const okv_config *cfg);
+
+/* Bytes of workspace the split-K partials need in the worst case under cfg (every
+ * sequence at full capacity, the smallest split size the library would choose or
+ * cfg->split_tokens if set); < 0 on a bad cfg. */
+int64_t okv_workspace_bytes(const okv_config *cfg);
+
+/* ---- offload plan (pure host functions, no GPU, no context) ------------------- */
+
+/* Which layers live on the host for an offload ratio C_off = coff_num / coff_den
+ * (paper §IV-C, Case 3: C_off is the share of the KV cache that has to leave the
+ * GPU).  Whole layers are moved; their number is the smallest integer that is at
+ * least C_off * n_layers; they are spread evenly: on_host[l] = 1 exactly when
+ * floor((l+1) * n_off / n_layers) > floor(l * n_off / n_layers).
+ *   on_host  HOST out, [n_layers], 1 = host, 0 = HBM
+ *   n_off    HOST out, number of host layers (may be NULL)
+ * OKV_EINVAL unless n_layers >= 1, coff_den > 0 and 0 <= coff_num <= coff_den. */
+int kv_offload_plan(int32_t n_layers, int64_t coff_num, int64_t coff_den,
+                    uint8_t *on_host, int32_t *n_off);
+
+/* The same decision from memory sizes (paper §IV-C and Algorithm 1):
+ *   mem_avail_bytes >= n_layers * layer_bytes       -> Case 1, nothing moves
+ *   layer_bytes > mem_avail_bytes                   -> Case 2, OKV_ENOSPC
+ *   otherwise Case 3: staging buffers (two if two layers fit, else one) come out
+ *   of mem_avail_bytes, the layers that still fit stay resident, the rest go to
+ *   the host, placed as kv_offload_plan places them.  The share moved is never
+ *   below 1 - mem_avail / (n_layers * layer_bytes).
+ *   n_staging HOST out: 0, 1 or 2 (may be NULL). */
+int okv_plan_from_bytes(int32_t n_layers, int64_t layer_bytes, int64_t mem_avail_bytes,
+                        uint8_t *on_host, int32_t *n_off, int32_t *n_staging);
+
+/* The order of operations the copy pipeline enqueues for a plan, without a GPU
+ * (the runtime walks the same scheduler).  ops is a HOST array of max_ops
+ * records of six int32: kind, step, layer, buf, copy_idx, wait_idx with
+ *   kind 0 COPY     h2d stream: wait consumed[wait_idx] if >= 0, copy `layer`'s
+ *                   host pool into staging `buf`, signal ready[copy_idx]
+ *   kind 1 APPEND   compute stream: wait ready[wait_idx] if >= 0, store K/V
+ *                   (buf = -1: resident layer)
+ *   kind 2 ATTN     compute stream: attention reading staging `buf` (or the
+ *                   resident pool when buf = -1)
+ *   kind 3 RELEASE  compute stream: signal consumed[copy_idx]
+ * n_ops receives the number of records written.  OKV_ENOSPC if max_ops is too small. */
+int okv_schedule_trace(int32_t n_layers, const uint8_t *on_host, int32_t n_staging,
+                       int32_t n_steps, int32_t *ops, int64_t max_ops, int64_t *n_ops);
+
+/* ---- context -------------------------------------------------------------------- */
+
+/* Validates cfg, copies it, allocates the bookkeeping arrays on the current
+ * device.  *out is NULL on failure (then okv_last_error(NULL) has the reason). */
+int okv_create(const okv_config *cfg, okv_ctx **out);
+
+/* Waits for both streams, frees what okv_create allocated.  Caller buffers are
+ * untouched. */
+int okv_destroy(okv_ctx *ctx);
+
+/* Message of the last failure on ctx (or of the last failure without a context
+ * when ctx is NULL).  The pointer stays valid until the next call on ctx. */
+const char *okv_last_error(const okv_ctx *ctx);
+
+/* Describes the batch that the following steps decode.
+ *   B            1 <= B <= max_batch
+ *   block_table  HOST int32 [B][max_blocks_per_seq]; block ids in
+ *                [0, blocks_per_layer), -1 = not allocated; no block may appear
+ *                twice.  The same table serves every layer.  Ignored (may be
+ *                NULL) for contiguous pools, where sequence b owns slice b.
+ *   ctx_lens     HOST int32 [B]: tokens already stored per sequence (>= 0), the
+ *                same in every layer.
+ * Synchronous: waits for both streams, uploads the tables, restarts the copy
+ * pipeline.  Must not be called between okv_step_begin and okv_step_end. */
+int okv_set_batch(okv_ctx *ctx, int32_t B, const int32_t *block_table, const int32_t *ctx_lens);
+
+/* Opens a decode step: every sequence's length grows by one (the slot kv_append
+ * fills), the split-K work list is rebuilt on the device, and for host layers
+ * the first copies are enqueued if none are in flight.
+ * OKV_ENOSPC if a sequence would outgrow its capacity or reach an unallocated
+ * block (nothing is changed then). */
+int okv_step_begin(okv_ctx *ctx);
+
+/* Closes the step.  OKV_ESTATE unless every layer had its decode_attn. */
+int okv_step_end(okv_ctx *ctx);
+
+/* Stores this step's key and value rows of `layer` at position ctx_len - 1 of each
+ * sequence (paper §II-A: K/V of every processed token are kept for the following
+ * decode steps).  For a host layer the rows are written both into the staged copy
+ * (so this step's attention sees them) and into the host pool (so later steps do).
+ *   k_new, v_new  DEVICE fp16 [B][G][d]
+ * Within a step layers are visited in order 0 .. L-1, kv_append(l) before
+ * decode_attn(l); anything else is OKV_ESTATE. */
+int kv_append(okv_ctx *ctx, int32_t layer, const void *k_new, const void *v_new);
+
+/* Attention of the step's query over all stored keys of `layer`, including the one
+ * just appended (paper §II-A; cost model §IV-D: 4 flops per cached K/V element):
+ *   out[b][h] = sum_i softmax_i(q[b][h] . k_i / sqrt(d)) v_i,  i < ctx_len[b],
+ * query head h reading KV head h / (H / G).
+ *   q    DEVICE fp16 [B][H][d]
+ *   out  DEVICE [B][H][d], fp16 or fp32 as cfg.out_dtype says
+ * For a host layer the call first makes the compute stream wait for the layer's
+ * copy, and afterwards hands the staging buffer back and enqueues the next copy. */
+int decode_attn(okv_ctx *ctx, int32_t layer, const void *q, void *out);
+
+/* Blocks until everything enqueued on both streams has finished. */
+int okv_synchronize(okv_ctx *ctx);
+
+/* ---- introspection used by tests and the benchmark -------------------------------- */
+
+/* Overrides the split size (0 = back to the library's choice).  Takes effect at the
+ * next okv_step_begin.  OKV_ENOSPC if the workspace is too small for it. */
+int okv_set_split_tokens(okv_ctx *ctx, int32_t split_tokens);
+
+/* The split size in use (after the last okv_step_begin / okv_set_batch). */
+int32_t okv_get_split_tokens(const okv_ctx *ctx);
+
+/* Copies the device-side sequence lengths back.  out: HOST int32 [B].  Synchronous. */
+int okv_get_ctx_lens(okv_ctx *ctx, int32_t *out);
+
+/* The current split-K work list as (sequence, first key, one-past-last key) triples,
+ * in launch order.  from_device = 0 walks the host copy of the tables;
+ * from_device = 1 runs a small kernel that decodes every item exactly as the
+ * attention kernel does and copies the result back (synchronous).
+ *   items  HOST int32 [max_items][3];  n_items HOST out. */
+int okv_worklist(okv_ctx *ctx, int32_t from_device, int32_t *items, int64_t max_items,
+                 int64_t *n_items);
+
+/* Per-kernel timing.  While enabled every decode_attn brackets its split-K kernel
+ * with HIP events on the compute stream.  okv_profile_read waits for the stream,
+ * returns the summed kernel time (ms) and the number of launches since the last
+ * read, and resets both. */
+int okv_profile_enable(okv_ctx *ctx, int32_t on);
+int okv_profile_read(okv_ctx *ctx, double *attn_ms, int64_t *attn_launches);
+
+/* Measured host-to-device rate: `reps` plain hipMemcpyAsync copies of `bytes` from
+ * pinned HOST memory `src` to DEVICE memory `dst` on `stream`, each timed with HIP
+ * events; *gbps_median receives the median in GB/s (1e9 bytes).  Synchronous. */
+int okv_measure_h2d(void *dst, const void *src, int64_t bytes, int32_t reps, void *stream,
+                    double *gbps_median);
+
+/* A plain device-to-device copy kernel (16 bytes per lane, grid-stride), the
+ * yardstick the attention kernel's HBM traffic and rate are compared with.
+ * bytes must be a multiple of 16.  Asynchronous on `stream`. */
+int okv_probe_copy(void *dst, const void *src, int64_t bytes, void *stream);
+
+/* A plain read kernel over `bytes` of DEVICE memory (sums into a 4-byte sink so the
+ * loads are kept): the read-only yardstick.  Asynchronous on `stream`. */
+int okv_probe_read(const void *src, int64_t bytes, void *sink, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OKV_H */

@@ -1,0 +1,262 @@
+"""ctypes binding of libokv.so: the same names as include/okv.h, argument
+marshalling only.  Every step of the path runs in the library's kernels; there
+is no fallback: a missing library raises."""
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libokv.so")
+
+OKV_OK, OKV_EINVAL, OKV_ENOSPC, OKV_ESTATE, OKV_EHIP = 0, -1, -2, -3, -4
+_CODE_NAMES = {0: "OKV_OK", -1: "OKV_EINVAL", -2: "OKV_ENOSPC", -3: "OKV_ESTATE", -4: "OKV_EHIP"}
+
+# every symbol include/okv.h declares
+EXPORTS = [
+    "okv_layer_pool_bytes", "okv_workspace_bytes", "kv_offload_plan", "okv_plan_from_bytes",
+    "okv_schedule_trace", "okv_create", "okv_destroy", "okv_last_error", "okv_set_batch",
+    "okv_step_begin", "okv_step_end", "kv_append", "decode_attn", "okv_synchronize",
+    "okv_set_split_tokens", "okv_get_split_tokens", "okv_get_ctx_lens", "okv_worklist",
+    "okv_profile_enable", "okv_profile_read", "okv_measure_h2d", "okv_probe_copy", "okv_probe_read",
+]
+
+
+class OkvError(RuntimeError):
+    def __init__(self, code, message):
+        super().__init__(f"{_CODE_NAMES.get(code, code)}: {message}")
+        self.code = code
+
+
+class OkvConfig(ctypes.Structure):
+    _fields_ = [
+        ("n_layers", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("block_tokens", ctypes.c_int32), ("max_batch", ctypes.c_int32),
+        ("max_blocks_per_seq", ctypes.c_int32), ("max_ctx", ctypes.c_int32),
+        ("blocks_per_layer", ctypes.c_int64), ("out_dtype", ctypes.c_int32), ("split_tokens", ctypes.c_int32),
+        ("dev_pool", ctypes.POINTER(ctypes.c_void_p)), ("host_pool", ctypes.POINTER(ctypes.c_void_p)),
+        ("staging", ctypes.c_void_p * 2), ("staging_bytes", ctypes.c_int64),
+        ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_int64),
+        ("compute_stream", ctypes.c_void_p), ("h2d_stream", ctypes.c_void_p),
+    ]
+
+
+_lib_handle = None
+
+
+def lib():
+    """The loaded library; raises if it has not been built."""
+    global _lib_handle
+    if _lib_handle is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2504_11816_amd.build` "
+                "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        P, I32, I64 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64
+        cfgp = ctypes.POINTER(OkvConfig)
+        sig = {
+            "okv_layer_pool_bytes": (I64, [cfgp]),
+            "okv_workspace_bytes": (I64, [cfgp]),
+            "kv_offload_plan": (ctypes.c_int, [I32, I64, I64, P, ctypes.POINTER(I32)]),
+            "okv_plan_from_bytes": (ctypes.c_int, [I32, I64, I64, P, ctypes.POINTER(I32), ctypes.POINTER(I32)]),
+            "okv_schedule_trace": (ctypes.c_int, [I32, P, I32, I32, P, I64, ctypes.POINTER(I64)]),
+            "okv_create": (ctypes.c_int, [cfgp, ctypes.POINTER(P)]),
+            "okv_destroy": (ctypes.c_int, [P]),
+            "okv_last_error": (ctypes.c_char_p, [P]),
+            "okv_set_batch": (ctypes.c_int, [P, I32, P, P]),
+            "okv_step_begin": (ctypes.c_int, [P]),
+            "okv_step_end": (ctypes.c_int, [P]),
+            "kv_append": (ctypes.c_int, [P, I32, P, P]),
+            "decode_attn": (ctypes.c_int, [P, I32, P, P]),
+            "okv_synchronize": (ctypes.c_int, [P]),
+            "okv_set_split_tokens": (ctypes.c_int, [P, I32]),
+            "okv_get_split_tokens": (I32, [P]),
+            "okv_get_ctx_lens": (ctypes.c_int, [P, P]),
+            "okv_worklist": (ctypes.c_int, [P, I32, P, I64, ctypes.POINTER(I64)]),
+            "okv_profile_enable": (ctypes.c_int, [P, I32]),
+            "okv_profile_read": (ctypes.c_int, [P, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(I64)]),
+            "okv_measure_h2d": (ctypes.c_int, [P, P, I64, I32, P, ctypes.POINTER(ctypes.c_double)]),
+            "okv_probe_copy": (ctypes.c_int, [P, P, I64, P]),
+            "okv_probe_read": (ctypes.c_int, [P, I64, P, P]),
+        }
+        for name, (res, args) in sig.items():
+            fn = getattr(L, name)
+            fn.restype, fn.argtypes = res, args
+        _lib_handle = L
+    return _lib_handle
+
+
+def _ptr(x):
+    """Address of a torch tensor / numpy array / int / None as c_void_p."""
+    if x is None:
+        return ctypes.c_void_p(0)
+    if isinstance(x, int):
+        return ctypes.c_void_p(x)
+    if hasattr(x, "data_ptr"):
+        return ctypes.c_void_p(x.data_ptr())
+    if isinstance(x, np.ndarray):
+        return ctypes.c_void_p(x.ctypes.data)
+    raise TypeError(f"cannot take the address of {type(x)}")
+
+
+def _check(rc, ctx=None):
+    if rc != 0:
+        msg = lib().okv_last_error(ctx)
+        raise OkvError(rc, msg.decode() if msg else "")
+    return rc
+
+
+# ---- pure host functions --------------------------------------------------------
+
+def kv_offload_plan(n_layers, coff_num, coff_den):
+    """-> (on_host uint8 [n_layers], n_off)"""
+    on_host = np.zeros(max(n_layers, 1), dtype=np.uint8)
+    n_off = ctypes.c_int32(0)
+    _check(lib().kv_offload_plan(n_layers, coff_num, coff_den, _ptr(on_host), ctypes.byref(n_off)))
+    return on_host[:n_layers], n_off.value
+
+
+def okv_plan_from_bytes(n_layers, layer_bytes, mem_avail_bytes):
+    """-> (on_host uint8 [n_layers], n_off, n_staging)"""
+    on_host = np.zeros(max(n_layers, 1), dtype=np.uint8)
+    n_off, n_st = ctypes.c_int32(0), ctypes.c_int32(0)
+    _check(lib().okv_plan_from_bytes(n_layers, layer_bytes, mem_avail_bytes, _ptr(on_host),
+                                     ctypes.byref(n_off), ctypes.byref(n_st)))
+    return on_host[:n_layers], n_off.value, n_st.value
+
+
+def okv_schedule_trace(on_host, n_staging, n_steps):
+    """-> list of (kind, step, layer, buf, copy_idx, wait_idx)"""
+    on_host = np.ascontiguousarray(on_host, dtype=np.uint8)
+    L = len(on_host)
+    max_ops = 4 * L * max(n_steps, 1) + 8
+    ops = np.zeros((max_ops, 6), dtype=np.int32)
+    n = ctypes.c_int64(0)
+    _check(lib().okv_schedule_trace(L, _ptr(on_host), n_staging, n_steps, _ptr(ops), max_ops, ctypes.byref(n)))
+    return [tuple(int(v) for v in row) for row in ops[:n.value]]
+
+
+def make_config(**kw):
+    cfg = OkvConfig()
+    for k, v in kw.items():
+        setattr(cfg, k, v)
+    return cfg
+
+
+def okv_layer_pool_bytes(cfg):
+    r = lib().okv_layer_pool_bytes(ctypes.byref(cfg))
+    if r < 0:
+        _check(int(r))
+    return int(r)
+
+
+def okv_workspace_bytes(cfg):
+    r = lib().okv_workspace_bytes(ctypes.byref(cfg))
+    if r < 0:
+        _check(int(r))
+    return int(r)
+
+
+def okv_measure_h2d(dst, src, nbytes, reps, stream):
+    g = ctypes.c_double(0)
+    _check(lib().okv_measure_h2d(_ptr(dst), _ptr(src), nbytes, reps, _ptr(stream), ctypes.byref(g)))
+    return g.value
+
+
+def okv_probe_copy(dst, src, nbytes, stream):
+    _check(lib().okv_probe_copy(_ptr(dst), _ptr(src), nbytes, _ptr(stream)))
+
+
+def okv_probe_read(src, nbytes, sink, stream):
+    _check(lib().okv_probe_read(_ptr(src), nbytes, _ptr(sink), _ptr(stream)))
+
+
+# ---- context ------------------------------------------------------------------------
+
+class Context:
+    """okv_ctx with the header's calls as methods.  Pointers are raw addresses
+    (ints) or objects with data_ptr(); the caller keeps the memory alive."""
+
+    def __init__(self, *, n_layers, n_q_heads, n_kv_heads, head_dim, block_tokens, max_batch,
+                 max_blocks_per_seq=0, max_ctx=0, blocks_per_layer=0, out_dtype=0, split_tokens=0,
+                 dev_pool, host_pool=None, staging=(None, None), staging_bytes=0,
+                 workspace, workspace_bytes, compute_stream=0, h2d_stream=0):
+        L = n_layers
+        self._dev = (ctypes.c_void_p * L)(*[_ptr(p) for p in dev_pool])
+        self._host = (ctypes.c_void_p * L)(*[_ptr(p) for p in (host_pool or [None] * L)])
+        cfg = OkvConfig()
+        cfg.n_layers, cfg.n_q_heads, cfg.n_kv_heads, cfg.head_dim = n_layers, n_q_heads, n_kv_heads, head_dim
+        cfg.block_tokens, cfg.max_batch, cfg.max_blocks_per_seq = block_tokens, max_batch, max_blocks_per_seq
+        cfg.max_ctx, cfg.blocks_per_layer, cfg.out_dtype, cfg.split_tokens = max_ctx, blocks_per_layer, out_dtype, split_tokens
+        cfg.dev_pool = ctypes.cast(self._dev, ctypes.POINTER(ctypes.c_void_p))
+        cfg.host_pool = ctypes.cast(self._host, ctypes.POINTER(ctypes.c_void_p))
+        cfg.staging[0], cfg.staging[1] = _ptr(staging[0]), _ptr(staging[1])
+        cfg.staging_bytes = staging_bytes
+        cfg.workspace, cfg.workspace_bytes = _ptr(workspace), workspace_bytes
+        cfg.compute_stream, cfg.h2d_stream = _ptr(compute_stream), _ptr(h2d_stream)
+        self.cfg = cfg
+        self.B = 0
+        self._h = ctypes.c_void_p(0)
+        _check(lib().okv_create(ctypes.byref(cfg), ctypes.byref(self._h)))
+
+    def close(self):
+        if self._h:
+            lib().okv_destroy(self._h)
+            self._h = ctypes.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _c(self, rc):
+        return _check(rc, self._h)
+
+    def okv_set_batch(self, block_table, ctx_lens):
+        ctx_lens = np.ascontiguousarray(ctx_lens, dtype=np.int32)
+        self.B = len(ctx_lens)
+        if block_table is not None:
+            block_table = np.ascontiguousarray(block_table, dtype=np.int32)
+        self._c(lib().okv_set_batch(self._h, self.B, _ptr(block_table), _ptr(ctx_lens)))
+
+    def okv_step_begin(self):
+        self._c(lib().okv_step_begin(self._h))
+
+    def okv_step_end(self):
+        self._c(lib().okv_step_end(self._h))
+
+    def kv_append(self, layer, k_new, v_new):
+        self._c(lib().kv_append(self._h, layer, _ptr(k_new), _ptr(v_new)))
+
+    def decode_attn(self, layer, q, out):
+        self._c(lib().decode_attn(self._h, layer, _ptr(q), _ptr(out)))
+
+    def okv_synchronize(self):
+        self._c(lib().okv_synchronize(self._h))
+
+    def okv_set_split_tokens(self, s):
+        self._c(lib().okv_set_split_tokens(self._h, s))
+
+    def okv_get_split_tokens(self):
+        return int(lib().okv_get_split_tokens(self._h))
+
+    def okv_get_ctx_lens(self):
+        out = np.zeros(self.B, dtype=np.int32)
+        self._c(lib().okv_get_ctx_lens(self._h, _ptr(out)))
+        return out
+
+    def okv_worklist(self, from_device=False, max_items=1 << 20):
+        items = np.zeros((max_items, 3), dtype=np.int32)
+        n = ctypes.c_int64(0)
+        self._c(lib().okv_worklist(self._h, 1 if from_device else 0, _ptr(items), max_items, ctypes.byref(n)))
+        return items[:n.value].copy()
+
+    def okv_profile_enable(self, on):
+        self._c(lib().okv_profile_enable(self._h, 1 if on else 0))
+
+    def okv_profile_read(self):
+        ms, n = ctypes.c_double(0), ctypes.c_int64(0)
+        self._c(lib().okv_profile_read(self._h, ctypes.byref(ms), ctypes.byref(n)))
+        return ms.value, n.value

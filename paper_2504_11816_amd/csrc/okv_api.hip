@@ -1,0 +1,665 @@
+// C ABI of the okv library: argument checks, batch / step bookkeeping and the
+// copy pipeline for host layers.  All arithmetic on K/V/q happens in the kernels
+// (okv_kernels.hip); nothing here touches tensor values.
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <string>
+#include <utility>
+#include <vector>
+
+#include "../../include/okv.h"
+#include "okv_host.h"
+#include "okv_kernels.h"
+
+using okv::Op;
+
+namespace {
+
+constexpr int kEventRing = 4;            // > copies in flight (at most 2)
+constexpr int32_t kMinAutoSplit = 128;   // smallest split size the library picks by itself
+constexpr int64_t kTargetUnits = 8192;   // wavefront-sized work items wanted per launch
+constexpr int64_t kMaxItemBlocks = 64;   // paged: blocks one work item may span (one id per lane)
+
+thread_local std::string g_error;        // failures that have no context to live in
+
+}  // namespace
+
+struct okv_ctx {
+  okv_config cfg;
+  std::vector<void *> dev_pool, host_pool;
+  okv::PoolShape shape;
+  int64_t pool_bytes = 0, block_bytes = 0;
+  int32_t cap_tokens = 0;                // per sequence
+  bool any_host = false;
+  int32_t n_staging = 0;
+  hipStream_t compute = nullptr, h2d = nullptr;
+
+  int32_t *d_block_table = nullptr, *d_ctx_lens = nullptr, *d_chunk_prefix = nullptr;
+  int32_t *d_item_seq = nullptr, *d_items_dump = nullptr;
+  int64_t max_items = 0;
+  float *part_o = nullptr, *part_ml = nullptr;
+
+  std::vector<int32_t> h_block_table, h_ctx_lens;
+  int32_t B = 0, split = 0, split_override = 0, n_items = 0;
+  bool need_merge = false;
+  int64_t copy_bytes = 0;
+
+  bool batch_set = false, in_step = false, appended = false;
+  int64_t step = 0;
+  int32_t next_layer = 0;
+  okv::Scheduler sched;
+  hipEvent_t ready_ev[kEventRing] = {}, consumed_ev[kEventRing] = {};
+
+  bool profile = false;
+  std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
+  size_t prof_used = 0;
+
+  std::string err;
+};
+
+namespace {
+
+int fail(okv_ctx *ctx, int code, const char *fmt, ...) {
+  char buf[512];
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(buf, sizeof buf, fmt, ap);
+  va_end(ap);
+  (ctx ? ctx->err : g_error) = buf;
+  return code;
+}
+
+#define OKV_HIP(ctx, expr)                                                                  \
+  do {                                                                                      \
+    hipError_t e_ = (expr);                                                                 \
+    if (e_ != hipSuccess) return fail(ctx, OKV_EHIP, "%s: %s", #expr, hipGetErrorString(e_)); \
+  } while (0)
+
+bool is_pow2(int64_t x) { return x > 0 && (x & (x - 1)) == 0; }
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15) == 0; }
+
+// Checks the shape fields; returns a message or NULL.
+const char *shape_problem(const okv_config *c) {
+  if (!c) return "cfg is NULL";
+  if (c->n_layers < 1) return "n_layers < 1";
+  if (c->n_kv_heads < 1 || c->n_q_heads < 1 || c->n_q_heads % c->n_kv_heads) return "n_q_heads must be a multiple of n_kv_heads";
+  int r = c->n_q_heads / c->n_kv_heads;
+  if (r != 1 && r != 2 && r != 4 && r != 8) return "n_q_heads / n_kv_heads must be 1, 2, 4 or 8";
+  if (c->n_kv_heads > 65535) return "n_kv_heads too large";
+  if (c->head_dim != 64 && c->head_dim != 128) return "head_dim must be 64 or 128";
+  if (c->max_batch < 1 || c->max_batch > 65535) return "max_batch out of range";
+  if (c->out_dtype != 0 && c->out_dtype != 1) return "out_dtype must be 0 or 1";
+  if (c->split_tokens < 0) return "split_tokens < 0";
+  if (c->block_tokens == 0) {
+    if (c->max_ctx < 16 || c->max_ctx % 16) return "contiguous pools need max_ctx >= 16 and a multiple of 16";
+  } else {
+    if (!is_pow2(c->block_tokens) || c->block_tokens < 16 || c->block_tokens > 1024) return "block_tokens must be 0 or a power of two in [16, 1024]";
+    if (c->max_blocks_per_seq < 1) return "max_blocks_per_seq < 1";
+    if (c->blocks_per_layer < 1 || c->blocks_per_layer > 0x7fffffff) return "blocks_per_layer out of range";
+    if ((int64_t)c->max_blocks_per_seq * c->block_tokens > 0x3fffffff) return "capacity per sequence too large";
+  }
+  return nullptr;
+}
+
+int64_t cap_tokens_of(const okv_config *c) {
+  return c->block_tokens ? (int64_t)c->max_blocks_per_seq * c->block_tokens : c->max_ctx;
+}
+
+int64_t pool_bytes_of(const okv_config *c) {
+  int64_t row = (int64_t)c->head_dim * 2;
+  if (c->block_tokens) return c->blocks_per_layer * 2 * c->n_kv_heads * c->block_tokens * row;
+  return (int64_t)c->max_batch * 2 * c->n_kv_heads * c->max_ctx * row;
+}
+
+int64_t bytes_per_item(const okv_config *c) { return (int64_t)c->n_q_heads * (c->head_dim + 2) * 4; }
+
+int64_t count_items(const int32_t *ctx, int32_t B, int32_t S) {
+  int64_t n = 0;
+  for (int32_t b = 0; b < B; ++b) n += (ctx[b] + S - 1) / S;
+  return n;
+}
+
+// Largest power-of-two multiple of kMinAutoSplit that still yields kTargetUnits
+// wavefront items, and no more items than the workspace holds.
+int32_t choose_split(const okv_ctx *ctx, const std::vector<int32_t> &lens) {
+  if (ctx->split_override) return ctx->split_override;
+  if (ctx->cfg.split_tokens) return ctx->cfg.split_tokens;
+  int32_t S = kMinAutoSplit;
+  int32_t longest = 1;
+  for (int32_t b = 0; b < ctx->B; ++b) longest = std::max(longest, lens[b]);
+  const int64_t S_max = ctx->cfg.block_tokens ? (int64_t)ctx->cfg.block_tokens * kMaxItemBlocks : (1 << 30);
+  while (S < longest && S * 2 <= S_max &&
+         count_items(lens.data(), ctx->B, S * 2) * ctx->cfg.n_kv_heads >= kTargetUnits)
+    S *= 2;
+  while (S * 2 <= S_max && count_items(lens.data(), ctx->B, S) > ctx->max_items) S *= 2;
+  return S;
+}
+
+// Paged pools: the split kernel keeps one block id per lane, so an item may touch at
+// most kMaxItemBlocks blocks (items start at multiples of S).
+bool split_fits_block_window(const okv_config *c, int64_t S) {
+  if (!c->block_tokens) return true;
+  const int64_t T = c->block_tokens;
+  const int64_t spanned = S % T == 0 ? S / T : (S + T - 1) / T + 1;
+  return spanned <= kMaxItemBlocks;
+}
+
+int exec_op(okv_ctx *ctx, const Op &op, const void *a0, const void *a1, void *out) {
+  switch (op.kind) {
+    case okv::OP_COPY: {
+      if (op.wait_idx >= 0) OKV_HIP(ctx, hipStreamWaitEvent(ctx->h2d, ctx->consumed_ev[op.wait_idx % kEventRing], 0));
+      OKV_HIP(ctx, hipMemcpyAsync(ctx->cfg.staging[op.buf], ctx->host_pool[op.layer], (size_t)ctx->copy_bytes,
+                                  hipMemcpyHostToDevice, ctx->h2d));
+      OKV_HIP(ctx, hipEventRecord(ctx->ready_ev[op.copy_idx % kEventRing], ctx->h2d));
+      return OKV_OK;
+    }
+    case okv::OP_APPEND: {
+      if (op.wait_idx >= 0) OKV_HIP(ctx, hipStreamWaitEvent(ctx->compute, ctx->ready_ev[op.wait_idx % kEventRing], 0));
+      void *pool_a = op.buf >= 0 ? ctx->cfg.staging[op.buf] : ctx->dev_pool[op.layer];
+      void *pool_b = op.buf >= 0 ? ctx->host_pool[op.layer] : nullptr;
+      OKV_HIP(ctx, okv::launch_append(ctx->shape, ctx->d_block_table, ctx->d_ctx_lens, ctx->B, a0, a1, pool_a,
+                                      pool_b, ctx->compute));
+      return OKV_OK;
+    }
+    case okv::OP_ATTN: {
+      okv::AttnLaunch a;
+      a.shape = ctx->shape;
+      a.batch = okv::BatchState{ctx->d_block_table, ctx->d_ctx_lens, ctx->d_chunk_prefix, ctx->d_item_seq,
+                                ctx->B, ctx->split, ctx->n_items};
+      a.q = a0;
+      a.pool = op.buf >= 0 ? ctx->cfg.staging[op.buf] : ctx->dev_pool[op.layer];
+      a.out = out;
+      a.part_o = ctx->part_o;
+      a.part_ml = ctx->part_ml;
+      a.out_fp32 = ctx->cfg.out_dtype;
+      a.need_merge = ctx->need_merge;
+      hipEvent_t e0 = nullptr, e1 = nullptr;
+      if (ctx->profile) {
+        if (ctx->prof_used == ctx->prof_events.size()) {
+          hipEvent_t x, y;
+          OKV_HIP(ctx, hipEventCreate(&x));
+          OKV_HIP(ctx, hipEventCreate(&y));
+          ctx->prof_events.emplace_back(x, y);
+        }
+        e0 = ctx->prof_events[ctx->prof_used].first;
+        e1 = ctx->prof_events[ctx->prof_used].second;
+        ++ctx->prof_used;
+      }
+      OKV_HIP(ctx, okv::launch_decode_attn(a, ctx->compute, e0, e1));
+      return OKV_OK;
+    }
+    case okv::OP_RELEASE:
+      OKV_HIP(ctx, hipEventRecord(ctx->consumed_ev[op.copy_idx % kEventRing], ctx->compute));
+      return OKV_OK;
+  }
+  return fail(ctx, OKV_ESTATE, "unknown pipeline op %d", op.kind);
+}
+
+int exec_ops(okv_ctx *ctx, const std::vector<Op> &ops, const void *a0, const void *a1, void *out) {
+  for (const Op &op : ops) {
+    int rc = exec_op(ctx, op, a0, a1, out);
+    if (rc) return rc;
+  }
+  return OKV_OK;
+}
+
+// Recomputes split size, item count and merge flag from the host lengths and
+// rebuilds the device work list (adding `inc` to every device length first).
+int rebuild_worklist(okv_ctx *ctx, int32_t inc) {
+  ctx->split = choose_split(ctx, ctx->h_ctx_lens);
+  int64_t n = count_items(ctx->h_ctx_lens.data(), ctx->B, ctx->split);
+  if (n > ctx->max_items)
+    return fail(ctx, OKV_ENOSPC, "split size %d needs %lld work items, workspace holds %lld", ctx->split,
+                (long long)n, (long long)ctx->max_items);
+  ctx->n_items = (int32_t)n;
+  ctx->need_merge = false;
+  for (int32_t b = 0; b < ctx->B; ++b)
+    if (ctx->h_ctx_lens[b] > ctx->split) ctx->need_merge = true;
+  OKV_HIP(ctx, okv::launch_step_advance(ctx->d_ctx_lens, ctx->d_chunk_prefix, ctx->d_item_seq, ctx->B,
+                                        ctx->split, inc, ctx->compute));
+  return OKV_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t okv_layer_pool_bytes(const okv_config *cfg) {
+  if (const char *why = shape_problem(cfg)) return fail(nullptr, OKV_EINVAL, "%s", why);
+  return pool_bytes_of(cfg);
+}
+
+int64_t okv_workspace_bytes(const okv_config *cfg) {
+  if (const char *why = shape_problem(cfg)) return fail(nullptr, OKV_EINVAL, "%s", why);
+  int64_t S = cfg->split_tokens ? cfg->split_tokens : kMinAutoSplit;
+  int64_t cap = cap_tokens_of(cfg);
+  int64_t items = (int64_t)cfg->max_batch * ((cap + S - 1) / S);
+  return items * bytes_per_item(cfg);
+}
+
+int kv_offload_plan(int32_t n_layers, int64_t coff_num, int64_t coff_den, uint8_t *on_host, int32_t *n_off) {
+  if (n_layers < 1 || !on_host) return fail(nullptr, OKV_EINVAL, "kv_offload_plan: n_layers < 1 or on_host NULL");
+  if (coff_den <= 0 || coff_num < 0 || coff_num > coff_den)
+    return fail(nullptr, OKV_EINVAL, "kv_offload_plan: C_off must lie in [0, 1]");
+  int32_t k = okv::plan_count(n_layers, coff_num, coff_den);
+  okv::plan_place(n_layers, k, on_host);
+  if (n_off) *n_off = k;
+  return OKV_OK;
+}
+
+int okv_plan_from_bytes(int32_t n_layers, int64_t layer_bytes, int64_t mem_avail_bytes, uint8_t *on_host,
+                        int32_t *n_off, int32_t *n_staging) {
+  if (n_layers < 1 || layer_bytes < 1 || mem_avail_bytes < 0 || !on_host)
+    return fail(nullptr, OKV_EINVAL, "okv_plan_from_bytes: bad argument");
+  int32_t k = 0, ns = 0;
+  if ((__int128)mem_avail_bytes >= (__int128)layer_bytes * n_layers) {
+    k = 0;                                                      // Case 1
+  } else if (layer_bytes > mem_avail_bytes) {
+    return fail(nullptr, OKV_ENOSPC, "one layer's KV (%lld B) exceeds the available memory (%lld B)",
+                (long long)layer_bytes, (long long)mem_avail_bytes);   // Case 2
+  } else {
+    int64_t fit = mem_avail_bytes / layer_bytes;                // Case 3: 1 <= fit < n_layers
+    ns = fit >= 2 ? 2 : 1;
+    k = n_layers - (int32_t)(fit - ns);
+  }
+  okv::plan_place(n_layers, k, on_host);
+  if (n_off) *n_off = k;
+  if (n_staging) *n_staging = ns;
+  return OKV_OK;
+}
+
+int okv_schedule_trace(int32_t n_layers, const uint8_t *on_host, int32_t n_staging, int32_t n_steps,
+                       int32_t *ops, int64_t max_ops, int64_t *n_ops) {
+  if (n_layers < 1 || !on_host || n_steps < 0 || !ops || !n_ops || n_staging < 0 || n_staging > 2)
+    return fail(nullptr, OKV_EINVAL, "okv_schedule_trace: bad argument");
+  okv::Scheduler s;
+  s.reset(n_layers, on_host, n_staging);
+  if (s.n_host() > 0 && n_staging < 1) return fail(nullptr, OKV_EINVAL, "host layers need a staging buffer");
+  std::vector<Op> v;
+  if (n_steps > 0) s.prime(v);
+  for (int32_t step = 0; step < n_steps; ++step)
+    for (int32_t l = 0; l < n_layers; ++l) {
+      s.on_append(step, l, v);
+      s.on_attn(step, l, v);
+    }
+  *n_ops = (int64_t)v.size();
+  if ((int64_t)v.size() > max_ops) return fail(nullptr, OKV_ENOSPC, "trace needs %zu records", v.size());
+  for (size_t i = 0; i < v.size(); ++i) {
+    int32_t *o = ops + i * 6;
+    o[0] = v[i].kind, o[1] = v[i].step, o[2] = v[i].layer, o[3] = v[i].buf, o[4] = v[i].copy_idx, o[5] = v[i].wait_idx;
+  }
+  return OKV_OK;
+}
+
+int okv_create(const okv_config *cfg, okv_ctx **out) {
+  if (!out) return fail(nullptr, OKV_EINVAL, "okv_create: out is NULL");
+  *out = nullptr;
+  if (const char *why = shape_problem(cfg)) return fail(nullptr, OKV_EINVAL, "okv_create: %s", why);
+  const int32_t L = cfg->n_layers;
+  if (!cfg->dev_pool) return fail(nullptr, OKV_EINVAL, "okv_create: dev_pool is NULL");
+  bool any_host = false;
+  for (int32_t l = 0; l < L; ++l) {
+    void *d = cfg->dev_pool[l], *h = cfg->host_pool ? cfg->host_pool[l] : nullptr;
+    if ((d != nullptr) == (h != nullptr))
+      return fail(nullptr, OKV_EINVAL, "okv_create: layer %d needs exactly one of dev_pool / host_pool", l);
+    if (!aligned16(d) || !aligned16(h)) return fail(nullptr, OKV_EINVAL, "okv_create: layer %d pool not 16-byte aligned", l);
+    any_host |= h != nullptr;
+  }
+  const int64_t pool_bytes = pool_bytes_of(cfg);
+  int32_t n_staging = 0;
+  if (any_host) {
+    if (!cfg->staging[0]) return fail(nullptr, OKV_EINVAL, "okv_create: host layers need staging[0]");
+    if (cfg->staging_bytes < pool_bytes)
+      return fail(nullptr, OKV_ENOSPC, "okv_create: staging_bytes %lld < one layer's pool %lld (a layer's KV must fit on the GPU)",
+                  (long long)cfg->staging_bytes, (long long)pool_bytes);
+    if (!aligned16(cfg->staging[0]) || !aligned16(cfg->staging[1])) return fail(nullptr, OKV_EINVAL, "okv_create: staging not 16-byte aligned");
+    if (cfg->h2d_stream == cfg->compute_stream) return fail(nullptr, OKV_EINVAL, "okv_create: h2d_stream must differ from compute_stream");
+    n_staging = cfg->staging[1] ? 2 : 1;
+  }
+  if (cfg->split_tokens && !split_fits_block_window(cfg, cfg->split_tokens))
+    return fail(nullptr, OKV_EINVAL, "okv_create: split_tokens %d spans more than %lld blocks of %d tokens",
+                cfg->split_tokens, (long long)kMaxItemBlocks, cfg->block_tokens);
+  const int64_t need_ws = okv_workspace_bytes(cfg);
+  if (!cfg->workspace || !aligned16(cfg->workspace)) return fail(nullptr, OKV_EINVAL, "okv_create: workspace NULL or misaligned");
+  if (cfg->workspace_bytes < need_ws)
+    return fail(nullptr, OKV_ENOSPC, "okv_create: workspace_bytes %lld < %lld", (long long)cfg->workspace_bytes, (long long)need_ws);
+
+  okv_ctx *ctx = new (std::nothrow) okv_ctx();
+  if (!ctx) return fail(nullptr, OKV_ENOSPC, "okv_create: out of host memory");
+  ctx->cfg = *cfg;
+  ctx->dev_pool.assign(cfg->dev_pool, cfg->dev_pool + L);
+  if (cfg->host_pool) ctx->host_pool.assign(cfg->host_pool, cfg->host_pool + L);
+  else ctx->host_pool.assign(L, nullptr);
+  ctx->cfg.dev_pool = ctx->dev_pool.data();
+  ctx->cfg.host_pool = ctx->host_pool.data();
+  ctx->any_host = any_host;
+  ctx->n_staging = n_staging;
+  ctx->pool_bytes = pool_bytes;
+  ctx->cap_tokens = (int32_t)cap_tokens_of(cfg);
+  ctx->compute = static_cast<hipStream_t>(cfg->compute_stream);
+  ctx->h2d = static_cast<hipStream_t>(cfg->h2d_stream);
+  okv::PoolShape &s = ctx->shape;
+  s.H = cfg->n_q_heads, s.G = cfg->n_kv_heads, s.D = cfg->head_dim;
+  s.paged = cfg->block_tokens != 0;
+  s.log2_T = 0;
+  while (s.paged && (1 << s.log2_T) < cfg->block_tokens) ++s.log2_T;
+  s.tcap = s.paged ? cfg->block_tokens : cfg->max_ctx;
+  s.max_blocks = s.paged ? cfg->max_blocks_per_seq : 1;
+  ctx->block_bytes = (int64_t)2 * s.G * s.tcap * s.D * 2;
+
+  // workspace: [max_items * H][D] floats of weighted sums, then [max_items * H][2] floats
+  const int64_t per_item = bytes_per_item(cfg);
+  int64_t max_items = cfg->workspace_bytes / per_item;
+  max_items = std::min<int64_t>(max_items, (int64_t)cfg->max_batch * ctx->cap_tokens);
+  max_items = std::min<int64_t>(max_items, 0x7fffffff / (3 * (int64_t)std::max(1, s.H)));
+  ctx->max_items = max_items;
+  ctx->part_o = static_cast<float *>(cfg->workspace);
+  ctx->part_ml = ctx->part_o + max_items * s.H * s.D;
+
+  auto bail = [&](int code) {
+    std::string msg = ctx->err;
+    okv_destroy(ctx);
+    g_error = msg;
+    return code;
+  };
+#define OKV_TRY_CREATE(expr)                                                   \
+  do {                                                                         \
+    hipError_t e_ = (expr);                                                    \
+    if (e_ != hipSuccess) {                                                    \
+      fail(ctx, OKV_EHIP, "okv_create: %s: %s", #expr, hipGetErrorString(e_)); \
+      return bail(OKV_EHIP);                                                   \
+    }                                                                          \
+  } while (0)
+  const size_t tbl = (size_t)cfg->max_batch * s.max_blocks * sizeof(int32_t);
+  OKV_TRY_CREATE(hipMalloc(&ctx->d_block_table, tbl));
+  OKV_TRY_CREATE(hipMemset(ctx->d_block_table, 0, tbl));
+  OKV_TRY_CREATE(hipMalloc(&ctx->d_ctx_lens, (size_t)cfg->max_batch * sizeof(int32_t)));
+  OKV_TRY_CREATE(hipMalloc(&ctx->d_chunk_prefix, ((size_t)cfg->max_batch + 1) * sizeof(int32_t)));
+  OKV_TRY_CREATE(hipMalloc(&ctx->d_item_seq, (size_t)std::max<int64_t>(1, max_items) * sizeof(int32_t)));
+  for (int i = 0; i < kEventRing; ++i) {
+    OKV_TRY_CREATE(hipEventCreateWithFlags(&ctx->ready_ev[i], hipEventDisableTiming));
+    OKV_TRY_CREATE(hipEventCreateWithFlags(&ctx->consumed_ev[i], hipEventDisableTiming));
+  }
+#undef OKV_TRY_CREATE
+  *out = ctx;
+  return OKV_OK;
+}
+
+int okv_destroy(okv_ctx *ctx) {
+  if (!ctx) return OKV_OK;
+  if (ctx->h2d) (void)hipStreamSynchronize(ctx->h2d);
+  (void)hipStreamSynchronize(ctx->compute);
+  (void)hipFree(ctx->d_block_table);
+  (void)hipFree(ctx->d_ctx_lens);
+  (void)hipFree(ctx->d_chunk_prefix);
+  (void)hipFree(ctx->d_item_seq);
+  (void)hipFree(ctx->d_items_dump);
+  for (int i = 0; i < kEventRing; ++i) {
+    if (ctx->ready_ev[i]) (void)hipEventDestroy(ctx->ready_ev[i]);
+    if (ctx->consumed_ev[i]) (void)hipEventDestroy(ctx->consumed_ev[i]);
+  }
+  for (auto &p : ctx->prof_events) {
+    (void)hipEventDestroy(p.first);
+    (void)hipEventDestroy(p.second);
+  }
+  delete ctx;
+  return OKV_OK;
+}
+
+const char *okv_last_error(const okv_ctx *ctx) { return ctx ? ctx->err.c_str() : g_error.c_str(); }
+
+int okv_synchronize(okv_ctx *ctx) {
+  if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
+  if (ctx->any_host) OKV_HIP(ctx, hipStreamSynchronize(ctx->h2d));
+  OKV_HIP(ctx, hipStreamSynchronize(ctx->compute));
+  return OKV_OK;
+}
+
+int okv_set_batch(okv_ctx *ctx, int32_t B, const int32_t *block_table, const int32_t *ctx_lens) {
+  if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
+  if (ctx->in_step) return fail(ctx, OKV_ESTATE, "okv_set_batch inside a step");
+  if (B < 1 || B > ctx->cfg.max_batch) return fail(ctx, OKV_EINVAL, "B = %d outside [1, %d]", B, ctx->cfg.max_batch);
+  if (!ctx_lens) return fail(ctx, OKV_EINVAL, "ctx_lens is NULL");
+  const okv::PoolShape &s = ctx->shape;
+  if (s.paged && !block_table) return fail(ctx, OKV_EINVAL, "block_table is NULL");
+  int64_t max_blk = -1;
+  if (s.paged) {
+    std::vector<uint8_t> seen((size_t)ctx->cfg.blocks_per_layer, 0);
+    for (int32_t b = 0; b < B; ++b)
+      for (int32_t i = 0; i < s.max_blocks; ++i) {
+        int32_t id = block_table[(size_t)b * s.max_blocks + i];
+        if (id == -1) continue;
+        if (id < 0 || id >= ctx->cfg.blocks_per_layer)
+          return fail(ctx, OKV_EINVAL, "block_table[%d][%d] = %d outside [0, %lld)", b, i, id, (long long)ctx->cfg.blocks_per_layer);
+        if (seen[id]) return fail(ctx, OKV_EINVAL, "block %d appears twice in the block table", id);
+        seen[id] = 1;
+        max_blk = std::max<int64_t>(max_blk, id);
+      }
+  }
+  for (int32_t b = 0; b < B; ++b) {
+    if (ctx_lens[b] < 0 || ctx_lens[b] > ctx->cap_tokens)
+      return fail(ctx, OKV_EINVAL, "ctx_lens[%d] = %d outside [0, %d]", b, ctx_lens[b], ctx->cap_tokens);
+    if (s.paged) {
+      int32_t need = (ctx_lens[b] + ctx->cfg.block_tokens - 1) >> s.log2_T;
+      for (int32_t i = 0; i < need; ++i)
+        if (block_table[(size_t)b * s.max_blocks + i] < 0)
+          return fail(ctx, OKV_EINVAL, "sequence %d holds %d tokens but block %d is not allocated", b, ctx_lens[b], i);
+    }
+  }
+  int rc = okv_synchronize(ctx);
+  if (rc) return rc;
+  ctx->B = B;
+  ctx->h_ctx_lens.assign(ctx_lens, ctx_lens + B);
+  if (s.paged) {
+    ctx->h_block_table.assign(block_table, block_table + (size_t)B * s.max_blocks);
+    OKV_HIP(ctx, hipMemcpy(ctx->d_block_table, block_table, (size_t)B * s.max_blocks * sizeof(int32_t), hipMemcpyHostToDevice));
+    ctx->copy_bytes = (max_blk + 1) * ctx->block_bytes;
+  } else {
+    ctx->copy_bytes = (int64_t)B * ctx->block_bytes;
+  }
+  OKV_HIP(ctx, hipMemcpy(ctx->d_ctx_lens, ctx_lens, (size_t)B * sizeof(int32_t), hipMemcpyHostToDevice));
+  std::vector<uint8_t> on_host(ctx->cfg.n_layers, 0);
+  for (int32_t l = 0; l < ctx->cfg.n_layers; ++l) on_host[l] = ctx->host_pool[l] != nullptr;
+  ctx->sched.reset(ctx->cfg.n_layers, on_host.data(), ctx->n_staging);
+  ctx->step = 0;
+  ctx->next_layer = 0;
+  ctx->appended = false;
+  ctx->batch_set = true;
+  rc = rebuild_worklist(ctx, 0);
+  if (rc) { ctx->batch_set = false; return rc; }
+  return OKV_OK;
+}
+
+int okv_step_begin(okv_ctx *ctx) {
+  if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
+  if (!ctx->batch_set) return fail(ctx, OKV_ESTATE, "okv_step_begin before okv_set_batch");
+  if (ctx->in_step) return fail(ctx, OKV_ESTATE, "okv_step_begin inside a step");
+  const okv::PoolShape &s = ctx->shape;
+  for (int32_t b = 0; b < ctx->B; ++b) {
+    int32_t n = ctx->h_ctx_lens[b];
+    if (n + 1 > ctx->cap_tokens) return fail(ctx, OKV_ENOSPC, "sequence %d is at its capacity of %d tokens", b, ctx->cap_tokens);
+    if (s.paged && ctx->h_block_table[(size_t)b * s.max_blocks + (n >> s.log2_T)] < 0)
+      return fail(ctx, OKV_ENOSPC, "sequence %d has no block allocated for token %d", b, n);
+  }
+  for (int32_t b = 0; b < ctx->B; ++b) ctx->h_ctx_lens[b] += 1;
+  int rc = rebuild_worklist(ctx, 1);
+  if (rc) {
+    for (int32_t b = 0; b < ctx->B; ++b) ctx->h_ctx_lens[b] -= 1;
+    return rc;
+  }
+  if (ctx->any_host && !ctx->sched.primed()) {
+    std::vector<Op> ops;
+    ctx->sched.prime(ops);
+    rc = exec_ops(ctx, ops, nullptr, nullptr, nullptr);
+    if (rc) return rc;
+  }
+  ctx->in_step = true;
+  ctx->next_layer = 0;
+  ctx->appended = false;
+  return OKV_OK;
+}
+
+int okv_step_end(okv_ctx *ctx) {
+  if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
+  if (!ctx->in_step) return fail(ctx, OKV_ESTATE, "okv_step_end outside a step");
+  if (ctx->next_layer != ctx->cfg.n_layers)
+    return fail(ctx, OKV_ESTATE, "okv_step_end after %d of %d layers", ctx->next_layer, ctx->cfg.n_layers);
+  ctx->in_step = false;
+  ctx->step += 1;
+  return OKV_OK;
+}
+
+int kv_append(okv_ctx *ctx, int32_t layer, const void *k_new, const void *v_new) {
+  if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
+  if (!ctx->in_step) return fail(ctx, OKV_ESTATE, "kv_append outside a step");
+  if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, OKV_EINVAL, "layer %d outside [0, %d)", layer, ctx->cfg.n_layers);
+  if (layer != ctx->next_layer || ctx->appended)
+    return fail(ctx, OKV_ESTATE, "kv_append(%d) out of order: expected %s(%d)", layer,
+                ctx->appended ? "decode_attn" : "kv_append", ctx->next_layer);
+  if (!k_new || !v_new || !aligned16(k_new) || !aligned16(v_new)) return fail(ctx, OKV_EINVAL, "k_new / v_new NULL or not 16-byte aligned");
+  std::vector<Op> ops;
+  ctx->sched.on_append(ctx->step, layer, ops);
+  int rc = exec_ops(ctx, ops, k_new, v_new, nullptr);
+  if (rc) return rc;
+  ctx->appended = true;
+  return OKV_OK;
+}
+
+int decode_attn(okv_ctx *ctx, int32_t layer, const void *q, void *out) {
+  if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
+  if (!ctx->in_step) return fail(ctx, OKV_ESTATE, "decode_attn outside a step");
+  if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, OKV_EINVAL, "layer %d outside [0, %d)", layer, ctx->cfg.n_layers);
+  if (layer != ctx->next_layer || !ctx->appended)
+    return fail(ctx, OKV_ESTATE, "decode_attn(%d) out of order: expected %s(%d)", layer,
+                ctx->appended ? "decode_attn" : "kv_append", ctx->next_layer);
+  if (!q || !out || !aligned16(q) || !aligned16(out)) return fail(ctx, OKV_EINVAL, "q / out NULL or not 16-byte aligned");
+  std::vector<Op> ops;
+  ctx->sched.on_attn(ctx->step, layer, ops);
+  int rc = exec_ops(ctx, ops, q, nullptr, out);
+  if (rc) return rc;
+  ctx->appended = false;
+  ctx->next_layer = layer + 1;
+  return OKV_OK;
+}
+
+int okv_set_split_tokens(okv_ctx *ctx, int32_t split_tokens) {
+  if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
+  if (split_tokens < 0) return fail(ctx, OKV_EINVAL, "split_tokens < 0");
+  if (ctx->in_step) return fail(ctx, OKV_ESTATE, "okv_set_split_tokens inside a step");
+  if (split_tokens > 0 && !split_fits_block_window(&ctx->cfg, split_tokens))
+    return fail(ctx, OKV_EINVAL, "split size %d spans more than %lld blocks of %d tokens", split_tokens,
+                (long long)kMaxItemBlocks, ctx->cfg.block_tokens);
+  if (split_tokens > 0) {
+    int64_t worst = (int64_t)ctx->cfg.max_batch * (((int64_t)ctx->cap_tokens + split_tokens - 1) / split_tokens);
+    if (worst > ctx->max_items)
+      return fail(ctx, OKV_ENOSPC, "split size %d can need %lld work items, workspace holds %lld", split_tokens,
+                  (long long)worst, (long long)ctx->max_items);
+  }
+  ctx->split_override = split_tokens;
+  if (ctx->batch_set) return rebuild_worklist(ctx, 0);
+  return OKV_OK;
+}
+
+int32_t okv_get_split_tokens(const okv_ctx *ctx) { return ctx ? ctx->split : 0; }
+
+int okv_get_ctx_lens(okv_ctx *ctx, int32_t *out) {
+  if (!ctx || !out) return fail(ctx, OKV_EINVAL, "ctx or out is NULL");
+  if (!ctx->batch_set) return fail(ctx, OKV_ESTATE, "no batch set");
+  OKV_HIP(ctx, hipStreamSynchronize(ctx->compute));
+  OKV_HIP(ctx, hipMemcpy(out, ctx->d_ctx_lens, (size_t)ctx->B * sizeof(int32_t), hipMemcpyDeviceToHost));
+  return OKV_OK;
+}
+
+int okv_worklist(okv_ctx *ctx, int32_t from_device, int32_t *items, int64_t max_items, int64_t *n_items) {
+  if (!ctx || !items || !n_items) return fail(ctx, OKV_EINVAL, "NULL argument");
+  if (!ctx->batch_set) return fail(ctx, OKV_ESTATE, "no batch set");
+  *n_items = ctx->n_items;
+  if (ctx->n_items > max_items) return fail(ctx, OKV_ENOSPC, "work list has %d items", ctx->n_items);
+  if (ctx->n_items == 0) return OKV_OK;
+  if (from_device) {
+    if (!ctx->d_items_dump) OKV_HIP(ctx, hipMalloc(&ctx->d_items_dump, (size_t)ctx->max_items * 3 * sizeof(int32_t)));
+    okv::BatchState bs{ctx->d_block_table, ctx->d_ctx_lens, ctx->d_chunk_prefix, ctx->d_item_seq, ctx->B, ctx->split, ctx->n_items};
+    OKV_HIP(ctx, okv::launch_worklist_dump(bs, ctx->d_items_dump, ctx->compute));
+    OKV_HIP(ctx, hipStreamSynchronize(ctx->compute));
+    OKV_HIP(ctx, hipMemcpy(items, ctx->d_items_dump, (size_t)ctx->n_items * 3 * sizeof(int32_t), hipMemcpyDeviceToHost));
+    return OKV_OK;
+  }
+  // host walk: the same tables the device kernel builds, then the same decode
+  std::vector<int32_t> prefix(ctx->B + 1, 0), seq;
+  for (int32_t b = 0; b < ctx->B; ++b) {
+    int32_t cnt = (ctx->h_ctx_lens[b] + ctx->split - 1) / ctx->split;
+    prefix[b + 1] = prefix[b] + cnt;
+    seq.insert(seq.end(), cnt, b);
+  }
+  for (int32_t it = 0; it < ctx->n_items; ++it) {
+    okv::ItemRange r = okv::decode_item(it, seq.data(), prefix.data(), ctx->h_ctx_lens.data(), ctx->split);
+    items[it * 3 + 0] = r.b, items[it * 3 + 1] = r.lo, items[it * 3 + 2] = r.hi;
+  }
+  return OKV_OK;
+}
+
+int okv_profile_enable(okv_ctx *ctx, int32_t on) {
+  if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
+  ctx->profile = on != 0;
+  return OKV_OK;
+}
+
+int okv_profile_read(okv_ctx *ctx, double *attn_ms, int64_t *attn_launches) {
+  if (!ctx || !attn_ms || !attn_launches) return fail(ctx, OKV_EINVAL, "NULL argument");
+  OKV_HIP(ctx, hipStreamSynchronize(ctx->compute));
+  double total = 0;
+  for (size_t i = 0; i < ctx->prof_used; ++i) {
+    float ms = 0;
+    OKV_HIP(ctx, hipEventElapsedTime(&ms, ctx->prof_events[i].first, ctx->prof_events[i].second));
+    total += ms;
+  }
+  *attn_ms = total;
+  *attn_launches = (int64_t)ctx->prof_used;
+  ctx->prof_used = 0;
+  return OKV_OK;
+}
+
+int okv_measure_h2d(void *dst, const void *src, int64_t bytes, int32_t reps, void *stream, double *gbps_median) {
+  if (!dst || !src || bytes < 1 || reps < 1 || !gbps_median) return fail(nullptr, OKV_EINVAL, "okv_measure_h2d: bad argument");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipEvent_t e0, e1;
+  OKV_HIP(nullptr, hipEventCreate(&e0));
+  OKV_HIP(nullptr, hipEventCreate(&e1));
+  std::vector<double> rates;
+  int rc = OKV_OK;
+  for (int32_t i = 0; i < reps + 1 && rc == OKV_OK; ++i) {            // the first copy is a warm-up
+    hipError_t e = hipEventRecord(e0, st);
+    if (e == hipSuccess) e = hipMemcpyAsync(dst, src, (size_t)bytes, hipMemcpyHostToDevice, st);
+    if (e == hipSuccess) e = hipEventRecord(e1, st);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e != hipSuccess) rc = fail(nullptr, OKV_EHIP, "okv_measure_h2d: %s", hipGetErrorString(e));
+    else if (i > 0) rates.push_back((double)bytes / (ms * 1e-3) / 1e9);
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (rc) return rc;
+  std::sort(rates.begin(), rates.end());
+  *gbps_median = rates[rates.size() / 2];
+  return OKV_OK;
+}
+
+int okv_probe_copy(void *dst, const void *src, int64_t bytes, void *stream) {
+  if (!dst || !src || bytes < 0 || bytes % 16 || !aligned16(dst) || !aligned16(src))
+    return fail(nullptr, OKV_EINVAL, "okv_probe_copy: bad argument");
+  OKV_HIP(nullptr, okv::launch_probe_copy(dst, src, bytes, static_cast<hipStream_t>(stream)));
+  return OKV_OK;
+}
+
+int okv_probe_read(const void *src, int64_t bytes, void *sink, void *stream) {
+  if (!src || !sink || bytes < 0 || bytes % 16 || !aligned16(src)) return fail(nullptr, OKV_EINVAL, "okv_probe_read: bad argument");
+  OKV_HIP(nullptr, okv::launch_probe_read(src, bytes, sink, static_cast<hipStream_t>(stream)));
+  return OKV_OK;
+}
+
+}  // extern "C"

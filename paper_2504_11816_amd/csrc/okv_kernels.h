@@ -1,0 +1,60 @@
+// Kernel launchers of the okv library (gfx950).  Plain structs and pointers;
+// the C ABI in okv_api.hip validates shapes before anything here is called.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace okv {
+
+// Shape of one layer's pool and of the batch, shared by all kernels.
+struct PoolShape {
+  int32_t H, G, D;         // query heads, KV heads, head dim
+  int32_t paged;           // 1: block table lookup, 0: sequence b owns slice b
+  int32_t log2_T;          // paged: log2(block tokens)
+  int32_t tcap;            // tokens per pool slice: T (paged) or max_ctx (contiguous)
+  int32_t max_blocks;      // paged: columns of the block table
+};
+
+struct BatchState {        // device arrays owned by the context
+  const int32_t *block_table;   // [B][max_blocks]
+  const int32_t *ctx_lens;      // [B]
+  const int32_t *chunk_prefix;  // [B + 1]
+  const int32_t *item_seq;      // [n_items]
+  int32_t B;
+  int32_t split_tokens;
+  int32_t n_items;
+};
+
+struct AttnLaunch {
+  PoolShape shape;
+  BatchState batch;
+  const void *q;           // fp16 [B][H][D]
+  const void *pool;        // the layer's KV pool (HBM: resident pool or staging buffer)
+  void *out;               // [B][H][D] fp16 or fp32
+  float *part_o;           // [n_items * H][D]
+  float *part_ml;          // [n_items * H][2]  (max in log2 units, sum)
+  int32_t out_fp32;
+  int32_t need_merge;      // some sequence has more than one item
+};
+
+// Split-K partial attention followed, if needed, by the merge of the partials.
+hipError_t launch_decode_attn(const AttnLaunch &a, hipStream_t stream,
+                              hipEvent_t ev_begin, hipEvent_t ev_end);
+
+// ctx_lens[b] += inc; rebuilds chunk_prefix and item_seq for split size S.
+hipError_t launch_step_advance(int32_t *ctx_lens, int32_t *chunk_prefix, int32_t *item_seq,
+                               int32_t B, int32_t S, int32_t inc, hipStream_t stream);
+
+// Scatter of one step's K/V rows into pool_a and (if not NULL) pool_b.
+hipError_t launch_append(const PoolShape &shape, const int32_t *block_table,
+                         const int32_t *ctx_lens, int32_t B, const void *k_new,
+                         const void *v_new, void *pool_a, void *pool_b, hipStream_t stream);
+
+// items[it] = (b, lo, hi) decoded on the device.
+hipError_t launch_worklist_dump(const BatchState &batch, int32_t *items, hipStream_t stream);
+
+hipError_t launch_probe_copy(void *dst, const void *src, int64_t bytes, hipStream_t stream);
+hipError_t launch_probe_read(const void *src, int64_t bytes, void *sink, hipStream_t stream);
+
+}  // namespace okv

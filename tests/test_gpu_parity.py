@@ -1,0 +1,329 @@
+"""GPU parity: the HIP path through the C ABI against the fp64 CPU oracle,
+element by element, on seeded inputs.  Tolerance: max abs error <= 2e-3 and
+per-vector relative L2 error <= 1e-2 (fp16 KV, fp32 accumulation); integer
+work (work list, append scatter, lengths) bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as oa
+from oracle import kv_layout, worklist
+from paper_2504_11816_amd import binding, synth
+from paper_2504_11816_amd.harness import Stack
+
+from gpu_util import assert_close, build_stack, make_inputs, oracle_pairs, run_and_check
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# ---- the small configuration in full ------------------------------------------------
+
+@pytest.mark.parametrize("T", [0, 16])
+@pytest.mark.parametrize("out_dtype", [0, 1])
+def test_cfg1_single_layer_all_outputs(T, out_dtype):
+    say(f"cfg1 T={T} out_dtype={out_dtype}")
+    st = build_stack(L=1, H=8, G=8, d=64, T=T, ctx_before=[255] * 4, cap_tokens=256, out_dtype=out_dtype)
+    run_and_check(st, n_steps=1)
+    assert st.ctx.okv_get_ctx_lens().tolist() == [256] * 4
+    st.close()
+
+
+# ---- several tiles, ragged tails, every head grouping --------------------------------
+
+@pytest.mark.parametrize("d", [64, 128])
+@pytest.mark.parametrize("H,G", [(4, 4), (4, 2), (8, 2), (8, 1)])
+@pytest.mark.parametrize("T", [0, 16, 64])
+def test_ragged_contexts_all_groupings(d, H, G, T):
+    say(f"ragged d={d} H={H} G={G} T={T}")
+    ctx = [0, 14, 15, 16, 31, 130, 299, 700]       # after the append: 1, 15, 16, 17, 32, 131, 300, 701
+    st = build_stack(L=2, H=H, G=G, d=d, T=T, ctx_before=ctx, cap_tokens=704, out_dtype=1, seed=3)
+    run_and_check(st, n_steps=2, seed=5)
+    st.close()
+
+
+@pytest.mark.parametrize("split", [1, 7, 16, 100, 128, 256, 1024])
+def test_result_does_not_depend_on_the_split_size(split):
+    say(f"split={split}")
+    ctx = [9, 127, 128, 300, 513]
+    for T in (0, 16):
+        st = build_stack(L=1, H=4, G=2, d=128, T=T, ctx_before=ctx, cap_tokens=544, out_dtype=1, seed=7,
+                         split_tokens=1024)
+        ref = run_and_check(st, n_steps=1, seed=9)[0][0]
+        st.close()
+        st = build_stack(L=1, H=4, G=2, d=128, T=T, ctx_before=ctx, cap_tokens=544, out_dtype=1, seed=7,
+                         split_tokens=split)
+        assert st.ctx.okv_get_split_tokens() == split
+        got = run_and_check(st, n_steps=1, seed=9)[0][0]
+        st.close()
+        # one split versus many: equal up to fp32 summation order
+        rel = np.abs(got - ref).max() / np.abs(ref).max()
+        assert rel < 2e-5, rel
+
+
+def test_paged_equals_contiguous_on_the_same_logical_kv_bit_for_bit():
+    say("paged == contiguous")
+    B, H, G, d, T, C = 3, 4, 2, 128, 16, 320
+    ctx = np.array([16, 250, 303], dtype=np.int32)
+    stc = build_stack(L=1, H=H, G=G, d=d, T=0, ctx_before=ctx, cap_tokens=C, out_dtype=1, seed=11)
+    pool_c = stc.read_pool(0).reshape(B, 2, G, C, d)
+    stp = build_stack(L=1, H=H, G=G, d=d, T=T, ctx_before=ctx, cap_tokens=C, out_dtype=1, seed=12,
+                      shuffle_seed=5)
+    # write the contiguous run's logical KV into the paged pool through the table
+    pool_p = stp.read_pool(0).reshape(stp.blocks_per_layer, 2, G, T, d)
+    for b in range(B):
+        for i in range(C):
+            blk = stp.block_table[b, i // T]
+            pool_p[blk, :, :, i % T, :] = pool_c[b, :, :, i, :]
+    stp.pools[0].copy_(torch.from_numpy(pool_p.reshape(-1)))
+    torch.cuda.synchronize()
+    outs = []
+    for st in (stc, stp):
+        st.ctx.okv_set_split_tokens(128)
+        q, k, v, out = make_inputs(st, 21, 0, st.device)
+        st.step(q, k, v, out)
+        st.synchronize()
+        outs.append(out[0].cpu().numpy())
+    np.testing.assert_array_equal(outs[0], outs[1])
+    # and a second shuffle of the physical blocks changes nothing either
+    stp2 = build_stack(L=1, H=H, G=G, d=d, T=T, ctx_before=ctx, cap_tokens=C, out_dtype=1, seed=13,
+                       shuffle_seed=99)
+    pool_p2 = stp2.read_pool(0).reshape(stp2.blocks_per_layer, 2, G, T, d)
+    for b in range(B):
+        for i in range(C):
+            pool_p2[stp2.block_table[b, i // T], :, :, i % T, :] = pool_c[b, :, :, i, :]
+    stp2.pools[0].copy_(torch.from_numpy(pool_p2.reshape(-1)))
+    torch.cuda.synchronize()
+    stp2.ctx.okv_set_split_tokens(128)
+    q, k, v, out = make_inputs(stp2, 21, 0, stp2.device)
+    stp2.step(q, k, v, out)
+    stp2.synchronize()
+    np.testing.assert_array_equal(out[0].cpu().numpy(), outs[0])
+    for st in (stc, stp, stp2):
+        st.close()
+
+
+# ---- closed forms on the GPU ------------------------------------------------------------
+
+def test_closed_forms_on_gpu():
+    say("closed forms")
+    B, H, G, d = 2, 4, 4, 128
+    # context 1: the output is the appended value row, exactly
+    st = build_stack(L=1, H=H, G=G, d=d, T=16, ctx_before=[0, 0], cap_tokens=64, out_dtype=0, seed=31)
+    q, k, v, out = make_inputs(st, 33, 0, st.device)
+    st.step(q, k, v, out)
+    st.synchronize()
+    np.testing.assert_array_equal(out[0].cpu().numpy(), v[0].cpu().numpy())
+    st.close()
+    # identical keys: the mean of the value rows; constant values: that constant
+    n = 77
+    st = build_stack(L=1, H=H, G=G, d=d, T=0, ctx_before=[n - 1, n - 1], cap_tokens=80, out_dtype=1, seed=35)
+    pool = st.read_pool(0).reshape(B, 2, G, st.max_ctx, d)
+    key = synth.randn_f16_numpy((B, G, d), 36)
+    pool[:, 0, :, :, :] = key[:, :, None, :]
+    pool[1, 1] = np.float16(0.625)
+    st.pools[0].copy_(torch.from_numpy(pool.reshape(-1)))
+    q, k, v, out = make_inputs(st, 37, 0, st.device)
+    k[0].copy_(torch.from_numpy(key))
+    v[0][1] = 0.625
+    torch.cuda.synchronize()
+    st.step(q, k, v, out)
+    st.synchronize()
+    got = out[0].cpu().numpy()
+    vals = st.read_pool(0).reshape(B, 2, G, st.max_ctx, d)[:, 1, :, :n, :].astype(np.float64)
+    np.testing.assert_allclose(got[0], vals[0].mean(axis=1), rtol=2e-6, atol=2e-6)
+    np.testing.assert_allclose(got[1], np.full((H, d), 0.625), rtol=1e-6)
+    st.close()
+
+
+def test_unused_slots_full_of_nan_do_not_leak():
+    say("NaN in unused slots")
+    ctx = [4, 21, 40]
+    for T in (0, 16):
+        st = build_stack(L=1, H=4, G=2, d=128, T=T, ctx_before=ctx, cap_tokens=64, out_dtype=1, seed=41)
+        good = run_and_check(st, n_steps=1, seed=43)[0][0]
+        st.close()
+        st = build_stack(L=1, H=4, G=2, d=128, T=T, ctx_before=ctx, cap_tokens=64, out_dtype=1, seed=41)
+        pool = st.read_pool(0)
+        lay = st.layout()
+        keep = np.zeros(pool.shape, dtype=bool)
+        for b, n in enumerate(ctx):
+            for kv in range(2):
+                for g in range(2):
+                    for i in range(n):
+                        off = kv_layout.token_row_offset(lay, b, kv, g, i)
+                        keep[off:off + 128] = True
+        pool.view(np.uint16)[~keep] = 0x7E00          # fp16 quiet NaN everywhere that holds no token
+        st.pools[0].copy_(torch.from_numpy(pool))
+        torch.cuda.synchronize()
+        got = run_and_check(st, n_steps=1, seed=43)[0][0]
+        st.close()
+        np.testing.assert_array_equal(got, good)
+
+
+# ---- integer work: bit-exact --------------------------------------------------------------
+
+def test_worklist_on_device_matches_host_and_oracle():
+    say("work list")
+    ctx = synth.ragged_ctx_lens(37, 1, 900, 51)
+    st = build_stack(L=1, H=2, G=2, d=64, T=16, ctx_before=ctx, cap_tokens=1024, seed=53, split_tokens=1)
+    for split in (0, 1, 5, 16, 128, 333, 1024):
+        st.ctx.okv_set_split_tokens(split)
+        S = st.ctx.okv_get_split_tokens()
+        host = st.ctx.okv_worklist(from_device=False)
+        dev = st.ctx.okv_worklist(from_device=True)
+        want = np.array(worklist.expected_items(ctx, S), dtype=np.int32)
+        np.testing.assert_array_equal(host, want)
+        np.testing.assert_array_equal(dev, want)
+        assert worklist.check_tiling([tuple(r) for r in dev], ctx)
+    # after a step every sequence is one token longer, on both sides
+    st.ctx.okv_set_split_tokens(100)
+    q, k, v, out = make_inputs(st, 55, 0, st.device)
+    st.step(q, k, v, out)
+    np.testing.assert_array_equal(st.ctx.okv_get_ctx_lens(), ctx + 1)
+    dev = st.ctx.okv_worklist(from_device=True)
+    np.testing.assert_array_equal(dev, np.array(worklist.expected_items(ctx + 1, 100), dtype=np.int32))
+    st.close()
+
+
+@pytest.mark.parametrize("T", [0, 16, 32])
+@pytest.mark.parametrize("on_host", [[0, 0], [1, 0], [1, 1]])
+def test_append_scatter_is_bit_exact(T, on_host):
+    say(f"append T={T} on_host={on_host}")
+    ctx = np.array([0, 15, 16, 31, 47], dtype=np.int32)
+    st = build_stack(L=2, H=4, G=2, d=64, T=T, ctx_before=ctx, cap_tokens=64, on_host=on_host, seed=61)
+    want = [st.read_pool(l) for l in range(2)]
+    n = ctx.copy()
+    for step in range(4):
+        q, k, v, out = make_inputs(st, 63, step, st.device)
+        st.step(q, k, v, out)
+        st.synchronize()
+        n += 1
+        for l in range(2):
+            kv_layout.append_scatter(want[l], st.layout(), n, k[l].cpu().numpy(), v[l].cpu().numpy())
+    for l in range(2):
+        got = st.read_pool(l)
+        np.testing.assert_array_equal(got.view(np.uint16), want[l].view(np.uint16))
+    st.close()
+
+
+# ---- offloaded layers: residency never changes the result -------------------------------------
+
+def test_streaming_is_bit_identical_to_resident_and_matches_oracle():
+    say("streaming")
+    L = 6
+    ctx = [100, 257, 31, 480]
+    plans = {
+        "resident": [0] * L,
+        "half": binding.kv_offload_plan(L, 1, 2)[0].tolist(),
+        "all": [1] * L,
+        "one": [0, 0, 1, 0, 0, 0],
+        "sixty": binding.kv_offload_plan(L, 3, 5)[0].tolist(),
+    }
+    ref = None
+    for name, on_host in plans.items():
+        for n_staging in ((2, 1) if name in ("half", "all") else (2,)):
+            say(f"  plan {name} {on_host} staging {n_staging}")
+            st = build_stack(L=L, H=4, G=2, d=128, T=16, ctx_before=ctx, cap_tokens=512, on_host=on_host,
+                             out_dtype=0, seed=71, n_staging=n_staging)
+            for s in st.staging:
+                if s is not None:
+                    s.fill_(float("nan"))             # a stale or missing copy poisons the output
+            torch.cuda.synchronize()
+            outs = run_and_check(st, n_steps=3, seed=73, pairs=[(0, 0), (1, 3), (2, 1), (3, 2)])
+            st.close()
+            if ref is None:
+                ref = outs
+            else:
+                for step in range(3):
+                    for l in range(L):
+                        np.testing.assert_array_equal(outs[step][l], ref[step][l])
+
+
+# ---- failure handling, forced from the host ------------------------------------------------------
+
+def test_error_paths():
+    say("error paths")
+    st = build_stack(L=2, H=4, G=2, d=64, T=16, ctx_before=[10, 20], cap_tokens=32, seed=81)
+    c = st.ctx
+    q, k, v, out = make_inputs(st, 83, 0, st.device)
+
+    def code(fn, *a):
+        with pytest.raises(binding.OkvError) as e:
+            fn(*a)
+        return e.value.code
+
+    assert code(c.kv_append, 0, k[0], v[0]) == binding.OKV_ESTATE            # outside a step
+    c.okv_step_begin()
+    assert code(c.okv_step_begin) == binding.OKV_ESTATE
+    assert code(c.decode_attn, 0, q[0], out[0]) == binding.OKV_ESTATE         # attention before append
+    assert code(c.kv_append, 1, k[1], v[1]) == binding.OKV_ESTATE             # layer out of order
+    assert code(c.kv_append, 5, k[0], v[0]) == binding.OKV_EINVAL
+    assert code(c.kv_append, 0, None, v[0]) == binding.OKV_EINVAL
+    assert code(c.okv_step_end) == binding.OKV_ESTATE                         # layers missing
+    for l in range(2):
+        c.kv_append(l, k[l], v[l])
+        c.decode_attn(l, q[l], out[l])
+    c.okv_step_end()
+    # capacity: 32 tokens; 20 + 1 stored, 11 more fit
+    st.set_batch([10, 32], st.block_table)
+    assert code(c.okv_step_begin) == binding.OKV_ENOSPC
+    np.testing.assert_array_equal(c.okv_get_ctx_lens(), [10, 32])            # nothing changed
+    tbl = st.block_table.copy()
+    tbl[0, 1] = -1
+    st.set_batch([16, 5], tbl)
+    assert code(c.okv_step_begin) == binding.OKV_ENOSPC                       # next block not allocated
+    tbl[0, 1] = tbl[1, 0]
+    assert code(st.set_batch, [3, 5], tbl) == binding.OKV_EINVAL              # block shared
+    tbl[0, 1] = 10 ** 6
+    assert code(st.set_batch, [3, 5], tbl) == binding.OKV_EINVAL              # block id out of range
+    assert code(st.set_batch, [3, 33], st.block_table) == binding.OKV_EINVAL  # beyond capacity
+    assert code(c.okv_set_split_tokens, 16 * 64 + 16) == binding.OKV_EINVAL   # item would span > 64 blocks
+    st.close()
+    # creation: staging smaller than a layer, both / neither pool given
+    with pytest.raises(binding.OkvError) as e:
+        ws = torch.empty(1 << 20, dtype=torch.uint8, device="cuda")
+        pool = torch.empty(1 << 16, dtype=torch.float16, device="cuda")
+        binding.Context(n_layers=1, n_q_heads=4, n_kv_heads=2, head_dim=64, block_tokens=0, max_batch=2,
+                        max_ctx=64, dev_pool=[pool], host_pool=[pool], workspace=ws, workspace_bytes=1 << 20)
+    assert e.value.code == binding.OKV_EINVAL
+
+
+# ---- the benchmark shapes at full size, sampled -----------------------------------------------------
+
+def _sampled_full_size(name, B, H, G, T, ctx_before, cap, on_host, pairs, steps=2, L=2):
+    say(f"full size {name}")
+    st = Stack(L=L, H=H, G=G, d=128, B=B, T=T, cap_tokens=cap, on_host=on_host, out_dtype=0)
+    for l in range(L):
+        st.fill_pool(l, synth.stream_seed(91, synth.TENSOR_POOL, l))
+    table = None
+    if T:
+        table = synth.shuffled_block_table([st.cap_tokens] * B, T, st.blocks_per_layer, 93,
+                                           max_blocks_per_seq=st.max_blocks)
+    st.set_batch(ctx_before, table)
+    say(f"  split {st.ctx.okv_get_split_tokens()}")
+    run_and_check(st, n_steps=steps, seed=95, pairs=pairs)
+    st.close()
+
+
+def test_full_size_cfg2_contiguous_mha_sampled():
+    # 32 heads x 128, batch 32, contexts 513 and 514 of capacity 1024; two of the 32 layers
+    _sampled_full_size("cfg2", 32, 32, 32, 0, [512] * 32, 1024, None, [(0, 0), (13, 7), (31, 31), (5, 18)])
+
+
+def test_full_size_cfg2_last_steps_sampled():
+    _sampled_full_size("cfg2 end", 32, 32, 32, 0, [1022] * 32, 1024, None, [(0, 31), (31, 0), (17, 9)])
+
+
+def test_full_size_cfg3_paged_half_offloaded_sampled():
+    # batch 64, context 2048, 16-token blocks, one resident and one host layer (2 GiB each)
+    _sampled_full_size("cfg3", 64, 32, 32, 16, [2047] * 64, 2064, [0, 1], [(0, 0), (63, 31), (20, 11)])
+
+
+def test_full_size_cfg4_gqa_ragged_sampled():
+    ctx = synth.ragged_ctx_lens(128, 512, 4096, 97) - 1
+    lo, hi = int(np.argmin(ctx)), int(np.argmax(ctx))
+    _sampled_full_size("cfg4", 128, 32, 8, 16, ctx, 4112, None, [(lo, 0), (hi, 31), (64, 13), (1, 20)])

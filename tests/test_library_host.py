@@ -1,0 +1,121 @@
+"""The C-ABI library without a GPU: it loads, exports what the header declares,
+and its pure host functions (offload plan, pipeline schedule) agree with the
+oracle.  No compute call is made here."""
+import os
+import re
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import offload_plan, pipeline_sim
+from paper_2504_11816_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_functions():
+    text = open(os.path.join(ROOT, "include", "okv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    names = re.findall(r"\b([a-z_0-9]+)\s*\(", text)
+    return sorted({n for n in names if n.startswith("okv_") or n in ("kv_append", "decode_attn", "kv_offload_plan")})
+
+
+def test_library_loads_and_exports_every_declared_symbol():
+    lib = binding.lib()
+    decl = declared_functions()
+    assert len(decl) >= 20
+    for name in decl:
+        assert hasattr(lib, name), f"{name} is declared in okv.h but not exported"
+    assert sorted(binding.EXPORTS) == decl
+
+
+def test_plan_matches_oracle_brute_force():
+    for L in range(1, 65):
+        for den in range(1, 33):
+            for num in range(0, den + 1):
+                on, k = binding.kv_offload_plan(L, num, den)
+                want, wk = offload_plan.plan_layers(L, Fraction(num, den))
+                assert k == wk and on.tolist() == want, (L, num, den)
+    for L in (1, 7, 32, 64):
+        for den in (33, 47, 64):
+            for num in range(0, den + 1):
+                on, k = binding.kv_offload_plan(L, num, den)
+                want, wk = offload_plan.plan_layers(L, Fraction(num, den))
+                assert k == wk and on.tolist() == want, (L, num, den)
+
+
+def test_plan_with_byte_sized_ratio_and_errors():
+    # C_off given as bytes: 1 - avail / total for a 64 GiB cache with 37 GiB available
+    total, avail = 64 << 30, 37 << 30
+    on, k = binding.kv_offload_plan(32, total - avail, total)
+    want, wk = offload_plan.plan_layers(32, offload_plan.c_off_case3(avail, total))
+    assert (on.tolist(), k) == (want, wk)
+    for bad in ((0, 1, 2), (4, -1, 2), (4, 3, 2), (4, 1, 0)):
+        with pytest.raises(binding.OkvError) as e:
+            binding.kv_offload_plan(*bad)
+        assert e.value.code == binding.OKV_EINVAL
+
+
+def test_plan_from_bytes_matches_oracle():
+    LB = 4096
+    for L in (1, 2, 5, 32):
+        for avail in list(range(0, (L + 2) * LB, 509)) + [LB, 2 * LB, L * LB, L * LB - 1]:
+            st, on, k, ns = offload_plan.plan_from_bytes(L, LB, avail)
+            if st == "infeasible":
+                with pytest.raises(binding.OkvError) as e:
+                    binding.okv_plan_from_bytes(L, LB, avail)
+                assert e.value.code == binding.OKV_ENOSPC
+            else:
+                got_on, got_k, got_ns = binding.okv_plan_from_bytes(L, LB, avail)
+                assert (got_on.tolist(), got_k, got_ns) == (on, k, ns), (L, avail)
+
+
+@pytest.mark.parametrize("on_host", [[0, 1, 0, 1], [1, 1, 1], [0, 0, 1], [1], [0, 0], [1, 0, 1, 1, 0, 1],
+                                     [0, 1] * 16, [1] * 32])
+@pytest.mark.parametrize("n_staging", [1, 2])
+def test_schedule_trace_replays_without_hazard(on_host, n_staging):
+    trace = binding.okv_schedule_trace(on_host, n_staging, 5)
+    for seed in range(6):
+        for cs, ks in ((1.0, 1.0), (25.0, 0.04), (0.04, 25.0)):
+            pipeline_sim.replay(trace, on_host, seed=seed, copy_scale=cs, compute_scale=ks)
+    k = sum(on_host)
+    copies = [op for op in trace if op[0] == pipeline_sim.COPY]
+    if k:
+        depth = min(n_staging, k)
+        assert len(copies) == 5 * k + depth            # every consumption refills, `depth` run ahead
+        assert [c[4] for c in copies] == list(range(len(copies)))
+        hl = [l for l, v in enumerate(on_host) if v]
+        assert all(c[2] == hl[c[4] % k] and c[3] == c[4] % depth for c in copies)
+    else:
+        assert not copies
+
+
+def test_schedule_keeps_the_link_busy_when_copies_dominate():
+    on_host = [0, 1] * 16
+    trace = binding.okv_schedule_trace(on_host, 2, 6)
+    r = pipeline_sim.replay(trace, on_host, seed=0, copy_scale=60.0, compute_scale=0.05)
+    assert r["copy_busy"] / r["copy_span"] > 0.99
+
+
+def test_schedule_trace_argument_errors():
+    with pytest.raises(binding.OkvError):
+        binding.okv_schedule_trace([0, 1], 0, 2)          # host layer but no staging buffer
+    assert binding.okv_schedule_trace([0, 0], 0, 2)       # fine without host layers
+
+
+def test_size_queries_and_shape_errors():
+    cfg = binding.make_config(n_layers=32, n_q_heads=32, n_kv_heads=32, head_dim=128, block_tokens=16,
+                              max_batch=64, max_blocks_per_seq=128, blocks_per_layer=8192)
+    assert binding.okv_layer_pool_bytes(cfg) == 2 << 30            # 2 GiB per layer (Table II per-layer size)
+    cfg = binding.make_config(n_layers=32, n_q_heads=32, n_kv_heads=32, head_dim=128, block_tokens=0,
+                              max_batch=32, max_ctx=1024)
+    assert binding.okv_layer_pool_bytes(cfg) == 512 << 20
+    assert binding.okv_workspace_bytes(cfg) == 32 * 8 * 32 * 130 * 4
+    for bad in (dict(head_dim=96), dict(n_q_heads=48), dict(block_tokens=24), dict(max_ctx=1000),
+                dict(n_layers=0), dict(out_dtype=3)):
+        kw = dict(n_layers=2, n_q_heads=8, n_kv_heads=8, head_dim=64, block_tokens=0, max_batch=4, max_ctx=256)
+        kw.update(bad)
+        with pytest.raises(binding.OkvError) as e:
+            binding.okv_layer_pool_bytes(binding.make_config(**kw))
+        assert e.value.code == binding.OKV_EINVAL
