@@ -1,0 +1,253 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode-attention hot path on one MI355X.
+
+A step is one decode step of the whole stack: for every layer, kv_append of
+the step's K/V rows followed by decode_attn over everything stored so far.
+The headline workload is the all-resident 32-layer stack (32 heads x 128,
+batch 32, prompt 512, 512 generated tokens, contiguous fp16 KV); an offloaded
+leg (paged KV, half of the layers streamed from pinned host memory) is timed
+after it and reported under "offload" in the same JSON line.
+
+Prints ONE JSON line.  `value` is decode tokens/s with all inputs already in
+HBM (resident layers) or pinned host memory (offloaded layers) when the timed
+region starts.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published peak
+PCIE5_X16_GBPS = 64.0       # nominal, one direction
+
+
+def log(msg):
+    print(msg, file=sys.stderr, flush=True)
+
+
+def fixed_inputs(st, seed):
+    """q / k_new / v_new per layer, drawn once and reused every step, plus outputs."""
+    import torch
+    from paper_2504_11816_amd import synth
+    dev = st.device
+    q = [synth.randn_f16_torch((st.B, st.H, st.d), synth.stream_seed(seed, synth.TENSOR_Q, l), dev) for l in range(st.L)]
+    k = [synth.randn_f16_torch((st.B, st.G, st.d), synth.stream_seed(seed, synth.TENSOR_KNEW, l), dev) for l in range(st.L)]
+    v = [synth.randn_f16_torch((st.B, st.G, st.d), synth.stream_seed(seed, synth.TENSOR_VNEW, l), dev) for l in range(st.L)]
+    out = [torch.empty((st.B, st.H, st.d), dtype=st.out_torch_dtype, device=dev) for _ in range(st.L)]
+    torch.cuda.synchronize()
+    return q, k, v, out
+
+
+def kv_bytes_of_steps(ctx0, steps, G, d, L):
+    """Algorithmic KV bytes read over `steps` decode steps that start from
+    ctx0 stored tokens: sum over steps, layers and sequences of n_b * 2*G*d*2."""
+    ctx0 = np.asarray(ctx0, dtype=np.int64)
+    per_tok = 2 * G * d * 2
+    total = 0
+    for s in range(1, steps + 1):
+        total += int((ctx0 + s).sum()) * per_tok * L
+    return total
+
+
+def timed_steps(st, ctx0, table, inputs, steps, warmup):
+    """W untimed steps, state reset, then exactly K timed steps."""
+    import torch
+    q, k, v, out = inputs
+    st.set_batch(ctx0, table)
+    for _ in range(warmup):
+        st.step(q, k, v, out)
+    st.synchronize()
+    st.set_batch(ctx0, table)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        st.step(q, k, v, out)
+    st.synchronize()
+    torch.cuda.synchronize()
+    return time.perf_counter() - t0
+
+
+def kernel_time(st, ctx0, table, inputs, steps):
+    """Same K steps again with every split-K kernel bracketed by HIP events on
+    the compute stream: summed kernel time (s) and number of launches."""
+    q, k, v, out = inputs
+    st.set_batch(ctx0, table)
+    st.ctx.okv_profile_enable(True)
+    for _ in range(steps):
+        st.step(q, k, v, out)
+    ms, n = st.ctx.okv_profile_read()
+    st.ctx.okv_profile_enable(False)
+    return ms * 1e-3, n
+
+
+def cpu_baseline(st, layer, ctx_now, q_layer, budget_s=15.0):
+    """The fp64 oracle, as it stands, on this host: (b, h) pairs of one layer of
+    the same workload until the time budget is used."""
+    from threadpoolctl import threadpool_limits
+    from oracle import attention as oa
+    pool = st.read_pool(layer)
+    qn = q_layer.cpu().numpy()
+    layout = st.layout()
+    pairs = [(b, h) for b in range(st.B) for h in range(st.H)]
+    done, tokens = 0, 0
+    with threadpool_limits(limits=1):
+        t0 = time.perf_counter()
+        for (b, h) in pairs:
+            oa.decode_attn(qn, pool, layout, ctx_now, st.H, sample=[(b, h)])
+            done += 1
+            tokens += int(ctx_now[b])
+            if time.perf_counter() - t0 > budget_s:
+                break
+        dt = time.perf_counter() - t0
+    # one (b, h) pair of one layer is 1 / (H * L) of a generated token's attention
+    pair_rate = done / dt
+    tok_rate = pair_rate / (st.H * st.L_full)
+    kv_gbps = tokens * 2 * st.d * 2 / dt / 1e9
+    return {"value": tok_rate, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+            "kv_gbps": kv_gbps,
+            "sample": f"{done} (sequence, head) pairs of one layer at context {int(np.mean(ctx_now))}, "
+                      f"{dt:.1f} s of single-thread numpy fp64, scaled to {st.H} heads x {st.L_full} layers"}
+
+
+def run_resident(args):
+    import torch
+    from paper_2504_11816_amd import synth
+    from paper_2504_11816_amd.harness import Stack
+    w = dict(synth.WORKLOADS[args.workload])
+    steps = args.steps if args.steps else w["steps"]
+    L, H, G, d, B, T = w["L"], w["H"], w["G"], w["d"], w["B"], w["T"]
+    if w["ragged"]:
+        ctx_first = synth.ragged_ctx_lens(B, w["ragged"][0], w["ragged"][1], args.seed)
+    else:
+        ctx_first = np.full(B, w["ctx"], dtype=np.int32)
+    ctx0 = ctx_first - 1                                   # stored before the first timed step
+    cap = int(ctx0.max()) + max(steps, args.warmup) + 1
+    on_host = None
+    if w["c_off"][0]:
+        from paper_2504_11816_amd import binding
+        on_host = binding.kv_offload_plan(L, w["c_off"][0], w["c_off"][1])[0]
+    log(f"[bench] {args.workload}: L={L} H={H} G={G} d={d} B={B} T={T} ctx {int(ctx_first.min())}..{int(ctx_first.max())} "
+        f"steps={steps} capacity={cap}")
+    st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=cap, on_host=on_host, out_dtype=0)
+    st.L_full = L
+    for l in range(L):
+        st.fill_pool(l, synth.stream_seed(args.seed, synth.TENSOR_POOL, l))
+    table = None
+    if T:
+        table = synth.shuffled_block_table([st.cap_tokens] * B, T, st.blocks_per_layer, args.seed + 1,
+                                           max_blocks_per_seq=st.max_blocks)
+    inputs = fixed_inputs(st, args.seed)
+    log("[bench] pools filled; timing")
+    dt = timed_steps(st, ctx0, table, inputs, steps, args.warmup)
+    split = st.ctx.okv_get_split_tokens()
+    kv_bytes = kv_bytes_of_steps(ctx0, steps, G, d, L)
+    log(f"[bench] {steps} steps in {dt * 1e3:.1f} ms, split {split}")
+    k_s, k_n = kernel_time(st, ctx0, table, inputs, steps)
+    log(f"[bench] split-K kernel: {k_n} launches, {k_s / max(k_n, 1) * 1e6:.1f} us average")
+    res = {
+        "tokens_per_s": B * steps / dt, "ms_per_step": dt / steps * 1e3, "kv_gbps": kv_bytes / dt / 1e9,
+        "kernel_gbps": kv_bytes / k_s / 1e9, "kernel_avg_us": k_s / max(k_n, 1) * 1e6, "kernel_launches": k_n,
+        "kv_bytes_per_launch": kv_bytes / max(k_n, 1), "split_tokens": split, "steps": steps,
+        "B": B, "L": L, "H": H, "G": G, "d": d, "T": T,
+        "ctx_first": int(ctx_first.max()), "ctx_last": int(ctx_first.max()) + steps - 1,
+    }
+    cpu = None
+    if not args.no_cpu:
+        log("[bench] timing the CPU oracle on a sample")
+        mid = ctx0 + steps                                  # lengths as the run left them
+        cpu = cpu_baseline(st, 0, mid, inputs[0][0], args.cpu_seconds)
+    st.close()
+    del st
+    torch.cuda.empty_cache()
+    return res, cpu
+
+
+def run_offload(args):
+    """Paged KV, half of the layers in pinned host memory, streamed per layer."""
+    import torch
+    from paper_2504_11816_amd import binding, synth
+    from paper_2504_11816_amd.harness import Stack
+    w = dict(synth.WORKLOADS["cfg3"])
+    L, H, G, d, B, T = w["L"], w["H"], w["G"], w["d"], args.offload_batch or w["B"], w["T"]
+    steps, warmup = args.offload_steps, 2
+    ctx0 = np.full(B, w["ctx"] - 1, dtype=np.int32)
+    cap = w["ctx"] + steps + warmup
+    on_host, n_off = binding.kv_offload_plan(L, w["c_off"][0], w["c_off"][1])
+    log(f"[bench] offload leg: B={B} ctx={w['ctx']} T={T} host layers {n_off}/{L} steps={steps}")
+    st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=cap, on_host=on_host, out_dtype=0)
+    for l in range(L):
+        st.fill_pool(l, synth.stream_seed(args.seed, synth.TENSOR_POOL, l))
+    table = synth.shuffled_block_table([st.cap_tokens] * B, T, st.blocks_per_layer, args.seed + 1,
+                                       max_blocks_per_seq=st.max_blocks)
+    inputs = fixed_inputs(st, args.seed)
+    host_layer = int(np.flatnonzero(on_host)[0])
+    link = binding.okv_measure_h2d(st.staging[0], st.pools[host_layer], min(st.pool_bytes, 2 << 30), 10,
+                                   st.h2d_stream.cuda_stream)
+    log(f"[bench] host-to-device link: {link:.1f} GB/s (plain hipMemcpyAsync, pinned, median of 10)")
+    dt = timed_steps(st, ctx0, table, inputs, steps, warmup)
+    per_tok = 2 * G * d * 2
+    link_bytes = sum(int((ctx0 + s).sum()) * per_tok * n_off for s in range(1, steps + 1))
+    kv_bytes = kv_bytes_of_steps(ctx0, steps, G, d, L)
+    res = {
+        "workload": "cfg3", "B": B, "ctx": w["ctx"], "host_layers": int(n_off), "layers": L, "steps": steps,
+        "tokens_per_s": B * steps / dt, "ms_per_step": dt / steps * 1e3, "kv_gbps": kv_bytes / dt / 1e9,
+        "link_gbps_measured": link, "link_gbps_nominal": PCIE5_X16_GBPS,
+        "link_gbps_achieved": link_bytes / dt / 1e9, "link_frac": link_bytes / dt / 1e9 / link,
+        "pinned_gib": n_off * st.pool_bytes / 2 ** 30,
+    }
+    log(f"[bench] offload leg: {res['ms_per_step']:.1f} ms/step, link {res['link_gbps_achieved']:.1f} GB/s "
+        f"= {100 * res['link_frac']:.1f}% of measured")
+    st.close()
+    del st
+    torch.cuda.empty_cache()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=0, help="decode steps to time (0 = the workload's own count)")
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg4"])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
+    ap.add_argument("--cpu-seconds", type=float, default=15.0)
+    ap.add_argument("--no-offload", action="store_true", help="skip the offloaded leg")
+    ap.add_argument("--offload-steps", type=int, default=6)
+    ap.add_argument("--offload-batch", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this library runs on one GPU; there is no multi-GPU path (--gpus 1 only)")
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    res, cpu = run_resident(args)
+    off = None if args.no_offload else run_offload(args)
+    line = {
+        "metric": "decode_attn_tokens_per_s", "value": res["tokens_per_s"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": res["steps"], "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload}: {res['L']} layers, {res['H']} q heads / {res['G']} kv heads x {res['d']}, "
+                               f"batch {res['B']}, context {res['ctx_first']}..{res['ctx_last']}, fp16 KV "
+                               f"{'paged T=%d' % res['T'] if res['T'] else 'contiguous'}, all resident",
+                   "split_tokens": res["split_tokens"]},
+        "kv_gbps": res["kv_gbps"], "hbm_frac": res["kv_gbps"] / HBM_PEAK_GBPS,
+        "roofline": {"bound": "hbm", "achieved": res["kernel_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+                     "frac": res["kernel_gbps"] / HBM_PEAK_GBPS, "traffic": None,
+                     "kernel": "attn_split_kernel", "avg_us": res["kernel_avg_us"],
+                     "launches": res["kernel_launches"], "bytes_per_launch": res["kv_bytes_per_launch"]},
+        "cpu_baseline": cpu,
+        "offload": off,
+    }
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

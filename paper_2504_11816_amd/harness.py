@@ -3,10 +3,48 @@
 PyTorch is used here only to own device / pinned-host memory and the two HIP
 streams; every computation is a call into libokv.so through binding.Context.
 """
+import ctypes
+
 import numpy as np
 import torch
 
 from . import binding, synth
+
+
+_hip = None
+
+
+def _hip_runtime():
+    global _hip
+    if _hip is None:
+        _hip = ctypes.CDLL("libamdhip64.so")
+        _hip.hipHostMalloc.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_size_t, ctypes.c_uint]
+        _hip.hipHostMalloc.restype = ctypes.c_int
+        _hip.hipHostFree.argtypes = [ctypes.c_void_p]
+        _hip.hipHostFree.restype = ctypes.c_int
+    return _hip
+
+
+class PinnedHalfBuffer:
+    """n fp16 elements of pinned, device-mapped host memory (hipHostMalloc of
+    exactly that size; torch's pinned allocator would round it up to a power of
+    two), viewed as a torch CPU tensor."""
+
+    def __init__(self, n_elems):
+        self.nbytes = n_elems * 2
+        p = ctypes.c_void_p(0)
+        rc = _hip_runtime().hipHostMalloc(ctypes.byref(p), self.nbytes, 0)
+        if rc != 0 or not p.value:
+            raise MemoryError(f"hipHostMalloc({self.nbytes}) failed with {rc}")
+        self.ptr = p.value
+        raw = (ctypes.c_char * self.nbytes).from_address(self.ptr)
+        self.tensor = torch.frombuffer(raw, dtype=torch.float16)
+
+    def free(self):
+        if self.ptr:
+            self.tensor = None
+            _hip_runtime().hipHostFree(ctypes.c_void_p(self.ptr))
+            self.ptr = 0
 
 
 class Stack:
@@ -42,10 +80,11 @@ class Stack:
         self.pool_bytes = binding.okv_layer_pool_bytes(shape)
         self.workspace_bytes = binding.okv_workspace_bytes(shape)
         n_el = self.pool_bytes // 2
-        self.pools = []
+        self.pools, self._pinned = [], []
         for l in range(L):
             if self.on_host[l]:
-                self.pools.append(torch.empty(n_el, dtype=torch.float16, pin_memory=True))
+                self._pinned.append(PinnedHalfBuffer(n_el))
+                self.pools.append(self._pinned[-1].tensor)
             else:
                 self.pools.append(torch.empty(n_el, dtype=torch.float16, device=self.device))
         any_host = bool(self.on_host.any())
@@ -135,3 +174,7 @@ class Stack:
 
     def close(self):
         self.ctx.close()
+        self.pools = []
+        for p in self._pinned:
+            p.free()
+        self._pinned = []
