@@ -175,6 +175,10 @@ int okv_step_end(okv_ctx *ctx);
  * decode steps).  For a host layer the rows are written both into the staged copy
  * (so this step's attention sees them) and into the host pool (so later steps do).
  *   k_new, v_new  DEVICE fp16 [B][G][d]
+ * The store is carried out by the same kernel launch as the layer's decode_attn:
+ * kv_append makes the compute stream wait for the layer's copy (host layers) and
+ * hands the rows to that launch, so k_new / v_new must stay valid until the work of
+ * decode_attn(layer) has finished, and the pool holds the rows from then on.
  * Within a step layers are visited in order 0 .. L-1, kv_append(l) before
  * decode_attn(l); anything else is OKV_ESTATE. */
 int kv_append(okv_ctx *ctx, int32_t layer, const void *k_new, const void *v_new);
@@ -215,7 +219,8 @@ int okv_worklist(okv_ctx *ctx, int32_t from_device, int32_t *items, int64_t max_
 /* Per-kernel timing.  While enabled every decode_attn brackets its split-K kernel
  * with HIP events on the compute stream.  okv_profile_read waits for the stream,
  * returns the summed kernel time (ms) and the number of launches since the last
- * read, and resets both. */
+ * read, and resets both.  The time an empty pair of event records takes on the
+ * same stream (median of 15, measured at the read) is subtracted per launch. */
 int okv_profile_enable(okv_ctx *ctx, int32_t on);
 int okv_profile_read(okv_ctx *ctx, double *attn_ms, int64_t *attn_launches);
 

@@ -7,7 +7,9 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libokv.so")
+# OKV_LIBRARY may name another build of the same library (e.g. one compiled with
+# different tuning macros); by default the in-tree build is used.
+LIB_PATH = os.environ.get("OKV_LIBRARY") or os.path.join(_HERE, "libokv.so")
 
 OKV_OK, OKV_EINVAL, OKV_ENOSPC, OKV_ESTATE, OKV_EHIP = 0, -1, -2, -3, -4
 _CODE_NAMES = {0: "OKV_OK", -1: "OKV_EINVAL", -2: "OKV_ENOSPC", -3: "OKV_ESTATE", -4: "OKV_EHIP"}

@@ -21,8 +21,7 @@ namespace {
 
 constexpr int kEventRing = 4;            // > copies in flight (at most 2)
 constexpr int32_t kMinAutoSplit = 128;   // smallest split size the library picks by itself
-constexpr int64_t kTargetUnits = 8192;   // wavefront-sized work items wanted per launch
-constexpr int64_t kMaxItemBlocks = 64;   // paged: blocks one work item may span (one id per lane)
+constexpr int64_t kTargetUnits = 1024;   // wavefront-sized work items wanted per launch (4 per CU)
 
 thread_local std::string g_error;        // failures that have no context to live in
 
@@ -49,6 +48,7 @@ struct okv_ctx {
   int64_t copy_bytes = 0;
 
   bool batch_set = false, in_step = false, appended = false;
+  const void *pending_k = nullptr, *pending_v = nullptr;   // rows of the current layer's kv_append
   int64_t step = 0;
   int32_t next_layer = 0;
   okv::Scheduler sched;
@@ -123,29 +123,18 @@ int64_t count_items(const int32_t *ctx, int32_t B, int32_t S) {
   return n;
 }
 
-// Largest power-of-two multiple of kMinAutoSplit that still yields kTargetUnits
-// wavefront items, and no more items than the workspace holds.
+// The fewest, longest work items that still give kTargetUnits wavefronts: S doubles
+// from kMinAutoSplit while the launch keeps that many (item, KV head) units; if even
+// whole sequences give enough units nothing is split and no merge pass is needed.
 int32_t choose_split(const okv_ctx *ctx, const std::vector<int32_t> &lens) {
   if (ctx->split_override) return ctx->split_override;
   if (ctx->cfg.split_tokens) return ctx->cfg.split_tokens;
   int32_t S = kMinAutoSplit;
   int32_t longest = 1;
   for (int32_t b = 0; b < ctx->B; ++b) longest = std::max(longest, lens[b]);
-  const int64_t S_max = ctx->cfg.block_tokens ? (int64_t)ctx->cfg.block_tokens * kMaxItemBlocks : (1 << 30);
-  while (S < longest && S * 2 <= S_max &&
-         count_items(lens.data(), ctx->B, S * 2) * ctx->cfg.n_kv_heads >= kTargetUnits)
-    S *= 2;
-  while (S * 2 <= S_max && count_items(lens.data(), ctx->B, S) > ctx->max_items) S *= 2;
+  while (S < longest && count_items(lens.data(), ctx->B, S * 2) * ctx->cfg.n_kv_heads >= kTargetUnits) S *= 2;
+  while (count_items(lens.data(), ctx->B, S) > ctx->max_items) S *= 2;
   return S;
-}
-
-// Paged pools: the split kernel keeps one block id per lane, so an item may touch at
-// most kMaxItemBlocks blocks (items start at multiples of S).
-bool split_fits_block_window(const okv_config *c, int64_t S) {
-  if (!c->block_tokens) return true;
-  const int64_t T = c->block_tokens;
-  const int64_t spanned = S % T == 0 ? S / T : (S + T - 1) / T + 1;
-  return spanned <= kMaxItemBlocks;
 }
 
 int exec_op(okv_ctx *ctx, const Op &op, const void *a0, const void *a1, void *out) {
@@ -158,11 +147,11 @@ int exec_op(okv_ctx *ctx, const Op &op, const void *a0, const void *a1, void *ou
       return OKV_OK;
     }
     case okv::OP_APPEND: {
+      // The rows are stored by the attention launch of the same layer (one kernel instead
+      // of two); here the compute stream only starts to wait for the layer's copy.
       if (op.wait_idx >= 0) OKV_HIP(ctx, hipStreamWaitEvent(ctx->compute, ctx->ready_ev[op.wait_idx % kEventRing], 0));
-      void *pool_a = op.buf >= 0 ? ctx->cfg.staging[op.buf] : ctx->dev_pool[op.layer];
-      void *pool_b = op.buf >= 0 ? ctx->host_pool[op.layer] : nullptr;
-      OKV_HIP(ctx, okv::launch_append(ctx->shape, ctx->d_block_table, ctx->d_ctx_lens, ctx->B, a0, a1, pool_a,
-                                      pool_b, ctx->compute));
+      ctx->pending_k = a0;
+      ctx->pending_v = a1;
       return OKV_OK;
     }
     case okv::OP_ATTN: {
@@ -172,6 +161,10 @@ int exec_op(okv_ctx *ctx, const Op &op, const void *a0, const void *a1, void *ou
                                 ctx->B, ctx->split, ctx->n_items};
       a.q = a0;
       a.pool = op.buf >= 0 ? ctx->cfg.staging[op.buf] : ctx->dev_pool[op.layer];
+      a.k_new = ctx->pending_k;
+      a.v_new = ctx->pending_v;
+      a.pool_mirror = op.buf >= 0 ? ctx->host_pool[op.layer] : nullptr;
+      ctx->pending_k = ctx->pending_v = nullptr;
       a.out = out;
       a.part_o = ctx->part_o;
       a.part_ml = ctx->part_ml;
@@ -320,9 +313,6 @@ int okv_create(const okv_config *cfg, okv_ctx **out) {
     if (cfg->h2d_stream == cfg->compute_stream) return fail(nullptr, OKV_EINVAL, "okv_create: h2d_stream must differ from compute_stream");
     n_staging = cfg->staging[1] ? 2 : 1;
   }
-  if (cfg->split_tokens && !split_fits_block_window(cfg, cfg->split_tokens))
-    return fail(nullptr, OKV_EINVAL, "okv_create: split_tokens %d spans more than %lld blocks of %d tokens",
-                cfg->split_tokens, (long long)kMaxItemBlocks, cfg->block_tokens);
   const int64_t need_ws = okv_workspace_bytes(cfg);
   if (!cfg->workspace || !aligned16(cfg->workspace)) return fail(nullptr, OKV_EINVAL, "okv_create: workspace NULL or misaligned");
   if (cfg->workspace_bytes < need_ws)
@@ -550,9 +540,6 @@ int okv_set_split_tokens(okv_ctx *ctx, int32_t split_tokens) {
   if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
   if (split_tokens < 0) return fail(ctx, OKV_EINVAL, "split_tokens < 0");
   if (ctx->in_step) return fail(ctx, OKV_ESTATE, "okv_set_split_tokens inside a step");
-  if (split_tokens > 0 && !split_fits_block_window(&ctx->cfg, split_tokens))
-    return fail(ctx, OKV_EINVAL, "split size %d spans more than %lld blocks of %d tokens", split_tokens,
-                (long long)kMaxItemBlocks, ctx->cfg.block_tokens);
   if (split_tokens > 0) {
     int64_t worst = (int64_t)ctx->cfg.max_batch * (((int64_t)ctx->cap_tokens + split_tokens - 1) / split_tokens);
     if (worst > ctx->max_items)
@@ -617,7 +604,34 @@ int okv_profile_read(okv_ctx *ctx, double *attn_ms, int64_t *attn_launches) {
     OKV_HIP(ctx, hipEventElapsedTime(&ms, ctx->prof_events[i].first, ctx->prof_events[i].second));
     total += ms;
   }
-  *attn_ms = total;
+  // What a pair of event records costs with nothing between them (median of 15 pairs)
+  // is taken off every bracket, so that the sum is kernel time, not kernel + markers.
+  double overhead = 0;
+  if (ctx->prof_used > 0) {
+    hipEvent_t a, b;
+    OKV_HIP(ctx, hipEventCreate(&a));
+    OKV_HIP(ctx, hipEventCreate(&b));
+    std::vector<float> gaps;
+    for (int i = 0; i < 15; ++i) {
+      hipError_t e = hipEventRecord(a, ctx->compute);
+      if (e == hipSuccess) e = hipEventRecord(b, ctx->compute);
+      if (e == hipSuccess) e = hipEventSynchronize(b);
+      float ms = 0;
+      if (e == hipSuccess) e = hipEventElapsedTime(&ms, a, b);
+      if (e != hipSuccess) {
+        (void)hipEventDestroy(a);
+        (void)hipEventDestroy(b);
+        return fail(ctx, OKV_EHIP, "okv_profile_read: %s", hipGetErrorString(e));
+      }
+      gaps.push_back(ms);
+    }
+    (void)hipEventDestroy(a);
+    (void)hipEventDestroy(b);
+    std::sort(gaps.begin(), gaps.end());
+    overhead = gaps[gaps.size() / 2];
+  }
+  total -= overhead * (double)ctx->prof_used;
+  *attn_ms = total > 0 ? total : 0;
   *attn_launches = (int64_t)ctx->prof_used;
   ctx->prof_used = 0;
   return OKV_OK;

@@ -30,7 +30,10 @@ struct AttnLaunch {
   PoolShape shape;
   BatchState batch;
   const void *q;           // fp16 [B][H][D]
-  const void *pool;        // the layer's KV pool (HBM: resident pool or staging buffer)
+  void *pool;              // the layer's KV pool (HBM: resident pool or staging buffer)
+  const void *k_new;       // fp16 [B][G][D] rows to store at position ctx_len - 1, or NULL
+  const void *v_new;
+  void *pool_mirror;       // host layer: the pinned host pool that gets the same rows, else NULL
   void *out;               // [B][H][D] fp16 or fp32
   float *part_o;           // [n_items * H][D]
   float *part_ml;          // [n_items * H][2]  (max in log2 units, sum)
@@ -38,18 +41,14 @@ struct AttnLaunch {
   int32_t need_merge;      // some sequence has more than one item
 };
 
-// Split-K partial attention followed, if needed, by the merge of the partials.
+// Store of the step's K/V rows and split-K partial attention in one launch, followed,
+// if needed, by the merge of the partials.
 hipError_t launch_decode_attn(const AttnLaunch &a, hipStream_t stream,
                               hipEvent_t ev_begin, hipEvent_t ev_end);
 
 // ctx_lens[b] += inc; rebuilds chunk_prefix and item_seq for split size S.
 hipError_t launch_step_advance(int32_t *ctx_lens, int32_t *chunk_prefix, int32_t *item_seq,
                                int32_t B, int32_t S, int32_t inc, hipStream_t stream);
-
-// Scatter of one step's K/V rows into pool_a and (if not NULL) pool_b.
-hipError_t launch_append(const PoolShape &shape, const int32_t *block_table,
-                         const int32_t *ctx_lens, int32_t B, const void *k_new,
-                         const void *v_new, void *pool_a, void *pool_b, hipStream_t stream);
 
 // items[it] = (b, lo, hi) decoded on the device.
 hipError_t launch_worklist_dump(const BatchState &batch, int32_t *items, hipStream_t stream);

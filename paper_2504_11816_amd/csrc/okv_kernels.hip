@@ -12,6 +12,8 @@
 //   * each row of d/8 lanes reduces its dot product with DPP adds; the 64/(d/8)
 //     rows of a wavefront run independent online softmaxes over interleaved
 //     tokens and are combined once at the end of the item;
+//   * the wavefront that reaches a sequence's last key also stores the step's new K/V
+//     rows (kv_append is folded into the attention launch);
 //   * items of a sequence are combined by a small merge kernel (skipped when
 //     every sequence has a single item).
 #include "okv_kernels.h"
@@ -118,6 +120,9 @@ __device__ __forceinline__ void tile_update(const Tile<D / 32> &t, const uint4 (
 struct AttnArgs {
   const uint16_t *q;
   const uint16_t *pool;
+  const uint16_t *k_new, *v_new;   // this step's rows [B][G][D] to store, or NULL
+  uint16_t *pool_store;            // where they go: the same pool as `pool`
+  uint16_t *pool_mirror;           // and, for a host layer, its pinned host pool (else NULL)
   void *out;
   float *part_o;
   float *part_ml;
@@ -128,7 +133,7 @@ struct AttnArgs {
 
 template <int D, int R, bool PAGED, int PIPE>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_kernel(const AttnArgs a) {
-  constexpr int LPR = D / 8, LPT = D / 32;
+  constexpr int LPR = D / 8, RPL = 64 / LPR, LPT = D / 32;
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int it = blockIdx.x * kWavesPerBlock + wave;
@@ -137,6 +142,19 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_kernel(const A
   const ItemRange ir = decode_item(it, a.item_seq, a.chunk_prefix, a.ctx_lens, a.split_tokens);
   const int b = ir.b, lo = ir.lo, hi = ir.hi;
   const int row = lane / LPR, col = lane % LPR;
+
+  // The item that ends at the sequence's last key also stores this step's K/V rows
+  // (paper §II-A: keys and values of every processed token are kept).  The rows are
+  // patched into the tile in registers, so the attention below does not depend on
+  // reading its own store back; the store itself is issued at the end of the kernel.
+  const int pos = a.ctx_lens[b] - 1;
+  const bool appending = a.k_new != nullptr && hi == pos + 1;
+  uint4 k_row = make_uint4(0u, 0u, 0u, 0u), v_row = k_row;
+  if (appending) {
+    const size_t at = ((size_t)b * a.G + g) * LPR + col;
+    k_row = reinterpret_cast<const uint4 *>(a.k_new)[at];
+    v_row = reinterpret_cast<const uint4 *>(a.v_new)[at];
+  }
 
   uint4 q[R];
   {
@@ -157,23 +175,18 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_kernel(const A
   const int64_t slice = (int64_t)a.tcap * D;                 // elements of one (blk, kv, g) slice
   const int64_t kv_stride = slice * a.G;                     // K slice -> V slice of the same block
 
-  // Block ids of the item's blocks, one per lane (an item spans at most 64 blocks).
-  int tbl = 0;
-  const int blk_first = PAGED ? (t_begin << 4) >> a.log2_T : 0;
-  if (PAGED) {
-    const int idx = blk_first + lane;
-    tbl = idx < a.max_blocks ? a.block_table[(size_t)b * a.max_blocks + idx] : 0;
-  }
-
-  auto load_tile = [&](Tile<LPT> &t, int tile) {
-    int64_t base;
-    if (PAGED) {
-      const int blk = __builtin_amdgcn_readlane(tbl, ((tile << 4) >> a.log2_T) - blk_first);
-      const int slot0 = (tile << 4) & (a.tcap - 1);
-      base = ((int64_t)blk * 2 * a.G + g) * slice + (int64_t)slot0 * D;
-    } else {
-      base = ((int64_t)b * 2 * a.G + g) * slice + (int64_t)(tile << 4) * D;
-    }
+  // Block id of a tile: a wavefront-uniform (scalar) load from the block table.  The index
+  // is clamped so that look-ahead past the item's last tile stays inside the table.
+  const int32_t *tbl_row = a.block_table + (size_t)b * a.max_blocks;
+  auto blk_of = [&](int tile) -> int {
+    if (!PAGED) return b;
+    int bi = (tile << 4) >> a.log2_T;
+    bi = bi < a.max_blocks ? bi : a.max_blocks - 1;
+    return tbl_row[bi];
+  };
+  auto load_tile = [&](Tile<LPT> &t, int tile, int blk) {
+    const int slot0 = PAGED ? (tile << 4) & (a.tcap - 1) : (tile << 4);
+    const int64_t base = ((int64_t)blk * 2 * a.G + g) * slice + (int64_t)slot0 * D;
     const uint4 *kp = reinterpret_cast<const uint4 *>(a.pool + base) + lane;
     const uint4 *vp = reinterpret_cast<const uint4 *>(a.pool + base + kv_stride) + lane;
 #pragma unroll
@@ -181,7 +194,9 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_kernel(const A
 #pragma unroll
     for (int j = 0; j < LPT; ++j) t.v[j] = vp[j * 64];
   };
-  auto is_full = [&](int tile) { return (tile << 4) >= lo && (tile << 4) + 16 <= hi; };
+  auto is_full = [&](int tile) {
+    return (tile << 4) >= lo && (tile << 4) + 16 <= hi && !(appending && tile == (pos >> 4));
+  };
 
   Tile<LPT> buf[PIPE];
 
@@ -194,41 +209,54 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_kernel(const A
     if (t0 >= t1) break;
     const int tile = k == 0 ? t0 : t1 - 1;
     if (is_full(tile)) continue;
-    load_tile(buf[0], tile);
+    load_tile(buf[0], tile, blk_of(tile));
+    if (appending && tile == (pos >> 4)) {
+#pragma unroll
+      for (int j = 0; j < LPT; ++j)
+        if ((tile << 4) + row + j * RPL == pos) {
+          buf[0].k[j] = k_row;
+          buf[0].v[j] = v_row;
+        }
+    }
     tile_update<D, R, true>(buf[0], q, m, l, o, (tile << 4) + row, lo, hi, a.scale_log2e);
     if (k == 0) ++t0; else --t1;
   }
 
   // Full tiles [t0, t1): PIPE tiles are in flight ahead of the one being reduced.  The
   // steady-state loop has no conditional loads, so each wait covers exactly the tile
-  // it needs and the younger loads stay in flight.
+  // it needs and the younger loads stay in flight; block ids are fetched one refill
+  // ahead through the scalar cache, which has its own counter.
   auto update = [&](const Tile<LPT> &t, int tile) {
     tile_update<D, R, false>(t, q, m, l, o, (tile << 4) + row, lo, hi, a.scale_log2e);
   };
   int t = t0;
   if (t1 - t0 >= 2 * PIPE) {
+    int next_blk[PIPE];
 #pragma unroll
-    for (int i = 0; i < PIPE; ++i) load_tile(buf[i], t0 + i);
+    for (int i = 0; i < PIPE; ++i) load_tile(buf[i], t0 + i, blk_of(t0 + i));
+#pragma unroll
+    for (int i = 0; i < PIPE; ++i) next_blk[i] = blk_of(t0 + i + PIPE);
     for (; t + 2 * PIPE <= t1; t += PIPE) {
 #pragma unroll
       for (int i = 0; i < PIPE; ++i) {
         update(buf[i], t + i);
         __builtin_amdgcn_sched_barrier(0);    // keep the refill behind the reduce that frees it,
-        load_tile(buf[i], t + i + PIPE);
+        load_tile(buf[i], t + i + PIPE, next_blk[i]);
+        next_blk[i] = blk_of(t + i + 2 * PIPE);
         __builtin_amdgcn_sched_barrier(0);    // and ahead of the next tile's reduce
       }
     }
   } else {
 #pragma unroll
     for (int i = 0; i < PIPE; ++i)
-      if (t0 + i < t1) load_tile(buf[i], t0 + i);
+      if (t0 + i < t1) load_tile(buf[i], t0 + i, blk_of(t0 + i));
   }
   // drain: at most 2 * PIPE - 1 tiles are left, the first PIPE of them in flight
 #pragma unroll
   for (int i = 0; i < PIPE; ++i)
     if (t + i < t1) {
       update(buf[i], t + i);
-      if (t + i + PIPE < t1) load_tile(buf[i], t + i + PIPE);
+      if (t + i + PIPE < t1) load_tile(buf[i], t + i + PIPE, blk_of(t + i + PIPE));
     }
 #pragma unroll
   for (int i = 0; i < PIPE; ++i)
@@ -279,6 +307,14 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_kernel(const A
       if (col == 0) *reinterpret_cast<float2 *>(a.part_ml + slot * 2) = make_float2(mt, lt);
     }
   }
+
+  if (appending && row < 2) {                          // row 0 stores the K row, row 1 the V row
+    const int slot = PAGED ? pos & (a.tcap - 1) : pos;
+    const int64_t at = (((int64_t)blk_of(pos >> 4) * 2 + row) * a.G + g) * slice + (int64_t)slot * D + col * 8;
+    const uint4 val = row == 0 ? k_row : v_row;
+    *reinterpret_cast<uint4 *>(a.pool_store + at) = val;
+    if (a.pool_mirror) *reinterpret_cast<uint4 *>(a.pool_mirror + at) = val;
+  }
 }
 
 // out[b][h] = sum_c o_c 2^(m_c - M) / sum_c l_c 2^(m_c - M) over the items c of sequence b.
@@ -312,9 +348,28 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(const AttnArgs a) {
   }
 }
 
+// Tiles in flight per wavefront, by query-group size (more heads = more registers per tile).
+#ifndef OKV_PIPE_R1
+#define OKV_PIPE_R1 2
+#endif
+#ifndef OKV_PIPE_R2
+#define OKV_PIPE_R2 2
+#endif
+#ifndef OKV_PIPE_R4
+#define OKV_PIPE_R4 2
+#endif
+#ifndef OKV_PIPE_R8
+#define OKV_PIPE_R8 2
+#endif
+template <int R>
+constexpr int pipe_depth() {
+  return R == 1 ? OKV_PIPE_R1 : R == 2 ? OKV_PIPE_R2 : R == 4 ? OKV_PIPE_R4 : OKV_PIPE_R8;
+}
+
 template <int D, int R, bool PAGED>
 hipError_t launch_split(const AttnArgs &args, dim3 grid, hipStream_t stream) {
-  hipLaunchKernelGGL((attn_split_kernel<D, R, PAGED, 2>), grid, dim3(kWavesPerBlock * 64), 0, stream, args);
+  hipLaunchKernelGGL((attn_split_kernel<D, R, PAGED, pipe_depth<R>()>), grid, dim3(kWavesPerBlock * 64), 0,
+                     stream, args);
   return hipGetLastError();
 }
 
@@ -343,6 +398,10 @@ hipError_t launch_decode_attn(const AttnLaunch &a, hipStream_t stream, hipEvent_
   AttnArgs args;
   args.q = static_cast<const uint16_t *>(a.q);
   args.pool = static_cast<const uint16_t *>(a.pool);
+  args.k_new = static_cast<const uint16_t *>(a.k_new);
+  args.v_new = static_cast<const uint16_t *>(a.v_new);
+  args.pool_store = static_cast<uint16_t *>(a.pool);
+  args.pool_mirror = static_cast<uint16_t *>(a.pool_mirror);
   args.out = a.out;
   args.part_o = a.part_o;
   args.part_ml = a.part_ml;
@@ -421,32 +480,6 @@ __global__ __launch_bounds__(kStepThreads) void step_advance_kernel(int32_t *ctx
   if (tid == kStepThreads - 1) chunk_prefix[B] = part[tid];
 }
 
-__global__ void append_kernel(PoolShape s, const int32_t *block_table, const int32_t *ctx_lens,
-                              int32_t B, const uint4 *k_new, const uint4 *v_new, uint16_t *pool_a,
-                              uint16_t *pool_b) {
-  const int cpr = s.D / 8;                                     // 16-byte chunks per row
-  const int64_t total = (int64_t)B * s.G * 2 * cpr;
-  const int64_t idx = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (idx >= total) return;
-  const int c = (int)(idx % cpr);
-  const int kv = (int)((idx / cpr) % 2);
-  const int g = (int)((idx / (2 * cpr)) % s.G);
-  const int b = (int)(idx / ((int64_t)2 * cpr * s.G));
-  const int pos = ctx_lens[b] - 1;
-  int64_t blk, slot;
-  if (s.paged) {
-    blk = block_table[(size_t)b * s.max_blocks + (pos >> s.log2_T)];
-    slot = pos & (s.tcap - 1);
-  } else {
-    blk = b;
-    slot = pos;
-  }
-  const int64_t dst = (((blk * 2 + kv) * s.G + g) * s.tcap + slot) * s.D + c * 8;
-  const uint4 val = (kv ? v_new : k_new)[((size_t)b * s.G + g) * cpr + c];
-  *reinterpret_cast<uint4 *>(pool_a + dst) = val;
-  if (pool_b) *reinterpret_cast<uint4 *>(pool_b + dst) = val;
-}
-
 __global__ void worklist_dump_kernel(BatchState bs, int32_t *items) {
   const int it = blockIdx.x * blockDim.x + threadIdx.x;
   if (it >= bs.n_items) return;
@@ -477,19 +510,6 @@ hipError_t launch_step_advance(int32_t *ctx_lens, int32_t *chunk_prefix, int32_t
                                int32_t B, int32_t S, int32_t inc, hipStream_t stream) {
   hipLaunchKernelGGL(step_advance_kernel, dim3(1), dim3(kStepThreads), 0, stream, ctx_lens,
                      chunk_prefix, item_seq, B, S, inc);
-  return hipGetLastError();
-}
-
-hipError_t launch_append(const PoolShape &shape, const int32_t *block_table,
-                         const int32_t *ctx_lens, int32_t B, const void *k_new, const void *v_new,
-                         void *pool_a, void *pool_b, hipStream_t stream) {
-  const int64_t total = (int64_t)B * shape.G * 2 * (shape.D / 8);
-  const int threads = 256;
-  const int64_t blocks = (total + threads - 1) / threads;
-  hipLaunchKernelGGL(append_kernel, dim3((unsigned)blocks), dim3(threads), 0, stream, shape,
-                     block_table, ctx_lens, B, static_cast<const uint4 *>(k_new),
-                     static_cast<const uint4 *>(v_new), static_cast<uint16_t *>(pool_a),
-                     static_cast<uint16_t *>(pool_b));
   return hipGetLastError();
 }
 
