@@ -26,6 +26,32 @@ import numpy as np  # noqa: E402
 HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published peak
 PCIE5_X16_GBPS = 64.0       # nominal, one direction
 
+# HBM traffic of one launch of the split kernel, from two rocprofv3 --pmc runs of this
+# file's default workload (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch averaged over the
+# timed launches), each scaled by what the same counter read for the plain copy kernel of
+# known size in the same run.  Valid only for the kernel source it was taken on: if
+# okv_kernels.hip has changed since, `traffic` is reported as null.
+TRAFFIC_RECORD = {
+    "workload": "cfg2", "steps": 512,
+    "kernel_sha256": "",
+    "fetch_kib": 0.0, "fetch_scale": 2.0,
+    "write_kib": 0.0, "write_scale": 1.0,
+}
+
+
+def recorded_traffic(workload, steps):
+    """HBM bytes per launch from the recorded counters, or None if they do not apply."""
+    import hashlib
+    rec = TRAFFIC_RECORD
+    src = os.path.join(ROOT, "paper_2504_11816_amd", "csrc", "okv_kernels.hip")
+    try:
+        sha = hashlib.sha256(open(src, "rb").read()).hexdigest()
+    except OSError:
+        return None
+    if not rec["kernel_sha256"] or sha != rec["kernel_sha256"] or workload != rec["workload"] or steps != rec["steps"]:
+        return None
+    return (rec["fetch_kib"] * rec["fetch_scale"] + rec["write_kib"] * rec["write_scale"]) * 1024.0
+
 
 def log(msg):
     print(msg, file=sys.stderr, flush=True)
@@ -86,33 +112,36 @@ def kernel_time(st, ctx0, table, inputs, steps):
     return ms * 1e-3, n
 
 
-def cpu_baseline(st, layer, ctx_now, q_layer, budget_s=15.0):
-    """The fp64 oracle, as it stands, on this host: (b, h) pairs of one layer of
-    the same workload until the time budget is used."""
+def cpu_baseline(st, ctx_now, q_layers, budget_s=15.0):
+    """The fp64 oracle, as it stands, on this host: (b, h) pairs of the same
+    workload, layer after layer, until the time budget is used."""
     from threadpoolctl import threadpool_limits
     from oracle import attention as oa
-    pool = st.read_pool(layer)
-    qn = q_layer.cpu().numpy()
     layout = st.layout()
     pairs = [(b, h) for b in range(st.B) for h in range(st.H)]
-    done, tokens = 0, 0
+    done, tokens, dt, layers = 0, 0, 0.0, 0
     with threadpool_limits(limits=1):
-        t0 = time.perf_counter()
-        for (b, h) in pairs:
-            oa.decode_attn(qn, pool, layout, ctx_now, st.H, sample=[(b, h)])
-            done += 1
-            tokens += int(ctx_now[b])
-            if time.perf_counter() - t0 > budget_s:
+        for layer in range(st.L):
+            pool = st.read_pool(layer)                       # not timed: the oracle starts from host memory
+            qn = q_layers[layer].cpu().numpy()
+            layers += 1
+            t0 = time.perf_counter()
+            for (b, h) in pairs:
+                oa.decode_attn(qn, pool, layout, ctx_now, st.H, sample=[(b, h)])
+                done += 1
+                tokens += int(ctx_now[b])
+                if dt + time.perf_counter() - t0 > budget_s:
+                    break
+            dt += time.perf_counter() - t0
+            if dt > budget_s:
                 break
-        dt = time.perf_counter() - t0
     # one (b, h) pair of one layer is 1 / (H * L) of a generated token's attention
-    pair_rate = done / dt
-    tok_rate = pair_rate / (st.H * st.L_full)
-    kv_gbps = tokens * 2 * st.d * 2 / dt / 1e9
+    tok_rate = done / dt / (st.H * st.L)
+    kv_gbps = tokens * 2 * st.d * 2 * (st.G / st.H) / dt / 1e9
     return {"value": tok_rate, "unit": "tokens/s", "cores": 1, "kind": "oracle",
             "kv_gbps": kv_gbps,
-            "sample": f"{done} (sequence, head) pairs of one layer at context {int(np.mean(ctx_now))}, "
-                      f"{dt:.1f} s of single-thread numpy fp64, scaled to {st.H} heads x {st.L_full} layers"}
+            "sample": f"{done} (sequence, head) pairs over {layers} layer(s) at context {int(np.mean(ctx_now))}, "
+                      f"{dt:.1f} s of single-thread numpy fp64, scaled to {st.H} heads x {st.L} layers"}
 
 
 def run_resident(args):
@@ -135,7 +164,6 @@ def run_resident(args):
     log(f"[bench] {args.workload}: L={L} H={H} G={G} d={d} B={B} T={T} ctx {int(ctx_first.min())}..{int(ctx_first.max())} "
         f"steps={steps} capacity={cap}")
     st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=cap, on_host=on_host, out_dtype=0)
-    st.L_full = L
     for l in range(L):
         st.fill_pool(l, synth.stream_seed(args.seed, synth.TENSOR_POOL, l))
     table = None
@@ -161,11 +189,38 @@ def run_resident(args):
     if not args.no_cpu:
         log("[bench] timing the CPU oracle on a sample")
         mid = ctx0 + steps                                  # lengths as the run left them
-        cpu = cpu_baseline(st, 0, mid, inputs[0][0], args.cpu_seconds)
+        cpu = cpu_baseline(st, mid, inputs[0], args.cpu_seconds)
     st.close()
     del st
     torch.cuda.empty_cache()
     return res, cpu
+
+
+def run_probe(nbytes=1 << 30, reps=5):
+    """Plain 16-byte-per-lane copy and read kernels over 1 GiB: what a kernel with no
+    arithmetic reaches on this GPU, and the known-size dispatches HBM counters are scaled by."""
+    import torch
+    from paper_2504_11816_amd import binding
+    dev = torch.device("cuda:0")
+    src = torch.empty(nbytes, dtype=torch.uint8, device=dev).random_(0, 255)
+    dst = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+    st = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    out = {"bytes": nbytes}
+    for name, fn, moved in (("copy", lambda: binding.okv_probe_copy(dst, src, nbytes, st.cuda_stream), 2 * nbytes),
+                            ("read", lambda: binding.okv_probe_read(src, nbytes, sink, st.cuda_stream), nbytes)):
+        fn()
+        st.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(st)
+        for _ in range(reps):
+            fn()
+        e1.record(st)
+        st.synchronize()
+        out[name + "_gbps"] = moved * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    log(f"[bench] plain kernels on 1 GiB: copy {out['copy_gbps']:.0f} GB/s (read+write), read {out['read_gbps']:.0f} GB/s")
+    return out
 
 
 def run_offload(args):
@@ -221,6 +276,8 @@ def main():
     ap.add_argument("--no-offload", action="store_true", help="skip the offloaded leg")
     ap.add_argument("--offload-steps", type=int, default=6)
     ap.add_argument("--offload-batch", type=int, default=0)
+    ap.add_argument("--probe", action="store_true",
+                    help="also run the plain copy / read kernels on 1 GiB (the yardstick for HBM counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this library runs on one GPU; there is no multi-GPU path (--gpus 1 only)")
@@ -228,6 +285,7 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     res, cpu = run_resident(args)
+    probe = run_probe() if args.probe else None
     off = None if args.no_offload else run_offload(args)
     line = {
         "metric": "decode_attn_tokens_per_s", "value": res["tokens_per_s"], "unit": "tokens/s",
@@ -240,12 +298,15 @@ def main():
                    "split_tokens": res["split_tokens"]},
         "kv_gbps": res["kv_gbps"], "hbm_frac": res["kv_gbps"] / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": res["kernel_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": res["kernel_gbps"] / HBM_PEAK_GBPS, "traffic": None,
+                     "frac": res["kernel_gbps"] / HBM_PEAK_GBPS,
+                     "traffic": recorded_traffic(args.workload, res["steps"]),
                      "kernel": "attn_split_kernel", "avg_us": res["kernel_avg_us"],
                      "launches": res["kernel_launches"], "bytes_per_launch": res["kv_bytes_per_launch"]},
         "cpu_baseline": cpu,
         "offload": off,
     }
+    if probe:
+        line["probe"] = probe
     print(json.dumps(line), flush=True)
 
 

@@ -65,7 +65,9 @@ typedef struct okv_config {
                                   paged: ignored (capacity is max_blocks_per_seq * T)        */
   int64_t blocks_per_layer;    /* paged: blocks in each layer's pool; contiguous: ignored    */
   int32_t out_dtype;           /* 0 = fp16 (round to nearest even), 1 = fp32                 */
-  int32_t split_tokens;        /* keys per split-K work item; 0 lets the library choose      */
+  int32_t split_tokens;        /* upper bound on the keys of one split-K work item (a sequence
+                                  of n keys is cut into ceil(n / split_tokens) equal pieces,
+                                  rounded up to multiples of 16); 0 lets the library choose  */
   void  **dev_pool;            /* HOST array [L] of DEVICE pointers: the pool of each layer
                                   that stays in HBM, NULL for a layer kept on the host       */
   void  **host_pool;           /* HOST array [L] of HOST pointers to PINNED, device-mapped
@@ -198,8 +200,9 @@ int okv_synchronize(okv_ctx *ctx);
 
 /* ---- introspection used by tests and the benchmark -------------------------------- */
 
-/* Overrides the split size (0 = back to the library's choice).  Takes effect at the
- * next okv_step_begin.  OKV_ENOSPC if the workspace is too small for it. */
+/* Overrides the split size (0 = back to cfg.split_tokens, or to the library's choice
+ * if that is 0 too).  The work list is rebuilt at once.  OKV_ENOSPC if the workspace
+ * is too small for it. */
 int okv_set_split_tokens(okv_ctx *ctx, int32_t split_tokens);
 
 /* The split size in use (after the last okv_step_begin / okv_set_batch). */
@@ -209,7 +212,8 @@ int32_t okv_get_split_tokens(const okv_ctx *ctx);
 int okv_get_ctx_lens(okv_ctx *ctx, int32_t *out);
 
 /* The current split-K work list as (sequence, first key, one-past-last key) triples,
- * in launch order.  from_device = 0 walks the host copy of the tables;
+ * in launch order: sequence by sequence, each cut into equal pieces that start at
+ * multiples of 16 keys.  from_device = 0 walks the host copy of the tables;
  * from_device = 1 runs a small kernel that decodes every item exactly as the
  * attention kernel does and copies the result back (synchronous).
  *   items  HOST int32 [max_items][3];  n_items HOST out. */

@@ -4,10 +4,22 @@ TEST INFRASTRUCTURE ONLY; shares no code with the HIP library.
 
 Decode attention over a long context is cut along the keys into work items
 that are reduced independently and merged afterwards.  The contract with the
-library: with split size S (tokens), sequence b with n_b keys contributes the
-items [c*S, min((c+1)*S, n_b)) for c = 0, 1, ...; items are listed sequence
-by sequence, in order, and each item is processed once per KV head.
+library: with split size S (tokens), sequence b with n_b keys is first cut
+into c0 = ceil(n_b / S) equal pieces; the piece length ceil(n_b / c0) is then
+rounded up to a multiple of 16 (work items start on 16-key boundaries), and
+the sequence contributes the items [c*size, min((c+1)*size, n_b)) for
+c = 0, 1, ... while they are non-empty.  Items are listed sequence by
+sequence, in order, and each item is processed once per KV head.
 """
+
+
+def piece_size(n, split_tokens):
+    """Keys per item of a sequence with n keys (n >= 1)."""
+    pieces = -(-n // split_tokens)
+    longest = -(-n // pieces)
+    while longest % 16:
+        longest += 1
+    return longest
 
 
 def expected_items(ctx_lens, split_tokens):
@@ -15,9 +27,12 @@ def expected_items(ctx_lens, split_tokens):
     items = []
     for b, n in enumerate(ctx_lens):
         n = int(n)
+        if n < 1:
+            continue
+        size = piece_size(n, split_tokens)
         start = 0
         while start < n:
-            stop = start + split_tokens
+            stop = start + size
             if stop > n:
                 stop = n
             items.append((b, start, stop))

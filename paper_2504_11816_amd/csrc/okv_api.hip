@@ -21,7 +21,6 @@ namespace {
 
 constexpr int kEventRing = 4;            // > copies in flight (at most 2)
 constexpr int32_t kMinAutoSplit = 128;   // smallest split size the library picks by itself
-constexpr int64_t kTargetUnits = 1024;   // wavefront-sized work items wanted per launch (4 per CU)
 
 thread_local std::string g_error;        // failures that have no context to live in
 
@@ -37,7 +36,7 @@ struct okv_ctx {
   int32_t n_staging = 0;
   hipStream_t compute = nullptr, h2d = nullptr;
 
-  int32_t *d_block_table = nullptr, *d_ctx_lens = nullptr, *d_chunk_prefix = nullptr;
+  int32_t *d_block_table = nullptr, *d_ctx_lens = nullptr, *d_chunk_prefix = nullptr, *d_chunk_size = nullptr;
   int32_t *d_item_seq = nullptr, *d_items_dump = nullptr;
   int64_t max_items = 0;
   float *part_o = nullptr, *part_ml = nullptr;
@@ -119,22 +118,78 @@ int64_t bytes_per_item(const okv_config *c) { return (int64_t)c->n_q_heads * (c-
 
 int64_t count_items(const int32_t *ctx, int32_t B, int32_t S) {
   int64_t n = 0;
-  for (int32_t b = 0; b < B; ++b) n += (ctx[b] + S - 1) / S;
+  for (int32_t b = 0; b < B; ++b) {
+    int32_t cnt, sz;
+    okv::seq_chunks(ctx[b], S, &cnt, &sz);
+    n += cnt;
+  }
   return n;
 }
 
-// The fewest, longest work items that still give kTargetUnits wavefronts: S doubles
-// from kMinAutoSplit while the launch keeps that many (item, KV head) units; if even
-// whole sequences give enough units nothing is split and no merge pass is needed.
+// Split size by a small cost model of one launch, evaluated for S = 128, 256, 512, ...
+//   time(S) = max( (bytes + items * kItemOverheadBytes) / kLaunchBytesPerUs + tail / 2,
+//                  longest item / kWaveBytesPerUs )
+// A wavefront alone pulls at most kWaveBytesPerUs, so about kSaturatingWaves of them
+// are needed to keep HBM busy; `tail` is the time the longest item keeps running after
+// fewer than that many items are left (they all start together and finish by size).
+// Fewer, longer items save per-item cost and the merge pass; equal items avoid a tail.
+// The constants are measured on MI355X with this kernel (d = 128 rows).
+constexpr double kLaunchBytesPerUs = 5.8e6;      // what the split kernel sustains, bytes per microsecond
+constexpr double kWaveBytesPerUs = 6.5e3;        // one wavefront with two tiles in flight
+constexpr double kItemOverheadBytes = 10240;     // prologue, epilogue, partial result, merge share
+constexpr int64_t kSaturatingWaves = 890;        // kLaunchBytesPerUs / kWaveBytesPerUs
+
+double launch_cost_us(const okv_ctx *ctx, const std::vector<int32_t> &lens, int32_t S, int64_t *n_items) {
+  const int32_t G = ctx->cfg.n_kv_heads;
+  const double row_bytes = 2.0 * ctx->cfg.head_dim * 2;            // K row + V row of one KV head
+  std::vector<std::pair<int32_t, int64_t>> sizes;                  // (keys per item, wavefront items)
+  double bytes = 0;
+  int64_t items = 0, units = 0;
+  for (int32_t b = 0; b < ctx->B; ++b) {
+    int32_t cnt, sz;
+    okv::seq_chunks(lens[b], S, &cnt, &sz);
+    if (cnt == 0) continue;
+    const int32_t longest_piece = cnt == 1 ? lens[b] : sz;
+    sizes.emplace_back(longest_piece, (int64_t)cnt * G);
+    bytes += (double)lens[b] * G * row_bytes;
+    items += cnt;
+    units += (int64_t)cnt * G;
+  }
+  *n_items = items;
+  if (sizes.empty()) return 0;
+  std::sort(sizes.begin(), sizes.end(), [](const auto &x, const auto &y) { return x.first > y.first; });
+  const double longest = sizes[0].first * row_bytes;
+  double at_saturation = 0;                                        // size of the kSaturatingWaves-th largest item
+  int64_t seen = 0;
+  for (const auto &p : sizes) {
+    seen += p.second;
+    if (seen >= kSaturatingWaves) {
+      at_saturation = p.first * row_bytes;
+      break;
+    }
+  }
+  const double tail = (longest - at_saturation) / kWaveBytesPerUs;
+  const double stream = (bytes + (double)units * kItemOverheadBytes) / kLaunchBytesPerUs;
+  return std::max(stream + 0.5 * tail, longest / kWaveBytesPerUs);
+}
+
 int32_t choose_split(const okv_ctx *ctx, const std::vector<int32_t> &lens) {
   if (ctx->split_override) return ctx->split_override;
   if (ctx->cfg.split_tokens) return ctx->cfg.split_tokens;
-  int32_t S = kMinAutoSplit;
   int32_t longest = 1;
   for (int32_t b = 0; b < ctx->B; ++b) longest = std::max(longest, lens[b]);
-  while (S < longest && count_items(lens.data(), ctx->B, S * 2) * ctx->cfg.n_kv_heads >= kTargetUnits) S *= 2;
-  while (count_items(lens.data(), ctx->B, S) > ctx->max_items) S *= 2;
-  return S;
+  int32_t best = 0;
+  double best_cost = 0;
+  for (int64_t S = kMinAutoSplit; ; S *= 2) {
+    int64_t n_items = 0;
+    const double cost = launch_cost_us(ctx, lens, (int32_t)S, &n_items);
+    if (n_items <= ctx->max_items && (best == 0 || cost < best_cost * 0.999)) {
+      best = (int32_t)S;
+      best_cost = cost;
+    }
+    if (S >= longest) break;
+  }
+  return best ? best : kMinAutoSplit;
 }
 
 int exec_op(okv_ctx *ctx, const Op &op, const void *a0, const void *a1, void *out) {
@@ -157,7 +212,7 @@ int exec_op(okv_ctx *ctx, const Op &op, const void *a0, const void *a1, void *ou
     case okv::OP_ATTN: {
       okv::AttnLaunch a;
       a.shape = ctx->shape;
-      a.batch = okv::BatchState{ctx->d_block_table, ctx->d_ctx_lens, ctx->d_chunk_prefix, ctx->d_item_seq,
+      a.batch = okv::BatchState{ctx->d_block_table, ctx->d_ctx_lens, ctx->d_chunk_prefix, ctx->d_chunk_size, ctx->d_item_seq,
                                 ctx->B, ctx->split, ctx->n_items};
       a.q = a0;
       a.pool = op.buf >= 0 ? ctx->cfg.staging[op.buf] : ctx->dev_pool[op.layer];
@@ -210,10 +265,13 @@ int rebuild_worklist(okv_ctx *ctx, int32_t inc) {
                 (long long)n, (long long)ctx->max_items);
   ctx->n_items = (int32_t)n;
   ctx->need_merge = false;
-  for (int32_t b = 0; b < ctx->B; ++b)
-    if (ctx->h_ctx_lens[b] > ctx->split) ctx->need_merge = true;
-  OKV_HIP(ctx, okv::launch_step_advance(ctx->d_ctx_lens, ctx->d_chunk_prefix, ctx->d_item_seq, ctx->B,
-                                        ctx->split, inc, ctx->compute));
+  for (int32_t b = 0; b < ctx->B; ++b) {
+    int32_t cnt, sz;
+    okv::seq_chunks(ctx->h_ctx_lens[b], ctx->split, &cnt, &sz);
+    if (cnt > 1) ctx->need_merge = true;
+  }
+  OKV_HIP(ctx, okv::launch_step_advance(ctx->d_ctx_lens, ctx->d_chunk_prefix, ctx->d_chunk_size, ctx->d_item_seq,
+                                        ctx->B, ctx->split, inc, ctx->compute));
   return OKV_OK;
 }
 
@@ -229,6 +287,7 @@ int64_t okv_layer_pool_bytes(const okv_config *cfg) {
 int64_t okv_workspace_bytes(const okv_config *cfg) {
   if (const char *why = shape_problem(cfg)) return fail(nullptr, OKV_EINVAL, "%s", why);
   int64_t S = cfg->split_tokens ? cfg->split_tokens : kMinAutoSplit;
+  if (S < 16) S = 16;                                  // items never hold fewer than 16 keys
   int64_t cap = cap_tokens_of(cfg);
   int64_t items = (int64_t)cfg->max_batch * ((cap + S - 1) / S);
   return items * bytes_per_item(cfg);
@@ -369,6 +428,7 @@ int okv_create(const okv_config *cfg, okv_ctx **out) {
   OKV_TRY_CREATE(hipMemset(ctx->d_block_table, 0, tbl));
   OKV_TRY_CREATE(hipMalloc(&ctx->d_ctx_lens, (size_t)cfg->max_batch * sizeof(int32_t)));
   OKV_TRY_CREATE(hipMalloc(&ctx->d_chunk_prefix, ((size_t)cfg->max_batch + 1) * sizeof(int32_t)));
+  OKV_TRY_CREATE(hipMalloc(&ctx->d_chunk_size, (size_t)cfg->max_batch * sizeof(int32_t)));
   OKV_TRY_CREATE(hipMalloc(&ctx->d_item_seq, (size_t)std::max<int64_t>(1, max_items) * sizeof(int32_t)));
   for (int i = 0; i < kEventRing; ++i) {
     OKV_TRY_CREATE(hipEventCreateWithFlags(&ctx->ready_ev[i], hipEventDisableTiming));
@@ -386,6 +446,7 @@ int okv_destroy(okv_ctx *ctx) {
   (void)hipFree(ctx->d_block_table);
   (void)hipFree(ctx->d_ctx_lens);
   (void)hipFree(ctx->d_chunk_prefix);
+  (void)hipFree(ctx->d_chunk_size);
   (void)hipFree(ctx->d_item_seq);
   (void)hipFree(ctx->d_items_dump);
   for (int i = 0; i < kEventRing; ++i) {
@@ -541,7 +602,8 @@ int okv_set_split_tokens(okv_ctx *ctx, int32_t split_tokens) {
   if (split_tokens < 0) return fail(ctx, OKV_EINVAL, "split_tokens < 0");
   if (ctx->in_step) return fail(ctx, OKV_ESTATE, "okv_set_split_tokens inside a step");
   if (split_tokens > 0) {
-    int64_t worst = (int64_t)ctx->cfg.max_batch * (((int64_t)ctx->cap_tokens + split_tokens - 1) / split_tokens);
+    const int64_t S = std::max(split_tokens, 16);
+    int64_t worst = (int64_t)ctx->cfg.max_batch * (((int64_t)ctx->cap_tokens + S - 1) / S);
     if (worst > ctx->max_items)
       return fail(ctx, OKV_ENOSPC, "split size %d can need %lld work items, workspace holds %lld", split_tokens,
                   (long long)worst, (long long)ctx->max_items);
@@ -569,21 +631,22 @@ int okv_worklist(okv_ctx *ctx, int32_t from_device, int32_t *items, int64_t max_
   if (ctx->n_items == 0) return OKV_OK;
   if (from_device) {
     if (!ctx->d_items_dump) OKV_HIP(ctx, hipMalloc(&ctx->d_items_dump, (size_t)ctx->max_items * 3 * sizeof(int32_t)));
-    okv::BatchState bs{ctx->d_block_table, ctx->d_ctx_lens, ctx->d_chunk_prefix, ctx->d_item_seq, ctx->B, ctx->split, ctx->n_items};
+    okv::BatchState bs{ctx->d_block_table, ctx->d_ctx_lens, ctx->d_chunk_prefix, ctx->d_chunk_size, ctx->d_item_seq, ctx->B, ctx->split, ctx->n_items};
     OKV_HIP(ctx, okv::launch_worklist_dump(bs, ctx->d_items_dump, ctx->compute));
     OKV_HIP(ctx, hipStreamSynchronize(ctx->compute));
     OKV_HIP(ctx, hipMemcpy(items, ctx->d_items_dump, (size_t)ctx->n_items * 3 * sizeof(int32_t), hipMemcpyDeviceToHost));
     return OKV_OK;
   }
   // host walk: the same tables the device kernel builds, then the same decode
-  std::vector<int32_t> prefix(ctx->B + 1, 0), seq;
+  std::vector<int32_t> prefix(ctx->B + 1, 0), size(ctx->B, 16), seq;
   for (int32_t b = 0; b < ctx->B; ++b) {
-    int32_t cnt = (ctx->h_ctx_lens[b] + ctx->split - 1) / ctx->split;
+    int32_t cnt;
+    okv::seq_chunks(ctx->h_ctx_lens[b], ctx->split, &cnt, &size[b]);
     prefix[b + 1] = prefix[b] + cnt;
     seq.insert(seq.end(), cnt, b);
   }
   for (int32_t it = 0; it < ctx->n_items; ++it) {
-    okv::ItemRange r = okv::decode_item(it, seq.data(), prefix.data(), ctx->h_ctx_lens.data(), ctx->split);
+    okv::ItemRange r = okv::decode_item(it, seq.data(), prefix.data(), size.data(), ctx->h_ctx_lens.data());
     items[it * 3 + 0] = r.b, items[it * 3 + 1] = r.lo, items[it * 3 + 2] = r.hi;
   }
   return OKV_OK;

@@ -119,24 +119,41 @@ class Scheduler {
 
 // ---- split-K work list ------------------------------------------------------
 //
-// Sequence b with n_b keys is cut into ceil(n_b / S) items of S keys (the last
-// one shorter).  chunk_prefix[b] = number of items of sequences 0 .. b-1; item
-// `it` belongs to the sequence item_seq[it], is its chunk it - chunk_prefix[b]
-// and covers keys [c * S, min((c + 1) * S, n_b)).  The same decode runs on the
-// host (for the grid size and for checks) and in the kernels.
+// Sequence b with n_b keys is cut into items of equal size: with split size S it gets
+// c0 = ceil(n_b / S) pieces of ceil(n_b / c0) keys, the piece size rounded up to a
+// multiple of 16 (so that items start on tile boundaries), which leaves
+// count = ceil(n_b / size) items.  Equal pieces matter when the launch is a single
+// round of wavefronts: the longest item sets the time.  chunk_prefix[b] = number of
+// items of sequences 0 .. b-1; item `it` belongs to sequence item_seq[it], is its
+// chunk c = it - chunk_prefix[b] and covers keys [c * size_b, min((c + 1) * size_b, n_b)).
+// The same arithmetic runs on the host (grid size, checks) and in the kernels.
 struct ItemRange {
   int32_t b, lo, hi;
 };
 
+__host__ __device__ inline void seq_chunks(int32_t n, int32_t S, int32_t *count, int32_t *size) {
+  if (n <= 0) {
+    *count = 0;
+    *size = 16;
+    return;
+  }
+  const int32_t c0 = (n + S - 1) / S;
+  const int32_t sz = (((n + c0 - 1) / c0) + 15) & ~15;
+  *size = sz;
+  *count = (n + sz - 1) / sz;
+}
+
 __host__ __device__ inline ItemRange decode_item(int32_t it, const int32_t *item_seq,
                                                  const int32_t *chunk_prefix,
-                                                 const int32_t *ctx_lens, int32_t S) {
+                                                 const int32_t *chunk_size,
+                                                 const int32_t *ctx_lens) {
   ItemRange r;
   r.b = item_seq[it];
-  int32_t c = it - chunk_prefix[r.b];
-  r.lo = c * S;
-  int32_t n = ctx_lens[r.b];
-  r.hi = r.lo + S < n ? r.lo + S : n;
+  const int32_t c = it - chunk_prefix[r.b];
+  const int32_t sz = chunk_size[r.b];
+  r.lo = c * sz;
+  const int32_t n = ctx_lens[r.b];
+  r.hi = r.lo + sz < n ? r.lo + sz : n;
   return r;
 }
 

@@ -20,6 +20,7 @@ struct BatchState {        // device arrays owned by the context
   const int32_t *block_table;   // [B][max_blocks]
   const int32_t *ctx_lens;      // [B]
   const int32_t *chunk_prefix;  // [B + 1]
+  const int32_t *chunk_size;    // [B] keys per item of the sequence (multiple of 16)
   const int32_t *item_seq;      // [n_items]
   int32_t B;
   int32_t split_tokens;
@@ -46,9 +47,10 @@ struct AttnLaunch {
 hipError_t launch_decode_attn(const AttnLaunch &a, hipStream_t stream,
                               hipEvent_t ev_begin, hipEvent_t ev_end);
 
-// ctx_lens[b] += inc; rebuilds chunk_prefix and item_seq for split size S.
-hipError_t launch_step_advance(int32_t *ctx_lens, int32_t *chunk_prefix, int32_t *item_seq,
-                               int32_t B, int32_t S, int32_t inc, hipStream_t stream);
+// ctx_lens[b] += inc; rebuilds chunk_prefix, chunk_size and item_seq for split size S.
+hipError_t launch_step_advance(int32_t *ctx_lens, int32_t *chunk_prefix, int32_t *chunk_size,
+                               int32_t *item_seq, int32_t B, int32_t S, int32_t inc,
+                               hipStream_t stream);
 
 // items[it] = (b, lo, hi) decoded on the device.
 hipError_t launch_worklist_dump(const BatchState &batch, int32_t *items, hipStream_t stream);

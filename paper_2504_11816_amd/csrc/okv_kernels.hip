@@ -26,7 +26,10 @@ namespace {
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 
-constexpr int kWavesPerBlock = 4;
+#ifndef OKV_WAVES_PER_BLOCK
+#define OKV_WAVES_PER_BLOCK 4
+#endif
+constexpr int kWavesPerBlock = OKV_WAVES_PER_BLOCK;   // independent work items per workgroup
 constexpr float kNegBig = -1.0e30f;   // "no key seen yet"; finite so that differences stay finite
 
 template <int CTRL>
@@ -126,8 +129,8 @@ struct AttnArgs {
   void *out;
   float *part_o;
   float *part_ml;
-  const int32_t *block_table, *ctx_lens, *chunk_prefix, *item_seq;
-  int32_t H, G, log2_T, tcap, max_blocks, split_tokens, n_items, out_fp32;
+  const int32_t *block_table, *ctx_lens, *chunk_prefix, *chunk_size, *item_seq;
+  int32_t H, G, log2_T, tcap, max_blocks, n_items, out_fp32;
   float scale_log2e;
 };
 
@@ -139,7 +142,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_kernel(const A
   const int it = blockIdx.x * kWavesPerBlock + wave;
   if (it >= a.n_items) return;                       // whole wavefront leaves together
   const int g = blockIdx.y;
-  const ItemRange ir = decode_item(it, a.item_seq, a.chunk_prefix, a.ctx_lens, a.split_tokens);
+  const ItemRange ir = decode_item(it, a.item_seq, a.chunk_prefix, a.chunk_size, a.ctx_lens);
   const int b = ir.b, lo = ir.lo, hi = ir.hi;
   const int row = lane / LPR, col = lane % LPR;
 
@@ -408,13 +411,13 @@ hipError_t launch_decode_attn(const AttnLaunch &a, hipStream_t stream, hipEvent_
   args.block_table = a.batch.block_table;
   args.ctx_lens = a.batch.ctx_lens;
   args.chunk_prefix = a.batch.chunk_prefix;
+  args.chunk_size = a.batch.chunk_size;
   args.item_seq = a.batch.item_seq;
   args.H = s.H;
   args.G = s.G;
   args.log2_T = s.log2_T;
   args.tcap = s.tcap;
   args.max_blocks = s.max_blocks;
-  args.split_tokens = a.batch.split_tokens;
   args.n_items = a.batch.n_items;
   args.out_fp32 = a.out_fp32;
   // exp(x) = 2^(x log2 e): the 1/sqrt(d) scale and log2 e are folded into one factor
@@ -450,6 +453,7 @@ constexpr int kStepThreads = 256;
 
 __global__ __launch_bounds__(kStepThreads) void step_advance_kernel(int32_t *ctx_lens,
                                                                    int32_t *chunk_prefix,
+                                                                   int32_t *chunk_size,
                                                                    int32_t *item_seq, int32_t B,
                                                                    int32_t S, int32_t inc) {
   __shared__ int32_t part[kStepThreads];
@@ -460,7 +464,10 @@ __global__ __launch_bounds__(kStepThreads) void step_advance_kernel(int32_t *ctx
   for (int b = b0; b < b1; ++b) {
     const int32_t n = ctx_lens[b] + inc;
     ctx_lens[b] = n;
-    mine += (n + S - 1) / S;
+    int32_t cnt, sz;
+    seq_chunks(n, S, &cnt, &sz);
+    chunk_size[b] = sz;
+    mine += cnt;
   }
   part[tid] = mine;
   __syncthreads();
@@ -473,7 +480,8 @@ __global__ __launch_bounds__(kStepThreads) void step_advance_kernel(int32_t *ctx
   int32_t at = part[tid] - mine;                               // exclusive prefix of this thread
   for (int b = b0; b < b1; ++b) {
     chunk_prefix[b] = at;
-    const int32_t cnt = (ctx_lens[b] + S - 1) / S;
+    int32_t cnt, sz;
+    seq_chunks(ctx_lens[b], S, &cnt, &sz);
     for (int32_t c = 0; c < cnt; ++c) item_seq[at + c] = b;
     at += cnt;
   }
@@ -483,7 +491,7 @@ __global__ __launch_bounds__(kStepThreads) void step_advance_kernel(int32_t *ctx
 __global__ void worklist_dump_kernel(BatchState bs, int32_t *items) {
   const int it = blockIdx.x * blockDim.x + threadIdx.x;
   if (it >= bs.n_items) return;
-  const ItemRange r = decode_item(it, bs.item_seq, bs.chunk_prefix, bs.ctx_lens, bs.split_tokens);
+  const ItemRange r = decode_item(it, bs.item_seq, bs.chunk_prefix, bs.chunk_size, bs.ctx_lens);
   items[it * 3 + 0] = r.b;
   items[it * 3 + 1] = r.lo;
   items[it * 3 + 2] = r.hi;
@@ -506,10 +514,11 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const uint4 *src, int64
 
 }  // namespace
 
-hipError_t launch_step_advance(int32_t *ctx_lens, int32_t *chunk_prefix, int32_t *item_seq,
-                               int32_t B, int32_t S, int32_t inc, hipStream_t stream) {
+hipError_t launch_step_advance(int32_t *ctx_lens, int32_t *chunk_prefix, int32_t *chunk_size,
+                               int32_t *item_seq, int32_t B, int32_t S, int32_t inc,
+                               hipStream_t stream) {
   hipLaunchKernelGGL(step_advance_kernel, dim3(1), dim3(kStepThreads), 0, stream, ctx_lens,
-                     chunk_prefix, item_seq, B, S, inc);
+                     chunk_prefix, chunk_size, item_seq, B, S, inc);
   return hipGetLastError();
 }
 

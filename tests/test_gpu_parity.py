@@ -292,6 +292,29 @@ def test_error_paths():
     assert e.value.code == binding.OKV_EINVAL
 
 
+def test_probe_kernels_and_link_measurement():
+    say("probe kernels")
+    n = 1 << 24
+    src = torch.randint(0, 255, (n,), dtype=torch.uint8, device="cuda")
+    dst = torch.zeros(n, dtype=torch.uint8, device="cuda")
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    s = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    binding.okv_probe_copy(dst, src, n, s.cuda_stream)
+    binding.okv_probe_read(src, n, sink, s.cuda_stream)
+    s.synchronize()
+    assert torch.equal(dst, src)
+    with pytest.raises(binding.OkvError):
+        binding.okv_probe_copy(dst, src, n - 3, s.cuda_stream)          # not a multiple of 16
+    host = torch.empty(n, dtype=torch.uint8, pin_memory=True)
+    host.copy_(src)
+    dst.zero_()
+    torch.cuda.synchronize()
+    gbps = binding.okv_measure_h2d(dst, host, n, 3, s.cuda_stream)
+    assert gbps > 1.0
+    assert torch.equal(dst, src)
+
+
 # ---- the benchmark shapes at full size, sampled -----------------------------------------------------
 
 def _sampled_full_size(name, B, H, G, T, ctx_before, cap, on_host, pairs, steps=2, L=2):
@@ -321,6 +344,14 @@ def test_full_size_cfg2_last_steps_sampled():
 def test_full_size_cfg3_paged_half_offloaded_sampled():
     # batch 64, context 2048, 16-token blocks, one resident and one host layer (2 GiB each)
     _sampled_full_size("cfg3", 64, 32, 32, 16, [2047] * 64, 2064, [0, 1], [(0, 0), (63, 31), (20, 11)])
+
+
+def test_full_size_cfg5_shape_reduced_batch_sampled():
+    # context 4096, 16-token blocks, 3 of 5 layers on the host (60 %); batch 16 of the 192
+    on_host = binding.kv_offload_plan(5, 3, 5)[0]
+    assert on_host.tolist() == [0, 1, 0, 1, 1]
+    _sampled_full_size("cfg5 shape", 16, 32, 32, 16, [4094] * 16, 4112, on_host, [(0, 0), (15, 31), (7, 16)],
+                       steps=2, L=5)
 
 
 def test_full_size_cfg4_gqa_ragged_sampled():

@@ -110,24 +110,36 @@ def test_paper_offline_runs_are_transfer_bound_as_the_formulas_say():
 
 def test_worklist_expected_items_tile_exactly():
     rng = np.random.default_rng(3)
-    for _ in range(50):
+    for _ in range(200):
         B = int(rng.integers(1, 6))
-        ctx = rng.integers(1, 70, size=B)
-        S = int(rng.integers(1, 40))
+        ctx = rng.integers(0, 700, size=B)
+        S = int(rng.integers(1, 400))
         items = worklist.expected_items(ctx, S)
         assert worklist.check_tiling(items, ctx)
-        assert all(hi - lo <= S for _, lo, hi in items)
-        assert len(items) == sum(-(-int(n) // S) for n in ctx)
-    items = worklist.expected_items([5, 3], 2)
-    assert items == [(0, 0, 2), (0, 2, 4), (0, 4, 5), (1, 0, 2), (1, 2, 3)]
+        for b, n in enumerate(ctx):
+            mine = [(lo, hi) for bb, lo, hi in items if bb == b]
+            if n == 0:
+                assert not mine
+                continue
+            assert all(lo % 16 == 0 for lo, _ in mine)                 # items start on tile boundaries
+            sizes = [hi - lo for lo, hi in mine]
+            assert max(sizes) <= max(S, 16) + 15                        # at most S, up to the rounding
+            assert len(set(sizes[:-1])) <= 1                            # equal pieces, last one shorter
+            assert len(mine) <= -(-int(n) // S)                         # never more items than ceil(n / S)
+    # hand cases: 1100 keys, S = 1024 -> two pieces of 560 (not 1024 + 76)
+    assert worklist.expected_items([1100], 1024) == [(0, 0, 560), (0, 560, 1100)]
+    assert worklist.expected_items([17], 8) == [(0, 0, 16), (0, 16, 17)]
+    assert worklist.expected_items([1024, 513], 1024) == [(0, 0, 1024), (1, 0, 513)]
+    assert worklist.expected_items([5, 0, 3], 2) == [(0, 0, 5), (2, 0, 3)]
 
 
 def test_worklist_checker_rejects_bad_tilings():
-    ctx = [5, 3]
-    good = worklist.expected_items(ctx, 2)
+    ctx = [40, 20]
+    good = worklist.expected_items(ctx, 16)
+    assert worklist.check_tiling(good, ctx) and len(good) == 5
     assert not worklist.check_tiling(good[:-1], ctx)                  # a gap
     assert not worklist.check_tiling(good + [(1, 0, 1)], ctx)         # an overlap
-    assert not worklist.check_tiling(good[:-1] + [(1, 2, 4)], ctx)    # beyond the context
+    assert not worklist.check_tiling(good[:-1] + [(1, 16, 24)], ctx)  # beyond the context
     assert not worklist.check_tiling([(2, 0, 1)] + good, ctx)         # unknown sequence
 
 
