@@ -33,9 +33,9 @@ PCIE5_X16_GBPS = 64.0       # nominal, one direction
 # okv_kernels.hip has changed since, `traffic` is reported as null.
 TRAFFIC_RECORD = {
     "workload": "cfg2", "steps": 512,
-    "kernel_sha256": "",
-    "fetch_kib": 0.0, "fetch_scale": 2.0,
-    "write_kib": 0.0, "write_scale": 1.0,
+    "kernel_sha256": "7fa364811eca8c25b64e4d63f9dbd19b9281c2c20ae5684e04f0b311c743a174",
+    "fetch_kib": 199115.1, "fetch_scale": 2.0000,
+    "write_kib": 768.0, "write_scale": 1.0000,
 }
 
 
@@ -151,6 +151,8 @@ def run_resident(args):
     w = dict(synth.WORKLOADS[args.workload])
     steps = args.steps if args.steps else w["steps"]
     L, H, G, d, B, T = w["L"], w["H"], w["G"], w["d"], w["B"], w["T"]
+    if args.layers:
+        L = min(L, args.layers)
     if w["ragged"]:
         ctx_first = synth.ragged_ctx_lens(B, w["ragged"][0], w["ragged"][1], args.seed)
     else:
@@ -271,6 +273,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg4"])
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--layers", type=int, default=0,
+                    help="run only this many layers of the stack (counter runs: per-launch figures do not "
+                         "depend on the depth); 0 = the workload's own depth")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
     ap.add_argument("--no-offload", action="store_true", help="skip the offloaded leg")
