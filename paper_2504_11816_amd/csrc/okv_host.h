@@ -124,9 +124,9 @@ class Scheduler {
 // multiple of 16 (so that items start on tile boundaries), which leaves
 // count = ceil(n_b / size) items.  Equal pieces matter when the launch is a single
 // round of wavefronts: the longest item sets the time.  chunk_prefix[b] = number of
-// items of sequences 0 .. b-1; item `it` belongs to sequence item_seq[it], is its
-// chunk c = it - chunk_prefix[b] and covers keys [c * size_b, min((c + 1) * size_b, n_b)).
-// The same arithmetic runs on the host (grid size, checks) and in the kernels.
+// items of sequences 0 .. b-1; chunk c of sequence b is item chunk_prefix[b] + c and
+// covers keys [c * size_b, min((c + 1) * size_b, n_b)).  The same arithmetic runs on
+// the host (item count, checks) and in the kernel that builds the item list.
 struct ItemRange {
   int32_t b, lo, hi;
 };
@@ -143,16 +143,11 @@ __host__ __device__ inline void seq_chunks(int32_t n, int32_t S, int32_t *count,
   *count = (n + sz - 1) / sz;
 }
 
-__host__ __device__ inline ItemRange decode_item(int32_t it, const int32_t *item_seq,
-                                                 const int32_t *chunk_prefix,
-                                                 const int32_t *chunk_size,
-                                                 const int32_t *ctx_lens) {
+// Chunk c of sequence b with n keys and chunk size sz.
+__host__ __device__ inline ItemRange chunk_range(int32_t b, int32_t c, int32_t sz, int32_t n) {
   ItemRange r;
-  r.b = item_seq[it];
-  const int32_t c = it - chunk_prefix[r.b];
-  const int32_t sz = chunk_size[r.b];
+  r.b = b;
   r.lo = c * sz;
-  const int32_t n = ctx_lens[r.b];
   r.hi = r.lo + sz < n ? r.lo + sz : n;
   return r;
 }

@@ -19,9 +19,8 @@ struct PoolShape {
 struct BatchState {        // device arrays owned by the context
   const int32_t *block_table;   // [B][max_blocks]
   const int32_t *ctx_lens;      // [B]
-  const int32_t *chunk_prefix;  // [B + 1]
-  const int32_t *chunk_size;    // [B] keys per item of the sequence (multiple of 16)
-  const int32_t *item_seq;      // [n_items]
+  const int32_t *chunk_prefix;  // [B + 1] items of the sequences before b
+  const int4 *item_desc;        // [n_items] (sequence, first key, one past last key, flags)
   int32_t B;
   int32_t split_tokens;
   int32_t n_items;
@@ -40,6 +39,8 @@ struct AttnLaunch {
   float *part_ml;          // [n_items * H][2]  (max in log2 units, sum)
   int32_t out_fp32;
   int32_t need_merge;      // some sequence has more than one item
+  uint32_t *queue;         // this launch's ticket counter (zeroed by launch_step_advance)
+  int32_t max_waves;       // wavefronts of the persistent launch (a multiple of 4)
 };
 
 // Store of the step's K/V rows and split-K partial attention in one launch, followed,
@@ -47,10 +48,11 @@ struct AttnLaunch {
 hipError_t launch_decode_attn(const AttnLaunch &a, hipStream_t stream,
                               hipEvent_t ev_begin, hipEvent_t ev_end);
 
-// ctx_lens[b] += inc; rebuilds chunk_prefix, chunk_size and item_seq for split size S.
-hipError_t launch_step_advance(int32_t *ctx_lens, int32_t *chunk_prefix, int32_t *chunk_size,
-                               int32_t *item_seq, int32_t B, int32_t S, int32_t inc,
-                               hipStream_t stream);
+// ctx_lens[b] += inc; rebuilds chunk_prefix and the item list for split size S; zeroes the
+// n_queues ticket counters.
+hipError_t launch_step_advance(int32_t *ctx_lens, int32_t *chunk_prefix, int4 *item_desc,
+                               uint32_t *queues, int32_t n_queues, int32_t B, int32_t S,
+                               int32_t inc, hipStream_t stream);
 
 // items[it] = (b, lo, hi) decoded on the device.
 hipError_t launch_worklist_dump(const BatchState &batch, int32_t *items, hipStream_t stream);

@@ -18,6 +18,8 @@
 //     every sequence has a single item).
 #include "okv_kernels.h"
 
+#include <algorithm>
+
 #include "okv_host.h"
 
 namespace okv {
@@ -25,12 +27,14 @@ namespace okv {
 namespace {
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef const int32_t __attribute__((address_space(4))) *const_i32_ptr;   // never written while a kernel runs
 
 #ifndef OKV_WAVES_PER_BLOCK
 #define OKV_WAVES_PER_BLOCK 4
 #endif
 constexpr int kWavesPerBlock = OKV_WAVES_PER_BLOCK;   // independent work items per workgroup
 constexpr float kNegBig = -1.0e30f;   // "no key seen yet"; finite so that differences stay finite
+constexpr int kItemLast = 1, kItemWhole = 2;   // flags of a work item (item_desc.w)
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_move(float x) {
@@ -129,29 +133,29 @@ struct AttnArgs {
   void *out;
   float *part_o;
   float *part_ml;
-  const int32_t *block_table, *ctx_lens, *chunk_prefix, *chunk_size, *item_seq;
-  int32_t H, G, log2_T, tcap, max_blocks, n_items, out_fp32;
+  const int32_t *block_table, *chunk_prefix;
+  const int4 *item_desc;           // [n_items] (sequence, first key, one past last key, flags)
+  uint32_t *queue;                 // ticket counter of this launch, zero when the kernel starts
+  int32_t H, G, log2_T, tcap, max_blocks, n_items, n_units, out_fp32;
   float scale_log2e;
 };
 
+// One work item (a run of keys of one sequence) for one KV head, by one wavefront.
 template <int D, int R, bool PAGED, int PIPE>
-__global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_kernel(const AttnArgs a) {
+__device__ __forceinline__ void attend_item(const AttnArgs &a, const int it, const int g, const int lane) {
   constexpr int LPR = D / 8, RPL = 64 / LPR, LPT = D / 32;
-  const int lane = threadIdx.x & 63;
-  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int it = blockIdx.x * kWavesPerBlock + wave;
-  if (it >= a.n_items) return;                       // whole wavefront leaves together
-  const int g = blockIdx.y;
-  const ItemRange ir = decode_item(it, a.item_seq, a.chunk_prefix, a.chunk_size, a.ctx_lens);
-  const int b = ir.b, lo = ir.lo, hi = ir.hi;
   const int row = lane / LPR, col = lane % LPR;
+  const int4 desc = a.item_desc[it];
+  const int b = desc.x, lo = desc.y, hi = desc.z;
+  const bool seq_last = (desc.w & kItemLast) != 0;        // the item ends at the sequence's last key
+  const bool seq_whole = (desc.w & kItemWhole) != 0;      // and is the sequence's only item
 
   // The item that ends at the sequence's last key also stores this step's K/V rows
   // (paper §II-A: keys and values of every processed token are kept).  The rows are
   // patched into the tile in registers, so the attention below does not depend on
-  // reading its own store back; the store itself is issued at the end of the kernel.
-  const int pos = a.ctx_lens[b] - 1;
-  const bool appending = a.k_new != nullptr && hi == pos + 1;
+  // reading its own store back; the store itself is issued after the reduction.
+  const int pos = hi - 1;
+  const bool appending = a.k_new != nullptr && seq_last;
   uint4 k_row = make_uint4(0u, 0u, 0u, 0u), v_row = k_row;
   if (appending) {
     const size_t at = ((size_t)b * a.G + g) * LPR + col;
@@ -174,13 +178,16 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_kernel(const A
     for (int e = 0; e < 8; ++e) o[r][e] = 0.f;
   }
 
-  const int t_begin = lo >> 4, t_end = (hi + 15) >> 4;      // 16-token tiles, absolute grid
+  const int t0 = lo >> 4, t1 = (hi + 15) >> 4;               // 16-token tiles; lo is a multiple of 16
   const int64_t slice = (int64_t)a.tcap * D;                 // elements of one (blk, kv, g) slice
   const int64_t kv_stride = slice * a.G;                     // K slice -> V slice of the same block
 
   // Block id of a tile: a wavefront-uniform (scalar) load from the block table.  The index
   // is clamped so that look-ahead past the item's last tile stays inside the table.
-  const int32_t *tbl_row = a.block_table + (size_t)b * a.max_blocks;
+  // The table is read through the constant address space: the kernel also stores (outputs,
+  // appended rows) and without that promise the compiler would turn these look-ups into
+  // vector loads, which share the tile loads' counter and would drain the pipeline.
+  const const_i32_ptr tbl_row = (const_i32_ptr)(uintptr_t)(a.block_table + (size_t)b * a.max_blocks);
   auto blk_of = [&](int tile) -> int {
     if (!PAGED) return b;
     int bi = (tile << 4) >> a.log2_T;
@@ -197,41 +204,30 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_kernel(const A
 #pragma unroll
     for (int j = 0; j < LPT; ++j) t.v[j] = vp[j * 64];
   };
-  auto is_full = [&](int tile) {
-    return (tile << 4) >= lo && (tile << 4) + 16 <= hi && !(appending && tile == (pos >> 4));
+  // Steady state: every tile is full (only the item's last tile can stick out of [lo, hi)
+  // or hold the appended row, and the last tile is always reduced in the drain below).
+  auto update = [&](const Tile<LPT> &t, int tile) {
+    tile_update<D, R, false>(t, q, m, l, o, (tile << 4) + row, lo, hi, a.scale_log2e);
   };
-
-  Tile<LPT> buf[PIPE];
-
-  // Tiles that stick out of [lo, hi) can only be the first and the last one.  They are
-  // reduced first, one at a time, with the masked update; the order of tiles does not
-  // matter to the running softmax.
-  int t0 = t_begin, t1 = t_end;
-#pragma nounroll
-  for (int k = 0; k < 2; ++k) {
-    if (t0 >= t1) break;
-    const int tile = k == 0 ? t0 : t1 - 1;
-    if (is_full(tile)) continue;
-    load_tile(buf[0], tile, blk_of(tile));
+  // Drain: masked form for every tile (at most 2 * PIPE - 1 of them); the appended row
+  // replaces whatever the slot held.
+  auto update_last = [&](Tile<LPT> &t, int tile) {
     if (appending && tile == (pos >> 4)) {
 #pragma unroll
       for (int j = 0; j < LPT; ++j)
         if ((tile << 4) + row + j * RPL == pos) {
-          buf[0].k[j] = k_row;
-          buf[0].v[j] = v_row;
+          t.k[j] = k_row;
+          t.v[j] = v_row;
         }
     }
-    tile_update<D, R, true>(buf[0], q, m, l, o, (tile << 4) + row, lo, hi, a.scale_log2e);
-    if (k == 0) ++t0; else --t1;
-  }
-
-  // Full tiles [t0, t1): PIPE tiles are in flight ahead of the one being reduced.  The
-  // steady-state loop has no conditional loads, so each wait covers exactly the tile
-  // it needs and the younger loads stay in flight; block ids are fetched one refill
-  // ahead through the scalar cache, which has its own counter.
-  auto update = [&](const Tile<LPT> &t, int tile) {
-    tile_update<D, R, false>(t, q, m, l, o, (tile << 4) + row, lo, hi, a.scale_log2e);
+    tile_update<D, R, true>(t, q, m, l, o, (tile << 4) + row, lo, hi, a.scale_log2e);
   };
+
+  // PIPE tiles are in flight ahead of the one being reduced.  The steady-state loop has no
+  // conditional loads, so each wait covers exactly the tile it needs and the younger loads
+  // stay in flight; block ids are fetched one refill ahead through the scalar cache, which
+  // has its own counter.
+  Tile<LPT> buf[PIPE];
   int t = t0;
   if (t1 - t0 >= 2 * PIPE) {
     int next_blk[PIPE];
@@ -258,15 +254,14 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_kernel(const A
 #pragma unroll
   for (int i = 0; i < PIPE; ++i)
     if (t + i < t1) {
-      update(buf[i], t + i);
+      update_last(buf[i], t + i);
       if (t + i + PIPE < t1) load_tile(buf[i], t + i + PIPE, blk_of(t + i + PIPE));
     }
 #pragma unroll
   for (int i = 0; i < PIPE; ++i)
-    if (t + PIPE + i < t1) update(buf[i], t + PIPE + i);
+    if (t + PIPE + i < t1) update_last(buf[i], t + PIPE + i);
 
   // Combine the RPL rows of the wavefront (each saw the tokens congruent to its row).
-  const int n_chunks = a.chunk_prefix[b + 1] - a.chunk_prefix[b];
 #pragma unroll
   for (int r = 0; r < R; ++r) {
     float mt = m[r];
@@ -286,7 +281,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_kernel(const A
     }
     if (row != 0) continue;
     const int h = g * R + r;
-    if (n_chunks == 1) {                               // the item is the whole sequence
+    if (seq_whole) {                                   // the item is the whole sequence
       const float inv = 1.0f / lt;
       const size_t at = ((size_t)b * a.H + h) * D + col * 8;
       if (a.out_fp32) {
@@ -320,28 +315,88 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_kernel(const A
   }
 }
 
+// Persistent wavefronts: each one starts on the unit (item, KV head) with its own number
+// and then draws further units from a ticket counter until none are left, so a faster
+// compute unit or XCD simply takes more of them (workgroups are dealt to the eight XCDs in
+// fixed rotation, which a static split cannot correct).  A launch that has no more units
+// than wavefronts never touches the counter: same-address atomics are served one at a
+// time, and a burst of them at the start would cost more than it balances.  Every
+// wavefront leaves as soon as its ticket is past the end; nothing ever waits.
+template <int D, int R, bool PAGED, int PIPE>
+__global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_kernel(const AttnArgs a) {
+  const int lane = threadIdx.x & 63;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t n_waves = gridDim.x * kWavesPerBlock;
+  uint32_t ticket = blockIdx.x * kWavesPerBlock + wave;
+  while (ticket < (uint32_t)a.n_units) {
+    const int it = (int)(ticket / (uint32_t)a.G);
+    const int g = (int)(ticket - (uint32_t)it * (uint32_t)a.G);
+    attend_item<D, R, PAGED, PIPE>(a, it, g, lane);
+    if (n_waves >= (uint32_t)a.n_units) break;           // every unit had its own wavefront
+    uint32_t drawn = 0;
+    if (lane == 0) drawn = atomicAdd(a.queue, 1u);
+    ticket = n_waves + __builtin_amdgcn_readfirstlane(drawn);
+  }
+}
+
 // out[b][h] = sum_c o_c 2^(m_c - M) / sum_c l_c 2^(m_c - M) over the items c of sequence b.
+// One wavefront per (b, h).  Lane c first fetches (m_c, l_c) of item c, so the maxima and
+// weights of up to 64 items are formed by wavefront reductions instead of a chain of
+// dependent loads; the weighted sums then stream the partial rows four items at a time.
 template <int D>
 __global__ __launch_bounds__(64) void attn_merge_kernel(const AttnArgs a) {
   constexpr int EPT = D / 64;
-  const int b = blockIdx.y, h = blockIdx.x;
+  const int b = blockIdx.y, h = blockIdx.x, lane = threadIdx.x;
   const int first = a.chunk_prefix[b];
   const int n_chunks = a.chunk_prefix[b + 1] - first;
   if (n_chunks <= 1) return;                           // written by the split kernel
   float M = kNegBig;
-  for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, a.part_ml[((size_t)(first + c) * a.H + h) * 2]);
+  for (int c0 = 0; c0 < n_chunks; c0 += 64) {
+    const int c = c0 + lane;
+    float mc = c < n_chunks ? a.part_ml[((size_t)(first + c) * a.H + h) * 2] : kNegBig;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) mc = fmaxf(mc, __shfl_xor(mc, off));
+    M = fmaxf(M, mc);
+  }
   float L = 0.f, acc[EPT];
 #pragma unroll
   for (int e = 0; e < EPT; ++e) acc[e] = 0.f;
-  for (int c = 0; c < n_chunks; ++c) {
-    const size_t slot = (size_t)(first + c) * a.H + h;
-    const float w = __builtin_amdgcn_exp2f(a.part_ml[slot * 2] - M);
-    L += a.part_ml[slot * 2 + 1] * w;
+  for (int c0 = 0; c0 < n_chunks; c0 += 64) {
+    const int c = c0 + lane;
+    float w = 0.f, lw = 0.f;
+    if (c < n_chunks) {
+      const float2 ml = *reinterpret_cast<const float2 *>(a.part_ml + ((size_t)(first + c) * a.H + h) * 2);
+      w = __builtin_amdgcn_exp2f(ml.x - M);
+      lw = ml.y * w;
+    }
 #pragma unroll
-    for (int e = 0; e < EPT; ++e) acc[e] += a.part_o[slot * D + threadIdx.x * EPT + e] * w;
+    for (int off = 32; off > 0; off >>= 1) lw += __shfl_xor(lw, off);
+    L += lw;
+    const int cnt = min(64, n_chunks - c0);
+    int i = 0;
+    for (; i + 4 <= cnt; i += 4) {                     // four independent rows in flight
+      float x[4][EPT];
+#pragma unroll
+      for (int k = 0; k < 4; ++k)
+#pragma unroll
+        for (int e = 0; e < EPT; ++e)
+          x[k][e] = a.part_o[((size_t)(first + c0 + i + k) * a.H + h) * D + lane * EPT + e];
+#pragma unroll
+      for (int k = 0; k < 4; ++k) {
+        const float wk = __shfl(w, i + k);
+#pragma unroll
+        for (int e = 0; e < EPT; ++e) acc[e] += x[k][e] * wk;
+      }
+    }
+    for (; i < cnt; ++i) {
+      const float wk = __shfl(w, i);
+#pragma unroll
+      for (int e = 0; e < EPT; ++e)
+        acc[e] += a.part_o[((size_t)(first + c0 + i) * a.H + h) * D + lane * EPT + e] * wk;
+    }
   }
   const float inv = 1.0f / L;
-  const size_t at = ((size_t)b * a.H + h) * D + threadIdx.x * EPT;
+  const size_t at = ((size_t)b * a.H + h) * D + lane * EPT;
 #pragma unroll
   for (int e = 0; e < EPT; ++e) {
     if (a.out_fp32)
@@ -409,21 +464,24 @@ hipError_t launch_decode_attn(const AttnLaunch &a, hipStream_t stream, hipEvent_
   args.part_o = a.part_o;
   args.part_ml = a.part_ml;
   args.block_table = a.batch.block_table;
-  args.ctx_lens = a.batch.ctx_lens;
   args.chunk_prefix = a.batch.chunk_prefix;
-  args.chunk_size = a.batch.chunk_size;
-  args.item_seq = a.batch.item_seq;
+  args.item_desc = a.batch.item_desc;
+  args.queue = a.queue;
   args.H = s.H;
   args.G = s.G;
   args.log2_T = s.log2_T;
   args.tcap = s.tcap;
   args.max_blocks = s.max_blocks;
   args.n_items = a.batch.n_items;
+  args.n_units = a.batch.n_items * s.G;
   args.out_fp32 = a.out_fp32;
   // exp(x) = 2^(x log2 e): the 1/sqrt(d) scale and log2 e are folded into one factor
   args.scale_log2e = 1.4426950408889634f / sqrtf((float)s.D);
   const int R = s.H / s.G;
-  dim3 grid((a.batch.n_items + kWavesPerBlock - 1) / kWavesPerBlock, s.G);
+  // persistent launch: no more wavefronts than there are units, no more than a.max_waves
+  const int64_t want = ((int64_t)args.n_units + kWavesPerBlock - 1) / kWavesPerBlock;
+  const int64_t cap = std::max<int64_t>(1, a.max_waves / kWavesPerBlock);
+  dim3 grid((unsigned)std::min(want, cap));
   hipError_t e;
   if (ev_begin && (e = hipEventRecord(ev_begin, stream)) != hipSuccess) return e;
   if (s.D == 128)
@@ -453,11 +511,12 @@ constexpr int kStepThreads = 256;
 
 __global__ __launch_bounds__(kStepThreads) void step_advance_kernel(int32_t *ctx_lens,
                                                                    int32_t *chunk_prefix,
-                                                                   int32_t *chunk_size,
-                                                                   int32_t *item_seq, int32_t B,
+                                                                   int4 *item_desc, uint32_t *queues,
+                                                                   int32_t n_queues, int32_t B,
                                                                    int32_t S, int32_t inc) {
   __shared__ int32_t part[kStepThreads];
   const int tid = threadIdx.x;
+  for (int i = tid; i < n_queues; i += kStepThreads) queues[i] = 0u;   // one ticket counter per layer
   const int per = (B + kStepThreads - 1) / kStepThreads;     // consecutive sequences per thread
   const int b0 = tid * per, b1 = min(B, b0 + per);
   int32_t mine = 0;
@@ -466,7 +525,6 @@ __global__ __launch_bounds__(kStepThreads) void step_advance_kernel(int32_t *ctx
     ctx_lens[b] = n;
     int32_t cnt, sz;
     seq_chunks(n, S, &cnt, &sz);
-    chunk_size[b] = sz;
     mine += cnt;
   }
   part[tid] = mine;
@@ -480,9 +538,14 @@ __global__ __launch_bounds__(kStepThreads) void step_advance_kernel(int32_t *ctx
   int32_t at = part[tid] - mine;                               // exclusive prefix of this thread
   for (int b = b0; b < b1; ++b) {
     chunk_prefix[b] = at;
+    const int32_t n = ctx_lens[b];
     int32_t cnt, sz;
-    seq_chunks(ctx_lens[b], S, &cnt, &sz);
-    for (int32_t c = 0; c < cnt; ++c) item_seq[at + c] = b;
+    seq_chunks(n, S, &cnt, &sz);
+    for (int32_t c = 0; c < cnt; ++c) {
+      const ItemRange r = chunk_range(b, c, sz, n);
+      const int32_t flags = (c == cnt - 1 ? kItemLast : 0) | (cnt == 1 ? kItemWhole : 0);
+      item_desc[at + c] = make_int4(r.b, r.lo, r.hi, flags);
+    }
     at += cnt;
   }
   if (tid == kStepThreads - 1) chunk_prefix[B] = part[tid];
@@ -491,10 +554,10 @@ __global__ __launch_bounds__(kStepThreads) void step_advance_kernel(int32_t *ctx
 __global__ void worklist_dump_kernel(BatchState bs, int32_t *items) {
   const int it = blockIdx.x * blockDim.x + threadIdx.x;
   if (it >= bs.n_items) return;
-  const ItemRange r = decode_item(it, bs.item_seq, bs.chunk_prefix, bs.chunk_size, bs.ctx_lens);
-  items[it * 3 + 0] = r.b;
-  items[it * 3 + 1] = r.lo;
-  items[it * 3 + 2] = r.hi;
+  const int4 d = bs.item_desc[it];
+  items[it * 3 + 0] = d.x;
+  items[it * 3 + 1] = d.y;
+  items[it * 3 + 2] = d.z;
 }
 
 __global__ __launch_bounds__(256) void probe_copy_kernel(uint4 *dst, const uint4 *src, int64_t n) {
@@ -514,11 +577,11 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const uint4 *src, int64
 
 }  // namespace
 
-hipError_t launch_step_advance(int32_t *ctx_lens, int32_t *chunk_prefix, int32_t *chunk_size,
-                               int32_t *item_seq, int32_t B, int32_t S, int32_t inc,
-                               hipStream_t stream) {
+hipError_t launch_step_advance(int32_t *ctx_lens, int32_t *chunk_prefix, int4 *item_desc,
+                               uint32_t *queues, int32_t n_queues, int32_t B, int32_t S,
+                               int32_t inc, hipStream_t stream) {
   hipLaunchKernelGGL(step_advance_kernel, dim3(1), dim3(kStepThreads), 0, stream, ctx_lens,
-                     chunk_prefix, chunk_size, item_seq, B, S, inc);
+                     chunk_prefix, item_desc, queues, n_queues, B, S, inc);
   return hipGetLastError();
 }
 
