@@ -234,6 +234,12 @@ int okv_profile_read(okv_ctx *ctx, double *attn_ms, int64_t *attn_launches);
 int okv_measure_h2d(void *dst, const void *src, int64_t bytes, int32_t reps, void *stream,
                     double *gbps_median);
 
+/* The copies of one decode step alone: every host layer's pool is copied into the staging
+ * buffers (alternating), back to back on the h2d stream, nothing else running; *ms receives
+ * the elapsed time.  The yardstick for how well a real step hides its compute behind the
+ * copies.  Needs a batch (okv_set_batch), must not be called inside a step.  Synchronous. */
+int okv_time_copies(okv_ctx *ctx, double *ms);
+
 /* A plain device-to-device copy kernel (16 bytes per lane, grid-stride), the
  * yardstick the attention kernel's HBM traffic and rate are compared with.
  * bytes must be a multiple of 16.  Asynchronous on `stream`. */

@@ -20,7 +20,8 @@ EXPORTS = [
     "okv_schedule_trace", "okv_create", "okv_destroy", "okv_last_error", "okv_set_batch",
     "okv_step_begin", "okv_step_end", "kv_append", "decode_attn", "okv_synchronize",
     "okv_set_split_tokens", "okv_get_split_tokens", "okv_get_ctx_lens", "okv_worklist",
-    "okv_profile_enable", "okv_profile_read", "okv_measure_h2d", "okv_probe_copy", "okv_probe_read",
+    "okv_profile_enable", "okv_profile_read", "okv_measure_h2d", "okv_time_copies", "okv_probe_copy",
+    "okv_probe_read",
 ]
 
 
@@ -79,6 +80,7 @@ def lib():
             "okv_profile_enable": (ctypes.c_int, [P, I32]),
             "okv_profile_read": (ctypes.c_int, [P, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(I64)]),
             "okv_measure_h2d": (ctypes.c_int, [P, P, I64, I32, P, ctypes.POINTER(ctypes.c_double)]),
+            "okv_time_copies": (ctypes.c_int, [P, ctypes.POINTER(ctypes.c_double)]),
             "okv_probe_copy": (ctypes.c_int, [P, P, I64, P]),
             "okv_probe_read": (ctypes.c_int, [P, I64, P, P]),
         }
@@ -254,6 +256,11 @@ class Context:
         n = ctypes.c_int64(0)
         self._c(lib().okv_worklist(self._h, 1 if from_device else 0, _ptr(items), max_items, ctypes.byref(n)))
         return items[:n.value].copy()
+
+    def okv_time_copies(self):
+        ms = ctypes.c_double(0)
+        self._c(lib().okv_time_copies(self._h, ctypes.byref(ms)))
+        return ms.value
 
     def okv_profile_enable(self, on):
         self._c(lib().okv_profile_enable(self._h, 1 if on else 0))

@@ -745,6 +745,40 @@ int okv_measure_h2d(void *dst, const void *src, int64_t bytes, int32_t reps, voi
   return OKV_OK;
 }
 
+int okv_time_copies(okv_ctx *ctx, double *ms) {
+  if (!ctx || !ms) return fail(ctx, OKV_EINVAL, "NULL argument");
+  if (!ctx->batch_set) return fail(ctx, OKV_ESTATE, "no batch set");
+  if (ctx->in_step) return fail(ctx, OKV_ESTATE, "okv_time_copies inside a step");
+  *ms = 0;
+  if (!ctx->any_host) return OKV_OK;
+  int rc = okv_synchronize(ctx);
+  if (rc) return rc;
+  hipEvent_t e0, e1;
+  OKV_HIP(ctx, hipEventCreate(&e0));
+  OKV_HIP(ctx, hipEventCreate(&e1));
+  hipError_t e = hipEventRecord(e0, ctx->h2d);
+  int buf = 0;
+  for (int32_t l = 0; l < ctx->cfg.n_layers && e == hipSuccess; ++l) {
+    if (!ctx->host_pool[l]) continue;
+    e = hipMemcpyAsync(ctx->cfg.staging[buf], ctx->host_pool[l], (size_t)ctx->copy_bytes, hipMemcpyHostToDevice, ctx->h2d);
+    buf = (buf + 1) % ctx->n_staging;
+  }
+  if (e == hipSuccess) e = hipEventRecord(e1, ctx->h2d);
+  if (e == hipSuccess) e = hipEventSynchronize(e1);
+  float t = 0;
+  if (e == hipSuccess) e = hipEventElapsedTime(&t, e0, e1);
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (e != hipSuccess) return fail(ctx, OKV_EHIP, "okv_time_copies: %s", hipGetErrorString(e));
+  *ms = t;
+  // the staging buffers no longer hold what the pipeline had prefetched: start it afresh
+  std::vector<uint8_t> on_host(ctx->cfg.n_layers, 0);
+  for (int32_t l = 0; l < ctx->cfg.n_layers; ++l) on_host[l] = ctx->host_pool[l] != nullptr;
+  ctx->sched.reset(ctx->cfg.n_layers, on_host.data(), ctx->n_staging);
+  ctx->step = 0;                                       // copy indices count from the restart
+  return OKV_OK;
+}
+
 int okv_probe_copy(void *dst, const void *src, int64_t bytes, void *stream) {
   if (!dst || !src || bytes < 0 || bytes % 16 || !aligned16(dst) || !aligned16(src))
     return fail(nullptr, OKV_EINVAL, "okv_probe_copy: bad argument");

@@ -64,6 +64,20 @@ def test_result_does_not_depend_on_the_split_size(split):
         assert rel < 2e-5, rel
 
 
+@pytest.mark.parametrize("H,G,d", [(8, 4, 64), (16, 16, 128)])
+def test_more_work_units_than_wavefronts_all_outputs(H, G, d):
+    # Thousands of 16-key items: most units are drawn from the ticket counter by
+    # wavefronts that have already finished one, and every sequence needs the merge.
+    say(f"ticket queue H={H} G={G} d={d}")
+    ctx = synth.ragged_ctx_lens(48, 200, 420, 77)
+    st = build_stack(L=1, H=H, G=G, d=d, T=16, ctx_before=ctx, cap_tokens=448, out_dtype=1, seed=79,
+                     split_tokens=16)
+    n_items = len(st.ctx.okv_worklist(from_device=True))
+    assert n_items * G > 3000
+    run_and_check(st, n_steps=2, seed=81)
+    st.close()
+
+
 def test_paged_equals_contiguous_on_the_same_logical_kv_bit_for_bit():
     say("paged == contiguous")
     B, H, G, d, T, C = 3, 4, 2, 128, 16, 320
