@@ -33,8 +33,8 @@ PCIE5_X16_GBPS = 64.0       # nominal, one direction
 # okv_kernels.hip has changed since, `traffic` is reported as null.
 TRAFFIC_RECORD = {
     "workload": "cfg2", "steps": 512,
-    "kernel_sha256": "7fa364811eca8c25b64e4d63f9dbd19b9281c2c20ae5684e04f0b311c743a174",
-    "fetch_kib": 199115.1, "fetch_scale": 2.0000,
+    "kernel_sha256": "c7cf5686e5011d988559339dab197f39adb6ee3ca3654ebfb0ba59bf8baf06be",
+    "fetch_kib": 199116.0, "fetch_scale": 2.0000,
     "write_kib": 768.0, "write_scale": 1.0000,
 }
 
