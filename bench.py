@@ -247,7 +247,8 @@ def run_offload(args):
     cap = w["ctx"] + steps + warmup
     on_host, n_off = binding.kv_offload_plan(L, w["c_off"][0], w["c_off"][1])
     log(f"[bench] offload leg {name}: B={B} ctx={w['ctx']} T={T} host layers {n_off}/{L} steps={steps}")
-    st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=cap, on_host=on_host, out_dtype=0)
+    st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=cap, on_host=on_host, out_dtype=0,
+               n_staging=args.staging)
     for l in range(L):
         st.fill_pool(l, synth.stream_seed(args.seed, synth.TENSOR_POOL, l))
     table = synth.shuffled_block_table([st.cap_tokens] * B, T, st.blocks_per_layer, args.seed + 1,
@@ -272,7 +273,8 @@ def run_offload(args):
         "link_gbps_achieved": link_bytes / dt / 1e9, "link_frac": link_bytes / dt / 1e9 / link,
         "attn_kernel_ms_per_step": k_s * 1e3, "attn_kernel_gbps": kv_bytes / steps / k_s / 1e9,
         "copy_only_ms_per_step": copy_ms,
-        "pinned_gib": n_off * st.pool_bytes / 2 ** 30,
+        "pinned_gib": n_off * st.pool_bytes / 2 ** 30, "staging_buffers": args.staging,
+        "staging_gib": args.staging * st.pool_bytes / 2 ** 30,
     }
     # What a step costs beyond its copies run back to back, set against the attention it contains:
     # below 1 means compute is (partly) hidden; the per-copy dependency latency of the two-stream
@@ -304,6 +306,7 @@ def main():
     ap.add_argument("--offload-workload", default="cfg3", choices=["cfg3", "cfg5"])
     ap.add_argument("--offload-steps", type=int, default=0)
     ap.add_argument("--offload-batch", type=int, default=0)
+    ap.add_argument("--staging", type=int, default=2, help="staging buffers for host layers (1..4)")
     ap.add_argument("--probe", action="store_true",
                     help="also run the plain copy / read kernels on 1 GiB (the yardstick for HBM counters)")
     args = ap.parse_args()

@@ -51,6 +51,8 @@ extern "C" {
 #define OKV_ESTATE  (-3)  /* call out of order                                      */
 #define OKV_EHIP    (-4)  /* a HIP runtime call failed; see okv_last_error          */
 
+#define OKV_MAX_STAGING 4
+
 typedef struct okv_ctx okv_ctx;   /* opaque */
 
 typedef struct okv_config {
@@ -75,9 +77,11 @@ typedef struct okv_config {
                                   for a resident layer.  Exactly one of dev_pool[l],
                                   host_pool[l] is non-NULL.  May be NULL if no layer is on
                                   the host.                                                   */
-  void   *staging[2];          /* DEVICE: buffers host layers are copied into, each at least
-                                  okv_layer_pool_bytes; staging[1] may be NULL (no overlap of
-                                  copy and compute then); both NULL if no layer is on the host */
+  void   *staging[OKV_MAX_STAGING]; /* DEVICE: buffers host layers are copied into, each at least
+                                  okv_layer_pool_bytes.  The leading non-NULL entries are used:
+                                  one = no overlap of copy and compute; two = the copy of the next
+                                  host layer runs during this one's attention (more than two
+                                  measured no faster).  All NULL if no layer is on the host      */
   int64_t staging_bytes;       /* size of each staging buffer                                */
   void   *workspace;           /* DEVICE: split-K partial results                            */
   int64_t workspace_bytes;     /* at least okv_workspace_bytes(cfg)                          */

@@ -38,7 +38,7 @@ class OkvConfig(ctypes.Structure):
         ("max_blocks_per_seq", ctypes.c_int32), ("max_ctx", ctypes.c_int32),
         ("blocks_per_layer", ctypes.c_int64), ("out_dtype", ctypes.c_int32), ("split_tokens", ctypes.c_int32),
         ("dev_pool", ctypes.POINTER(ctypes.c_void_p)), ("host_pool", ctypes.POINTER(ctypes.c_void_p)),
-        ("staging", ctypes.c_void_p * 2), ("staging_bytes", ctypes.c_int64),
+        ("staging", ctypes.c_void_p * 4), ("staging_bytes", ctypes.c_int64),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_int64),
         ("compute_stream", ctypes.c_void_p), ("h2d_stream", ctypes.c_void_p),
     ]
@@ -195,7 +195,8 @@ class Context:
         cfg.max_ctx, cfg.blocks_per_layer, cfg.out_dtype, cfg.split_tokens = max_ctx, blocks_per_layer, out_dtype, split_tokens
         cfg.dev_pool = ctypes.cast(self._dev, ctypes.POINTER(ctypes.c_void_p))
         cfg.host_pool = ctypes.cast(self._host, ctypes.POINTER(ctypes.c_void_p))
-        cfg.staging[0], cfg.staging[1] = _ptr(staging[0]), _ptr(staging[1])
+        for i in range(4):
+            cfg.staging[i] = _ptr(staging[i] if i < len(staging) else None)
         cfg.staging_bytes = staging_bytes
         cfg.workspace, cfg.workspace_bytes = _ptr(workspace), workspace_bytes
         cfg.compute_stream, cfg.h2d_stream = _ptr(compute_stream), _ptr(h2d_stream)

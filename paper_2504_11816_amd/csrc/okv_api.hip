@@ -19,7 +19,7 @@ using okv::Op;
 
 namespace {
 
-constexpr int kEventRing = 4;            // > copies in flight (at most 2)
+constexpr int kEventRing = 8;            // > copies in flight (at most OKV_MAX_STAGING)
 // Persistent wavefronts per compute unit.  With one query head per KV head the kernel is
 // light on the vector ALU and two wavefronts per SIMD hide each other's item switches;
 // with grouped heads one per SIMD measured faster (5.9 against 5.6 TB/s on ragged batches).
@@ -340,7 +340,7 @@ int okv_plan_from_bytes(int32_t n_layers, int64_t layer_bytes, int64_t mem_avail
 
 int okv_schedule_trace(int32_t n_layers, const uint8_t *on_host, int32_t n_staging, int32_t n_steps,
                        int32_t *ops, int64_t max_ops, int64_t *n_ops) {
-  if (n_layers < 1 || !on_host || n_steps < 0 || !ops || !n_ops || n_staging < 0 || n_staging > 2)
+  if (n_layers < 1 || !on_host || n_steps < 0 || !ops || !n_ops || n_staging < 0 || n_staging > OKV_MAX_STAGING)
     return fail(nullptr, OKV_EINVAL, "okv_schedule_trace: bad argument");
   okv::Scheduler s;
   s.reset(n_layers, on_host, n_staging);
@@ -382,9 +382,10 @@ int okv_create(const okv_config *cfg, okv_ctx **out) {
     if (cfg->staging_bytes < pool_bytes)
       return fail(nullptr, OKV_ENOSPC, "okv_create: staging_bytes %lld < one layer's pool %lld (a layer's KV must fit on the GPU)",
                   (long long)cfg->staging_bytes, (long long)pool_bytes);
-    if (!aligned16(cfg->staging[0]) || !aligned16(cfg->staging[1])) return fail(nullptr, OKV_EINVAL, "okv_create: staging not 16-byte aligned");
+    for (int i = 0; i < OKV_MAX_STAGING; ++i)
+      if (!aligned16(cfg->staging[i])) return fail(nullptr, OKV_EINVAL, "okv_create: staging not 16-byte aligned");
     if (cfg->h2d_stream == cfg->compute_stream) return fail(nullptr, OKV_EINVAL, "okv_create: h2d_stream must differ from compute_stream");
-    n_staging = cfg->staging[1] ? 2 : 1;
+    while (n_staging < OKV_MAX_STAGING && cfg->staging[n_staging]) ++n_staging;
   }
   const int64_t need_ws = okv_workspace_bytes(cfg);
   if (!cfg->workspace || !aligned16(cfg->workspace)) return fail(nullptr, OKV_EINVAL, "okv_create: workspace NULL or misaligned");

@@ -89,7 +89,7 @@ class Stack:
                 self.pools.append(torch.empty(n_el, dtype=torch.float16, device=self.device))
         any_host = bool(self.on_host.any())
         self.staging = [torch.empty(n_el, dtype=torch.float16, device=self.device) if any_host and i < n_staging
-                        else None for i in range(2)]
+                        else None for i in range(4)]
         self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=self.device)
         self.compute_stream = torch.cuda.Stream(device=self.device)
         self.h2d_stream = torch.cuda.Stream(device=self.device)
@@ -100,7 +100,7 @@ class Stack:
             out_dtype=out_dtype, split_tokens=split_tokens,
             dev_pool=[None if self.on_host[l] else self.pools[l] for l in range(L)],
             host_pool=[self.pools[l] if self.on_host[l] else None for l in range(L)],
-            staging=(self.staging[0], self.staging[1]), staging_bytes=self.pool_bytes if any_host else 0,
+            staging=tuple(self.staging), staging_bytes=self.pool_bytes if any_host else 0,
             workspace=self.workspace, workspace_bytes=self.workspace_bytes,
             compute_stream=self.compute_stream.cuda_stream, h2d_stream=self.h2d_stream.cuda_stream)
         self.block_table = None
