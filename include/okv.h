@@ -87,7 +87,10 @@ typedef struct okv_config {
   int64_t workspace_bytes;     /* at least okv_workspace_bytes(cfg)                          */
   void   *compute_stream;      /* hipStream_t for kernels (NULL = the default stream)        */
   void   *h2d_stream;          /* hipStream_t for host-to-device copies; must differ from
-                                  compute_stream when any layer is on the host               */
+                                  compute_stream when any layer is on the host.  With two or
+                                  more staging buffers the library creates one more copy
+                                  stream of its own (default priority) for the odd-numbered
+                                  buffers; okv_synchronize waits for it as well.             */
 } okv_config;
 
 /* ---- sizes ------------------------------------------------------------------ */
