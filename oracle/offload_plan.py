@@ -76,3 +76,27 @@ def plan_from_bytes(n_layers, layer_bytes, mem_avail_bytes):
 def c_off_case3(mem_avail_bytes, mem_kv_bytes):
     """C_off of Case 3 as an exact fraction."""
     return 1 - Fraction(mem_avail_bytes, mem_kv_bytes)
+
+
+def block_split(n_blocks, c_off):
+    """(blocks that stay in HBM, blocks on the host) of n_blocks blocks for an
+    offload ratio c_off: the host gets the smallest integer >= c_off * n_blocks."""
+    n_host = n_offloaded(n_blocks, c_off)
+    return n_blocks - n_host, n_host
+
+
+def host_blocks_per_sequence(blocks_per_seq, n_host):
+    """How many of each sequence's blocks go to the host when n_host blocks in
+    total do: walking the sequences with a quota that grows by
+    n_host / total per block, a sequence gives the whole part gained while its
+    blocks are walked."""
+    total = sum(blocks_per_seq)
+    if not (0 <= n_host <= total):
+        raise ValueError("n_host outside [0, total]")
+    out, quota, whole_before = [], Fraction(0), 0
+    for nb in blocks_per_seq:
+        quota += Fraction(nb * n_host, total) if total else 0
+        whole_now = quota.numerator // quota.denominator
+        out.append(whole_now - whole_before)
+        whole_before = whole_now
+    return out

@@ -10,6 +10,18 @@ rounded up to a multiple of 16 (work items start on 16-key boundaries), and
 the sequence contributes the items [c*size, min((c+1)*size, n_b)) for
 c = 0, 1, ... while they are non-empty.  Items are listed sequence by
 sequence, in order, and each item is processed once per KV head.
+
+Block-granular offload (paper §IV-C: a share C_off of the cache lives in host
+memory) adds one more cut.  Block ids below `resident_blocks` are in HBM
+(class 0); the others are in the host pool, which is streamed in chunks of
+`chunk_blocks` consecutive blocks (host block i belongs to class 1 + i //
+chunk_blocks).  Each class is attended by a launch of its own, so an item may
+not cross from one class into another: a sequence is first cut into maximal
+runs of consecutive positions whose blocks are in one class, and every run is
+then cut into equal pieces exactly as a whole sequence is above (the run's
+length taking the place of n_b, positions counted from the run's start).
+Items are listed class by class; inside a class sequence by sequence, and
+inside a sequence by position.
 """
 
 
@@ -52,3 +64,46 @@ def check_tiling(items, ctx_lens):
         for t in range(lo, hi):
             seen[b][t] += 1
     return all(c == 1 for row in seen for c in row)
+
+
+def block_class(block_id, resident_blocks, chunk_blocks):
+    """0 if the block stays in HBM, else 1 + the chunk of the host pool it is in."""
+    if block_id < resident_blocks:
+        return 0
+    return 1 + (block_id - resident_blocks) // chunk_blocks
+
+
+def expected_items_by_class(ctx_lens, block_table, block_tokens, resident_blocks, chunk_blocks,
+                            split_tokens, n_classes):
+    """A list with one item list per class, written out with plain loops over
+    the positions of every sequence."""
+    per_class = [[] for _ in range(n_classes)]
+    for b, n in enumerate(ctx_lens):
+        n = int(n)
+        if n < 1:
+            continue
+        cls_of = [block_class(int(block_table[b][t // block_tokens]), resident_blocks, chunk_blocks)
+                  for t in range(n)]
+        run_start = 0
+        for t in range(1, n + 1):
+            if t < n and cls_of[t] == cls_of[run_start]:
+                continue
+            length = t - run_start                      # positions run_start .. t-1 form a run
+            size = piece_size(length, split_tokens)
+            start = run_start
+            while start < t:
+                stop = min(start + size, t)
+                per_class[cls_of[run_start]].append((b, start, stop))
+                start = stop
+            run_start = t
+    return per_class
+
+
+def check_classes(per_class, block_table, block_tokens, resident_blocks, chunk_blocks):
+    """True iff every position of every item lies in a block of the item's class."""
+    for cls, items in enumerate(per_class):
+        for (b, lo, hi) in items:
+            for t in range(lo, hi):
+                if block_class(int(block_table[b][t // block_tokens]), resident_blocks, chunk_blocks) != cls:
+                    return False
+    return True

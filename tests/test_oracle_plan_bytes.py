@@ -145,38 +145,41 @@ def test_worklist_checker_rejects_bad_tilings():
 
 # ---- pipeline replay ------------------------------------------------------------
 
-def _hand_trace(on_host, n_steps, depth, clamp=True):
+def _hand_trace(host_chunks, n_steps, depth, clamp=True, has_resident=None):
     """A correct trace written independently of the library: copies run
-    `depth` ahead, each released buffer is refilled at once."""
-    C, A, T, R = pipeline_sim.COPY, pipeline_sim.APPEND, pipeline_sim.ATTN, pipeline_sim.RELEASE
-    hl = [l for l, v in enumerate(on_host) if v]
-    k = len(hl)
+    `depth` ahead, each released buffer is refilled at once.  host_chunks[l] is
+    the number of streamed chunks of layer l."""
+    C, A, T, R, M = (pipeline_sim.COPY, pipeline_sim.APPEND, pipeline_sim.ATTN, pipeline_sim.RELEASE,
+                     pipeline_sim.MERGE)
+    L = len(host_chunks)
+    if has_resident is None:
+        has_resident = [1 if host_chunks[l] == 0 else 0 for l in range(L)]
+    units = [(l, c) for l in range(L) for c in range(host_chunks[l])]
+    k = len(units)
     tr = []
-    if k == 0:
-        for s in range(n_steps):
-            for l in range(len(on_host)):
-                tr += [(A, s, l, -1, -1, -1), (T, s, l, -1, -1, -1)]
-        return tr
-    if clamp:
+    if k and clamp:
         depth = min(depth, k)
-    for j in range(depth):
-        tr.append((C, j // k, hl[j % k], j % depth, j, -1))
+    if k:
+        for j in range(depth):
+            tr.append((C, j // k, units[j % k][0], units[j % k][1], j % depth, j, -1))
     j = 0
     for s in range(n_steps):
-        for l in range(len(on_host)):
-            if not on_host[l]:
-                tr += [(A, s, l, -1, -1, -1), (T, s, l, -1, -1, -1)]
-                continue
-            buf = j % depth
-            tr += [(A, s, l, buf, -1, j), (T, s, l, buf, -1, -1), (R, s, l, buf, j, -1)]
-            nj = j + depth
-            tr.append((C, nj // k, hl[nj % k], buf, nj, j))
-            j += 1
+        for l in range(L):
+            tr.append((A, s, l, -1, -1, -1, -1))
+            if has_resident[l]:
+                tr.append((T, s, l, -1, -1, -1, -1))
+            for c in range(host_chunks[l]):
+                buf = j % depth
+                tr += [(T, s, l, c, buf, j, j), (R, s, l, c, buf, j, -1)]
+                nj = j + depth
+                tr.append((C, nj // k, units[nj % k][0], units[nj % k][1], buf, nj, j))
+                j += 1
+            tr.append((M, s, l, -1, -1, -1, -1))
     return tr
 
 
 @pytest.mark.parametrize("on_host", [[0, 1, 0, 1], [1, 1, 1], [0, 0, 1], [1], [0, 0], [1, 0, 1, 1, 0, 1]])
-@pytest.mark.parametrize("depth", [1, 2])
+@pytest.mark.parametrize("depth", [1, 2, 3])
 def test_replay_accepts_a_correct_trace(on_host, depth):
     tr = _hand_trace(on_host, 4, depth)
     for seed in range(10):
@@ -184,46 +187,64 @@ def test_replay_accepts_a_correct_trace(on_host, depth):
             pipeline_sim.replay(tr, on_host, seed=seed, copy_scale=cs, compute_scale=ks)
 
 
+@pytest.mark.parametrize("chunks,resident", [([3, 3, 3], [1, 1, 1]), ([2, 2], [0, 0]), ([1, 4, 0, 2], [1, 0, 1, 1]),
+                                             ([5], [1])])
+@pytest.mark.parametrize("depth", [1, 2, 4])
+def test_replay_accepts_a_correct_chunked_trace(chunks, resident, depth):
+    tr = _hand_trace(chunks, 4, depth, has_resident=resident)
+    for seed in range(6):
+        for cs, ks in ((1.0, 1.0), (20.0, 0.05), (0.05, 20.0)):
+            pipeline_sim.replay(tr, chunks, resident, seed=seed, copy_scale=cs, compute_scale=ks)
+
+
+def _fails(trace, chunks, resident=None):
+    hit = 0
+    for seed in range(20):
+        for cs, ks in ((1.0, 1.0), (20.0, 0.05), (0.05, 20.0)):
+            try:
+                pipeline_sim.replay(trace, chunks, resident, seed=seed, copy_scale=cs, compute_scale=ks)
+            except pipeline_sim.Hazard:
+                hit += 1
+    return hit > 0
+
+
 def test_replay_catches_planted_mistakes():
-    C, A = pipeline_sim.COPY, pipeline_sim.APPEND
+    C, T = pipeline_sim.COPY, pipeline_sim.ATTN
     on_host = [0, 1, 0, 1, 1]
     good = _hand_trace(on_host, 4, 2)
-
-    def fails(trace):
-        hit = 0
-        for seed in range(20):
-            for cs, ks in ((1.0, 1.0), (20.0, 0.05), (0.05, 20.0)):
-                try:
-                    pipeline_sim.replay(trace, on_host, seed=seed, copy_scale=cs, compute_scale=ks)
-                except pipeline_sim.Hazard:
-                    hit += 1
-        return hit > 0
-
-    assert not fails(good)
+    assert not _fails(good, on_host)
     # 1. a copy that does not wait for its buffer to be released
-    bad = [(k, s, l, b, c, -1) if (k == C and c == 5) else (k, s, l, b, c, w) for (k, s, l, b, c, w) in good]
-    assert fails(bad)
-    # 2. an append that does not wait for its copy
-    first = next(i for i, op in enumerate(good) if op[0] == A and op[5] >= 0)
+    bad = [(k, s, l, ch, b, c, -1) if (k == C and c == 5) else (k, s, l, ch, b, c, w)
+           for (k, s, l, ch, b, c, w) in good]
+    assert _fails(bad, on_host)
+    # 2. an attention that does not wait for its copy
+    first = next(i for i, op in enumerate(good) if op[0] == T and op[6] >= 0)
     bad = list(good)
-    k, s, l, b, c, w = bad[first]
-    bad[first] = (k, s, l, b, c, -1)
-    assert fails(bad)
+    k, s, l, ch, b, c, w = bad[first]
+    bad[first] = (k, s, l, ch, b, c, -1)
+    assert _fails(bad, on_host)
+    # 2b. ... or waits for the copy before the one it reads
+    later = [i for i, op in enumerate(good) if op[0] == T and op[6] >= 2][0]
+    bad = list(good)
+    k, s, l, ch, b, c, w = bad[later]
+    bad[later] = (k, s, l, ch, b, c, w - 2)
+    assert _fails(bad, on_host)
     # 3. the copy goes to the other buffer
-    bad = [(k, s, l, 1 - b, c, w) if (k == C and c == 3) else (k, s, l, b, c, w) for (k, s, l, b, c, w) in good]
-    assert fails(bad)
+    bad = [(k, s, l, ch, 1 - b, c, w) if (k == C and c == 3) else (k, s, l, ch, b, c, w)
+           for (k, s, l, ch, b, c, w) in good]
+    assert _fails(bad, on_host)
     # 4. the copy fetches the wrong layer
-    bad = [(k, s, 1 if l == 3 else 3, b, c, w) if (k == C and c == 4) else (k, s, l, b, c, w)
-           for (k, s, l, b, c, w) in good]
-    assert fails(bad)
+    bad = [(k, s, 1 if l == 3 else 3, ch, b, c, w) if (k == C and c == 4) else (k, s, l, ch, b, c, w)
+           for (k, s, l, ch, b, c, w) in good]
+    assert _fails(bad, on_host)
     # 5. a copy issued before the release it waits on
-    idx = next(i for i, op in enumerate(good) if op[0] == C and op[5] >= 0)
+    idx = next(i for i, op in enumerate(good) if op[0] == C and op[6] >= 0)
     bad = list(good)
     op = bad.pop(idx)
-    bad.insert(idx - 3, op)
-    assert fails(bad)
+    bad.insert(idx - 2, op)
+    assert _fails(bad, on_host)
     # 6. with a single host layer, running two copies ahead reads the host
-    #    pool before the previous step's append has landed
+    #    pool before the previous step's rows have landed
     one = [0, 1, 0]
     for seed in range(5):
         pipeline_sim.replay(_hand_trace(one, 4, 2), one, seed=seed, copy_scale=0.05, compute_scale=20.0)
@@ -232,8 +253,41 @@ def test_replay_catches_planted_mistakes():
                             copy_scale=0.05, compute_scale=20.0)
 
 
+def test_replay_catches_planted_mistakes_in_chunked_traces():
+    C, T, M = pipeline_sim.COPY, pipeline_sim.ATTN, pipeline_sim.MERGE
+    chunks, resident = [3, 3], [1, 1]
+    good = _hand_trace(chunks, 3, 2, has_resident=resident)
+    assert not _fails(good, chunks, resident)
+    # the copy fetches the wrong chunk of the right layer
+    bad = [(k, s, l, (ch + 1) % 3, b, c, w) if (k == C and c == 4) else (k, s, l, ch, b, c, w)
+           for (k, s, l, ch, b, c, w) in good]
+    assert _fails(bad, chunks, resident)
+    # a chunk is never attended
+    victim = next(i for i, op in enumerate(good) if op[0] == T and op[3] == 1)
+    assert _fails(good[:victim] + good[victim + 1:], chunks, resident)
+    # the keys that stay in HBM are never attended
+    victim = next(i for i, op in enumerate(good) if op[0] == T and op[3] == -1)
+    assert _fails(good[:victim] + good[victim + 1:], chunks, resident)
+    # the merge runs before the layer's last chunk
+    m = next(i for i, op in enumerate(good) if op[0] == M)
+    bad = list(good)
+    op = bad.pop(m)
+    bad.insert(m - 4, op)
+    assert _fails(bad, chunks, resident)
+    # a chunk is attended twice in one step
+    t = next(i for i, op in enumerate(good) if op[0] == T and op[3] == 2)
+    assert _fails(good[:t + 1] + [good[t]] + good[t + 1:], chunks, resident)
+    # one layer with two chunks and three copies in flight: the third copy re-reads chunk 0
+    # of the host pool before the rows of the step before have landed
+    one = [2]
+    assert not _fails(_hand_trace(one, 4, 2, has_resident=[1]), one, [1])
+    with pytest.raises(pipeline_sim.Hazard):
+        pipeline_sim.replay(_hand_trace(one, 4, 3, clamp=False, has_resident=[1]), one, [1], seed=0,
+                            copy_scale=0.05, compute_scale=20.0)
+
+
 def test_overlap_keeps_the_copy_stream_busy():
-    # When copies dominate, a depth-2 pipeline leaves (almost) no gap on the copy stream.
+    # When copies dominate, a depth-2 pipeline leaves (almost) no gap on the copy engine.
     on_host = [0, 1] * 4
     tr = _hand_trace(on_host, 6, 2)
     r = pipeline_sim.replay(tr, on_host, seed=0, copy_scale=50.0, compute_scale=0.05)
@@ -241,3 +295,101 @@ def test_overlap_keeps_the_copy_stream_busy():
     tr1 = _hand_trace(on_host, 6, 1)
     r1 = pipeline_sim.replay(tr1, on_host, seed=0, copy_scale=50.0, compute_scale=0.05)
     assert r1["copy_busy"] / r1["copy_span"] <= r["copy_busy"] / r["copy_span"]
+
+
+# ---- block-granular split of the cache and its work list -------------------------
+
+def test_block_split_counts():
+    assert offload_plan.block_split(100, Fraction(0)) == (100, 0)
+    assert offload_plan.block_split(100, Fraction(1)) == (0, 100)
+    assert offload_plan.block_split(100, Fraction(1, 3)) == (66, 34)      # 33.3 -> 34 leave
+    assert offload_plan.block_split(7, Fraction(1, 7)) == (6, 1)
+    for n in (1, 5, 64, 1000):
+        for num in range(0, 11):
+            c = Fraction(num, 10)
+            res, host = offload_plan.block_split(n, c)
+            assert res + host == n and host >= c * n and (host == 0 or host - 1 < c * n)
+
+
+def test_host_blocks_per_sequence_shares():
+    rng = np.random.default_rng(5)
+    for _ in range(50):
+        nb = [int(x) for x in rng.integers(0, 40, size=int(rng.integers(1, 12)))]
+        total = sum(nb)
+        for n_host in {0, total, total // 2, total // 3}:
+            h = offload_plan.host_blocks_per_sequence(nb, n_host)
+            assert sum(h) == n_host
+            for hb, n in zip(h, nb):
+                assert 0 <= hb <= n
+                if total:                                   # each share within one block of its quota
+                    assert abs(hb - Fraction(n * n_host, total)) < 1 + 1e-9 or hb in (0, n)
+    assert offload_plan.host_blocks_per_sequence([4, 4, 4, 4], 8) == [2, 2, 2, 2]
+    assert offload_plan.host_blocks_per_sequence([10, 0, 10], 20) == [10, 0, 10]
+
+
+def _random_table(rng, ctx_lens, T, n_total):
+    ids = rng.permutation(n_total)
+    table, at = [], 0
+    width = max(-(-int(n) // T) for n in ctx_lens) + 1
+    for n in ctx_lens:
+        nb = -(-int(n) // T)
+        row = [int(x) for x in ids[at:at + nb]] + [-1] * (width - nb)
+        at += nb
+        table.append(row)
+    return table
+
+
+def test_items_by_class_hand_case():
+    # T = 16, blocks 0..1 in HBM, host chunks of 2 blocks: ids 2,3 -> class 1, ids 4,5 -> class 2
+    table = [[4, 5, 0, 2], [1, 3, -1, -1]]
+    lens = [55, 20]
+    got = worklist.expected_items_by_class(lens, table, 16, 2, 2, 1 << 20, 3)
+    assert got[0] == [(0, 32, 48), (1, 0, 16)]
+    assert got[1] == [(0, 48, 55), (1, 16, 20)]
+    assert got[2] == [(0, 0, 32)]
+    # a split size of 16 cuts the two-block run in two
+    got = worklist.expected_items_by_class(lens, table, 16, 2, 2, 16, 3)
+    assert got[2] == [(0, 0, 16), (0, 16, 32)]
+
+
+def test_items_by_class_tile_and_stay_in_class():
+    rng = np.random.default_rng(11)
+    for trial in range(30):
+        T = int(rng.choice([16, 32, 64]))
+        B = int(rng.integers(1, 6))
+        lens = [int(x) for x in rng.integers(0, 400, size=B)]
+        if max(lens) == 0:
+            lens[0] = 7
+        need = sum(-(-n // T) for n in lens)
+        n_total = need + int(rng.integers(0, 5))
+        R = int(rng.integers(0, n_total + 1))
+        CB = int(rng.integers(1, 6))
+        n_cls = 1 + -(-(n_total - R) // CB) if n_total > R else 1
+        table = _random_table(rng, lens, T, n_total)
+        S = int(rng.choice([16, 48, 128, 4096]))
+        per = worklist.expected_items_by_class(lens, table, T, R, CB, S, n_cls)
+        flat = [it for items in per for it in items]
+        assert worklist.check_tiling(flat, lens)
+        assert worklist.check_classes(per, table, T, R, CB)
+        for items in per:
+            assert items == sorted(items)                      # by sequence, then position
+            for (b, lo, hi) in items:
+                assert lo % 16 == 0 and hi - lo <= max(16, -(-S // 16) * 16)
+        # planted: an item moved to a neighbouring class is noticed
+        donor = next((c for c, items in enumerate(per) if items), None)
+        if donor is not None and n_cls > 1:
+            wrong = [list(items) for items in per]
+            it = wrong[donor].pop()
+            wrong[(donor + 1) % n_cls].append(it)
+            assert not worklist.check_classes(wrong, table, T, R, CB)
+
+
+def test_items_by_class_reduces_to_the_plain_list():
+    # everything in HBM (or everything in one chunk): one run per sequence = the unsplit-cache list
+    lens = [1, 16, 17, 300, 0, 1025]
+    T = 16
+    table = _random_table(np.random.default_rng(2), lens, T, 200)
+    for S in (16, 100, 256, 4096):
+        plain = worklist.expected_items(lens, S)
+        assert worklist.expected_items_by_class(lens, table, T, 200, 8, S, 1)[0] == plain
+        assert worklist.expected_items_by_class(lens, table, T, 0, 200, S, 2) == [[], plain]
