@@ -9,6 +9,7 @@
  * layer's KV in GPU memory.  This library is that hot loop and nothing else:
  *
  *   kv_offload_plan   which layers live on the host for a given C_off
+ *                     (okv_plan_block_split: which share of every layer's blocks)
  *   kv_append         store this step's K/V rows of one layer
  *   decode_attn       softmax(q K^T / sqrt(d)) V of one layer for a batch
  *
@@ -91,6 +92,20 @@ typedef struct okv_config {
                                   more staging buffers the library creates one more copy
                                   stream of its own (default priority) for the odd-numbered
                                   buffers; okv_synchronize waits for it as well.             */
+  /* Block-granular offload (paper §IV-C: C_off is a share of the cache, not a number of
+   * layers).  chunk_blocks == 0: off, whole layers are resident or on the host as
+   * described above.  chunk_blocks > 0 (paged pools only): in EVERY layer the blocks with
+   * ids below resident_blocks are in dev_pool[l] (resident_blocks blocks; NULL if that is
+   * 0) and the blocks with ids from resident_blocks on are in host_pool[l] at index
+   * id - resident_blocks (blocks_per_layer - resident_blocks blocks; NULL if none).  The
+   * host part is streamed in chunks of chunk_blocks consecutive blocks through the
+   * staging buffers, each of which then only has to hold one chunk
+   * (chunk_blocks * okv_block_bytes); every chunk and the resident part are attended by
+   * a launch of their own and merged afterwards.  Which blocks a sequence gets is up to
+   * the caller's block table; the fewer stretches of one class a sequence has, the
+   * fewer work items. */
+  int64_t resident_blocks;
+  int64_t chunk_blocks;
 } okv_config;
 
 /* ---- sizes ------------------------------------------------------------------ */
@@ -99,6 +114,10 @@ typedef struct okv_config {
  * shape fields of cfg are read.  This is the paper's Mem_KVcache,per_layer
  * (Table II) for the pool's capacity. */
 int64_t okv_layer_pool_bytes(const okv_config *cfg);
+
+/* Bytes of one block of a paged pool (K and V of block_tokens tokens for every KV
+ * head), or of one sequence's slice of a contiguous pool; < 0 on a bad cfg. */
+int64_t okv_block_bytes(const okv_config *cfg);
 
 /* Bytes of workspace the split-K partials need in the worst case under cfg (every
  * sequence at full capacity, the smallest split size the library would choose or
@@ -129,19 +148,33 @@ int kv_offload_plan(int32_t n_layers, int64_t coff_num, int64_t coff_den,
 int okv_plan_from_bytes(int32_t n_layers, int64_t layer_bytes, int64_t mem_avail_bytes,
                         uint8_t *on_host, int32_t *n_off, int32_t *n_staging);
 
-/* The order of operations the copy pipeline enqueues for a plan, without a GPU
- * (the runtime walks the same scheduler).  ops is a HOST array of max_ops
- * records of six int32: kind, step, layer, buf, copy_idx, wait_idx with
- *   kind 0 COPY     h2d stream: wait consumed[wait_idx] if >= 0, copy `layer`'s
- *                   host pool into staging `buf`, signal ready[copy_idx]
- *   kind 1 APPEND   compute stream: wait ready[wait_idx] if >= 0, store K/V
- *                   (buf = -1: resident layer)
- *   kind 2 ATTN     compute stream: attention reading staging `buf` (or the
- *                   resident pool when buf = -1)
+/* The same rule at block granularity (paper §IV-C): of n_blocks blocks the smallest
+ * whole number that is at least C_off * n_blocks goes to the host.
+ *   resident_blocks, host_blocks  HOST out; their sum is n_blocks. */
+int okv_plan_block_split(int64_t n_blocks, int64_t coff_num, int64_t coff_den,
+                         int64_t *resident_blocks, int64_t *host_blocks);
+
+/* The order of operations the copy pipeline enqueues, without a GPU (the runtime
+ * walks the same scheduler).
+ *   host_chunks   HOST int32 [n_layers]: streamed chunks of each layer (whole-layer
+ *                 offload: 1 for a host layer, 0 for a resident one)
+ *   has_resident  HOST uint8 [n_layers]: 1 if the layer also has keys in HBM; NULL
+ *                 means "exactly the layers without chunks"
+ * ops is a HOST array of max_ops records of seven int32:
+ * kind, step, layer, chunk, buf, copy_idx, wait_idx with
+ *   kind 0 COPY     copy stream: wait consumed[wait_idx] if >= 0, copy chunk `chunk` of
+ *                   `layer`'s host pool into staging `buf`, signal ready[copy_idx]
+ *   kind 1 APPEND   the step's K/V rows of `layer` are noted for the launches below
+ *   kind 2 ATTN     compute stream: wait ready[wait_idx] if >= 0; attention over the
+ *                   keys of chunk `chunk` in staging `buf` (chunk = buf = -1: the keys
+ *                   in HBM); stores the new rows of the sequences whose newest
+ *                   position it meets
  *   kind 3 RELEASE  compute stream: signal consumed[copy_idx]
+ *   kind 4 MERGE    compute stream: combine the layer's partial results
  * n_ops receives the number of records written.  OKV_ENOSPC if max_ops is too small. */
-int okv_schedule_trace(int32_t n_layers, const uint8_t *on_host, int32_t n_staging,
-                       int32_t n_steps, int32_t *ops, int64_t max_ops, int64_t *n_ops);
+int okv_schedule_trace(int32_t n_layers, const int32_t *host_chunks, const uint8_t *has_resident,
+                       int32_t n_staging, int32_t n_steps, int32_t *ops, int64_t max_ops,
+                       int64_t *n_ops);
 
 /* ---- context -------------------------------------------------------------------- */
 
@@ -161,7 +194,10 @@ const char *okv_last_error(const okv_ctx *ctx);
  *   B            1 <= B <= max_batch
  *   block_table  HOST int32 [B][max_blocks_per_seq]; block ids in
  *                [0, blocks_per_layer), -1 = not allocated; no block may appear
- *                twice.  The same table serves every layer.  Ignored (may be
+ *                twice.  The same table serves every layer.  With block-granular
+ *                offload the id also says where the block lives (see okv_config),
+ *                and OKV_ENOSPC is returned if the batch is cut into more work
+ *                items than the workspace holds.  Ignored (may be
  *                NULL) for contiguous pools, where sequence b owns slice b.
  *   ctx_lens     HOST int32 [B]: tokens already stored per sequence (>= 0), the
  *                same in every layer.
@@ -187,7 +223,8 @@ int okv_step_end(okv_ctx *ctx);
  * The store is carried out by the same kernel launch as the layer's decode_attn:
  * kv_append makes the compute stream wait for the layer's copy (host layers) and
  * hands the rows to that launch, so k_new / v_new must stay valid until the work of
- * decode_attn(layer) has finished, and the pool holds the rows from then on.
+ * decode_attn(layer) has finished, and the pool holds the rows from then on.  A row whose
+ * block is on the host (block-granular offload) is written to the host pool directly.
  * Within a step layers are visited in order 0 .. L-1, kv_append(l) before
  * decode_attn(l); anything else is OKV_ESTATE. */
 int kv_append(okv_ctx *ctx, int32_t layer, const void *k_new, const void *v_new);
@@ -199,7 +236,10 @@ int kv_append(okv_ctx *ctx, int32_t layer, const void *k_new, const void *v_new)
  *   q    DEVICE fp16 [B][H][d]
  *   out  DEVICE [B][H][d], fp16 or fp32 as cfg.out_dtype says
  * For a host layer the call first makes the compute stream wait for the layer's
- * copy, and afterwards hands the staging buffer back and enqueues the next copy. */
+ * copy, and afterwards hands the staging buffer back and enqueues the next copy.
+ * With block-granular offload it launches once over the keys in HBM and once per
+ * chunk of the host pool (waiting for that chunk's copy, releasing its buffer and
+ * enqueueing the next copy each time), then merges. */
 int decode_attn(okv_ctx *ctx, int32_t layer, const void *q, void *out);
 
 /* Blocks until everything enqueued on both streams has finished. */
@@ -223,9 +263,19 @@ int okv_get_ctx_lens(okv_ctx *ctx, int32_t *out);
  * multiples of 16 keys.  from_device = 0 walks the host copy of the tables;
  * from_device = 1 runs a small kernel that decodes every item exactly as the
  * attention kernel does and copies the result back (synchronous).
+ * With block-granular offload the list is class by class (class 0 = the blocks in
+ * HBM, class 1 + c = chunk c of the host pool); inside a class sequence by sequence;
+ * a sequence is cut where its blocks change class and each stretch into equal pieces.
  *   items  HOST int32 [max_items][3];  n_items HOST out. */
 int okv_worklist(okv_ctx *ctx, int32_t from_device, int32_t *items, int64_t max_items,
                  int64_t *n_items);
+
+/* Where each class starts in that list: class_first[c] .. class_first[c + 1] are the
+ * items of class c; *n_classes receives the number of classes (1 without
+ * block-granular offload).  from_device = 1 reads the prefix the kernels use.
+ *   class_first  HOST int32 [max_classes], needs n_classes + 1 entries. */
+int okv_worklist_classes(okv_ctx *ctx, int32_t from_device, int32_t *class_first,
+                         int32_t max_classes, int32_t *n_classes);
 
 /* Per-kernel timing.  While enabled every decode_attn brackets its split-K kernel
  * with HIP events on the compute stream.  okv_profile_read waits for the stream,
@@ -241,8 +291,8 @@ int okv_profile_read(okv_ctx *ctx, double *attn_ms, int64_t *attn_launches);
 int okv_measure_h2d(void *dst, const void *src, int64_t bytes, int32_t reps, void *stream,
                     double *gbps_median);
 
-/* The copies of one decode step alone: every host layer's pool is copied into the staging
- * buffers (alternating), back to back on the h2d stream, nothing else running; *ms receives
+/* The copies of one decode step alone: every host layer's pool (every streamed chunk of
+ * every layer) is copied into the staging buffers (alternating), back to back on the h2d stream, nothing else running; *ms receives
  * the elapsed time.  The yardstick for how well a real step hides its compute behind the
  * copies.  Needs a batch (okv_set_batch), must not be called inside a step.  Synchronous. */
 int okv_time_copies(okv_ctx *ctx, double *ms);

@@ -16,10 +16,11 @@ _CODE_NAMES = {0: "OKV_OK", -1: "OKV_EINVAL", -2: "OKV_ENOSPC", -3: "OKV_ESTATE"
 
 # every symbol include/okv.h declares
 EXPORTS = [
-    "okv_layer_pool_bytes", "okv_workspace_bytes", "kv_offload_plan", "okv_plan_from_bytes",
-    "okv_schedule_trace", "okv_create", "okv_destroy", "okv_last_error", "okv_set_batch",
+    "okv_layer_pool_bytes", "okv_block_bytes", "okv_workspace_bytes", "kv_offload_plan", "okv_plan_from_bytes",
+    "okv_plan_block_split", "okv_schedule_trace", "okv_create", "okv_destroy", "okv_last_error", "okv_set_batch",
     "okv_step_begin", "okv_step_end", "kv_append", "decode_attn", "okv_synchronize",
     "okv_set_split_tokens", "okv_get_split_tokens", "okv_get_ctx_lens", "okv_worklist",
+    "okv_worklist_classes",
     "okv_profile_enable", "okv_profile_read", "okv_measure_h2d", "okv_time_copies", "okv_probe_copy",
     "okv_probe_read",
 ]
@@ -41,6 +42,7 @@ class OkvConfig(ctypes.Structure):
         ("staging", ctypes.c_void_p * 4), ("staging_bytes", ctypes.c_int64),
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_int64),
         ("compute_stream", ctypes.c_void_p), ("h2d_stream", ctypes.c_void_p),
+        ("resident_blocks", ctypes.c_int64), ("chunk_blocks", ctypes.c_int64),
     ]
 
 
@@ -60,10 +62,13 @@ def lib():
         cfgp = ctypes.POINTER(OkvConfig)
         sig = {
             "okv_layer_pool_bytes": (I64, [cfgp]),
+            "okv_block_bytes": (I64, [cfgp]),
             "okv_workspace_bytes": (I64, [cfgp]),
+            "okv_plan_block_split": (ctypes.c_int, [I64, I64, I64, ctypes.POINTER(I64), ctypes.POINTER(I64)]),
+            "okv_worklist_classes": (ctypes.c_int, [P, I32, P, I32, ctypes.POINTER(I32)]),
             "kv_offload_plan": (ctypes.c_int, [I32, I64, I64, P, ctypes.POINTER(I32)]),
             "okv_plan_from_bytes": (ctypes.c_int, [I32, I64, I64, P, ctypes.POINTER(I32), ctypes.POINTER(I32)]),
-            "okv_schedule_trace": (ctypes.c_int, [I32, P, I32, I32, P, I64, ctypes.POINTER(I64)]),
+            "okv_schedule_trace": (ctypes.c_int, [I32, P, P, I32, I32, P, I64, ctypes.POINTER(I64)]),
             "okv_create": (ctypes.c_int, [cfgp, ctypes.POINTER(P)]),
             "okv_destroy": (ctypes.c_int, [P]),
             "okv_last_error": (ctypes.c_char_p, [P]),
@@ -130,14 +135,24 @@ def okv_plan_from_bytes(n_layers, layer_bytes, mem_avail_bytes):
     return on_host[:n_layers], n_off.value, n_st.value
 
 
-def okv_schedule_trace(on_host, n_staging, n_steps):
-    """-> list of (kind, step, layer, buf, copy_idx, wait_idx)"""
-    on_host = np.ascontiguousarray(on_host, dtype=np.uint8)
-    L = len(on_host)
-    max_ops = 4 * L * max(n_steps, 1) + 8
-    ops = np.zeros((max_ops, 6), dtype=np.int32)
+def okv_plan_block_split(n_blocks, coff_num, coff_den):
+    """-> (resident_blocks, host_blocks)"""
+    res, host = ctypes.c_int64(0), ctypes.c_int64(0)
+    _check(lib().okv_plan_block_split(n_blocks, coff_num, coff_den, ctypes.byref(res), ctypes.byref(host)))
+    return res.value, host.value
+
+
+def okv_schedule_trace(host_chunks, n_staging, n_steps, has_resident=None):
+    """-> list of (kind, step, layer, chunk, buf, copy_idx, wait_idx)"""
+    host_chunks = np.ascontiguousarray(host_chunks, dtype=np.int32)
+    if has_resident is not None:
+        has_resident = np.ascontiguousarray(has_resident, dtype=np.uint8)
+    L = len(host_chunks)
+    max_ops = (3 + 3 * int(host_chunks.sum())) * max(n_steps, 1) + 3 * L * max(n_steps, 1) + 8
+    ops = np.zeros((max_ops, 7), dtype=np.int32)
     n = ctypes.c_int64(0)
-    _check(lib().okv_schedule_trace(L, _ptr(on_host), n_staging, n_steps, _ptr(ops), max_ops, ctypes.byref(n)))
+    _check(lib().okv_schedule_trace(L, _ptr(host_chunks), _ptr(has_resident), n_staging, n_steps, _ptr(ops),
+                                    max_ops, ctypes.byref(n)))
     return [tuple(int(v) for v in row) for row in ops[:n.value]]
 
 
@@ -150,6 +165,13 @@ def make_config(**kw):
 
 def okv_layer_pool_bytes(cfg):
     r = lib().okv_layer_pool_bytes(ctypes.byref(cfg))
+    if r < 0:
+        _check(int(r))
+    return int(r)
+
+
+def okv_block_bytes(cfg):
+    r = lib().okv_block_bytes(ctypes.byref(cfg))
     if r < 0:
         _check(int(r))
     return int(r)
@@ -185,7 +207,7 @@ class Context:
     def __init__(self, *, n_layers, n_q_heads, n_kv_heads, head_dim, block_tokens, max_batch,
                  max_blocks_per_seq=0, max_ctx=0, blocks_per_layer=0, out_dtype=0, split_tokens=0,
                  dev_pool, host_pool=None, staging=(None, None), staging_bytes=0,
-                 workspace, workspace_bytes, compute_stream=0, h2d_stream=0):
+                 workspace, workspace_bytes, compute_stream=0, h2d_stream=0, resident_blocks=0, chunk_blocks=0):
         L = n_layers
         self._dev = (ctypes.c_void_p * L)(*[_ptr(p) for p in dev_pool])
         self._host = (ctypes.c_void_p * L)(*[_ptr(p) for p in (host_pool or [None] * L)])
@@ -200,6 +222,7 @@ class Context:
         cfg.staging_bytes = staging_bytes
         cfg.workspace, cfg.workspace_bytes = _ptr(workspace), workspace_bytes
         cfg.compute_stream, cfg.h2d_stream = _ptr(compute_stream), _ptr(h2d_stream)
+        cfg.resident_blocks, cfg.chunk_blocks = resident_blocks, chunk_blocks
         self.cfg = cfg
         self.B = 0
         self._h = ctypes.c_void_p(0)
@@ -257,6 +280,12 @@ class Context:
         n = ctypes.c_int64(0)
         self._c(lib().okv_worklist(self._h, 1 if from_device else 0, _ptr(items), max_items, ctypes.byref(n)))
         return items[:n.value].copy()
+
+    def okv_worklist_classes(self, from_device=False, max_classes=8192):
+        first = np.zeros(max_classes, dtype=np.int32)
+        n = ctypes.c_int32(0)
+        self._c(lib().okv_worklist_classes(self._h, 1 if from_device else 0, _ptr(first), max_classes, ctypes.byref(n)))
+        return first[:n.value + 1].copy()
 
     def okv_time_copies(self):
         ms = ctypes.c_double(0)

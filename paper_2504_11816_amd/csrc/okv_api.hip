@@ -30,6 +30,8 @@ constexpr int kEventRing = 8;            // > copies in flight (at most OKV_MAX_
 #define OKV_WAVES_PER_CU_GQA 4
 #endif
 constexpr int32_t kMinAutoSplit = 128;   // smallest split size the library picks by itself
+constexpr int32_t kClassSplit = 512;     // split size with block classes unless the caller sets one
+constexpr int64_t kMaxClasses = 4096;
 
 thread_local std::string g_error;        // failures that have no context to live in
 
@@ -45,6 +47,20 @@ struct okv_ctx {
   int32_t n_staging = 0;
   hipStream_t compute = nullptr, h2d = nullptr;
   hipStream_t h2d_odd = nullptr;         // library-owned second copy stream (odd staging buffers)
+
+  // block classes (a share of every layer's blocks on the host); n_cls == 1 otherwise
+  bool by_class = false;
+  int64_t resident_blocks = 0, chunk_blocks = 0;
+  int32_t n_cls = 1;
+  std::vector<okv::Run> h_runs;          // sorted by (class, sequence, position)
+  std::vector<int32_t> h_pair_first;     // [n_cls * B + 1]
+  std::vector<int32_t> cls_first, cls_count;   // items of each class in the current work list
+  std::vector<int32_t> active_chunks;    // chunks of the host pool that hold blocks of the batch
+  std::vector<int64_t> unit_offset, unit_bytes;   // per streamed chunk: where it starts in the host pool, its size
+  bool has_resident = false;
+  int4 *d_runs = nullptr;
+  int32_t *d_pair_first = nullptr, *d_seq_total = nullptr;
+  int64_t runs_cap = 0;
 
   int32_t *d_block_table = nullptr, *d_ctx_lens = nullptr, *d_chunk_prefix = nullptr;
   int4 *d_item_desc = nullptr;
@@ -114,6 +130,13 @@ const char *shape_problem(const okv_config *c) {
     if (c->blocks_per_layer < 1 || c->blocks_per_layer > 0x7fffffff) return "blocks_per_layer out of range";
     if ((int64_t)c->max_blocks_per_seq * c->block_tokens > 0x3fffffff) return "capacity per sequence too large";
   }
+  if (c->chunk_blocks < 0) return "chunk_blocks < 0";
+  if (c->chunk_blocks > 0) {
+    if (c->block_tokens == 0) return "block classes (chunk_blocks > 0) need paged pools";
+    if (c->resident_blocks < 0 || c->resident_blocks > c->blocks_per_layer) return "resident_blocks outside [0, blocks_per_layer]";
+    if ((c->blocks_per_layer - c->resident_blocks + c->chunk_blocks - 1) / c->chunk_blocks + 1 > kMaxClasses)
+      return "too many chunks: raise chunk_blocks";
+  }
   return nullptr;
 }
 
@@ -125,6 +148,17 @@ int64_t pool_bytes_of(const okv_config *c) {
   int64_t row = (int64_t)c->head_dim * 2;
   if (c->block_tokens) return c->blocks_per_layer * 2 * c->n_kv_heads * c->block_tokens * row;
   return (int64_t)c->max_batch * 2 * c->n_kv_heads * c->max_ctx * row;
+}
+
+int64_t block_bytes_of(const okv_config *c) {
+  int64_t tcap = c->block_tokens ? c->block_tokens : c->max_ctx;
+  return (int64_t)2 * c->n_kv_heads * tcap * c->head_dim * 2;
+}
+
+// Classes a context can meet: the blocks in HBM plus every chunk of the host pool.
+int32_t max_classes_of(const okv_config *c) {
+  if (c->chunk_blocks <= 0) return 1;
+  return 1 + (int32_t)((c->blocks_per_layer - c->resident_blocks + c->chunk_blocks - 1) / c->chunk_blocks);
 }
 
 int64_t bytes_per_item(const okv_config *c) { return (int64_t)c->n_q_heads * (c->head_dim + 2) * 4; }
@@ -207,6 +241,28 @@ int32_t choose_split(const okv_ctx *ctx, const std::vector<int32_t> &lens) {
 
 hipStream_t copy_stream(okv_ctx *ctx, int buf) { return (buf & 1) && ctx->h2d_odd ? ctx->h2d_odd : ctx->h2d; }
 
+okv::AttnLaunch base_launch(okv_ctx *ctx) {
+  okv::AttnLaunch a;
+  a.shape = ctx->shape;
+  a.batch = okv::BatchState{ctx->d_block_table, ctx->d_ctx_lens, ctx->d_chunk_prefix, ctx->d_item_desc,
+                            ctx->B, ctx->split, ctx->n_items, ctx->n_cls};
+  a.q = nullptr;
+  a.pool = nullptr;
+  a.k_new = a.v_new = nullptr;
+  a.pool_mirror = nullptr;
+  a.out = nullptr;
+  a.part_o = ctx->part_o;
+  a.part_ml = ctx->part_ml;
+  a.out_fp32 = ctx->cfg.out_dtype;
+  a.need_merge = ctx->need_merge;
+  a.queue = nullptr;
+  a.max_waves = ctx->max_waves;
+  a.item_first = 0;
+  a.item_count = ctx->n_items;
+  a.id_base = a.mirror_base = 0;
+  return a;
+}
+
 int exec_op(okv_ctx *ctx, const Op &op, const void *a0, const void *a1, void *out) {
   switch (op.kind) {
     case okv::OP_COPY: {
@@ -215,37 +271,40 @@ int exec_op(okv_ctx *ctx, const Op &op, const void *a0, const void *a1, void *ou
       // about 2 % of the copy time) then overlaps with the next copy instead of delaying it.
       hipStream_t cs = copy_stream(ctx, op.buf);
       if (op.wait_idx >= 0) OKV_HIP(ctx, hipStreamWaitEvent(cs, ctx->consumed_ev[op.wait_idx % kEventRing], 0));
-      OKV_HIP(ctx, hipMemcpyAsync(ctx->cfg.staging[op.buf], ctx->host_pool[op.layer], (size_t)ctx->copy_bytes,
+      const char *src = static_cast<const char *>(ctx->host_pool[op.layer]) + ctx->unit_offset[op.chunk];
+      OKV_HIP(ctx, hipMemcpyAsync(ctx->cfg.staging[op.buf], src, (size_t)ctx->unit_bytes[op.chunk],
                                   hipMemcpyHostToDevice, cs));
       OKV_HIP(ctx, hipEventRecord(ctx->ready_ev[op.copy_idx % kEventRing], cs));
       return OKV_OK;
     }
-    case okv::OP_APPEND: {
-      // The rows are stored by the attention launch of the same layer (one kernel instead
-      // of two); here the compute stream only starts to wait for the layer's copy.
-      if (op.wait_idx >= 0) OKV_HIP(ctx, hipStreamWaitEvent(ctx->compute, ctx->ready_ev[op.wait_idx % kEventRing], 0));
+    case okv::OP_APPEND:
+      // The rows are stored by the attention launch that meets each sequence's newest position
+      // (one kernel instead of two); here they are only noted.
       ctx->pending_k = a0;
       ctx->pending_v = a1;
       return OKV_OK;
-    }
     case okv::OP_ATTN: {
-      okv::AttnLaunch a;
-      a.shape = ctx->shape;
-      a.batch = okv::BatchState{ctx->d_block_table, ctx->d_ctx_lens, ctx->d_chunk_prefix, ctx->d_item_desc,
-                                ctx->B, ctx->split, ctx->n_items};
-      a.queue = ctx->d_queues + op.layer;
-      a.max_waves = ctx->max_waves;
+      if (op.wait_idx >= 0) OKV_HIP(ctx, hipStreamWaitEvent(ctx->compute, ctx->ready_ev[op.wait_idx % kEventRing], 0));
+      okv::AttnLaunch a = base_launch(ctx);
+      int32_t cls = 0;
+      if (ctx->by_class) {
+        if (op.chunk >= 0) {
+          const int32_t chunk = ctx->active_chunks[op.chunk];
+          cls = 1 + chunk;
+          a.id_base = (int32_t)(ctx->resident_blocks + (int64_t)chunk * ctx->chunk_blocks);
+          a.mirror_base = (int32_t)ctx->resident_blocks;
+        }
+        a.item_first = ctx->cls_first[cls];
+        a.item_count = ctx->cls_count[cls];
+      }
+      if (a.item_count == 0) return OKV_OK;              // no key of the batch lies in this class at this step
+      a.queue = ctx->d_queues + (size_t)op.layer * ctx->n_cls + cls;
       a.q = a0;
       a.pool = op.buf >= 0 ? ctx->cfg.staging[op.buf] : ctx->dev_pool[op.layer];
       a.k_new = ctx->pending_k;
       a.v_new = ctx->pending_v;
       a.pool_mirror = op.buf >= 0 ? ctx->host_pool[op.layer] : nullptr;
-      ctx->pending_k = ctx->pending_v = nullptr;
       a.out = out;
-      a.part_o = ctx->part_o;
-      a.part_ml = ctx->part_ml;
-      a.out_fp32 = ctx->cfg.out_dtype;
-      a.need_merge = ctx->need_merge;
       hipEvent_t e0 = nullptr, e1 = nullptr;
       if (ctx->profile) {
         if (ctx->prof_used == ctx->prof_events.size()) {
@@ -264,6 +323,14 @@ int exec_op(okv_ctx *ctx, const Op &op, const void *a0, const void *a1, void *ou
     case okv::OP_RELEASE:
       OKV_HIP(ctx, hipEventRecord(ctx->consumed_ev[op.copy_idx % kEventRing], ctx->compute));
       return OKV_OK;
+    case okv::OP_MERGE: {
+      ctx->pending_k = ctx->pending_v = nullptr;
+      if (!ctx->need_merge) return OKV_OK;
+      okv::AttnLaunch a = base_launch(ctx);
+      a.out = out;
+      OKV_HIP(ctx, okv::launch_merge(a, ctx->compute));
+      return OKV_OK;
+    }
   }
   return fail(ctx, OKV_ESTATE, "unknown pipeline op %d", op.kind);
 }
@@ -279,6 +346,32 @@ int exec_ops(okv_ctx *ctx, const std::vector<Op> &ops, const void *a0, const voi
 // Recomputes split size, item count and merge flag from the host lengths and
 // rebuilds the device work list (adding `inc` to every device length first).
 int rebuild_worklist(okv_ctx *ctx, int32_t inc) {
+  if (ctx->by_class) {
+    ctx->split = ctx->split_override ? ctx->split_override : ctx->cfg.split_tokens ? ctx->cfg.split_tokens : kClassSplit;
+    std::vector<int32_t> per_seq(ctx->B, 0);
+    ctx->cls_count.assign(ctx->n_cls, 0);
+    int64_t n = 0;
+    for (const okv::Run &r : ctx->h_runs) {
+      int32_t sz;
+      const int32_t cnt = okv::run_items(r.lo, r.hi_cap, ctx->h_ctx_lens[r.b], ctx->split, &sz);
+      ctx->cls_count[r.cls] += cnt;
+      per_seq[r.b] += cnt;
+      n += cnt;
+    }
+    if (n > ctx->max_items)
+      return fail(ctx, OKV_ENOSPC, "split size %d needs %lld work items, workspace holds %lld", ctx->split,
+                  (long long)n, (long long)ctx->max_items);
+    ctx->n_items = (int32_t)n;
+    ctx->cls_first.assign(ctx->n_cls + 1, 0);
+    for (int32_t c = 0; c < ctx->n_cls; ++c) ctx->cls_first[c + 1] = ctx->cls_first[c] + ctx->cls_count[c];
+    ctx->need_merge = false;
+    for (int32_t b = 0; b < ctx->B; ++b) ctx->need_merge |= per_seq[b] > 1;
+    OKV_HIP(ctx, okv::launch_step_advance_classes(ctx->d_ctx_lens, ctx->d_runs, ctx->d_pair_first, ctx->d_chunk_prefix,
+                                                  ctx->d_item_desc, ctx->d_seq_total, ctx->d_queues,
+                                                  ctx->cfg.n_layers * ctx->n_cls, ctx->B, ctx->n_cls, ctx->split, inc,
+                                                  ctx->compute));
+    return OKV_OK;
+  }
   ctx->split = choose_split(ctx, ctx->h_ctx_lens);
   int64_t n = count_items(ctx->h_ctx_lens.data(), ctx->B, ctx->split);
   if (n > ctx->max_items)
@@ -296,6 +389,24 @@ int rebuild_worklist(okv_ctx *ctx, int32_t inc) {
   return OKV_OK;
 }
 
+// Restarts the copy pipeline for the batch just described.
+void reset_schedule(okv_ctx *ctx) {
+  const int32_t L = ctx->cfg.n_layers;
+  std::vector<int32_t> chunks(L, 0);
+  std::vector<uint8_t> resident(L, 0);
+  for (int32_t l = 0; l < L; ++l) {
+    if (ctx->by_class) {
+      chunks[l] = (int32_t)ctx->active_chunks.size();
+      resident[l] = ctx->has_resident;
+    } else {
+      chunks[l] = ctx->host_pool[l] != nullptr;
+      resident[l] = ctx->host_pool[l] == nullptr;
+    }
+  }
+  ctx->sched.reset(L, chunks.data(), resident.data(), ctx->n_staging);
+  ctx->step = 0;                                       // copy indices count from the restart
+}
+
 }  // namespace
 
 extern "C" {
@@ -310,7 +421,11 @@ int64_t okv_workspace_bytes(const okv_config *cfg) {
   int64_t S = cfg->split_tokens ? cfg->split_tokens : kMinAutoSplit;
   if (S < 16) S = 16;                                  // items never hold fewer than 16 keys
   int64_t cap = cap_tokens_of(cfg);
-  int64_t items = (int64_t)cfg->max_batch * ((cap + S - 1) / S);
+  if (cfg->chunk_blocks > 0 && !cfg->split_tokens) S = kClassSplit;
+  // with block classes a sequence has at least one item per class it has blocks in; the
+  // figure assumes one run per class (an allocator that keeps a sequence's blocks of a
+  // class together); a batch that needs more is refused by okv_set_batch
+  int64_t items = (int64_t)cfg->max_batch * ((cap + S - 1) / S + (max_classes_of(cfg) - 1));
   return items * bytes_per_item(cfg);
 }
 
@@ -345,13 +460,21 @@ int okv_plan_from_bytes(int32_t n_layers, int64_t layer_bytes, int64_t mem_avail
   return OKV_OK;
 }
 
-int okv_schedule_trace(int32_t n_layers, const uint8_t *on_host, int32_t n_staging, int32_t n_steps,
-                       int32_t *ops, int64_t max_ops, int64_t *n_ops) {
-  if (n_layers < 1 || !on_host || n_steps < 0 || !ops || !n_ops || n_staging < 0 || n_staging > OKV_MAX_STAGING)
+int okv_schedule_trace(int32_t n_layers, const int32_t *host_chunks, const uint8_t *has_resident, int32_t n_staging,
+                       int32_t n_steps, int32_t *ops, int64_t max_ops, int64_t *n_ops) {
+  if (n_layers < 1 || !host_chunks || n_steps < 0 || !ops || !n_ops || n_staging < 0 || n_staging > OKV_MAX_STAGING)
     return fail(nullptr, OKV_EINVAL, "okv_schedule_trace: bad argument");
+  std::vector<uint8_t> res(n_layers);
+  bool any = false;
+  for (int32_t l = 0; l < n_layers; ++l) {
+    if (host_chunks[l] < 0) return fail(nullptr, OKV_EINVAL, "okv_schedule_trace: host_chunks[%d] < 0", l);
+    res[l] = has_resident ? has_resident[l] != 0 : host_chunks[l] == 0;
+    if (!res[l] && host_chunks[l] == 0) return fail(nullptr, OKV_EINVAL, "okv_schedule_trace: layer %d holds nothing", l);
+    any |= host_chunks[l] > 0;
+  }
+  if (any && n_staging < 1) return fail(nullptr, OKV_EINVAL, "streamed chunks need a staging buffer");
   okv::Scheduler s;
-  s.reset(n_layers, on_host, n_staging);
-  if (s.n_host() > 0 && n_staging < 1) return fail(nullptr, OKV_EINVAL, "host layers need a staging buffer");
+  s.reset(n_layers, host_chunks, res.data(), n_staging);
   std::vector<Op> v;
   if (n_steps > 0) s.prime(v);
   for (int32_t step = 0; step < n_steps; ++step)
@@ -362,10 +485,28 @@ int okv_schedule_trace(int32_t n_layers, const uint8_t *on_host, int32_t n_stagi
   *n_ops = (int64_t)v.size();
   if ((int64_t)v.size() > max_ops) return fail(nullptr, OKV_ENOSPC, "trace needs %zu records", v.size());
   for (size_t i = 0; i < v.size(); ++i) {
-    int32_t *o = ops + i * 6;
-    o[0] = v[i].kind, o[1] = v[i].step, o[2] = v[i].layer, o[3] = v[i].buf, o[4] = v[i].copy_idx, o[5] = v[i].wait_idx;
+    int32_t *o = ops + i * 7;
+    o[0] = v[i].kind, o[1] = v[i].step, o[2] = v[i].layer, o[3] = v[i].chunk, o[4] = v[i].buf;
+    o[5] = (int32_t)v[i].copy_idx, o[6] = (int32_t)v[i].wait_idx;
   }
   return OKV_OK;
+}
+
+int okv_plan_block_split(int64_t n_blocks, int64_t coff_num, int64_t coff_den, int64_t *resident_blocks,
+                         int64_t *host_blocks) {
+  if (n_blocks < 0 || !resident_blocks || !host_blocks) return fail(nullptr, OKV_EINVAL, "okv_plan_block_split: bad argument");
+  if (coff_den <= 0 || coff_num < 0 || coff_num > coff_den)
+    return fail(nullptr, OKV_EINVAL, "okv_plan_block_split: C_off must lie in [0, 1]");
+  const __int128 x = (__int128)coff_num * n_blocks;
+  const int64_t host = (int64_t)((x + coff_den - 1) / coff_den);
+  *host_blocks = host;
+  *resident_blocks = n_blocks - host;
+  return OKV_OK;
+}
+
+int64_t okv_block_bytes(const okv_config *cfg) {
+  if (const char *why = shape_problem(cfg)) return fail(nullptr, OKV_EINVAL, "%s", why);
+  return block_bytes_of(cfg);
 }
 
 int okv_create(const okv_config *cfg, okv_ctx **out) {
@@ -374,11 +515,19 @@ int okv_create(const okv_config *cfg, okv_ctx **out) {
   if (const char *why = shape_problem(cfg)) return fail(nullptr, OKV_EINVAL, "okv_create: %s", why);
   const int32_t L = cfg->n_layers;
   if (!cfg->dev_pool) return fail(nullptr, OKV_EINVAL, "okv_create: dev_pool is NULL");
+  const bool by_class = cfg->chunk_blocks > 0;
+  const int64_t host_blocks = by_class ? cfg->blocks_per_layer - cfg->resident_blocks : 0;
   bool any_host = false;
   for (int32_t l = 0; l < L; ++l) {
     void *d = cfg->dev_pool[l], *h = cfg->host_pool ? cfg->host_pool[l] : nullptr;
-    if ((d != nullptr) == (h != nullptr))
+    if (by_class) {
+      if ((cfg->resident_blocks > 0) != (d != nullptr))
+        return fail(nullptr, OKV_EINVAL, "okv_create: layer %d: dev_pool must be set exactly when resident_blocks > 0", l);
+      if ((host_blocks > 0) != (h != nullptr))
+        return fail(nullptr, OKV_EINVAL, "okv_create: layer %d: host_pool must be set exactly when blocks live on the host", l);
+    } else if ((d != nullptr) == (h != nullptr)) {
       return fail(nullptr, OKV_EINVAL, "okv_create: layer %d needs exactly one of dev_pool / host_pool", l);
+    }
     if (!aligned16(d) || !aligned16(h)) return fail(nullptr, OKV_EINVAL, "okv_create: layer %d pool not 16-byte aligned", l);
     any_host |= h != nullptr;
   }
@@ -386,9 +535,10 @@ int okv_create(const okv_config *cfg, okv_ctx **out) {
   int32_t n_staging = 0;
   if (any_host) {
     if (!cfg->staging[0]) return fail(nullptr, OKV_EINVAL, "okv_create: host layers need staging[0]");
-    if (cfg->staging_bytes < pool_bytes)
-      return fail(nullptr, OKV_ENOSPC, "okv_create: staging_bytes %lld < one layer's pool %lld (a layer's KV must fit on the GPU)",
-                  (long long)cfg->staging_bytes, (long long)pool_bytes);
+    const int64_t need_staging = by_class ? std::min(cfg->chunk_blocks, host_blocks) * block_bytes_of(cfg) : pool_bytes;
+    if (cfg->staging_bytes < need_staging)
+      return fail(nullptr, OKV_ENOSPC, "okv_create: staging_bytes %lld < %lld (what is streamed at once must fit on the GPU)",
+                  (long long)cfg->staging_bytes, (long long)need_staging);
     for (int i = 0; i < OKV_MAX_STAGING; ++i)
       if (!aligned16(cfg->staging[i])) return fail(nullptr, OKV_EINVAL, "okv_create: staging not 16-byte aligned");
     if (cfg->h2d_stream == cfg->compute_stream) return fail(nullptr, OKV_EINVAL, "okv_create: h2d_stream must differ from compute_stream");
@@ -421,6 +571,10 @@ int okv_create(const okv_config *cfg, okv_ctx **out) {
   s.tcap = s.paged ? cfg->block_tokens : cfg->max_ctx;
   s.max_blocks = s.paged ? cfg->max_blocks_per_seq : 1;
   ctx->block_bytes = (int64_t)2 * s.G * s.tcap * s.D * 2;
+  ctx->by_class = by_class;
+  ctx->resident_blocks = cfg->resident_blocks;
+  ctx->chunk_blocks = cfg->chunk_blocks;
+  ctx->n_cls = max_classes_of(cfg);
 
   // workspace: [max_items * H][D] floats of weighted sums, then [max_items * H][2] floats
   const int64_t per_item = bytes_per_item(cfg);
@@ -449,10 +603,14 @@ int okv_create(const okv_config *cfg, okv_ctx **out) {
   OKV_TRY_CREATE(hipMalloc(&ctx->d_block_table, tbl));
   OKV_TRY_CREATE(hipMemset(ctx->d_block_table, 0, tbl));
   OKV_TRY_CREATE(hipMalloc(&ctx->d_ctx_lens, (size_t)cfg->max_batch * sizeof(int32_t)));
-  OKV_TRY_CREATE(hipMalloc(&ctx->d_chunk_prefix, ((size_t)cfg->max_batch + 1) * sizeof(int32_t)));
+  OKV_TRY_CREATE(hipMalloc(&ctx->d_chunk_prefix, ((size_t)cfg->max_batch * ctx->n_cls + 1) * sizeof(int32_t)));
+  if (by_class) {
+    OKV_TRY_CREATE(hipMalloc(&ctx->d_pair_first, ((size_t)cfg->max_batch * ctx->n_cls + 1) * sizeof(int32_t)));
+    OKV_TRY_CREATE(hipMalloc(&ctx->d_seq_total, (size_t)cfg->max_batch * sizeof(int32_t)));
+  }
   OKV_TRY_CREATE(hipMalloc(&ctx->d_item_desc, (size_t)std::max<int64_t>(1, max_items) * sizeof(int4)));
-  OKV_TRY_CREATE(hipMalloc(&ctx->d_queues, (size_t)L * sizeof(uint32_t)));
-  OKV_TRY_CREATE(hipMemset(ctx->d_queues, 0, (size_t)L * sizeof(uint32_t)));
+  OKV_TRY_CREATE(hipMalloc(&ctx->d_queues, (size_t)L * ctx->n_cls * sizeof(uint32_t)));
+  OKV_TRY_CREATE(hipMemset(ctx->d_queues, 0, (size_t)L * ctx->n_cls * sizeof(uint32_t)));
   {
     int dev = 0, cus = 0;
     OKV_TRY_CREATE(hipGetDevice(&dev));
@@ -483,6 +641,9 @@ int okv_destroy(okv_ctx *ctx) {
   (void)hipFree(ctx->d_item_desc);
   (void)hipFree(ctx->d_queues);
   (void)hipFree(ctx->d_items_dump);
+  (void)hipFree(ctx->d_runs);
+  (void)hipFree(ctx->d_pair_first);
+  (void)hipFree(ctx->d_seq_total);
   for (int i = 0; i < kEventRing; ++i) {
     if (ctx->ready_ev[i]) (void)hipEventDestroy(ctx->ready_ev[i]);
     if (ctx->consumed_ev[i]) (void)hipEventDestroy(ctx->consumed_ev[i]);
@@ -538,6 +699,7 @@ int okv_set_batch(okv_ctx *ctx, int32_t B, const int32_t *block_table, const int
   }
   int rc = okv_synchronize(ctx);
   if (rc) return rc;
+  ctx->batch_set = false;
   ctx->B = B;
   ctx->h_ctx_lens.assign(ctx_lens, ctx_lens + B);
   if (s.paged) {
@@ -548,10 +710,45 @@ int okv_set_batch(okv_ctx *ctx, int32_t B, const int32_t *block_table, const int
     ctx->copy_bytes = (int64_t)B * ctx->block_bytes;
   }
   OKV_HIP(ctx, hipMemcpy(ctx->d_ctx_lens, ctx_lens, (size_t)B * sizeof(int32_t), hipMemcpyHostToDevice));
-  std::vector<uint8_t> on_host(ctx->cfg.n_layers, 0);
-  for (int32_t l = 0; l < ctx->cfg.n_layers; ++l) on_host[l] = ctx->host_pool[l] != nullptr;
-  ctx->sched.reset(ctx->cfg.n_layers, on_host.data(), ctx->n_staging);
-  ctx->step = 0;
+  ctx->unit_offset.assign(1, 0);
+  ctx->unit_bytes.assign(1, ctx->copy_bytes);
+  if (ctx->by_class) {
+    // runs of one class per sequence, and the chunks of the host pool the batch touches
+    okv::build_runs(block_table, B, s.max_blocks, ctx->cfg.block_tokens, ctx->resident_blocks, ctx->chunk_blocks,
+                    ctx->n_cls, ctx->h_runs, ctx->h_pair_first);
+    std::vector<int64_t> used(ctx->n_cls, 0);            // blocks of each class up to the highest id in the table
+    for (int32_t b = 0; b < B; ++b)
+      for (int32_t i = 0; i < s.max_blocks; ++i) {
+        const int64_t id = block_table[(size_t)b * s.max_blocks + i];
+        if (id < ctx->resident_blocks) continue;          // in HBM, or not allocated
+        const int64_t local = id - ctx->resident_blocks;
+        const int64_t chunk = local / ctx->chunk_blocks;
+        used[1 + chunk] = std::max(used[1 + chunk], local - chunk * ctx->chunk_blocks + 1);
+      }
+    ctx->active_chunks.clear();
+    ctx->unit_offset.clear();
+    ctx->unit_bytes.clear();
+    for (int32_t c = 1; c < ctx->n_cls; ++c)
+      if (used[c] > 0) {
+        ctx->active_chunks.push_back(c - 1);
+        ctx->unit_offset.push_back((int64_t)(c - 1) * ctx->chunk_blocks * ctx->block_bytes);
+        ctx->unit_bytes.push_back(used[c] * ctx->block_bytes);
+      }
+    ctx->has_resident = ctx->h_pair_first[B] > 0;         // some run of class 0
+    const int64_t n_runs = (int64_t)ctx->h_runs.size();
+    if (n_runs > ctx->runs_cap) {
+      (void)hipFree(ctx->d_runs);
+      ctx->d_runs = nullptr;
+      ctx->runs_cap = 0;
+      OKV_HIP(ctx, hipMalloc(&ctx->d_runs, (size_t)n_runs * sizeof(int4)));
+      ctx->runs_cap = n_runs;
+    }
+    static_assert(sizeof(okv::Run) == sizeof(int4), "runs are uploaded as they are");
+    if (n_runs) OKV_HIP(ctx, hipMemcpy(ctx->d_runs, ctx->h_runs.data(), (size_t)n_runs * sizeof(int4), hipMemcpyHostToDevice));
+    OKV_HIP(ctx, hipMemcpy(ctx->d_pair_first, ctx->h_pair_first.data(), ctx->h_pair_first.size() * sizeof(int32_t),
+                           hipMemcpyHostToDevice));
+  }
+  reset_schedule(ctx);
   ctx->next_layer = 0;
   ctx->appended = false;
   ctx->batch_set = true;
@@ -577,7 +774,7 @@ int okv_step_begin(okv_ctx *ctx) {
     for (int32_t b = 0; b < ctx->B; ++b) ctx->h_ctx_lens[b] -= 1;
     return rc;
   }
-  if (ctx->any_host && !ctx->sched.primed()) {
+  if (ctx->sched.n_units() > 0 && !ctx->sched.primed()) {
     std::vector<Op> ops;
     ctx->sched.prime(ops);
     rc = exec_ops(ctx, ops, nullptr, nullptr, nullptr);
@@ -666,7 +863,8 @@ int okv_worklist(okv_ctx *ctx, int32_t from_device, int32_t *items, int64_t max_
   if (ctx->n_items == 0) return OKV_OK;
   if (from_device) {
     if (!ctx->d_items_dump) OKV_HIP(ctx, hipMalloc(&ctx->d_items_dump, (size_t)ctx->max_items * 3 * sizeof(int32_t)));
-    okv::BatchState bs{ctx->d_block_table, ctx->d_ctx_lens, ctx->d_chunk_prefix, ctx->d_item_desc, ctx->B, ctx->split, ctx->n_items};
+    okv::BatchState bs{ctx->d_block_table, ctx->d_ctx_lens, ctx->d_chunk_prefix, ctx->d_item_desc, ctx->B, ctx->split,
+                       ctx->n_items, ctx->n_cls};
     OKV_HIP(ctx, okv::launch_worklist_dump(bs, ctx->d_items_dump, ctx->compute));
     OKV_HIP(ctx, hipStreamSynchronize(ctx->compute));
     OKV_HIP(ctx, hipMemcpy(items, ctx->d_items_dump, (size_t)ctx->n_items * 3 * sizeof(int32_t), hipMemcpyDeviceToHost));
@@ -674,6 +872,18 @@ int okv_worklist(okv_ctx *ctx, int32_t from_device, int32_t *items, int64_t max_
   }
   // host walk: the same arithmetic the device kernel runs
   int64_t it = 0;
+  if (ctx->by_class) {
+    for (const okv::Run &r : ctx->h_runs) {               // sorted by (class, sequence, position)
+      int32_t sz;
+      const int32_t n = ctx->h_ctx_lens[r.b];
+      const int32_t cnt = okv::run_items(r.lo, r.hi_cap, n, ctx->split, &sz);
+      const int32_t end = std::min(r.hi_cap, n);
+      for (int32_t c = 0; c < cnt; ++c, ++it) {
+        items[it * 3 + 0] = r.b, items[it * 3 + 1] = r.lo + c * sz, items[it * 3 + 2] = std::min(r.lo + (c + 1) * sz, end);
+      }
+    }
+    return OKV_OK;
+  }
   for (int32_t b = 0; b < ctx->B; ++b) {
     int32_t cnt, sz;
     okv::seq_chunks(ctx->h_ctx_lens[b], ctx->split, &cnt, &sz);
@@ -681,6 +891,26 @@ int okv_worklist(okv_ctx *ctx, int32_t from_device, int32_t *items, int64_t max_
       okv::ItemRange r = okv::chunk_range(b, c, sz, ctx->h_ctx_lens[b]);
       items[it * 3 + 0] = r.b, items[it * 3 + 1] = r.lo, items[it * 3 + 2] = r.hi;
     }
+  }
+  return OKV_OK;
+}
+
+int okv_worklist_classes(okv_ctx *ctx, int32_t from_device, int32_t *class_first, int32_t max_classes, int32_t *n_classes) {
+  if (!ctx || !class_first || !n_classes) return fail(ctx, OKV_EINVAL, "NULL argument");
+  if (!ctx->batch_set) return fail(ctx, OKV_ESTATE, "no batch set");
+  *n_classes = ctx->n_cls;
+  if (ctx->n_cls + 1 > max_classes) return fail(ctx, OKV_ENOSPC, "%d classes", ctx->n_cls);
+  if (from_device) {
+    OKV_HIP(ctx, hipStreamSynchronize(ctx->compute));
+    for (int32_t c = 0; c <= ctx->n_cls; ++c)             // chunk_prefix[cls * B] = items before class cls
+      OKV_HIP(ctx, hipMemcpy(class_first + c, ctx->d_chunk_prefix + (size_t)c * ctx->B, sizeof(int32_t), hipMemcpyDeviceToHost));
+    return OKV_OK;
+  }
+  if (ctx->by_class) {
+    for (int32_t c = 0; c <= ctx->n_cls; ++c) class_first[c] = ctx->cls_first[c];
+  } else {
+    class_first[0] = 0;
+    class_first[1] = ctx->n_items;
   }
   return OKV_OK;
 }
@@ -764,7 +994,7 @@ int okv_time_copies(okv_ctx *ctx, double *ms) {
   if (!ctx->batch_set) return fail(ctx, OKV_ESTATE, "no batch set");
   if (ctx->in_step) return fail(ctx, OKV_ESTATE, "okv_time_copies inside a step");
   *ms = 0;
-  if (!ctx->any_host) return OKV_OK;
+  if (ctx->sched.n_units() == 0) return OKV_OK;
   int rc = okv_synchronize(ctx);
   if (rc) return rc;
   hipEvent_t e0, e1;
@@ -774,8 +1004,11 @@ int okv_time_copies(okv_ctx *ctx, double *ms) {
   int buf = 0;
   for (int32_t l = 0; l < ctx->cfg.n_layers && e == hipSuccess; ++l) {
     if (!ctx->host_pool[l]) continue;
-    e = hipMemcpyAsync(ctx->cfg.staging[buf], ctx->host_pool[l], (size_t)ctx->copy_bytes, hipMemcpyHostToDevice, ctx->h2d);
-    buf = (buf + 1) % ctx->n_staging;
+    for (size_t u = 0; u < ctx->unit_bytes.size() && e == hipSuccess; ++u) {
+      const char *src = static_cast<const char *>(ctx->host_pool[l]) + ctx->unit_offset[u];
+      e = hipMemcpyAsync(ctx->cfg.staging[buf], src, (size_t)ctx->unit_bytes[u], hipMemcpyHostToDevice, ctx->h2d);
+      buf = (buf + 1) % ctx->n_staging;
+    }
   }
   if (e == hipSuccess) e = hipEventRecord(e1, ctx->h2d);
   if (e == hipSuccess) e = hipEventSynchronize(e1);
@@ -786,10 +1019,7 @@ int okv_time_copies(okv_ctx *ctx, double *ms) {
   if (e != hipSuccess) return fail(ctx, OKV_EHIP, "okv_time_copies: %s", hipGetErrorString(e));
   *ms = t;
   // the staging buffers no longer hold what the pipeline had prefetched: start it afresh
-  std::vector<uint8_t> on_host(ctx->cfg.n_layers, 0);
-  for (int32_t l = 0; l < ctx->cfg.n_layers; ++l) on_host[l] = ctx->host_pool[l] != nullptr;
-  ctx->sched.reset(ctx->cfg.n_layers, on_host.data(), ctx->n_staging);
-  ctx->step = 0;                                       // copy indices count from the restart
+  reset_schedule(ctx);
   return OKV_OK;
 }
 

@@ -30,53 +30,59 @@ inline void plan_place(int32_t n_layers, int32_t n_off, uint8_t *on_host) {
 
 // ---- copy pipeline (paper §II-B: offloaded KV is fetched back before use) ----
 //
-// Host layers are consumed in layer order, step after step; the j-th consumption
-// overall ("copy index" j) is of host layer hl[j % k] in step j / k and uses
-// staging buffer j % depth, depth = min(n_staging, k).  Copy j may start once
-// the consumer of copy j - depth has released the buffer; because depth <= k
-// that consumer ran after the previous step's append to the same layer, so the
-// host pool the copy reads is up to date.  Each release immediately enqueues
-// copy j + depth, which keeps `depth` copies in flight, across step boundaries.
+// The streamed unit is a chunk of a layer's host pool: the whole pool when whole layers
+// are offloaded (one chunk per host layer), a run of consecutive blocks when a share of
+// every layer's blocks is.  Chunks are consumed layer by layer, chunk by chunk, step
+// after step; the j-th consumption overall ("copy index" j) is of unit j % k (k units per
+// step) in step j / k and uses staging buffer j % depth, depth = min(n_staging, k).  Copy
+// j may start once the consumer of copy j - depth has released the buffer; because
+// depth <= k that consumer is no earlier than the previous step's attention over the same
+// chunk, which is the launch that stored new rows into that chunk of the host pool, so
+// what the copy reads is up to date.  Each release immediately enqueues copy j + depth,
+// which keeps `depth` copies in flight, across step boundaries.
 
-enum OpKind : int32_t { OP_COPY = 0, OP_APPEND = 1, OP_ATTN = 2, OP_RELEASE = 3 };
+enum OpKind : int32_t { OP_COPY = 0, OP_APPEND = 1, OP_ATTN = 2, OP_RELEASE = 3, OP_MERGE = 4 };
 
 struct Op {
-  int32_t kind, step, layer, buf, copy_idx, wait_idx;
+  int32_t kind, step, layer, chunk, buf;   // chunk = -1, buf = -1: the keys that stay in HBM
+  int64_t copy_idx, wait_idx;
 };
 
 class Scheduler {
  public:
-  void reset(int32_t n_layers, const uint8_t *on_host, int32_t n_staging) {
+  // host_chunks[l]: streamed chunks of layer l; has_resident[l]: layer l has keys in HBM.
+  void reset(int32_t n_layers, const int32_t *host_chunks, const uint8_t *has_resident, int32_t n_staging) {
     n_layers_ = n_layers;
-    on_host_.assign(on_host, on_host + n_layers);
-    host_layers_.clear();
-    rank_.assign(n_layers, -1);
-    for (int32_t l = 0; l < n_layers; ++l)
-      if (on_host[l]) {
-        rank_[l] = (int32_t)host_layers_.size();
-        host_layers_.push_back(l);
+    chunks_.assign(host_chunks, host_chunks + n_layers);
+    resident_.assign(has_resident, has_resident + n_layers);
+    first_unit_.assign(n_layers, 0);
+    unit_layer_.clear();
+    unit_chunk_.clear();
+    for (int32_t l = 0; l < n_layers; ++l) {
+      first_unit_[l] = (int32_t)unit_layer_.size();
+      for (int32_t c = 0; c < chunks_[l]; ++c) {
+        unit_layer_.push_back(l);
+        unit_chunk_.push_back(c);
       }
-    k_ = (int32_t)host_layers_.size();
+    }
+    k_ = (int32_t)unit_layer_.size();
     depth_ = k_ < n_staging ? k_ : n_staging;
     primed_ = false;
   }
 
   int32_t depth() const { return depth_; }
-  int32_t n_host() const { return k_; }
-  bool is_host(int32_t layer) const { return on_host_[layer] != 0; }
+  int32_t n_units() const { return k_; }
   bool primed() const { return primed_; }
-
-  // Copy index of (step, host layer).
-  int64_t copy_index(int64_t step, int32_t layer) const { return step * k_ + rank_[layer]; }
 
   Op make_copy(int64_t j, int64_t wait) const {
     Op op;
     op.kind = OP_COPY;
     op.step = (int32_t)(j / k_);
-    op.layer = host_layers_[j % k_];
+    op.layer = unit_layer_[j % k_];
+    op.chunk = unit_chunk_[j % k_];
     op.buf = (int32_t)(j % depth_);
-    op.copy_idx = (int32_t)j;
-    op.wait_idx = (int32_t)wait;
+    op.copy_idx = j;
+    op.wait_idx = wait;
     return op;
   }
 
@@ -88,33 +94,26 @@ class Scheduler {
   }
 
   void on_append(int64_t step, int32_t layer, std::vector<Op> &out) const {
-    Op op{OP_APPEND, (int32_t)step, layer, -1, -1, -1};
-    if (is_host(layer)) {
-      int64_t j = copy_index(step, layer);
-      op.buf = (int32_t)(j % depth_);
-      op.wait_idx = (int32_t)j;
-    }
-    out.push_back(op);
+    out.push_back(Op{OP_APPEND, (int32_t)step, layer, -1, -1, -1, -1});
   }
 
   void on_attn(int64_t step, int32_t layer, std::vector<Op> &out) const {
-    Op op{OP_ATTN, (int32_t)step, layer, -1, -1, -1};
-    if (!is_host(layer)) {
-      out.push_back(op);
-      return;
+    if (resident_[layer]) out.push_back(Op{OP_ATTN, (int32_t)step, layer, -1, -1, -1, -1});
+    for (int32_t c = 0; c < chunks_[layer]; ++c) {
+      const int64_t j = step * k_ + first_unit_[layer] + c;
+      const int32_t buf = (int32_t)(j % depth_);
+      out.push_back(Op{OP_ATTN, (int32_t)step, layer, c, buf, j, j});
+      out.push_back(Op{OP_RELEASE, (int32_t)step, layer, c, buf, j, -1});
+      out.push_back(make_copy(j + depth_, j));
     }
-    int64_t j = copy_index(step, layer);
-    op.buf = (int32_t)(j % depth_);
-    out.push_back(op);
-    out.push_back(Op{OP_RELEASE, (int32_t)step, layer, op.buf, (int32_t)j, -1});
-    out.push_back(make_copy(j + depth_, j));
+    out.push_back(Op{OP_MERGE, (int32_t)step, layer, -1, -1, -1, -1});
   }
 
  private:
   int32_t n_layers_ = 0, k_ = 0, depth_ = 0;
   bool primed_ = false;
-  std::vector<uint8_t> on_host_;
-  std::vector<int32_t> host_layers_, rank_;
+  std::vector<int32_t> chunks_, first_unit_, unit_layer_, unit_chunk_;
+  std::vector<uint8_t> resident_;
 };
 
 // ---- split-K work list ------------------------------------------------------
@@ -150,6 +149,54 @@ __host__ __device__ inline ItemRange chunk_range(int32_t b, int32_t c, int32_t s
   r.lo = c * sz;
   r.hi = r.lo + sz < n ? r.lo + sz : n;
   return r;
+}
+
+// ---- block classes (paper §IV-C: a share C_off of the cache lives in host memory) ----
+//
+// With block-granular offload, block ids below `resident` are in HBM (class 0); the others
+// are in the host pool, streamed in chunks of `chunk` consecutive blocks (host block i is in
+// class 1 + i / chunk).  Every class is attended by a launch of its own, so a sequence is
+// first cut into runs of consecutive positions whose blocks share a class, and each run is
+// cut into equal pieces by seq_chunks with the run's length in place of the sequence's.
+inline int32_t block_class(int64_t id, int64_t resident, int64_t chunk) {
+  return id < resident ? 0 : 1 + (int32_t)((id - resident) / chunk);
+}
+
+struct Run {
+  int32_t b, lo, hi_cap, cls;   // positions [lo, hi_cap) of sequence b lie in blocks of class cls
+};
+
+// Runs over the allocated prefix of every table row, sorted by (class, sequence, position);
+// pair_first[cls * B + b] .. pair_first[cls * B + b + 1] are the runs of sequence b in class cls.
+inline void build_runs(const int32_t *table, int32_t B, int32_t max_blocks, int32_t T, int64_t resident,
+                       int64_t chunk, int32_t n_cls, std::vector<Run> &runs, std::vector<int32_t> &pair_first) {
+  std::vector<Run> found;
+  std::vector<int32_t> count((size_t)n_cls * B + 1, 0);
+  for (int32_t b = 0; b < B; ++b) {
+    const int32_t *row = table + (size_t)b * max_blocks;
+    int32_t j = 0;
+    while (j < max_blocks && row[j] >= 0) {
+      const int32_t cls = block_class(row[j], resident, chunk);
+      int32_t e = j + 1;
+      while (e < max_blocks && row[e] >= 0 && block_class(row[e], resident, chunk) == cls) ++e;
+      found.push_back(Run{b, j * T, e * T, cls});
+      count[(size_t)cls * B + b] += 1;
+      j = e;
+    }
+  }
+  pair_first.assign((size_t)n_cls * B + 1, 0);
+  for (size_t p = 0; p < (size_t)n_cls * B; ++p) pair_first[p + 1] = pair_first[p] + count[p];
+  std::vector<int32_t> at(pair_first.begin(), pair_first.end() - 1);
+  runs.resize(found.size());
+  for (const Run &r : found) runs[at[(size_t)r.cls * B + r.b]++] = r;   // rows were walked in position order
+}
+
+// Items of one run when its sequence holds n keys.
+__host__ __device__ inline int32_t run_items(int32_t lo, int32_t hi_cap, int32_t n, int32_t S, int32_t *size) {
+  const int32_t len = (hi_cap < n ? hi_cap : n) - lo;
+  int32_t cnt;
+  seq_chunks(len, S, &cnt, size);
+  return cnt;
 }
 
 }  // namespace okv

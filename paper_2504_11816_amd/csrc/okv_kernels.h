@@ -19,11 +19,12 @@ struct PoolShape {
 struct BatchState {        // device arrays owned by the context
   const int32_t *block_table;   // [B][max_blocks]
   const int32_t *ctx_lens;      // [B]
-  const int32_t *chunk_prefix;  // [B + 1] items of the sequences before b
+  const int32_t *chunk_prefix;  // [n_cls * B + 1] items before those of (class, sequence), class-major
   const int4 *item_desc;        // [n_items] (sequence, first key, one past last key, flags)
   int32_t B;
   int32_t split_tokens;
-  int32_t n_items;
+  int32_t n_items;              // over all classes
+  int32_t n_cls;                // block classes: 1 unless a share of every layer's blocks is on the host
 };
 
 struct AttnLaunch {
@@ -41,18 +42,36 @@ struct AttnLaunch {
   int32_t need_merge;      // some sequence has more than one item
   uint32_t *queue;         // this launch's ticket counter (zeroed by launch_step_advance)
   int32_t max_waves;       // wavefronts of the persistent launch (a multiple of 4)
+  // The launch covers items [item_first, item_first + item_count) of the list: all of them, or
+  // those of one block class.  `pool` then holds the blocks with ids from id_base on, and
+  // `pool_mirror` those from mirror_base on.
+  int32_t item_first, item_count;
+  int32_t id_base, mirror_base;
 };
 
-// Store of the step's K/V rows and split-K partial attention in one launch, followed,
-// if needed, by the merge of the partials.
+// Store of the step's K/V rows and split-K partial attention over the launch's items.
 hipError_t launch_decode_attn(const AttnLaunch &a, hipStream_t stream,
                               hipEvent_t ev_begin, hipEvent_t ev_end);
+
+// Merge of the partial results of every sequence that has more than one item (reads
+// shape, batch, out, part_o, part_ml, out_fp32 of `a`).
+hipError_t launch_merge(const AttnLaunch &a, hipStream_t stream);
 
 // ctx_lens[b] += inc; rebuilds chunk_prefix and the item list for split size S; zeroes the
 // n_queues ticket counters.
 hipError_t launch_step_advance(int32_t *ctx_lens, int32_t *chunk_prefix, int4 *item_desc,
                                uint32_t *queues, int32_t n_queues, int32_t B, int32_t S,
                                int32_t inc, hipStream_t stream);
+
+// The same for block classes: runs[r] = (sequence, first position, one past the last position
+// the run can hold, class), sorted by (class, sequence, position); pair_first[cls * B + b] is the
+// first run of (class, sequence).  Items are listed class by class; chunk_prefix[cls * B + b]
+// counts the items before those of (class, sequence).  seq_total[b] receives the sequence's
+// item count.
+hipError_t launch_step_advance_classes(int32_t *ctx_lens, const int4 *runs, const int32_t *pair_first,
+                                       int32_t *chunk_prefix, int4 *item_desc, int32_t *seq_total,
+                                       uint32_t *queues, int32_t n_queues, int32_t B, int32_t n_cls,
+                                       int32_t S, int32_t inc, hipStream_t stream);
 
 // items[it] = (b, lo, hi) decoded on the device.
 hipError_t launch_worklist_dump(const BatchState &batch, int32_t *items, hipStream_t stream);

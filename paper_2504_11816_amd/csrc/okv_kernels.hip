@@ -136,7 +136,11 @@ struct AttnArgs {
   const int32_t *block_table, *chunk_prefix;
   const int4 *item_desc;           // [n_items] (sequence, first key, one past last key, flags)
   uint32_t *queue;                 // ticket counter of this launch, zero when the kernel starts
-  int32_t H, G, log2_T, tcap, max_blocks, n_items, n_units, out_fp32;
+  int32_t H, G, log2_T, tcap, max_blocks, n_units, out_fp32;
+  int32_t item_first;              // the launch's first item in item_desc (and in the partial slots)
+  int32_t id_base;                 // `pool` holds the blocks with ids id_base, id_base + 1, ...
+  int32_t mirror_shift;            // id_base minus the id of the first block of pool_mirror
+  int32_t B, n_cls;                // merge: chunk_prefix is [n_cls][B] (+ 1)
   float scale_log2e;
 };
 
@@ -192,7 +196,7 @@ __device__ __forceinline__ void attend_item(const AttnArgs &a, const int it, con
     if (!PAGED) return b;
     int bi = (tile << 4) >> a.log2_T;
     bi = bi < a.max_blocks ? bi : a.max_blocks - 1;
-    return tbl_row[bi];
+    return tbl_row[bi] - a.id_base;
   };
   auto load_tile = [&](Tile<LPT> &t, int tile, int blk) {
     const int slot0 = PAGED ? (tile << 4) & (a.tcap - 1) : (tile << 4);
@@ -308,10 +312,12 @@ __device__ __forceinline__ void attend_item(const AttnArgs &a, const int it, con
 
   if (appending && row < 2) {                          // row 0 stores the K row, row 1 the V row
     const int slot = PAGED ? pos & (a.tcap - 1) : pos;
-    const int64_t at = (((int64_t)blk_of(pos >> 4) * 2 + row) * a.G + g) * slice + (int64_t)slot * D + col * 8;
+    const int blk = blk_of(pos >> 4);
+    const int64_t in_blk = ((int64_t)row * a.G + g) * slice + (int64_t)slot * D + col * 8;
     const uint4 val = row == 0 ? k_row : v_row;
-    *reinterpret_cast<uint4 *>(a.pool_store + at) = val;
-    if (a.pool_mirror) *reinterpret_cast<uint4 *>(a.pool_mirror + at) = val;
+    *reinterpret_cast<uint4 *>(a.pool_store + (int64_t)blk * 2 * a.G * slice + in_blk) = val;
+    if (a.pool_mirror)
+      *reinterpret_cast<uint4 *>(a.pool_mirror + (int64_t)(blk + (PAGED ? a.mirror_shift : 0)) * 2 * a.G * slice + in_blk) = val;
   }
 }
 
@@ -331,7 +337,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_kernel(const A
   while (ticket < (uint32_t)a.n_units) {
     const int it = (int)(ticket / (uint32_t)a.G);
     const int g = (int)(ticket - (uint32_t)it * (uint32_t)a.G);
-    attend_item<D, R, PAGED, PIPE>(a, it, g, lane);
+    attend_item<D, R, PAGED, PIPE>(a, a.item_first + it, g, lane);
     if (n_waves >= (uint32_t)a.n_units) break;           // every unit had its own wavefront
     uint32_t drawn = 0;
     if (lane == 0) drawn = atomicAdd(a.queue, 1u);
@@ -340,59 +346,68 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_kernel(const A
 }
 
 // out[b][h] = sum_c o_c 2^(m_c - M) / sum_c l_c 2^(m_c - M) over the items c of sequence b.
-// One wavefront per (b, h).  Lane c first fetches (m_c, l_c) of item c, so the maxima and
-// weights of up to 64 items are formed by wavefront reductions instead of a chain of
-// dependent loads; the weighted sums then stream the partial rows four items at a time.
+// One wavefront per (b, h).  The items of a sequence are one contiguous range of the list per
+// block class.  Lane c first fetches (m_c, l_c) of item c, so the maxima and weights of up to
+// 64 items are formed by wavefront reductions instead of a chain of dependent loads; the
+// weighted sums then stream the partial rows four items at a time.
 template <int D>
 __global__ __launch_bounds__(64) void attn_merge_kernel(const AttnArgs a) {
   constexpr int EPT = D / 64;
   const int b = blockIdx.y, h = blockIdx.x, lane = threadIdx.x;
-  const int first = a.chunk_prefix[b];
-  const int n_chunks = a.chunk_prefix[b + 1] - first;
-  if (n_chunks <= 1) return;                           // written by the split kernel
   float M = kNegBig;
-  for (int c0 = 0; c0 < n_chunks; c0 += 64) {
-    const int c = c0 + lane;
-    float mc = c < n_chunks ? a.part_ml[((size_t)(first + c) * a.H + h) * 2] : kNegBig;
+  int total = 0;
+  for (int cls = 0; cls < a.n_cls; ++cls) {
+    const int first = a.chunk_prefix[cls * a.B + b];
+    const int n_chunks = a.chunk_prefix[cls * a.B + b + 1] - first;
+    total += n_chunks;
+    for (int c0 = 0; c0 < n_chunks; c0 += 64) {
+      const int c = c0 + lane;
+      float mc = c < n_chunks ? a.part_ml[((size_t)(first + c) * a.H + h) * 2] : kNegBig;
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) mc = fmaxf(mc, __shfl_xor(mc, off));
-    M = fmaxf(M, mc);
+      for (int off = 32; off > 0; off >>= 1) mc = fmaxf(mc, __shfl_xor(mc, off));
+      M = fmaxf(M, mc);
+    }
   }
+  if (total <= 1) return;                              // written by the split kernel
   float L = 0.f, acc[EPT];
 #pragma unroll
   for (int e = 0; e < EPT; ++e) acc[e] = 0.f;
-  for (int c0 = 0; c0 < n_chunks; c0 += 64) {
-    const int c = c0 + lane;
-    float w = 0.f, lw = 0.f;
-    if (c < n_chunks) {
-      const float2 ml = *reinterpret_cast<const float2 *>(a.part_ml + ((size_t)(first + c) * a.H + h) * 2);
-      w = __builtin_amdgcn_exp2f(ml.x - M);
-      lw = ml.y * w;
-    }
+  for (int cls = 0; cls < a.n_cls; ++cls) {
+    const int first = a.chunk_prefix[cls * a.B + b];
+    const int n_chunks = a.chunk_prefix[cls * a.B + b + 1] - first;
+    for (int c0 = 0; c0 < n_chunks; c0 += 64) {
+      const int c = c0 + lane;
+      float w = 0.f, lw = 0.f;
+      if (c < n_chunks) {
+        const float2 ml = *reinterpret_cast<const float2 *>(a.part_ml + ((size_t)(first + c) * a.H + h) * 2);
+        w = __builtin_amdgcn_exp2f(ml.x - M);
+        lw = ml.y * w;
+      }
 #pragma unroll
-    for (int off = 32; off > 0; off >>= 1) lw += __shfl_xor(lw, off);
-    L += lw;
-    const int cnt = min(64, n_chunks - c0);
-    int i = 0;
-    for (; i + 4 <= cnt; i += 4) {                     // four independent rows in flight
-      float x[4][EPT];
+      for (int off = 32; off > 0; off >>= 1) lw += __shfl_xor(lw, off);
+      L += lw;
+      const int cnt = min(64, n_chunks - c0);
+      int i = 0;
+      for (; i + 4 <= cnt; i += 4) {                     // four independent rows in flight
+        float x[4][EPT];
 #pragma unroll
-      for (int k = 0; k < 4; ++k)
+        for (int k = 0; k < 4; ++k)
+#pragma unroll
+          for (int e = 0; e < EPT; ++e)
+            x[k][e] = a.part_o[((size_t)(first + c0 + i + k) * a.H + h) * D + lane * EPT + e];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          const float wk = __shfl(w, i + k);
+#pragma unroll
+          for (int e = 0; e < EPT; ++e) acc[e] += x[k][e] * wk;
+        }
+      }
+      for (; i < cnt; ++i) {
+        const float wk = __shfl(w, i);
 #pragma unroll
         for (int e = 0; e < EPT; ++e)
-          x[k][e] = a.part_o[((size_t)(first + c0 + i + k) * a.H + h) * D + lane * EPT + e];
-#pragma unroll
-      for (int k = 0; k < 4; ++k) {
-        const float wk = __shfl(w, i + k);
-#pragma unroll
-        for (int e = 0; e < EPT; ++e) acc[e] += x[k][e] * wk;
+          acc[e] += a.part_o[((size_t)(first + c0 + i) * a.H + h) * D + lane * EPT + e] * wk;
       }
-    }
-    for (; i < cnt; ++i) {
-      const float wk = __shfl(w, i);
-#pragma unroll
-      for (int e = 0; e < EPT; ++e)
-        acc[e] += a.part_o[((size_t)(first + c0 + i) * a.H + h) * D + lane * EPT + e] * wk;
     }
   }
   const float inv = 1.0f / L;
@@ -449,10 +464,10 @@ hipError_t launch_split_group(const AttnArgs &args, int R, bool paged, dim3 grid
 
 }  // namespace
 
-hipError_t launch_decode_attn(const AttnLaunch &a, hipStream_t stream, hipEvent_t ev_begin,
-                              hipEvent_t ev_end) {
+namespace {
+
+AttnArgs make_args(const AttnLaunch &a) {
   const PoolShape &s = a.shape;
-  if (a.batch.n_items <= 0) return hipErrorInvalidValue;
   AttnArgs args;
   args.q = static_cast<const uint16_t *>(a.q);
   args.pool = static_cast<const uint16_t *>(a.pool);
@@ -472,11 +487,26 @@ hipError_t launch_decode_attn(const AttnLaunch &a, hipStream_t stream, hipEvent_
   args.log2_T = s.log2_T;
   args.tcap = s.tcap;
   args.max_blocks = s.max_blocks;
-  args.n_items = a.batch.n_items;
-  args.n_units = a.batch.n_items * s.G;
+  args.n_units = a.item_count * s.G;
   args.out_fp32 = a.out_fp32;
+  args.item_first = a.item_first;
+  args.id_base = a.id_base;
+  args.mirror_shift = a.id_base - a.mirror_base;
+  args.B = a.batch.B;
+  args.n_cls = a.batch.n_cls;
   // exp(x) = 2^(x log2 e): the 1/sqrt(d) scale and log2 e are folded into one factor
   args.scale_log2e = 1.4426950408889634f / sqrtf((float)s.D);
+  return args;
+}
+
+}  // namespace
+
+hipError_t launch_decode_attn(const AttnLaunch &a, hipStream_t stream, hipEvent_t ev_begin,
+                              hipEvent_t ev_end) {
+  const PoolShape &s = a.shape;
+  if (a.item_count <= 0 || a.item_first < 0 || a.item_first + a.item_count > a.batch.n_items)
+    return hipErrorInvalidValue;
+  const AttnArgs args = make_args(a);
   const int R = s.H / s.G;
   // persistent launch: no more wavefronts than there are units, no more than a.max_waves
   const int64_t want = ((int64_t)args.n_units + kWavesPerBlock - 1) / kWavesPerBlock;
@@ -492,15 +522,20 @@ hipError_t launch_decode_attn(const AttnLaunch &a, hipStream_t stream, hipEvent_
     e = hipErrorInvalidValue;
   if (e != hipSuccess) return e;
   if (ev_end && (e = hipEventRecord(ev_end, stream)) != hipSuccess) return e;
-  if (a.need_merge) {
-    dim3 mgrid(s.H, a.batch.B);
-    if (s.D == 128)
-      hipLaunchKernelGGL(attn_merge_kernel<128>, mgrid, dim3(64), 0, stream, args);
-    else
-      hipLaunchKernelGGL(attn_merge_kernel<64>, mgrid, dim3(64), 0, stream, args);
-    e = hipGetLastError();
-  }
-  return e;
+  return hipSuccess;
+}
+
+hipError_t launch_merge(const AttnLaunch &a, hipStream_t stream) {
+  const PoolShape &s = a.shape;
+  const AttnArgs args = make_args(a);
+  dim3 mgrid(s.H, a.batch.B);
+  if (s.D == 128)
+    hipLaunchKernelGGL(attn_merge_kernel<128>, mgrid, dim3(64), 0, stream, args);
+  else if (s.D == 64)
+    hipLaunchKernelGGL(attn_merge_kernel<64>, mgrid, dim3(64), 0, stream, args);
+  else
+    return hipErrorInvalidValue;
+  return hipGetLastError();
 }
 
 // ---- step bookkeeping ------------------------------------------------------------
@@ -551,6 +586,68 @@ __global__ __launch_bounds__(kStepThreads) void step_advance_kernel(int32_t *ctx
   if (tid == kStepThreads - 1) chunk_prefix[B] = part[tid];
 }
 
+// The same bookkeeping when a sequence is cut into runs of one block class each.  Pairs
+// (class, sequence) take the place of sequences: thread t owns a stretch of consecutive
+// pairs, counts their items, the counts are scanned, and the items are written class by
+// class.  chunk_prefix doubles as the store of the per-pair counts between the passes.
+__global__ __launch_bounds__(kStepThreads) void step_advance_classes_kernel(
+    int32_t *ctx_lens, const int4 *runs, const int32_t *pair_first, int32_t *chunk_prefix, int4 *item_desc,
+    int32_t *seq_total, uint32_t *queues, int32_t n_queues, int32_t B, int32_t n_cls, int32_t S, int32_t inc) {
+  __shared__ int32_t part[kStepThreads];
+  const int tid = threadIdx.x;
+  for (int i = tid; i < n_queues; i += kStepThreads) queues[i] = 0u;
+  for (int b = tid; b < B; b += kStepThreads) ctx_lens[b] += inc;
+  __syncthreads();
+  const int P = n_cls * B;
+  const int per = (P + kStepThreads - 1) / kStepThreads;
+  const int p0 = min(P, tid * per), p1 = min(P, p0 + per);
+  int32_t mine = 0;
+  for (int p = p0; p < p1; ++p) {
+    const int32_t n = ctx_lens[p % B];
+    int32_t cnt = 0;
+    for (int r = pair_first[p]; r < pair_first[p + 1]; ++r) {
+      const int4 run = runs[r];
+      int32_t sz;
+      cnt += run_items(run.y, run.z, n, S, &sz);
+    }
+    chunk_prefix[p] = cnt;
+    mine += cnt;
+  }
+  part[tid] = mine;
+  __syncthreads();
+  for (int b = tid; b < B; b += kStepThreads) {
+    int32_t total = 0;
+    for (int cls = 0; cls < n_cls; ++cls) total += chunk_prefix[cls * B + b];
+    seq_total[b] = total;
+  }
+  for (int off = 1; off < kStepThreads; off <<= 1) {
+    int32_t add = tid >= off ? part[tid - off] : 0;
+    __syncthreads();
+    part[tid] += add;
+    __syncthreads();
+  }
+  int32_t at = part[tid] - mine;
+  for (int p = p0; p < p1; ++p) {
+    const int b = p % B;
+    const int32_t n = ctx_lens[b];
+    const int32_t whole = seq_total[b] == 1 ? kItemWhole : 0;
+    chunk_prefix[p] = at;
+    for (int r = pair_first[p]; r < pair_first[p + 1]; ++r) {
+      const int4 run = runs[r];
+      int32_t sz;
+      const int32_t cnt = run_items(run.y, run.z, n, S, &sz);
+      const int32_t end = run.z < n ? run.z : n;
+      for (int32_t c = 0; c < cnt; ++c) {
+        const int32_t lo = run.y + c * sz;
+        const int32_t hi = lo + sz < end ? lo + sz : end;
+        item_desc[at + c] = make_int4(b, lo, hi, (hi == n ? kItemLast : 0) | whole);
+      }
+      at += cnt;
+    }
+  }
+  if (tid == kStepThreads - 1) chunk_prefix[P] = part[tid];
+}
+
 __global__ void worklist_dump_kernel(BatchState bs, int32_t *items) {
   const int it = blockIdx.x * blockDim.x + threadIdx.x;
   if (it >= bs.n_items) return;
@@ -582,6 +679,15 @@ hipError_t launch_step_advance(int32_t *ctx_lens, int32_t *chunk_prefix, int4 *i
                                int32_t inc, hipStream_t stream) {
   hipLaunchKernelGGL(step_advance_kernel, dim3(1), dim3(kStepThreads), 0, stream, ctx_lens,
                      chunk_prefix, item_desc, queues, n_queues, B, S, inc);
+  return hipGetLastError();
+}
+
+hipError_t launch_step_advance_classes(int32_t *ctx_lens, const int4 *runs, const int32_t *pair_first,
+                                       int32_t *chunk_prefix, int4 *item_desc, int32_t *seq_total,
+                                       uint32_t *queues, int32_t n_queues, int32_t B, int32_t n_cls,
+                                       int32_t S, int32_t inc, hipStream_t stream) {
+  hipLaunchKernelGGL(step_advance_classes_kernel, dim3(1), dim3(kStepThreads), 0, stream, ctx_lens, runs,
+                     pair_first, chunk_prefix, item_desc, seq_total, queues, n_queues, B, n_cls, S, inc);
   return hipGetLastError();
 }
 

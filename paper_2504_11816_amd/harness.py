@@ -51,11 +51,14 @@ class Stack:
     """All buffers of one decode workload plus the okv context that uses them.
 
     on_host[l] = 1 puts layer l's pool in pinned host memory (streamed through
-    two staging buffers), 0 keeps it in HBM.
+    two staging buffers), 0 keeps it in HBM.  With chunk_blocks > 0 every layer
+    instead keeps the blocks with ids below resident_blocks in HBM and the others
+    in pinned host memory, streamed in chunks of chunk_blocks blocks.
     """
 
     def __init__(self, *, L, H, G, d, B, T, cap_tokens, on_host=None, out_dtype=0, split_tokens=0,
-                 blocks_per_layer=None, n_staging=2, device="cuda:0"):
+                 blocks_per_layer=None, n_staging=2, device="cuda:0", resident_blocks=0, chunk_blocks=0,
+                 workspace_items=None):
         if not torch.cuda.is_available():
             raise RuntimeError("the okv library needs a GPU; there is no CPU path")
         self.L, self.H, self.G, self.d, self.B, self.T = L, H, G, d, B, T
@@ -76,19 +79,42 @@ class Stack:
         shape = binding.make_config(n_layers=L, n_q_heads=H, n_kv_heads=G, head_dim=d, block_tokens=T,
                                     max_batch=B, max_blocks_per_seq=self.max_blocks, max_ctx=self.max_ctx,
                                     blocks_per_layer=self.blocks_per_layer, out_dtype=out_dtype,
-                                    split_tokens=split_tokens)
+                                    split_tokens=split_tokens, resident_blocks=resident_blocks,
+                                    chunk_blocks=chunk_blocks)
         self.pool_bytes = binding.okv_layer_pool_bytes(shape)
         self.workspace_bytes = binding.okv_workspace_bytes(shape)
+        if workspace_items:
+            self.workspace_bytes = max(self.workspace_bytes, workspace_items * H * (d + 2) * 4)
         n_el = self.pool_bytes // 2
+        self.by_class = chunk_blocks > 0
+        self.resident_blocks, self.chunk_blocks = resident_blocks, chunk_blocks
         self.pools, self._pinned = [], []
-        for l in range(L):
-            if self.on_host[l]:
-                self._pinned.append(PinnedHalfBuffer(n_el))
-                self.pools.append(self._pinned[-1].tensor)
-            else:
-                self.pools.append(torch.empty(n_el, dtype=torch.float16, device=self.device))
-        any_host = bool(self.on_host.any())
-        self.staging = [torch.empty(n_el, dtype=torch.float16, device=self.device) if any_host and i < n_staging
+        self.dev_part, self.host_part = [None] * L, [None] * L
+        if self.by_class:
+            self.block_elems = binding.okv_block_bytes(shape) // 2
+            self.split_at = resident_blocks * self.block_elems      # first element of the host part
+            host_el = n_el - self.split_at
+            for l in range(L):
+                if self.split_at:
+                    self.dev_part[l] = torch.empty(self.split_at, dtype=torch.float16, device=self.device)
+                if host_el:
+                    self._pinned.append(PinnedHalfBuffer(host_el))
+                    self.host_part[l] = self._pinned[-1].tensor
+            any_host = host_el > 0
+            staging_el = min(chunk_blocks, self.blocks_per_layer - resident_blocks) * self.block_elems
+        else:
+            for l in range(L):
+                if self.on_host[l]:
+                    self._pinned.append(PinnedHalfBuffer(n_el))
+                    self.pools.append(self._pinned[-1].tensor)
+                    self.host_part[l] = self.pools[-1]
+                else:
+                    self.pools.append(torch.empty(n_el, dtype=torch.float16, device=self.device))
+                    self.dev_part[l] = self.pools[-1]
+            any_host = bool(self.on_host.any())
+            staging_el = n_el
+        self.staging_bytes = staging_el * 2 if any_host else 0
+        self.staging = [torch.empty(staging_el, dtype=torch.float16, device=self.device) if any_host and i < n_staging
                         else None for i in range(4)]
         self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=self.device)
         self.compute_stream = torch.cuda.Stream(device=self.device)
@@ -98,9 +124,9 @@ class Stack:
             n_layers=L, n_q_heads=H, n_kv_heads=G, head_dim=d, block_tokens=T, max_batch=B,
             max_blocks_per_seq=self.max_blocks, max_ctx=self.max_ctx, blocks_per_layer=self.blocks_per_layer,
             out_dtype=out_dtype, split_tokens=split_tokens,
-            dev_pool=[None if self.on_host[l] else self.pools[l] for l in range(L)],
-            host_pool=[self.pools[l] if self.on_host[l] else None for l in range(L)],
-            staging=tuple(self.staging), staging_bytes=self.pool_bytes if any_host else 0,
+            dev_pool=self.dev_part, host_pool=self.host_part,
+            staging=tuple(self.staging), staging_bytes=self.staging_bytes,
+            resident_blocks=resident_blocks, chunk_blocks=chunk_blocks,
             workspace=self.workspace, workspace_bytes=self.workspace_bytes,
             compute_stream=self.compute_stream.cuda_stream, h2d_stream=self.h2d_stream.cuda_stream)
         self.block_table = None
@@ -122,36 +148,49 @@ class Stack:
     def fill_pool(self, layer, seed, chunk_elems=1 << 27):
         """N(0,1) fp16 into the whole pool of `layer` (generated on the GPU;
         host pools receive it by plain copies)."""
-        pool = self.pools[layer]
-        if pool.is_cuda:
-            synth.fill_randn_f16_(pool, seed, chunk_elems)
-            return
-        gen = torch.Generator(device=self.device)
-        gen.manual_seed(seed)
-        n = pool.numel()
-        for lo in range(0, n, chunk_elems):
-            hi = min(n, lo + chunk_elems)
-            tmp = torch.randn(hi - lo, generator=gen, device=self.device, dtype=torch.float32).to(torch.float16)
-            pool[lo:hi].copy_(tmp)
+        parts = [p for p in (self.dev_part[layer], self.host_part[layer]) if p is not None]
+        for part, sd in zip(parts, (seed, seed ^ 0x5DEECE66D)):     # a layer in one piece gets `seed` wherever it lives
+            if part.is_cuda:
+                synth.fill_randn_f16_(part, sd, chunk_elems)
+                continue
+            gen = torch.Generator(device=self.device)
+            gen.manual_seed(sd)
+            n = part.numel()
+            for lo in range(0, n, chunk_elems):
+                hi = min(n, lo + chunk_elems)
+                tmp = torch.randn(hi - lo, generator=gen, device=self.device, dtype=torch.float32).to(torch.float16)
+                part[lo:hi].copy_(tmp)
         torch.cuda.synchronize(self.device)
 
+    def _parts(self, layer):
+        """[(first element, tensor)] of the layer's pool in id order."""
+        out, at = [], 0
+        for part in (self.dev_part[layer], self.host_part[layer]):
+            if part is not None:
+                out.append((at, part))
+                at += part.numel()
+        return out
+
     def read_pool(self, layer):
-        """A host numpy copy (fp16, flat) of the layer's pool as it is stored."""
+        """A host numpy copy (fp16, flat) of the layer's pool as it is stored
+        (HBM part first, then the host part)."""
         torch.cuda.synchronize(self.device)
-        return self.pools[layer].cpu().numpy().copy()
+        return np.concatenate([p.cpu().numpy() for _, p in self._parts(layer)])
 
     def read_rows(self, layer, row_offsets):
         """Rows of d fp16 numbers at the given element offsets -> [n][d] numpy."""
         torch.cuda.synchronize(self.device)
-        pool = self.pools[layer]
         idx = torch.as_tensor(np.asarray(row_offsets, dtype=np.int64))
         cols = torch.arange(self.d, dtype=torch.int64)
-        flat = (idx[:, None] + cols[None, :]).reshape(-1)
-        if pool.is_cuda:
-            rows = pool[flat.to(self.device)].cpu()
-        else:
-            rows = pool[flat]
-        return rows.numpy().reshape(len(row_offsets), self.d).copy()
+        out = torch.empty((len(row_offsets), self.d), dtype=torch.float16)
+        for first, part in self._parts(layer):
+            sel = (idx >= first) & (idx < first + part.numel())
+            if not bool(sel.any()):
+                continue
+            flat = ((idx[sel] - first)[:, None] + cols[None, :]).reshape(-1)
+            rows = part[flat.to(self.device)].cpu() if part.is_cuda else part[flat]
+            out[sel] = rows.reshape(-1, self.d)
+        return out.numpy().copy()
 
     # ---- one decode step ---------------------------------------------------------
     def step(self, q, k_new, v_new, out):
@@ -174,7 +213,7 @@ class Stack:
 
     def close(self):
         self.ctx.close()
-        self.pools = []
+        self.pools, self.dev_part, self.host_part = [], [], []
         for p in self._pinned:
             p.free()
         self._pinned = []

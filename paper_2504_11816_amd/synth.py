@@ -106,6 +106,65 @@ def identity_block_table(ctx_caps, T, max_blocks_per_seq=None):
     return table
 
 
+def classed_block_table(ctx_caps, T, resident_blocks, host_blocks, n_host_used, policy, seed,
+                        max_blocks_per_seq=None):
+    """A block table for a pool whose ids below resident_blocks are in HBM and whose
+    other ids (host_blocks of them) are in host memory.  n_host_used of the blocks the
+    sequences need are taken from the host part, the rest from the HBM part:
+      "prefix"    every sequence keeps its oldest blocks on the host, an even share of
+                  n_host_used each (by a running quota), handed out in id order; its
+                  newest blocks are in HBM, shuffled;
+      "sequence"  whole sequences go to the host, in order, while n_host_used lasts
+                  (the sequence at the boundary is cut like "prefix");
+      "scatter"   a random choice of n_host_used block positions over all sequences,
+                  ids shuffled in both parts (worst case: many short stretches).
+    Returns int32 [B][max_blocks]; unused entries are -1."""
+    need = [blocks_needed(c, T) for c in ctx_caps]
+    total = sum(need)
+    if max_blocks_per_seq is None:
+        max_blocks_per_seq = max(need)
+    if not (0 <= n_host_used <= min(total, host_blocks)) or total - n_host_used > resident_blocks:
+        raise ValueError("the requested split does not fit the two parts of the pool")
+    rng = np.random.Generator(np.random.PCG64(seed))
+    on_host = [np.zeros(k, dtype=bool) for k in need]
+    if policy == "prefix":
+        cum = 0
+        for b, k in enumerate(need):
+            share = ((cum + k) * n_host_used) // total - (cum * n_host_used) // total if total else 0
+            on_host[b][:share] = True
+            cum += k
+    elif policy == "sequence":
+        left = n_host_used
+        for b, k in enumerate(need):
+            take = min(k, left)
+            on_host[b][:take] = True
+            left -= take
+    elif policy == "scatter":
+        flat = np.zeros(total, dtype=bool)
+        flat[rng.choice(total, size=n_host_used, replace=False)] = True
+        at = 0
+        for b, k in enumerate(need):
+            on_host[b] = flat[at:at + k]
+            at += k
+    else:
+        raise ValueError(f"unknown policy {policy}")
+    res_ids = rng.permutation(resident_blocks).astype(np.int64)
+    host_ids = np.arange(host_blocks, dtype=np.int64)
+    if policy == "scatter":
+        host_ids = rng.permutation(host_blocks).astype(np.int64)
+    table = np.full((len(ctx_caps), max_blocks_per_seq), -1, dtype=np.int32)
+    r_at = h_at = 0
+    for b, k in enumerate(need):
+        for i in range(k):
+            if on_host[b][i]:
+                table[b, i] = resident_blocks + host_ids[h_at]
+                h_at += 1
+            else:
+                table[b, i] = res_ids[r_at]
+                r_at += 1
+    return table
+
+
 # The five workload shapes.  "ctx" is the number of keys attended at the
 # first timed step (after that step's append); "steps" how many decode steps
 # the full workload runs; c_off as an exact fraction (numerator, denominator).

@@ -1,0 +1,208 @@
+"""GPU parity for block-granular offload: a share of every layer's blocks lives in
+pinned host memory and is streamed in chunks; the keys in HBM and every chunk are
+attended by launches of their own and merged.  Same bar as the other parity tests:
+outputs against the fp64 oracle within 2e-3 max abs / 1e-2 relative L2, integer
+work (work list, class boundaries, appended rows in both parts of the pool) bit-exact."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import kv_layout, offload_plan, worklist
+from paper_2504_11816_amd import binding, synth
+from paper_2504_11816_amd.harness import Stack
+
+from gpu_util import make_inputs, run_and_check
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def classed_stack(*, L, H, G, d, T, ctx_before, cap_tokens, c_off, chunk_blocks, policy, seed, n_staging=2,
+                  split_tokens=0, workspace_items=None, spare_resident=2, spare_host=3, out_dtype=0):
+    """A Stack in block-class mode: of the blocks the batch can grow into, the share c_off
+    (a Fraction) is taken from the host part of the pool by `policy`."""
+    ctx_before = np.asarray(ctx_before, dtype=np.int32)
+    B = len(ctx_before)
+    need = B * synth.blocks_needed(cap_tokens, T)
+    n_res, n_host = binding.okv_plan_block_split(need, c_off.numerator, c_off.denominator)
+    assert (n_res, n_host) == offload_plan.block_split(need, c_off)
+    R = n_res + spare_resident
+    host_blocks = n_host + (spare_host if n_host else 0)
+    st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=cap_tokens, blocks_per_layer=R + host_blocks,
+               n_staging=n_staging, resident_blocks=R, chunk_blocks=chunk_blocks, split_tokens=split_tokens,
+               workspace_items=workspace_items, out_dtype=out_dtype)
+    for l in range(L):
+        st.fill_pool(l, synth.stream_seed(seed, synth.TENSOR_POOL, l))
+    table = synth.classed_block_table([st.cap_tokens] * B, T, R, host_blocks, n_host, policy, seed + 1,
+                                      max_blocks_per_seq=st.max_blocks)
+    st.set_batch(ctx_before, table)
+    return st
+
+
+def poison_staging(st):
+    for s in st.staging:
+        if s is not None:
+            s.fill_(float("nan"))                 # a stale or missing copy poisons the output
+    torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("policy", ["prefix", "sequence", "scatter"])
+@pytest.mark.parametrize("c_off", [Fraction(0), Fraction(1, 3), Fraction(3, 5), Fraction(1)])
+def test_all_outputs_for_every_placement(policy, c_off):
+    say(f"classes policy={policy} c_off={c_off}")
+    ctx = [0, 17, 200, 333, 64, 15]
+    st = classed_stack(L=2, H=8, G=2, d=64, T=16, ctx_before=ctx, cap_tokens=352, c_off=c_off, chunk_blocks=9,
+                       policy=policy, seed=101, workspace_items=6 * 24, split_tokens=64)
+    poison_staging(st)
+    run_and_check(st, n_steps=3, seed=103)
+    assert st.ctx.okv_get_ctx_lens().tolist() == [c + 3 for c in ctx]
+    st.close()
+
+
+@pytest.mark.parametrize("n_staging", [1, 2, 3, 4])
+@pytest.mark.parametrize("d,H,G", [(128, 4, 4), (64, 8, 1)])
+def test_staging_depths_and_head_groupings(n_staging, d, H, G):
+    say(f"classes staging={n_staging} d={d} H={H} G={G}")
+    ctx = [100, 257, 31, 480]
+    st = classed_stack(L=3, H=H, G=G, d=d, T=16, ctx_before=ctx, cap_tokens=512, c_off=Fraction(1, 2),
+                       chunk_blocks=16, policy="prefix", seed=111, n_staging=n_staging)
+    poison_staging(st)
+    run_and_check(st, n_steps=3, seed=113)
+    st.close()
+
+
+def test_large_blocks_and_a_single_chunk():
+    say("classes T=64, one chunk")
+    ctx = [130, 700, 64, 1]
+    st = classed_stack(L=2, H=4, G=2, d=128, T=64, ctx_before=ctx, cap_tokens=768, c_off=Fraction(2, 3),
+                       chunk_blocks=1000, policy="sequence", seed=121, out_dtype=1)
+    poison_staging(st)
+    run_and_check(st, n_steps=2, seed=123)
+    st.close()
+
+
+def test_placement_does_not_change_the_result_beyond_rounding():
+    # the same K/V bytes under three placements: outputs agree with the oracle each time, and with
+    # each other up to the order of the fp32 sums
+    say("classes: placements agree")
+    ctx = [90, 300, 511]
+    outs = {}
+    for policy, c_off in (("prefix", Fraction(0)), ("prefix", Fraction(1, 2)), ("scatter", Fraction(1, 2))):
+        st = classed_stack(L=1, H=4, G=4, d=64, T=16, ctx_before=ctx, cap_tokens=528, c_off=c_off, chunk_blocks=8,
+                           policy=policy, seed=131, workspace_items=3 * 40, out_dtype=1)
+        # overwrite the pool so that every placement holds the same rows at the same positions
+        layout = st.layout()
+        pool = st.read_pool(0)
+        for b, n in enumerate(ctx):
+            for kv in (0, 1):
+                for g in range(4):
+                    rows = synth.randn_f16_numpy((n, 64), synth.stream_seed(133, 10 + kv, g, b))
+                    for i in range(n):
+                        at = kv_layout.token_row_offset(layout, b, kv, g, i)
+                        pool[at:at + 64] = rows[i]
+        flat = torch.from_numpy(pool)
+        at = 0
+        for part in (st.dev_part[0], st.host_part[0]):
+            if part is not None:
+                part.copy_(flat[at:at + part.numel()])
+                at += part.numel()
+        torch.cuda.synchronize()
+        outs[(policy, c_off)] = run_and_check(st, n_steps=1, seed=135)[0][0]
+        st.close()
+    base = outs[("prefix", Fraction(0))]
+    for key, o in outs.items():
+        assert np.abs(o - base).max() < 2e-5, key
+
+
+def test_worklist_by_class_matches_oracle_bit_for_bit():
+    say("classes: work list")
+    ctx = synth.ragged_ctx_lens(23, 1, 700, 141)
+    for policy in ("prefix", "sequence", "scatter"):
+        st = classed_stack(L=1, H=2, G=2, d=64, T=16, ctx_before=ctx, cap_tokens=720, c_off=Fraction(2, 5),
+                           chunk_blocks=37, policy=policy, seed=143, workspace_items=23 * 45, split_tokens=16)
+        R, CB = st.resident_blocks, st.chunk_blocks
+        for split in (16, 100, 512, 4096):
+            st.ctx.okv_set_split_tokens(split)
+            first_h = st.ctx.okv_worklist_classes(from_device=False)
+            first_d = st.ctx.okv_worklist_classes(from_device=True)
+            n_cls = len(first_h) - 1
+            want = worklist.expected_items_by_class(ctx, st.block_table, 16, R, CB, split, n_cls)
+            flat = [it for items in want for it in items]
+            bounds = np.cumsum([0] + [len(items) for items in want])
+            np.testing.assert_array_equal(first_h, bounds)
+            np.testing.assert_array_equal(first_d, bounds)
+            np.testing.assert_array_equal(st.ctx.okv_worklist(from_device=False), np.array(flat, dtype=np.int32))
+            np.testing.assert_array_equal(st.ctx.okv_worklist(from_device=True), np.array(flat, dtype=np.int32))
+            assert worklist.check_tiling(flat, ctx)
+        # one step later every sequence is a token longer on both sides
+        st.ctx.okv_set_split_tokens(100)
+        q, k, v, out = make_inputs(st, 145, 0, st.device)
+        st.step(q, k, v, out)
+        want = worklist.expected_items_by_class(ctx + 1, st.block_table, 16, R, CB, 100, n_cls)
+        flat = np.array([it for items in want for it in items], dtype=np.int32)
+        np.testing.assert_array_equal(st.ctx.okv_worklist(from_device=True), flat)
+        np.testing.assert_array_equal(st.ctx.okv_worklist(from_device=False), flat)
+        st.close()
+
+
+@pytest.mark.parametrize("policy", ["prefix", "scatter"])
+def test_appended_rows_land_in_the_right_part_bit_exact(policy):
+    say(f"classes: append {policy}")
+    ctx = np.array([0, 15, 16, 31, 47, 60], dtype=np.int32)
+    st = classed_stack(L=2, H=4, G=2, d=64, T=16, ctx_before=ctx, cap_tokens=80, c_off=Fraction(1, 2), chunk_blocks=4,
+                       policy=policy, seed=151, workspace_items=6 * 8)
+    want = [st.read_pool(l) for l in range(2)]
+    n = ctx.copy()
+    for step in range(6):
+        q, k, v, out = make_inputs(st, 153, step, st.device)
+        st.step(q, k, v, out)
+        st.synchronize()
+        n += 1
+        for l in range(2):
+            kv_layout.append_scatter(want[l], st.layout(), n, k[l].cpu().numpy(), v[l].cpu().numpy())
+    for l in range(2):
+        np.testing.assert_array_equal(st.read_pool(l).view(np.uint16), want[l].view(np.uint16))
+    st.close()
+
+
+def test_class_mode_error_paths():
+    say("classes: errors")
+    ws = torch.empty(1 << 22, dtype=torch.uint8, device="cuda")
+    dev = torch.empty(1 << 20, dtype=torch.float16, device="cuda")
+    kw = dict(n_layers=1, n_q_heads=4, n_kv_heads=2, head_dim=64, block_tokens=16, max_batch=2,
+              max_blocks_per_seq=8, blocks_per_layer=32, workspace=ws, workspace_bytes=1 << 22,
+              resident_blocks=16, chunk_blocks=4)
+    with pytest.raises(binding.OkvError) as e:                  # blocks on the host but no host pool
+        binding.Context(dev_pool=[dev], host_pool=[None], **kw)
+    assert e.value.code == binding.OKV_EINVAL
+    # a scattered table cuts the batch into more items than the default workspace holds
+    ctx = [300] * 4
+    st = classed_stack(L=1, H=2, G=2, d=64, T=16, ctx_before=ctx, cap_tokens=320, c_off=Fraction(1, 2), chunk_blocks=1000,
+                       policy="prefix", seed=161, split_tokens=4096)
+    scattered = synth.classed_block_table([320] * 4, 16, st.resident_blocks, st.blocks_per_layer - st.resident_blocks,
+                                          40, "scatter", 163, max_blocks_per_seq=st.max_blocks)
+    with pytest.raises(binding.OkvError) as e:
+        st.set_batch(ctx, scattered)
+    assert e.value.code == binding.OKV_ENOSPC
+    with pytest.raises(binding.OkvError) as e:                  # and the context refuses to step without a batch
+        st.ctx.okv_step_begin()
+    assert e.value.code == binding.OKV_ESTATE
+    st.close()
+
+
+def test_full_size_context_4096_three_fifths_of_the_blocks_on_the_host_sampled():
+    # the large offline shape per layer (32 heads x 128, context 4096, 16-token blocks) at batch 32,
+    # C_off = 3/5 of every layer's blocks, streamed in 256 MiB chunks through two staging buffers
+    say("classes: full size")
+    B, L = 32, 3
+    st = classed_stack(L=L, H=32, G=32, d=128, T=16, ctx_before=[4094] * B, cap_tokens=4112, c_off=Fraction(3, 5),
+                       chunk_blocks=1024, policy="prefix", seed=171)
+    assert st.staging_bytes == 256 << 20
+    poison_staging(st)
+    run_and_check(st, n_steps=2, seed=173, pairs=[(0, 0), (31, 31), (7, 16), (20, 5)])
+    st.close()

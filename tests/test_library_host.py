@@ -73,7 +73,7 @@ def test_plan_from_bytes_matches_oracle():
 
 @pytest.mark.parametrize("on_host", [[0, 1, 0, 1], [1, 1, 1], [0, 0, 1], [1], [0, 0], [1, 0, 1, 1, 0, 1],
                                      [0, 1] * 16, [1] * 32])
-@pytest.mark.parametrize("n_staging", [1, 2])
+@pytest.mark.parametrize("n_staging", [1, 2, 4])
 def test_schedule_trace_replays_without_hazard(on_host, n_staging):
     trace = binding.okv_schedule_trace(on_host, n_staging, 5)
     for seed in range(6):
@@ -84,11 +84,30 @@ def test_schedule_trace_replays_without_hazard(on_host, n_staging):
     if k:
         depth = min(n_staging, k)
         assert len(copies) == 5 * k + depth            # every consumption refills, `depth` run ahead
-        assert [c[4] for c in copies] == list(range(len(copies)))
+        assert [c[5] for c in copies] == list(range(len(copies)))
         hl = [l for l, v in enumerate(on_host) if v]
-        assert all(c[2] == hl[c[4] % k] and c[3] == c[4] % depth for c in copies)
+        assert all(c[2] == hl[c[5] % k] and c[3] == 0 and c[4] == c[5] % depth for c in copies)
     else:
         assert not copies
+
+
+@pytest.mark.parametrize("chunks,resident", [([3, 3, 3], [1, 1, 1]), ([2, 2], [0, 0]), ([1, 4, 0, 2], [1, 0, 1, 1]),
+                                             ([5], [1]), ([8] * 32, [1] * 32), ([1], [1])])
+@pytest.mark.parametrize("n_staging", [1, 2, 3, 4])
+def test_chunked_schedule_trace_replays_without_hazard(chunks, resident, n_staging):
+    n_steps = 4
+    trace = binding.okv_schedule_trace(chunks, n_staging, n_steps, has_resident=resident)
+    for seed in range(4):
+        for cs, ks in ((1.0, 1.0), (25.0, 0.04), (0.04, 25.0)):
+            pipeline_sim.replay(trace, chunks, resident, seed=seed, copy_scale=cs, compute_scale=ks)
+    k = sum(chunks)
+    depth = min(n_staging, k)
+    copies = [op for op in trace if op[0] == pipeline_sim.COPY]
+    assert len(copies) == n_steps * k + depth
+    units = [(l, c) for l in range(len(chunks)) for c in range(chunks[l])]
+    assert all((c[2], c[3]) == units[c[5] % k] and c[4] == c[5] % depth for c in copies)
+    attn = [op for op in trace if op[0] == pipeline_sim.ATTN]
+    assert len(attn) == n_steps * (k + sum(resident))
 
 
 def test_schedule_keeps_the_link_busy_when_copies_dominate():
@@ -96,12 +115,31 @@ def test_schedule_keeps_the_link_busy_when_copies_dominate():
     trace = binding.okv_schedule_trace(on_host, 2, 6)
     r = pipeline_sim.replay(trace, on_host, seed=0, copy_scale=60.0, compute_scale=0.05)
     assert r["copy_busy"] / r["copy_span"] > 0.99
+    chunks = [6] * 8
+    trace = binding.okv_schedule_trace(chunks, 2, 6, has_resident=[1] * 8)
+    r = pipeline_sim.replay(trace, chunks, [1] * 8, seed=0, copy_scale=60.0, compute_scale=0.05)
+    assert r["copy_busy"] / r["copy_span"] > 0.99
 
 
 def test_schedule_trace_argument_errors():
     with pytest.raises(binding.OkvError):
         binding.okv_schedule_trace([0, 1], 0, 2)          # host layer but no staging buffer
     assert binding.okv_schedule_trace([0, 0], 0, 2)       # fine without host layers
+    with pytest.raises(binding.OkvError):
+        binding.okv_schedule_trace([0, -1], 2, 2)
+    with pytest.raises(binding.OkvError):
+        binding.okv_schedule_trace([0, 2], 2, 2, has_resident=[0, 0])   # layer 0 would hold nothing
+
+
+def test_block_split_matches_oracle():
+    for n in list(range(0, 40)) + [1000, 12288, (1 << 31) - 1]:
+        for den in (1, 2, 3, 7, 10, 64):
+            for num in range(0, den + 1):
+                want = offload_plan.block_split(n, Fraction(num, den))
+                assert binding.okv_plan_block_split(n, num, den) == want, (n, num, den)
+    for bad in ((-1, 1, 2), (4, -1, 2), (4, 3, 2), (4, 1, 0)):
+        with pytest.raises(binding.OkvError):
+            binding.okv_plan_block_split(*bad)
 
 
 def test_size_queries_and_shape_errors():
@@ -112,6 +150,19 @@ def test_size_queries_and_shape_errors():
                               max_batch=32, max_ctx=1024)
     assert binding.okv_layer_pool_bytes(cfg) == 512 << 20
     assert binding.okv_workspace_bytes(cfg) == 32 * 8 * 32 * 130 * 4
+    assert binding.okv_block_bytes(cfg) == 2 * 32 * 1024 * 128 * 2      # one sequence's slice
+    cfg = binding.make_config(n_layers=2, n_q_heads=8, n_kv_heads=8, head_dim=64, block_tokens=16,
+                              max_batch=4, max_blocks_per_seq=16, blocks_per_layer=64,
+                              resident_blocks=24, chunk_blocks=8)
+    assert binding.okv_block_bytes(cfg) == 2 * 8 * 16 * 64 * 2
+    # 16 blocks of 16 tokens at the default split of 512 -> 1 item, plus one per chunk of the host pool (5)
+    assert binding.okv_workspace_bytes(cfg) == 4 * (1 + 5) * 8 * 66 * 4
+    for bad in (dict(resident_blocks=65), dict(resident_blocks=-1), dict(chunk_blocks=-2), dict(block_tokens=0, max_ctx=256)):
+        kw = dict(n_layers=2, n_q_heads=8, n_kv_heads=8, head_dim=64, block_tokens=16, max_batch=4,
+                  max_blocks_per_seq=16, blocks_per_layer=64, resident_blocks=24, chunk_blocks=8)
+        kw.update(bad)
+        with pytest.raises(binding.OkvError):
+            binding.okv_block_bytes(binding.make_config(**kw))
     for bad in (dict(head_dim=96), dict(n_q_heads=48), dict(block_tokens=24), dict(max_ctx=1000),
                 dict(n_layers=0), dict(out_dtype=3)):
         kw = dict(n_layers=2, n_q_heads=8, n_kv_heads=8, head_dim=64, block_tokens=0, max_batch=4, max_ctx=256)
