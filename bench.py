@@ -6,7 +6,9 @@ the step's K/V rows followed by decode_attn over everything stored so far.
 The headline workload is the all-resident 32-layer stack (32 heads x 128,
 batch 32, prompt 512, 512 generated tokens, contiguous fp16 KV); an offloaded
 leg (paged KV, half of the layers streamed from pinned host memory) is timed
-after it and reported under "offload" in the same JSON line.
+after it and reported under "offload" in the same JSON line, and the same
+shape with the offloaded half taken block by block and streamed in chunks
+under "offload_blocks".
 
 Prints ONE JSON line.  `value` is decode tokens/s with all inputs already in
 HBM (resident layers) or pinned host memory (offloaded layers) when the timed
@@ -290,6 +292,72 @@ def run_offload(args):
     return res
 
 
+def run_offload_blocks(args):
+    """The same shape with the offload share taken block by block: in every layer the
+    oldest blocks of each sequence (C_off of the blocks the batch can grow into) are in
+    pinned host memory and streamed in chunks; the staging buffers hold one chunk each."""
+    import torch
+    from paper_2504_11816_amd import binding, synth
+    from paper_2504_11816_amd.harness import Stack
+    name = args.offload_workload
+    w = dict(synth.WORKLOADS[name])
+    L, H, G, d, T = w["L"], w["H"], w["G"], w["d"], w["T"]
+    B = args.offload_batch or OFFLOAD_DEFAULT_BATCH[name]
+    steps, warmup = args.offload_steps or (4 if name == "cfg3" else 2), 1
+    ctx0 = np.full(B, w["ctx"] - 1, dtype=np.int32)
+    cap = w["ctx"] + steps + warmup
+    need = B * synth.blocks_needed(cap, T)
+    n_res, n_host = binding.okv_plan_block_split(need, w["c_off"][0], w["c_off"][1])
+    shape = binding.make_config(n_layers=L, n_q_heads=H, n_kv_heads=G, head_dim=d, block_tokens=T, max_batch=B,
+                                max_blocks_per_seq=synth.blocks_needed(cap, T), blocks_per_layer=need)
+    block_bytes = binding.okv_block_bytes(shape)
+    chunk_blocks = max(1, (args.chunk_mib << 20) // block_bytes)
+    log(f"[bench] block-granular leg {name}: B={B} ctx={w['ctx']} T={T} host blocks {n_host}/{need} per layer, "
+        f"chunks of {chunk_blocks} blocks ({chunk_blocks * block_bytes / 2 ** 20:.0f} MiB), {args.staging} staging buffers")
+    st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=cap, out_dtype=0, n_staging=args.staging,
+               blocks_per_layer=need, resident_blocks=n_res, chunk_blocks=chunk_blocks)
+    # link rate first (it overwrites the start of layer 0's HBM part, which is filled afterwards)
+    probe_bytes = min(st.dev_part[0].numel() * 2, st.host_part[0].numel() * 2, 2 << 30)
+    link = binding.okv_measure_h2d(st.dev_part[0], st.host_part[0], probe_bytes, 10, st.h2d_stream.cuda_stream)
+    log(f"[bench] host-to-device link: {link:.1f} GB/s ({probe_bytes / 2 ** 20:.0f} MiB copies)")
+    for l in range(L):
+        st.fill_pool(l, synth.stream_seed(args.seed, synth.TENSOR_POOL, l))
+    table = synth.classed_block_table([st.cap_tokens] * B, T, n_res, n_host, n_host, args.placement, args.seed + 1,
+                                      max_blocks_per_seq=st.max_blocks)
+    inputs = fixed_inputs(st, args.seed)
+    dt = timed_steps(st, ctx0, table, inputs, steps, warmup)
+    # what crosses the link per step: every host block of every layer (all of them hold keys:
+    # the oldest blocks of a sequence are full)
+    host_tokens = int(((table >= n_res).sum(axis=1) * T).sum())
+    assert all(int((table[b] >= n_res).sum()) * T <= int(ctx0[b]) for b in range(B)) or args.placement != "prefix"
+    link_bytes = host_tokens * 2 * G * d * 2 * L * steps
+    kv_bytes = kv_bytes_of_steps(ctx0, steps, G, d, L)
+    k_s, k_n = kernel_time(st, ctx0, table, inputs, 1)
+    st.set_batch(ctx0, table)
+    copy_ms = st.ctx.okv_time_copies()
+    res = {
+        "workload": name, "placement": args.placement, "B": B, "ctx": w["ctx"], "layers": L, "steps": steps,
+        "host_blocks_per_layer": int(n_host), "blocks_per_layer": int(need),
+        "host_share_of_keys": host_tokens / float((ctx0 + 1).sum()),
+        "chunk_mib": chunk_blocks * block_bytes / 2 ** 20, "copies_per_step": len(st.ctx_units()) * L,
+        "tokens_per_s": B * steps / dt, "ms_per_step": dt / steps * 1e3, "kv_gbps": kv_bytes / dt / 1e9,
+        "link_gbps_measured": link, "link_gbps_achieved": link_bytes / dt / 1e9,
+        "link_frac": link_bytes / dt / 1e9 / link,
+        "attn_kernel_ms_per_step": k_s * 1e3, "attn_launches_per_step": k_n,
+        "copy_only_ms_per_step": copy_ms, "step_minus_copies_ms": dt / steps * 1e3 - copy_ms,
+        "pinned_gib": L * st.host_part[0].numel() * 2 / 2 ** 30,
+        "staging_buffers": args.staging, "staging_gib": args.staging * st.staging_bytes / 2 ** 30,
+        "split_tokens": st.ctx.okv_get_split_tokens(),
+    }
+    log(f"[bench] block-granular leg {name}: {res['ms_per_step']:.1f} ms/step, link {res['link_gbps_achieved']:.1f} GB/s "
+        f"= {100 * res['link_frac']:.1f}% of measured; copies alone {copy_ms:.1f} ms; attention alone "
+        f"{res['attn_kernel_ms_per_step']:.1f} ms/step in {k_n} launches; staging {res['staging_gib']:.2f} GiB")
+    st.close()
+    del st
+    torch.cuda.empty_cache()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -307,6 +375,10 @@ def main():
     ap.add_argument("--offload-steps", type=int, default=0)
     ap.add_argument("--offload-batch", type=int, default=0)
     ap.add_argument("--staging", type=int, default=2, help="staging buffers for host layers (1..4)")
+    ap.add_argument("--no-blocks", action="store_true", help="skip the block-granular offloaded leg")
+    ap.add_argument("--chunk-mib", type=int, default=256, help="block-granular leg: size of a streamed chunk")
+    ap.add_argument("--placement", default="prefix", choices=["prefix", "sequence", "scatter"],
+                    help="block-granular leg: which blocks of a sequence live on the host")
     ap.add_argument("--probe", action="store_true",
                     help="also run the plain copy / read kernels on 1 GiB (the yardstick for HBM counters)")
     args = ap.parse_args()
@@ -318,6 +390,7 @@ def main():
     res, cpu = run_resident(args)
     probe = run_probe() if args.probe else None
     off = None if args.no_offload else run_offload(args)
+    off_blocks = None if (args.no_offload or args.no_blocks) else run_offload_blocks(args)
     line = {
         "metric": "decode_attn_tokens_per_s", "value": res["tokens_per_s"], "unit": "tokens/s",
         "n_gpus": 1, "steps": res["steps"], "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
@@ -335,6 +408,7 @@ def main():
                      "launches": res["kernel_launches"], "bytes_per_launch": res["kv_bytes_per_launch"]},
         "cpu_baseline": cpu,
         "offload": off,
+        "offload_blocks": off_blocks,
     }
     if probe:
         line["probe"] = probe

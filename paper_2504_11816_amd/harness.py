@@ -208,6 +208,12 @@ class Stack:
         if self.ctx_lens is not None:
             self.ctx_lens += 1
 
+    def ctx_units(self):
+        """The chunks of the host pool that hold blocks of the current batch (block-class
+        mode): each is copied once per layer and step."""
+        host_ids = self.block_table[self.block_table >= self.resident_blocks] - self.resident_blocks
+        return sorted(set((host_ids // self.chunk_blocks).tolist()))
+
     def synchronize(self):
         self.ctx.okv_synchronize()
 
