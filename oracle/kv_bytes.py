@@ -54,6 +54,24 @@ def t_trans_decode(c_off, L_in, L_out, h1, BS, bw_cpu_to_gpu, prec=2):
     return (Fraction(c_off) * 2 * (L_in + 1) + L_out) * h1 * prec * BS / Fraction(bw_cpu_to_gpu)
 
 
+def t_trans_prefill(c_off, L_in, h1, BS, bw_gpu_to_cpu, prec=2):
+    """§IV-D, prefill-stage KV transfer time per layer, as printed:
+    C_off * 2 * (L_in + 1) * h1 * prec * BS / BW  -- the offloaded share of the
+    keys and values of the prompt and of the first generated token."""
+    return Fraction(c_off) * 2 * (L_in + 1) * h1 * prec * BS / Fraction(bw_gpu_to_cpu)
+
+
+def t_prefill(t_compute, t_trans):
+    """Eq. 5: in the prefill stage a layer's write-out overlaps the computation, so the
+    layer takes the longer of the two."""
+    return max(t_compute, t_trans)
+
+
+def kv_bytes_written(n_new, G, d, prec=2):
+    """Bytes of K and V that storing n_new[b] tokens per sequence adds to one layer."""
+    return sum(int(n) for n in n_new) * kv_bytes_per_token_per_layer(G, d, prec)
+
+
 def t_task(t_pre, t_dec, n_layers, L_out):
     """Eq. 4: prefill once per layer, decode per layer for L_out - 1 tokens
     (the first output token comes out of the prefill)."""

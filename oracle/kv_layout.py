@@ -78,3 +78,28 @@ def append_scatter(pool_flat, layout, ctx_lens_after, k_new, v_new):
             pool_flat[ok:ok + d] = k_new[b, g]
             pool_flat[ov:ov + d] = v_new[b, g]
     return pool_flat
+
+
+def bulk_append_scatter(pool_flat, layout, ctx_lens_before, n_new, k_rows, v_rows):
+    """What storing a whole prompt (or a run of new tokens) does to a layer's pool,
+    in place (paper §II-A: the prefill stage produces the keys and values of every
+    prompt token; §IV-D: with offloading they are then moved to host memory).
+
+    Sequence b holds ctx_lens_before[b] tokens and receives n_new[b] more, at
+    positions ctx_lens_before[b], ctx_lens_before[b] + 1, ...  k_rows, v_rows:
+    [sum(n_new)][G][d] arrays of the pool's dtype, the rows of sequence 0 first,
+    then those of sequence 1, ... each in position order (bit copy, no rounding).
+    """
+    G, d = layout["G"], layout["d"]
+    row = 0
+    for b in range(len(n_new)):
+        for i in range(int(n_new[b])):
+            pos = int(ctx_lens_before[b]) + i
+            for g in range(G):
+                ok = token_row_offset(layout, b, 0, g, pos)
+                ov = token_row_offset(layout, b, 1, g, pos)
+                pool_flat[ok:ok + d] = k_rows[row, g]
+                pool_flat[ov:ov + d] = v_rows[row, g]
+            row += 1
+    assert row == len(k_rows) == len(v_rows)
+    return pool_flat
