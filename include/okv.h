@@ -12,6 +12,7 @@
  *                     (okv_plan_block_split: which share of every layer's blocks)
  *   kv_append         store this step's K/V rows of one layer
  *   decode_attn       softmax(q K^T / sqrt(d)) V of one layer for a batch
+ *   kv_append_bulk    store a whole prompt's K/V rows of one layer (prefill side)
  *
  * plus the small amount of state around them (batch description, step
  * bookkeeping, the copy pipeline for host layers).
@@ -242,7 +243,49 @@ int kv_append(okv_ctx *ctx, int32_t layer, const void *k_new, const void *v_new)
  * enqueueing the next copy each time), then merges. */
 int decode_attn(okv_ctx *ctx, int32_t layer, const void *q, void *out);
 
-/* Blocks until everything enqueued on both streams has finished. */
+/* ---- storing prompts (the prefill side) ---------------------------------------------
+ *
+ * The prefill stage produces the keys and values of every prompt token, layer by
+ * layer; with offloading, a layer's share for the host is moved there while the next
+ * layer computes, so that a layer costs the longer of the two (paper §II-A, §IV-D
+ * T_pre = max(compute, T_trans^p)).  The computation itself is the caller's; these
+ * calls store its K/V output:
+ *
+ *   okv_prefill_begin(n_new)              sequence b will receive n_new[b] tokens
+ *   for l = 0 .. L-1:  kv_append_bulk(l, k_rows, v_rows)
+ *                      ... okv_prefill_release(l) before k_rows / v_rows of l are reused
+ *   okv_prefill_end()                     lengths grow by n_new; decode steps may follow
+ */
+
+/* Opens a prefill.  n_new: HOST int32 [B], tokens to add per sequence (>= 0), at
+ * positions ctx_len[b] .. ctx_len[b] + n_new[b] - 1.  Synchronous (waits for all
+ * streams, uploads a small tile list).  OKV_ENOSPC if a sequence would outgrow its
+ * capacity or reach an unallocated block; OKV_ESTATE inside a step or a prefill. */
+int okv_prefill_begin(okv_ctx *ctx, const int32_t *n_new);
+
+/* Stores the new rows of `layer` (layers in order 0 .. L-1, once each).
+ *   k_rows, v_rows  DEVICE fp16 [sum(n_new)][G][d]: the rows of sequence 0 first, then
+ *                   those of sequence 1, ..., each in position order (token-major, as
+ *                   a projection writes them).
+ * Rows whose block is in HBM are stored by a kernel on the compute stream.  Rows whose
+ * block (or whole layer) is on the host are written straight into the pinned host
+ * pool by a kernel on a stream of the library's own, which first waits for the work
+ * enqueued so far on the compute stream (the producer of k_rows / v_rows); it runs
+ * beside whatever the caller enqueues next.  k_rows / v_rows must stay untouched until
+ * that kernel has finished: see okv_prefill_release. */
+int kv_append_bulk(okv_ctx *ctx, int32_t layer, const void *k_rows, const void *v_rows);
+
+/* Makes the compute stream wait until the rows given to kv_append_bulk(layer) have been
+ * stored, so that work enqueued on the compute stream afterwards may overwrite
+ * k_rows / v_rows of that layer.  Returns at once (no host wait). */
+int okv_prefill_release(okv_ctx *ctx, int32_t layer);
+
+/* Closes the prefill: OKV_ESTATE unless every layer was stored.  Waits for the stores,
+ * adds n_new to the sequence lengths, rebuilds the work list and restarts the copy
+ * pipeline.  Synchronous. */
+int okv_prefill_end(okv_ctx *ctx);
+
+/* Blocks until everything enqueued on the library's streams has finished. */
 int okv_synchronize(okv_ctx *ctx);
 
 /* ---- introspection used by tests and the benchmark -------------------------------- */
@@ -289,6 +332,10 @@ int okv_profile_read(okv_ctx *ctx, double *attn_ms, int64_t *attn_launches);
  * pinned HOST memory `src` to DEVICE memory `dst` on `stream`, each timed with HIP
  * events; *gbps_median receives the median in GB/s (1e9 bytes).  Synchronous. */
 int okv_measure_h2d(void *dst, const void *src, int64_t bytes, int32_t reps, void *stream,
+                    double *gbps_median);
+
+/* The same for the other direction: DEVICE `src` to pinned HOST `dst`. */
+int okv_measure_d2h(void *dst, const void *src, int64_t bytes, int32_t reps, void *stream,
                     double *gbps_median);
 
 /* The copies of one decode step alone: every host layer's pool (every streamed chunk of

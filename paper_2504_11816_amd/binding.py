@@ -20,7 +20,8 @@ EXPORTS = [
     "okv_plan_block_split", "okv_schedule_trace", "okv_create", "okv_destroy", "okv_last_error", "okv_set_batch",
     "okv_step_begin", "okv_step_end", "kv_append", "decode_attn", "okv_synchronize",
     "okv_set_split_tokens", "okv_get_split_tokens", "okv_get_ctx_lens", "okv_worklist",
-    "okv_worklist_classes",
+    "okv_worklist_classes", "okv_prefill_begin", "kv_append_bulk", "okv_prefill_release", "okv_prefill_end",
+    "okv_measure_d2h",
     "okv_profile_enable", "okv_profile_read", "okv_measure_h2d", "okv_time_copies", "okv_probe_copy",
     "okv_probe_read",
 ]
@@ -85,6 +86,11 @@ def lib():
             "okv_profile_enable": (ctypes.c_int, [P, I32]),
             "okv_profile_read": (ctypes.c_int, [P, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(I64)]),
             "okv_measure_h2d": (ctypes.c_int, [P, P, I64, I32, P, ctypes.POINTER(ctypes.c_double)]),
+            "okv_measure_d2h": (ctypes.c_int, [P, P, I64, I32, P, ctypes.POINTER(ctypes.c_double)]),
+            "okv_prefill_begin": (ctypes.c_int, [P, P]),
+            "kv_append_bulk": (ctypes.c_int, [P, I32, P, P]),
+            "okv_prefill_release": (ctypes.c_int, [P, I32]),
+            "okv_prefill_end": (ctypes.c_int, [P]),
             "okv_time_copies": (ctypes.c_int, [P, ctypes.POINTER(ctypes.c_double)]),
             "okv_probe_copy": (ctypes.c_int, [P, P, I64, P]),
             "okv_probe_read": (ctypes.c_int, [P, I64, P, P]),
@@ -190,6 +196,12 @@ def okv_measure_h2d(dst, src, nbytes, reps, stream):
     return g.value
 
 
+def okv_measure_d2h(dst, src, nbytes, reps, stream):
+    g = ctypes.c_double(0)
+    _check(lib().okv_measure_d2h(_ptr(dst), _ptr(src), nbytes, reps, _ptr(stream), ctypes.byref(g)))
+    return g.value
+
+
 def okv_probe_copy(dst, src, nbytes, stream):
     _check(lib().okv_probe_copy(_ptr(dst), _ptr(src), nbytes, _ptr(stream)))
 
@@ -260,6 +272,21 @@ class Context:
 
     def decode_attn(self, layer, q, out):
         self._c(lib().decode_attn(self._h, layer, _ptr(q), _ptr(out)))
+
+    def okv_prefill_begin(self, n_new):
+        n_new = np.ascontiguousarray(n_new, dtype=np.int32)
+        if len(n_new) != self.B:
+            raise ValueError("n_new needs one entry per sequence")
+        self._c(lib().okv_prefill_begin(self._h, _ptr(n_new)))
+
+    def kv_append_bulk(self, layer, k_rows, v_rows):
+        self._c(lib().kv_append_bulk(self._h, layer, _ptr(k_rows), _ptr(v_rows)))
+
+    def okv_prefill_release(self, layer):
+        self._c(lib().okv_prefill_release(self._h, layer))
+
+    def okv_prefill_end(self):
+        self._c(lib().okv_prefill_end(self._h))
 
     def okv_synchronize(self):
         self._c(lib().okv_synchronize(self._h))

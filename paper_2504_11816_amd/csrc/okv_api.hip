@@ -32,6 +32,11 @@ constexpr int kEventRing = 8;            // > copies in flight (at most OKV_MAX_
 constexpr int32_t kMinAutoSplit = 128;   // smallest split size the library picks by itself
 constexpr int32_t kClassSplit = 512;     // split size with block classes unless the caller sets one
 constexpr int64_t kMaxClasses = 4096;
+// Workgroups of a bulk store that writes into host memory: the link, not the GPU, sets its
+// pace, so it is kept small enough to leave the compute units to whatever runs beside it.
+#ifndef OKV_HOST_WRITE_WORKGROUPS
+#define OKV_HOST_WRITE_WORKGROUPS 256
+#endif
 
 thread_local std::string g_error;        // failures that have no context to live in
 
@@ -74,6 +79,19 @@ struct okv_ctx {
   int32_t B = 0, split = 0, split_override = 0, n_items = 0;
   bool need_merge = false;
   int64_t copy_bytes = 0;
+
+  // bulk store of prompts (prefill side)
+  bool in_prefill = false;
+  int32_t prefill_next_layer = 0;
+  std::vector<int32_t> h_n_new;
+  int4 *d_tiles = nullptr;
+  int32_t *d_row_base = nullptr;
+  int64_t tiles_cap = 0;
+  int32_t n_tiles_hbm = 0, n_tiles_host = 0;       // d_tiles = [tiles stored into HBM][tiles stored into host memory]
+  hipStream_t d2h = nullptr;                         // library-owned stream of the stores into host memory
+  hipEvent_t rows_ready_ev = nullptr, prefill_done_ev = nullptr;
+  std::vector<hipEvent_t> stored_ev;                 // per layer: its rows have left the caller's buffers
+  std::vector<uint8_t> stored_set;
 
   bool batch_set = false, in_step = false, appended = false;
   const void *pending_k = nullptr, *pending_v = nullptr;   // rows of the current layer's kv_append
@@ -345,7 +363,13 @@ int exec_ops(okv_ctx *ctx, const std::vector<Op> &ops, const void *a0, const voi
 
 // Recomputes split size, item count and merge flag from the host lengths and
 // rebuilds the device work list (adding `inc` to every device length first).
-int rebuild_worklist(okv_ctx *ctx, int32_t inc) {
+int rebuild_worklist(okv_ctx *ctx, int32_t inc, bool upload_lens = false) {
+  if (upload_lens) {
+    // the device lengths are replaced by the host's (after a bulk store); h_ctx_lens is pageable
+    // memory, so the copy is over when the call returns, and the kernels below are enqueued after it
+    OKV_HIP(ctx, hipStreamSynchronize(ctx->compute));
+    OKV_HIP(ctx, hipMemcpy(ctx->d_ctx_lens, ctx->h_ctx_lens.data(), (size_t)ctx->B * sizeof(int32_t), hipMemcpyHostToDevice));
+  }
   if (ctx->by_class) {
     ctx->split = ctx->split_override ? ctx->split_override : ctx->cfg.split_tokens ? ctx->cfg.split_tokens : kClassSplit;
     std::vector<int32_t> per_seq(ctx->B, 0);
@@ -641,6 +665,16 @@ int okv_destroy(okv_ctx *ctx) {
   (void)hipFree(ctx->d_item_desc);
   (void)hipFree(ctx->d_queues);
   (void)hipFree(ctx->d_items_dump);
+  if (ctx->d2h) {
+    (void)hipStreamSynchronize(ctx->d2h);
+    (void)hipStreamDestroy(ctx->d2h);
+  }
+  if (ctx->rows_ready_ev) (void)hipEventDestroy(ctx->rows_ready_ev);
+  if (ctx->prefill_done_ev) (void)hipEventDestroy(ctx->prefill_done_ev);
+  for (hipEvent_t e : ctx->stored_ev)
+    if (e) (void)hipEventDestroy(e);
+  (void)hipFree(ctx->d_tiles);
+  (void)hipFree(ctx->d_row_base);
   (void)hipFree(ctx->d_runs);
   (void)hipFree(ctx->d_pair_first);
   (void)hipFree(ctx->d_seq_total);
@@ -662,13 +696,14 @@ int okv_synchronize(okv_ctx *ctx) {
   if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
   if (ctx->any_host) OKV_HIP(ctx, hipStreamSynchronize(ctx->h2d));
   if (ctx->h2d_odd) OKV_HIP(ctx, hipStreamSynchronize(ctx->h2d_odd));
+  if (ctx->d2h) OKV_HIP(ctx, hipStreamSynchronize(ctx->d2h));
   OKV_HIP(ctx, hipStreamSynchronize(ctx->compute));
   return OKV_OK;
 }
 
 int okv_set_batch(okv_ctx *ctx, int32_t B, const int32_t *block_table, const int32_t *ctx_lens) {
   if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
-  if (ctx->in_step) return fail(ctx, OKV_ESTATE, "okv_set_batch inside a step");
+  if (ctx->in_step || ctx->in_prefill) return fail(ctx, OKV_ESTATE, "okv_set_batch inside a step or a prefill");
   if (B < 1 || B > ctx->cfg.max_batch) return fail(ctx, OKV_EINVAL, "B = %d outside [1, %d]", B, ctx->cfg.max_batch);
   if (!ctx_lens) return fail(ctx, OKV_EINVAL, "ctx_lens is NULL");
   const okv::PoolShape &s = ctx->shape;
@@ -760,7 +795,7 @@ int okv_set_batch(okv_ctx *ctx, int32_t B, const int32_t *block_table, const int
 int okv_step_begin(okv_ctx *ctx) {
   if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
   if (!ctx->batch_set) return fail(ctx, OKV_ESTATE, "okv_step_begin before okv_set_batch");
-  if (ctx->in_step) return fail(ctx, OKV_ESTATE, "okv_step_begin inside a step");
+  if (ctx->in_step || ctx->in_prefill) return fail(ctx, OKV_ESTATE, "okv_step_begin inside a step or a prefill");
   const okv::PoolShape &s = ctx->shape;
   for (int32_t b = 0; b < ctx->B; ++b) {
     int32_t n = ctx->h_ctx_lens[b];
@@ -827,6 +862,137 @@ int decode_attn(okv_ctx *ctx, int32_t layer, const void *q, void *out) {
   ctx->appended = false;
   ctx->next_layer = layer + 1;
   return OKV_OK;
+}
+
+// ---- bulk store of prompts ------------------------------------------------------------
+
+int okv_prefill_begin(okv_ctx *ctx, const int32_t *n_new) {
+  if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
+  if (!n_new) return fail(ctx, OKV_EINVAL, "n_new is NULL");
+  if (!ctx->batch_set) return fail(ctx, OKV_ESTATE, "okv_prefill_begin before okv_set_batch");
+  if (ctx->in_step || ctx->in_prefill) return fail(ctx, OKV_ESTATE, "okv_prefill_begin inside a step or a prefill");
+  const okv::PoolShape &s = ctx->shape;
+  const int32_t B = ctx->B;
+  for (int32_t b = 0; b < B; ++b) {
+    if (n_new[b] < 0) return fail(ctx, OKV_EINVAL, "n_new[%d] < 0", b);
+    const int64_t end = (int64_t)ctx->h_ctx_lens[b] + n_new[b];
+    if (end > ctx->cap_tokens) return fail(ctx, OKV_ENOSPC, "sequence %d would hold %lld tokens, capacity %d", b, (long long)end, ctx->cap_tokens);
+    if (s.paged && n_new[b] > 0)
+      for (int32_t i = ctx->h_ctx_lens[b] >> s.log2_T; i <= (int32_t)((end - 1) >> s.log2_T); ++i)
+        if (ctx->h_block_table[(size_t)b * s.max_blocks + i] < 0)
+          return fail(ctx, OKV_ENOSPC, "sequence %d has no block allocated for token %d", b, i << s.log2_T);
+  }
+  int rc = okv_synchronize(ctx);                        // a change of phase: nothing of a decode step is left in flight
+  if (rc) return rc;
+  // 16-position tiles that receive rows, those stored into HBM first, then those stored into host memory
+  std::vector<int4> hbm, host;
+  std::vector<int32_t> row_base(B);
+  int64_t row = 0;
+  for (int32_t b = 0; b < B; ++b) {
+    const int32_t lo = ctx->h_ctx_lens[b], hi = lo + n_new[b];
+    row_base[b] = (int32_t)(row - lo);
+    row += n_new[b];
+    for (int32_t t = lo >> 4; (t << 4) < hi; ++t) {
+      const int4 d = make_int4(b, t, std::max(lo, t << 4), std::min(hi, (t << 4) + 16));
+      bool to_host = false;
+      if (ctx->by_class) to_host = ctx->h_block_table[(size_t)b * s.max_blocks + ((t << 4) >> s.log2_T)] >= ctx->resident_blocks;
+      (to_host ? host : hbm).push_back(d);
+    }
+  }
+  if (row > 0x7fffffff) return fail(ctx, OKV_EINVAL, "too many new rows");
+  const int64_t n_tiles = (int64_t)hbm.size() + (int64_t)host.size();
+  if (n_tiles > ctx->tiles_cap) {
+    (void)hipFree(ctx->d_tiles);
+    ctx->d_tiles = nullptr;
+    ctx->tiles_cap = 0;
+    OKV_HIP(ctx, hipMalloc(&ctx->d_tiles, (size_t)n_tiles * sizeof(int4)));
+    ctx->tiles_cap = n_tiles;
+  }
+  if (!ctx->d_row_base) OKV_HIP(ctx, hipMalloc(&ctx->d_row_base, (size_t)ctx->cfg.max_batch * sizeof(int32_t)));
+  if (!hbm.empty()) OKV_HIP(ctx, hipMemcpy(ctx->d_tiles, hbm.data(), hbm.size() * sizeof(int4), hipMemcpyHostToDevice));
+  if (!host.empty())
+    OKV_HIP(ctx, hipMemcpy(ctx->d_tiles + hbm.size(), host.data(), host.size() * sizeof(int4), hipMemcpyHostToDevice));
+  OKV_HIP(ctx, hipMemcpy(ctx->d_row_base, row_base.data(), (size_t)B * sizeof(int32_t), hipMemcpyHostToDevice));
+  ctx->n_tiles_hbm = (int32_t)hbm.size();
+  ctx->n_tiles_host = (int32_t)host.size();
+  if (!ctx->d2h) {
+    OKV_HIP(ctx, hipStreamCreateWithFlags(&ctx->d2h, hipStreamNonBlocking));
+    OKV_HIP(ctx, hipEventCreateWithFlags(&ctx->rows_ready_ev, hipEventDisableTiming));
+    OKV_HIP(ctx, hipEventCreateWithFlags(&ctx->prefill_done_ev, hipEventDisableTiming));
+    ctx->stored_ev.assign(ctx->cfg.n_layers, nullptr);
+    for (int32_t l = 0; l < ctx->cfg.n_layers; ++l)
+      OKV_HIP(ctx, hipEventCreateWithFlags(&ctx->stored_ev[l], hipEventDisableTiming));
+  }
+  ctx->stored_set.assign(ctx->cfg.n_layers, 0);
+  ctx->h_n_new.assign(n_new, n_new + B);
+  ctx->in_prefill = true;
+  ctx->prefill_next_layer = 0;
+  return OKV_OK;
+}
+
+int kv_append_bulk(okv_ctx *ctx, int32_t layer, const void *k_rows, const void *v_rows) {
+  if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
+  if (!ctx->in_prefill) return fail(ctx, OKV_ESTATE, "kv_append_bulk outside a prefill");
+  if (layer < 0 || layer >= ctx->cfg.n_layers) return fail(ctx, OKV_EINVAL, "layer %d outside [0, %d)", layer, ctx->cfg.n_layers);
+  if (layer != ctx->prefill_next_layer) return fail(ctx, OKV_ESTATE, "kv_append_bulk(%d) out of order: expected layer %d", layer, ctx->prefill_next_layer);
+  if (!k_rows || !v_rows || !aligned16(k_rows) || !aligned16(v_rows)) return fail(ctx, OKV_EINVAL, "k_rows / v_rows NULL or not 16-byte aligned");
+  okv::BulkLaunch a;
+  a.shape = ctx->shape;
+  a.block_table = ctx->d_block_table;
+  a.row_base = ctx->d_row_base;
+  a.k_rows = k_rows;
+  a.v_rows = v_rows;
+  // the tiles stored into HBM, on the compute stream
+  const bool whole_layer_on_host = !ctx->by_class && ctx->host_pool[layer] != nullptr;
+  if (!whole_layer_on_host && ctx->n_tiles_hbm > 0) {
+    a.tiles = ctx->d_tiles;
+    a.n_tiles = ctx->n_tiles_hbm;
+    a.pool = ctx->dev_pool[layer];
+    a.id_base = 0;
+    a.max_workgroups = 0;
+    OKV_HIP(ctx, okv::launch_bulk_append(a, ctx->compute));
+  }
+  // the tiles stored into host memory, on the library's own stream once the rows are there
+  const int32_t first = whole_layer_on_host ? 0 : ctx->n_tiles_hbm;
+  const int32_t count = whole_layer_on_host ? ctx->n_tiles_hbm : ctx->n_tiles_host;
+  if (count > 0) {
+    OKV_HIP(ctx, hipEventRecord(ctx->rows_ready_ev, ctx->compute));
+    OKV_HIP(ctx, hipStreamWaitEvent(ctx->d2h, ctx->rows_ready_ev, 0));
+    a.tiles = ctx->d_tiles + first;
+    a.n_tiles = count;
+    a.pool = ctx->host_pool[layer];
+    a.id_base = ctx->by_class ? (int32_t)ctx->resident_blocks : 0;
+    a.max_workgroups = OKV_HOST_WRITE_WORKGROUPS;
+    OKV_HIP(ctx, okv::launch_bulk_append(a, ctx->d2h));
+    OKV_HIP(ctx, hipEventRecord(ctx->stored_ev[layer], ctx->d2h));
+    ctx->stored_set[layer] = 1;
+  }
+  ctx->prefill_next_layer = layer + 1;
+  return OKV_OK;
+}
+
+int okv_prefill_release(okv_ctx *ctx, int32_t layer) {
+  if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
+  if (!ctx->in_prefill) return fail(ctx, OKV_ESTATE, "okv_prefill_release outside a prefill");
+  if (layer < 0 || layer >= ctx->prefill_next_layer) return fail(ctx, OKV_EINVAL, "layer %d has not been stored in this prefill", layer);
+  if (ctx->stored_set[layer]) OKV_HIP(ctx, hipStreamWaitEvent(ctx->compute, ctx->stored_ev[layer], 0));
+  return OKV_OK;
+}
+
+int okv_prefill_end(okv_ctx *ctx) {
+  if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
+  if (!ctx->in_prefill) return fail(ctx, OKV_ESTATE, "okv_prefill_end outside a prefill");
+  if (ctx->prefill_next_layer != ctx->cfg.n_layers)
+    return fail(ctx, OKV_ESTATE, "okv_prefill_end after %d of %d layers", ctx->prefill_next_layer, ctx->cfg.n_layers);
+  // what follows (attention, copies of host pools) comes after every store of the prefill
+  OKV_HIP(ctx, hipEventRecord(ctx->prefill_done_ev, ctx->d2h));
+  OKV_HIP(ctx, hipStreamWaitEvent(ctx->compute, ctx->prefill_done_ev, 0));
+  if (ctx->h2d != ctx->compute) OKV_HIP(ctx, hipStreamWaitEvent(ctx->h2d, ctx->prefill_done_ev, 0));
+  if (ctx->h2d_odd) OKV_HIP(ctx, hipStreamWaitEvent(ctx->h2d_odd, ctx->prefill_done_ev, 0));
+  for (int32_t b = 0; b < ctx->B; ++b) ctx->h_ctx_lens[b] += ctx->h_n_new[b];
+  ctx->in_prefill = false;
+  reset_schedule(ctx);
+  return rebuild_worklist(ctx, 0, /*upload_lens=*/true);
 }
 
 int okv_set_split_tokens(okv_ctx *ctx, int32_t split_tokens) {
@@ -979,6 +1145,32 @@ int okv_measure_h2d(void *dst, const void *src, int64_t bytes, int32_t reps, voi
     float ms = 0;
     if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
     if (e != hipSuccess) rc = fail(nullptr, OKV_EHIP, "okv_measure_h2d: %s", hipGetErrorString(e));
+    else if (i > 0) rates.push_back((double)bytes / (ms * 1e-3) / 1e9);
+  }
+  (void)hipEventDestroy(e0);
+  (void)hipEventDestroy(e1);
+  if (rc) return rc;
+  std::sort(rates.begin(), rates.end());
+  *gbps_median = rates[rates.size() / 2];
+  return OKV_OK;
+}
+
+int okv_measure_d2h(void *dst, const void *src, int64_t bytes, int32_t reps, void *stream, double *gbps_median) {
+  if (!dst || !src || bytes < 1 || reps < 1 || !gbps_median) return fail(nullptr, OKV_EINVAL, "okv_measure_d2h: bad argument");
+  hipStream_t st = static_cast<hipStream_t>(stream);
+  hipEvent_t e0, e1;
+  OKV_HIP(nullptr, hipEventCreate(&e0));
+  OKV_HIP(nullptr, hipEventCreate(&e1));
+  std::vector<double> rates;
+  int rc = OKV_OK;
+  for (int32_t i = 0; i < reps + 1 && rc == OKV_OK; ++i) {            // the first copy is a warm-up
+    hipError_t e = hipEventRecord(e0, st);
+    if (e == hipSuccess) e = hipMemcpyAsync(dst, src, (size_t)bytes, hipMemcpyDeviceToHost, st);
+    if (e == hipSuccess) e = hipEventRecord(e1, st);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    float ms = 0;
+    if (e == hipSuccess) e = hipEventElapsedTime(&ms, e0, e1);
+    if (e != hipSuccess) rc = fail(nullptr, OKV_EHIP, "okv_measure_d2h: %s", hipGetErrorString(e));
     else if (i > 0) rates.push_back((double)bytes / (ms * 1e-3) / 1e9);
   }
   (void)hipEventDestroy(e0);

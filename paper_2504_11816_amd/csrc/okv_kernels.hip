@@ -648,6 +648,53 @@ __global__ __launch_bounds__(kStepThreads) void step_advance_classes_kernel(
   if (tid == kStepThreads - 1) chunk_prefix[P] = part[tid];
 }
 
+// Bulk store of new rows: one wavefront per (tile, K or V, KV head).  A tile's destination is
+// one contiguous run of 16 * D * 2 bytes of the pool; its source rows are D * 2 bytes each,
+// G * D * 2 bytes apart (token-major input, as a projection writes it).  Every lane moves 16
+// bytes per load; rows outside [first, last) of the tile are left alone.
+struct BulkArgs {
+  const uint16_t *k_rows, *v_rows;
+  uint16_t *pool;
+  const int32_t *block_table;
+  const int4 *tiles;
+  const int32_t *row_base;
+  int32_t G, log2_T, tcap, max_blocks, n_units, id_base;
+};
+
+template <int D, bool PAGED>
+__global__ __launch_bounds__(256) void bulk_append_kernel(const BulkArgs a) {
+  constexpr int LPR = D / 8, RPL = 64 / LPR, LPT = D / 32;
+  const int lane = threadIdx.x & 63;
+  const int row = lane / LPR, col = lane % LPR;
+  const int64_t slice = (int64_t)a.tcap * D;
+  const int n_waves = gridDim.x * 4;
+  for (int unit = blockIdx.x * 4 + (threadIdx.x >> 6); unit < a.n_units; unit += n_waves) {
+    const int t = unit / (2 * a.G);
+    const int rest = unit - t * 2 * a.G;
+    const int kv = rest / a.G, g = rest - kv * a.G;
+    const int4 tile = a.tiles[t];
+    const int b = tile.x, pos0 = tile.y << 4;
+    const int blk = PAGED ? a.block_table[(size_t)b * a.max_blocks + (pos0 >> a.log2_T)] - a.id_base : b;
+    const int slot0 = PAGED ? pos0 & (a.tcap - 1) : pos0;
+    const uint16_t *src = (kv ? a.v_rows : a.k_rows) + (size_t)g * D + col * 8;
+    uint16_t *dst = a.pool + ((int64_t)blk * 2 * a.G + (int64_t)kv * a.G + g) * slice + (int64_t)slot0 * D + col * 8;
+    const int64_t base_row = (int64_t)a.row_base[b] + pos0;
+    uint4 v[LPT];
+    bool ok[LPT];
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) {
+      const int r = row + j * RPL;
+      ok[j] = pos0 + r >= tile.z && pos0 + r < tile.w;
+      if (ok[j]) v[j] = *reinterpret_cast<const uint4 *>(src + (base_row + r) * a.G * D);
+    }
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) {
+      const int r = row + j * RPL;
+      if (ok[j]) *reinterpret_cast<uint4 *>(dst + (int64_t)r * D) = v[j];
+    }
+  }
+}
+
 __global__ void worklist_dump_kernel(BatchState bs, int32_t *items) {
   const int it = blockIdx.x * blockDim.x + threadIdx.x;
   if (it >= bs.n_items) return;
@@ -688,6 +735,40 @@ hipError_t launch_step_advance_classes(int32_t *ctx_lens, const int4 *runs, cons
                                        int32_t S, int32_t inc, hipStream_t stream) {
   hipLaunchKernelGGL(step_advance_classes_kernel, dim3(1), dim3(kStepThreads), 0, stream, ctx_lens, runs,
                      pair_first, chunk_prefix, item_desc, seq_total, queues, n_queues, B, n_cls, S, inc);
+  return hipGetLastError();
+}
+
+hipError_t launch_bulk_append(const BulkLaunch &a, hipStream_t stream) {
+  if (a.n_tiles <= 0) return hipSuccess;
+  const PoolShape &s = a.shape;
+  BulkArgs args;
+  args.k_rows = static_cast<const uint16_t *>(a.k_rows);
+  args.v_rows = static_cast<const uint16_t *>(a.v_rows);
+  args.pool = static_cast<uint16_t *>(a.pool);
+  args.block_table = a.block_table;
+  args.tiles = a.tiles;
+  args.row_base = a.row_base;
+  args.G = s.G;
+  args.log2_T = s.log2_T;
+  args.tcap = s.tcap;
+  args.max_blocks = s.max_blocks;
+  const int64_t units = (int64_t)a.n_tiles * 2 * s.G;
+  if (units > 0x7fffffff) return hipErrorInvalidValue;
+  args.n_units = (int32_t)units;
+  args.id_base = a.id_base;
+  int64_t blocks = (units + 3) / 4;
+  if (a.max_workgroups > 0) blocks = std::min<int64_t>(blocks, a.max_workgroups);
+  blocks = std::min<int64_t>(blocks, 1 << 20);
+  dim3 grid((unsigned)blocks);
+  if (s.D == 128) {
+    if (s.paged) hipLaunchKernelGGL((bulk_append_kernel<128, true>), grid, dim3(256), 0, stream, args);
+    else hipLaunchKernelGGL((bulk_append_kernel<128, false>), grid, dim3(256), 0, stream, args);
+  } else if (s.D == 64) {
+    if (s.paged) hipLaunchKernelGGL((bulk_append_kernel<64, true>), grid, dim3(256), 0, stream, args);
+    else hipLaunchKernelGGL((bulk_append_kernel<64, false>), grid, dim3(256), 0, stream, args);
+  } else {
+    return hipErrorInvalidValue;
+  }
   return hipGetLastError();
 }
 

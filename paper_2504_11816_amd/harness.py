@@ -208,6 +208,21 @@ class Stack:
         if self.ctx_lens is not None:
             self.ctx_lens += 1
 
+    def prefill(self, n_new, k_rows, v_rows, release=True):
+        """Stores n_new[b] new tokens per sequence in every layer.  k_rows / v_rows are
+        per-layer lists of device tensors [sum(n_new)][G][d] (or single tensors reused)."""
+        def pick(x, l):
+            return x[l] if isinstance(x, (list, tuple)) else x
+        c = self.ctx
+        c.okv_prefill_begin(n_new)
+        for l in range(self.L):
+            c.kv_append_bulk(l, pick(k_rows, l), pick(v_rows, l))
+            if release:
+                c.okv_prefill_release(l)
+        c.okv_prefill_end()
+        if self.ctx_lens is not None:
+            self.ctx_lens += np.asarray(n_new, dtype=np.int32)
+
     def ctx_units(self):
         """The chunks of the host pool that hold blocks of the current batch (block-class
         mode): each is copied once per layer and step."""

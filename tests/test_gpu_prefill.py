@@ -1,0 +1,146 @@
+"""GPU parity for the prefill-side store: whole prompts written into the pools (HBM
+and pinned host memory) bit for bit as the oracle's scatter does, and decode steps on
+top of them against the fp64 attention oracle."""
+from fractions import Fraction
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import kv_layout
+from paper_2504_11816_amd import binding, synth
+from paper_2504_11816_amd.harness import Stack
+
+from gpu_util import build_stack, make_inputs, run_and_check
+from test_gpu_block_classes import classed_stack
+
+pytestmark = pytest.mark.gpu
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def prompt_rows(st, n_new, seed, step=0):
+    """Per-layer K/V rows [sum(n_new)][G][d] on the device, each from its own stream."""
+    rows = int(np.sum(n_new))
+    k = [synth.randn_f16_torch((rows, st.G, st.d), synth.stream_seed(seed, synth.TENSOR_KNEW, l, step), st.device)
+         for l in range(st.L)]
+    v = [synth.randn_f16_torch((rows, st.G, st.d), synth.stream_seed(seed, synth.TENSOR_VNEW, l, step), st.device)
+         for l in range(st.L)]
+    torch.cuda.synchronize()
+    return k, v
+
+
+def check_prefill(st, chunks, seed):
+    """Runs the given prefills one after the other; after each, every layer's pool must equal the
+    oracle's scatter applied to the pool as it was."""
+    want = [st.read_pool(l) for l in range(st.L)]
+    n = st.ctx_lens.copy()
+    for i, n_new in enumerate(chunks):
+        n_new = np.asarray(n_new, dtype=np.int32)
+        k, v = prompt_rows(st, n_new, seed, i)
+        st.prefill(n_new, k, v)
+        st.synchronize()
+        for l in range(st.L):
+            kv_layout.bulk_append_scatter(want[l], st.layout(), n, n_new, k[l].cpu().numpy(), v[l].cpu().numpy())
+            np.testing.assert_array_equal(st.read_pool(l).view(np.uint16), want[l].view(np.uint16))
+        n = n + n_new
+        np.testing.assert_array_equal(st.ctx.okv_get_ctx_lens(), n)
+
+
+@pytest.mark.parametrize("T", [0, 16, 64])
+@pytest.mark.parametrize("on_host", [[0, 0], [1, 0], [1, 1]])
+@pytest.mark.parametrize("d,G", [(64, 2), (128, 3)])
+def test_prompt_store_is_bit_exact(T, on_host, d, G):
+    say(f"prefill T={T} on_host={on_host} d={d} G={G}")
+    ctx = np.array([0, 0, 5, 16, 31], dtype=np.int32)
+    st = build_stack(L=2, H=2 * G if G == 2 else G, G=G, d=d, T=T, ctx_before=ctx, cap_tokens=256, on_host=on_host, seed=201)
+    # a ragged prompt, then a chunk that starts in the middle of a tile, then one with empty sequences
+    check_prefill(st, [[100, 1, 43, 16, 0], [17, 64, 0, 33, 7], [0, 0, 0, 0, 3]], seed=203)
+    # and the cache is usable: decode steps on top agree with the oracle
+    run_and_check(st, n_steps=2, seed=205)
+    st.close()
+
+
+@pytest.mark.parametrize("policy", ["prefix", "sequence", "scatter"])
+def test_prompt_store_with_blocks_on_the_host(policy):
+    say(f"prefill classes {policy}")
+    ctx = np.array([0, 3, 40, 0], dtype=np.int32)
+    st = classed_stack(L=2, H=4, G=2, d=64, T=16, ctx_before=ctx, cap_tokens=320, c_off=Fraction(1, 2), chunk_blocks=7,
+                       policy=policy, seed=211, workspace_items=4 * 24, split_tokens=64)
+    check_prefill(st, [[200, 77, 1, 0], [30, 16, 100, 250]], seed=213)
+    run_and_check(st, n_steps=2, seed=215)
+    st.close()
+
+
+def test_decode_then_prefill_then_decode():
+    # a prefill after decode steps restarts the copy pipeline: staged copies made before it are stale
+    say("prefill between decode steps")
+    st = build_stack(L=3, H=4, G=2, d=128, T=16, ctx_before=[50, 9], cap_tokens=256, on_host=[1, 0, 1], seed=221)
+    run_and_check(st, n_steps=2, seed=223)
+    check_prefill(st, [[60, 100]], seed=225)
+    run_and_check(st, n_steps=2, seed=227)
+    st.close()
+
+
+def test_prefill_error_paths():
+    say("prefill errors")
+    st = build_stack(L=2, H=4, G=2, d=64, T=16, ctx_before=[10, 20], cap_tokens=64, seed=231)
+    c = st.ctx
+    k, v = prompt_rows(st, [4, 4], 233)
+
+    def code(fn, *a):
+        with pytest.raises(binding.OkvError) as e:
+            fn(*a)
+        return e.value.code
+
+    assert code(c.kv_append_bulk, 0, k[0], v[0]) == binding.OKV_ESTATE          # no prefill open
+    assert code(c.okv_prefill_end) == binding.OKV_ESTATE
+    assert code(c.okv_prefill_begin, [-1, 2]) == binding.OKV_EINVAL
+    assert code(c.okv_prefill_begin, [55, 2]) == binding.OKV_ENOSPC             # 10 + 55 > 64
+    c.okv_prefill_begin([4, 4])
+    assert code(c.okv_prefill_begin, [1, 1]) == binding.OKV_ESTATE
+    assert code(c.okv_step_begin) == binding.OKV_ESTATE
+    assert code(c.kv_append_bulk, 1, k[1], v[1]) == binding.OKV_ESTATE          # layer out of order
+    assert code(c.kv_append_bulk, 0, None, v[0]) == binding.OKV_EINVAL
+    assert code(c.okv_prefill_release, 0) == binding.OKV_EINVAL                 # not stored yet
+    assert code(c.okv_prefill_end) == binding.OKV_ESTATE                        # layers missing
+    for l in range(2):
+        c.kv_append_bulk(l, k[l], v[l])
+        c.okv_prefill_release(l)
+    c.okv_prefill_end()
+    np.testing.assert_array_equal(c.okv_get_ctx_lens(), [14, 24])
+    tbl = st.block_table.copy()
+    tbl[0, 2] = -1
+    st.set_batch([14, 24], tbl)
+    assert code(c.okv_prefill_begin, [30, 0]) == binding.OKV_ENOSPC             # would reach an unallocated block
+    st.close()
+
+
+def test_full_size_prompt_2048_half_of_the_layers_on_the_host_sampled():
+    # batch 64 x prompt 2048, 32 KV heads x 128: 2 GiB of K/V per layer; one resident and one host layer.
+    # Sampled check: rows of a few (sequence, position, head) against the input, then a decode step.
+    say("prefill full size")
+    B, P = 64, 2048
+    st = Stack(L=2, H=32, G=32, d=128, B=B, T=16, cap_tokens=P + 16, on_host=[0, 1], out_dtype=0)
+    for l in range(2):
+        st.fill_pool(l, synth.stream_seed(241, synth.TENSOR_POOL, l))
+    table = synth.shuffled_block_table([st.cap_tokens] * B, 16, st.blocks_per_layer, 243, max_blocks_per_seq=st.max_blocks)
+    st.set_batch([0] * B, table)
+    k, v = prompt_rows(st, [P] * B, 245)
+    st.prefill([P] * B, k, v)
+    st.synchronize()
+    layout = st.layout()
+    rng = np.random.default_rng(247)
+    for l in range(2):
+        picks = [(int(rng.integers(B)), int(rng.integers(P)), int(rng.integers(32))) for _ in range(64)]
+        picks += [(0, 0, 0), (B - 1, P - 1, 31)]
+        for kv, rows in ((0, k[l]), (1, v[l])):
+            offs = [kv_layout.token_row_offset(layout, b, kv, g, pos) for (b, pos, g) in picks]
+            got = st.read_rows(l, offs)
+            want = np.stack([rows[b * P + pos, g].cpu().numpy() for (b, pos, g) in picks])
+            np.testing.assert_array_equal(got.view(np.uint16), want.view(np.uint16))
+    del k, v
+    run_and_check(st, n_steps=1, seed=249, pairs=[(0, 0), (63, 31), (20, 11)])
+    st.close()

@@ -18,7 +18,7 @@ def declared_functions():
     text = open(os.path.join(ROOT, "include", "okv.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
     names = re.findall(r"\b([a-z_0-9]+)\s*\(", text)
-    return sorted({n for n in names if n.startswith("okv_") or n in ("kv_append", "decode_attn", "kv_offload_plan")})
+    return sorted({n for n in names if n.startswith("okv_") or n in ("kv_append", "kv_append_bulk", "decode_attn", "kv_offload_plan")})
 
 
 def test_library_loads_and_exports_every_declared_symbol():
