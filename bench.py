@@ -358,6 +358,105 @@ def run_offload_blocks(args):
     return res
 
 
+def run_prefill(args):
+    """The prefill side of the offloaded shape: the K/V rows of a whole prompt batch are
+    stored layer by layer, half of the layers into pinned host memory.  Timed twice: the
+    stores alone, and next to a stand-in for the layer's computation (a plain read kernel
+    over a buffer sized to take about as long as a layer's write-out), to show that a layer
+    costs the longer of the two rather than their sum."""
+    import torch
+    from paper_2504_11816_amd import binding, synth
+    from paper_2504_11816_amd.harness import Stack
+    name = args.offload_workload
+    w = dict(synth.WORKLOADS[name])
+    L, H, G, d, T = w["L"], w["H"], w["G"], w["d"], w["T"]
+    B = args.offload_batch or OFFLOAD_DEFAULT_BATCH[name]
+    P = w["ctx"]
+    on_host, n_off = binding.kv_offload_plan(L, w["c_off"][0], w["c_off"][1])
+    log(f"[bench] prefill leg {name}: B={B} prompt={P} T={T} host layers {n_off}/{L}")
+    st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=P + 16, on_host=on_host, out_dtype=0, n_staging=args.staging)
+    if args.prefill_table == "ordered":                  # a sequence's blocks are neighbours in the pool
+        table = synth.identity_block_table([st.cap_tokens] * B, T, max_blocks_per_seq=st.max_blocks)
+    else:
+        table = synth.shuffled_block_table([st.cap_tokens] * B, T, st.blocks_per_layer, args.seed + 1,
+                                           max_blocks_per_seq=st.max_blocks)
+    rows = B * P
+    layer_bytes = rows * 2 * G * d * 2
+    # two sets of row buffers, used alternately: the projection of layer l + 2 may only
+    # overwrite a set once the store of layer l has left it (okv_prefill_release)
+    bufs = [(synth.randn_f16_torch((rows, G, d), synth.stream_seed(args.seed, synth.TENSOR_KNEW, i), st.device),
+             synth.randn_f16_torch((rows, G, d), synth.stream_seed(args.seed, synth.TENSOR_VNEW, i), st.device))
+            for i in range(2)]
+    host_layer = int(np.flatnonzero(on_host)[0])
+    link = binding.okv_measure_d2h(st.pools[host_layer], bufs[0][0], min(layer_bytes // 2, 2 << 30), 10,
+                                   st.h2d_stream.cuda_stream)
+    log(f"[bench] device-to-host link: {link:.1f} GB/s (plain hipMemcpyAsync, pinned, median of 10)")
+    # the stand-in computation: a read of `work` bytes takes about one host layer's write-out
+    sink = torch.zeros(4, dtype=torch.int32, device=st.device)
+    scratch = torch.empty(args.standin_gib << 30, dtype=torch.uint8, device=st.device)
+    cs = st.compute_stream.cuda_stream
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    binding.okv_probe_read(scratch, scratch.numel(), sink, cs)
+    st.compute_stream.synchronize()
+    e0.record(st.compute_stream)
+    for _ in range(8):
+        binding.okv_probe_read(scratch, scratch.numel(), sink, cs)
+    e1.record(st.compute_stream)
+    st.compute_stream.synchronize()
+    read_ms = e0.elapsed_time(e1) / 8
+    want_ms = layer_bytes / (link * 1e9) * 1e3 * n_off / L      # so that compute and write-out are about level
+    reads_per_layer = max(1, int(round(want_ms / read_ms)))
+
+    plan = {}
+
+    def one_pass(with_compute):
+        st.set_batch([0] * B, table)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        c = st.ctx
+        c.okv_prefill_begin([P] * B)
+        plan.update(c.okv_prefill_plan())
+        for l in range(L):
+            k_rows, v_rows = bufs[l % 2]
+            if l >= 2:
+                c.okv_prefill_release(l - 2)                   # this layer's "projection" overwrites the set of layer l - 2
+            if with_compute:
+                for _ in range(reads_per_layer):
+                    binding.okv_probe_read(scratch, scratch.numel(), sink, cs)
+            c.kv_append_bulk(l, k_rows, v_rows)
+        c.okv_prefill_end()
+        st.synchronize()
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    one_pass(False)                                            # warm-up (first touch of the pinned pools)
+    t_store = one_pass(False)
+    t_both = one_pass(True)
+    t_compute = L * reads_per_layer * read_ms * 1e-3
+    host_bytes = n_off * layer_bytes
+    hbm_bytes = (L - n_off) * layer_bytes
+    res = {
+        "workload": name, "B": B, "prompt": P, "layers": L, "host_layers": int(n_off),
+        "tokens_per_s": B * P / t_store, "ms_stores_alone": t_store * 1e3,
+        "link_gbps_measured": link, "link_gbps_achieved": host_bytes / t_store / 1e9,
+        "link_frac": host_bytes / t_store / 1e9 / link,
+        "standin_compute_ms": t_compute * 1e3, "ms_with_compute": t_both * 1e3,
+        "max_of_the_two_ms": max(t_compute, t_store) * 1e3, "sum_of_the_two_ms": (t_compute + t_store) * 1e3,
+        "host_gib": host_bytes / 2 ** 30, "hbm_gib": hbm_bytes / 2 ** 30,
+        "block_table": args.prefill_table,
+        "route": "staging + copy engines" if plan.get("staged_groups") else "kernel through the mapped pointer",
+        "copies_per_host_layer": plan.get("copies", 0),
+    }
+    log(f"[bench] prefill leg {name}: stores alone {res['ms_stores_alone']:.1f} ms = {res['link_gbps_achieved']:.1f} GB/s to the host "
+        f"({100 * res['link_frac']:.1f}% of measured); stand-in compute alone {res['standin_compute_ms']:.1f} ms; together "
+        f"{res['ms_with_compute']:.1f} ms (max {res['max_of_the_two_ms']:.1f}, sum {res['sum_of_the_two_ms']:.1f}); "
+        f"route: {res['route']}, {res['copies_per_host_layer']} copies per host layer")
+    st.close()
+    del st, bufs, scratch
+    torch.cuda.empty_cache()
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -370,12 +469,19 @@ def main():
                          "depend on the depth); 0 = the workload's own depth")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline")
     ap.add_argument("--cpu-seconds", type=float, default=15.0)
-    ap.add_argument("--no-offload", action="store_true", help="skip the offloaded leg")
+    ap.add_argument("--no-offload", action="store_true", help="skip every offloaded leg")
+    ap.add_argument("--no-layers", action="store_true", help="skip the whole-layer offloaded leg")
     ap.add_argument("--offload-workload", default="cfg3", choices=["cfg3", "cfg5"])
     ap.add_argument("--offload-steps", type=int, default=0)
     ap.add_argument("--offload-batch", type=int, default=0)
     ap.add_argument("--staging", type=int, default=2, help="staging buffers for host layers (1..4)")
     ap.add_argument("--no-blocks", action="store_true", help="skip the block-granular offloaded leg")
+    ap.add_argument("--no-prefill", action="store_true", help="skip the prefill-side store leg")
+    ap.add_argument("--prefill-table", default="ordered", choices=["ordered", "shuffled"],
+                    help="prefill leg: blocks handed out in order (host blocks go through staging and the copy "
+                         "engines) or shuffled (written by a kernel through the mapped pointer)")
+    ap.add_argument("--standin-gib", type=int, default=8,
+                    help="prefill leg: bytes one kernel of the stand-in computation reads")
     ap.add_argument("--chunk-mib", type=int, default=256, help="block-granular leg: size of a streamed chunk")
     ap.add_argument("--placement", default="prefix", choices=["prefix", "sequence", "scatter"],
                     help="block-granular leg: which blocks of a sequence live on the host")
@@ -389,8 +495,9 @@ def main():
         sys.exit("bench.py needs a GPU")
     res, cpu = run_resident(args)
     probe = run_probe() if args.probe else None
-    off = None if args.no_offload else run_offload(args)
+    off = None if (args.no_offload or args.no_layers) else run_offload(args)
     off_blocks = None if (args.no_offload or args.no_blocks) else run_offload_blocks(args)
+    prefill = None if (args.no_offload or args.no_prefill) else run_prefill(args)
     line = {
         "metric": "decode_attn_tokens_per_s", "value": res["tokens_per_s"], "unit": "tokens/s",
         "n_gpus": 1, "steps": res["steps"], "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
@@ -409,6 +516,7 @@ def main():
         "cpu_baseline": cpu,
         "offload": off,
         "offload_blocks": off_blocks,
+        "prefill_store": prefill,
     }
     if probe:
         line["probe"] = probe

@@ -20,7 +20,7 @@ EXPORTS = [
     "okv_plan_block_split", "okv_schedule_trace", "okv_create", "okv_destroy", "okv_last_error", "okv_set_batch",
     "okv_step_begin", "okv_step_end", "kv_append", "decode_attn", "okv_synchronize",
     "okv_set_split_tokens", "okv_get_split_tokens", "okv_get_ctx_lens", "okv_worklist",
-    "okv_worklist_classes", "okv_prefill_begin", "kv_append_bulk", "okv_prefill_release", "okv_prefill_end",
+    "okv_worklist_classes", "okv_prefill_begin", "kv_append_bulk", "okv_prefill_release", "okv_prefill_end", "okv_prefill_plan",
     "okv_measure_d2h",
     "okv_profile_enable", "okv_profile_read", "okv_measure_h2d", "okv_time_copies", "okv_probe_copy",
     "okv_probe_read",
@@ -91,6 +91,7 @@ def lib():
             "kv_append_bulk": (ctypes.c_int, [P, I32, P, P]),
             "okv_prefill_release": (ctypes.c_int, [P, I32]),
             "okv_prefill_end": (ctypes.c_int, [P]),
+            "okv_prefill_plan": (ctypes.c_int, [P] + [ctypes.POINTER(I64)] * 4),
             "okv_time_copies": (ctypes.c_int, [P, ctypes.POINTER(ctypes.c_double)]),
             "okv_probe_copy": (ctypes.c_int, [P, P, I64, P]),
             "okv_probe_read": (ctypes.c_int, [P, I64, P, P]),
@@ -284,6 +285,12 @@ class Context:
 
     def okv_prefill_release(self, layer):
         self._c(lib().okv_prefill_release(self._h, layer))
+
+    def okv_prefill_plan(self):
+        """-> dict(staged_groups, copies, staged_tiles, direct_tiles) of the last okv_prefill_begin"""
+        v = [ctypes.c_int64(0) for _ in range(4)]
+        self._c(lib().okv_prefill_plan(self._h, *[ctypes.byref(x) for x in v]))
+        return dict(zip(("staged_groups", "copies", "staged_tiles", "direct_tiles"), [x.value for x in v]))
 
     def okv_prefill_end(self):
         self._c(lib().okv_prefill_end(self._h))

@@ -35,8 +35,12 @@ constexpr int64_t kMaxClasses = 4096;
 // Workgroups of a bulk store that writes into host memory: the link, not the GPU, sets its
 // pace, so it is kept small enough to leave the compute units to whatever runs beside it.
 #ifndef OKV_HOST_WRITE_WORKGROUPS
-#define OKV_HOST_WRITE_WORKGROUPS 256
+#define OKV_HOST_WRITE_WORKGROUPS 64
 #endif
+// Blocks bound for the host are gathered in a staging buffer and moved by the copy engines when,
+// on average, at least this many bytes of them are adjacent in the host pool; below that the
+// per-copy cost outweighs the engines' advantage and the rows are written by a kernel instead.
+constexpr int64_t kMinStagedRunBytes = 1 << 20;
 
 thread_local std::string g_error;        // failures that have no context to live in
 
@@ -87,7 +91,15 @@ struct okv_ctx {
   int4 *d_tiles = nullptr;
   int32_t *d_row_base = nullptr;
   int64_t tiles_cap = 0;
-  int32_t n_tiles_hbm = 0, n_tiles_host = 0;       // d_tiles = [tiles stored into HBM][tiles stored into host memory]
+  // d_tiles = [tiles of a layer that is all in HBM][tiles bound for HBM blocks][tiles written straight
+  //            into host memory][tiles of staged group 0][group 1] ...
+  struct TileSpan { int32_t first = 0, count = 0; };
+  struct CopyRun { int64_t host_off, staging_off, bytes; };
+  struct StagedGroup { TileSpan tiles; std::vector<CopyRun> runs; };
+  TileSpan tiles_all, tiles_hbm, tiles_direct;
+  std::vector<StagedGroup> groups;
+  int64_t group_counter = 0;                         // staged groups issued since okv_create (picks buffer and events)
+  hipEvent_t filled_ev[kEventRing] = {}, copied_ev[kEventRing] = {};
   hipStream_t d2h = nullptr;                         // library-owned stream of the stores into host memory
   hipEvent_t rows_ready_ev = nullptr, prefill_done_ev = nullptr;
   std::vector<hipEvent_t> stored_ev;                 // per layer: its rows have left the caller's buffers
@@ -669,6 +681,10 @@ int okv_destroy(okv_ctx *ctx) {
     (void)hipStreamSynchronize(ctx->d2h);
     (void)hipStreamDestroy(ctx->d2h);
   }
+  for (int i = 0; i < kEventRing; ++i) {
+    if (ctx->filled_ev[i]) (void)hipEventDestroy(ctx->filled_ev[i]);
+    if (ctx->copied_ev[i]) (void)hipEventDestroy(ctx->copied_ev[i]);
+  }
   if (ctx->rows_ready_ev) (void)hipEventDestroy(ctx->rows_ready_ev);
   if (ctx->prefill_done_ev) (void)hipEventDestroy(ctx->prefill_done_ev);
   for (hipEvent_t e : ctx->stored_ev)
@@ -884,23 +900,92 @@ int okv_prefill_begin(okv_ctx *ctx, const int32_t *n_new) {
   }
   int rc = okv_synchronize(ctx);                        // a change of phase: nothing of a decode step is left in flight
   if (rc) return rc;
-  // 16-position tiles that receive rows, those stored into HBM first, then those stored into host memory
-  std::vector<int4> hbm, host;
+  // 16-position tiles that receive rows.  A tile is (sequence, tile, first and last position
+  // inside it, destination block relative to the pool the launch writes into).
+  auto tile_desc = [](int32_t b, int32_t t, int32_t lo, int32_t hi, int32_t dest) {
+    return make_int4(b, t, (lo - (t << 4)) | ((hi - (t << 4)) << 8), dest);
+  };
+  struct HostTile { int32_t b, t, lo, hi; int64_t blk; };   // blk: index in the host pool
+  std::vector<int4> all, hbm;
+  std::vector<HostTile> host;
   std::vector<int32_t> row_base(B);
+  const bool any_resident_layer = !ctx->by_class && std::any_of(ctx->dev_pool.begin(), ctx->dev_pool.end(), [](void *p) { return p != nullptr; });
+  const bool any_host_layer = !ctx->by_class && ctx->any_host;
   int64_t row = 0;
   for (int32_t b = 0; b < B; ++b) {
     const int32_t lo = ctx->h_ctx_lens[b], hi = lo + n_new[b];
     row_base[b] = (int32_t)(row - lo);
     row += n_new[b];
     for (int32_t t = lo >> 4; (t << 4) < hi; ++t) {
-      const int4 d = make_int4(b, t, std::max(lo, t << 4), std::min(hi, (t << 4) + 16));
-      bool to_host = false;
-      if (ctx->by_class) to_host = ctx->h_block_table[(size_t)b * s.max_blocks + ((t << 4) >> s.log2_T)] >= ctx->resident_blocks;
-      (to_host ? host : hbm).push_back(d);
+      const int32_t t_lo = std::max(lo, t << 4), t_hi = std::min(hi, (t << 4) + 16);
+      const int64_t id = s.paged ? ctx->h_block_table[(size_t)b * s.max_blocks + ((t << 4) >> s.log2_T)] : b;
+      if (ctx->by_class) {
+        if (id < ctx->resident_blocks) hbm.push_back(tile_desc(b, t, t_lo, t_hi, (int32_t)id));
+        else host.push_back(HostTile{b, t, t_lo, t_hi, id - ctx->resident_blocks});
+      } else {
+        if (any_resident_layer) all.push_back(tile_desc(b, t, t_lo, t_hi, (int32_t)id));
+        if (any_host_layer) host.push_back(HostTile{b, t, t_lo, t_hi, id});
+      }
     }
   }
   if (row > 0x7fffffff) return fail(ctx, OKV_EINVAL, "too many new rows");
-  const int64_t n_tiles = (int64_t)hbm.size() + (int64_t)host.size();
+  // Host side.  A block whose first stored position is its first slot holds nothing old, so it may
+  // be assembled in a staging buffer and copied over whole (slots past the new rows are unused and
+  // may hold anything).  Such blocks are sorted by id; neighbours in the host pool become one copy.
+  // Everything else (a prompt that continues in the middle of a block, contiguous pools, blocks
+  // scattered one by one) is written by the kernel straight through the mapped pointer.
+  std::vector<int4> direct;
+  std::vector<std::vector<int4>> group_tiles;
+  ctx->groups.clear();
+  if (!host.empty()) {
+    std::vector<int64_t> fresh;                          // host blocks that are written from their first slot
+    if (s.paged) {
+      for (const HostTile &h : host)
+        if (((h.t << 4) & (s.tcap - 1)) == 0 && h.lo == (h.t << 4)) fresh.push_back(h.blk);
+      std::sort(fresh.begin(), fresh.end());
+    }
+    int64_t n_runs = 0;
+    for (size_t i = 0; i < fresh.size(); ++i) n_runs += i == 0 || fresh[i] != fresh[i - 1] + 1;
+    const int64_t cap_blocks = ctx->n_staging > 0 ? ctx->cfg.staging_bytes / ctx->block_bytes : 0;
+    const bool staged = n_runs > 0 && cap_blocks > 0 && (int64_t)fresh.size() * ctx->block_bytes >= n_runs * kMinStagedRunBytes;
+    if (!staged) fresh.clear();
+    auto rank_of = [&](int64_t blk) -> int64_t {
+      auto it = std::lower_bound(fresh.begin(), fresh.end(), blk);
+      return it != fresh.end() && *it == blk ? it - fresh.begin() : -1;
+    };
+    const int64_t n_groups = staged ? ((int64_t)fresh.size() + cap_blocks - 1) / cap_blocks : 0;
+    group_tiles.resize(n_groups);
+    ctx->groups.resize(n_groups);
+    for (const HostTile &h : host) {
+      const int64_t r = rank_of(h.blk);
+      if (r < 0) direct.push_back(tile_desc(h.b, h.t, h.lo, h.hi, (int32_t)h.blk));
+      else group_tiles[r / cap_blocks].push_back(tile_desc(h.b, h.t, h.lo, h.hi, (int32_t)(r % cap_blocks)));
+    }
+    for (int64_t g = 0; g < n_groups; ++g) {
+      const int64_t first = g * cap_blocks, last = std::min<int64_t>((int64_t)fresh.size(), first + cap_blocks);
+      for (int64_t i = first; i < last;) {
+        int64_t e = i + 1;
+        while (e < last && fresh[e] == fresh[e - 1] + 1) ++e;
+        ctx->groups[g].runs.push_back(okv_ctx::CopyRun{fresh[i] * ctx->block_bytes, (i - first) * ctx->block_bytes,
+                                                      (e - i) * ctx->block_bytes});
+        i = e;
+      }
+    }
+  }
+  // one device array, one span per launch
+  std::vector<int4> flat;
+  auto add_span = [&](const std::vector<int4> &v) {
+    okv_ctx::TileSpan sp;
+    sp.first = (int32_t)flat.size();
+    sp.count = (int32_t)v.size();
+    flat.insert(flat.end(), v.begin(), v.end());
+    return sp;
+  };
+  ctx->tiles_all = add_span(all);
+  ctx->tiles_hbm = add_span(hbm);
+  ctx->tiles_direct = add_span(direct);
+  for (size_t g = 0; g < group_tiles.size(); ++g) ctx->groups[g].tiles = add_span(group_tiles[g]);
+  const int64_t n_tiles = (int64_t)flat.size();
   if (n_tiles > ctx->tiles_cap) {
     (void)hipFree(ctx->d_tiles);
     ctx->d_tiles = nullptr;
@@ -909,22 +994,23 @@ int okv_prefill_begin(okv_ctx *ctx, const int32_t *n_new) {
     ctx->tiles_cap = n_tiles;
   }
   if (!ctx->d_row_base) OKV_HIP(ctx, hipMalloc(&ctx->d_row_base, (size_t)ctx->cfg.max_batch * sizeof(int32_t)));
-  if (!hbm.empty()) OKV_HIP(ctx, hipMemcpy(ctx->d_tiles, hbm.data(), hbm.size() * sizeof(int4), hipMemcpyHostToDevice));
-  if (!host.empty())
-    OKV_HIP(ctx, hipMemcpy(ctx->d_tiles + hbm.size(), host.data(), host.size() * sizeof(int4), hipMemcpyHostToDevice));
+  if (n_tiles) OKV_HIP(ctx, hipMemcpy(ctx->d_tiles, flat.data(), (size_t)n_tiles * sizeof(int4), hipMemcpyHostToDevice));
   OKV_HIP(ctx, hipMemcpy(ctx->d_row_base, row_base.data(), (size_t)B * sizeof(int32_t), hipMemcpyHostToDevice));
-  ctx->n_tiles_hbm = (int32_t)hbm.size();
-  ctx->n_tiles_host = (int32_t)host.size();
   if (!ctx->d2h) {
     OKV_HIP(ctx, hipStreamCreateWithFlags(&ctx->d2h, hipStreamNonBlocking));
     OKV_HIP(ctx, hipEventCreateWithFlags(&ctx->rows_ready_ev, hipEventDisableTiming));
     OKV_HIP(ctx, hipEventCreateWithFlags(&ctx->prefill_done_ev, hipEventDisableTiming));
+    for (int i = 0; i < kEventRing; ++i) {
+      OKV_HIP(ctx, hipEventCreateWithFlags(&ctx->filled_ev[i], hipEventDisableTiming));
+      OKV_HIP(ctx, hipEventCreateWithFlags(&ctx->copied_ev[i], hipEventDisableTiming));
+    }
     ctx->stored_ev.assign(ctx->cfg.n_layers, nullptr);
     for (int32_t l = 0; l < ctx->cfg.n_layers; ++l)
       OKV_HIP(ctx, hipEventCreateWithFlags(&ctx->stored_ev[l], hipEventDisableTiming));
   }
   ctx->stored_set.assign(ctx->cfg.n_layers, 0);
   ctx->h_n_new.assign(n_new, n_new + B);
+  ctx->group_counter = 0;                                // okv_synchronize above: no staged group is in flight
   ctx->in_prefill = true;
   ctx->prefill_next_layer = 0;
   return OKV_OK;
@@ -938,36 +1024,63 @@ int kv_append_bulk(okv_ctx *ctx, int32_t layer, const void *k_rows, const void *
   if (!k_rows || !v_rows || !aligned16(k_rows) || !aligned16(v_rows)) return fail(ctx, OKV_EINVAL, "k_rows / v_rows NULL or not 16-byte aligned");
   okv::BulkLaunch a;
   a.shape = ctx->shape;
-  a.block_table = ctx->d_block_table;
   a.row_base = ctx->d_row_base;
   a.k_rows = k_rows;
   a.v_rows = v_rows;
-  // the tiles stored into HBM, on the compute stream
-  const bool whole_layer_on_host = !ctx->by_class && ctx->host_pool[layer] != nullptr;
-  if (!whole_layer_on_host && ctx->n_tiles_hbm > 0) {
-    a.tiles = ctx->d_tiles;
-    a.n_tiles = ctx->n_tiles_hbm;
-    a.pool = ctx->dev_pool[layer];
-    a.id_base = 0;
-    a.max_workgroups = 0;
-    OKV_HIP(ctx, okv::launch_bulk_append(a, ctx->compute));
+  a.max_workgroups = 0;
+  a.throttle = 0;
+  auto launch = [&](const okv_ctx::TileSpan &sp, void *pool, hipStream_t stream) -> hipError_t {
+    a.tiles = ctx->d_tiles + sp.first;
+    a.n_tiles = sp.count;
+    a.pool = pool;
+    return okv::launch_bulk_append(a, stream);
+  };
+  const bool host_layer = !ctx->by_class && ctx->host_pool[layer] != nullptr;
+  // rows bound for HBM, on the compute stream
+  if (!ctx->by_class && !host_layer) OKV_HIP(ctx, launch(ctx->tiles_all, ctx->dev_pool[layer], ctx->compute));
+  if (ctx->by_class && ctx->tiles_hbm.count) OKV_HIP(ctx, launch(ctx->tiles_hbm, ctx->dev_pool[layer], ctx->compute));
+  if (!ctx->by_class && !host_layer) {
+    ctx->prefill_next_layer = layer + 1;
+    return OKV_OK;
   }
-  // the tiles stored into host memory, on the library's own stream once the rows are there
-  const int32_t first = whole_layer_on_host ? 0 : ctx->n_tiles_hbm;
-  const int32_t count = whole_layer_on_host ? ctx->n_tiles_hbm : ctx->n_tiles_host;
-  if (count > 0) {
+  // blocks gathered in a staging buffer (compute stream) and copied over by the copy engines
+  for (const okv_ctx::StagedGroup &g : ctx->groups) {
+    const int64_t n = ctx->group_counter++;
+    const int buf = (int)(n % ctx->n_staging);
+    if (n >= ctx->n_staging) OKV_HIP(ctx, hipStreamWaitEvent(ctx->compute, ctx->copied_ev[(n - ctx->n_staging) % kEventRing], 0));
+    OKV_HIP(ctx, launch(g.tiles, ctx->cfg.staging[buf], ctx->compute));
+    OKV_HIP(ctx, hipEventRecord(ctx->filled_ev[n % kEventRing], ctx->compute));
+    OKV_HIP(ctx, hipStreamWaitEvent(ctx->d2h, ctx->filled_ev[n % kEventRing], 0));
+    for (const okv_ctx::CopyRun &r : g.runs)
+      OKV_HIP(ctx, hipMemcpyAsync(static_cast<char *>(ctx->host_pool[layer]) + r.host_off,
+                                  static_cast<const char *>(ctx->cfg.staging[buf]) + r.staging_off, (size_t)r.bytes,
+                                  hipMemcpyDeviceToHost, ctx->d2h));
+    OKV_HIP(ctx, hipEventRecord(ctx->copied_ev[n % kEventRing], ctx->d2h));
+  }
+  // the rest straight into host memory, by a small kernel on the library's own stream once the rows are there
+  if (ctx->tiles_direct.count) {
     OKV_HIP(ctx, hipEventRecord(ctx->rows_ready_ev, ctx->compute));
     OKV_HIP(ctx, hipStreamWaitEvent(ctx->d2h, ctx->rows_ready_ev, 0));
-    a.tiles = ctx->d_tiles + first;
-    a.n_tiles = count;
-    a.pool = ctx->host_pool[layer];
-    a.id_base = ctx->by_class ? (int32_t)ctx->resident_blocks : 0;
     a.max_workgroups = OKV_HOST_WRITE_WORKGROUPS;
-    OKV_HIP(ctx, okv::launch_bulk_append(a, ctx->d2h));
+    a.throttle = 1;
+    OKV_HIP(ctx, launch(ctx->tiles_direct, ctx->host_pool[layer], ctx->d2h));
     OKV_HIP(ctx, hipEventRecord(ctx->stored_ev[layer], ctx->d2h));
     ctx->stored_set[layer] = 1;
   }
   ctx->prefill_next_layer = layer + 1;
+  return OKV_OK;
+}
+
+int okv_prefill_plan(const okv_ctx *ctx, int64_t *staged_groups, int64_t *copies, int64_t *staged_tiles, int64_t *direct_tiles) {
+  if (!ctx || !staged_groups || !copies || !staged_tiles || !direct_tiles) return OKV_EINVAL;
+  *staged_groups = (int64_t)ctx->groups.size();
+  *copies = 0;
+  *staged_tiles = 0;
+  for (const okv_ctx::StagedGroup &g : ctx->groups) {
+    *copies += (int64_t)g.runs.size();
+    *staged_tiles += g.tiles.count;
+  }
+  *direct_tiles = ctx->tiles_direct.count;
   return OKV_OK;
 }
 

@@ -73,21 +73,22 @@ hipError_t launch_step_advance_classes(int32_t *ctx_lens, const int4 *runs, cons
                                        uint32_t *queues, int32_t n_queues, int32_t B, int32_t n_cls,
                                        int32_t S, int32_t inc, hipStream_t stream);
 
-// Bulk store of new K/V rows (a prompt).  tiles[i] = (sequence, 16-position tile, first
-// position, one past the last position to store in it); the row of position p of sequence b
-// is row row_base[b] + p of k_rows / v_rows, which are [rows][G][D] fp16.  `pool` holds the
-// blocks with ids from id_base on (or, contiguous layout, slice b for sequence b).
-// max_blocks_in_flight bounds the grid (0 = as many workgroups as there is work).
+// Bulk store of new K/V rows (a prompt).  tiles[i] = (sequence, 16-position tile, first slot of
+// the tile to store | one past the last << 8, destination block); the row of position p of
+// sequence b is row row_base[b] + p of k_rows / v_rows, which are [rows][G][D] fp16.  The
+// destination block counts in blocks of `pool` (an HBM pool, a host pool through its mapped
+// pointer, or a staging buffer in which blocks are being gathered); for contiguous pools it
+// is the sequence's slice.  max_workgroups bounds the grid (0 = as many as there is work);
+// throttle = 1 holds each wavefront to one tile's stores in flight.
 struct BulkLaunch {
   PoolShape shape;
-  const int32_t *block_table;
   const int4 *tiles;
   const int32_t *row_base;
   int32_t n_tiles;
   const void *k_rows, *v_rows;
   void *pool;
-  int32_t id_base;
   int32_t max_workgroups;
+  int32_t throttle;
 };
 hipError_t launch_bulk_append(const BulkLaunch &a, hipStream_t stream);
 

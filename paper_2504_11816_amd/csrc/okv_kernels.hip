@@ -655,10 +655,10 @@ __global__ __launch_bounds__(kStepThreads) void step_advance_classes_kernel(
 struct BulkArgs {
   const uint16_t *k_rows, *v_rows;
   uint16_t *pool;
-  const int32_t *block_table;
   const int4 *tiles;
   const int32_t *row_base;
-  int32_t G, log2_T, tcap, max_blocks, n_units, id_base;
+  int32_t G, tcap, n_units;
+  int32_t drain_each_tile;   // wait for a tile's stores before starting the next one
 };
 
 template <int D, bool PAGED>
@@ -674,7 +674,8 @@ __global__ __launch_bounds__(256) void bulk_append_kernel(const BulkArgs a) {
     const int kv = rest / a.G, g = rest - kv * a.G;
     const int4 tile = a.tiles[t];
     const int b = tile.x, pos0 = tile.y << 4;
-    const int blk = PAGED ? a.block_table[(size_t)b * a.max_blocks + (pos0 >> a.log2_T)] - a.id_base : b;
+    const int first = tile.z & 0xff, last = tile.z >> 8;      // slots of the tile to store: [first, last)
+    const int blk = tile.w;
     const int slot0 = PAGED ? pos0 & (a.tcap - 1) : pos0;
     const uint16_t *src = (kv ? a.v_rows : a.k_rows) + (size_t)g * D + col * 8;
     uint16_t *dst = a.pool + ((int64_t)blk * 2 * a.G + (int64_t)kv * a.G + g) * slice + (int64_t)slot0 * D + col * 8;
@@ -684,7 +685,7 @@ __global__ __launch_bounds__(256) void bulk_append_kernel(const BulkArgs a) {
 #pragma unroll
     for (int j = 0; j < LPT; ++j) {
       const int r = row + j * RPL;
-      ok[j] = pos0 + r >= tile.z && pos0 + r < tile.w;
+      ok[j] = r >= first && r < last;
       if (ok[j]) v[j] = *reinterpret_cast<const uint4 *>(src + (base_row + r) * a.G * D);
     }
 #pragma unroll
@@ -692,6 +693,11 @@ __global__ __launch_bounds__(256) void bulk_append_kernel(const BulkArgs a) {
       const int r = row + j * RPL;
       if (ok[j]) *reinterpret_cast<uint4 *>(dst + (int64_t)r * D) = v[j];
     }
+    // Stores into host memory leave at the link's pace.  Left alone, every wavefront queues
+    // dozens of them and anything else on the GPU that has to drain the memory pipeline (each
+    // kernel boundary does) waits behind that backlog; holding a wavefront to one tile in
+    // flight keeps the backlog to a few KiB per wavefront at no cost in link rate.
+    if (a.drain_each_tile) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
   }
 }
 
@@ -745,17 +751,14 @@ hipError_t launch_bulk_append(const BulkLaunch &a, hipStream_t stream) {
   args.k_rows = static_cast<const uint16_t *>(a.k_rows);
   args.v_rows = static_cast<const uint16_t *>(a.v_rows);
   args.pool = static_cast<uint16_t *>(a.pool);
-  args.block_table = a.block_table;
   args.tiles = a.tiles;
   args.row_base = a.row_base;
   args.G = s.G;
-  args.log2_T = s.log2_T;
   args.tcap = s.tcap;
-  args.max_blocks = s.max_blocks;
   const int64_t units = (int64_t)a.n_tiles * 2 * s.G;
   if (units > 0x7fffffff) return hipErrorInvalidValue;
   args.n_units = (int32_t)units;
-  args.id_base = a.id_base;
+  args.drain_each_tile = a.throttle;
   int64_t blocks = (units + 3) / 4;
   if (a.max_workgroups > 0) blocks = std::min<int64_t>(blocks, a.max_workgroups);
   blocks = std::min<int64_t>(blocks, 1 << 20);
