@@ -457,6 +457,74 @@ def run_prefill(args):
     return res
 
 
+def run_model(args, off):
+    """The paper's prediction model on this GPU's own numbers (§IV-D, §IV-F): the decode
+    attention time per layer is measured at several batch sizes, the calibration line
+    CTCF(t) = alpha t + beta is fitted by least squares against the theoretical time
+    (attention flops over the published FP16 matrix peak, as the paper does with vendor
+    figures), checked on batch sizes left out of the fit, and then used with the measured
+    link rate to predict the offloaded leg's step time, which is compared with the measurement."""
+    import torch
+    from paper_2504_11816_amd import infersave as isv, synth
+    from paper_2504_11816_amd.harness import Stack
+    w = dict(synth.WORKLOADS["cfg3"])
+    H, G, d, T = w["H"], w["G"], w["d"], w["T"]
+    ctx, layers, steps = w["ctx"], 4, 3
+    h1 = H * d
+    flops = 2.5e15                                            # MI355X dense FP16 matrix peak
+    fit_b, hold_b = [8, 16, 32, 64, 96], [12, 24, 48, 80]
+    times = {}
+    for B in sorted(fit_b + hold_b):
+        st = Stack(L=layers, H=H, G=G, d=d, B=B, T=T, cap_tokens=ctx + 16, out_dtype=0)
+        for l in range(layers):
+            st.fill_pool(l, synth.stream_seed(args.seed, synth.TENSOR_POOL, l))
+        table = synth.shuffled_block_table([st.cap_tokens] * B, T, st.blocks_per_layer, args.seed + 1,
+                                           max_blocks_per_seq=st.max_blocks)
+        inputs = fixed_inputs(st, args.seed)
+        ctx0 = np.full(B, ctx - 1, dtype=np.int32)
+        kernel_time(st, ctx0, table, inputs, 1)              # warm-up
+        k_s, k_n = kernel_time(st, ctx0, table, inputs, steps)
+        times[B] = k_s / k_n                                  # seconds per layer and step
+        st.close()
+        del st
+        torch.cuda.empty_cache()
+    theory = {B: isv.isv_attention_flops_decode(B, ctx + (steps - 1) / 2, h1) / flops for B in times}
+    alpha, beta, fit_err = isv.isv_ctcf_fit([theory[B] for B in fit_b], [times[B] for B in fit_b])
+    hold_err = float(np.mean([abs(alpha * theory[B] + beta - times[B]) / times[B] for B in hold_b]))
+    res = {
+        "theory": "4 BS context h1 flops per layer over 2.5 PFLOP/s", "context": ctx, "fit_batches": fit_b,
+        "holdout_batches": hold_b, "alpha": alpha, "beta_us": beta * 1e6, "fit_mean_rel_err": fit_err,
+        "holdout_mean_rel_err": hold_err,
+        "measured_us_per_layer": {str(B): times[B] * 1e6 for B in sorted(times)},
+    }
+    log(f"[bench] CTCF on decode attention at context {ctx}: alpha {alpha:.1f}, beta {beta * 1e6:.1f} us; mean error "
+        f"{100 * fit_err:.1f}% on the fitted batch sizes, {100 * hold_err:.1f}% on the held-out ones")
+    if off:
+        # the offloaded leg: per layer max(CTCF(compute), transfer) with the measured link rate (overlap),
+        # and the paper's compute + transfer (Eq. 6) beside it
+        B, L = off["B"], off["layers"]
+        c_off = off["host_layers"] / L
+        model = isv.IsvModel(0.0, h1, 4 * h1, L, 2)
+        # a one-token task at the leg's context: (c_off 2 (L_in + 1) + L_out) h1 prec BS / BW with L_in + 1 = context
+        work = isv.IsvWorkload(B, off["ctx"] - 1, 2)
+        t_attn = isv.isv_attention_flops_decode(B, off["ctx"], h1) / flops
+        full = isv.isv_predict(model, work, isv.IsvInstance(288e9, 1.0, flops, off["link_gbps_measured"] * 1e9,
+                                                            off["link_gbps_measured"] * 1e9, 1, 0, 1, 0), c_off, True)
+        t_trans = full["t_trans_dec"]
+        cd = alpha * t_attn + beta
+        overlap_ms = L * max(cd, t_trans) * 1e3
+        summed_ms = L * (cd + t_trans) * 1e3
+        res["offload_prediction"] = {
+            "c_off": c_off, "t_trans_per_layer_ms": t_trans * 1e3, "ctcf_attention_per_layer_ms": cd * 1e3,
+            "predicted_ms_per_step_overlap": overlap_ms, "predicted_ms_per_step_eq6_sum": summed_ms,
+            "measured_ms_per_step": off["ms_per_step"],
+            "rel_err_overlap": abs(overlap_ms - off["ms_per_step"]) / off["ms_per_step"],
+        }
+        log(f"[bench] model on the offloaded leg: predicted {overlap_ms:.1f} ms/step with overlap ({summed_ms:.1f} as the "
+            f"sum of Eq. 6), measured {off['ms_per_step']:.1f}")
+    return res
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -476,6 +544,7 @@ def main():
     ap.add_argument("--offload-batch", type=int, default=0)
     ap.add_argument("--staging", type=int, default=2, help="staging buffers for host layers (1..4)")
     ap.add_argument("--no-blocks", action="store_true", help="skip the block-granular offloaded leg")
+    ap.add_argument("--no-model", action="store_true", help="skip the prediction-model leg")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill-side store leg")
     ap.add_argument("--prefill-table", default="ordered", choices=["ordered", "shuffled"],
                     help="prefill leg: blocks handed out in order (host blocks go through staging and the copy "
@@ -498,6 +567,7 @@ def main():
     off = None if (args.no_offload or args.no_layers) else run_offload(args)
     off_blocks = None if (args.no_offload or args.no_blocks) else run_offload_blocks(args)
     prefill = None if (args.no_offload or args.no_prefill) else run_prefill(args)
+    model = None if args.no_model else run_model(args, off)
     line = {
         "metric": "decode_attn_tokens_per_s", "value": res["tokens_per_s"], "unit": "tokens/s",
         "n_gpus": 1, "steps": res["steps"], "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
@@ -517,6 +587,7 @@ def main():
         "offload": off,
         "offload_blocks": off_blocks,
         "prefill_store": prefill,
+        "model": model,
     }
     if probe:
         line["probe"] = probe

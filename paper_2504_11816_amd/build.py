@@ -35,5 +35,27 @@ def build_library(verbose=False):
     return LIB
 
 
+MODEL_LIB = os.path.join(HERE, "libinfersave.so")
+
+
+def build_model_library(verbose=False):
+    """Compile the host-only selection model (plain C) into libinfersave.so; always recompiles."""
+    gcc = shutil.which("gcc")
+    if not gcc:
+        raise RuntimeError("gcc not found: the selection-model library cannot be built")
+    cmd = [gcc, "-O2", "-std=c11", "-fPIC", "-shared", "-Wall", "-Wextra", "-I", os.path.join(os.path.dirname(HERE), "include"),
+           os.path.join(CSRC, "infersave.c"), "-lm", "-o", MODEL_LIB + ".tmp"]
+    if verbose:
+        print(" ".join(cmd), flush=True)
+    proc = subprocess.run(cmd, capture_output=True, text=True)
+    if proc.returncode != 0:
+        raise RuntimeError("gcc failed:\n" + proc.stdout + proc.stderr)
+    if verbose and proc.stderr.strip():
+        print(proc.stderr)
+    os.replace(MODEL_LIB + ".tmp", MODEL_LIB)
+    return MODEL_LIB
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_model_library(verbose=True))
