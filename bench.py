@@ -35,8 +35,8 @@ PCIE5_X16_GBPS = 64.0       # nominal, one direction
 # okv_kernels.hip has changed since, `traffic` is reported as null.
 TRAFFIC_RECORD = {
     "workload": "cfg2", "steps": 512,
-    "kernel_sha256": "c7cf5686e5011d988559339dab197f39adb6ee3ca3654ebfb0ba59bf8baf06be",
-    "fetch_kib": 199116.0, "fetch_scale": 2.0000,
+    "kernel_sha256": "f290e5bb1785d910e525dd26f574adfffae4a15e51beb0fba754f662dac9c2fb",
+    "fetch_kib": 199111.8, "fetch_scale": 2.0000,
     "write_kib": 768.0, "write_scale": 1.0000,
 }
 
