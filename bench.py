@@ -444,7 +444,7 @@ def run_prefill(args):
         "max_of_the_two_ms": max(t_compute, t_store) * 1e3, "sum_of_the_two_ms": (t_compute + t_store) * 1e3,
         "host_gib": host_bytes / 2 ** 30, "hbm_gib": hbm_bytes / 2 ** 30,
         "block_table": args.prefill_table,
-        "route": "staging + copy engines" if plan.get("staged_groups") else "kernel through the mapped pointer",
+        "route": "staging + hipMemcpyAsync" if plan.get("staged_groups") else "kernel through the mapped pointer",
         "copies_per_host_layer": plan.get("copies", 0),
     }
     log(f"[bench] prefill leg {name}: stores alone {res['ms_stores_alone']:.1f} ms = {res['link_gbps_achieved']:.1f} GB/s to the host "
@@ -547,8 +547,7 @@ def main():
     ap.add_argument("--no-model", action="store_true", help="skip the prediction-model leg")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill-side store leg")
     ap.add_argument("--prefill-table", default="ordered", choices=["ordered", "shuffled"],
-                    help="prefill leg: blocks handed out in order (host blocks go through staging and the copy "
-                         "engines) or shuffled (written by a kernel through the mapped pointer)")
+                    help="prefill leg: how the block table hands out blocks")
     ap.add_argument("--standin-gib", type=int, default=8,
                     help="prefill leg: bytes one kernel of the stand-in computation reads")
     ap.add_argument("--chunk-mib", type=int, default=256, help="block-granular leg: size of a streamed chunk")

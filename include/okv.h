@@ -271,8 +271,9 @@ int okv_prefill_begin(okv_ctx *ctx, const int32_t *n_new);
  * block (or whole layer) is on the host take one of two routes (okv_prefill_plan tells
  * which): blocks that are filled from their first slot and lie next to each other in
  * the host pool are gathered, in pool layout, in the staging buffers by a kernel on the
- * compute stream and moved by hipMemcpyAsync on a stream of the library's own (copy
- * engines do not disturb the kernels running beside them); slots of such a block past
+ * compute stream and moved by hipMemcpyAsync on a stream of the library's own (measured
+ * to slow kernels running beside it by a few percent, where a kernel writing through
+ * the mapped pointer slowed an HBM-bound neighbour several times over); slots of such a block past
  * the new rows are unused and receive unspecified bits.  Everything else (a prompt that
  * continues in the middle of a block, contiguous pools, blocks scattered singly) is
  * written straight into the pinned pool by a small kernel on that stream, which first
@@ -283,8 +284,8 @@ int kv_append_bulk(okv_ctx *ctx, int32_t layer, const void *k_rows, const void *
 
 /* How the last okv_prefill_begin routes the rows bound for host memory, per layer that has
  * any: blocks written from their first slot whose neighbours in the host pool add up to
- * 1 MiB per stretch on average are gathered in the staging buffers and copied by the copy
- * engines (staged_groups buffer fills, `copies` hipMemcpyAsync calls, staged_tiles 16-token
+ * 1 MiB per stretch on average are gathered in the staging buffers and copied over by
+ * the runtime (staged_groups buffer fills, `copies` hipMemcpyAsync calls, staged_tiles 16-token
  * tiles); the rest is written by a kernel through the mapped pointer (direct_tiles). */
 int okv_prefill_plan(const okv_ctx *ctx, int64_t *staged_groups, int64_t *copies,
                      int64_t *staged_tiles, int64_t *direct_tiles);

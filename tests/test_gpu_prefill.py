@@ -102,7 +102,7 @@ def test_prompt_store_with_blocks_on_the_host(policy):
 @pytest.mark.parametrize("T", [16, 64])
 def test_prompt_store_through_staging_when_blocks_are_adjacent(n_staging, T):
     # blocks handed out in order: a sequence's blocks are neighbours in the host pool, so they are
-    # gathered in a staging buffer and moved by the copy engines; a second prefill that continues in
+    # gathered in a staging buffer and moved by hipMemcpyAsync; a second prefill that continues in
     # the middle of a block takes the direct path for that block
     say(f"prefill staged T={T} staging={n_staging}")
     B, cap = 6, 2048
