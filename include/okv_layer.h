@@ -1,0 +1,66 @@
+/*
+ * okv_layer -- the linear layers of a decoder layer in the decode stage, for one MI355X.
+ *
+ * Next to the attention, the paper counts 8 h1^2 + 4 h1 h2 flops per generated token and
+ * layer (§IV-D): four h1 x h1 projections and the two matrices of the feed-forward
+ * block.  With a decode batch of a few dozen tokens every weight is read once per step
+ * and used BS times, so these products are bound by reading the weights from HBM, like
+ * the attention is by reading the KV cache.  The entry points below are those products
+ * and the layer norm between them; together with kv_append / decode_attn (okv.h) they
+ * make a whole decoder layer of the models the paper runs (OPT: layer norm before the
+ * attention and before the feed-forward block, ReLU, biases, residual connections).
+ *
+ * Conventions as in okv.h: C ABI, every pointer DEVICE unless labelled, fp16 tensors
+ * row-major, the caller owns all memory, calls enqueue on `stream` (a hipStream_t, NULL
+ * = the default stream) and return at once; OKV_OK or a negative OKV_E* code;
+ * okv_last_error(NULL) has the message.
+ */
+#ifndef OKV_LAYER_H
+#define OKV_LAYER_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define OKV_LINEAR_MAX_ROWS 128
+
+/* Rearranges a weight matrix for okv_linear.
+ *   src  fp16 [n_out][n_in] row-major (the layout of a framework's linear layer:
+ *        out = x * src^T)
+ *   dst  fp16, n_out * n_in elements: 16 output features x 32 inputs at a time, stored as
+ *        the 64 x 16-byte pieces a wavefront loads with one instruction and feeds to two
+ *        matrix-core instructions: piece (lane) of block (n / 16, k / 32) holds
+ *        src[16 * (n / 16) + lane % 16][32 * (k / 32) + 8 * (lane / 16) .. + 7]
+ * n_out must be a multiple of 16 and n_in of 32.  dst and src must not overlap. */
+int okv_pack_linear_weight(void *dst, const void *src, int32_t n_out, int32_t n_in, void *stream);
+
+/* out = act(x * W^T + bias) + residual for a batch of m <= OKV_LINEAR_MAX_ROWS rows
+ * (paper §IV-D: the linear layers of the decode stage, 2 n_out n_in flops per row).
+ *   x         fp16 [m][n_in]
+ *   w_packed  fp16, as okv_pack_linear_weight leaves it
+ *   bias      fp16 [n_out] or NULL
+ *   residual  fp16 [m][n_out] or NULL (added after the activation; n_seg must be 1)
+ *   out       HOST array of n_seg DEVICE pointers: the n_out output features are cut into
+ *             n_seg equal runs (1 <= n_seg <= 3, n_out / n_seg a multiple of 16) and run s
+ *             is written as fp16 [m][n_out / n_seg] to out[s] -- one product for the query,
+ *             key and value projections, each landing in a tensor of its own
+ *   relu      1: act = max(., 0); 0: act = identity
+ * Products accumulate in fp32 on the matrix cores; the result is rounded to fp16 once.
+ * residual may alias out[0] (each element is read before it is written, by the same lane). */
+int okv_linear(const void *x, const void *w_packed, const void *bias, const void *residual,
+               void *const *out, int32_t n_seg, int32_t m, int32_t n_out, int32_t n_in,
+               int32_t relu, void *stream);
+
+/* out[i] = (x[i] - mean_i) / sqrt(var_i + eps) * gamma + beta for each of m rows of h
+ * numbers (population variance; statistics in fp32).
+ *   x, out  fp16 [m][h] (may be the same buffer);  gamma, beta  fp16 [h]
+ * h must be a multiple of 8 and at most 16384. */
+int okv_layernorm(const void *x, const void *gamma, const void *beta, void *out, int32_t m,
+                  int32_t h, float eps, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* OKV_LAYER_H */

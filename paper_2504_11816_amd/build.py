@@ -6,7 +6,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libokv.so")
-SOURCES = ["okv_kernels.hip", "okv_api.hip"]
+SOURCES = ["okv_kernels.hip", "okv_layer.hip", "okv_api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
          # keep the compiler from forming packed-fp32 instructions
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

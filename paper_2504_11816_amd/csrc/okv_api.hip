@@ -12,6 +12,7 @@
 #include <vector>
 
 #include "../../include/okv.h"
+#include "../../include/okv_layer.h"
 #include "okv_host.h"
 #include "okv_kernels.h"
 
@@ -1331,6 +1332,43 @@ int okv_time_copies(okv_ctx *ctx, double *ms) {
   *ms = t;
   // the staging buffers no longer hold what the pipeline had prefetched: start it afresh
   reset_schedule(ctx);
+  return OKV_OK;
+}
+
+// ---- linear layers ---------------------------------------------------------------------------
+
+int okv_pack_linear_weight(void *dst, const void *src, int32_t n_out, int32_t n_in, void *stream) {
+  if (!dst || !src || !aligned16(dst) || !aligned16(src)) return fail(nullptr, OKV_EINVAL, "okv_pack_linear_weight: NULL or misaligned pointer");
+  if (n_out < 16 || n_out % 16 || n_in < 32 || n_in % 32) return fail(nullptr, OKV_EINVAL, "okv_pack_linear_weight: n_out must be a multiple of 16 and n_in of 32");
+  OKV_HIP(nullptr, okv::launch_pack_weight(dst, src, n_out, n_in, static_cast<hipStream_t>(stream)));
+  return OKV_OK;
+}
+
+int okv_linear(const void *x, const void *w_packed, const void *bias, const void *residual, void *const *out, int32_t n_seg,
+               int32_t m, int32_t n_out, int32_t n_in, int32_t relu, void *stream) {
+  if (!x || !w_packed || !out || !aligned16(x) || !aligned16(w_packed)) return fail(nullptr, OKV_EINVAL, "okv_linear: NULL or misaligned pointer");
+  if (m < 1 || m > OKV_LINEAR_MAX_ROWS) return fail(nullptr, OKV_EINVAL, "okv_linear: m = %d outside [1, %d]", m, OKV_LINEAR_MAX_ROWS);
+  if (n_out < 16 || n_out % 16 || n_in < 32 || n_in % 32 || n_in > (1 << 20))
+    return fail(nullptr, OKV_EINVAL, "okv_linear: n_out must be a multiple of 16 and n_in of 32");
+  if (n_seg < 1 || n_seg > 3 || n_out % (16 * n_seg)) return fail(nullptr, OKV_EINVAL, "okv_linear: n_seg must be 1..3 and divide n_out / 16");
+  if (residual && n_seg != 1) return fail(nullptr, OKV_EINVAL, "okv_linear: a residual needs n_seg = 1");
+  if (relu != 0 && relu != 1) return fail(nullptr, OKV_EINVAL, "okv_linear: relu must be 0 or 1");
+  okv::LinearLaunch l;
+  l.x = x, l.w_packed = w_packed, l.bias = bias, l.residual = residual;
+  for (int s = 0; s < 3; ++s) {
+    l.out[s] = s < n_seg ? out[s] : nullptr;
+    if (s < n_seg && !out[s]) return fail(nullptr, OKV_EINVAL, "okv_linear: out[%d] is NULL", s);
+  }
+  l.n_seg = n_seg, l.m = m, l.n_out = n_out, l.n_in = n_in, l.relu = relu;
+  OKV_HIP(nullptr, okv::launch_linear(l, static_cast<hipStream_t>(stream)));
+  return OKV_OK;
+}
+
+int okv_layernorm(const void *x, const void *gamma, const void *beta, void *out, int32_t m, int32_t h, float eps, void *stream) {
+  if (!x || !gamma || !beta || !out || !aligned16(x) || !aligned16(gamma) || !aligned16(beta) || !aligned16(out))
+    return fail(nullptr, OKV_EINVAL, "okv_layernorm: NULL or misaligned pointer");
+  if (m < 1 || h < 8 || h % 8 || h > 16384 || !(eps >= 0)) return fail(nullptr, OKV_EINVAL, "okv_layernorm: bad shape or eps");
+  OKV_HIP(nullptr, okv::launch_layernorm(x, gamma, beta, out, m, h, eps, static_cast<hipStream_t>(stream)));
   return OKV_OK;
 }
 

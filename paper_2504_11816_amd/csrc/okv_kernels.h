@@ -95,6 +95,17 @@ hipError_t launch_bulk_append(const BulkLaunch &a, hipStream_t stream);
 // items[it] = (b, lo, hi) decoded on the device.
 hipError_t launch_worklist_dump(const BatchState &batch, int32_t *items, hipStream_t stream);
 
+// ---- linear layers of a decoder layer (okv_layer.hip) ----------------------------------------
+struct LinearLaunch {
+  const void *x, *w_packed, *bias, *residual;
+  void *out[3];
+  int32_t n_seg, m, n_out, n_in, relu;
+};
+hipError_t launch_linear(const LinearLaunch &l, hipStream_t stream);
+hipError_t launch_pack_weight(void *dst, const void *src, int32_t n_out, int32_t n_in, hipStream_t stream);
+hipError_t launch_layernorm(const void *x, const void *gamma, const void *beta, void *out, int32_t m, int32_t h, float eps,
+                            hipStream_t stream);
+
 hipError_t launch_probe_copy(void *dst, const void *src, int64_t bytes, hipStream_t stream);
 hipError_t launch_probe_read(const void *src, int64_t bytes, void *sink, hipStream_t stream);
 

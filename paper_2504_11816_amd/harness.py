@@ -238,3 +238,76 @@ class Stack:
         for p in self._pinned:
             p.free()
         self._pinned = []
+
+
+class LayerWeights:
+    """The matrices and vectors of one decoder layer (fp16 on the device), row-major as a
+    framework holds them, plus the rearranged copies okv_linear reads.  The query, key and
+    value projections are stacked into one [3 h1][h1] matrix so that one product serves all
+    three."""
+
+    NAMES = ("ln1_g", "ln1_b", "wq", "bq", "wk", "bk", "wv", "bv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
+
+    def __init__(self, h1, h2, seed, layer, device):
+        self.h1, self.h2 = h1, h2
+        t = {}
+        for i, name in enumerate(self.NAMES):
+            sd = synth.stream_seed(seed, 100 + i, layer)
+            if name.startswith("w"):
+                n_out, n_in = (h2, h1) if name == "w1" else (h1, h2) if name == "w2" else (h1, h1)
+                t[name] = (synth.randn_f16_torch((n_out, n_in), sd, device).float() / n_in ** 0.5).to(torch.float16)
+            elif name.endswith("_g"):
+                t[name] = (1.0 + 0.1 * synth.randn_f16_torch((h1,), sd, device).float()).to(torch.float16)
+            else:
+                n = h2 if name == "b1" else h1
+                t[name] = (0.1 * synth.randn_f16_torch((n,), sd, device).float()).to(torch.float16)
+        self.t = t
+        self.wqkv = torch.cat([t["wq"], t["wk"], t["wv"]], dim=0).contiguous()
+        self.bqkv = torch.cat([t["bq"], t["bk"], t["bv"]], dim=0).contiguous()
+        self.packed = {}
+        for name, w in (("wqkv", self.wqkv), ("wo", t["wo"]), ("w1", t["w1"]), ("w2", t["w2"])):
+            dst = torch.empty_like(w)
+            binding.okv_pack_linear_weight(dst, w, w.shape[0], w.shape[1])
+            self.packed[name] = dst
+        torch.cuda.synchronize(device)
+
+    def numpy(self):
+        """fp64 copies for the oracle."""
+        return {k: v.double().cpu().numpy() for k, v in self.t.items()}
+
+    def bytes_read_per_step(self):
+        return sum(w.numel() * 2 for w in self.packed.values())
+
+
+class LayerScratch:
+    """Activation buffers of one decode step (fp16, reused by every layer)."""
+
+    def __init__(self, B, h1, h2, G, d, device):
+        def buf(*shape):
+            return torch.empty(shape, dtype=torch.float16, device=device)
+        self.a, self.q, self.k, self.v = buf(B, h1), buf(B, h1), buf(B, G * d), buf(B, G * d)
+        self.t, self.y, self.z, self.u = buf(B, h1), buf(B, h1), buf(B, h1), buf(B, h2)
+
+
+def decode_step_with_layers(st, weights, scratch, x):
+    """One decode step of whole decoder layers: for every layer, layer norm, the stacked
+    query/key/value projection, kv_append + decode_attn, output projection with residual,
+    layer norm, feed-forward block with ReLU and residual.  x: fp16 [B][h1] on the device,
+    overwritten with the stack's output.  Every operation is a call into the library on the
+    stack's compute stream."""
+    c, s, B = st.ctx, scratch, st.B
+    cs = st.compute_stream.cuda_stream
+    h1, h2 = weights[0].h1, weights[0].h2
+    c.okv_step_begin()
+    for l, w in enumerate(weights):
+        binding.okv_layernorm(x, w.t["ln1_g"], w.t["ln1_b"], s.a, B, h1, 1e-5, cs)
+        binding.okv_linear(s.a, w.packed["wqkv"], w.bqkv, None, [s.q, s.k, s.v], B, 3 * h1, h1, False, cs)
+        c.kv_append(l, s.k, s.v)
+        c.decode_attn(l, s.q, s.t)
+        binding.okv_linear(s.t, w.packed["wo"], w.t["bo"], x, s.y, B, h1, h1, False, cs)
+        binding.okv_layernorm(s.y, w.t["ln2_g"], w.t["ln2_b"], s.z, B, h1, 1e-5, cs)
+        binding.okv_linear(s.z, w.packed["w1"], w.t["b1"], None, s.u, B, h2, h1, True, cs)
+        binding.okv_linear(s.u, w.packed["w2"], w.t["b2"], s.y, x, B, h1, h2, False, cs)
+    c.okv_step_end()
+    if st.ctx_lens is not None:
+        st.ctx_lens += 1

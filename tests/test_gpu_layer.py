@@ -1,0 +1,169 @@
+"""GPU parity for the linear layers around the attention: weight rearrangement bit-exact,
+okv_linear and okv_layernorm against the fp64 oracle on the same fp16 inputs, and whole decoder
+layers (with the attention and the KV cache in between) against the oracle rounding to fp16
+where the GPU stores fp16.
+
+Tolerance of one product or layer norm: |gpu - oracle| <= 2e-3 + 2e-3 |oracle| per element
+(fp16 inputs are exact in fp32, sums of up to 16384 terms in fp32, one rounding to fp16 of
+results of size O(1..8)).  Whole layers: 1.5e-2 + 1.5e-2 |oracle| (a different rounding decision at one
+fp16 store moves a value by 2^-11 relative, and four products and two norms follow one another)."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import attention as oa
+from oracle import decode_layer as dl
+from oracle import kv_layout
+from paper_2504_11816_amd import binding, synth
+from paper_2504_11816_amd.harness import LayerScratch, LayerWeights, decode_step_with_layers
+
+from gpu_util import build_stack
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def close(got, want, atol=2e-3, rtol=2e-3, what=""):
+    got, want = np.asarray(got, dtype=np.float64), np.asarray(want, dtype=np.float64)
+    assert got.shape == want.shape and np.all(np.isfinite(got)), what
+    err = np.abs(got - want) - rtol * np.abs(want)
+    assert err.max() <= atol, f"{what}: worst excess {err.max():.3e} over {atol}"
+
+
+def packed_layout(w):
+    """The rearrangement okv_pack_linear_weight is specified to produce, written with plain loops."""
+    n_out, n_in = w.shape
+    out = np.empty(n_out * n_in, dtype=w.dtype)
+    at = 0
+    for nt in range(n_out // 16):
+        for kb in range(n_in // 32):
+            for lane in range(64):
+                n, k = 16 * nt + lane % 16, 32 * kb + 8 * (lane // 16)
+                out[at:at + 8] = w[n, k:k + 8]
+                at += 8
+    return out
+
+
+@pytest.mark.parametrize("n_out,n_in", [(16, 32), (48, 96), (256, 1024)])
+def test_weight_rearrangement_is_bit_exact(n_out, n_in):
+    say(f"pack {n_out}x{n_in}")
+    w = synth.randn_f16_torch((n_out, n_in), synth.stream_seed(301, 1), DEV)
+    dst = torch.zeros_like(w)
+    binding.okv_pack_linear_weight(dst, w, n_out, n_in)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(dst.cpu().numpy().reshape(-1).view(np.uint16), packed_layout(w.cpu().numpy()).view(np.uint16))
+
+
+def run_linear(m, n_out, n_in, seed, bias=True, relu=False, residual=False, n_seg=1):
+    x = synth.randn_f16_torch((m, n_in), synth.stream_seed(seed, 1), DEV)
+    w = (synth.randn_f16_torch((n_out, n_in), synth.stream_seed(seed, 2), DEV).float() / n_in ** 0.5).to(torch.float16)
+    b = synth.randn_f16_torch((n_out,), synth.stream_seed(seed, 3), DEV) if bias else None
+    r = synth.randn_f16_torch((m, n_out), synth.stream_seed(seed, 4), DEV) if residual else None
+    wp = torch.empty_like(w)
+    binding.okv_pack_linear_weight(wp, w, n_out, n_in)
+    outs = [torch.full((m, n_out // n_seg), float("nan"), dtype=torch.float16, device=DEV) for _ in range(n_seg)]
+    binding.okv_linear(x, wp, b, r, outs, m, n_out, n_in, relu)
+    torch.cuda.synchronize()
+    want = dl.linear(x.double().cpu().numpy(), w.double().cpu().numpy(), None if b is None else b.double().cpu().numpy())
+    if relu:
+        want = dl.relu(want)
+    if residual:
+        want = want + r.double().cpu().numpy()
+    got = np.concatenate([o.float().cpu().numpy() for o in outs], axis=1)
+    close(got, want, what=f"linear m={m} {n_out}x{n_in}")
+
+
+@pytest.mark.parametrize("m", [1, 5, 16, 17, 32, 33, 64, 100, 128])
+def test_linear_every_row_count(m):
+    say(f"linear m={m}")
+    run_linear(m, 96, 320, 311 + m)                      # 10 blocks of 32 inputs: uneven shares for the 8 wavefronts
+    run_linear(m, 64, 2048, 411 + m, relu=True)
+
+
+@pytest.mark.parametrize("n_out,n_in", [(16, 32), (32, 64), (48, 4096), (4096, 256), (144, 992)])
+def test_linear_shapes(n_out, n_in):
+    say(f"linear {n_out}x{n_in}")
+    run_linear(32, n_out, n_in, 321)
+    run_linear(7, n_out, n_in, 322, bias=False)
+
+
+def test_linear_epilogue_variants():
+    say("linear epilogue")
+    run_linear(32, 192, 512, 331, bias=True, relu=True, residual=True)
+    run_linear(32, 192, 512, 332, bias=False, relu=False, residual=True)
+    run_linear(20, 192, 512, 333, n_seg=3)
+    run_linear(20, 192, 512, 334, n_seg=2, relu=True)
+    # residual aliasing the output: y = y + x W^T
+    m, n = 24, 128
+    x = synth.randn_f16_torch((m, 256), synth.stream_seed(335, 1), DEV)
+    w = (synth.randn_f16_torch((n, 256), synth.stream_seed(335, 2), DEV).float() / 16).to(torch.float16)
+    y = synth.randn_f16_torch((m, n), synth.stream_seed(335, 3), DEV)
+    y0 = y.double().cpu().numpy()
+    wp = torch.empty_like(w)
+    binding.okv_pack_linear_weight(wp, w, n, 256)
+    binding.okv_linear(x, wp, None, y, y, m, n, 256)
+    torch.cuda.synchronize()
+    close(y.float().cpu().numpy(), y0 + dl.linear(x.double().cpu().numpy(), w.double().cpu().numpy()), what="aliased residual")
+
+
+def test_linear_full_size_projection_and_feed_forward():
+    say("linear full size")
+    run_linear(32, 4096, 4096, 341)
+    run_linear(64, 12288, 4096, 342, n_seg=3)
+    run_linear(32, 16384, 4096, 343, relu=True)
+    run_linear(32, 4096, 16384, 344, residual=True)
+    run_linear(128, 4096, 4096, 345)
+
+
+@pytest.mark.parametrize("m,h", [(1, 8), (3, 64), (32, 2560), (64, 4096), (5, 16384), (128, 768)])
+def test_layernorm(m, h):
+    say(f"layernorm {m}x{h}")
+    x = (3.0 * synth.randn_f16_torch((m, h), synth.stream_seed(351, 1), DEV).float() + 1.5).to(torch.float16)
+    g = (1.0 + 0.2 * synth.randn_f16_torch((h,), synth.stream_seed(351, 2), DEV).float()).to(torch.float16)
+    b = (0.3 * synth.randn_f16_torch((h,), synth.stream_seed(351, 3), DEV).float()).to(torch.float16)
+    out = torch.full((m, h), float("nan"), dtype=torch.float16, device=DEV)
+    binding.okv_layernorm(x, g, b, out, m, h, 1e-5)
+    torch.cuda.synchronize()
+    want = dl.layernorm(x.double().cpu().numpy(), g.double().cpu().numpy(), b.double().cpu().numpy(), 1e-5)
+    close(out.float().cpu().numpy(), want, what=f"layernorm {m}x{h}")
+    # in place
+    binding.okv_layernorm(x, g, b, x, m, h, 1e-5)
+    torch.cuda.synchronize()
+    assert torch.equal(x, out)
+
+
+@pytest.mark.parametrize("T,on_host", [(0, None), (16, [0, 1])])
+def test_whole_decoder_layers_against_the_oracle(T, on_host):
+    say(f"decoder layers T={T} on_host={on_host}")
+    L, H, d, B = 2, 4, 64, 5
+    h1, h2 = H * d, 4 * H * d
+    ctx = [3, 40, 100, 17, 64]
+    st = build_stack(L=L, H=H, G=H, d=d, T=T, ctx_before=ctx, cap_tokens=128, on_host=on_host, seed=361)
+    weights = [LayerWeights(h1, h2, 363, l, st.device) for l in range(L)]
+    scratch = LayerScratch(B, h1, h2, H, d, st.device)
+    layout = st.layout()
+    pools = [st.read_pool(l).copy() for l in range(L)]
+    n = np.array(ctx, dtype=np.int32)
+    for step in range(2):
+        x = synth.randn_f16_torch((B, h1), synth.stream_seed(365, 1, 0, step), st.device)
+        x_ref = x.double().cpu().numpy()
+        decode_step_with_layers(st, weights, scratch, x)
+        st.synchronize()
+        n = n + 1
+        for l in range(L):
+            p = weights[l].numpy()
+            q, k, v = dl.qkv(x_ref, p, fp16_between=True)
+            kv_layout.append_scatter(pools[l], layout, n, k.astype(np.float16).reshape(B, H, d), v.astype(np.float16).reshape(B, H, d))
+            t = oa.decode_attn(q.reshape(B, H, d), pools[l], layout, n, H)
+            t = dl.round16(np.asarray(t).reshape(B, h1))
+            x_ref = dl.after_attention(x_ref, t, p, fp16_between=True)
+        close(x.float().cpu().numpy(), x_ref, atol=1.5e-2, rtol=1.5e-2, what=f"step {step}")
+        # the cache holds the keys and values the oracle's projections produce (fp16 rounding decisions may differ by an ulp)
+        for l in range(L):
+            got = st.read_pool(l).astype(np.float64)
+            assert np.abs(got - pools[l].astype(np.float64)).max() < 2e-2
+    st.close()

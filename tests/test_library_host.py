@@ -30,6 +30,27 @@ def test_library_loads_and_exports_every_declared_symbol():
     assert sorted(binding.EXPORTS) == decl
 
 
+def test_layer_header_symbols_are_exported():
+    text = open(os.path.join(ROOT, "include", "okv_layer.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    decl = sorted(set(re.findall(r"\b(okv_[a-z_0-9]+)\s*\(", text)))
+    lib = binding.lib()
+    for name in decl:
+        assert hasattr(lib, name), name
+    assert decl == sorted(binding.LAYER_EXPORTS)
+    # argument checks need no GPU
+    for bad in (dict(m=0), dict(m=129), dict(n_out=24), dict(n_in=48), dict(n_seg=4), dict(n_seg=3, n_out=64)):
+        kw = dict(m=4, n_out=96, n_in=64, n_seg=1)
+        kw.update(bad)
+        with pytest.raises(binding.OkvError) as e:
+            binding.okv_linear(16, 16, None, None, [16] * kw["n_seg"], kw["m"], kw["n_out"], kw["n_in"])
+        assert e.value.code == binding.OKV_EINVAL
+    with pytest.raises(binding.OkvError):
+        binding.okv_layernorm(16, 16, 16, 16, 4, 100)           # h not a multiple of 8
+    with pytest.raises(binding.OkvError):
+        binding.okv_pack_linear_weight(16, 32, 100, 64)         # n_out not a multiple of 16
+
+
 def test_plan_matches_oracle_brute_force():
     for L in range(1, 65):
         for den in range(1, 33):
