@@ -457,6 +457,81 @@ def run_prefill(args):
     return res
 
 
+def run_layers(args):
+    """Whole decoder layers in the decode stage: the headline stack (32 layers, hidden 4096,
+    feed-forward 16384, batch 32, context 513 upwards) with random weights; per step every
+    layer reads its 402 MB of weights and its share of the KV cache once.  Also times each
+    linear product alone."""
+    import torch
+    from paper_2504_11816_amd import binding, synth
+    from paper_2504_11816_amd.harness import LayerScratch, LayerWeights, Stack, decode_step_with_layers
+    w = dict(synth.WORKLOADS["cfg2"])
+    L, H, G, d, B = w["L"], w["H"], w["G"], w["d"], w["B"]
+    if args.layers:
+        L = min(L, args.layers)
+    h1, h2 = H * d, 4 * H * d
+    steps, warmup = args.layer_steps, 4
+    ctx0 = np.full(B, w["ctx"] - 1, dtype=np.int32)
+    st = Stack(L=L, H=H, G=G, d=d, B=B, T=0, cap_tokens=int(ctx0.max()) + steps + warmup + 1, out_dtype=0)
+    for l in range(L):
+        st.fill_pool(l, synth.stream_seed(args.seed, synth.TENSOR_POOL, l))
+    weights = [LayerWeights(h1, h2, args.seed, l, st.device) for l in range(L)]
+    scratch = LayerScratch(B, h1, h2, G, d, st.device)
+    x0 = synth.randn_f16_torch((B, h1), synth.stream_seed(args.seed, synth.TENSOR_Q), st.device)
+    x = x0.clone()
+
+    def run(n):
+        for _ in range(n):
+            x.copy_(x0)                    # keep the activations at the scale of the inputs (random weights amplify)
+            decode_step_with_layers(st, weights, scratch, x)
+    st.set_batch(ctx0, None)
+    with torch.cuda.stream(st.compute_stream):
+        run(warmup)
+        st.synchronize()
+        st.set_batch(ctx0, None)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        run(steps)
+        st.synchronize()
+        torch.cuda.synchronize()
+        dt = time.perf_counter() - t0
+    kv_bytes = kv_bytes_of_steps(ctx0, steps, G, d, L)
+    w_bytes = sum(wt.bytes_read_per_step() for wt in weights) * steps
+    # each product alone, 50 launches back to back
+    cs = st.compute_stream
+    alone = {}
+    wt = weights[0]
+    for name, fn, nbytes in (
+            ("qkv 12288x4096", lambda: binding.okv_linear(scratch.a, wt.packed["wqkv"], wt.bqkv, None, [scratch.q, scratch.k, scratch.v], B, 3 * h1, h1, False, cs.cuda_stream, scratch.ws, scratch.ws_bytes), 3 * h1 * h1 * 2),
+            ("out 4096x4096", lambda: binding.okv_linear(scratch.t, wt.packed["wo"], wt.t["bo"], scratch.z, scratch.y, B, h1, h1, False, cs.cuda_stream, scratch.ws, scratch.ws_bytes), h1 * h1 * 2),
+            ("ffn1 16384x4096", lambda: binding.okv_linear(scratch.z, wt.packed["w1"], wt.t["b1"], None, scratch.u, B, h2, h1, True, cs.cuda_stream, scratch.ws, scratch.ws_bytes), h1 * h2 * 2),
+            ("ffn2 4096x16384", lambda: binding.okv_linear(scratch.u, wt.packed["w2"], wt.t["b2"], scratch.z, scratch.y, B, h1, h2, False, cs.cuda_stream, scratch.ws, scratch.ws_bytes), h1 * h2 * 2)):
+        fn()
+        cs.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record(cs)
+        for _ in range(50):
+            fn()
+        e1.record(cs)
+        cs.synchronize()
+        us = e0.elapsed_time(e1) / 50 * 1e3
+        alone[name] = {"us": us, "weight_gbps": nbytes / us / 1e3}
+    res = {
+        "workload": f"{L} decoder layers, hidden {h1}, feed-forward {h2}, batch {B}, context {w['ctx']}..{w['ctx'] + steps - 1}, random weights",
+        "steps": steps, "tokens_per_s": B * steps / dt, "ms_per_step": dt / steps * 1e3,
+        "weight_gb_per_step": w_bytes / steps / 1e9, "kv_gb_per_step": kv_bytes / steps / 1e9,
+        "hbm_gbps": (w_bytes + kv_bytes) / dt / 1e9, "hbm_frac": (w_bytes + kv_bytes) / dt / 1e9 / HBM_PEAK_GBPS,
+        "linear_alone": alone,
+    }
+    log(f"[bench] decoder layers: {res['ms_per_step']:.2f} ms/step, {res['tokens_per_s']:.0f} tokens/s, "
+        f"{res['hbm_gbps']:.0f} GB/s of weights + KV ({100 * res['hbm_frac']:.1f}% of HBM peak); products alone: "
+        + ", ".join(f"{k} {v['us']:.1f} us = {v['weight_gbps']:.0f} GB/s" for k, v in alone.items()))
+    st.close()
+    del st, weights, scratch
+    torch.cuda.empty_cache()
+    return res
+
+
 def run_model(args, off):
     """The paper's prediction model on this GPU's own numbers (§IV-D, §IV-F): the decode
     attention time per layer is measured at several batch sizes, the calibration line
@@ -545,6 +620,8 @@ def main():
     ap.add_argument("--staging", type=int, default=2, help="staging buffers for host layers (1..4)")
     ap.add_argument("--no-blocks", action="store_true", help="skip the block-granular offloaded leg")
     ap.add_argument("--no-model", action="store_true", help="skip the prediction-model leg")
+    ap.add_argument("--no-decoder", action="store_true", help="skip the whole-decoder-layer leg")
+    ap.add_argument("--layer-steps", type=int, default=32, help="decoder-layer leg: decode steps to time")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill-side store leg")
     ap.add_argument("--prefill-table", default="ordered", choices=["ordered", "shuffled"],
                     help="prefill leg: how the block table hands out blocks")
@@ -567,6 +644,7 @@ def main():
     off_blocks = None if (args.no_offload or args.no_blocks) else run_offload_blocks(args)
     prefill = None if (args.no_offload or args.no_prefill) else run_prefill(args)
     model = None if args.no_model else run_model(args, off)
+    layers = None if args.no_decoder else run_layers(args)
     line = {
         "metric": "decode_attn_tokens_per_s", "value": res["tokens_per_s"], "unit": "tokens/s",
         "n_gpus": 1, "steps": res["steps"], "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
@@ -587,6 +665,7 @@ def main():
         "offload_blocks": off_blocks,
         "prefill_store": prefill,
         "model": model,
+        "decoder_layers": layers,
     }
     if probe:
         line["probe"] = probe

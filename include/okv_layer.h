@@ -47,11 +47,24 @@ int okv_pack_linear_weight(void *dst, const void *src, int32_t n_out, int32_t n_
  *             is written as fp16 [m][n_out / n_seg] to out[s] -- one product for the query,
  *             key and value projections, each landing in a tensor of its own
  *   relu      1: act = max(., 0); 0: act = identity
+ *   workspace DEVICE scratch memory of at least okv_linear_workspace_bytes(m, n_out, n_in)
+ *             bytes (workspace_bytes says how much there is); its contents before and
+ *             after the call mean nothing.  Calls that may run at the same time (different
+ *             streams) need workspaces of their own.  When n_in is a multiple of 512 the
+ *             fast kernel runs: the input dimension is cut across workgroups, their fp32
+ *             shares go through the workspace and a second small kernel adds them in a
+ *             fixed order (results do not vary from run to run).  With another n_in, or
+ *             when a cut is wanted and the workspace is NULL or too small, a simpler,
+ *             slower kernel runs that needs no workspace.
  * Products accumulate in fp32 on the matrix cores; the result is rounded to fp16 once.
  * residual may alias out[0] (each element is read before it is written, by the same lane). */
 int okv_linear(const void *x, const void *w_packed, const void *bias, const void *residual,
                void *const *out, int32_t n_seg, int32_t m, int32_t n_out, int32_t n_in,
-               int32_t relu, void *stream);
+               int32_t relu, void *workspace, int64_t workspace_bytes, void *stream);
+
+/* Bytes of workspace okv_linear wants for this shape on the current device (0 if it
+ * would not use one); < 0 on a bad shape. */
+int64_t okv_linear_workspace_bytes(int32_t m, int32_t n_out, int32_t n_in);
 
 /* out[i] = (x[i] - mean_i) / sqrt(var_i + eps) * gamma + beta for each of m rows of h
  * numbers (population variance; statistics in fp32).

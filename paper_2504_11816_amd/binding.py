@@ -28,7 +28,7 @@ EXPORTS = [
 
 
 # every symbol include/okv_layer.h declares (same library)
-LAYER_EXPORTS = ["okv_pack_linear_weight", "okv_linear", "okv_layernorm"]
+LAYER_EXPORTS = ["okv_pack_linear_weight", "okv_linear", "okv_linear_workspace_bytes", "okv_layernorm"]
 
 
 class OkvError(RuntimeError):
@@ -99,7 +99,8 @@ def lib():
             "okv_time_copies": (ctypes.c_int, [P, ctypes.POINTER(ctypes.c_double)]),
             "okv_probe_copy": (ctypes.c_int, [P, P, I64, P]),
             "okv_pack_linear_weight": (ctypes.c_int, [P, P, I32, I32, P]),
-            "okv_linear": (ctypes.c_int, [P, P, P, P, ctypes.POINTER(P), I32, I32, I32, I32, I32, P]),
+            "okv_linear": (ctypes.c_int, [P, P, P, P, ctypes.POINTER(P), I32, I32, I32, I32, I32, P, I64, P]),
+            "okv_linear_workspace_bytes": (I64, [I32, I32, I32]),
             "okv_layernorm": (ctypes.c_int, [P, P, P, P, I32, I32, ctypes.c_float, P]),
             "okv_probe_read": (ctypes.c_int, [P, I64, P, P]),
         }
@@ -224,12 +225,20 @@ def okv_pack_linear_weight(dst, src, n_out, n_in, stream=0):
     _check(lib().okv_pack_linear_weight(_ptr(dst), _ptr(src), n_out, n_in, _ptr(stream)))
 
 
-def okv_linear(x, w_packed, bias, residual, out, m, n_out, n_in, relu=False, stream=0):
+def okv_linear(x, w_packed, bias, residual, out, m, n_out, n_in, relu=False, stream=0, workspace=None,
+               workspace_bytes=0):
     """out: one tensor, or a list of 1..3 tensors that share the n_out output features equally."""
     outs = list(out) if isinstance(out, (list, tuple)) else [out]
     arr = (ctypes.c_void_p * len(outs))(*[_ptr(o) for o in outs])
     _check(lib().okv_linear(_ptr(x), _ptr(w_packed), _ptr(bias), _ptr(residual), arr, len(outs), m, n_out, n_in,
-                            1 if relu else 0, _ptr(stream)))
+                            1 if relu else 0, _ptr(workspace), workspace_bytes, _ptr(stream)))
+
+
+def okv_linear_workspace_bytes(m, n_out, n_in):
+    r = lib().okv_linear_workspace_bytes(m, n_out, n_in)
+    if r < 0:
+        _check(int(r))
+    return int(r)
 
 
 def okv_layernorm(x, gamma, beta, out, m, h, eps=1e-5, stream=0):

@@ -1344,8 +1344,26 @@ int okv_pack_linear_weight(void *dst, const void *src, int32_t n_out, int32_t n_
   return OKV_OK;
 }
 
+namespace {
+int device_cus() {
+  static int cus = 0;                                   // one device per process in practice; re-read if it ever reports 0
+  if (cus <= 0) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0)
+      cus = 256;
+  }
+  return cus;
+}
+}  // namespace
+
+int64_t okv_linear_workspace_bytes(int32_t m, int32_t n_out, int32_t n_in) {
+  if (m < 1 || m > OKV_LINEAR_MAX_ROWS || n_out < 16 || n_out % 16 || n_in < 32 || n_in % 32)
+    return fail(nullptr, OKV_EINVAL, "okv_linear_workspace_bytes: bad shape");
+  return okv::linear_workspace_bytes(m, n_out, n_in, device_cus());
+}
+
 int okv_linear(const void *x, const void *w_packed, const void *bias, const void *residual, void *const *out, int32_t n_seg,
-               int32_t m, int32_t n_out, int32_t n_in, int32_t relu, void *stream) {
+               int32_t m, int32_t n_out, int32_t n_in, int32_t relu, void *workspace, int64_t workspace_bytes, void *stream) {
   if (!x || !w_packed || !out || !aligned16(x) || !aligned16(w_packed)) return fail(nullptr, OKV_EINVAL, "okv_linear: NULL or misaligned pointer");
   if (m < 1 || m > OKV_LINEAR_MAX_ROWS) return fail(nullptr, OKV_EINVAL, "okv_linear: m = %d outside [1, %d]", m, OKV_LINEAR_MAX_ROWS);
   if (n_out < 16 || n_out % 16 || n_in < 32 || n_in % 32 || n_in > (1 << 20))
@@ -1360,6 +1378,10 @@ int okv_linear(const void *x, const void *w_packed, const void *bias, const void
     if (s < n_seg && !out[s]) return fail(nullptr, OKV_EINVAL, "okv_linear: out[%d] is NULL", s);
   }
   l.n_seg = n_seg, l.m = m, l.n_out = n_out, l.n_in = n_in, l.relu = relu;
+  if (workspace && (!aligned16(workspace) || workspace_bytes < 0)) return fail(nullptr, OKV_EINVAL, "okv_linear: workspace misaligned");
+  l.workspace = workspace;
+  l.workspace_bytes = workspace_bytes;
+  l.n_cus = device_cus();
   OKV_HIP(nullptr, okv::launch_linear(l, static_cast<hipStream_t>(stream)));
   return OKV_OK;
 }

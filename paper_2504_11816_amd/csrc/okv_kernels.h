@@ -100,8 +100,12 @@ struct LinearLaunch {
   const void *x, *w_packed, *bias, *residual;
   void *out[3];
   int32_t n_seg, m, n_out, n_in, relu;
+  void *workspace;             // counters (zero between launches) + fp32 shares, or NULL: simple kernel
+  int64_t workspace_bytes;
+  int32_t n_cus;               // compute units of the device (decides how the input dimension is cut)
 };
 hipError_t launch_linear(const LinearLaunch &l, hipStream_t stream);
+int64_t linear_workspace_bytes(int32_t m, int32_t n_out, int32_t n_in, int32_t n_cus);
 hipError_t launch_pack_weight(void *dst, const void *src, int32_t n_out, int32_t n_in, hipStream_t stream);
 hipError_t launch_layernorm(const void *x, const void *gamma, const void *beta, void *out, int32_t m, int32_t h, float eps,
                             hipStream_t stream);

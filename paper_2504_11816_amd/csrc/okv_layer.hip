@@ -11,14 +11,26 @@
 //   * weights are stored pre-arranged (okv_pack_linear_weight) so that one load instruction
 //     brings a wavefront the 1 KiB it feeds to two matrix-core instructions: 16 output
 //     features x 32 inputs, lane l holding feature l % 16, inputs 8 (l / 16) .. + 7;
-//   * a workgroup owns 16 output features; its 8 wavefronts split the input dimension, each
-//     streaming its share of the weights kDepth pieces ahead, and add up through LDS, so no
-//     partial sums ever go to HBM and the epilogue (bias, ReLU, residual, rounding to fp16,
-//     scatter into up to three output tensors) runs in the same kernel;
-//   * the rows of x (a few hundred KiB, resident in L2) are fetched per lane in the layout
-//     the matrix core wants, the same distance ahead as the weights: the vector memory
-//     counter retires loads in order, so a shorter distance for x would drain the weights'
-//     queue every iteration.
+//   * beyond 16 rows, the rows of x must NOT be fetched per lane in the layout the matrix core
+//     wants: such a gather touches 16 half cache lines per instruction, every workgroup needs
+//     all of x, and the time grew by 14 us per 16 rows of batch on a 128 MiB matrix (21 us with
+//     16 rows, 36 with 32, 119 with 128) although x sits in L2.  So in the fast kernel a
+//     workgroup of 4 wavefronts takes 64 output features (one 16-feature tile per wavefront)
+//     over one stretch of the input dimension, and a fifth wavefront stages the rows of x for
+//     that stretch chunk by chunk in LDS (double buffered, one barrier per 256 inputs), from
+//     where the four read their operands: 28 us with 32 rows, 35 with 64, 54 with 128.  The
+//     staging has a wavefront of its own because the vector memory counter retires loads in
+//     order: a wavefront that waited for staged rows would also wait for the weight pieces
+//     it issued before them;
+//   * the input dimension is cut across workgroups so that the launch has one per compute
+//     unit (longer-lived workgroups measured faster than more of them); each writes its fp32
+//     share of the tile and a small second kernel adds the shares in a fixed order and applies
+//     the epilogue (bias, ReLU, residual, rounding to fp16, scatter into up to three output
+//     tensors).  A hand-over inside the kernel (last workgroup adds up) needs device-wide
+//     fences, which on this GPU write back and invalidate the L2 caches: 75 us instead of 11;
+//   * up to 16 rows, and shapes the fast kernel does not take (input dimension not a multiple
+//     of 256), run the simple kernel: a workgroup per 16 features, its wavefronts split the
+//     inputs and add up through LDS, x by gather (6.3-6.5 TB/s at up to 16 rows).
 #include "okv_kernels.h"
 
 #include <algorithm>
@@ -30,11 +42,20 @@ namespace {
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
-constexpr int kLinWaves = 8;
+#ifndef OKV_LIN_DEPTH
+#define OKV_LIN_DEPTH 8
+#endif
+#ifndef OKV_LIN_WG_PER_CU
+#define OKV_LIN_WG_PER_CU 1
+#endif
+#ifndef OKV_LIN_WAVES
+#define OKV_LIN_WAVES 4
+#endif
+constexpr int kLinWaves = OKV_LIN_WAVES;
 
 template <int MF>
 constexpr int lin_depth() {
-  return MF <= 2 ? 8 : MF <= 4 ? 4 : 2;       // pieces in flight: bounded by the registers x needs beside them
+  return MF <= 2 ? OKV_LIN_DEPTH : MF <= 4 ? OKV_LIN_DEPTH / 2 : OKV_LIN_DEPTH / 4;   // pieces in flight: bounded by the registers x needs beside them
 }
 
 struct LinearArgs {
@@ -43,6 +64,8 @@ struct LinearArgs {
   const _Float16 *bias, *residual;
   _Float16 *out[3];
   int32_t m, n_in, n_kb, seg_cols, relu;
+  int32_t n_tiles, n_out, splits;   // fast path: 16-feature tiles, cuts of the input dimension
+  float *shares;                    // fast path, splits > 1: [splits][m][n_out] fp32
 };
 
 __device__ __forceinline__ floatx4 mfma16(const uint2 a, const uint2 b, floatx4 c) {
@@ -73,10 +96,18 @@ __global__ __launch_bounds__(kLinWaves * 64) void linear_kernel(const LinearArgs
   for (int f = 0; f < MF; ++f) acc[f] = floatx4{0.f, 0.f, 0.f, 0.f};
 
   uint4 wbuf[D], xbuf[D][MF];
-  auto load = [&](int slot, int k) {                           // k: block index relative to kb0
-    wbuf[slot] = wp[(size_t)k * 64];
+  // Every wavefront walks its blocks from a different starting point (and wraps around).  All
+  // ranges have the same length and all wavefronts advance at the same pace, so without the
+  // shift every wavefront of the launch would be reading addresses that are equal modulo the
+  // range length at any moment, i.e. from a few of the memory channels at a time: measured
+  // 3.4-3.9 TB/s without against OKV_SKEW_RESULT with.
+  const int rot = nk > 0 ? (int)(((unsigned)ntile * 5u + (unsigned)wave * 11u) % (unsigned)nk) : 0;
+  auto load = [&](int slot, int k) {                           // k: position in this wavefront's walk
+    int kk = k + rot;
+    kk = kk >= nk ? kk - nk : kk;                              // block index relative to kb0
+    wbuf[slot] = wp[(size_t)kk * 64];
 #pragma unroll
-    for (int f = 0; f < MF; ++f) xbuf[slot][f] = xp[f][(size_t)k * 4];
+    for (int f = 0; f < MF; ++f) xbuf[slot][f] = xp[f][(size_t)kk * 4];
   };
   auto use = [&](int slot) {
     const uint4 w = wbuf[slot];
@@ -139,6 +170,140 @@ __global__ __launch_bounds__(kLinWaves * 64) void linear_kernel(const LinearArgs
     if (a.residual) v += (float)a.residual[at];
     a.out[seg][at] = (_Float16)v;
   }
+}
+
+// Fast path: kLinWaves wavefronts x 16 features, x staged in LDS by one more wavefront, input
+// dimension cut across workgroups.
+// 32-input blocks per staged chunk = weight pieces (1 KiB) in flight per wavefront; bounded by the LDS the
+// two x buffers take (2 x chunk x 16 MF rows x 64 bytes): 64 KiB at most.
+#ifndef OKV_LIN_CHUNK
+#define OKV_LIN_CHUNK 8
+#endif
+constexpr int lin_chunk(int mf) { return mf <= 2 ? OKV_LIN_CHUNK : mf <= 4 ? 8 : 4; }
+constexpr int kFastThreads = (kLinWaves + 1) * 64;
+constexpr int kTileCols = kLinWaves * 16;      // output features of a workgroup
+
+// waves_per_eu: without the hint the compiler aims at the occupancy that the LDS footprint would allow and
+// caps the kernel at 64 registers.
+template <int MF>
+__global__ __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(2, 4))) void linear_lds_kernel(const LinearArgs a) {
+  constexpr int C = lin_chunk(MF);
+  // x chunk in the order the matrix core reads it: xs[buffer][block][row fragment][lane] 16-byte pieces;
+  // after the last chunk the same memory holds the fp32 tile [16 MF rows][kTileCols features] for the epilogue
+  __shared__ uint4 xs[2][C][MF][64];
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int group = blockIdx.x, cut = blockIdx.y;
+  const int nk = a.n_kb / a.splits, kb0 = cut * nk, n_chunks = nk / C;
+  floatx4 acc[MF];
+#pragma unroll
+  for (int f = 0; f < MF; ++f) acc[f] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+  if (wave == kLinWaves) {
+    // The staging wavefront.  Its loads have a counter of their own, so waiting for them never
+    // holds up the weight stream of the others.  One load per (block, row fragment) writes
+    // straight into LDS, 16 bytes per lane, lane l landing in slot l: lane l fetches row
+    // 16 f + l % 16, inputs 8 (l / 16) .. + 7 of the block -- the order the matrix core reads.  (This is
+    // the half-line gather that was too dear once per wavefront; here it happens once per workgroup.)
+    const int row_pieces = a.n_in >> 3;
+    const uint4 *xg[MF];
+#pragma unroll
+    for (int f = 0; f < MF; ++f)     // rows past the batch read row 0: they only reach result rows that are not stored
+      xg[f] = a.x + (size_t)(f * 16 + (lane & 15) < a.m ? f * 16 + (lane & 15) : 0) * row_pieces + (size_t)kb0 * 4 + (lane >> 4);
+    auto stage = [&](int chunk, int buf) {
+#pragma unroll
+      for (int i = 0; i < C; ++i)
+#pragma unroll
+        for (int f = 0; f < MF; ++f)
+          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(xg[f] + ((size_t)chunk * C + i) * 4),
+                                           (__attribute__((address_space(3))) void *)&xs[buf][i][f][0], 16, 0, 0);
+    };
+    stage(0, 0);
+    __syncthreads();
+    for (int c = 0; c < n_chunks; ++c) {
+      if (c + 1 < n_chunks) stage(c + 1, (c + 1) & 1);       // nobody reads that buffer between these two barriers
+      __syncthreads();
+    }
+  } else {
+    const int ntile = group * kLinWaves + wave;
+    // a wavefront past the last tile streams tile 0 (valid memory) and never stores
+    const uint4 *wp = a.w + ((size_t)(ntile < a.n_tiles ? ntile : 0) * a.n_kb + kb0) * 64 + lane;
+    uint4 wbuf[C];
+#pragma unroll
+    for (int i = 0; i < C; ++i) {                            // oldest first: the loop waits for them in this order
+      wbuf[i] = wp[(size_t)i * 64];
+      __builtin_amdgcn_sched_barrier(0);
+    }
+    __syncthreads();
+    for (int c = 0; c < n_chunks; ++c) {
+      // the chunk after this one (the last chunk is fetched once more instead of branching: loads in
+      // this loop stay unconditional, so the waits stay exact)
+      const int cn = c + 1 < n_chunks ? c + 1 : c;
+      const int buf = c & 1;
+#pragma unroll
+      for (int i = 0; i < C; ++i) {
+        const uint4 w = wbuf[i];
+#pragma unroll
+        for (int f = 0; f < MF; ++f) {
+          const uint4 x = xs[buf][i][f][lane];
+          acc[f] = mfma16(make_uint2(x.x, x.y), make_uint2(w.x, w.y), acc[f]);
+          acc[f] = mfma16(make_uint2(x.z, x.w), make_uint2(w.z, w.w), acc[f]);
+        }
+        __builtin_amdgcn_sched_barrier(0);
+        wbuf[i] = wp[((size_t)cn * C + i) * 64];
+        __builtin_amdgcn_sched_barrier(0);
+      }
+      __syncthreads();
+    }
+  }
+
+  // this workgroup's share of the tile [16 MF][128] in LDS (all reads of xs are behind the barrier above):
+  // result element (row 16 f + 4 (lane / 16) + r, feature 16 wave + lane % 16) sits in acc[f][r]
+  float *tile = reinterpret_cast<float *>(&xs[0][0][0][0]);
+  if (wave < kLinWaves) {
+#pragma unroll
+    for (int f = 0; f < MF; ++f)
+#pragma unroll
+      for (int r = 0; r < 4; ++r) tile[(f * 16 + 4 * (lane >> 4) + r) * kTileCols + wave * 16 + (lane & 15)] = acc[f][r];
+  }
+  __syncthreads();
+  const int n0 = group * kTileCols;
+  if (a.splits > 1) {                                  // this cut's share; reduce_epilogue_kernel adds them up
+    float *mine = a.shares + (size_t)cut * a.m * a.n_out;
+    for (int o = tid; o < a.m * kTileCols; o += kFastThreads) {
+      const int mrow = o / kTileCols, n = n0 + o % kTileCols;
+      if (n < a.n_out) mine[(size_t)mrow * a.n_out + n] = tile[o];
+    }
+    return;
+  }
+  for (int o = tid; o < a.m * kTileCols; o += kFastThreads) {
+    const int mrow = o / kTileCols, n = n0 + o % kTileCols;
+    if (n >= a.n_out) continue;
+    float v = tile[o];
+    if (a.bias) v += (float)a.bias[n];
+    if (a.relu) v = fmaxf(v, 0.f);
+    const int seg = n / a.seg_cols, col = n - seg * a.seg_cols;
+    const size_t at = (size_t)mrow * a.seg_cols + col;
+    if (a.residual) v += (float)a.residual[at];
+    a.out[seg][at] = (_Float16)v;
+  }
+}
+
+// Adds the cuts' shares in a fixed order and applies the epilogue; one thread per output element, a
+// workgroup per 256 consecutive features of a row.  A launch of its own rather than a hand-over inside
+// the product kernel: a workgroup that reads what other workgroups wrote needs device-wide fences, and on
+// this GPU those write back and invalidate the L2 caches (measured: 75 us instead of 11 for a 32 MiB matrix).
+__global__ __launch_bounds__(256) void reduce_epilogue_kernel(const LinearArgs a) {
+  const int n = blockIdx.x * 256 + threadIdx.x, mrow = blockIdx.y;
+  if (n >= a.n_out) return;
+  float v = 0.f;
+  for (int s2 = 0; s2 < a.splits; ++s2) v += a.shares[((size_t)s2 * a.m + mrow) * a.n_out + n];
+  if (a.bias) v += (float)a.bias[n];
+  if (a.relu) v = fmaxf(v, 0.f);
+  const int seg = n / a.seg_cols, col = n - seg * a.seg_cols;
+  const size_t at = (size_t)mrow * a.seg_cols + col;
+  if (a.residual) v += (float)a.residual[at];
+  a.out[seg][at] = (_Float16)v;
 }
 
 // dst piece (block (nt, kb), lane) = src[16 nt + lane % 16][32 kb + 8 (lane / 16) .. + 7]
@@ -215,12 +380,44 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint4 *x, c
 }
 
 template <int MF>
-hipError_t launch_linear_mf(const LinearArgs &args, int n_tiles, hipStream_t stream) {
-  hipLaunchKernelGGL(linear_kernel<MF>, dim3(n_tiles), dim3(kLinWaves * 64), 0, stream, args);
+hipError_t launch_linear_mf(const LinearArgs &args, int n_tiles, bool fast, hipStream_t stream) {
+  if (fast) {
+    dim3 grid((n_tiles + kLinWaves - 1) / kLinWaves, args.splits);
+    hipLaunchKernelGGL(linear_lds_kernel<MF>, grid, dim3(kFastThreads), 0, stream, args);
+    if (args.splits > 1) {
+      hipError_t e = hipGetLastError();
+      if (e != hipSuccess) return e;
+      hipLaunchKernelGGL(reduce_epilogue_kernel, dim3((args.n_out + 255) / 256, args.m), dim3(256), 0, stream, args);
+    }
+  } else {
+    hipLaunchKernelGGL(linear_kernel<MF>, dim3(n_tiles), dim3(kLinWaves * 64), 0, stream, args);
+  }
   return hipGetLastError();
 }
 
 }  // namespace
+
+// How many ways the input dimension is cut: enough workgroups for two per compute unit, as long
+// as every cut keeps at least two chunks, and only cuts that divide the chunks evenly.
+int linear_splits(int32_t m, int32_t n_out, int32_t n_in, int32_t n_cus) {
+  const int chunk = lin_chunk((m + 15) / 16);
+  if (n_in % (32 * chunk)) return 0;                           // not a fast-path shape
+  const int chunks = n_in / (32 * chunk);
+  const int groups = (n_out / 16 + kLinWaves - 1) / kLinWaves;
+  int best = 1;
+  for (int s = 1; s <= chunks; ++s) {
+    if (chunks % s) continue;
+    if (s > 1 && chunks / s < 2) break;
+    best = s;
+    if ((int64_t)groups * s >= OKV_LIN_WG_PER_CU * (int64_t)n_cus) break;
+  }
+  return best;
+}
+
+int64_t linear_workspace_bytes(int32_t m, int32_t n_out, int32_t n_in, int32_t n_cus) {
+  const int s = m > 16 ? linear_splits(m, n_out, n_in, n_cus) : 0;
+  return s <= 1 ? 0 : (int64_t)s * m * n_out * 4;
+}
 
 hipError_t launch_linear(const LinearLaunch &l, hipStream_t stream) {
   LinearArgs a;
@@ -235,15 +432,26 @@ hipError_t launch_linear(const LinearLaunch &l, hipStream_t stream) {
   a.seg_cols = l.n_out / l.n_seg;
   a.relu = l.relu;
   const int n_tiles = l.n_out / 16;
+  a.n_tiles = n_tiles;
+  a.n_out = l.n_out;
+  a.splits = 1;
+  a.shares = nullptr;
+  bool fast = false;
+  const int s = linear_splits(l.m, l.n_out, l.n_in, l.n_cus);
+  if (l.m > 16 && (s == 1 || (s > 1 && l.workspace && l.workspace_bytes >= linear_workspace_bytes(l.m, l.n_out, l.n_in, l.n_cus)))) {
+    fast = true;
+    a.splits = s;
+    a.shares = static_cast<float *>(l.workspace);
+  }
   switch ((l.m + 15) / 16) {
-    case 1: return launch_linear_mf<1>(a, n_tiles, stream);
-    case 2: return launch_linear_mf<2>(a, n_tiles, stream);
-    case 3: return launch_linear_mf<3>(a, n_tiles, stream);
-    case 4: return launch_linear_mf<4>(a, n_tiles, stream);
-    case 5: return launch_linear_mf<5>(a, n_tiles, stream);
-    case 6: return launch_linear_mf<6>(a, n_tiles, stream);
-    case 7: return launch_linear_mf<7>(a, n_tiles, stream);
-    case 8: return launch_linear_mf<8>(a, n_tiles, stream);
+    case 1: return launch_linear_mf<1>(a, n_tiles, fast, stream);
+    case 2: return launch_linear_mf<2>(a, n_tiles, fast, stream);
+    case 3: return launch_linear_mf<3>(a, n_tiles, fast, stream);
+    case 4: return launch_linear_mf<4>(a, n_tiles, fast, stream);
+    case 5: return launch_linear_mf<5>(a, n_tiles, fast, stream);
+    case 6: return launch_linear_mf<6>(a, n_tiles, fast, stream);
+    case 7: return launch_linear_mf<7>(a, n_tiles, fast, stream);
+    case 8: return launch_linear_mf<8>(a, n_tiles, fast, stream);
   }
   return hipErrorInvalidValue;
 }

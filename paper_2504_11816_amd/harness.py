@@ -287,6 +287,10 @@ class LayerScratch:
             return torch.empty(shape, dtype=torch.float16, device=device)
         self.a, self.q, self.k, self.v = buf(B, h1), buf(B, h1), buf(B, G * d), buf(B, G * d)
         self.t, self.y, self.z, self.u = buf(B, h1), buf(B, h1), buf(B, h1), buf(B, h2)
+        # one workspace for the four products of a layer (they follow one another on one stream)
+        self.ws_bytes = max(16, max(binding.okv_linear_workspace_bytes(B, n_out, n_in)
+                                    for n_out, n_in in ((3 * h1, h1), (h1, h1), (h2, h1), (h1, h2))))
+        self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
 
 
 def decode_step_with_layers(st, weights, scratch, x):
@@ -301,13 +305,13 @@ def decode_step_with_layers(st, weights, scratch, x):
     c.okv_step_begin()
     for l, w in enumerate(weights):
         binding.okv_layernorm(x, w.t["ln1_g"], w.t["ln1_b"], s.a, B, h1, 1e-5, cs)
-        binding.okv_linear(s.a, w.packed["wqkv"], w.bqkv, None, [s.q, s.k, s.v], B, 3 * h1, h1, False, cs)
+        binding.okv_linear(s.a, w.packed["wqkv"], w.bqkv, None, [s.q, s.k, s.v], B, 3 * h1, h1, False, cs, s.ws, s.ws_bytes)
         c.kv_append(l, s.k, s.v)
         c.decode_attn(l, s.q, s.t)
-        binding.okv_linear(s.t, w.packed["wo"], w.t["bo"], x, s.y, B, h1, h1, False, cs)
+        binding.okv_linear(s.t, w.packed["wo"], w.t["bo"], x, s.y, B, h1, h1, False, cs, s.ws, s.ws_bytes)
         binding.okv_layernorm(s.y, w.t["ln2_g"], w.t["ln2_b"], s.z, B, h1, 1e-5, cs)
-        binding.okv_linear(s.z, w.packed["w1"], w.t["b1"], None, s.u, B, h2, h1, True, cs)
-        binding.okv_linear(s.u, w.packed["w2"], w.t["b2"], s.y, x, B, h1, h2, False, cs)
+        binding.okv_linear(s.z, w.packed["w1"], w.t["b1"], None, s.u, B, h2, h1, True, cs, s.ws, s.ws_bytes)
+        binding.okv_linear(s.u, w.packed["w2"], w.t["b2"], s.y, x, B, h1, h2, False, cs, s.ws, s.ws_bytes)
     c.okv_step_end()
     if st.ctx_lens is not None:
         st.ctx_lens += 1

@@ -58,7 +58,17 @@ def test_weight_rearrangement_is_bit_exact(n_out, n_in):
     np.testing.assert_array_equal(dst.cpu().numpy().reshape(-1).view(np.uint16), packed_layout(w.cpu().numpy()).view(np.uint16))
 
 
-def run_linear(m, n_out, n_in, seed, bias=True, relu=False, residual=False, n_seg=1):
+_WS = {}
+
+
+def workspace(nbytes):
+    """A workspace of at least nbytes, shared by the tests (calls follow one another)."""
+    if "t" not in _WS or _WS["t"].numel() < nbytes:
+        _WS["t"] = torch.empty(max(nbytes, 1 << 22), dtype=torch.uint8, device=DEV)
+    return _WS["t"]
+
+
+def run_linear(m, n_out, n_in, seed, bias=True, relu=False, residual=False, n_seg=1, fast=True):
     x = synth.randn_f16_torch((m, n_in), synth.stream_seed(seed, 1), DEV)
     w = (synth.randn_f16_torch((n_out, n_in), synth.stream_seed(seed, 2), DEV).float() / n_in ** 0.5).to(torch.float16)
     b = synth.randn_f16_torch((n_out,), synth.stream_seed(seed, 3), DEV) if bias else None
@@ -66,8 +76,15 @@ def run_linear(m, n_out, n_in, seed, bias=True, relu=False, residual=False, n_se
     wp = torch.empty_like(w)
     binding.okv_pack_linear_weight(wp, w, n_out, n_in)
     outs = [torch.full((m, n_out // n_seg), float("nan"), dtype=torch.float16, device=DEV) for _ in range(n_seg)]
-    binding.okv_linear(x, wp, b, r, outs, m, n_out, n_in, relu)
-    torch.cuda.synchronize()
+    if fast:
+        nb = binding.okv_linear_workspace_bytes(m, n_out, n_in)
+        ws = workspace(nb)
+        ws.fill_(0xFF)                                           # what the workspace held before means nothing (NaN bits)
+        binding.okv_linear(x, wp, b, r, outs, m, n_out, n_in, relu, 0, ws, ws.numel())
+        torch.cuda.synchronize()
+    else:
+        binding.okv_linear(x, wp, b, r, outs, m, n_out, n_in, relu)
+        torch.cuda.synchronize()
     want = dl.linear(x.double().cpu().numpy(), w.double().cpu().numpy(), None if b is None else b.double().cpu().numpy())
     if relu:
         want = dl.relu(want)
@@ -84,11 +101,31 @@ def test_linear_every_row_count(m):
     run_linear(m, 64, 2048, 411 + m, relu=True)
 
 
-@pytest.mark.parametrize("n_out,n_in", [(16, 32), (32, 64), (48, 4096), (4096, 256), (144, 992)])
+@pytest.mark.parametrize("n_out,n_in", [(16, 32), (32, 64), (48, 4096), (4096, 256), (144, 992), (128, 256), (272, 512),
+                                        (2560, 2560), (16, 8192)])
 def test_linear_shapes(n_out, n_in):
     say(f"linear {n_out}x{n_in}")
     run_linear(32, n_out, n_in, 321)
     run_linear(7, n_out, n_in, 322, bias=False)
+    run_linear(32, n_out, n_in, 323, fast=False)              # the kernel that needs no workspace
+
+
+def test_linear_results_do_not_depend_on_arrival_order():
+    say("linear determinism")
+    m, n_out, n_in = 32, 4096, 4096
+    x = synth.randn_f16_torch((m, n_in), synth.stream_seed(371, 1), DEV)
+    w = (synth.randn_f16_torch((n_out, n_in), synth.stream_seed(371, 2), DEV).float() / 64).to(torch.float16)
+    wp = torch.empty_like(w)
+    binding.okv_pack_linear_weight(wp, w, n_out, n_in)
+    ws = workspace(binding.okv_linear_workspace_bytes(m, n_out, n_in))
+    first = None
+    for _ in range(20):
+        out = torch.empty((m, n_out), dtype=torch.float16, device=DEV)
+        binding.okv_linear(x, wp, None, None, out, m, n_out, n_in, False, 0, ws, ws.numel())
+        torch.cuda.synchronize()
+        if first is None:
+            first = out
+        assert torch.equal(out, first)
 
 
 def test_linear_epilogue_variants():

@@ -44,6 +44,9 @@ def test_layer_header_symbols_are_exported():
         kw.update(bad)
         with pytest.raises(binding.OkvError) as e:
             binding.okv_linear(16, 16, None, None, [16] * kw["n_seg"], kw["m"], kw["n_out"], kw["n_in"])
+        if "n_seg" not in bad:
+            with pytest.raises(binding.OkvError):
+                binding.okv_linear_workspace_bytes(kw["m"], kw["n_out"], kw["n_in"])
         assert e.value.code == binding.OKV_EINVAL
     with pytest.raises(binding.OkvError):
         binding.okv_layernorm(16, 16, 16, 16, 4, 100)           # h not a multiple of 8
