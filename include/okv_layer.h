@@ -62,6 +62,21 @@ int okv_linear(const void *x, const void *w_packed, const void *bias, const void
                void *const *out, int32_t n_seg, int32_t m, int32_t n_out, int32_t n_in,
                int32_t relu, void *workspace, int64_t workspace_bytes, void *stream);
 
+/* okv_linear (one output tensor) followed by okv_layernorm of its result:
+ *   out      = act(x * W^T + bias) + residual          fp16 [m][n_out]
+ *   out_norm = LayerNorm(out) with gamma, beta, eps    fp16 [m][n_out], a buffer other than out
+ * -- the output projection feeding the second norm of a decoder layer, the feed-forward
+ * block feeding the next layer's first norm.  The norm is taken of `out` as stored (after
+ * its rounding to fp16), so `out` is bit for bit what okv_linear gives and out_norm what
+ * okv_layernorm gives up to the rounding of its fp32 arithmetic; when the fast
+ * kernel runs and the workspace holds okv_linear_workspace_bytes, the norm rides on the
+ * kernel that adds the shares and one launch and one pass over the rows are saved.
+ * n_out at most 16384; other arguments as for okv_linear. */
+int okv_linear_layernorm(const void *x, const void *w_packed, const void *bias,
+                         const void *residual, void *out, const void *gamma, const void *beta,
+                         float eps, void *out_norm, int32_t m, int32_t n_out, int32_t n_in,
+                         int32_t relu, void *workspace, int64_t workspace_bytes, void *stream);
+
 /* Bytes of workspace okv_linear wants for this shape on the current device (0 if it
  * would not use one); < 0 on a bad shape. */
 int64_t okv_linear_workspace_bytes(int32_t m, int32_t n_out, int32_t n_in);

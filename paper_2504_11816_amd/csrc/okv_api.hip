@@ -1362,8 +1362,10 @@ int64_t okv_linear_workspace_bytes(int32_t m, int32_t n_out, int32_t n_in) {
   return okv::linear_workspace_bytes(m, n_out, n_in, device_cus());
 }
 
-int okv_linear(const void *x, const void *w_packed, const void *bias, const void *residual, void *const *out, int32_t n_seg,
-               int32_t m, int32_t n_out, int32_t n_in, int32_t relu, void *workspace, int64_t workspace_bytes, void *stream) {
+namespace {
+int linear_impl(const void *x, const void *w_packed, const void *bias, const void *residual, void *const *out, int32_t n_seg,
+                int32_t m, int32_t n_out, int32_t n_in, int32_t relu, void *workspace, int64_t workspace_bytes,
+                const void *ln_gamma, const void *ln_beta, void *ln_out, float ln_eps, void *stream) {
   if (!x || !w_packed || !out || !aligned16(x) || !aligned16(w_packed)) return fail(nullptr, OKV_EINVAL, "okv_linear: NULL or misaligned pointer");
   if (m < 1 || m > OKV_LINEAR_MAX_ROWS) return fail(nullptr, OKV_EINVAL, "okv_linear: m = %d outside [1, %d]", m, OKV_LINEAR_MAX_ROWS);
   if (n_out < 16 || n_out % 16 || n_in < 32 || n_in % 32 || n_in > (1 << 20))
@@ -1382,8 +1384,28 @@ int okv_linear(const void *x, const void *w_packed, const void *bias, const void
   l.workspace = workspace;
   l.workspace_bytes = workspace_bytes;
   l.n_cus = device_cus();
+  l.ln_gamma = ln_gamma, l.ln_beta = ln_beta, l.ln_out = ln_out, l.ln_eps = ln_eps;
   OKV_HIP(nullptr, okv::launch_linear(l, static_cast<hipStream_t>(stream)));
   return OKV_OK;
+}
+}  // namespace
+
+int okv_linear(const void *x, const void *w_packed, const void *bias, const void *residual, void *const *out, int32_t n_seg,
+               int32_t m, int32_t n_out, int32_t n_in, int32_t relu, void *workspace, int64_t workspace_bytes, void *stream) {
+  return linear_impl(x, w_packed, bias, residual, out, n_seg, m, n_out, n_in, relu, workspace, workspace_bytes, nullptr, nullptr,
+                     nullptr, 0.f, stream);
+}
+
+int okv_linear_layernorm(const void *x, const void *w_packed, const void *bias, const void *residual, void *out, const void *gamma,
+                         const void *beta, float eps, void *out_norm, int32_t m, int32_t n_out, int32_t n_in, int32_t relu,
+                         void *workspace, int64_t workspace_bytes, void *stream) {
+  if (!out || !gamma || !beta || !out_norm || !aligned16(out) || !aligned16(gamma) || !aligned16(beta) || !aligned16(out_norm))
+    return fail(nullptr, OKV_EINVAL, "okv_linear_layernorm: NULL or misaligned pointer");
+  if (n_out > 16384 || !(eps >= 0)) return fail(nullptr, OKV_EINVAL, "okv_linear_layernorm: n_out > 16384 or eps < 0");
+  if (out == out_norm) return fail(nullptr, OKV_EINVAL, "okv_linear_layernorm: out and out_norm must differ");
+  void *outs[1] = {out};
+  return linear_impl(x, w_packed, bias, residual, outs, 1, m, n_out, n_in, relu, workspace, workspace_bytes, gamma, beta, out_norm,
+                     eps, stream);
 }
 
 int okv_layernorm(const void *x, const void *gamma, const void *beta, void *out, int32_t m, int32_t h, float eps, void *stream) {

@@ -100,8 +100,11 @@ struct LinearLaunch {
   const void *x, *w_packed, *bias, *residual;
   void *out[3];
   int32_t n_seg, m, n_out, n_in, relu;
-  void *workspace;             // counters (zero between launches) + fp32 shares, or NULL: simple kernel
+  void *workspace;             // fp32 shares of the cuts of the input dimension, or NULL
   int64_t workspace_bytes;
+  const void *ln_gamma, *ln_beta;   // with ln_out: layer norm of the result (n_seg = 1) written there as well
+  void *ln_out;
+  float ln_eps;
   int32_t n_cus;               // compute units of the device (decides how the input dimension is cut)
 };
 hipError_t launch_linear(const LinearLaunch &l, hipStream_t stream);

@@ -65,7 +65,11 @@ struct LinearArgs {
   _Float16 *out[3];
   int32_t m, n_in, n_kb, seg_cols, relu;
   int32_t n_tiles, n_out, splits;   // fast path: 16-feature tiles, cuts of the input dimension
-  float *shares;                    // fast path, splits > 1: [splits][m][n_out] fp32
+  float *shares;                    // fast path, splits > 1 or a layer norm to follow: [splits][m][n_out] fp32
+  int32_t to_shares;                // fast path: write the share even when there is a single cut
+  const _Float16 *ln_gamma, *ln_beta;
+  _Float16 *ln_out;                 // layer norm of the result, or NULL
+  float ln_eps;
 };
 
 __device__ __forceinline__ floatx4 mfma16(const uint2 a, const uint2 b, floatx4 c) {
@@ -268,7 +272,7 @@ __global__ __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(2,
   }
   __syncthreads();
   const int n0 = group * kTileCols;
-  if (a.splits > 1) {                                  // this cut's share; reduce_epilogue_kernel adds them up
+  if (a.splits > 1 || a.to_shares) {                   // this cut's share; a second kernel adds them up
     float *mine = a.shares + (size_t)cut * a.m * a.n_out;
     for (int o = tid; o < a.m * kTileCols; o += kFastThreads) {
       const int mrow = o / kTileCols, n = n0 + o % kTileCols;
@@ -379,15 +383,82 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint4 *x, c
   }
 }
 
+// The share reduction and epilogue for whole rows, followed by the layer norm of the result: one
+// workgroup per row, the row in registers as in layernorm_kernel.  Saves a launch and a pass over
+// the row whenever a product feeds a layer norm (output projection -> second norm, feed-forward
+// -> the next layer's first norm).
+__global__ __launch_bounds__(kLnThreads) void reduce_layernorm_kernel(const LinearArgs a) {
+  __shared__ float scratch[kLnThreads / 64];
+  const int h = a.n_out, pieces = h >> 3, mrow = blockIdx.x;
+  float v[kLnPieces][8];
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < kLnPieces; ++i) {
+    const int p = threadIdx.x + i * kLnThreads;
+    if (p < pieces) {
+      float acc[8];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) acc[e] = 0.f;
+      for (int s2 = 0; s2 < a.splits; ++s2) {
+        const float4 *sp = reinterpret_cast<const float4 *>(a.shares + ((size_t)s2 * a.m + mrow) * h + p * 8);
+        const float4 lo = sp[0], hi = sp[1];
+        acc[0] += lo.x, acc[1] += lo.y, acc[2] += lo.z, acc[3] += lo.w;
+        acc[4] += hi.x, acc[5] += hi.y, acc[6] += hi.z, acc[7] += hi.w;
+      }
+      uint4 rb = make_uint4(0u, 0u, 0u, 0u), bb = rb;
+      if (a.bias) bb = reinterpret_cast<const uint4 *>(a.bias)[p];
+      if (a.residual) rb = reinterpret_cast<const uint4 *>(a.residual + (size_t)mrow * h)[p];
+      const _Float16 *bp = reinterpret_cast<const _Float16 *>(&bb), *rp = reinterpret_cast<const _Float16 *>(&rb);
+      uint4 yo;
+      _Float16 *yp = reinterpret_cast<_Float16 *>(&yo);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        float y = acc[e] + (float)bp[e];
+        if (a.relu) y = fmaxf(y, 0.f);
+        y += (float)rp[e];
+        yp[e] = (_Float16)y;                               // the norm sees the row as it is stored
+        v[i][e] = (float)yp[e];
+        s += v[i][e];
+      }
+      reinterpret_cast<uint4 *>(a.out[0] + (size_t)mrow * h)[p] = yo;
+    }
+  }
+  const float mean = block_sum(s, scratch) / (float)h;
+  float q = 0.f;
+#pragma unroll
+  for (int i = 0; i < kLnPieces; ++i)
+    if (threadIdx.x + i * kLnThreads < pieces) {
+#pragma unroll
+      for (int e = 0; e < 8; ++e) q += (v[i][e] - mean) * (v[i][e] - mean);
+    }
+  const float rstd = 1.0f / sqrtf(block_sum(q, scratch) / (float)h + a.ln_eps);
+#pragma unroll
+  for (int i = 0; i < kLnPieces; ++i) {
+    const int p = threadIdx.x + i * kLnThreads;
+    if (p < pieces) {
+      const uint4 g = reinterpret_cast<const uint4 *>(a.ln_gamma)[p], b = reinterpret_cast<const uint4 *>(a.ln_beta)[p];
+      const _Float16 *gp = reinterpret_cast<const _Float16 *>(&g), *bp = reinterpret_cast<const _Float16 *>(&b);
+      uint4 o;
+      _Float16 *op = reinterpret_cast<_Float16 *>(&o);
+#pragma unroll
+      for (int e = 0; e < 8; ++e) op[e] = (_Float16)((v[i][e] - mean) * rstd * (float)gp[e] + (float)bp[e]);
+      reinterpret_cast<uint4 *>(a.ln_out + (size_t)mrow * h)[p] = o;
+    }
+  }
+}
+
 template <int MF>
 hipError_t launch_linear_mf(const LinearArgs &args, int n_tiles, bool fast, hipStream_t stream) {
   if (fast) {
     dim3 grid((n_tiles + kLinWaves - 1) / kLinWaves, args.splits);
     hipLaunchKernelGGL(linear_lds_kernel<MF>, grid, dim3(kFastThreads), 0, stream, args);
-    if (args.splits > 1) {
+    if (args.splits > 1 || args.to_shares) {
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
-      hipLaunchKernelGGL(reduce_epilogue_kernel, dim3((args.n_out + 255) / 256, args.m), dim3(256), 0, stream, args);
+      if (args.ln_out)
+        hipLaunchKernelGGL(reduce_layernorm_kernel, dim3(args.m), dim3(kLnThreads), 0, stream, args);
+      else
+        hipLaunchKernelGGL(reduce_epilogue_kernel, dim3((args.n_out + 255) / 256, args.m), dim3(256), 0, stream, args);
     }
   } else {
     hipLaunchKernelGGL(linear_kernel<MF>, dim3(n_tiles), dim3(kLinWaves * 64), 0, stream, args);
@@ -416,7 +487,7 @@ int linear_splits(int32_t m, int32_t n_out, int32_t n_in, int32_t n_cus) {
 
 int64_t linear_workspace_bytes(int32_t m, int32_t n_out, int32_t n_in, int32_t n_cus) {
   const int s = m > 16 ? linear_splits(m, n_out, n_in, n_cus) : 0;
-  return s <= 1 ? 0 : (int64_t)s * m * n_out * 4;
+  return s < 1 ? 0 : (int64_t)s * m * n_out * 4;        // a single cut still goes through a share when a layer norm follows
 }
 
 hipError_t launch_linear(const LinearLaunch &l, hipStream_t stream) {
@@ -436,6 +507,11 @@ hipError_t launch_linear(const LinearLaunch &l, hipStream_t stream) {
   a.n_out = l.n_out;
   a.splits = 1;
   a.shares = nullptr;
+  a.to_shares = 0;
+  a.ln_gamma = static_cast<const _Float16 *>(l.ln_gamma);
+  a.ln_beta = static_cast<const _Float16 *>(l.ln_beta);
+  a.ln_out = nullptr;
+  a.ln_eps = l.ln_eps;
   bool fast = false;
   const int s = linear_splits(l.m, l.n_out, l.n_in, l.n_cus);
   if (l.m > 16 && (s == 1 || (s > 1 && l.workspace && l.workspace_bytes >= linear_workspace_bytes(l.m, l.n_out, l.n_in, l.n_cus)))) {
@@ -443,17 +519,26 @@ hipError_t launch_linear(const LinearLaunch &l, hipStream_t stream) {
     a.splits = s;
     a.shares = static_cast<float *>(l.workspace);
   }
-  switch ((l.m + 15) / 16) {
-    case 1: return launch_linear_mf<1>(a, n_tiles, fast, stream);
-    case 2: return launch_linear_mf<2>(a, n_tiles, fast, stream);
-    case 3: return launch_linear_mf<3>(a, n_tiles, fast, stream);
-    case 4: return launch_linear_mf<4>(a, n_tiles, fast, stream);
-    case 5: return launch_linear_mf<5>(a, n_tiles, fast, stream);
-    case 6: return launch_linear_mf<6>(a, n_tiles, fast, stream);
-    case 7: return launch_linear_mf<7>(a, n_tiles, fast, stream);
-    case 8: return launch_linear_mf<8>(a, n_tiles, fast, stream);
+  // a layer norm of the result rides on the share reduction when there is one to ride on
+  const bool fuse_ln = l.ln_out && fast && l.n_seg == 1 && l.n_out <= kLnThreads * kLnPieces * 8 && l.workspace &&
+                       l.workspace_bytes >= (int64_t)a.splits * l.m * l.n_out * 4;
+  if (fuse_ln) {
+    a.to_shares = 1;
+    a.ln_out = static_cast<_Float16 *>(l.ln_out);
   }
-  return hipErrorInvalidValue;
+  hipError_t e = hipErrorInvalidValue;
+  switch ((l.m + 15) / 16) {
+    case 1: e = launch_linear_mf<1>(a, n_tiles, fast, stream); break;
+    case 2: e = launch_linear_mf<2>(a, n_tiles, fast, stream); break;
+    case 3: e = launch_linear_mf<3>(a, n_tiles, fast, stream); break;
+    case 4: e = launch_linear_mf<4>(a, n_tiles, fast, stream); break;
+    case 5: e = launch_linear_mf<5>(a, n_tiles, fast, stream); break;
+    case 6: e = launch_linear_mf<6>(a, n_tiles, fast, stream); break;
+    case 7: e = launch_linear_mf<7>(a, n_tiles, fast, stream); break;
+    case 8: e = launch_linear_mf<8>(a, n_tiles, fast, stream); break;
+  }
+  if (e != hipSuccess || !l.ln_out || fuse_ln) return e;
+  return launch_layernorm(l.out[0], l.ln_gamma, l.ln_beta, l.ln_out, l.m, l.n_out, l.ln_eps, stream);   // the same in two steps
 }
 
 hipError_t launch_pack_weight(void *dst, const void *src, int32_t n_out, int32_t n_in, hipStream_t stream) {

@@ -303,15 +303,21 @@ def decode_step_with_layers(st, weights, scratch, x):
     cs = st.compute_stream.cuda_stream
     h1, h2 = weights[0].h1, weights[0].h2
     c.okv_step_begin()
+    binding.okv_layernorm(x, weights[0].t["ln1_g"], weights[0].t["ln1_b"], s.a, B, h1, 1e-5, cs)
     for l, w in enumerate(weights):
-        binding.okv_layernorm(x, w.t["ln1_g"], w.t["ln1_b"], s.a, B, h1, 1e-5, cs)
         binding.okv_linear(s.a, w.packed["wqkv"], w.bqkv, None, [s.q, s.k, s.v], B, 3 * h1, h1, False, cs, s.ws, s.ws_bytes)
         c.kv_append(l, s.k, s.v)
         c.decode_attn(l, s.q, s.t)
-        binding.okv_linear(s.t, w.packed["wo"], w.t["bo"], x, s.y, B, h1, h1, False, cs, s.ws, s.ws_bytes)
-        binding.okv_layernorm(s.y, w.t["ln2_g"], w.t["ln2_b"], s.z, B, h1, 1e-5, cs)
+        # output projection + residual, and the second norm of its result in the same pass
+        binding.okv_linear_layernorm(s.t, w.packed["wo"], w.t["bo"], x, s.y, w.t["ln2_g"], w.t["ln2_b"], s.z, B, h1, h1, 1e-5,
+                                     False, cs, s.ws, s.ws_bytes)
         binding.okv_linear(s.z, w.packed["w1"], w.t["b1"], None, s.u, B, h2, h1, True, cs, s.ws, s.ws_bytes)
-        binding.okv_linear(s.u, w.packed["w2"], w.t["b2"], s.y, x, B, h1, h2, False, cs, s.ws, s.ws_bytes)
+        if l + 1 < len(weights):                         # ... and the next layer's first norm rides on the feed-forward block
+            nxt = weights[l + 1]
+            binding.okv_linear_layernorm(s.u, w.packed["w2"], w.t["b2"], s.y, x, nxt.t["ln1_g"], nxt.t["ln1_b"], s.a, B, h1, h2,
+                                         1e-5, False, cs, s.ws, s.ws_bytes)
+        else:
+            binding.okv_linear(s.u, w.packed["w2"], w.t["b2"], s.y, x, B, h1, h2, False, cs, s.ws, s.ws_bytes)
     c.okv_step_end()
     if st.ctx_lens is not None:
         st.ctx_lens += 1

@@ -110,6 +110,44 @@ def test_linear_shapes(n_out, n_in):
     run_linear(32, n_out, n_in, 323, fast=False)              # the kernel that needs no workspace
 
 
+@pytest.mark.parametrize("m,n_out,n_in,relu", [(32, 4096, 4096, False), (20, 256, 512, True), (64, 2560, 2560, False),
+                                               (8, 256, 512, False), (32, 192, 320, False), (33, 16384, 256, False)])
+def test_linear_followed_by_layernorm_in_one_call(m, n_out, n_in, relu):
+    # fast path (the norm rides on the share reduction), few rows and odd input sizes (two kernels): same contract
+    say(f"linear+layernorm m={m} {n_out}x{n_in}")
+    x = synth.randn_f16_torch((m, n_in), synth.stream_seed(381, 1), DEV)
+    w = (synth.randn_f16_torch((n_out, n_in), synth.stream_seed(381, 2), DEV).float() / n_in ** 0.5).to(torch.float16)
+    b = synth.randn_f16_torch((n_out,), synth.stream_seed(381, 3), DEV)
+    r = synth.randn_f16_torch((m, n_out), synth.stream_seed(381, 4), DEV)
+    g = (1.0 + 0.2 * synth.randn_f16_torch((n_out,), synth.stream_seed(381, 5), DEV).float()).to(torch.float16)
+    be = (0.3 * synth.randn_f16_torch((n_out,), synth.stream_seed(381, 6), DEV).float()).to(torch.float16)
+    wp = torch.empty_like(w)
+    binding.okv_pack_linear_weight(wp, w, n_out, n_in)
+    y = torch.full((m, n_out), float("nan"), dtype=torch.float16, device=DEV)
+    z = torch.full((m, n_out), float("nan"), dtype=torch.float16, device=DEV)
+    ws = workspace(binding.okv_linear_workspace_bytes(m, n_out, n_in))
+    ws.fill_(0xFF)
+    binding.okv_linear_layernorm(x, wp, b, r, y, g, be, z, m, n_out, n_in, 1e-5, relu, 0, ws, ws.numel())
+    torch.cuda.synchronize()
+    want_y = dl.linear(x.double().cpu().numpy(), w.double().cpu().numpy(), b.double().cpu().numpy())
+    if relu:
+        want_y = dl.relu(want_y)
+    want_y = want_y + r.double().cpu().numpy()
+    close(y.float().cpu().numpy(), want_y, what="product")
+    # the norm is defined on the stored (fp16) result
+    want_z = dl.layernorm(y.double().cpu().numpy(), g.double().cpu().numpy(), be.double().cpu().numpy(), 1e-5)
+    close(z.float().cpu().numpy(), want_z, what="norm of the product")
+    # the two separate calls give the same product bit for bit and the same norm up to its fp32 rounding
+    y2, z2 = torch.empty_like(y), torch.empty_like(z)
+    binding.okv_linear(x, wp, b, r, y2, m, n_out, n_in, relu, 0, ws, ws.numel())
+    binding.okv_layernorm(y2, g, be, z2, m, n_out, 1e-5)
+    torch.cuda.synchronize()
+    assert torch.equal(y, y2)
+    assert (z.float() - z2.float()).abs().max().item() <= 2e-3
+    with pytest.raises(binding.OkvError):
+        binding.okv_linear_layernorm(x, wp, b, r, y, g, be, y, m, n_out, n_in)        # out and out_norm must differ
+
+
 def test_linear_results_do_not_depend_on_arrival_order():
     say("linear determinism")
     m, n_out, n_in = 32, 4096, 4096
