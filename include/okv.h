@@ -30,13 +30,24 @@
  *     or throws.  okv_last_error gives a readable message for the last failure.
  *   - A context is not thread-safe: one host thread drives it.
  *
- * KV pool layouts (fp16, row-major; kv = 0 keys, kv = 1 values; G = n_kv_heads,
- * d = head_dim):
- *   contiguous (block_tokens == 0):  pool[b][kv][g][tok][d]    b < max_batch, tok < max_ctx
- *   paged      (block_tokens == T):  pool[blk][kv][g][slot][d] blk < blocks_per_layer, slot < T
- *     token i of sequence b is in block block_table[b][i / T], slot i % T.
- * In both, the K rows (and the V rows) of 16 consecutive tokens of one KV head
- * are one contiguous run of 16 * d * 2 bytes.
+ * KV pool layouts (fp16; kv = 0 keys, kv = 1 values; G = n_kv_heads, d = head_dim).
+ * A pool is a row of TILE SLABS.  A slab holds the K and V rows of 16 consecutive
+ * tokens for all G KV heads, the heads taken in groups of Gg consecutive heads, each
+ * group as its K rows and then its V rows, row-major:
+ *   slab[g / Gg][kv][g % Gg][slot][d]      slot < 16;  2 * G * 16 * d * 2 bytes
+ * Gg is the largest divisor of G with Gg * d <= 1024, i.e. the K rows of a group (and
+ * its V rows) are one run of at most 32 KiB: 8 heads at d = 128, 16 at d = 64, all G
+ * heads when there are fewer (okv_kv_head_group returns it).  The K rows (and the V
+ * rows) of 16 consecutive tokens of one KV head are one contiguous run of 16 * d * 2
+ * bytes, which is what a wavefront reads at a time; with this grouping the K run and
+ * the V run it reads together are 32 KiB apart and those of neighbouring heads adjoin,
+ * which measured 8-10 % faster on MI355X than keeping all K rows of a block before all
+ * its V rows.
+ *   contiguous (block_tokens == 0):  sequence b < max_batch owns the max_ctx / 16 slabs
+ *     from b * (max_ctx / 16) on; token i is in slab i / 16 of them, slot i % 16.
+ *   paged (block_tokens == T):  block blk < blocks_per_layer is the T / 16 slabs from
+ *     blk * (T / 16) on; token i of sequence b is in block block_table[b][i / T], slab
+ *     (i % T) / 16 of it, slot i % 16.
  */
 #ifndef OKV_H
 #define OKV_H
@@ -59,7 +70,7 @@ typedef struct okv_ctx okv_ctx;   /* opaque */
 
 typedef struct okv_config {
   int32_t n_layers;            /* L >= 1                                                     */
-  int32_t n_q_heads;           /* H; H % G == 0 and H / G in {1, 2, 4, 8}                    */
+  int32_t n_q_heads;           /* H; H % G == 0 and H / G in {1, 2, 4, 8, 16}                  */
   int32_t n_kv_heads;          /* G                                                          */
   int32_t head_dim;            /* d in {64, 128}                                             */
   int32_t block_tokens;        /* T: 0 = contiguous pools, else a power of two in [16, 1024] */
@@ -119,6 +130,10 @@ int64_t okv_layer_pool_bytes(const okv_config *cfg);
 /* Bytes of one block of a paged pool (K and V of block_tokens tokens for every KV
  * head), or of one sequence's slice of a contiguous pool; < 0 on a bad cfg. */
 int64_t okv_block_bytes(const okv_config *cfg);
+
+/* Gg of the pool layout above for n_kv_heads KV heads of head_dim numbers; < 0 unless
+ * n_kv_heads >= 1 and head_dim is 64 or 128.  Pure host function. */
+int32_t okv_kv_head_group(int32_t n_kv_heads, int32_t head_dim);
 
 /* Bytes of workspace the split-K partials need in the worst case under cfg (every
  * sequence at full capacity, the smallest split size the library would choose or

@@ -5,30 +5,64 @@ TEST INFRASTRUCTURE ONLY; shares no code with the HIP library.
 The KV cache holds, per layer, one key row and one value row of `d` fp16
 numbers per sequence, per token, per KV head (paper §II-A: keys and values of
 every processed token are kept for reuse by the decode stage).  The library
-fixes two pool layouts, both row-major, written here from their description:
+fixes two pool layouts, written here from their description.  Both are made of
+TILE SLABS: the K and V rows of 16 consecutive tokens for all G KV heads,
+row-major as
 
-  contiguous  pool[b][kv][g][tok][d]     b < B, tok < C (capacity in tokens)
-  paged       pool[blk][kv][g][slot][d]  blk < n_blocks, slot < T
-              token i of sequence b lives in block block_table[b][i // T],
-              slot i % T
+  slab[group][kv][head in group][slot][d]   group < G / Gg, head in group < Gg, slot < 16
 
-kv = 0 selects keys, kv = 1 selects values.  Offsets are in ELEMENTS (fp16),
-not bytes.
+where the KV heads are taken in groups of Gg consecutive heads, Gg being the
+largest divisor of G with Gg * d <= 1024 (so that the K rows of a group, and
+its V rows, are one run of at most 32 KiB), kv = 0 selects keys and kv = 1
+values.
+
+  contiguous  sequence b owns the C / 16 consecutive slabs from b * C / 16 on
+              (C = capacity in tokens, a multiple of 16); token tok is in slab
+              tok // 16 of them, slot tok % 16
+  paged       block blk is the T / 16 consecutive slabs from blk * T / 16 on;
+              token i of sequence b lives in block block_table[b][i // T], at
+              token (i % T) of that block: slab (i % T) // 16, slot i % 16
+
+Offsets are in ELEMENTS (fp16), not bytes.
 """
 import numpy as np
 
 
+def head_group(G, d):
+    """Gg: the largest divisor of G with Gg * d <= 1024."""
+    best = 1
+    for c in range(1, G + 1):
+        if G % c == 0 and c * d <= 1024:
+            best = c
+    return best
+
+
+def slab_row_offset(kv, g, slot, G, d):
+    """Element offset of row (kv, g, slot) inside one tile slab."""
+    assert 0 <= kv < 2 and 0 <= g < G and 0 <= slot < 16
+    Gg = head_group(G, d)
+    group, within = divmod(g, Gg)
+    return (((group * 2 + kv) * Gg + within) * 16 + slot) * d
+
+
+def slab_elems(G, d):
+    return 2 * G * 16 * d
+
+
 def contiguous_row_offset(b, kv, g, tok, G, C, d):
     """Element offset of row (b, kv, g, tok) in a contiguous pool."""
-    assert 0 <= kv < 2 and 0 <= g < G and 0 <= tok < C
-    return (((b * 2 + kv) * G + g) * C + tok) * d
+    assert C % 16 == 0 and 0 <= tok < C
+    slab = b * (C // 16) + tok // 16
+    return slab * slab_elems(G, d) + slab_row_offset(kv, g, tok % 16, G, d)
 
 
 def paged_row_offset(blk, kv, g, slot, G, T, d):
-    """Element offset of row (blk, kv, g, slot) in a paged pool."""
+    """Element offset of row (blk, kv, g, slot) in a paged pool (slot < T counts
+    tokens inside the block)."""
     assert blk >= 0, "token maps to an unallocated block"
-    assert 0 <= kv < 2 and 0 <= g < G and 0 <= slot < T
-    return (((blk * 2 + kv) * G + g) * T + slot) * d
+    assert T % 16 == 0 and 0 <= slot < T
+    slab = blk * (T // 16) + slot // 16
+    return slab * slab_elems(G, d) + slab_row_offset(kv, g, slot % 16, G, d)
 
 
 def token_row_offset(layout, b, kv, g, tok):

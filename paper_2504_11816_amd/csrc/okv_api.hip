@@ -30,6 +30,11 @@ constexpr int kEventRing = 8;            // > copies in flight (at most OKV_MAX_
 #ifndef OKV_WAVES_PER_CU_GQA
 #define OKV_WAVES_PER_CU_GQA 4
 #endif
+// 8 and 16 heads per KV head run on the matrix cores with one tile in flight per wavefront; there two
+// wavefronts per SIMD (all its registers allow) measured best: 6.4 TB/s against 5.8 with one.
+#ifndef OKV_WAVES_PER_CU_MFMA
+#define OKV_WAVES_PER_CU_MFMA 8
+#endif
 constexpr int32_t kMinAutoSplit = 128;   // smallest split size the library picks by itself
 constexpr int32_t kClassSplit = 512;     // split size with block classes unless the caller sets one
 constexpr int64_t kMaxClasses = 4096;
@@ -150,7 +155,7 @@ const char *shape_problem(const okv_config *c) {
   if (c->n_layers < 1) return "n_layers < 1";
   if (c->n_kv_heads < 1 || c->n_q_heads < 1 || c->n_q_heads % c->n_kv_heads) return "n_q_heads must be a multiple of n_kv_heads";
   int r = c->n_q_heads / c->n_kv_heads;
-  if (r != 1 && r != 2 && r != 4 && r != 8) return "n_q_heads / n_kv_heads must be 1, 2, 4 or 8";
+  if (r != 1 && r != 2 && r != 4 && r != 8 && r != 16) return "n_q_heads / n_kv_heads must be 1, 2, 4, 8 or 16";
   if (c->n_kv_heads > 65535) return "n_kv_heads too large";
   if (c->head_dim != 64 && c->head_dim != 128) return "head_dim must be 64 or 128";
   if (c->max_batch < 1 || c->max_batch > 65535) return "max_batch out of range";
@@ -544,6 +549,11 @@ int okv_plan_block_split(int64_t n_blocks, int64_t coff_num, int64_t coff_den, i
   return OKV_OK;
 }
 
+int32_t okv_kv_head_group(int32_t n_kv_heads, int32_t head_dim) {
+  if (n_kv_heads < 1 || (head_dim != 64 && head_dim != 128)) return OKV_EINVAL;
+  return okv::kv_head_group(n_kv_heads, head_dim);
+}
+
 int64_t okv_block_bytes(const okv_config *cfg) {
   if (const char *why = shape_problem(cfg)) return fail(nullptr, OKV_EINVAL, "%s", why);
   return block_bytes_of(cfg);
@@ -609,6 +619,7 @@ int okv_create(const okv_config *cfg, okv_ctx **out) {
   s.log2_T = 0;
   while (s.paged && (1 << s.log2_T) < cfg->block_tokens) ++s.log2_T;
   s.tcap = s.paged ? cfg->block_tokens : cfg->max_ctx;
+  s.gg = okv::kv_head_group(s.G, s.D);
   s.max_blocks = s.paged ? cfg->max_blocks_per_seq : 1;
   ctx->block_bytes = (int64_t)2 * s.G * s.tcap * s.D * 2;
   ctx->by_class = by_class;
@@ -655,7 +666,8 @@ int okv_create(const okv_config *cfg, okv_ctx **out) {
     int dev = 0, cus = 0;
     OKV_TRY_CREATE(hipGetDevice(&dev));
     OKV_TRY_CREATE(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
-    ctx->max_waves = std::max(1, cus) * (cfg->n_q_heads == cfg->n_kv_heads ? OKV_WAVES_PER_CU_MHA : OKV_WAVES_PER_CU_GQA);
+    const int group = cfg->n_q_heads / cfg->n_kv_heads;
+    ctx->max_waves = std::max(1, cus) * (group == 1 ? OKV_WAVES_PER_CU_MHA : group < 8 ? OKV_WAVES_PER_CU_GQA : OKV_WAVES_PER_CU_MFMA);
   }
   if (n_staging >= 2) OKV_TRY_CREATE(hipStreamCreateWithFlags(&ctx->h2d_odd, hipStreamNonBlocking));
   for (int i = 0; i < kEventRing; ++i) {

@@ -158,6 +158,17 @@ __host__ __device__ inline ItemRange chunk_range(int32_t b, int32_t c, int32_t s
 // class 1 + i / chunk).  Every class is attended by a launch of its own, so a sequence is
 // first cut into runs of consecutive positions whose blocks share a class, and each run is
 // cut into equal pieces by seq_chunks with the run's length in place of the sequence's.
+// KV heads per group inside a 16-token tile slab: the largest divisor of G whose K rows of one tile
+// (gg * 16 * d * 2 bytes) fit in 32 KiB.  Measured on MI355X with 4 KiB tiles (d = 128): a wavefront that
+// reads its K tile and its V tile 32 or 64 KiB apart runs at 6.4-6.6 TB/s, at 4-16 KiB or at a multiple of
+// 128 KiB apart at 5.5-6.1.
+inline int32_t kv_head_group(int32_t G, int32_t d) {
+  int32_t gg = 1;
+  for (int32_t c = 1; c <= G; ++c)
+    if (G % c == 0 && (int64_t)c * d <= 1024) gg = c;
+  return gg;
+}
+
 inline int32_t block_class(int64_t id, int64_t resident, int64_t chunk) {
   return id < resident ? 0 : 1 + (int32_t)((id - resident) / chunk);
 }

@@ -12,7 +12,8 @@ struct PoolShape {
   int32_t H, G, D;         // query heads, KV heads, head dim
   int32_t paged;           // 1: block table lookup, 0: sequence b owns slice b
   int32_t log2_T;          // paged: log2(block tokens)
-  int32_t tcap;            // tokens per pool slice: T (paged) or max_ctx (contiguous)
+  int32_t tcap;            // tokens per pool slice: T (paged) or max_ctx (contiguous); a multiple of 16
+  int32_t gg;              // KV heads per group inside a 16-token tile slab (divides G)
   int32_t max_blocks;      // paged: columns of the block table
 };
 

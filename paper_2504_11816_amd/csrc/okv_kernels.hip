@@ -36,6 +36,35 @@ constexpr int kWavesPerBlock = OKV_WAVES_PER_BLOCK;   // independent work items 
 constexpr float kNegBig = -1.0e30f;   // "no key seen yet"; finite so that differences stay finite
 constexpr int kItemLast = 1, kItemWhole = 2;   // flags of a work item (item_desc.w)
 
+// Where the rows of a 16-token tile live.  A pool is a sequence of tile slabs: the K and V rows of 16
+// consecutive tokens for every KV head, 2 * G * 16 * D elements.  Block blk of a paged pool is the
+// tcap / 16 slabs from blk * (tcap / 16) on; sequence b of a contiguous pool owns the tcap / 16 slabs
+// from b * (tcap / 16) on.  Inside a slab the KV heads come in groups of gg: the K rows of the group's
+// heads (16 * D elements each), then their V rows.
+struct TileAddr {
+  int64_t slab_elems;    // elements of one slab
+  int64_t head_k;        // offset of this KV head's K rows inside a slab
+  int64_t head_v;        // and of its V rows
+  int32_t tiles;         // slabs per block (paged) or per sequence (contiguous)
+};
+
+template <int D>
+__device__ __forceinline__ TileAddr tile_addr(int G, int gg, int tcap, int g) {
+  TileAddr t;
+  t.slab_elems = (int64_t)2 * G * 16 * D;
+  const int grp = g / gg;
+  t.head_k = ((int64_t)grp * 2 * gg + (g - grp * gg)) * (16 * D);
+  t.head_v = t.head_k + (int64_t)gg * (16 * D);
+  t.tiles = tcap >> 4;
+  return t;
+}
+
+// First element of the slab of 16-token tile `tile` in pool slice `blk` (a block, or a sequence's slice).
+template <bool PAGED>
+__device__ __forceinline__ int64_t slab_base(const TileAddr &t, int blk, int tile) {
+  return ((int64_t)blk * t.tiles + (PAGED ? tile & (t.tiles - 1) : tile)) * t.slab_elems;
+}
+
 template <int CTRL>
 __device__ __forceinline__ float dpp_move(float x) {
   return __builtin_bit_cast(
@@ -137,6 +166,7 @@ struct AttnArgs {
   const int4 *item_desc;           // [n_items] (sequence, first key, one past last key, flags)
   uint32_t *queue;                 // ticket counter of this launch, zero when the kernel starts
   int32_t H, G, log2_T, tcap, max_blocks, n_units, out_fp32;
+  int32_t gg;                      // KV heads per group inside a tile slab
   int32_t item_first;              // the launch's first item in item_desc (and in the partial slots)
   int32_t id_base;                 // `pool` holds the blocks with ids id_base, id_base + 1, ...
   int32_t mirror_shift;            // id_base minus the id of the first block of pool_mirror
@@ -183,8 +213,7 @@ __device__ __forceinline__ void attend_item(const AttnArgs &a, const int it, con
   }
 
   const int t0 = lo >> 4, t1 = (hi + 15) >> 4;               // 16-token tiles; lo is a multiple of 16
-  const int64_t slice = (int64_t)a.tcap * D;                 // elements of one (blk, kv, g) slice
-  const int64_t kv_stride = slice * a.G;                     // K slice -> V slice of the same block
+  const TileAddr ta = tile_addr<D>(a.G, a.gg, a.tcap, g);
 
   // Block id of a tile: a wavefront-uniform (scalar) load from the block table.  The index
   // is clamped so that look-ahead past the item's last tile stays inside the table.
@@ -199,10 +228,9 @@ __device__ __forceinline__ void attend_item(const AttnArgs &a, const int it, con
     return tbl_row[bi] - a.id_base;
   };
   auto load_tile = [&](Tile<LPT> &t, int tile, int blk) {
-    const int slot0 = PAGED ? (tile << 4) & (a.tcap - 1) : (tile << 4);
-    const int64_t base = ((int64_t)blk * 2 * a.G + g) * slice + (int64_t)slot0 * D;
-    const uint4 *kp = reinterpret_cast<const uint4 *>(a.pool + base) + lane;
-    const uint4 *vp = reinterpret_cast<const uint4 *>(a.pool + base + kv_stride) + lane;
+    const int64_t base = slab_base<PAGED>(ta, blk, tile);
+    const uint4 *kp = reinterpret_cast<const uint4 *>(a.pool + base + ta.head_k) + lane;
+    const uint4 *vp = reinterpret_cast<const uint4 *>(a.pool + base + ta.head_v) + lane;
 #pragma unroll
     for (int j = 0; j < LPT; ++j) t.k[j] = kp[j * 64];
 #pragma unroll
@@ -311,13 +339,268 @@ __device__ __forceinline__ void attend_item(const AttnArgs &a, const int it, con
   }
 
   if (appending && row < 2) {                          // row 0 stores the K row, row 1 the V row
-    const int slot = PAGED ? pos & (a.tcap - 1) : pos;
     const int blk = blk_of(pos >> 4);
-    const int64_t in_blk = ((int64_t)row * a.G + g) * slice + (int64_t)slot * D + col * 8;
+    const int64_t in_slab = (row == 0 ? ta.head_k : ta.head_v) + (int64_t)(pos & 15) * D + col * 8;
     const uint4 val = row == 0 ? k_row : v_row;
-    *reinterpret_cast<uint4 *>(a.pool_store + (int64_t)blk * 2 * a.G * slice + in_blk) = val;
+    *reinterpret_cast<uint4 *>(a.pool_store + slab_base<PAGED>(ta, blk, pos >> 4) + in_slab) = val;
     if (a.pool_mirror)
-      *reinterpret_cast<uint4 *>(a.pool_mirror + (int64_t)(blk + (PAGED ? a.mirror_shift : 0)) * 2 * a.G * slice + in_blk) = val;
+      *reinterpret_cast<uint4 *>(a.pool_mirror + slab_base<PAGED>(ta, blk + (PAGED ? a.mirror_shift : 0), pos >> 4) + in_slab) = val;
+  }
+}
+
+// ---- grouped query heads on the matrix cores -----------------------------------------------
+//
+// With 8 or 16 query heads per KV head the scores of a 16-key tile are a 16 x 16 x D product
+// and the weighted sum of its V rows a D x 16 x 16 one, and doing them lane by lane (as above)
+// makes the kernel bound by vector arithmetic instead of by reading the cache.  Here a
+// wavefront still owns one (item, KV head) unit and loads tiles exactly as above (whole rows,
+// 16 bytes per lane, PIPE tiles in flight); each tile then passes through a piece of LDS that
+// belongs to the wavefront alone (no barriers) to reach the register layout of the matrix core:
+//   S^T[key][head]  = K[key][:] . q[head][:]      v_mfma_f32_16x16x32_f16, A = K tile, B = q
+//   O^T[dim][head] += V^T[dim][key] P^T[key][head] v_mfma_f32_16x16x16_f16, A = V^T,   B = P^T
+// The score tile comes out with lane l holding head l % 16 and keys 4 (l / 16) .. + 3, which is
+// the layout of the B operand of the second product as it stands, so the weights never move
+// between lanes; max and sum over the keys need the lanes 16, 32 and 48 apart only.
+
+typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef float floatx4_t __attribute__((ext_vector_type(4)));
+
+// Rows of a tile in LDS are 16 bytes further apart than they are long: the 16 lanes that read
+// 16 bytes of 16 different rows, and the 64 lanes that read one dword of rows 4 apart, then fall
+// on different banks.
+template <int D>
+constexpr int lds_row_bytes() {
+  return D * 2 + 16;
+}
+template <int D>
+constexpr int lds_tile_bytes() {
+  return 16 * lds_row_bytes<D>();
+}
+
+template <int D, bool MASKED>
+__device__ __forceinline__ void tile_update_mfma(const Tile<D / 32> &t, const half8_t (&qb)[D / 32], float &m,
+                                                 float &l, floatx4_t (&o)[D / 16], char *ks, char *vs,
+                                                 const int lane, const int tok_tile, const int lo,
+                                                 const int hi, const float scale) {
+  constexpr int LPR = D / 8, RPL = 64 / LPR, LPT = D / 32, S = lds_row_bytes<D>();
+  const int row = lane / LPR, col = lane % LPR;
+  const int quarter = lane >> 4, rho = lane & 15;
+  // the tile as loaded (row-major) into LDS; V rows outside [lo, hi) as zeros, since unused
+  // slots may hold NaN bit patterns and a weight of zero would not remove those
+#pragma unroll
+  for (int j = 0; j < LPT; ++j) {
+    const int r = row + j * RPL;
+    const bool valid = !MASKED || (tok_tile + r >= lo && tok_tile + r < hi);
+    *reinterpret_cast<uint4 *>(ks + r * S + col * 16) = t.k[j];
+    *reinterpret_cast<uint4 *>(vs + r * S + col * 16) = valid ? t.v[j] : make_uint4(0u, 0u, 0u, 0u);
+  }
+  // scores: A = K, lane (quarter, rho) supplies key rho, dims 32 c + 8 quarter .. + 7, as q does
+  floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int c = 0; c < D / 32; ++c) {
+    const half8_t ka = *reinterpret_cast<const half8_t *>(ks + rho * S + c * 64 + quarter * 16);
+    acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qb[c], acc, 0, 0, 0);
+  }
+  float s[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    const int tok = tok_tile + 4 * quarter + r;
+    s[r] = (!MASKED || (tok >= lo && tok < hi)) ? acc[r] * scale : -__builtin_inff();
+  }
+  float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
+  mx = fmaxf(mx, __shfl_xor(mx, 16));
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  const float m_new = fmaxf(m, mx);
+  if (__any(m_new != m)) {                          // some head's maximum moved: rescale what is summed so far
+    const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+    l *= alpha;
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) o[i] *= alpha;
+    m = m_new;
+  }
+  float p[4];
+#pragma unroll
+  for (int r = 0; r < 4; ++r) {
+    p[r] = __builtin_amdgcn_exp2f(s[r] - m);
+    l += p[r];
+  }
+  const half4_t pb = {(_Float16)p[0], (_Float16)p[1], (_Float16)p[2], (_Float16)p[3]};
+  // weighted sum: A = V^T.  Lane (quarter, rho) reads, for keys 4 quarter .. + 3, the dword that holds
+  // dims 32 u + 2 rho and + 1; the low halves feed product 2 u (whose row rho is dim 32 u + 2 rho),
+  // the high halves product 2 u + 1 (dim 32 u + 2 rho + 1).
+#pragma unroll
+  for (int u = 0; u < D / 32; ++u) {
+    uint32_t w[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e)
+      w[e] = *reinterpret_cast<const uint32_t *>(vs + (4 * quarter + e) * S + (16 * u + rho) * 4);
+    const uint2 even = make_uint2(__builtin_amdgcn_perm(w[1], w[0], 0x05040100u),
+                                  __builtin_amdgcn_perm(w[3], w[2], 0x05040100u));
+    const uint2 odd = make_uint2(__builtin_amdgcn_perm(w[1], w[0], 0x07060302u),
+                                 __builtin_amdgcn_perm(w[3], w[2], 0x07060302u));
+    o[2 * u] = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(half4_t, even), pb, o[2 * u], 0, 0, 0);
+    o[2 * u + 1] = __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(half4_t, odd), pb, o[2 * u + 1], 0, 0, 0);
+  }
+}
+
+// One work item for one KV head with R = 8 or 16 query heads, by one wavefront; `lds` is the
+// wavefront's own 2 * lds_tile_bytes<D>() bytes.
+template <int D, int R, bool PAGED, int PIPE>
+__device__ __forceinline__ void attend_item_mfma(const AttnArgs &a, const int it, const int g, const int lane,
+                                                 char *lds) {
+  constexpr int LPR = D / 8, RPL = 64 / LPR, LPT = D / 32;
+  const int row = lane / LPR, col = lane % LPR;
+  const int quarter = lane >> 4, rho = lane & 15;
+  char *ks = lds, *vs = lds + lds_tile_bytes<D>();
+  const int4 desc = a.item_desc[it];
+  const int b = desc.x, lo = desc.y, hi = desc.z;
+  const bool seq_last = (desc.w & kItemLast) != 0;
+  const bool seq_whole = (desc.w & kItemWhole) != 0;
+
+  // this step's K/V rows: patched into the last tile in registers and stored at the end, as above
+  const int pos = hi - 1;
+  const bool appending = a.k_new != nullptr && seq_last;
+  uint4 k_row = make_uint4(0u, 0u, 0u, 0u), v_row = k_row;
+  if (appending) {
+    const size_t at = ((size_t)b * a.G + g) * LPR + col;
+    k_row = reinterpret_cast<const uint4 *>(a.k_new)[at];
+    v_row = reinterpret_cast<const uint4 *>(a.v_new)[at];
+  }
+
+  // q as the B operand of the score product: lane (quarter, rho) holds head rho, dims 32 c + 8 quarter .. + 7;
+  // columns past the group's heads are zero and never stored
+  half8_t qb[D / 32];
+#pragma unroll
+  for (int c = 0; c < D / 32; ++c) {
+    uint4 x = make_uint4(0u, 0u, 0u, 0u);
+    if (rho < R)
+      x = *reinterpret_cast<const uint4 *>(a.q + ((size_t)b * a.H + (size_t)g * R + rho) * D + 32 * c + 8 * quarter);
+    qb[c] = __builtin_bit_cast(half8_t, x);
+  }
+  float m = kNegBig, l = 0.f;
+  floatx4_t o[D / 16];
+#pragma unroll
+  for (int i = 0; i < D / 16; ++i) o[i] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+
+  const int t0 = lo >> 4, t1 = (hi + 15) >> 4;
+  const TileAddr ta = tile_addr<D>(a.G, a.gg, a.tcap, g);
+  const const_i32_ptr tbl_row = (const_i32_ptr)(uintptr_t)(a.block_table + (size_t)b * a.max_blocks);
+  auto blk_of = [&](int tile) -> int {
+    if (!PAGED) return b;
+    int bi = (tile << 4) >> a.log2_T;
+    bi = bi < a.max_blocks ? bi : a.max_blocks - 1;
+    return tbl_row[bi] - a.id_base;
+  };
+  auto load_tile = [&](Tile<LPT> &t, int tile, int blk) {
+    const int64_t base = slab_base<PAGED>(ta, blk, tile);
+    const uint4 *kp = reinterpret_cast<const uint4 *>(a.pool + base + ta.head_k) + lane;
+    const uint4 *vp = reinterpret_cast<const uint4 *>(a.pool + base + ta.head_v) + lane;
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) t.k[j] = kp[j * 64];
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) t.v[j] = vp[j * 64];
+  };
+  auto update = [&](const Tile<LPT> &t, int tile) {
+    tile_update_mfma<D, false>(t, qb, m, l, o, ks, vs, lane, tile << 4, lo, hi, a.scale_log2e);
+  };
+  auto update_last = [&](Tile<LPT> &t, int tile) {
+    if (appending && tile == (pos >> 4)) {
+#pragma unroll
+      for (int j = 0; j < LPT; ++j)
+        if ((tile << 4) + row + j * RPL == pos) {
+          t.k[j] = k_row;
+          t.v[j] = v_row;
+        }
+    }
+    tile_update_mfma<D, true>(t, qb, m, l, o, ks, vs, lane, tile << 4, lo, hi, a.scale_log2e);
+  };
+
+  // the same pipeline as attend_item: PIPE tiles in flight, unconditional loads in the steady state
+  Tile<LPT> buf[PIPE];
+  int t = t0;
+  if (t1 - t0 >= 2 * PIPE) {
+    int next_blk[PIPE];
+#pragma unroll
+    for (int i = 0; i < PIPE; ++i) load_tile(buf[i], t0 + i, blk_of(t0 + i));
+#pragma unroll
+    for (int i = 0; i < PIPE; ++i) next_blk[i] = blk_of(t0 + i + PIPE);
+    for (; t + 2 * PIPE <= t1; t += PIPE) {
+#pragma unroll
+      for (int i = 0; i < PIPE; ++i) {
+        update(buf[i], t + i);
+        __builtin_amdgcn_sched_barrier(0);
+        load_tile(buf[i], t + i + PIPE, next_blk[i]);
+        next_blk[i] = blk_of(t + i + 2 * PIPE);
+        __builtin_amdgcn_sched_barrier(0);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int i = 0; i < PIPE; ++i)
+      if (t0 + i < t1) load_tile(buf[i], t0 + i, blk_of(t0 + i));
+  }
+#pragma unroll
+  for (int i = 0; i < PIPE; ++i)
+    if (t + i < t1) {
+      update_last(buf[i], t + i);
+      if (t + i + PIPE < t1) load_tile(buf[i], t + i + PIPE, blk_of(t + i + PIPE));
+    }
+#pragma unroll
+  for (int i = 0; i < PIPE; ++i)
+    if (t + PIPE + i < t1) update_last(buf[i], t + PIPE + i);
+
+  // the four quarters of the wavefront saw different keys of every tile: their sums add up (the
+  // maximum is common to them already).  Lane (quarter, rho) holds, of head rho, the dims
+  // 32 u + 8 quarter .. + 7 for every u: dim 32 u + 8 quarter + 2 r + par sits in o[2 u + par][r].
+  float lt = l;
+  lt += __shfl_xor(lt, 16);
+  lt += __shfl_xor(lt, 32);
+  if (rho < R) {
+    const int h = g * R + rho;
+    const float inv = 1.0f / lt;
+#pragma unroll
+    for (int u = 0; u < D / 32; ++u) {
+      float ot[8];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        ot[2 * r] = o[2 * u][r];
+        ot[2 * r + 1] = o[2 * u + 1][r];
+      }
+      const int dim0 = 32 * u + 8 * quarter;
+      if (seq_whole) {
+        const size_t at = ((size_t)b * a.H + h) * D + dim0;
+        if (a.out_fp32) {
+          float4 *dst = reinterpret_cast<float4 *>(reinterpret_cast<float *>(a.out) + at);
+          dst[0] = make_float4(ot[0] * inv, ot[1] * inv, ot[2] * inv, ot[3] * inv);
+          dst[1] = make_float4(ot[4] * inv, ot[5] * inv, ot[6] * inv, ot[7] * inv);
+        } else {
+          half2_t h0 = {(_Float16)(ot[0] * inv), (_Float16)(ot[1] * inv)};
+          half2_t h1 = {(_Float16)(ot[2] * inv), (_Float16)(ot[3] * inv)};
+          half2_t h2 = {(_Float16)(ot[4] * inv), (_Float16)(ot[5] * inv)};
+          half2_t h3 = {(_Float16)(ot[6] * inv), (_Float16)(ot[7] * inv)};
+          uint4 pk = make_uint4(__builtin_bit_cast(uint32_t, h0), __builtin_bit_cast(uint32_t, h1),
+                                __builtin_bit_cast(uint32_t, h2), __builtin_bit_cast(uint32_t, h3));
+          *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(a.out) + at) = pk;
+        }
+      } else {
+        const size_t slot = (size_t)it * a.H + h;
+        float4 *dst = reinterpret_cast<float4 *>(a.part_o + slot * D + dim0);
+        dst[0] = make_float4(ot[0], ot[1], ot[2], ot[3]);
+        dst[1] = make_float4(ot[4], ot[5], ot[6], ot[7]);
+      }
+    }
+    if (!seq_whole && quarter == 0)
+      *reinterpret_cast<float2 *>(a.part_ml + ((size_t)it * a.H + h) * 2) = make_float2(m, lt);
+  }
+
+  if (appending && row < 2) {                          // row 0 stores the K row, row 1 the V row
+    const int blk = blk_of(pos >> 4);
+    const int64_t in_slab = (row == 0 ? ta.head_k : ta.head_v) + (int64_t)(pos & 15) * D + col * 8;
+    const uint4 val = row == 0 ? k_row : v_row;
+    *reinterpret_cast<uint4 *>(a.pool_store + slab_base<PAGED>(ta, blk, pos >> 4) + in_slab) = val;
+    if (a.pool_mirror)
+      *reinterpret_cast<uint4 *>(a.pool_mirror + slab_base<PAGED>(ta, blk + (PAGED ? a.mirror_shift : 0), pos >> 4) + in_slab) = val;
   }
 }
 
@@ -339,6 +622,25 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_kernel(const A
     const int g = (int)(ticket - (uint32_t)it * (uint32_t)a.G);
     attend_item<D, R, PAGED, PIPE>(a, a.item_first + it, g, lane);
     if (n_waves >= (uint32_t)a.n_units) break;           // every unit had its own wavefront
+    uint32_t drawn = 0;
+    if (lane == 0) drawn = atomicAdd(a.queue, 1u);
+    ticket = n_waves + __builtin_amdgcn_readfirstlane(drawn);
+  }
+}
+
+// The same persistent scheme for the matrix-core form; each wavefront has its own piece of LDS.
+template <int D, int R, bool PAGED, int PIPE>
+__global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(const AttnArgs a) {
+  __shared__ __attribute__((aligned(16))) char lds[kWavesPerBlock][2 * lds_tile_bytes<D>()];
+  const int lane = threadIdx.x & 63;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t n_waves = gridDim.x * kWavesPerBlock;
+  uint32_t ticket = blockIdx.x * kWavesPerBlock + wave;
+  while (ticket < (uint32_t)a.n_units) {
+    const int it = (int)(ticket / (uint32_t)a.G);
+    const int g = (int)(ticket - (uint32_t)it * (uint32_t)a.G);
+    attend_item_mfma<D, R, PAGED, PIPE>(a, a.item_first + it, g, lane, lds[wave]);
+    if (n_waves >= (uint32_t)a.n_units) break;
     uint32_t drawn = 0;
     if (lane == 0) drawn = atomicAdd(a.queue, 1u);
     ticket = n_waves + __builtin_amdgcn_readfirstlane(drawn);
@@ -451,13 +753,40 @@ hipError_t launch_split_layout(const AttnArgs &args, bool paged, dim3 grid, hipS
   return paged ? launch_split<D, R, true>(args, grid, stream) : launch_split<D, R, false>(args, grid, stream);
 }
 
+// One tile in flight per wavefront here: measured with 8 wavefronts per compute unit on 1 GiB of
+// KV per launch, 8 heads per KV head reach 6.4 TB/s with one tile in flight and 6.0 with two or three.
+#ifndef OKV_PIPE_MFMA
+#define OKV_PIPE_MFMA 1
+#endif
+template <int D, int R>
+hipError_t launch_split_mfma(const AttnArgs &args, bool paged, dim3 grid, hipStream_t stream) {
+  if (paged)
+    hipLaunchKernelGGL((attn_split_mfma_kernel<D, R, true, OKV_PIPE_MFMA>), grid, dim3(kWavesPerBlock * 64), 0, stream, args);
+  else
+    hipLaunchKernelGGL((attn_split_mfma_kernel<D, R, false, OKV_PIPE_MFMA>), grid, dim3(kWavesPerBlock * 64), 0, stream, args);
+  return hipGetLastError();
+}
+
+// Group sizes from this one on take the matrix-core kernel.  Below it the lane-by-lane kernel is not
+// bound by arithmetic, and on the ragged batch of 128 sequences with 4 heads per KV head it was the
+// faster of the two (209 against 207..221 us per launch over the settings tried).
+#ifndef OKV_MFMA_MIN_R
+#define OKV_MFMA_MIN_R 8
+#endif
+template <int D, int R>
+hipError_t launch_split_pick(const AttnArgs &args, bool paged, dim3 grid, hipStream_t stream) {
+  if (R >= OKV_MFMA_MIN_R) return launch_split_mfma<D, R>(args, paged, grid, stream);
+  return launch_split_layout<D, (R > 8 ? 8 : R)>(args, paged, grid, stream);
+}
+
 template <int D>
 hipError_t launch_split_group(const AttnArgs &args, int R, bool paged, dim3 grid, hipStream_t stream) {
   switch (R) {
-    case 1: return launch_split_layout<D, 1>(args, paged, grid, stream);
-    case 2: return launch_split_layout<D, 2>(args, paged, grid, stream);
-    case 4: return launch_split_layout<D, 4>(args, paged, grid, stream);
-    case 8: return launch_split_layout<D, 8>(args, paged, grid, stream);
+    case 1: return launch_split_pick<D, 1>(args, paged, grid, stream);
+    case 2: return launch_split_pick<D, 2>(args, paged, grid, stream);
+    case 4: return launch_split_pick<D, 4>(args, paged, grid, stream);
+    case 8: return launch_split_pick<D, 8>(args, paged, grid, stream);
+    case 16: return launch_split_mfma<D, 16>(args, paged, grid, stream);
   }
   return hipErrorInvalidValue;
 }
@@ -486,6 +815,7 @@ AttnArgs make_args(const AttnLaunch &a) {
   args.G = s.G;
   args.log2_T = s.log2_T;
   args.tcap = s.tcap;
+  args.gg = s.gg;
   args.max_blocks = s.max_blocks;
   args.n_units = a.item_count * s.G;
   args.out_fp32 = a.out_fp32;
@@ -649,7 +979,7 @@ __global__ __launch_bounds__(kStepThreads) void step_advance_classes_kernel(
 }
 
 // Bulk store of new rows: one wavefront per (tile, K or V, KV head).  A tile's destination is
-// one contiguous run of 16 * D * 2 bytes of the pool; its source rows are D * 2 bytes each,
+// one contiguous run of 16 * D * 2 bytes of the pool (the head's K or V rows in the tile's slab); its source rows are D * 2 bytes each,
 // G * D * 2 bytes apart (token-major input, as a projection writes it).  Every lane moves 16
 // bytes per load; rows outside [first, last) of the tile are left alone.
 struct BulkArgs {
@@ -657,7 +987,7 @@ struct BulkArgs {
   uint16_t *pool;
   const int4 *tiles;
   const int32_t *row_base;
-  int32_t G, tcap, n_units;
+  int32_t G, gg, tcap, n_units;
   int32_t drain_each_tile;   // wait for a tile's stores before starting the next one
 };
 
@@ -666,7 +996,6 @@ __global__ __launch_bounds__(256) void bulk_append_kernel(const BulkArgs a) {
   constexpr int LPR = D / 8, RPL = 64 / LPR, LPT = D / 32;
   const int lane = threadIdx.x & 63;
   const int row = lane / LPR, col = lane % LPR;
-  const int64_t slice = (int64_t)a.tcap * D;
   const int n_waves = gridDim.x * 4;
   for (int unit = blockIdx.x * 4 + (threadIdx.x >> 6); unit < a.n_units; unit += n_waves) {
     const int t = unit / (2 * a.G);
@@ -676,9 +1005,9 @@ __global__ __launch_bounds__(256) void bulk_append_kernel(const BulkArgs a) {
     const int b = tile.x, pos0 = tile.y << 4;
     const int first = tile.z & 0xff, last = tile.z >> 8;      // slots of the tile to store: [first, last)
     const int blk = tile.w;
-    const int slot0 = PAGED ? pos0 & (a.tcap - 1) : pos0;
+    const TileAddr ta = tile_addr<D>(a.G, a.gg, a.tcap, g);
     const uint16_t *src = (kv ? a.v_rows : a.k_rows) + (size_t)g * D + col * 8;
-    uint16_t *dst = a.pool + ((int64_t)blk * 2 * a.G + (int64_t)kv * a.G + g) * slice + (int64_t)slot0 * D + col * 8;
+    uint16_t *dst = a.pool + slab_base<PAGED>(ta, blk, tile.y) + (kv ? ta.head_v : ta.head_k) + col * 8;
     const int64_t base_row = (int64_t)a.row_base[b] + pos0;
     uint4 v[LPT];
     bool ok[LPT];
@@ -754,6 +1083,7 @@ hipError_t launch_bulk_append(const BulkLaunch &a, hipStream_t stream) {
   args.tiles = a.tiles;
   args.row_base = a.row_base;
   args.G = s.G;
+  args.gg = s.gg;
   args.tcap = s.tcap;
   const int64_t units = (int64_t)a.n_tiles * 2 * s.G;
   if (units > 0x7fffffff) return hipErrorInvalidValue;

@@ -11,6 +11,7 @@ from oracle import kv_layout, worklist
 from paper_2504_11816_amd import binding, synth
 from paper_2504_11816_amd.harness import Stack
 
+from layout_util import from_pool, to_pool
 from gpu_util import assert_close, build_stack, make_inputs, oracle_pairs, run_and_check
 
 pytestmark = pytest.mark.gpu
@@ -35,7 +36,7 @@ def test_cfg1_single_layer_all_outputs(T, out_dtype):
 # ---- several tiles, ragged tails, every head grouping --------------------------------
 
 @pytest.mark.parametrize("d", [64, 128])
-@pytest.mark.parametrize("H,G", [(4, 4), (4, 2), (8, 2), (8, 1)])
+@pytest.mark.parametrize("H,G", [(4, 4), (4, 2), (8, 2), (8, 1), (16, 1), (32, 2)])
 @pytest.mark.parametrize("T", [0, 16, 64])
 def test_ragged_contexts_all_groupings(d, H, G, T):
     say(f"ragged d={d} H={H} G={G} T={T}")
@@ -83,16 +84,16 @@ def test_paged_equals_contiguous_on_the_same_logical_kv_bit_for_bit():
     B, H, G, d, T, C = 3, 4, 2, 128, 16, 320
     ctx = np.array([16, 250, 303], dtype=np.int32)
     stc = build_stack(L=1, H=H, G=G, d=d, T=0, ctx_before=ctx, cap_tokens=C, out_dtype=1, seed=11)
-    pool_c = stc.read_pool(0).reshape(B, 2, G, C, d)
+    pool_c = from_pool(stc.read_pool(0), B, G, C, d)
     stp = build_stack(L=1, H=H, G=G, d=d, T=T, ctx_before=ctx, cap_tokens=C, out_dtype=1, seed=12,
                       shuffle_seed=5)
     # write the contiguous run's logical KV into the paged pool through the table
-    pool_p = stp.read_pool(0).reshape(stp.blocks_per_layer, 2, G, T, d)
+    pool_p = from_pool(stp.read_pool(0), stp.blocks_per_layer, G, T, d)
     for b in range(B):
         for i in range(C):
             blk = stp.block_table[b, i // T]
             pool_p[blk, :, :, i % T, :] = pool_c[b, :, :, i, :]
-    stp.pools[0].copy_(torch.from_numpy(pool_p.reshape(-1)))
+    stp.pools[0].copy_(torch.from_numpy(to_pool(pool_p)))
     torch.cuda.synchronize()
     outs = []
     for st in (stc, stp):
@@ -105,11 +106,11 @@ def test_paged_equals_contiguous_on_the_same_logical_kv_bit_for_bit():
     # and a second shuffle of the physical blocks changes nothing either
     stp2 = build_stack(L=1, H=H, G=G, d=d, T=T, ctx_before=ctx, cap_tokens=C, out_dtype=1, seed=13,
                        shuffle_seed=99)
-    pool_p2 = stp2.read_pool(0).reshape(stp2.blocks_per_layer, 2, G, T, d)
+    pool_p2 = from_pool(stp2.read_pool(0), stp2.blocks_per_layer, G, T, d)
     for b in range(B):
         for i in range(C):
             pool_p2[stp2.block_table[b, i // T], :, :, i % T, :] = pool_c[b, :, :, i, :]
-    stp2.pools[0].copy_(torch.from_numpy(pool_p2.reshape(-1)))
+    stp2.pools[0].copy_(torch.from_numpy(to_pool(pool_p2)))
     torch.cuda.synchronize()
     stp2.ctx.okv_set_split_tokens(128)
     q, k, v, out = make_inputs(stp2, 21, 0, stp2.device)
@@ -135,11 +136,11 @@ def test_closed_forms_on_gpu():
     # identical keys: the mean of the value rows; constant values: that constant
     n = 77
     st = build_stack(L=1, H=H, G=G, d=d, T=0, ctx_before=[n - 1, n - 1], cap_tokens=80, out_dtype=1, seed=35)
-    pool = st.read_pool(0).reshape(B, 2, G, st.max_ctx, d)
+    pool = from_pool(st.read_pool(0), B, G, st.max_ctx, d)
     key = synth.randn_f16_numpy((B, G, d), 36)
     pool[:, 0, :, :, :] = key[:, :, None, :]
     pool[1, 1] = np.float16(0.625)
-    st.pools[0].copy_(torch.from_numpy(pool.reshape(-1)))
+    st.pools[0].copy_(torch.from_numpy(to_pool(pool)))
     q, k, v, out = make_inputs(st, 37, 0, st.device)
     k[0].copy_(torch.from_numpy(key))
     v[0][1] = 0.625
@@ -147,7 +148,7 @@ def test_closed_forms_on_gpu():
     st.step(q, k, v, out)
     st.synchronize()
     got = out[0].cpu().numpy()
-    vals = st.read_pool(0).reshape(B, 2, G, st.max_ctx, d)[:, 1, :, :n, :].astype(np.float64)
+    vals = from_pool(st.read_pool(0), B, G, st.max_ctx, d)[:, 1, :, :n, :].astype(np.float64)
     np.testing.assert_allclose(got[0], vals[0].mean(axis=1), rtol=2e-6, atol=2e-6)
     np.testing.assert_allclose(got[1], np.full((H, d), 0.625), rtol=1e-6)
     st.close()

@@ -179,6 +179,14 @@ def test_size_queries_and_shape_errors():
                               max_batch=4, max_blocks_per_seq=16, blocks_per_layer=64,
                               resident_blocks=24, chunk_blocks=8)
     assert binding.okv_block_bytes(cfg) == 2 * 8 * 16 * 64 * 2
+    # KV heads per group of the pool layout: the library's rule against the oracle's statement of it
+    from oracle import kv_layout
+    for G in list(range(1, 41)) + [48, 64, 96, 128]:
+        for d in (64, 128):
+            assert binding.okv_kv_head_group(G, d) == kv_layout.head_group(G, d)
+    assert binding.okv_kv_head_group(32, 128) == 8 and binding.okv_kv_head_group(32, 64) == 16
+    with pytest.raises(binding.OkvError):
+        binding.okv_kv_head_group(8, 96)
     # 16 blocks of 16 tokens at the default split of 512 -> 1 item, plus one per chunk of the host pool (5)
     assert binding.okv_workspace_bytes(cfg) == 4 * (1 + 5) * 8 * 66 * 4
     for bad in (dict(resident_blocks=65), dict(resident_blocks=-1), dict(chunk_blocks=-2), dict(block_tokens=0, max_ctx=256)):

@@ -4,6 +4,8 @@ show each plausible mistake is caught by at least one pin.  CPU only."""
 import math
 
 import numpy as np
+
+from layout_util import to_pool
 import pytest
 
 from oracle import attention as oa
@@ -187,9 +189,9 @@ def _contig_case(B, H, G, d, n_list, C, seed):
 
 
 def test_batch_oracle_matches_attend_one_by_direct_slicing():
-    B, H, G, d, C = 3, 4, 2, 8, 12
-    q, pool, layout, n = _contig_case(B, H, G, d, [1, 7, 12], C, 200)
-    out = oa.decode_attn(q, pool.reshape(-1), layout, n, H)
+    B, H, G, d, C = 3, 4, 2, 8, 32
+    q, pool, layout, n = _contig_case(B, H, G, d, [1, 17, 32], C, 200)
+    out = oa.decode_attn(q, to_pool(pool), layout, n, H)
     for b in range(B):
         for h in range(H):
             g = h // (H // G)
@@ -199,21 +201,21 @@ def test_batch_oracle_matches_attend_one_by_direct_slicing():
 
 
 def test_gqa_equals_mha_on_replicated_kv():
-    B, H, G, d, C = 2, 8, 2, 8, 10
-    q, pool, layout, n = _contig_case(B, H, G, d, [10, 4], C, 210)
-    out_gqa = oa.decode_attn(q, pool.reshape(-1), layout, n, H)
+    B, H, G, d, C = 2, 8, 2, 8, 32
+    q, pool, layout, n = _contig_case(B, H, G, d, [20, 4], C, 210)
+    out_gqa = oa.decode_attn(q, to_pool(pool), layout, n, H)
     rep = np.repeat(pool, H // G, axis=2)                       # KV head g -> heads g*4 .. g*4+3
     layout_mha = {"kind": "contiguous", "G": H, "d": d, "C": C}
-    out_mha = oa.decode_attn(q, rep.reshape(-1), layout_mha, n, H)
+    out_mha = oa.decode_attn(q, to_pool(rep), layout_mha, n, H)
     np.testing.assert_array_equal(out_gqa, out_mha)
 
 
 def test_paged_equals_contiguous_and_is_invariant_to_block_permutation():
-    B, H, G, d, T = 3, 4, 2, 8, 4
-    n = np.array([5, 16, 9], dtype=np.int32)
-    C = 16
+    B, H, G, d, T = 3, 4, 2, 8, 16
+    n = np.array([5, 64, 33], dtype=np.int32)
+    C = 64
     q, pool_c, layout_c, _ = _contig_case(B, H, G, d, n, C, 220)
-    want = oa.decode_attn(q, pool_c.reshape(-1), layout_c, n, H)
+    want = oa.decode_attn(q, to_pool(pool_c), layout_c, n, H)
     n_blocks = 20
     for seed in (1, 2):
         table = synth.shuffled_block_table([C] * B, T, n_blocks, seed)
@@ -223,15 +225,15 @@ def test_paged_equals_contiguous_and_is_invariant_to_block_permutation():
                 blk = table[b, i // T]
                 pool_p[blk, :, :, i % T, :] = pool_c[b, :, :, i, :]
         layout_p = {"kind": "paged", "G": G, "d": d, "T": T, "block_table": table}
-        got = oa.decode_attn(q, pool_p.reshape(-1), layout_p, n, H)
+        got = oa.decode_attn(q, to_pool(pool_p), layout_p, n, H)
         np.testing.assert_array_equal(got, want)
 
 
 def test_sampled_pairs_equal_full_run():
-    B, H, G, d, C = 3, 4, 4, 8, 9
-    q, pool, layout, n = _contig_case(B, H, G, d, [9, 2, 5], C, 230)
-    full = oa.decode_attn(q, pool.reshape(-1), layout, n, H)
-    part = oa.decode_attn(q, pool.reshape(-1), layout, n, H, sample=[(2, 3), (0, 1)])
+    B, H, G, d, C = 3, 4, 4, 8, 16
+    q, pool, layout, n = _contig_case(B, H, G, d, [9, 2, 16], C, 230)
+    full = oa.decode_attn(q, to_pool(pool), layout, n, H)
+    part = oa.decode_attn(q, to_pool(pool), layout, n, H, sample=[(2, 3), (0, 1)])
     np.testing.assert_array_equal(part[2, 3], full[2, 3])
     np.testing.assert_array_equal(part[0, 1], full[0, 1])
     assert np.isnan(part[1, 0]).all()
@@ -277,9 +279,9 @@ def test_output_spread_of_the_synthetic_workload():
 
 
 def test_append_scatter_then_attend_sees_the_new_token():
-    B, H, G, d, T = 2, 2, 2, 4, 4
-    n_before = np.array([3, 4], dtype=np.int32)                 # second one opens a new block
-    table = synth.shuffled_block_table([8, 8], T, 6, 3)
+    B, H, G, d, T = 2, 2, 2, 4, 16
+    n_before = np.array([15, 16], dtype=np.int32)               # second one opens a new block
+    table = synth.shuffled_block_table([32, 32], T, 6, 3)
     pool = synth.randn_f16_numpy((6, 2, G, T, d), 260)
     layout = {"kind": "paged", "G": G, "d": d, "T": T, "block_table": table}
     k_new, v_new = synth.randn_f16_numpy((B, G, d), 261), synth.randn_f16_numpy((B, G, d), 262)
@@ -311,18 +313,35 @@ def test_append_scatter_then_attend_sees_the_new_token():
 
 def test_layout_offsets_address_probe():
     # Every (coordinate) -> offset map is a bijection onto the pool and row
-    # major in the stated order: fill by nested loops, compare with reshape.
-    G, T, d, nblk = 3, 4, 2, 5
-    ref = np.arange(nblk * 2 * G * T * d).reshape(nblk, 2, G, T, d)
-    for blk in range(nblk):
-        for kv in range(2):
-            for g in range(G):
-                for s in range(T):
-                    assert kv_layout.paged_row_offset(blk, kv, g, s, G, T, d) == ref[blk, kv, g, s, 0]
-    B, C = 3, 5
-    ref = np.arange(B * 2 * G * C * d).reshape(B, 2, G, C, d)
-    for b in range(B):
-        for kv in range(2):
-            for g in range(G):
-                for t in range(C):
-                    assert kv_layout.contiguous_row_offset(b, kv, g, t, G, C, d) == ref[b, kv, g, t, 0]
+    # major in the stated order: number the elements of a pool shaped as the
+    # description reads ([slabs][group][kv][head in group][slot][d]) and look
+    # every row up.
+    for G, d, Gg in ((16, 128, 8), (32, 64, 16), (3, 64, 3), (12, 128, 6)):
+        assert kv_layout.head_group(G, d) == Gg
+        T, nblk = 32, 3
+        ref = np.arange(nblk * (T // 16) * 2 * G * 16 * d).reshape(nblk, T // 16, G // Gg, 2, Gg, 16, d)
+        seen = set()
+        for blk in range(nblk):
+            for kv in range(2):
+                for g in range(G):
+                    for s in range(T):
+                        off = kv_layout.paged_row_offset(blk, kv, g, s, G, T, d)
+                        assert off == ref[blk, s // 16, g // Gg, kv, g % Gg, s % 16, 0]
+                        seen.add(off)
+        assert len(seen) == nblk * 2 * G * T and max(seen) == ref.size - d
+        B, C = 3, 48
+        ref = np.arange(B * (C // 16) * 2 * G * 16 * d).reshape(B, C // 16, G // Gg, 2, Gg, 16, d)
+        for b in range(B):
+            for kv in range(2):
+                for g in range(G):
+                    for t in range(C):
+                        assert kv_layout.contiguous_row_offset(b, kv, g, t, G, C, d) == ref[b, t // 16, g // Gg, kv, g % Gg, t % 16, 0]
+
+
+def test_head_group_rule():
+    # the largest divisor of G whose K rows of one 16-token tile fit in 32 KiB (Gg * d <= 1024)
+    want = {(32, 128): 8, (8, 128): 8, (4, 128): 4, (1, 128): 1, (32, 64): 16, (16, 64): 16, (12, 128): 6,
+            (7, 128): 7, (9, 128): 3, (40, 128): 8, (24, 64): 12, (11, 128): 1}
+    for (G, d), Gg in want.items():
+        assert kv_layout.head_group(G, d) == Gg, (G, d)
+        assert G % Gg == 0 and Gg * 16 * d * 2 <= 32768

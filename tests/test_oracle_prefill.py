@@ -5,6 +5,8 @@ import numpy as np
 
 from oracle import kv_bytes, kv_layout
 
+from layout_util import from_pool, to_pool
+
 
 def _random_case(rng, paged):
     G, d, T = int(rng.integers(1, 4)), int(rng.choice([4, 8])), 16
@@ -30,18 +32,18 @@ def _random_case(rng, paged):
 
 
 def test_bulk_store_equals_indexing_the_reshaped_pool():
-    # the same store written through numpy's own N-d indexing of the pool
+    # the same store written through numpy's own N-d indexing of the pool, brought into logical order by a
+    # reshape and a transposition and back
     rng = np.random.default_rng(3)
     for trial in range(40):
         paged = trial % 2 == 0
         layout, pool, before, n_new, k, v = _random_case(rng, paged)
         G, d = layout["G"], layout["d"]
-        want = pool.copy()
         if paged:
             T = layout["T"]
-            view = want.reshape(-1, 2, G, T, d)
+            view = from_pool(pool, len(pool) // (2 * G * T * d), G, T, d)
         else:
-            view = want.reshape(len(n_new), 2, G, layout["C"], d)
+            view = from_pool(pool, len(n_new), G, layout["C"], d)
         row = 0
         for b in range(len(n_new)):
             for i in range(int(n_new[b])):
@@ -53,6 +55,7 @@ def test_bulk_store_equals_indexing_the_reshaped_pool():
                     view[b, 0, :, pos, :] = k[row]
                     view[b, 1, :, pos, :] = v[row]
                 row += 1
+        want = to_pool(view)
         got = kv_layout.bulk_append_scatter(pool.copy(), layout, before, n_new, k, v)
         np.testing.assert_array_equal(got, want)
 
