@@ -101,16 +101,19 @@ def timed_steps(st, ctx0, table, inputs, steps, warmup):
     return time.perf_counter() - t0
 
 
-def kernel_time(st, ctx0, table, inputs, steps):
-    """Same K steps again with every split-K kernel bracketed by HIP events on
-    the compute stream: summed kernel time (s) and number of launches."""
+def kernel_time(st, ctx0, table, inputs, steps, per_step=False):
+    """Same K steps again with the split-K kernels bracketed by HIP events on the
+    compute stream: summed bracket time (s) and number of launches.  per_step: one
+    bracket around each step's launches, which then run back to back as in the
+    timed region (all layers resident); else one bracket per launch, which leaves
+    the GPU idle for a few microseconds before every kernel."""
     q, k, v, out = inputs
     st.set_batch(ctx0, table)
-    st.ctx.okv_profile_enable(True)
+    st.ctx.okv_profile_enable(2 if per_step else 1)
     for _ in range(steps):
         st.step(q, k, v, out)
     ms, n = st.ctx.okv_profile_read()
-    st.ctx.okv_profile_enable(False)
+    st.ctx.okv_profile_enable(0)
     return ms * 1e-3, n
 
 
@@ -180,7 +183,7 @@ def run_resident(args):
     split = st.ctx.okv_get_split_tokens()
     kv_bytes = kv_bytes_of_steps(ctx0, steps, G, d, L)
     log(f"[bench] {steps} steps in {dt * 1e3:.1f} ms, split {split}")
-    k_s, k_n = kernel_time(st, ctx0, table, inputs, steps)
+    k_s, k_n = kernel_time(st, ctx0, table, inputs, steps, per_step=True)
     log(f"[bench] split-K kernel: {k_n} launches, {k_s / max(k_n, 1) * 1e6:.1f} us average")
     res = {
         "tokens_per_s": B * steps / dt, "ms_per_step": dt / steps * 1e3, "kv_gbps": kv_bytes / dt / 1e9,
@@ -558,7 +561,7 @@ def run_model(args, off):
         inputs = fixed_inputs(st, args.seed)
         ctx0 = np.full(B, ctx - 1, dtype=np.int32)
         kernel_time(st, ctx0, table, inputs, 1)              # warm-up
-        k_s, k_n = kernel_time(st, ctx0, table, inputs, steps)
+        k_s, k_n = kernel_time(st, ctx0, table, inputs, steps, per_step=True)
         times[B] = k_s / k_n                                  # seconds per layer and step
         st.close()
         del st
@@ -658,7 +661,8 @@ def main():
         "roofline": {"bound": "hbm", "achieved": res["kernel_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": res["kernel_gbps"] / HBM_PEAK_GBPS,
                      "traffic": recorded_traffic(args.workload, res["steps"]),
-                     "kernel": "attn_split_kernel", "avg_us": res["kernel_avg_us"],
+                     "kernel": ("attn_split_mfma_kernel" if res["H"] // res["G"] in (1, 8, 16) else "attn_split_kernel"),
+                     "avg_us": res["kernel_avg_us"],
                      "launches": res["kernel_launches"], "bytes_per_launch": res["kv_bytes_per_launch"]},
         "cpu_baseline": cpu,
         "offload": off,

@@ -350,11 +350,18 @@ int okv_worklist(okv_ctx *ctx, int32_t from_device, int32_t *items, int64_t max_
 int okv_worklist_classes(okv_ctx *ctx, int32_t from_device, int32_t *class_first,
                          int32_t max_classes, int32_t *n_classes);
 
-/* Per-kernel timing.  While enabled every decode_attn brackets its split-K kernel
- * with HIP events on the compute stream.  okv_profile_read waits for the stream,
- * returns the summed kernel time (ms) and the number of launches since the last
- * read, and resets both.  The time an empty pair of event records takes on the
- * same stream (median of 15, measured at the read) is subtracted per launch. */
+/* Kernel timing with HIP events on the compute stream.
+ *   on = 1  every split-K launch is bracketed by a pair of events of its own.  The
+ *           markers leave the GPU idle for some microseconds before each kernel.
+ *   on = 2  one bracket per decode step, from just before the step's first split-K
+ *           launch (after the step's bookkeeping kernel) to okv_step_end: the
+ *           kernels run back to back as they do untimed; merge passes, where a
+ *           step needs them, and the copy waits of host layers fall inside it.
+ *   on = 0  off.  Not to be changed inside a step.
+ * okv_profile_read waits for the stream, returns the summed bracket time (ms) and the
+ * number of split-K launches inside the brackets since the last read, and resets both.
+ * The time an empty pair of event records takes on the same stream (median of 15,
+ * measured at the read) is subtracted per bracket. */
 int okv_profile_enable(okv_ctx *ctx, int32_t on);
 int okv_profile_read(okv_ctx *ctx, double *attn_ms, int64_t *attn_launches);
 

@@ -377,7 +377,8 @@ class Context:
         return ms.value
 
     def okv_profile_enable(self, on):
-        self._c(lib().okv_profile_enable(self._h, 1 if on else 0))
+        """0 / False: off; 1 / True: a bracket per split-K launch; 2: a bracket per step."""
+        self._c(lib().okv_profile_enable(self._h, int(on)))
 
     def okv_profile_read(self):
         ms, n = ctypes.c_double(0), ctypes.c_int64(0)

@@ -121,9 +121,11 @@ struct okv_ctx {
   okv::Scheduler sched;
   hipEvent_t ready_ev[kEventRing] = {}, consumed_ev[kEventRing] = {};
 
-  bool profile = false;
+  int profile = 0;                       // 0 off, 1 a bracket per split-K launch, 2 a bracket per step
   std::vector<std::pair<hipEvent_t, hipEvent_t>> prof_events;
   size_t prof_used = 0;
+  int64_t prof_launches = 0;             // split-K launches inside the brackets
+  bool prof_open = false;                // per-step mode: the step's bracket has begun
 
   std::string err;
 };
@@ -345,7 +347,7 @@ int exec_op(okv_ctx *ctx, const Op &op, const void *a0, const void *a1, void *ou
       a.pool_mirror = op.buf >= 0 ? ctx->host_pool[op.layer] : nullptr;
       a.out = out;
       hipEvent_t e0 = nullptr, e1 = nullptr;
-      if (ctx->profile) {
+      if (ctx->profile == 1 || (ctx->profile == 2 && !ctx->prof_open)) {
         if (ctx->prof_used == ctx->prof_events.size()) {
           hipEvent_t x, y;
           OKV_HIP(ctx, hipEventCreate(&x));
@@ -353,9 +355,14 @@ int exec_op(okv_ctx *ctx, const Op &op, const void *a0, const void *a1, void *ou
           ctx->prof_events.emplace_back(x, y);
         }
         e0 = ctx->prof_events[ctx->prof_used].first;
-        e1 = ctx->prof_events[ctx->prof_used].second;
-        ++ctx->prof_used;
+        if (ctx->profile == 1) {
+          e1 = ctx->prof_events[ctx->prof_used].second;
+          ++ctx->prof_used;
+        } else {
+          ctx->prof_open = true;                         // okv_step_end records the closing event
+        }
       }
+      if (ctx->profile) ++ctx->prof_launches;
       OKV_HIP(ctx, okv::launch_decode_attn(a, ctx->compute, e0, e1));
       return OKV_OK;
     }
@@ -858,6 +865,11 @@ int okv_step_end(okv_ctx *ctx) {
   if (!ctx->in_step) return fail(ctx, OKV_ESTATE, "okv_step_end outside a step");
   if (ctx->next_layer != ctx->cfg.n_layers)
     return fail(ctx, OKV_ESTATE, "okv_step_end after %d of %d layers", ctx->next_layer, ctx->cfg.n_layers);
+  if (ctx->prof_open) {
+    OKV_HIP(ctx, hipEventRecord(ctx->prof_events[ctx->prof_used].second, ctx->compute));
+    ++ctx->prof_used;
+    ctx->prof_open = false;
+  }
   ctx->in_step = false;
   ctx->step += 1;
   return OKV_OK;
@@ -1215,7 +1227,9 @@ int okv_worklist_classes(okv_ctx *ctx, int32_t from_device, int32_t *class_first
 
 int okv_profile_enable(okv_ctx *ctx, int32_t on) {
   if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
-  ctx->profile = on != 0;
+  if (on < 0 || on > 2) return fail(ctx, OKV_EINVAL, "okv_profile_enable: mode %d outside 0..2", on);
+  if (ctx->in_step) return fail(ctx, OKV_ESTATE, "okv_profile_enable inside a step");
+  ctx->profile = on;
   return OKV_OK;
 }
 
@@ -1256,8 +1270,9 @@ int okv_profile_read(okv_ctx *ctx, double *attn_ms, int64_t *attn_launches) {
   }
   total -= overhead * (double)ctx->prof_used;
   *attn_ms = total > 0 ? total : 0;
-  *attn_launches = (int64_t)ctx->prof_used;
+  *attn_launches = ctx->prof_launches;
   ctx->prof_used = 0;
+  ctx->prof_launches = 0;
   return OKV_OK;
 }
 

@@ -767,15 +767,23 @@ hipError_t launch_split_mfma(const AttnArgs &args, bool paged, dim3 grid, hipStr
   return hipGetLastError();
 }
 
-// Group sizes from this one on take the matrix-core kernel.  Below it the lane-by-lane kernel is not
-// bound by arithmetic, and on the ragged batch of 128 sequences with 4 heads per KV head it was the
-// faster of the two (209 against 207..221 us per launch over the settings tried).
-#ifndef OKV_MFMA_MIN_R
-#define OKV_MFMA_MIN_R 8
+// Which group sizes take the matrix-core kernel.  8 and 16 heads per KV head are bound by vector
+// arithmetic in the lane-by-lane kernel (4.7 against 6.5 TB/s).  With one head per KV head both are
+// bound by memory, and the matrix-core kernel, which has next to no vector work left per tile, is the
+// faster one (62 against 66 us per launch on the 32-layer MHA stack at contexts 513..1024).  With 2 and
+// 4 heads it wins on uniform batches (6.4 against 5.9 TB/s) and loses on the ragged batch of 128
+// sequences cut into 1024-key items (213 against 210 us per launch); those stay where they were.
+constexpr bool use_matrix_cores(int R) {
+#ifdef OKV_MFMA_ALL
+  return true;
+#else
+  return R == 1 || R >= 8;
 #endif
+}
+
 template <int D, int R>
 hipError_t launch_split_pick(const AttnArgs &args, bool paged, dim3 grid, hipStream_t stream) {
-  if (R >= OKV_MFMA_MIN_R) return launch_split_mfma<D, R>(args, paged, grid, stream);
+  if (use_matrix_cores(R)) return launch_split_mfma<D, R>(args, paged, grid, stream);
   return launch_split_layout<D, (R > 8 ? 8 : R)>(args, paged, grid, stream);
 }
 

@@ -88,7 +88,8 @@ def test_large_blocks_and_a_single_chunk():
 
 def test_placement_does_not_change_the_result_beyond_rounding():
     # the same K/V bytes under three placements: outputs agree with the oracle each time, and with
-    # each other up to the order of the fp32 sums
+    # each other up to the order of the fp32 sums and the fp16 rounding of the softmax weights (taken
+    # relative to each item's own running maximum, so it depends on how the keys are cut into items)
     say("classes: placements agree")
     ctx = [90, 300, 511]
     outs = {}
@@ -116,7 +117,7 @@ def test_placement_does_not_change_the_result_beyond_rounding():
         st.close()
     base = outs[("prefix", Fraction(0))]
     for key, o in outs.items():
-        assert np.abs(o - base).max() < 2e-5, key
+        assert np.abs(o - base).max() < 2e-4, key
 
 
 def test_worklist_by_class_matches_oracle_bit_for_bit():

@@ -373,3 +373,21 @@ def test_full_size_cfg4_gqa_ragged_sampled():
     ctx = synth.ragged_ctx_lens(128, 512, 4096, 97) - 1
     lo, hi = int(np.argmin(ctx)), int(np.argmax(ctx))
     _sampled_full_size("cfg4", 128, 32, 8, 16, ctx, 4112, None, [(lo, 0), (hi, 31), (64, 13), (1, 20)])
+
+
+def test_kernel_timing_modes_count_every_launch():
+    say("profile modes")
+    st = build_stack(L=3, H=4, G=4, d=64, T=16, ctx_before=[40, 100], cap_tokens=128, seed=301)
+    for mode in (1, 2):
+        st.ctx.okv_profile_enable(mode)
+        for step in range(4):
+            q, k, v, out = make_inputs(st, 303, step, st.device)
+            st.step(q, k, v, out)
+        ms, n = st.ctx.okv_profile_read()
+        assert n == 3 * 4 and 0 < ms < 100
+        st.ctx.okv_profile_enable(0)
+        assert st.ctx.okv_profile_read() == (0.0, 0)
+    with pytest.raises(binding.OkvError) as e:
+        st.ctx.okv_profile_enable(3)
+    assert e.value.code == binding.OKV_EINVAL
+    st.close()
