@@ -35,8 +35,8 @@ PCIE5_X16_GBPS = 64.0       # nominal, one direction
 # okv_kernels.hip has changed since, `traffic` is reported as null.
 TRAFFIC_RECORD = {
     "workload": "cfg2", "steps": 512,
-    "kernel_sha256": "f290e5bb1785d910e525dd26f574adfffae4a15e51beb0fba754f662dac9c2fb",
-    "fetch_kib": 199111.8, "fetch_scale": 2.0000,
+    "kernel_sha256": "e94f26d35600defab3b0755dce4caf5f6710601cfb1622e96933e61e96ea9e90",
+    "fetch_kib": 199057.5, "fetch_scale": 2.0000,
     "write_kib": 768.0, "write_scale": 1.0000,
 }
 
@@ -608,7 +608,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="decode steps to time (0 = the workload's own count)")
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg4", "gqa8", "gqa16"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3_resident", "cfg4", "gqa8", "gqa16"])
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--layers", type=int, default=0,
                     help="run only this many layers of the stack (counter runs: per-launch figures do not "

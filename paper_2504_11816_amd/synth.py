@@ -179,6 +179,8 @@ WORKLOADS = {
                  ragged=(512, 4096), note="GQA 32/8, ragged contexts, paged, resident"),
     "cfg5": dict(L=32, H=32, G=32, d=128, B=192, ctx=4096, steps=3, T=16, c_off=(3, 5), ragged=None,
                  note="offline large batch, 60% of layers on host"),
+    "cfg3_resident": dict(L=32, H=32, G=32, d=128, B=64, ctx=2048, steps=8, T=16, c_off=(0, 1), ragged=None,
+                          note="the cfg3 stack with every layer in HBM: what the attention alone costs there"),
     # beyond the paper's models (all of them one query head per KV head): larger query groups at the same
     # 1 GiB of KV per layer, the shapes that take the matrix-core kernel
     "gqa8": dict(L=32, H=64, G=8, d=128, B=128, ctx=2048, steps=20, T=16, c_off=(0, 1), ragged=None,
