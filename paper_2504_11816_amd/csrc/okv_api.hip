@@ -21,19 +21,20 @@ using okv::Op;
 namespace {
 
 constexpr int kEventRing = 8;            // > copies in flight (at most OKV_MAX_STAGING)
-// Persistent wavefronts per compute unit.  With one query head per KV head the kernel is
-// light on the vector ALU and two wavefronts per SIMD hide each other's item switches;
-// with grouped heads one per SIMD measured faster (5.9 against 5.6 TB/s on ragged batches).
+// Wavefronts of the persistent attention launch per compute unit: one per SIMD.  The kernels keep one tile
+// (matrix-core form) or two (lane by lane) of 8 KiB in flight per wavefront, and about 1000 wavefronts
+// saturate the memory system: with 2048 equal units, 4 per compute unit working through two units each
+// reach 6.5 TB/s and 8 per compute unit with one unit each 6.1-6.3; ragged batches gain less (0-4 %).
+// (The lane-by-lane kernel with one head per KV head, no longer used, was the exception: 8 measured
+// faster there.)
 #ifndef OKV_WAVES_PER_CU_MHA
-#define OKV_WAVES_PER_CU_MHA 8
+#define OKV_WAVES_PER_CU_MHA 4
 #endif
 #ifndef OKV_WAVES_PER_CU_GQA
 #define OKV_WAVES_PER_CU_GQA 4
 #endif
-// 8 and 16 heads per KV head run on the matrix cores with one tile in flight per wavefront; there two
-// wavefronts per SIMD (all its registers allow) measured best: 6.4 TB/s against 5.8 with one.
 #ifndef OKV_WAVES_PER_CU_MFMA
-#define OKV_WAVES_PER_CU_MFMA 8
+#define OKV_WAVES_PER_CU_MFMA 4
 #endif
 constexpr int32_t kMinAutoSplit = 128;   // smallest split size the library picks by itself
 constexpr int32_t kClassSplit = 512;     // split size with block classes unless the caller sets one
