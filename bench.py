@@ -170,7 +170,8 @@ def run_resident(args):
         on_host = binding.kv_offload_plan(L, w["c_off"][0], w["c_off"][1])[0]
     log(f"[bench] {args.workload}: L={L} H={H} G={G} d={d} B={B} T={T} ctx {int(ctx_first.min())}..{int(ctx_first.max())} "
         f"steps={steps} capacity={cap}")
-    st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=cap, on_host=on_host, out_dtype=0)
+    st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=cap, on_host=on_host, out_dtype=0,
+               split_tokens=args.split_tokens)
     for l in range(L):
         st.fill_pool(l, synth.stream_seed(args.seed, synth.TENSOR_POOL, l))
     table = None
@@ -610,6 +611,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=8)
     ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3_resident", "cfg4", "gqa8", "gqa16"])
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--split-tokens", type=int, default=0,
+                    help="resident leg: upper bound on the keys of one work item (0 = the library chooses)")
     ap.add_argument("--layers", type=int, default=0,
                     help="run only this many layers of the stack (counter runs: per-launch figures do not "
                          "depend on the depth); 0 = the workload's own depth")
@@ -661,7 +664,7 @@ def main():
         "roofline": {"bound": "hbm", "achieved": res["kernel_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": res["kernel_gbps"] / HBM_PEAK_GBPS,
                      "traffic": recorded_traffic(args.workload, res["steps"]),
-                     "kernel": ("attn_split_mfma_kernel" if res["H"] // res["G"] in (1, 8, 16) else "attn_split_kernel"),
+                     "kernel": "attn_split_mfma_kernel",
                      "avg_us": res["kernel_avg_us"],
                      "launches": res["kernel_launches"], "bytes_per_launch": res["kv_bytes_per_launch"]},
         "cpu_baseline": cpu,

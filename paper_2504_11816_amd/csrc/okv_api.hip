@@ -83,7 +83,7 @@ struct okv_ctx {
 
   int32_t *d_block_table = nullptr, *d_ctx_lens = nullptr, *d_chunk_prefix = nullptr;
   int4 *d_item_desc = nullptr;
-  uint32_t *d_queues = nullptr;          // one ticket counter per layer, zeroed at every step
+  uint32_t *d_queues = nullptr;          // one ticket counter per layer and class, zeroed at every step
   int32_t *d_items_dump = nullptr;
   int32_t max_waves = 0;                 // wavefronts of the persistent attention launch
   int64_t max_items = 0;
@@ -158,7 +158,7 @@ const char *shape_problem(const okv_config *c) {
   if (c->n_layers < 1) return "n_layers < 1";
   if (c->n_kv_heads < 1 || c->n_q_heads < 1 || c->n_q_heads % c->n_kv_heads) return "n_q_heads must be a multiple of n_kv_heads";
   int r = c->n_q_heads / c->n_kv_heads;
-  if (r != 1 && r != 2 && r != 4 && r != 8 && r != 16) return "n_q_heads / n_kv_heads must be 1, 2, 4, 8 or 16";
+  if (r < 1 || r > 16) return "n_q_heads / n_kv_heads must be between 1 and 16";
   if (c->n_kv_heads > 65535) return "n_kv_heads too large";
   if (c->head_dim != 64 && c->head_dim != 128) return "head_dim must be 64 or 128";
   if (c->max_batch < 1 || c->max_batch > 65535) return "max_batch out of range";

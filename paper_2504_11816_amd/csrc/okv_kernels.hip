@@ -65,93 +65,11 @@ __device__ __forceinline__ int64_t slab_base(const TileAddr &t, int blk, int til
   return ((int64_t)blk * t.tiles + (PAGED ? tile & (t.tiles - 1) : tile)) * t.slab_elems;
 }
 
-template <int CTRL>
-__device__ __forceinline__ float dpp_move(float x) {
-  return __builtin_bit_cast(
-      float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xf, 0xf, true));
-}
-
-// Sum over a row of LANES (8 or 16) consecutive lanes; every lane of the row gets the sum.
-template <int LANES>
-__device__ __forceinline__ float row_sum(float x) {
-  x += dpp_move<0xB1>(x);    // quad_perm [1,0,3,2]
-  x += dpp_move<0x4E>(x);    // quad_perm [2,3,0,1]
-  x += dpp_move<0x141>(x);   // row_half_mirror
-  if (LANES == 16) x += dpp_move<0x140>(x);   // row_mirror
-  return x;
-}
-
-__device__ __forceinline__ float dot8(const uint4 &k, const uint4 &q) {
-  float acc = 0.f;
-  acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, k.x), __builtin_bit_cast(half2_t, q.x), acc, false);
-  acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, k.y), __builtin_bit_cast(half2_t, q.y), acc, false);
-  acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, k.z), __builtin_bit_cast(half2_t, q.z), acc, false);
-  acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, k.w), __builtin_bit_cast(half2_t, q.w), acc, false);
-  return acc;
-}
-
-__device__ __forceinline__ void axpy8(float (&o)[8], float p, const uint4 &v) {
-  half2_t a = __builtin_bit_cast(half2_t, v.x), b = __builtin_bit_cast(half2_t, v.y);
-  half2_t c = __builtin_bit_cast(half2_t, v.z), d = __builtin_bit_cast(half2_t, v.w);
-  o[0] = __builtin_fmaf((float)a.x, p, o[0]);
-  o[1] = __builtin_fmaf((float)a.y, p, o[1]);
-  o[2] = __builtin_fmaf((float)b.x, p, o[2]);
-  o[3] = __builtin_fmaf((float)b.y, p, o[3]);
-  o[4] = __builtin_fmaf((float)c.x, p, o[4]);
-  o[5] = __builtin_fmaf((float)c.y, p, o[5]);
-  o[6] = __builtin_fmaf((float)d.x, p, o[6]);
-  o[7] = __builtin_fmaf((float)d.y, p, o[7]);
-}
-
 template <int LPT>
 struct Tile {
   uint4 k[LPT];
   uint4 v[LPT];
 };
-
-// Online-softmax update of one wavefront with one 16-token tile.
-//   tok0: token index of this lane's row in load 0; load j holds token tok0 + j * RPL.
-//   MASKED: tokens outside [lo, hi) get score -inf (weight exactly 0; the running max
-//   stays finite because it starts at kNegBig) and their V rows are read as zero, since
-//   unused slots may hold NaN bit patterns.  Only the first / last tile of an item
-//   can need it; the steady-state loop uses the unmasked form.
-template <int D, int R, bool MASKED>
-__device__ __forceinline__ void tile_update(const Tile<D / 32> &t, const uint4 (&q)[R], float (&m)[R],
-                                            float (&l)[R], float (&o)[R][8], int tok0, int lo,
-                                            int hi, float scale) {
-  constexpr int LPR = D / 8, RPL = 64 / LPR, LPT = D / 32;
-  bool valid[LPT];
-  uint4 v[LPT];
-#pragma unroll
-  for (int j = 0; j < LPT; ++j) {
-    const int tok = tok0 + j * RPL;
-    valid[j] = !MASKED || (tok >= lo && tok < hi);
-    v[j] = valid[j] ? t.v[j] : make_uint4(0u, 0u, 0u, 0u);
-  }
-#pragma unroll
-  for (int r = 0; r < R; ++r) {
-    float s[LPT];
-    float mx = m[r];
-#pragma unroll
-    for (int j = 0; j < LPT; ++j) {
-      const float x = row_sum<LPR>(dot8(t.k[j], q[r])) * scale;
-      s[j] = valid[j] ? x : -__builtin_inff();
-      mx = fmaxf(mx, s[j]);
-    }
-    const float alpha = __builtin_amdgcn_exp2f(m[r] - mx);
-    m[r] = mx;
-    float lsum = l[r] * alpha;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) o[r][e] *= alpha;
-#pragma unroll
-    for (int j = 0; j < LPT; ++j) {
-      const float p = __builtin_amdgcn_exp2f(s[j] - mx);
-      lsum += p;
-      axpy8(o[r], p, v[j]);
-    }
-    l[r] = lsum;
-  }
-}
 
 struct AttnArgs {
   const uint16_t *q;
@@ -174,193 +92,22 @@ struct AttnArgs {
   float scale_log2e;
 };
 
-// One work item (a run of keys of one sequence) for one KV head, by one wavefront.
-template <int D, int R, bool PAGED, int PIPE>
-__device__ __forceinline__ void attend_item(const AttnArgs &a, const int it, const int g, const int lane) {
-  constexpr int LPR = D / 8, RPL = 64 / LPR, LPT = D / 32;
-  const int row = lane / LPR, col = lane % LPR;
-  const int4 desc = a.item_desc[it];
-  const int b = desc.x, lo = desc.y, hi = desc.z;
-  const bool seq_last = (desc.w & kItemLast) != 0;        // the item ends at the sequence's last key
-  const bool seq_whole = (desc.w & kItemWhole) != 0;      // and is the sequence's only item
-
-  // The item that ends at the sequence's last key also stores this step's K/V rows
-  // (paper §II-A: keys and values of every processed token are kept).  The rows are
-  // patched into the tile in registers, so the attention below does not depend on
-  // reading its own store back; the store itself is issued after the reduction.
-  const int pos = hi - 1;
-  const bool appending = a.k_new != nullptr && seq_last;
-  uint4 k_row = make_uint4(0u, 0u, 0u, 0u), v_row = k_row;
-  if (appending) {
-    const size_t at = ((size_t)b * a.G + g) * LPR + col;
-    k_row = reinterpret_cast<const uint4 *>(a.k_new)[at];
-    v_row = reinterpret_cast<const uint4 *>(a.v_new)[at];
-  }
-
-  uint4 q[R];
-  {
-    const uint4 *qp = reinterpret_cast<const uint4 *>(a.q + ((size_t)b * a.H + (size_t)g * R) * D) + col;
-#pragma unroll
-    for (int r = 0; r < R; ++r) q[r] = qp[r * LPR];
-  }
-  float m[R], l[R], o[R][8];
-#pragma unroll
-  for (int r = 0; r < R; ++r) {
-    m[r] = kNegBig;
-    l[r] = 0.f;
-#pragma unroll
-    for (int e = 0; e < 8; ++e) o[r][e] = 0.f;
-  }
-
-  const int t0 = lo >> 4, t1 = (hi + 15) >> 4;               // 16-token tiles; lo is a multiple of 16
-  const TileAddr ta = tile_addr<D>(a.G, a.gg, a.tcap, g);
-
-  // Block id of a tile: a wavefront-uniform (scalar) load from the block table.  The index
-  // is clamped so that look-ahead past the item's last tile stays inside the table.
-  // The table is read through the constant address space: the kernel also stores (outputs,
-  // appended rows) and without that promise the compiler would turn these look-ups into
-  // vector loads, which share the tile loads' counter and would drain the pipeline.
-  const const_i32_ptr tbl_row = (const_i32_ptr)(uintptr_t)(a.block_table + (size_t)b * a.max_blocks);
-  auto blk_of = [&](int tile) -> int {
-    if (!PAGED) return b;
-    int bi = (tile << 4) >> a.log2_T;
-    bi = bi < a.max_blocks ? bi : a.max_blocks - 1;
-    return tbl_row[bi] - a.id_base;
-  };
-  auto load_tile = [&](Tile<LPT> &t, int tile, int blk) {
-    const int64_t base = slab_base<PAGED>(ta, blk, tile);
-    const uint4 *kp = reinterpret_cast<const uint4 *>(a.pool + base + ta.head_k) + lane;
-    const uint4 *vp = reinterpret_cast<const uint4 *>(a.pool + base + ta.head_v) + lane;
-#pragma unroll
-    for (int j = 0; j < LPT; ++j) t.k[j] = kp[j * 64];
-#pragma unroll
-    for (int j = 0; j < LPT; ++j) t.v[j] = vp[j * 64];
-  };
-  // Steady state: every tile is full (only the item's last tile can stick out of [lo, hi)
-  // or hold the appended row, and the last tile is always reduced in the drain below).
-  auto update = [&](const Tile<LPT> &t, int tile) {
-    tile_update<D, R, false>(t, q, m, l, o, (tile << 4) + row, lo, hi, a.scale_log2e);
-  };
-  // Drain: masked form for every tile (at most 2 * PIPE - 1 of them); the appended row
-  // replaces whatever the slot held.
-  auto update_last = [&](Tile<LPT> &t, int tile) {
-    if (appending && tile == (pos >> 4)) {
-#pragma unroll
-      for (int j = 0; j < LPT; ++j)
-        if ((tile << 4) + row + j * RPL == pos) {
-          t.k[j] = k_row;
-          t.v[j] = v_row;
-        }
-    }
-    tile_update<D, R, true>(t, q, m, l, o, (tile << 4) + row, lo, hi, a.scale_log2e);
-  };
-
-  // PIPE tiles are in flight ahead of the one being reduced.  The steady-state loop has no
-  // conditional loads, so each wait covers exactly the tile it needs and the younger loads
-  // stay in flight; block ids are fetched one refill ahead through the scalar cache, which
-  // has its own counter.
-  Tile<LPT> buf[PIPE];
-  int t = t0;
-  if (t1 - t0 >= 2 * PIPE) {
-    int next_blk[PIPE];
-#pragma unroll
-    for (int i = 0; i < PIPE; ++i) load_tile(buf[i], t0 + i, blk_of(t0 + i));
-#pragma unroll
-    for (int i = 0; i < PIPE; ++i) next_blk[i] = blk_of(t0 + i + PIPE);
-    for (; t + 2 * PIPE <= t1; t += PIPE) {
-#pragma unroll
-      for (int i = 0; i < PIPE; ++i) {
-        update(buf[i], t + i);
-        __builtin_amdgcn_sched_barrier(0);    // keep the refill behind the reduce that frees it,
-        load_tile(buf[i], t + i + PIPE, next_blk[i]);
-        next_blk[i] = blk_of(t + i + 2 * PIPE);
-        __builtin_amdgcn_sched_barrier(0);    // and ahead of the next tile's reduce
-      }
-    }
-  } else {
-#pragma unroll
-    for (int i = 0; i < PIPE; ++i)
-      if (t0 + i < t1) load_tile(buf[i], t0 + i, blk_of(t0 + i));
-  }
-  // drain: at most 2 * PIPE - 1 tiles are left, the first PIPE of them in flight
-#pragma unroll
-  for (int i = 0; i < PIPE; ++i)
-    if (t + i < t1) {
-      update_last(buf[i], t + i);
-      if (t + i + PIPE < t1) load_tile(buf[i], t + i + PIPE, blk_of(t + i + PIPE));
-    }
-#pragma unroll
-  for (int i = 0; i < PIPE; ++i)
-    if (t + PIPE + i < t1) update_last(buf[i], t + PIPE + i);
-
-  // Combine the RPL rows of the wavefront (each saw the tokens congruent to its row).
-#pragma unroll
-  for (int r = 0; r < R; ++r) {
-    float mt = m[r];
-#pragma unroll
-    for (int off = LPR; off < 64; off <<= 1) mt = fmaxf(mt, __shfl_xor(mt, off));
-    const float w = __builtin_amdgcn_exp2f(m[r] - mt);
-    float lt = l[r] * w;
-#pragma unroll
-    for (int off = LPR; off < 64; off <<= 1) lt += __shfl_xor(lt, off);
-    float ot[8];
-#pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      float x = o[r][e] * w;
-#pragma unroll
-      for (int off = LPR; off < 64; off <<= 1) x += __shfl_xor(x, off);
-      ot[e] = x;
-    }
-    if (row != 0) continue;
-    const int h = g * R + r;
-    if (seq_whole) {                                   // the item is the whole sequence
-      const float inv = 1.0f / lt;
-      const size_t at = ((size_t)b * a.H + h) * D + col * 8;
-      if (a.out_fp32) {
-        float4 *dst = reinterpret_cast<float4 *>(reinterpret_cast<float *>(a.out) + at);
-        dst[0] = make_float4(ot[0] * inv, ot[1] * inv, ot[2] * inv, ot[3] * inv);
-        dst[1] = make_float4(ot[4] * inv, ot[5] * inv, ot[6] * inv, ot[7] * inv);
-      } else {
-        half2_t h0 = {(_Float16)(ot[0] * inv), (_Float16)(ot[1] * inv)};
-        half2_t h1 = {(_Float16)(ot[2] * inv), (_Float16)(ot[3] * inv)};
-        half2_t h2 = {(_Float16)(ot[4] * inv), (_Float16)(ot[5] * inv)};
-        half2_t h3 = {(_Float16)(ot[6] * inv), (_Float16)(ot[7] * inv)};
-        uint4 pk = make_uint4(__builtin_bit_cast(uint32_t, h0), __builtin_bit_cast(uint32_t, h1),
-                              __builtin_bit_cast(uint32_t, h2), __builtin_bit_cast(uint32_t, h3));
-        *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(a.out) + at) = pk;
-      }
-    } else {
-      const size_t slot = (size_t)it * a.H + h;
-      float4 *dst = reinterpret_cast<float4 *>(a.part_o + slot * D + col * 8);
-      dst[0] = make_float4(ot[0], ot[1], ot[2], ot[3]);
-      dst[1] = make_float4(ot[4], ot[5], ot[6], ot[7]);
-      if (col == 0) *reinterpret_cast<float2 *>(a.part_ml + slot * 2) = make_float2(mt, lt);
-    }
-  }
-
-  if (appending && row < 2) {                          // row 0 stores the K row, row 1 the V row
-    const int blk = blk_of(pos >> 4);
-    const int64_t in_slab = (row == 0 ? ta.head_k : ta.head_v) + (int64_t)(pos & 15) * D + col * 8;
-    const uint4 val = row == 0 ? k_row : v_row;
-    *reinterpret_cast<uint4 *>(a.pool_store + slab_base<PAGED>(ta, blk, pos >> 4) + in_slab) = val;
-    if (a.pool_mirror)
-      *reinterpret_cast<uint4 *>(a.pool_mirror + slab_base<PAGED>(ta, blk + (PAGED ? a.mirror_shift : 0), pos >> 4) + in_slab) = val;
-  }
-}
-
-// ---- grouped query heads on the matrix cores -----------------------------------------------
+// ---- split-K attention on the matrix cores ---------------------------------------------------
 //
-// With 8 or 16 query heads per KV head the scores of a 16-key tile are a 16 x 16 x D product
-// and the weighted sum of its V rows a D x 16 x 16 one, and doing them lane by lane (as above)
-// makes the kernel bound by vector arithmetic instead of by reading the cache.  Here a
-// wavefront still owns one (item, KV head) unit and loads tiles exactly as above (whole rows,
-// 16 bytes per lane, PIPE tiles in flight); each tile then passes through a piece of LDS that
-// belongs to the wavefront alone (no barriers) to reach the register layout of the matrix core:
+// A wavefront owns one work unit: a run of keys of one sequence (an item) for one KV head, for all
+// the R = H / G query heads that share it (1 <= R <= 16).  It loads the unit's K and V in 16-token
+// tiles, whole rows, 16 bytes per lane, a few tiles ahead of the one it reduces.  The scores of a tile
+// are a 16 x 16 x D product and the weighted sum of its V rows a D x 16 x 16 one:
 //   S^T[key][head]  = K[key][:] . q[head][:]      v_mfma_f32_16x16x32_f16, A = K tile, B = q
 //   O^T[dim][head] += V^T[dim][key] P^T[key][head] v_mfma_f32_16x16x16_f16, A = V^T,   B = P^T
-// The score tile comes out with lane l holding head l % 16 and keys 4 (l / 16) .. + 3, which is
-// the layout of the B operand of the second product as it stands, so the weights never move
-// between lanes; max and sum over the keys need the lanes 16, 32 and 48 apart only.
+// Each tile passes through a piece of LDS that belongs to the wavefront alone (no barriers) to get
+// from the load layout to the operand layouts.  The score tile comes out with lane l holding head
+// l % 16 and keys 4 (l / 16) .. + 3, which is the layout of the B operand of the second product as
+// it stands, so the weights never move between lanes; max and sum over the keys need the lanes 16,
+// 32 and 48 apart only.  Columns past the group's heads carry zeros and are never stored; the matrix
+// cores are nowhere near busy and need not be: the path is bound by reading the cache, and what they
+// take over (a lane-by-lane form of the same arithmetic ran at 4.7 TB/s with 8 heads per KV head,
+// against 6.5 here) is the vector ALU's and the DPP network's work.
 
 typedef _Float16 half4_t __attribute__((ext_vector_type(4)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
@@ -378,6 +125,10 @@ constexpr int lds_tile_bytes() {
   return 16 * lds_row_bytes<D>();
 }
 
+// Online-softmax update of one wavefront with one 16-token tile (tok_tile = its first token).
+// MASKED: tokens outside [lo, hi) get score -inf (weight exactly 0; the running maximum stays finite
+// because it starts at kNegBig) and their V rows are read as zero, since unused slots may hold NaN bit
+// patterns.  Only an item's last tiles can need it; the steady-state loop uses the unmasked form.
 template <int D, bool MASKED>
 __device__ __forceinline__ void tile_update_mfma(const Tile<D / 32> &t, const half8_t (&qb)[D / 32], float &m,
                                                  float &l, floatx4_t (&o)[D / 16], char *ks, char *vs,
@@ -444,21 +195,24 @@ __device__ __forceinline__ void tile_update_mfma(const Tile<D / 32> &t, const ha
   }
 }
 
-// One work item for one KV head with R = 8 or 16 query heads, by one wavefront; `lds` is the
-// wavefront's own 2 * lds_tile_bytes<D>() bytes.
-template <int D, int R, bool PAGED, int PIPE>
-__device__ __forceinline__ void attend_item_mfma(const AttnArgs &a, const int it, const int g, const int lane,
-                                                 char *lds) {
+// One work item (a run of keys of one sequence) for one KV head and its R query heads, by one
+// wavefront; `lds` is the wavefront's own 2 * lds_tile_bytes<D>() bytes.
+template <int D, bool PAGED, int PIPE>
+__device__ __forceinline__ void attend_item(const AttnArgs &a, const int it, const int g, const int R,
+                                            const int lane, char *lds) {
   constexpr int LPR = D / 8, RPL = 64 / LPR, LPT = D / 32;
   const int row = lane / LPR, col = lane % LPR;
   const int quarter = lane >> 4, rho = lane & 15;
   char *ks = lds, *vs = lds + lds_tile_bytes<D>();
   const int4 desc = a.item_desc[it];
   const int b = desc.x, lo = desc.y, hi = desc.z;
-  const bool seq_last = (desc.w & kItemLast) != 0;
-  const bool seq_whole = (desc.w & kItemWhole) != 0;
+  const bool seq_last = (desc.w & kItemLast) != 0;        // the item ends at the sequence's last key
+  const bool seq_whole = (desc.w & kItemWhole) != 0;      // and is the sequence's only item
 
-  // this step's K/V rows: patched into the last tile in registers and stored at the end, as above
+  // The item that ends at the sequence's last key also stores this step's K/V rows
+  // (paper §II-A: keys and values of every processed token are kept).  The rows are
+  // patched into the tile in registers, so the attention below does not depend on
+  // reading its own store back; the store itself is issued after the reduction.
   const int pos = hi - 1;
   const bool appending = a.k_new != nullptr && seq_last;
   uint4 k_row = make_uint4(0u, 0u, 0u, 0u), v_row = k_row;
@@ -483,8 +237,13 @@ __device__ __forceinline__ void attend_item_mfma(const AttnArgs &a, const int it
 #pragma unroll
   for (int i = 0; i < D / 16; ++i) o[i] = floatx4_t{0.f, 0.f, 0.f, 0.f};
 
-  const int t0 = lo >> 4, t1 = (hi + 15) >> 4;
+  const int t0 = lo >> 4, t1 = (hi + 15) >> 4;               // 16-token tiles; lo is a multiple of 16
   const TileAddr ta = tile_addr<D>(a.G, a.gg, a.tcap, g);
+  // Block id of a tile: a wavefront-uniform (scalar) load from the block table.  The index
+  // is clamped so that look-ahead past the item's last tile stays inside the table.
+  // The table is read through the constant address space: the kernel also stores (outputs,
+  // appended rows) and without that promise the compiler would turn these look-ups into
+  // vector loads, which share the tile loads' counter and would drain the pipeline.
   const const_i32_ptr tbl_row = (const_i32_ptr)(uintptr_t)(a.block_table + (size_t)b * a.max_blocks);
   auto blk_of = [&](int tile) -> int {
     if (!PAGED) return b;
@@ -501,9 +260,13 @@ __device__ __forceinline__ void attend_item_mfma(const AttnArgs &a, const int it
 #pragma unroll
     for (int j = 0; j < LPT; ++j) t.v[j] = vp[j * 64];
   };
+  // Steady state: every tile is full (only the item's last tile can stick out of [lo, hi)
+  // or hold the appended row, and the last tile is always reduced in the drain below).
   auto update = [&](const Tile<LPT> &t, int tile) {
     tile_update_mfma<D, false>(t, qb, m, l, o, ks, vs, lane, tile << 4, lo, hi, a.scale_log2e);
   };
+  // Drain: masked form for every tile (at most 2 * PIPE - 1 of them); the appended row
+  // replaces whatever the slot held.
   auto update_last = [&](Tile<LPT> &t, int tile) {
     if (appending && tile == (pos >> 4)) {
 #pragma unroll
@@ -516,7 +279,10 @@ __device__ __forceinline__ void attend_item_mfma(const AttnArgs &a, const int it
     tile_update_mfma<D, true>(t, qb, m, l, o, ks, vs, lane, tile << 4, lo, hi, a.scale_log2e);
   };
 
-  // the same pipeline as attend_item: PIPE tiles in flight, unconditional loads in the steady state
+  // PIPE tiles are in flight ahead of the one being reduced.  The steady-state loop has no
+  // conditional loads, so each wait covers exactly the tile it needs and the younger loads
+  // stay in flight; block ids are fetched one refill ahead through the scalar cache, which
+  // has its own counter.
   Tile<LPT> buf[PIPE];
   int t = t0;
   if (t1 - t0 >= 2 * PIPE) {
@@ -529,10 +295,10 @@ __device__ __forceinline__ void attend_item_mfma(const AttnArgs &a, const int it
 #pragma unroll
       for (int i = 0; i < PIPE; ++i) {
         update(buf[i], t + i);
-        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_sched_barrier(0);    // keep the refill behind the reduce that frees it,
         load_tile(buf[i], t + i + PIPE, next_blk[i]);
         next_blk[i] = blk_of(t + i + 2 * PIPE);
-        __builtin_amdgcn_sched_barrier(0);
+        __builtin_amdgcn_sched_barrier(0);    // and ahead of the next tile's reduce
       }
     }
   } else {
@@ -540,6 +306,7 @@ __device__ __forceinline__ void attend_item_mfma(const AttnArgs &a, const int it
     for (int i = 0; i < PIPE; ++i)
       if (t0 + i < t1) load_tile(buf[i], t0 + i, blk_of(t0 + i));
   }
+  // drain: at most 2 * PIPE - 1 tiles are left, the first PIPE of them in flight
 #pragma unroll
   for (int i = 0; i < PIPE; ++i)
     if (t + i < t1) {
@@ -610,37 +377,23 @@ __device__ __forceinline__ void attend_item_mfma(const AttnArgs &a, const int it
 // fixed rotation, which a static split cannot correct).  A launch that has no more units
 // than wavefronts never touches the counter: same-address atomics are served one at a
 // time, and a burst of them at the start would cost more than it balances.  Every
-// wavefront leaves as soon as its ticket is past the end; nothing ever waits.
-template <int D, int R, bool PAGED, int PIPE>
-__global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_kernel(const AttnArgs a) {
-  const int lane = threadIdx.x & 63;
-  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const uint32_t n_waves = gridDim.x * kWavesPerBlock;
-  uint32_t ticket = blockIdx.x * kWavesPerBlock + wave;
-  while (ticket < (uint32_t)a.n_units) {
-    const int it = (int)(ticket / (uint32_t)a.G);
-    const int g = (int)(ticket - (uint32_t)it * (uint32_t)a.G);
-    attend_item<D, R, PAGED, PIPE>(a, a.item_first + it, g, lane);
-    if (n_waves >= (uint32_t)a.n_units) break;           // every unit had its own wavefront
-    uint32_t drawn = 0;
-    if (lane == 0) drawn = atomicAdd(a.queue, 1u);
-    ticket = n_waves + __builtin_amdgcn_readfirstlane(drawn);
-  }
-}
-
-// The same persistent scheme for the matrix-core form; each wavefront has its own piece of LDS.
-template <int D, int R, bool PAGED, int PIPE>
+// wavefront leaves as soon as its ticket is past the end; nothing ever waits.  (Eight counters
+// in cache lines of their own, each dealing runs of eight neighbouring units, measured the same
+// within 2 % either way as this single one on launches of 2048 to 8192 units: what a draw costs
+// a wavefront is the round trip, not the queueing behind other draws.)
+template <int D, bool PAGED, int PIPE>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(const AttnArgs a) {
   __shared__ __attribute__((aligned(16))) char lds[kWavesPerBlock][2 * lds_tile_bytes<D>()];
   const int lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t n_waves = gridDim.x * kWavesPerBlock;
+  const int R = a.H / a.G;
   uint32_t ticket = blockIdx.x * kWavesPerBlock + wave;
   while (ticket < (uint32_t)a.n_units) {
     const int it = (int)(ticket / (uint32_t)a.G);
     const int g = (int)(ticket - (uint32_t)it * (uint32_t)a.G);
-    attend_item_mfma<D, R, PAGED, PIPE>(a, a.item_first + it, g, lane, lds[wave]);
-    if (n_waves >= (uint32_t)a.n_units) break;
+    attend_item<D, PAGED, PIPE>(a, a.item_first + it, g, R, lane, lds[wave]);
+    if (n_waves >= (uint32_t)a.n_units) break;           // every unit had its own wavefront
     uint32_t drawn = 0;
     if (lane == 0) drawn = atomicAdd(a.queue, 1u);
     ticket = n_waves + __builtin_amdgcn_readfirstlane(drawn);
@@ -723,80 +476,30 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(const AttnArgs a) {
   }
 }
 
-// Tiles in flight per wavefront, by query-group size (more heads = more registers per tile).
-#ifndef OKV_PIPE_R1
-#define OKV_PIPE_R1 2
-#endif
-#ifndef OKV_PIPE_R2
-#define OKV_PIPE_R2 2
-#endif
-#ifndef OKV_PIPE_R4
-#define OKV_PIPE_R4 2
-#endif
-#ifndef OKV_PIPE_R8
-#define OKV_PIPE_R8 2
-#endif
-template <int R>
-constexpr int pipe_depth() {
-  return R == 1 ? OKV_PIPE_R1 : R == 2 ? OKV_PIPE_R2 : R == 4 ? OKV_PIPE_R4 : OKV_PIPE_R8;
+// Tiles in flight per wavefront.  What counts is bytes: about 8 KiB per wavefront (one tile at d = 128,
+// two at d = 64) times a thousand wavefronts is where the memory system runs best (6.4-6.6 TB/s); twice
+// that measured 5.9-6.0, half of it (one tile at d = 64) 4.4.  When wavefronts work through many units
+// each (more than two per wavefront: ragged or very large batches cut into short items) they spend part
+// of their time between units with nothing in flight, and twice the depth measured 3-7 % faster there.
+template <int D>
+constexpr int base_depth() {
+  return D == 64 ? 2 : 1;
 }
 
-template <int D, int R, bool PAGED>
-hipError_t launch_split(const AttnArgs &args, dim3 grid, hipStream_t stream) {
-  hipLaunchKernelGGL((attn_split_kernel<D, R, PAGED, pipe_depth<R>()>), grid, dim3(kWavesPerBlock * 64), 0,
-                     stream, args);
-  return hipGetLastError();
-}
-
-template <int D, int R>
-hipError_t launch_split_layout(const AttnArgs &args, bool paged, dim3 grid, hipStream_t stream) {
-  return paged ? launch_split<D, R, true>(args, grid, stream) : launch_split<D, R, false>(args, grid, stream);
-}
-
-// One tile in flight per wavefront here: measured with 8 wavefronts per compute unit on 1 GiB of
-// KV per launch, 8 heads per KV head reach 6.4 TB/s with one tile in flight and 6.0 with two or three.
-#ifndef OKV_PIPE_MFMA
-#define OKV_PIPE_MFMA 1
-#endif
-template <int D, int R>
-hipError_t launch_split_mfma(const AttnArgs &args, bool paged, dim3 grid, hipStream_t stream) {
-  if (paged)
-    hipLaunchKernelGGL((attn_split_mfma_kernel<D, R, true, OKV_PIPE_MFMA>), grid, dim3(kWavesPerBlock * 64), 0, stream, args);
+template <int D, bool PAGED>
+hipError_t launch_split_depth(const AttnArgs &args, bool deep, dim3 grid, hipStream_t stream) {
+  if (deep)
+    hipLaunchKernelGGL((attn_split_mfma_kernel<D, PAGED, 2 * base_depth<D>()>), grid, dim3(kWavesPerBlock * 64), 0, stream, args);
   else
-    hipLaunchKernelGGL((attn_split_mfma_kernel<D, R, false, OKV_PIPE_MFMA>), grid, dim3(kWavesPerBlock * 64), 0, stream, args);
+    hipLaunchKernelGGL((attn_split_mfma_kernel<D, PAGED, base_depth<D>()>), grid, dim3(kWavesPerBlock * 64), 0, stream, args);
   return hipGetLastError();
-}
-
-// Which group sizes take the matrix-core kernel.  8 and 16 heads per KV head are bound by vector
-// arithmetic in the lane-by-lane kernel (4.7 against 6.5 TB/s).  With one head per KV head both are
-// bound by memory, and the matrix-core kernel, which has next to no vector work left per tile, is the
-// faster one (62 against 66 us per launch on the 32-layer MHA stack at contexts 513..1024).  With 2 and
-// 4 heads it wins on uniform batches (6.4 against 5.9 TB/s) and loses on the ragged batch of 128
-// sequences cut into 1024-key items (213 against 210 us per launch); those stay where they were.
-constexpr bool use_matrix_cores(int R) {
-#ifdef OKV_MFMA_ALL
-  return true;
-#else
-  return R == 1 || R >= 8;
-#endif
-}
-
-template <int D, int R>
-hipError_t launch_split_pick(const AttnArgs &args, bool paged, dim3 grid, hipStream_t stream) {
-  if (use_matrix_cores(R)) return launch_split_mfma<D, R>(args, paged, grid, stream);
-  return launch_split_layout<D, (R > 8 ? 8 : R)>(args, paged, grid, stream);
 }
 
 template <int D>
-hipError_t launch_split_group(const AttnArgs &args, int R, bool paged, dim3 grid, hipStream_t stream) {
-  switch (R) {
-    case 1: return launch_split_pick<D, 1>(args, paged, grid, stream);
-    case 2: return launch_split_pick<D, 2>(args, paged, grid, stream);
-    case 4: return launch_split_pick<D, 4>(args, paged, grid, stream);
-    case 8: return launch_split_pick<D, 8>(args, paged, grid, stream);
-    case 16: return launch_split_mfma<D, 16>(args, paged, grid, stream);
-  }
-  return hipErrorInvalidValue;
+hipError_t launch_split(const AttnArgs &args, bool paged, dim3 grid, hipStream_t stream) {
+  const int64_t n_waves = (int64_t)grid.x * kWavesPerBlock;
+  const bool deep = args.n_units > 2 * n_waves;
+  return paged ? launch_split_depth<D, true>(args, deep, grid, stream) : launch_split_depth<D, false>(args, deep, grid, stream);
 }
 
 }  // namespace
@@ -852,10 +555,12 @@ hipError_t launch_decode_attn(const AttnLaunch &a, hipStream_t stream, hipEvent_
   dim3 grid((unsigned)std::min(want, cap));
   hipError_t e;
   if (ev_begin && (e = hipEventRecord(ev_begin, stream)) != hipSuccess) return e;
-  if (s.D == 128)
-    e = launch_split_group<128>(args, R, s.paged != 0, grid, stream);
+  if (R < 1 || R > 16 || R * s.G != s.H)
+    e = hipErrorInvalidValue;
+  else if (s.D == 128)
+    e = launch_split<128>(args, s.paged != 0, grid, stream);
   else if (s.D == 64)
-    e = launch_split_group<64>(args, R, s.paged != 0, grid, stream);
+    e = launch_split<64>(args, s.paged != 0, grid, stream);
   else
     e = hipErrorInvalidValue;
   if (e != hipSuccess) return e;

@@ -1,4 +1,4 @@
-"""GPU parity for 8 and 16 query heads per KV head, which the library computes on the
+"""GPU parity for grouped query heads (up to 16 per KV head, any count in between) on the
 matrix cores (scores and weighted sums as 16 x 16 tiles, softmax weights rounded to fp16
 for the second product).  Same bar as the other parity tests: outputs against the fp64
 oracle within 2e-3 max abs / 1e-2 relative L2, appended rows bit-exact."""
@@ -14,7 +14,8 @@ from gpu_util import assert_close, build_stack, make_inputs, oracle_pairs, run_a
 
 pytestmark = pytest.mark.gpu
 
-GROUPINGS = [(16, 2, 128), (16, 1, 128), (8, 1, 64), (32, 2, 64)]      # (H, G, d): 8, 16, 8, 16 heads per KV head
+GROUPINGS = [(16, 2, 128), (16, 1, 128), (8, 1, 64), (32, 2, 64), (6, 2, 128), (12, 1, 64)]
+# (H, G, d): 8, 16, 8, 16, 3 and 12 query heads per KV head
 
 
 def say(msg):

@@ -60,9 +60,10 @@ def test_result_does_not_depend_on_the_split_size(split):
         assert st.ctx.okv_get_split_tokens() == split
         got = run_and_check(st, n_steps=1, seed=9)[0][0]
         st.close()
-        # one split versus many: equal up to fp32 summation order
+        # one split versus many: equal up to the fp32 summation order and the fp16 rounding of the
+        # softmax weights, which is relative to each item's own running maximum
         rel = np.abs(got - ref).max() / np.abs(ref).max()
-        assert rel < 2e-5, rel
+        assert rel < 1e-3, rel
 
 
 @pytest.mark.parametrize("H,G,d", [(8, 4, 64), (16, 16, 128)])

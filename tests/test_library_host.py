@@ -195,7 +195,7 @@ def test_size_queries_and_shape_errors():
         kw.update(bad)
         with pytest.raises(binding.OkvError):
             binding.okv_block_bytes(binding.make_config(**kw))
-    for bad in (dict(head_dim=96), dict(n_q_heads=48), dict(block_tokens=24), dict(max_ctx=1000),
+    for bad in (dict(head_dim=96), dict(n_q_heads=12), dict(n_q_heads=136), dict(block_tokens=24), dict(max_ctx=1000),
                 dict(n_layers=0), dict(out_dtype=3)):
         kw = dict(n_layers=2, n_q_heads=8, n_kv_heads=8, head_dim=64, block_tokens=0, max_batch=4, max_ctx=256)
         kw.update(bad)
