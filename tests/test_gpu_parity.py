@@ -36,7 +36,7 @@ def test_cfg1_single_layer_all_outputs(T, out_dtype):
 # ---- several tiles, ragged tails, every head grouping --------------------------------
 
 @pytest.mark.parametrize("d", [64, 128])
-@pytest.mark.parametrize("H,G", [(4, 4), (4, 2), (8, 2), (8, 1), (16, 1), (32, 2)])
+@pytest.mark.parametrize("H,G", [(4, 4), (4, 2), (8, 2), (8, 1), (16, 1), (32, 2), (12, 12), (40, 20), (9, 3)])
 @pytest.mark.parametrize("T", [0, 16, 64])
 def test_ragged_contexts_all_groupings(d, H, G, T):
     say(f"ragged d={d} H={H} G={G} T={T}")
