@@ -21,12 +21,11 @@ using okv::Op;
 namespace {
 
 constexpr int kEventRing = 8;            // > copies in flight (at most OKV_MAX_STAGING)
-// Wavefronts of the persistent attention launch per compute unit: one per SIMD.  The kernels keep one tile
-// (matrix-core form) or two (lane by lane) of 8 KiB in flight per wavefront, and about 1000 wavefronts
+// Wavefronts of the persistent attention launch per compute unit: one per SIMD.  The kernel keeps about
+// 8 KiB in flight per wavefront (16 when wavefronts take many units each), and about 1000 wavefronts
 // saturate the memory system: with 2048 equal units, 4 per compute unit working through two units each
 // reach 6.5 TB/s and 8 per compute unit with one unit each 6.1-6.3; ragged batches gain less (0-4 %).
-// (The lane-by-lane kernel with one head per KV head, no longer used, was the exception: 8 measured
-// faster there.)
+// Kept apart by query-group size (1 head per KV head, 2..7, 8 and more) for tuning; all 4 at present.
 #ifndef OKV_WAVES_PER_CU_MHA
 #define OKV_WAVES_PER_CU_MHA 4
 #endif
