@@ -2,16 +2,18 @@
 //
 // Decode attention (paper §II-A; cost §IV-D: two multiply-adds per cached K and
 // V element) reads every KV byte exactly once and does about one flop per byte,
-// so the kernel is organised around the memory system, not the matrix cores:
+// so the kernel is organised around the memory system:
 //
 //   * one wavefront owns one work item = (sequence, KV head, a run of keys) and
 //     all H/G query heads that share the KV head, so K/V is read once per group;
 //   * a K or V tile of 16 tokens is one contiguous run of 16*d*2 bytes; every
 //     load instruction moves 16 bytes per lane, 1 KiB per wavefront;
-//   * tiles are loaded PIPE deep ahead of their use into registers;
-//   * each row of d/8 lanes reduces its dot product with DPP adds; the 64/(d/8)
-//     rows of a wavefront run independent online softmaxes over interleaved
-//     tokens and are combined once at the end of the item;
+//   * tiles are loaded PIPE deep ahead of their use into registers, about 8 KiB in
+//     flight per wavefront, one wavefront per SIMD: a thousand such streams is
+//     where the memory system runs best;
+//   * the arithmetic of a tile (scores, online softmax, weighted sum of V rows) runs
+//     on the matrix cores, which takes it off the vector ALU; the tile passes through
+//     LDS that belongs to the wavefront alone to reach the operand layouts;
 //   * the wavefront that reaches a sequence's last key also stores the step's new K/V
 //     rows (kv_append is folded into the attention launch);
 //   * items of a sequence are combined by a small merge kernel (skipped when
