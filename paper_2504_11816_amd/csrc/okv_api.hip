@@ -91,6 +91,7 @@ struct okv_ctx {
   std::vector<int32_t> h_block_table, h_ctx_lens;
   int32_t B = 0, split = 0, split_override = 0, n_items = 0;
   bool need_merge = false;
+  bool even_units = false;               // every sequence of the batch has (within a tile) the same length
   int64_t copy_bytes = 0;
 
   // bulk store of prompts (prefill side)
@@ -296,6 +297,7 @@ okv::AttnLaunch base_launch(okv_ctx *ctx) {
   a.part_ml = ctx->part_ml;
   a.out_fp32 = ctx->cfg.out_dtype;
   a.need_merge = ctx->need_merge;
+  a.even_units = ctx->even_units ? 1 : 0;
   a.queue = nullptr;
   a.max_waves = ctx->max_waves;
   a.item_first = 0;
@@ -417,6 +419,7 @@ int rebuild_worklist(okv_ctx *ctx, int32_t inc, bool upload_lens = false) {
     ctx->cls_first.assign(ctx->n_cls + 1, 0);
     for (int32_t c = 0; c < ctx->n_cls; ++c) ctx->cls_first[c + 1] = ctx->cls_first[c] + ctx->cls_count[c];
     ctx->need_merge = false;
+    ctx->even_units = false;                             // stretches of blocks differ from sequence to sequence
     for (int32_t b = 0; b < ctx->B; ++b) ctx->need_merge |= per_seq[b] > 1;
     OKV_HIP(ctx, okv::launch_step_advance_classes(ctx->d_ctx_lens, ctx->d_runs, ctx->d_pair_first, ctx->d_chunk_prefix,
                                                   ctx->d_item_desc, ctx->d_seq_total, ctx->d_queues,
@@ -431,11 +434,15 @@ int rebuild_worklist(okv_ctx *ctx, int32_t inc, bool upload_lens = false) {
                 (long long)n, (long long)ctx->max_items);
   ctx->n_items = (int32_t)n;
   ctx->need_merge = false;
+  int32_t shortest = ctx->B ? ctx->h_ctx_lens[0] : 0, longest = shortest;
   for (int32_t b = 0; b < ctx->B; ++b) {
     int32_t cnt, sz;
     okv::seq_chunks(ctx->h_ctx_lens[b], ctx->split, &cnt, &sz);
     if (cnt > 1) ctx->need_merge = true;
+    shortest = std::min(shortest, ctx->h_ctx_lens[b]);
+    longest = std::max(longest, ctx->h_ctx_lens[b]);
   }
+  ctx->even_units = longest - shortest < 16;
   OKV_HIP(ctx, okv::launch_step_advance(ctx->d_ctx_lens, ctx->d_chunk_prefix, ctx->d_item_desc, ctx->d_queues,
                                         ctx->cfg.n_layers, ctx->B, ctx->split, inc, ctx->compute));
   return OKV_OK;

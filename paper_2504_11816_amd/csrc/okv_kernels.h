@@ -42,6 +42,7 @@ struct AttnLaunch {
   int32_t out_fp32;
   int32_t need_merge;      // some sequence has more than one item
   uint32_t *queue;         // this launch's ticket counter (zeroed by launch_step_advance)
+  int32_t even_units;      // all units are of (nearly) one length: deal them out in fixed rotation, no counter
   int32_t max_waves;       // wavefronts of the persistent launch (a multiple of 4)
   // The launch covers items [item_first, item_first + item_count) of the list: all of them, or
   // those of one block class.  `pool` then holds the blocks with ids from id_base on, and

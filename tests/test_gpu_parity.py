@@ -80,6 +80,20 @@ def test_more_work_units_than_wavefronts_all_outputs(H, G, d):
     st.close()
 
 
+@pytest.mark.parametrize("H,G,d,T", [(8, 4, 64, 16), (16, 16, 128, 0), (16, 2, 128, 16)])
+def test_equal_sequences_more_work_units_than_wavefronts(H, G, d, T):
+    # a batch of equal sequences cut into thousands of 16-key items: the units are dealt to the wavefronts in
+    # fixed rotation (no ticket counter); a second batch one key off per sequence takes the same path
+    say(f"fixed rotation H={H} G={G} d={d} T={T}")
+    for ctx in ([333] * 40, [320 + (b % 2) * 15 for b in range(40)]):
+        st = build_stack(L=1, H=H, G=G, d=d, T=T, ctx_before=ctx, cap_tokens=352, out_dtype=1, seed=83,
+                         split_tokens=16)
+        n_items = len(st.ctx.okv_worklist(from_device=True))
+        assert n_items * G > 1600
+        run_and_check(st, n_steps=2, seed=85, pairs=[(b, h) for b in range(0, 40, 3) for h in range(0, H, 3)])
+        st.close()
+
+
 def test_paged_equals_contiguous_on_the_same_logical_kv_bit_for_bit():
     say("paged == contiguous")
     B, H, G, d, T, C = 3, 4, 2, 128, 16, 320
