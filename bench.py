@@ -35,8 +35,8 @@ PCIE5_X16_GBPS = 64.0       # nominal, one direction
 # okv_kernels.hip has changed since, `traffic` is reported as null.
 TRAFFIC_RECORD = {
     "workload": "cfg2", "steps": 512,
-    "kernel_sha256": "fc82f1ee41a03bc5ecf5b7bbee7fee4261ce6b4a986f7a2d9e3f5c015512d863",
-    "fetch_kib": 199054.5, "fetch_scale": 2.0000,
+    "kernel_sha256": "30c715e11bd88933938913c4ab2927ceeea73319cd8f4b20953b5db252af4896",
+    "fetch_kib": 199055.0, "fetch_scale": 2.0000,
     "write_kib": 768.0, "write_scale": 1.0000,
 }
 
