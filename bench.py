@@ -501,24 +501,26 @@ def run_layers(args):
         dt = time.perf_counter() - t0
     kv_bytes = kv_bytes_of_steps(ctx0, steps, G, d, L)
     w_bytes = sum(wt.bytes_read_per_step() for wt in weights) * steps
-    # each product alone, 50 launches back to back
+    # each product alone, back to back over the layers' own matrices in turn (two rounds): with L layers the
+    # weights come from HBM as they do in a step, not from the memory-side cache a single matrix would sit in
     cs = st.compute_stream
     alone = {}
-    wt = weights[0]
     for name, fn, nbytes in (
-            ("qkv 12288x4096", lambda: binding.okv_linear(scratch.a, wt.packed["wqkv"], wt.bqkv, None, [scratch.q, scratch.k, scratch.v], B, 3 * h1, h1, False, cs.cuda_stream, scratch.ws, scratch.ws_bytes), 3 * h1 * h1 * 2),
-            ("out 4096x4096", lambda: binding.okv_linear(scratch.t, wt.packed["wo"], wt.t["bo"], scratch.z, scratch.y, B, h1, h1, False, cs.cuda_stream, scratch.ws, scratch.ws_bytes), h1 * h1 * 2),
-            ("ffn1 16384x4096", lambda: binding.okv_linear(scratch.z, wt.packed["w1"], wt.t["b1"], None, scratch.u, B, h2, h1, True, cs.cuda_stream, scratch.ws, scratch.ws_bytes), h1 * h2 * 2),
-            ("ffn2 4096x16384", lambda: binding.okv_linear(scratch.u, wt.packed["w2"], wt.t["b2"], scratch.z, scratch.y, B, h1, h2, False, cs.cuda_stream, scratch.ws, scratch.ws_bytes), h1 * h2 * 2)):
-        fn()
+            ("qkv 12288x4096", lambda wt: binding.okv_linear(scratch.a, wt.packed["wqkv"], wt.bqkv, None, [scratch.q, scratch.k, scratch.v], B, 3 * h1, h1, False, cs.cuda_stream, scratch.ws, scratch.ws_bytes), 3 * h1 * h1 * 2),
+            ("out 4096x4096", lambda wt: binding.okv_linear(scratch.t, wt.packed["wo"], wt.t["bo"], scratch.z, scratch.y, B, h1, h1, False, cs.cuda_stream, scratch.ws, scratch.ws_bytes), h1 * h1 * 2),
+            ("ffn1 16384x4096", lambda wt: binding.okv_linear(scratch.z, wt.packed["w1"], wt.t["b1"], None, scratch.u, B, h2, h1, True, cs.cuda_stream, scratch.ws, scratch.ws_bytes), h1 * h2 * 2),
+            ("ffn2 4096x16384", lambda wt: binding.okv_linear(scratch.u, wt.packed["w2"], wt.t["b2"], scratch.z, scratch.y, B, h1, h2, False, cs.cuda_stream, scratch.ws, scratch.ws_bytes), h1 * h2 * 2)):
+        for wt in weights:
+            fn(wt)
         cs.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record(cs)
-        for _ in range(50):
-            fn()
+        for _ in range(2):
+            for wt in weights:
+                fn(wt)
         e1.record(cs)
         cs.synchronize()
-        us = e0.elapsed_time(e1) / 50 * 1e3
+        us = e0.elapsed_time(e1) / (2 * len(weights)) * 1e3
         alone[name] = {"us": us, "weight_gbps": nbytes / us / 1e3}
     res = {
         "workload": f"{L} decoder layers, hidden {h1}, feed-forward {h2}, batch {B}, context {w['ctx']}..{w['ctx'] + steps - 1}, random weights",
