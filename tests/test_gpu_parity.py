@@ -406,3 +406,27 @@ def test_kernel_timing_modes_count_every_launch():
         st.ctx.okv_profile_enable(3)
     assert e.value.code == binding.OKV_EINVAL
     st.close()
+
+
+def test_random_configurations_against_the_oracle():
+    # 48 seeded draws over head counts (KV heads that are not powers of two, 1..16 query heads each), head
+    # dimension, layout, block size, batch, ragged contexts (from empty), split size and output type
+    say("random configurations")
+    rng = np.random.default_rng(20250411)
+    for case in range(48):
+        G = int(rng.choice([1, 2, 3, 4, 6, 8, 12]))
+        R = int(rng.integers(1, 17))
+        while G * R > 48:
+            R = int(rng.integers(1, 17))
+        d = int(rng.choice([64, 128]))
+        T = int(rng.choice([0, 16, 32, 64]))
+        B = int(rng.integers(1, 6))
+        ctx = [int(x) for x in rng.integers(0, 400, size=B)]
+        split = int(rng.choice([0, 16, 48, 256, 1024]))
+        out_dtype = int(rng.integers(0, 2))
+        say(f"  case {case}: H={G * R} G={G} d={d} T={T} ctx={ctx} split={split} out={out_dtype}")
+        st = build_stack(L=1, H=G * R, G=G, d=d, T=T, ctx_before=ctx, cap_tokens=416, out_dtype=out_dtype,
+                         seed=1000 + case, split_tokens=split, shuffle_seed=case)
+        pairs = [(b, h) for b in range(B) for h in range(0, G * R, max(1, (G * R) // 6))]
+        run_and_check(st, n_steps=2, seed=2000 + case, pairs=pairs)
+        st.close()
