@@ -86,16 +86,16 @@ def kv_bytes_of_steps(ctx0, steps, G, d, L):
 def timed_steps(st, ctx0, table, inputs, steps, warmup):
     """W untimed steps, state reset, then exactly K timed steps."""
     import torch
-    q, k, v, out = inputs
+    bound = st.bind_step(*inputs)          # every layer of a step goes out in one call (okv_decode_step)
     st.set_batch(ctx0, table)
     for _ in range(warmup):
-        st.step(q, k, v, out)
+        st.step_bound(bound)
     st.synchronize()
     st.set_batch(ctx0, table)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
-        st.step(q, k, v, out)
+        st.step_bound(bound)
     st.synchronize()
     torch.cuda.synchronize()
     return time.perf_counter() - t0
@@ -107,11 +107,11 @@ def kernel_time(st, ctx0, table, inputs, steps, per_step=False):
     bracket around each step's launches, which then run back to back as in the
     timed region (all layers resident); else one bracket per launch, which leaves
     the GPU idle for a few microseconds before every kernel."""
-    q, k, v, out = inputs
+    bound = st.bind_step(*inputs)
     st.set_batch(ctx0, table)
     st.ctx.okv_profile_enable(2 if per_step else 1)
     for _ in range(steps):
-        st.step(q, k, v, out)
+        st.step_bound(bound)
     ms, n = st.ctx.okv_profile_read()
     st.ctx.okv_profile_enable(0)
     return ms * 1e-3, n

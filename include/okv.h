@@ -258,6 +258,17 @@ int kv_append(okv_ctx *ctx, int32_t layer, const void *k_new, const void *v_new)
  * enqueueing the next copy each time), then merges. */
 int decode_attn(okv_ctx *ctx, int32_t layer, const void *q, void *out);
 
+/* One whole decode step in one call: okv_step_begin, then kv_append(l) and decode_attn(l)
+ * for l = 0 .. L-1, then okv_step_end -- exactly those calls, made from inside the library,
+ * for callers that have every layer's inputs ready (attention over a cache with no linear
+ * layers in between, benchmarks) and do not want to cross the ABI 2 L + 2 times a step.
+ *   q, k_new, v_new, out  HOST arrays [n_layers] of DEVICE pointers, each as in kv_append /
+ *                         decode_attn
+ * Stops at the first error and returns its code; the step is then left open as the failing
+ * call left it. */
+int okv_decode_step(okv_ctx *ctx, const void *const *q, const void *const *k_new,
+                    const void *const *v_new, void *const *out);
+
 /* ---- storing prompts (the prefill side) ---------------------------------------------
  *
  * The prefill stage produces the keys and values of every prompt token, layer by

@@ -18,7 +18,7 @@ _CODE_NAMES = {0: "OKV_OK", -1: "OKV_EINVAL", -2: "OKV_ENOSPC", -3: "OKV_ESTATE"
 EXPORTS = [
     "okv_layer_pool_bytes", "okv_block_bytes", "okv_kv_head_group", "okv_workspace_bytes", "kv_offload_plan", "okv_plan_from_bytes",
     "okv_plan_block_split", "okv_schedule_trace", "okv_create", "okv_destroy", "okv_last_error", "okv_set_batch",
-    "okv_step_begin", "okv_step_end", "kv_append", "decode_attn", "okv_synchronize",
+    "okv_step_begin", "okv_step_end", "kv_append", "decode_attn", "okv_decode_step", "okv_synchronize",
     "okv_set_split_tokens", "okv_get_split_tokens", "okv_get_ctx_lens", "okv_worklist",
     "okv_worklist_classes", "okv_prefill_begin", "kv_append_bulk", "okv_prefill_release", "okv_prefill_end", "okv_prefill_plan",
     "okv_measure_d2h",
@@ -83,6 +83,7 @@ def lib():
             "okv_step_end": (ctypes.c_int, [P]),
             "kv_append": (ctypes.c_int, [P, I32, P, P]),
             "decode_attn": (ctypes.c_int, [P, I32, P, P]),
+            "okv_decode_step": (ctypes.c_int, [P, P, P, P, P]),
             "okv_synchronize": (ctypes.c_int, [P]),
             "okv_set_split_tokens": (ctypes.c_int, [P, I32]),
             "okv_get_split_tokens": (I32, [P]),
@@ -323,6 +324,19 @@ class Context:
 
     def decode_attn(self, layer, q, out):
         self._c(lib().decode_attn(self._h, layer, _ptr(q), _ptr(out)))
+
+    @staticmethod
+    def pointer_arrays(q, k_new, v_new, out):
+        """The four HOST arrays of DEVICE pointers okv_decode_step takes, from per-layer lists of
+        tensors; build them once for buffers that are reused every step."""
+        return tuple((ctypes.c_void_p * len(ts))(*[_ptr(t) for t in ts]) for ts in (q, k_new, v_new, out))
+
+    def okv_decode_step(self, arrays):
+        """arrays: what pointer_arrays returned (one entry per layer in each)."""
+        q, k, v, o = arrays
+        if not (len(q) == len(k) == len(v) == len(o) == self.cfg.n_layers):
+            raise ValueError("one pointer per layer in each array")
+        self._c(lib().okv_decode_step(self._h, q, k, v, o))
 
     def okv_prefill_begin(self, n_new):
         n_new = np.ascontiguousarray(n_new, dtype=np.int32)

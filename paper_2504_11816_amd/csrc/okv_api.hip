@@ -915,6 +915,18 @@ int decode_attn(okv_ctx *ctx, int32_t layer, const void *q, void *out) {
   return OKV_OK;
 }
 
+int okv_decode_step(okv_ctx *ctx, const void *const *q, const void *const *k_new, const void *const *v_new,
+                    void *const *out) {
+  if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
+  if (!q || !k_new || !v_new || !out) return fail(ctx, OKV_EINVAL, "okv_decode_step: NULL pointer array");
+  int rc = okv_step_begin(ctx);
+  for (int32_t l = 0; rc == OKV_OK && l < ctx->cfg.n_layers; ++l) {
+    rc = kv_append(ctx, l, k_new[l], v_new[l]);
+    if (rc == OKV_OK) rc = decode_attn(ctx, l, q[l], out[l]);
+  }
+  return rc == OKV_OK ? okv_step_end(ctx) : rc;
+}
+
 // ---- bulk store of prompts ------------------------------------------------------------
 
 int okv_prefill_begin(okv_ctx *ctx, const int32_t *n_new) {

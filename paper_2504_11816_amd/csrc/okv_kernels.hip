@@ -207,10 +207,12 @@ __device__ __forceinline__ void attend_item(const AttnArgs &a, const int it, con
   const int row = lane / LPR, col = lane % LPR;
   const int quarter = lane >> 4, rho = lane & 15;
   char *ks = lds, *vs = lds + lds_tile_bytes<D>();
-  const int4 desc = a.item_desc[it];
-  const int b = desc.x, lo = desc.y, hi = desc.z;
-  const bool seq_last = (desc.w & kItemLast) != 0;        // the item ends at the sequence's last key
-  const bool seq_whole = (desc.w & kItemWhole) != 0;      // and is the sequence's only item
+  // the item's descriptor, like the block table below, comes through the scalar cache (constant address
+  // space: nothing writes it while this kernel runs), which is a shorter round trip than a vector load
+  const const_i32_ptr dp = (const_i32_ptr)(uintptr_t)(a.item_desc + it);
+  const int b = dp[0], lo = dp[1], hi = dp[2], flags = dp[3];
+  const bool seq_last = (flags & kItemLast) != 0;         // the item ends at the sequence's last key
+  const bool seq_whole = (flags & kItemWhole) != 0;       // and is the sequence's only item
 
   // The item that ends at the sequence's last key also stores this step's K/V rows
   // (paper §II-A: keys and values of every processed token are kept).  The rows are

@@ -208,6 +208,19 @@ class Stack:
         if self.ctx_lens is not None:
             self.ctx_lens += 1
 
+    def bind_step(self, q, k_new, v_new, out):
+        """Pointer arrays for step_bound: build once for buffers that every step reuses."""
+        def per_layer(x):
+            return list(x) if isinstance(x, (list, tuple)) else [x] * self.L
+        tensors = tuple(per_layer(x) for x in (q, k_new, v_new, out))
+        return self.ctx.pointer_arrays(*tensors), tensors          # the tensors ride along to stay alive
+
+    def step_bound(self, bound):
+        """The same pass as step(), all layers issued by one call into the library."""
+        self.ctx.okv_decode_step(bound[0])
+        if self.ctx_lens is not None:
+            self.ctx_lens += 1
+
     def prefill(self, n_new, k_rows, v_rows, release=True):
         """Stores n_new[b] new tokens per sequence in every layer.  k_rows / v_rows are
         per-layer lists of device tensors [sum(n_new)][G][d] (or single tensors reused)."""

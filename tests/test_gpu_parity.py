@@ -430,3 +430,33 @@ def test_random_configurations_against_the_oracle():
         pairs = [(b, h) for b in range(B) for h in range(0, G * R, max(1, (G * R) // 6))]
         run_and_check(st, n_steps=2, seed=2000 + case, pairs=pairs)
         st.close()
+
+
+def test_whole_step_in_one_call_is_the_same_step():
+    # okv_decode_step = okv_step_begin + (kv_append, decode_attn) per layer + okv_step_end: same outputs bit for
+    # bit, same pools, same lengths; and its error paths
+    say("okv_decode_step")
+    ctx = [5, 120, 300]
+    sts = [build_stack(L=3, H=8, G=4, d=64, T=16, ctx_before=ctx, cap_tokens=320, on_host=[0, 1, 0], seed=311)
+           for _ in range(2)]
+    for step in range(3):
+        q, k, v, out_a = make_inputs(sts[0], 313, step, sts[0].device)
+        sts[0].step(q, k, v, out_a)
+        _, _, _, out_b = make_inputs(sts[1], 313, step, sts[1].device)
+        sts[1].step_bound(sts[1].bind_step(q, k, v, out_b))
+        for st in sts:
+            st.synchronize()
+        for l in range(3):
+            np.testing.assert_array_equal(out_a[l].cpu().numpy().view(np.uint16), out_b[l].cpu().numpy().view(np.uint16))
+    for l in range(3):
+        np.testing.assert_array_equal(sts[0].read_pool(l).view(np.uint16), sts[1].read_pool(l).view(np.uint16))
+    assert sts[1].ctx.okv_get_ctx_lens().tolist() == [c + 3 for c in ctx]
+    arrays = sts[1].bind_step(q, k, v, out_b)[0]
+    with pytest.raises(ValueError):
+        sts[1].ctx.okv_decode_step(tuple(a if i else (type(a)._type_ * 2)() for i, a in enumerate(arrays)))
+    sts[1].ctx.okv_step_begin()
+    with pytest.raises(binding.OkvError) as e:                  # inside a step already
+        sts[1].ctx.okv_decode_step(arrays)
+    assert e.value.code == binding.OKV_ESTATE
+    for st in sts:
+        st.close()
