@@ -656,12 +656,13 @@ def main():
     line = {
         "metric": "decode_attn_tokens_per_s", "value": res["tokens_per_s"], "unit": "tokens/s",
         "n_gpus": 1, "steps": res["steps"], "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
-        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f32",
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
         "data": "synthetic",
         "config": {"workload": f"{args.workload}: {res['L']} layers, {res['H']} q heads / {res['G']} kv heads x {res['d']}, "
                                f"batch {res['B']}, context {res['ctx_desc']}, fp16 KV "
                                f"{'paged T=%d' % res['T'] if res['T'] else 'contiguous'}, all resident",
-                   "split_tokens": res["split_tokens"]},
+                   "split_tokens": res["split_tokens"],
+                   "arithmetic": "fp16 K/V/q and softmax weights into the matrix cores, fp32 accumulation and softmax"},
         "kv_gbps": res["kv_gbps"], "hbm_frac": res["kv_gbps"] / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": res["kernel_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": res["kernel_gbps"] / HBM_PEAK_GBPS,
