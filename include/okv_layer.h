@@ -11,7 +11,7 @@
  * attention and before the feed-forward block, ReLU, biases, residual connections).
  *
  * Conventions as in okv.h: C ABI, every pointer DEVICE unless labelled, fp16 tensors
- * row-major, the caller owns all memory, calls enqueue on `stream` (a hipStream_t, NULL
+ * row-major and 16-byte aligned, the caller owns all memory, calls enqueue on `stream` (a hipStream_t, NULL
  * = the default stream) and return at once; OKV_OK or a negative OKV_E* code;
  * okv_last_error(NULL) has the message.
  */

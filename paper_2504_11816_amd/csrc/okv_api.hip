@@ -1418,12 +1418,13 @@ int linear_impl(const void *x, const void *w_packed, const void *bias, const voi
     return fail(nullptr, OKV_EINVAL, "okv_linear: n_out must be a multiple of 16 and n_in of 32");
   if (n_seg < 1 || n_seg > 3 || n_out % (16 * n_seg)) return fail(nullptr, OKV_EINVAL, "okv_linear: n_seg must be 1..3 and divide n_out / 16");
   if (residual && n_seg != 1) return fail(nullptr, OKV_EINVAL, "okv_linear: a residual needs n_seg = 1");
+  if (!aligned16(bias) || !aligned16(residual)) return fail(nullptr, OKV_EINVAL, "okv_linear: bias / residual misaligned");
   if (relu != 0 && relu != 1) return fail(nullptr, OKV_EINVAL, "okv_linear: relu must be 0 or 1");
   okv::LinearLaunch l;
   l.x = x, l.w_packed = w_packed, l.bias = bias, l.residual = residual;
   for (int s = 0; s < 3; ++s) {
     l.out[s] = s < n_seg ? out[s] : nullptr;
-    if (s < n_seg && !out[s]) return fail(nullptr, OKV_EINVAL, "okv_linear: out[%d] is NULL", s);
+    if (s < n_seg && (!out[s] || !aligned16(out[s]))) return fail(nullptr, OKV_EINVAL, "okv_linear: out[%d] is NULL or misaligned", s);
   }
   l.n_seg = n_seg, l.m = m, l.n_out = n_out, l.n_in = n_in, l.relu = relu;
   if (workspace && (!aligned16(workspace) || workspace_bytes < 0)) return fail(nullptr, OKV_EINVAL, "okv_linear: workspace misaligned");

@@ -304,16 +304,49 @@ __global__ __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(2,
 // the product kernel: a workgroup that reads what other workgroups wrote needs device-wide fences, and on
 // this GPU those write back and invalidate the L2 caches (measured: 75 us instead of 11 for a 32 MiB matrix).
 __global__ __launch_bounds__(256) void reduce_epilogue_kernel(const LinearArgs a) {
-  const int n = blockIdx.x * 256 + threadIdx.x, mrow = blockIdx.y;
+  // four neighbouring features per thread; the shares are fetched four cuts at a time with loads that do not
+  // depend on one another (a cut past the last one re-reads the last with weight 0), so a thread waits for
+  // one round trip, not for one per cut
+  const int n = (blockIdx.x * 256 + threadIdx.x) * 4, mrow = blockIdx.y;
   if (n >= a.n_out) return;
-  float v = 0.f;
-  for (int s2 = 0; s2 < a.splits; ++s2) v += a.shares[((size_t)s2 * a.m + mrow) * a.n_out + n];
-  if (a.bias) v += (float)a.bias[n];
-  if (a.relu) v = fmaxf(v, 0.f);
-  const int seg = n / a.seg_cols, col = n - seg * a.seg_cols;
+  float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+  for (int s2 = 0; s2 < a.splits; s2 += 4) {
+    float4 part[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int sj = s2 + j < a.splits ? s2 + j : a.splits - 1;
+      part[j] = *reinterpret_cast<const float4 *>(a.shares + ((size_t)sj * a.m + mrow) * a.n_out + n);
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const float w = s2 + j < a.splits ? 1.f : 0.f;
+      v.x += w * part[j].x, v.y += w * part[j].y, v.z += w * part[j].z, v.w += w * part[j].w;
+    }
+  }
+  const int seg = n / a.seg_cols, col = n - seg * a.seg_cols;         // a segment is a multiple of 16 features wide
   const size_t at = (size_t)mrow * a.seg_cols + col;
-  if (a.residual) v += (float)a.residual[at];
-  a.out[seg][at] = (_Float16)v;
+  float y[4] = {v.x, v.y, v.z, v.w};
+  if (a.bias) {
+    const uint2 b = *reinterpret_cast<const uint2 *>(a.bias + n);
+    const _Float16 *bp = reinterpret_cast<const _Float16 *>(&b);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) y[e] += (float)bp[e];
+  }
+  if (a.relu) {
+#pragma unroll
+    for (int e = 0; e < 4; ++e) y[e] = fmaxf(y[e], 0.f);
+  }
+  if (a.residual) {
+    const uint2 r = *reinterpret_cast<const uint2 *>(a.residual + at);
+    const _Float16 *rp = reinterpret_cast<const _Float16 *>(&r);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) y[e] += (float)rp[e];
+  }
+  uint2 o;
+  _Float16 *op = reinterpret_cast<_Float16 *>(&o);
+#pragma unroll
+  for (int e = 0; e < 4; ++e) op[e] = (_Float16)y[e];
+  *reinterpret_cast<uint2 *>(a.out[seg] + at) = o;
 }
 
 // dst piece (block (nt, kb), lane) = src[16 nt + lane % 16][32 kb + 8 (lane / 16) .. + 7]
@@ -405,11 +438,20 @@ __global__ __launch_bounds__(kLnThreads) void reduce_layernorm_kernel(const Line
       float acc[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-      for (int s2 = 0; s2 < a.splits; ++s2) {
-        const float4 *sp = reinterpret_cast<const float4 *>(a.shares + ((size_t)s2 * a.m + mrow) * h + p * 8);
-        const float4 lo = sp[0], hi = sp[1];
-        acc[0] += lo.x, acc[1] += lo.y, acc[2] += lo.z, acc[3] += lo.w;
-        acc[4] += hi.x, acc[5] += hi.y, acc[6] += hi.z, acc[7] += hi.w;
+      for (int s2 = 0; s2 < a.splits; s2 += 4) {             // four cuts at a time, loads independent of one another
+        float4 lo[4], hi[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const int sj = s2 + j < a.splits ? s2 + j : a.splits - 1;      // past the last cut: the last again, weight 0
+          const float4 *sp = reinterpret_cast<const float4 *>(a.shares + ((size_t)sj * a.m + mrow) * h + p * 8);
+          lo[j] = sp[0], hi[j] = sp[1];
+        }
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          const float w = s2 + j < a.splits ? 1.f : 0.f;
+          acc[0] += w * lo[j].x, acc[1] += w * lo[j].y, acc[2] += w * lo[j].z, acc[3] += w * lo[j].w;
+          acc[4] += w * hi[j].x, acc[5] += w * hi[j].y, acc[6] += w * hi[j].z, acc[7] += w * hi[j].w;
+        }
       }
       uint4 rb = make_uint4(0u, 0u, 0u, 0u), bb = rb;
       if (a.bias) bb = reinterpret_cast<const uint4 *>(a.bias)[p];
@@ -429,6 +471,14 @@ __global__ __launch_bounds__(kLnThreads) void reduce_layernorm_kernel(const Line
       reinterpret_cast<uint4 *>(a.out[0] + (size_t)mrow * h)[p] = yo;
     }
   }
+  // gamma and beta are fetched before the reductions, whose barriers would otherwise stand between these
+  // loads and the statistics they do not depend on
+  uint4 gam[kLnPieces], bet[kLnPieces];
+#pragma unroll
+  for (int i = 0; i < kLnPieces; ++i) {
+    const int p = threadIdx.x + i * kLnThreads;
+    if (p < pieces) gam[i] = reinterpret_cast<const uint4 *>(a.ln_gamma)[p], bet[i] = reinterpret_cast<const uint4 *>(a.ln_beta)[p];
+  }
   const float mean = block_sum(s, scratch) / (float)h;
   float q = 0.f;
 #pragma unroll
@@ -442,8 +492,7 @@ __global__ __launch_bounds__(kLnThreads) void reduce_layernorm_kernel(const Line
   for (int i = 0; i < kLnPieces; ++i) {
     const int p = threadIdx.x + i * kLnThreads;
     if (p < pieces) {
-      const uint4 g = reinterpret_cast<const uint4 *>(a.ln_gamma)[p], b = reinterpret_cast<const uint4 *>(a.ln_beta)[p];
-      const _Float16 *gp = reinterpret_cast<const _Float16 *>(&g), *bp = reinterpret_cast<const _Float16 *>(&b);
+      const _Float16 *gp = reinterpret_cast<const _Float16 *>(&gam[i]), *bp = reinterpret_cast<const _Float16 *>(&bet[i]);
       uint4 o;
       _Float16 *op = reinterpret_cast<_Float16 *>(&o);
 #pragma unroll
@@ -464,7 +513,7 @@ hipError_t launch_linear_mf(const LinearArgs &args, int n_tiles, bool fast, hipS
       if (args.ln_out)
         hipLaunchKernelGGL(reduce_layernorm_kernel, dim3(args.m), dim3(kLnThreads), 0, stream, args);
       else
-        hipLaunchKernelGGL(reduce_epilogue_kernel, dim3((args.n_out + 255) / 256, args.m), dim3(256), 0, stream, args);
+        hipLaunchKernelGGL(reduce_epilogue_kernel, dim3((args.n_out + 1023) / 1024, args.m), dim3(256), 0, stream, args);
     }
   } else {
     hipLaunchKernelGGL(linear_kernel<MF>, dim3(n_tiles), dim3(kLinWaves * 64), 0, stream, args);
