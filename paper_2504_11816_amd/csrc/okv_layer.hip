@@ -401,7 +401,7 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint4 *x, c
   float q = 0.f;
 #pragma unroll
   for (int i = 0; i < kLnPieces; ++i)
-    if (threadIdx.x + i * kLnThreads < pieces) {
+    if ((int)threadIdx.x + i * kLnThreads < pieces) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) q += (v[i][e] - mean) * (v[i][e] - mean);
     }
@@ -483,7 +483,7 @@ __global__ __launch_bounds__(kLnThreads) void reduce_layernorm_kernel(const Line
   float q = 0.f;
 #pragma unroll
   for (int i = 0; i < kLnPieces; ++i)
-    if (threadIdx.x + i * kLnThreads < pieces) {
+    if ((int)threadIdx.x + i * kLnThreads < pieces) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) q += (v[i][e] - mean) * (v[i][e] - mean);
     }
