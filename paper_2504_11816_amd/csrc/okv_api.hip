@@ -216,17 +216,23 @@ int64_t count_items(const int32_t *ctx, int32_t B, int32_t S) {
 }
 
 // Split size by a small cost model of one launch, evaluated for S = 128, 256, 512, ...
-//   time(S) = max( (bytes + items * kItemOverheadBytes) / kLaunchBytesPerUs + tail / 2,
-//                  longest item / kWaveBytesPerUs )
+//   time(S) = max( (bytes + units * kItemOverheadBytes) / kLaunchBytesPerUs + tail / 2,
+//                  longest item / kWaveBytesPerUs,
+//                  rounds(S) )
 // A wavefront alone pulls at most kWaveBytesPerUs, so about kSaturatingWaves of them
 // are needed to keep HBM busy; `tail` is the time the longest item keeps running after
 // fewer than that many items are left (they all start together and finish by size).
-// Fewer, longer items save per-item cost and the merge pass; equal items avoid a tail.
+// rounds(S): the launch has W persistent wavefronts, so U units of the mean size take
+// floor(U / W) full rounds at the launch's rate and, if units are left over, one more
+// round in which each of them runs at what U mod W wavefronts can pull (1536 units of
+// 2048 keys on 1024 wavefronts take as long as 2048 of them; cut in two they take three
+// rounds of half the length).  Fewer, longer items save per-item cost and the merge pass;
+// equal items avoid a tail; a unit count that fills the rounds avoids idle wavefronts.
 // The constants are measured on MI355X with this kernel (d = 128 rows).
-constexpr double kLaunchBytesPerUs = 5.8e6;      // what the split kernel sustains, bytes per microsecond
-constexpr double kWaveBytesPerUs = 6.5e3;        // one wavefront with two tiles in flight
+constexpr double kLaunchBytesPerUs = 6.3e6;      // what the split kernel sustains, bytes per microsecond
+constexpr double kWaveBytesPerUs = 6.5e3;        // one wavefront with 8 KiB in flight
 constexpr double kItemOverheadBytes = 10240;     // prologue, epilogue, partial result, merge share
-constexpr int64_t kSaturatingWaves = 890;        // kLaunchBytesPerUs / kWaveBytesPerUs
+constexpr int64_t kSaturatingWaves = 970;        // kLaunchBytesPerUs / kWaveBytesPerUs
 
 double launch_cost_us(const okv_ctx *ctx, const std::vector<int32_t> &lens, int32_t S, int64_t *n_items) {
   const int32_t G = ctx->cfg.n_kv_heads;
@@ -259,7 +265,12 @@ double launch_cost_us(const okv_ctx *ctx, const std::vector<int32_t> &lens, int3
   }
   const double tail = (longest - at_saturation) / kWaveBytesPerUs;
   const double stream = (bytes + (double)units * kItemOverheadBytes) / kLaunchBytesPerUs;
-  return std::max(stream + 0.5 * tail, longest / kWaveBytesPerUs);
+  const int64_t W = std::max<int64_t>(1, ctx->max_waves);
+  const double unit_bytes = bytes / (double)units + kItemOverheadBytes;
+  const int64_t left = units % W;
+  double rounds = (double)(units / W) * unit_bytes * (double)W / kLaunchBytesPerUs;
+  if (left) rounds += unit_bytes / std::min(kWaveBytesPerUs, kLaunchBytesPerUs / (double)left);
+  return std::max({stream + 0.5 * tail, longest / kWaveBytesPerUs, rounds});
 }
 
 int32_t choose_split(const okv_ctx *ctx, const std::vector<int32_t> &lens) {
