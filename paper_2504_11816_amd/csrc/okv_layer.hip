@@ -40,6 +40,7 @@ namespace okv {
 namespace {
 
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 #ifndef OKV_LIN_DEPTH
@@ -74,6 +75,12 @@ struct LinearArgs {
 
 __device__ __forceinline__ floatx4 mfma16(const uint2 a, const uint2 b, floatx4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(half4, a), __builtin_bit_cast(half4, b), c, 0, 0, 0);
+}
+
+// 16 x 16 result tile += [16 rows][32 inputs] . [32 inputs][16 features]; a lane's 16 bytes of either operand are
+// inputs 8 (lane / 16) .. + 7 of row (feature) lane % 16
+__device__ __forceinline__ floatx4 mfma32(const uint4 a, const uint4 b, floatx4 c) {
+  return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8, a), __builtin_bit_cast(half8, b), c, 0, 0, 0);
 }
 
 template <int MF>
@@ -184,6 +191,15 @@ __global__ __launch_bounds__(kLinWaves * 64) void linear_kernel(const LinearArgs
 #define OKV_LIN_CHUNK 8
 #endif
 constexpr int lin_chunk(int mf) { return mf <= 2 ? OKV_LIN_CHUNK : mf <= 4 ? 8 : 4; }
+// How many chunks of x the staging wavefront is ahead of the others (one LDS buffer more than that).  Bounded by
+// LDS (a chunk takes lin_chunk x MF KiB) and by the counter of loads in flight, which stops at 63: the wait for a
+// chunk leaves the loads of the lead - 1 chunks after it outstanding.
+#ifndef OKV_LIN_LEAD
+#define OKV_LIN_LEAD 3
+#endif
+constexpr int lin_lead(int mf) { return mf <= 3 ? OKV_LIN_LEAD : 2; }
+// s_waitcnt operand that waits until at most n vector memory loads are outstanding and for nothing else
+constexpr int vmcnt_only(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
 constexpr int kFastThreads = (kLinWaves + 1) * 64;
 constexpr int kTileCols = kLinWaves * 16;      // output features of a workgroup
 
@@ -191,10 +207,14 @@ constexpr int kTileCols = kLinWaves * 16;      // output features of a workgroup
 // caps the kernel at 64 registers.
 template <int MF>
 __global__ __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(2, 4))) void linear_lds_kernel(const LinearArgs a) {
-  constexpr int C = lin_chunk(MF);
-  // x chunk in the order the matrix core reads it: xs[buffer][block][row fragment][lane] 16-byte pieces;
-  // after the last chunk the same memory holds the fp32 tile [16 MF rows][kTileCols features] for the epilogue
-  __shared__ uint4 xs[2][C][MF][64];
+  constexpr int C = lin_chunk(MF), LEAD = lin_lead(MF), NBUF = LEAD + 1, PER = C * MF;
+  static_assert((LEAD - 1) * PER <= 63, "the wait for a staged chunk must fit the load counter");
+  // A chunk of x, [16 MF rows][LPR 16-byte pieces] (LPR x 8 inputs).  Piece p of row r sits in slot (p - r) mod LPR of
+  // the row: a matrix-core operand read takes the same piece of 16 consecutive rows, and the shift spreads those
+  // over all the banks.  After the last chunk the same memory holds the fp32 tile [16 MF rows][kTileCols features]
+  // for the epilogue.
+  constexpr int LPR = C * 4, RPI = 64 / LPR;          // pieces per row; rows that one staging instruction brings
+  __shared__ uint4 xs[NBUF][PER][64];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int group = blockIdx.x, cut = blockIdx.y;
@@ -211,33 +231,61 @@ __global__ __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(2,
 
   if (wave == kLinWaves) {
     // The staging wavefront.  Its loads have a counter of their own, so waiting for them never
-    // holds up the weight stream of the others.  One load per (block, row fragment) writes
-    // straight into LDS, 16 bytes per lane, lane l landing in slot l: lane l fetches row
-    // 16 f + l % 16, inputs 8 (l / 16) .. + 7 of the block -- the order the matrix core reads.  (This is
-    // the half-line gather that was too dear once per wavefront; here it happens once per workgroup.)
+    // holds up the weight stream of the others.  A load instruction writes straight into LDS, 16 bytes per
+    // lane, lane l landing in slot l of the instruction's 1 KiB: it brings RPI whole rows of the chunk (LPR
+    // lanes a row, 512 contiguous bytes at 8 blocks a chunk), every lane fetching the piece that belongs in
+    // its slot.  (Fetched in the order the matrix core reads -- 16 rows x 64 bytes per instruction -- the same
+    // bytes took twice as many half-used cache lines.)
     const int row_pieces = a.n_in >> 3;
-    const uint4 *xg[MF];
+    const int h = lane / LPR, sl = lane % LPR;
+    const uint4 *xg[PER];
 #pragma unroll
-    for (int f = 0; f < MF; ++f)     // rows past the batch read row 0: they only reach result rows that are not stored
-      xg[f] = a.x + (size_t)(f * 16 + (lane & 15) < a.m ? f * 16 + (lane & 15) : 0) * row_pieces + (size_t)kb0 * 4 + (lane >> 4);
+    for (int j = 0; j < PER; ++j) {     // rows past the batch read row 0: they only reach result rows that are not stored
+      const int row = j * RPI + h;
+      xg[j] = a.x + (size_t)(row < a.m ? row : 0) * row_pieces + (size_t)kb0 * 4 + ((sl + row) & (LPR - 1));
+    }
     auto stage = [&](int chunk, int buf) {
 #pragma unroll
-      for (int i = 0; i < C; ++i)
-#pragma unroll
-        for (int f = 0; f < MF; ++f)
-          __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(xg[f] + ((size_t)chunk * C + i) * 4),
-                                           (__attribute__((address_space(3))) void *)&xs[buf][i][f][0], 16, 0, 0);
+      for (int j = 0; j < PER; ++j)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(xg[j] + (size_t)chunk * LPR),
+                                         (__attribute__((address_space(3))) void *)&xs[buf][j][0], 16, 0, 0);
     };
-    stage(rotc(0), 0);
-    __syncthreads();
+    // LEAD chunks ahead of the others, so that a chunk has LEAD of their chunk times to arrive, not one (with one:
+    // 3 us of 30 at 32 rows and 16 of 44 at 64 rows went into waiting for it, 16384 x 4096).  Before barrier c
+    // chunk c must have landed: the loads of the chunks issued after it, LEAD - 1 of them except at the end, may
+    // still be on their way.
+    auto landed = [&](int c) {
+      if (n_chunks - 1 - c >= LEAD - 1) __builtin_amdgcn_s_waitcnt(vmcnt_only((LEAD - 1) * PER));
+      else __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
+    };
+#pragma unroll
+    for (int j = 0; j < LEAD; ++j)
+      if (j < n_chunks) stage(rotc(j), j);
+    landed(0);
+    __builtin_amdgcn_s_barrier();
+    int buf = LEAD;
     for (int c = 0; c < n_chunks; ++c) {
-      if (c + 1 < n_chunks) stage(rotc(c + 1), (c + 1) & 1);       // nobody reads that buffer between these two barriers
-      __syncthreads();
+      // the buffer of chunk c - 1: the others finished with it before the barrier this wavefront just passed
+      if (c + LEAD < n_chunks) stage(rotc(c + LEAD), buf);
+      buf = buf + 1 == NBUF ? 0 : buf + 1;
+      if (c + 1 < n_chunks) landed(c + 1);
+      __builtin_amdgcn_s_barrier();
     }
   } else {
     const int ntile = group * kLinWaves + wave;
     // a wavefront past the last tile streams tile 0 (valid memory) and never stores
     const uint4 *wp = a.w + ((size_t)(ntile < a.n_tiles ? ntile : 0) * a.n_kb + kb0) * 64 + lane;
+    // where this lane's operand pieces sit in a chunk: row 16 f + lane % 16, piece 4 i + lane / 16 for block i
+    int xrow[MF], xrot[MF];
+#pragma unroll
+    for (int f = 0; f < MF; ++f) {
+      const int row = 16 * f + (lane & 15);
+      xrow[f] = row * LPR;
+      xrot[f] = (lane >> 4) - row;
+    }
+    auto xat = [&](int buf, int i, int f) -> uint4 {
+      return (&xs[buf][0][0])[xrow[f] + ((xrot[f] + 4 * i) & (LPR - 1))];
+    };
     uint4 wbuf[C];
 #pragma unroll
     for (int i = 0; i < C; ++i) {                            // oldest first: the loop waits for them in this order
@@ -245,31 +293,37 @@ __global__ __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(2,
       __builtin_amdgcn_sched_barrier(0);
     }
     __syncthreads();
+    int buf = 0;
     for (int c = 0; c < n_chunks; ++c) {
       // the chunk after this one (the last chunk is fetched once more instead of branching: loads in
       // this loop stay unconditional, so the waits stay exact)
       const int cn = rotc(c + 1 < n_chunks ? c + 1 : c);
-      const int buf = c & 1;
+      uint4 xr[MF];
+#pragma unroll
+      for (int f = 0; f < MF; ++f) xr[f] = xat(buf, 0, f);
 #pragma unroll
       for (int i = 0; i < C; ++i) {
         const uint4 w = wbuf[i];
 #pragma unroll
-        for (int f = 0; f < MF; ++f) {
-          const uint4 x = xs[buf][i][f][lane];
-          acc[f] = mfma16(make_uint2(x.x, x.y), make_uint2(w.x, w.y), acc[f]);
-          acc[f] = mfma16(make_uint2(x.z, x.w), make_uint2(w.z, w.w), acc[f]);
-        }
+        for (int f = 0; f < MF; ++f) acc[f] = mfma32(xr[f], w, acc[f]);
         __builtin_amdgcn_sched_barrier(0);
         wbuf[i] = wp[((size_t)cn * C + i) * 64];
+        // the rows of x for the next block are on their way from LDS while this wavefront waits for that
+        // block's weights
+        if (i + 1 < C) {
+#pragma unroll
+          for (int f = 0; f < MF; ++f) xr[f] = xat(buf, i + 1, f);
+        }
         __builtin_amdgcn_sched_barrier(0);
       }
+      buf = buf + 1 == NBUF ? 0 : buf + 1;
       __syncthreads();
     }
   }
 
   // this workgroup's share of the tile [16 MF][128] in LDS (all reads of xs are behind the barrier above):
   // result element (row 16 f + 4 (lane / 16) + r, feature 16 wave + lane % 16) sits in acc[f][r]
-  float *tile = reinterpret_cast<float *>(&xs[0][0][0][0]);
+  float *tile = reinterpret_cast<float *>(&xs[0][0][0]);
   if (wave < kLinWaves) {
 #pragma unroll
     for (int f = 0; f < MF; ++f)
