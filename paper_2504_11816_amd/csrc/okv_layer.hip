@@ -49,6 +49,9 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 #ifndef OKV_LIN_WG_PER_CU
 #define OKV_LIN_WG_PER_CU 1
 #endif
+#ifndef OKV_LIN_SIMPLE_ROWS
+#define OKV_LIN_SIMPLE_ROWS 16
+#endif
 #ifndef OKV_LIN_WAVES
 #define OKV_LIN_WAVES 4
 #endif
@@ -183,8 +186,9 @@ __global__ __launch_bounds__(kLinWaves * 64) void linear_kernel(const LinearArgs
   }
 }
 
-// Fast path: kLinWaves wavefronts x 16 features, x staged in LDS by one more wavefront, input
-// dimension cut across workgroups.
+// Fast path: NW wavefronts x 16 features, x staged in LDS by one more wavefront, input
+// dimension cut across workgroups.  NW = 4, or 3 where that gives one workgroup per compute unit without a cut
+// (12288 features on 256 units), which saves the kernel that adds up the shares.
 // 32-input blocks per staged chunk = weight pieces (1 KiB) in flight per wavefront; bounded by the LDS the
 // two x buffers take (2 x chunk x 16 MF rows x 64 bytes): 64 KiB at most.
 #ifndef OKV_LIN_CHUNK
@@ -200,13 +204,12 @@ constexpr int lin_chunk(int mf) { return mf <= 2 ? OKV_LIN_CHUNK : mf <= 4 ? 8 :
 constexpr int lin_lead(int mf) { return mf <= 3 ? OKV_LIN_LEAD : 2; }
 // s_waitcnt operand that waits until at most n vector memory loads are outstanding and for nothing else
 constexpr int vmcnt_only(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
-constexpr int kFastThreads = (kLinWaves + 1) * 64;
-constexpr int kTileCols = kLinWaves * 16;      // output features of a workgroup
 
 // waves_per_eu: without the hint the compiler aims at the occupancy that the LDS footprint would allow and
 // caps the kernel at 64 registers.
-template <int MF>
-__global__ __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(2, 4))) void linear_lds_kernel(const LinearArgs a) {
+template <int MF, int NW>
+__global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu(2, 4))) void linear_lds_kernel(const LinearArgs a) {
+  constexpr int kFastThreads = (NW + 1) * 64, kTileCols = NW * 16;      // kTileCols: output features of a workgroup
   constexpr int C = lin_chunk(MF), LEAD = lin_lead(MF), NBUF = LEAD + 1, PER = C * MF;
   static_assert((LEAD - 1) * PER <= 63, "the wait for a staged chunk must fit the load counter");
   // A chunk of x, [16 MF rows][LPR 16-byte pieces] (LPR x 8 inputs).  Piece p of row r sits in slot (p - r) mod LPR of
@@ -229,7 +232,7 @@ __global__ __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(2,
   const int rot = (int)(((unsigned)group * 5u + (unsigned)cut * 3u) % (unsigned)n_chunks);
   auto rotc = [&](int c) { int cc = c + rot; return cc >= n_chunks ? cc - n_chunks : cc; };
 
-  if (wave == kLinWaves) {
+  if (wave == NW) {
     // The staging wavefront.  Its loads have a counter of their own, so waiting for them never
     // holds up the weight stream of the others.  A load instruction writes straight into LDS, 16 bytes per
     // lane, lane l landing in slot l of the instruction's 1 KiB: it brings RPI whole rows of the chunk (LPR
@@ -272,7 +275,7 @@ __global__ __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(2,
       __builtin_amdgcn_s_barrier();
     }
   } else {
-    const int ntile = group * kLinWaves + wave;
+    const int ntile = group * NW + wave;
     // a wavefront past the last tile streams tile 0 (valid memory) and never stores
     const uint4 *wp = a.w + ((size_t)(ntile < a.n_tiles ? ntile : 0) * a.n_kb + kb0) * 64 + lane;
     // where this lane's operand pieces sit in a chunk: row 16 f + lane % 16, piece 4 i + lane / 16 for block i
@@ -324,7 +327,7 @@ __global__ __launch_bounds__(kFastThreads) __attribute__((amdgpu_waves_per_eu(2,
   // this workgroup's share of the tile [16 MF][128] in LDS (all reads of xs are behind the barrier above):
   // result element (row 16 f + 4 (lane / 16) + r, feature 16 wave + lane % 16) sits in acc[f][r]
   float *tile = reinterpret_cast<float *>(&xs[0][0][0]);
-  if (wave < kLinWaves) {
+  if (wave < NW) {
 #pragma unroll
     for (int f = 0; f < MF; ++f)
 #pragma unroll
@@ -557,10 +560,11 @@ __global__ __launch_bounds__(kLnThreads) void reduce_layernorm_kernel(const Line
 }
 
 template <int MF>
-hipError_t launch_linear_mf(const LinearArgs &args, int n_tiles, bool fast, hipStream_t stream) {
+hipError_t launch_linear_mf(const LinearArgs &args, int n_tiles, bool fast, int fast_waves, hipStream_t stream) {
   if (fast) {
-    dim3 grid((n_tiles + kLinWaves - 1) / kLinWaves, args.splits);
-    hipLaunchKernelGGL(linear_lds_kernel<MF>, grid, dim3(kFastThreads), 0, stream, args);
+    dim3 grid((n_tiles + fast_waves - 1) / fast_waves, args.splits);
+    if (fast_waves == 3) hipLaunchKernelGGL((linear_lds_kernel<MF, 3>), grid, dim3(4 * 64), 0, stream, args);
+    else hipLaunchKernelGGL((linear_lds_kernel<MF, 4>), grid, dim3(5 * 64), 0, stream, args);
     if (args.splits > 1 || args.to_shares) {
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
@@ -577,13 +581,14 @@ hipError_t launch_linear_mf(const LinearArgs &args, int n_tiles, bool fast, hipS
 
 }  // namespace
 
-// How many ways the input dimension is cut: enough workgroups for two per compute unit, as long
-// as every cut keeps at least two chunks, and only cuts that divide the chunks evenly.
-int linear_splits(int32_t m, int32_t n_out, int32_t n_in, int32_t n_cus) {
+// How many ways the input dimension is cut, with workgroups of `waves` streaming wavefronts: enough workgroups
+// for one per compute unit, as long as every cut keeps at least two chunks, and only cuts that divide the chunks
+// evenly.  0: not a shape for the fast kernel.
+int linear_splits(int32_t m, int32_t n_out, int32_t n_in, int32_t n_cus, int waves) {
   const int chunk = lin_chunk((m + 15) / 16);
-  if (n_in % (32 * chunk)) return 0;                           // not a fast-path shape
+  if (n_in % (32 * chunk)) return 0;
   const int chunks = n_in / (32 * chunk);
-  const int groups = (n_out / 16 + kLinWaves - 1) / kLinWaves;
+  const int groups = (n_out / 16 + waves - 1) / waves;
   int best = 1;
   for (int s = 1; s <= chunks; ++s) {
     if (chunks % s) continue;
@@ -594,8 +599,21 @@ int linear_splits(int32_t m, int32_t n_out, int32_t n_in, int32_t n_cus) {
   return best;
 }
 
+// Streaming wavefronts per workgroup and cuts: 4 wavefronts; 3 and no cut where 4 would need a cut and 3 fill the
+// compute units (at least nine in ten, none twice) without one.  Cuts 0: not a shape for the fast kernel.
+void linear_plan(int32_t m, int32_t n_out, int32_t n_in, int32_t n_cus, int *waves, int *cuts) {
+  *waves = 4;
+  *cuts = linear_splits(m, n_out, n_in, n_cus, 4);
+  const int groups3 = (n_out / 16 + 2) / 3;
+  if (*cuts > 1 && groups3 <= n_cus && groups3 * 10 >= n_cus * 9) {
+    *waves = 3;
+    *cuts = 1;
+  }
+}
+
 int64_t linear_workspace_bytes(int32_t m, int32_t n_out, int32_t n_in, int32_t n_cus) {
-  const int s = m > 16 ? linear_splits(m, n_out, n_in, n_cus) : 0;
+  int waves = 4, s = 0;
+  if (m > OKV_LIN_SIMPLE_ROWS) linear_plan(m, n_out, n_in, n_cus, &waves, &s);
   return s < 1 ? 0 : (int64_t)s * m * n_out * 4;        // a single cut still goes through a share when a layer norm follows
 }
 
@@ -622,8 +640,9 @@ hipError_t launch_linear(const LinearLaunch &l, hipStream_t stream) {
   a.ln_out = nullptr;
   a.ln_eps = l.ln_eps;
   bool fast = false;
-  const int s = linear_splits(l.m, l.n_out, l.n_in, l.n_cus);
-  if (l.m > 16 && (s == 1 || (s > 1 && l.workspace && l.workspace_bytes >= linear_workspace_bytes(l.m, l.n_out, l.n_in, l.n_cus)))) {
+  int fast_waves = 4, s = 0;
+  linear_plan(l.m, l.n_out, l.n_in, l.n_cus, &fast_waves, &s);
+  if (l.m > OKV_LIN_SIMPLE_ROWS && (s == 1 || (s > 1 && l.workspace && l.workspace_bytes >= linear_workspace_bytes(l.m, l.n_out, l.n_in, l.n_cus)))) {
     fast = true;
     a.splits = s;
     a.shares = static_cast<float *>(l.workspace);
@@ -637,14 +656,14 @@ hipError_t launch_linear(const LinearLaunch &l, hipStream_t stream) {
   }
   hipError_t e = hipErrorInvalidValue;
   switch ((l.m + 15) / 16) {
-    case 1: e = launch_linear_mf<1>(a, n_tiles, fast, stream); break;
-    case 2: e = launch_linear_mf<2>(a, n_tiles, fast, stream); break;
-    case 3: e = launch_linear_mf<3>(a, n_tiles, fast, stream); break;
-    case 4: e = launch_linear_mf<4>(a, n_tiles, fast, stream); break;
-    case 5: e = launch_linear_mf<5>(a, n_tiles, fast, stream); break;
-    case 6: e = launch_linear_mf<6>(a, n_tiles, fast, stream); break;
-    case 7: e = launch_linear_mf<7>(a, n_tiles, fast, stream); break;
-    case 8: e = launch_linear_mf<8>(a, n_tiles, fast, stream); break;
+    case 1: e = launch_linear_mf<1>(a, n_tiles, fast, fast_waves, stream); break;
+    case 2: e = launch_linear_mf<2>(a, n_tiles, fast, fast_waves, stream); break;
+    case 3: e = launch_linear_mf<3>(a, n_tiles, fast, fast_waves, stream); break;
+    case 4: e = launch_linear_mf<4>(a, n_tiles, fast, fast_waves, stream); break;
+    case 5: e = launch_linear_mf<5>(a, n_tiles, fast, fast_waves, stream); break;
+    case 6: e = launch_linear_mf<6>(a, n_tiles, fast, fast_waves, stream); break;
+    case 7: e = launch_linear_mf<7>(a, n_tiles, fast, fast_waves, stream); break;
+    case 8: e = launch_linear_mf<8>(a, n_tiles, fast, fast_waves, stream); break;
   }
   if (e != hipSuccess || !l.ln_out || fuse_ln) return e;
   return launch_layernorm(l.out[0], l.ln_gamma, l.ln_beta, l.ln_out, l.m, l.n_out, l.ln_eps, stream);   // the same in two steps

@@ -185,6 +185,16 @@ def test_linear_epilogue_variants():
     close(y.float().cpu().numpy(), y0 + dl.linear(x.double().cpu().numpy(), w.double().cpu().numpy()), what="aliased residual")
 
 
+@pytest.mark.parametrize("n_out", [12288, 12272, 11520])
+def test_linear_workgroups_of_three_streaming_wavefronts(n_out):
+    # feature counts for which three 16-feature tiles per workgroup fill the 256 compute units without a cut of the
+    # inputs; 12272 = 767 tiles leaves the last workgroup one tile short
+    say(f"linear three-wavefront form {n_out}")
+    assert binding.okv_linear_workspace_bytes(32, n_out, 1024) == 32 * n_out * 4       # one share (for a layer norm to follow): no cut
+    run_linear(32, n_out, 1024, 341, relu=True, residual=True)
+    run_linear(40, n_out, 1024, 342)
+
+
 def test_linear_full_size_projection_and_feed_forward():
     say("linear full size")
     run_linear(32, 4096, 4096, 341)
