@@ -5,32 +5,36 @@
 // With so few rows every weight is read once and used `m` times: the product is bound by
 // streaming W from HBM, so the kernel is built like the attention kernel -- long runs of
 // 16-byte-per-lane loads kept many deep in flight -- with the matrix cores doing the
-// arithmetic on the side (a 16x16x16 fp16 instruction per 512 bytes of weights and 16
-// rows of x: a few percent of the time the loads take).
+// arithmetic on the side (one fp16 instruction per KiB of weights and 16 rows of x: a few
+// percent of the time the loads take).
 //
 //   * weights are stored pre-arranged (okv_pack_linear_weight) so that one load instruction
-//     brings a wavefront the 1 KiB it feeds to two matrix-core instructions: 16 output
-//     features x 32 inputs, lane l holding feature l % 16, inputs 8 (l / 16) .. + 7;
-//   * beyond 16 rows, the rows of x must NOT be fetched per lane in the layout the matrix core
-//     wants: such a gather touches 16 half cache lines per instruction, every workgroup needs
-//     all of x, and the time grew by 14 us per 16 rows of batch on a 128 MiB matrix (21 us with
-//     16 rows, 36 with 32, 119 with 128) although x sits in L2.  So in the fast kernel a
-//     workgroup of 4 wavefronts takes 64 output features (one 16-feature tile per wavefront)
-//     over one stretch of the input dimension, and a fifth wavefront stages the rows of x for
-//     that stretch chunk by chunk in LDS (double buffered, one barrier per 256 inputs), from
-//     where the four read their operands: 28 us with 32 rows, 35 with 64, 54 with 128.  The
-//     staging has a wavefront of its own because the vector memory counter retires loads in
-//     order: a wavefront that waited for staged rows would also wait for the weight pieces
-//     it issued before them;
+//     brings a wavefront the 1 KiB it feeds to one 16x16x32 matrix-core instruction per 16 rows:
+//     16 output features x 32 inputs, lane l holding feature l % 16, inputs 8 (l / 16) .. + 7;
+//   * beyond a few rows, the rows of x must NOT be fetched per lane in the layout the matrix core
+//     wants: such a gather touches 16 half cache lines per instruction, every wavefront needs
+//     its own, and the time grows with the rows although x sits in L2 (16384 x 4096, weights
+//     from HBM: 25.4 us at 4 rows, 26.6 at 8, 34.3 at 16).  So in the fast kernel a workgroup of
+//     4 (or 3) wavefronts takes 64 (48) output features, one 16-feature tile per wavefront, over
+//     one stretch of the input dimension, and one more wavefront stages the rows of x for that
+//     stretch chunk by chunk in LDS, from where the others read their operands.  The staging
+//     wavefront fetches whole rows of a chunk (512 contiguous bytes each), keeps three chunks
+//     ahead of the others and meets them at one barrier per 256 inputs; it is a wavefront of
+//     its own because the vector memory counter retires loads in order: a wavefront that waited
+//     for staged rows would also wait for the weight pieces it issued before them.  16384 x
+//     4096 from HBM: 28.4 us at 32 rows, 31.0 at 64, 44.6 at 128; with the staging switched off
+//     (timing only) 27.6 and 28.5, of which about 5 us do not depend on the size of the matrix;
 //   * the input dimension is cut across workgroups so that the launch has one per compute
 //     unit (longer-lived workgroups measured faster than more of them); each writes its fp32
 //     share of the tile and a small second kernel adds the shares in a fixed order and applies
 //     the epilogue (bias, ReLU, residual, rounding to fp16, scatter into up to three output
 //     tensors).  A hand-over inside the kernel (last workgroup adds up) needs device-wide
-//     fences, which on this GPU write back and invalidate the L2 caches: 75 us instead of 11;
-//   * up to 16 rows, and shapes the fast kernel does not take (input dimension not a multiple
+//     fences, which on this GPU write back and invalidate the L2 caches: 75 us instead of 11.
+//     Where three tiles per workgroup fill the compute units without a cut (12288 features on
+//     256 units) the workgroups have three streaming wavefronts and there is no second kernel;
+//   * up to 8 rows, and shapes the fast kernel does not take (input dimension not a multiple
 //     of 256), run the simple kernel: a workgroup per 16 features, its wavefronts split the
-//     inputs and add up through LDS, x by gather (6.3-6.5 TB/s at up to 16 rows).
+//     inputs and add up through LDS, x by gather.
 #include "okv_kernels.h"
 
 #include <algorithm>
@@ -49,8 +53,11 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 #ifndef OKV_LIN_WG_PER_CU
 #define OKV_LIN_WG_PER_CU 1
 #endif
+// Up to this many rows the simple kernel is the faster one (its gather of x costs in proportion to the rows, and it
+// has more, shorter-lived workgroups and needs no second kernel); measured with the weights coming from HBM, 16384 x
+// 4096: 26.6 us against 27.0 at 8 rows, 27.8 against 26.9 at 10, 34.3 against 27.4 at 16.
 #ifndef OKV_LIN_SIMPLE_ROWS
-#define OKV_LIN_SIMPLE_ROWS 16
+#define OKV_LIN_SIMPLE_ROWS 8
 #endif
 #ifndef OKV_LIN_WAVES
 #define OKV_LIN_WAVES 4
