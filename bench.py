@@ -35,8 +35,8 @@ PCIE5_X16_GBPS = 64.0       # nominal, one direction
 # okv_kernels.hip has changed since, `traffic` is reported as null.
 TRAFFIC_RECORD = {
     "workload": "cfg2", "steps": 512,
-    "kernel_sha256": "30c715e11bd88933938913c4ab2927ceeea73319cd8f4b20953b5db252af4896",
-    "fetch_kib": 199055.0, "fetch_scale": 2.0000,
+    "kernel_sha256": "5f7ae3e703292c3097a3b865f97a54078bd2c14c6649f1ca24ded28bd0359ae1",
+    "fetch_kib": 199056.5, "fetch_scale": 2.0000,
     "write_kib": 768.0, "write_scale": 1.0000,
 }
 
