@@ -425,9 +425,13 @@ __global__ __launch_bounds__(256) void pack_weight_kernel(uint4 *dst, const uint
   }
 }
 
-// One workgroup per row; every thread keeps its (at most 8) 16-byte pieces in registers, so the row
-// is read once: mean, then variance around it, then the output.
-constexpr int kLnThreads = 256, kLnPieces = 8;
+// One workgroup per row; every thread keeps its (one or two) 16-byte pieces in registers, so the row
+// is read once: mean, then variance around it, then the output.  As many threads as the row has pieces, up
+// to 1024: with so few rows the kernel takes as long as its chain of dependent loads, and a thread with one
+// piece has one round of them.
+constexpr int kLnMaxThreads = 1024, kLnMaxPieces = 2;
+constexpr int kLnMaxWidth = kLnMaxThreads * kLnMaxPieces * 8;
+inline int ln_threads(int h) { return std::min(kLnMaxThreads, ((h >> 3) + 63) / 64 * 64); }
 
 __device__ __forceinline__ float block_sum(float v, float *scratch) {
 #pragma unroll
@@ -436,21 +440,21 @@ __device__ __forceinline__ float block_sum(float v, float *scratch) {
   if ((threadIdx.x & 63) == 0) scratch[threadIdx.x >> 6] = v;
   __syncthreads();
   float t = 0.f;
-#pragma unroll
-  for (int w = 0; w < kLnThreads / 64; ++w) t += scratch[w];
+  for (int w = 0; w < (int)(blockDim.x >> 6); ++w) t += scratch[w];
   return t;
 }
 
-__global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint4 *x, const uint4 *gamma, const uint4 *beta, uint4 *out,
+template <int PPT>
+__global__ __launch_bounds__(kLnMaxThreads) void layernorm_kernel(const uint4 *x, const uint4 *gamma, const uint4 *beta, uint4 *out,
                                                                 int32_t h, float eps) {
-  __shared__ float scratch[kLnThreads / 64];
+  __shared__ float scratch[kLnMaxThreads / 64];
   const int pieces = h >> 3;
   const uint4 *xr = x + (size_t)blockIdx.x * pieces;
-  float v[kLnPieces][8];
+  float v[PPT][8];
   float s = 0.f;
 #pragma unroll
-  for (int i = 0; i < kLnPieces; ++i) {
-    const int p = threadIdx.x + i * kLnThreads;
+  for (int i = 0; i < PPT; ++i) {
+    const int p = threadIdx.x + i * blockDim.x;
     if (p < pieces) {
       const uint4 u = xr[p];
       const _Float16 *hp = reinterpret_cast<const _Float16 *>(&u);
@@ -464,16 +468,16 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint4 *x, c
   const float mean = block_sum(s, scratch) / (float)h;
   float q = 0.f;
 #pragma unroll
-  for (int i = 0; i < kLnPieces; ++i)
-    if ((int)threadIdx.x + i * kLnThreads < pieces) {
+  for (int i = 0; i < PPT; ++i)
+    if ((int)threadIdx.x + i * blockDim.x < pieces) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) q += (v[i][e] - mean) * (v[i][e] - mean);
     }
   const float rstd = 1.0f / sqrtf(block_sum(q, scratch) / (float)h + eps);
   uint4 *orow = out + (size_t)blockIdx.x * pieces;
 #pragma unroll
-  for (int i = 0; i < kLnPieces; ++i) {
-    const int p = threadIdx.x + i * kLnThreads;
+  for (int i = 0; i < PPT; ++i) {
+    const int p = threadIdx.x + i * blockDim.x;
     if (p < pieces) {
       const uint4 g = gamma[p], b = beta[p];
       const _Float16 *gp = reinterpret_cast<const _Float16 *>(&g), *bp = reinterpret_cast<const _Float16 *>(&b);
@@ -490,14 +494,15 @@ __global__ __launch_bounds__(kLnThreads) void layernorm_kernel(const uint4 *x, c
 // workgroup per row, the row in registers as in layernorm_kernel.  Saves a launch and a pass over
 // the row whenever a product feeds a layer norm (output projection -> second norm, feed-forward
 // -> the next layer's first norm).
-__global__ __launch_bounds__(kLnThreads) void reduce_layernorm_kernel(const LinearArgs a) {
-  __shared__ float scratch[kLnThreads / 64];
+template <int PPT>
+__global__ __launch_bounds__(kLnMaxThreads) void reduce_layernorm_kernel(const LinearArgs a) {
+  __shared__ float scratch[kLnMaxThreads / 64];
   const int h = a.n_out, pieces = h >> 3, mrow = blockIdx.x;
-  float v[kLnPieces][8];
+  float v[PPT][8];
   float s = 0.f;
 #pragma unroll
-  for (int i = 0; i < kLnPieces; ++i) {
-    const int p = threadIdx.x + i * kLnThreads;
+  for (int i = 0; i < PPT; ++i) {
+    const int p = threadIdx.x + i * blockDim.x;
     if (p < pieces) {
       float acc[8];
 #pragma unroll
@@ -537,24 +542,24 @@ __global__ __launch_bounds__(kLnThreads) void reduce_layernorm_kernel(const Line
   }
   // gamma and beta are fetched before the reductions, whose barriers would otherwise stand between these
   // loads and the statistics they do not depend on
-  uint4 gam[kLnPieces], bet[kLnPieces];
+  uint4 gam[PPT], bet[PPT];
 #pragma unroll
-  for (int i = 0; i < kLnPieces; ++i) {
-    const int p = threadIdx.x + i * kLnThreads;
+  for (int i = 0; i < PPT; ++i) {
+    const int p = threadIdx.x + i * blockDim.x;
     if (p < pieces) gam[i] = reinterpret_cast<const uint4 *>(a.ln_gamma)[p], bet[i] = reinterpret_cast<const uint4 *>(a.ln_beta)[p];
   }
   const float mean = block_sum(s, scratch) / (float)h;
   float q = 0.f;
 #pragma unroll
-  for (int i = 0; i < kLnPieces; ++i)
-    if ((int)threadIdx.x + i * kLnThreads < pieces) {
+  for (int i = 0; i < PPT; ++i)
+    if ((int)threadIdx.x + i * blockDim.x < pieces) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) q += (v[i][e] - mean) * (v[i][e] - mean);
     }
   const float rstd = 1.0f / sqrtf(block_sum(q, scratch) / (float)h + a.ln_eps);
 #pragma unroll
-  for (int i = 0; i < kLnPieces; ++i) {
-    const int p = threadIdx.x + i * kLnThreads;
+  for (int i = 0; i < PPT; ++i) {
+    const int p = threadIdx.x + i * blockDim.x;
     if (p < pieces) {
       const _Float16 *gp = reinterpret_cast<const _Float16 *>(&gam[i]), *bp = reinterpret_cast<const _Float16 *>(&bet[i]);
       uint4 o;
@@ -575,8 +580,10 @@ hipError_t launch_linear_mf(const LinearArgs &args, int n_tiles, bool fast, int 
     if (args.splits > 1 || args.to_shares) {
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
-      if (args.ln_out)
-        hipLaunchKernelGGL(reduce_layernorm_kernel, dim3(args.m), dim3(kLnThreads), 0, stream, args);
+      if (args.ln_out && (args.n_out >> 3) <= kLnMaxThreads)
+        hipLaunchKernelGGL(reduce_layernorm_kernel<1>, dim3(args.m), dim3(ln_threads(args.n_out)), 0, stream, args);
+      else if (args.ln_out)
+        hipLaunchKernelGGL(reduce_layernorm_kernel<2>, dim3(args.m), dim3(ln_threads(args.n_out)), 0, stream, args);
       else
         hipLaunchKernelGGL(reduce_epilogue_kernel, dim3((args.n_out + 1023) / 1024, args.m), dim3(256), 0, stream, args);
     }
@@ -655,7 +662,7 @@ hipError_t launch_linear(const LinearLaunch &l, hipStream_t stream) {
     a.shares = static_cast<float *>(l.workspace);
   }
   // a layer norm of the result rides on the share reduction when there is one to ride on
-  const bool fuse_ln = l.ln_out && fast && l.n_seg == 1 && l.n_out <= kLnThreads * kLnPieces * 8 && l.workspace &&
+  const bool fuse_ln = l.ln_out && fast && l.n_seg == 1 && l.n_out <= kLnMaxWidth && l.workspace &&
                        l.workspace_bytes >= (int64_t)a.splits * l.m * l.n_out * 4;
   if (fuse_ln) {
     a.to_shares = 1;
@@ -686,7 +693,11 @@ hipError_t launch_pack_weight(void *dst, const void *src, int32_t n_out, int32_t
 
 hipError_t launch_layernorm(const void *x, const void *gamma, const void *beta, void *out, int32_t m, int32_t h, float eps,
                             hipStream_t stream) {
-  hipLaunchKernelGGL(layernorm_kernel, dim3(m), dim3(kLnThreads), 0, stream, static_cast<const uint4 *>(x),
+  if ((h >> 3) > kLnMaxThreads)
+    hipLaunchKernelGGL(layernorm_kernel<2>, dim3(m), dim3(ln_threads(h)), 0, stream, static_cast<const uint4 *>(x),
+                       static_cast<const uint4 *>(gamma), static_cast<const uint4 *>(beta), static_cast<uint4 *>(out), h, eps);
+  else
+  hipLaunchKernelGGL(layernorm_kernel<1>, dim3(m), dim3(ln_threads(h)), 0, stream, static_cast<const uint4 *>(x),
                      static_cast<const uint4 *>(gamma), static_cast<const uint4 *>(beta), static_cast<uint4 *>(out), h, eps);
   return hipGetLastError();
 }
