@@ -196,34 +196,45 @@ __global__ __launch_bounds__(kLinWaves * 64) void linear_kernel(const LinearArgs
 // Fast path: NW wavefronts x 16 features, x staged in LDS by one more wavefront, input
 // dimension cut across workgroups.  NW = 4, or 3 where that gives one workgroup per compute unit without a cut
 // (12288 features on 256 units), which saves the kernel that adds up the shares.
-// 32-input blocks per staged chunk = weight pieces (1 KiB) in flight per wavefront; bounded by the LDS the
-// two x buffers take (2 x chunk x 16 MF rows x 64 bytes): 64 KiB at most.
-#ifndef OKV_LIN_CHUNK
-#define OKV_LIN_CHUNK 8
-#endif
-constexpr int lin_chunk(int mf) { return mf <= 2 ? OKV_LIN_CHUNK : mf <= 4 ? 8 : 4; }
-// How many chunks of x the staging wavefront is ahead of the others (one LDS buffer more than that).  Bounded by
-// LDS (a chunk takes lin_chunk x MF KiB) and by the counter of loads in flight, which stops at 63: the wait for a
-// chunk leaves the loads of the lead - 1 chunks after it outstanding.
-#ifndef OKV_LIN_LEAD
-#define OKV_LIN_LEAD 3
-#endif
-constexpr int lin_lead(int mf) { return mf <= 3 ? OKV_LIN_LEAD : 2; }
+// 32-input blocks per staged chunk of x: 8 (256 inputs), 4 from 112 rows on.  A chunk takes chunk x MF KiB of LDS
+// and there are lead + 1 of them: 128 KiB at most (4 x 32 at 64 and at 128 rows), 144 at 96 rows (3 x 48).
+constexpr int lin_chunk(int mf) { return mf <= 6 ? 8 : 4; }
+// How many chunks of x the staging wavefronts are ahead of the others (one LDS buffer more than that).  Bounded by
+// LDS and by the counter of loads in flight, which stops at 63: the wait for a chunk leaves the loads of the
+// lead - 1 chunks after it outstanding.
+constexpr int lin_lead(int mf) { return mf == 5 || mf == 6 ? 2 : 3; }
+// Staging wavefronts per workgroup: two from 64 rows on, each taking every other instruction of a chunk.  (At 128
+// rows the rows of x that the workgroups fetch from L2 are twice the bytes of the weights, and that traffic is
+// what the time then follows: 16384 x 4096 takes 40 us, 31 with the staging switched off, whether one wavefront
+// stages or two, whatever the lead; the second wavefront is worth 1 us.)
+constexpr int lin_stagers(int mf) { return mf >= 4 ? 2 : 1; }
+// chunks of weights a streaming wavefront has in flight: 8 KiB either way
+constexpr int lin_weight_lead(int mf) { return 8 / lin_chunk(mf) > 1 ? 8 / lin_chunk(mf) : 1; }
 // s_waitcnt operand that waits until at most n vector memory loads are outstanding and for nothing else
 constexpr int vmcnt_only(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
 
 // waves_per_eu: without the hint the compiler aims at the occupancy that the LDS footprint would allow and
 // caps the kernel at 64 registers.
 template <int MF, int NW>
-__global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu(2, 4))) void linear_lds_kernel(const LinearArgs a) {
-  constexpr int kFastThreads = (NW + 1) * 64, kTileCols = NW * 16;      // kTileCols: output features of a workgroup
-  constexpr int C = lin_chunk(MF), LEAD = lin_lead(MF), NBUF = LEAD + 1, PER = C * MF;
-  static_assert((LEAD - 1) * PER <= 63, "the wait for a staged chunk must fit the load counter");
-  // A chunk of x, [16 MF rows][LPR 16-byte pieces] (LPR x 8 inputs).  Piece p of row r sits in slot (p - r) mod LPR of
-  // the row: a matrix-core operand read takes the same piece of 16 consecutive rows, and the shift spreads those
-  // over all the banks.  After the last chunk the same memory holds the fp32 tile [16 MF rows][kTileCols features]
-  // for the epilogue.
-  constexpr int LPR = C * 4, RPI = 64 / LPR;          // pieces per row; rows that one staging instruction brings
+__global__ __launch_bounds__((NW + lin_stagers(MF)) * 64) __attribute__((amdgpu_waves_per_eu(2, 4))) void linear_lds_kernel(const LinearArgs a) {
+  constexpr int NS = lin_stagers(MF);
+  constexpr int kFastThreads = (NW + NS) * 64, kTileCols = NW * 16;      // kTileCols: output features of a workgroup
+  constexpr int C = lin_chunk(MF), LEAD = lin_lead(MF), NBUF = LEAD + 1, PER = C * MF, MINE = PER / NS;
+  static_assert(PER % NS == 0 && (LEAD - 1) * MINE <= 63, "the wait for a staged chunk must fit the load counter");
+  // A chunk of x, 16 MF rows of LPR 16-byte pieces (LPR x 8 inputs), as PER staging instructions' worth of 64
+  // pieces each.  An operand read takes, for block i of the chunk, piece 4 i + q of row 16 f + rr in lane 16 q + rr.
+  // The LDS serves a 16-byte-per-lane read in groups of 16 lanes that are not consecutive (lanes 0-3, 12-15, 20-23,
+  // 24-27 and so on: measured, a layout that only spread 16 consecutive lanes over the banks had every read take
+  // twice its cycles), so the bank (16-byte unit modulo 16) of a piece is (rr + 2 i + q / 2) mod 16: it does not
+  // depend on the low bit of q, and within any such group all 16 rows rr occur once.  The two pieces that share
+  // a bank (q even and odd) and the rows of an instruction take the unit's upper bits:
+  //   unit = 64 * instruction + 16 * (2 * (rr & 1) + (q & 1)) + bank,
+  //   instruction = 8 f + rr / 2 (8 blocks a chunk: rows 2 t and 2 t + 1, 512 bytes each), or
+  //                 4 f + (rr % 8) / 2 (4 blocks: rows 2 t, 2 t + 1, 2 t + 8, 2 t + 9, 256 bytes each; of rr and
+  //                 rr + 8 exactly one has (bank - rr) mod 16 below 8, which is where 2 i + q / 2 lives then).
+  // After the last chunk the same memory holds the fp32 tile [16 MF rows][kTileCols features] for the epilogue.
+  static_assert(C == 8 || C == 4, "the LDS layout of x is laid out for chunks of 8 or 4 blocks");
+  constexpr int LPR = C * 4, IPF = C;                  // pieces per row; staging instructions per 16 rows
   __shared__ uint4 xs[NBUF][PER][64];
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -239,33 +250,41 @@ __global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu(2
   const int rot = (int)(((unsigned)group * 5u + (unsigned)cut * 3u) % (unsigned)n_chunks);
   auto rotc = [&](int c) { int cc = c + rot; return cc >= n_chunks ? cc - n_chunks : cc; };
 
-  if (wave == NW) {
+  if (wave >= NW) {
     // The staging wavefront.  Its loads have a counter of their own, so waiting for them never
     // holds up the weight stream of the others.  A load instruction writes straight into LDS, 16 bytes per
-    // lane, lane l landing in slot l of the instruction's 1 KiB: it brings RPI whole rows of the chunk (LPR
-    // lanes a row, 512 contiguous bytes at 8 blocks a chunk), every lane fetching the piece that belongs in
-    // its slot.  (Fetched in the order the matrix core reads -- 16 rows x 64 bytes per instruction -- the same
-    // bytes took twice as many half-used cache lines.)
+    // lane, lane l landing in unit l of the instruction's 1 KiB; every lane fetches the piece that belongs
+    // there.  An instruction brings whole rows of the chunk (2 x 512 or 4 x 256 contiguous bytes).  (Fetched in
+    // the order the matrix core reads -- 16 rows x 64 bytes per instruction -- the same bytes took twice as
+    // many half-used cache lines.)
     const int row_pieces = a.n_in >> 3;
-    const int h = lane / LPR, sl = lane % LPR;
-    const uint4 *xg[PER];
+    const int bank = lane & 15, ql = (lane >> 4) & 1, odd = lane >> 5;
+    const int first = wave - NW;                   // this staging wavefront takes instructions first, first + NS, ...
+    const uint4 *xg[MINE];
 #pragma unroll
-    for (int j = 0; j < PER; ++j) {     // rows past the batch read row 0: they only reach result rows that are not stored
-      const int row = j * RPI + h;
-      xg[j] = a.x + (size_t)(row < a.m ? row : 0) * row_pieces + (size_t)kb0 * 4 + ((sl + row) & (LPR - 1));
+    for (int k = 0; k < MINE; ++k) {
+      const int j = first + NS * k;
+      const int f = j / IPF, t = j % IPF;
+      int rr = 2 * t + odd;
+      const int d = (bank - rr) & 15;
+      if (C == 4 && d >= 8) rr += 8;
+      const int v = C == 4 ? (d & 7) : d;                            // 2 i + q / 2
+      const int piece = 4 * (v >> 1) + 2 * (v & 1) + ql;
+      const int row = 16 * f + rr;                 // rows past the batch read row 0: they only reach result rows that are not stored
+      xg[k] = a.x + (size_t)(row < a.m ? row : 0) * row_pieces + (size_t)kb0 * 4 + piece;
     }
     auto stage = [&](int chunk, int buf) {
 #pragma unroll
-      for (int j = 0; j < PER; ++j)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(xg[j] + (size_t)chunk * LPR),
-                                         (__attribute__((address_space(3))) void *)&xs[buf][j][0], 16, 0, 0);
+      for (int k = 0; k < MINE; ++k)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(xg[k] + (size_t)chunk * LPR),
+                                         (__attribute__((address_space(3))) void *)&xs[buf][first + NS * k][0], 16, 0, 0);
     };
     // LEAD chunks ahead of the others, so that a chunk has LEAD of their chunk times to arrive, not one (with one:
     // 3 us of 30 at 32 rows and 16 of 44 at 64 rows went into waiting for it, 16384 x 4096).  Before barrier c
     // chunk c must have landed: the loads of the chunks issued after it, LEAD - 1 of them except at the end, may
     // still be on their way.
     auto landed = [&](int c) {
-      if (n_chunks - 1 - c >= LEAD - 1) __builtin_amdgcn_s_waitcnt(vmcnt_only((LEAD - 1) * PER));
+      if (n_chunks - 1 - c >= LEAD - 1) __builtin_amdgcn_s_waitcnt(vmcnt_only((LEAD - 1) * MINE));
       else __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
     };
 #pragma unroll
@@ -285,49 +304,57 @@ __global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu(2
     const int ntile = group * NW + wave;
     // a wavefront past the last tile streams tile 0 (valid memory) and never stores
     const uint4 *wp = a.w + ((size_t)(ntile < a.n_tiles ? ntile : 0) * a.n_kb + kb0) * 64 + lane;
-    // where this lane's operand pieces sit in a chunk: row 16 f + lane % 16, piece 4 i + lane / 16 for block i
-    int xrow[MF], xrot[MF];
-#pragma unroll
-    for (int f = 0; f < MF; ++f) {
-      const int row = 16 * f + (lane & 15);
-      xrow[f] = row * LPR;
-      xrot[f] = (lane >> 4) - row;
-    }
+    // where this lane's operand pieces sit in a chunk (see the layout above): rr = lane % 16, q = lane / 16
+    const int rr = lane & 15, q = lane >> 4;
+    const int xbase = 64 * (C == 8 ? rr >> 1 : (rr & 7) >> 1) + 16 * (2 * (rr & 1) + (q & 1));
+    const int xrq = rr + (q >> 1);
     auto xat = [&](int buf, int i, int f) -> uint4 {
-      return (&xs[buf][0][0])[xrow[f] + ((xrot[f] + 4 * i) & (LPR - 1))];
+      return (&xs[buf][0][0])[64 * IPF * f + xbase + ((xrq + 2 * i) & 15)];
     };
-    uint4 wbuf[C];
+    // Weights are fetched WD chunks ahead: with more than 64 rows a chunk is only 4 blocks (LDS), and 4 KiB in
+    // flight, each refill waiting behind eight matrix instructions, did not keep the stream going (16384 x 4096
+    // at 128 rows: 43 us; without the staging and the LDS reads still 36).
+    constexpr int WD = lin_weight_lead(MF);
+    uint4 wbuf[WD][C];
+    auto ahead = [&](int c) { return rotc(c < n_chunks ? c : n_chunks - 1); };   // past the end: the last chunk again
 #pragma unroll
-    for (int i = 0; i < C; ++i) {                            // oldest first: the loop waits for them in this order
-      wbuf[i] = wp[((size_t)rotc(0) * C + i) * 64];
-      __builtin_amdgcn_sched_barrier(0);
-    }
-    __syncthreads();
-    int buf = 0;
-    for (int c = 0; c < n_chunks; ++c) {
-      // the chunk after this one (the last chunk is fetched once more instead of branching: loads in
-      // this loop stay unconditional, so the waits stay exact)
-      const int cn = rotc(c + 1 < n_chunks ? c + 1 : c);
-      uint4 xr[MF];
+    for (int u = 0; u < WD; ++u)
 #pragma unroll
-      for (int f = 0; f < MF; ++f) xr[f] = xat(buf, 0, f);
-#pragma unroll
-      for (int i = 0; i < C; ++i) {
-        const uint4 w = wbuf[i];
-#pragma unroll
-        for (int f = 0; f < MF; ++f) acc[f] = mfma32(xr[f], w, acc[f]);
-        __builtin_amdgcn_sched_barrier(0);
-        wbuf[i] = wp[((size_t)cn * C + i) * 64];
-        // the rows of x for the next block are on their way from LDS while this wavefront waits for that
-        // block's weights
-        if (i + 1 < C) {
-#pragma unroll
-          for (int f = 0; f < MF; ++f) xr[f] = xat(buf, i + 1, f);
-        }
+      for (int i = 0; i < C; ++i) {                          // oldest first: the loop waits for them in this order
+        wbuf[u][i] = wp[((size_t)ahead(u) * C + i) * 64];
         __builtin_amdgcn_sched_barrier(0);
       }
-      buf = buf + 1 == NBUF ? 0 : buf + 1;
-      __syncthreads();
+    __syncthreads();
+    int buf = 0;
+    for (int c0 = 0; c0 < n_chunks; c0 += WD) {
+#pragma unroll
+      for (int u = 0; u < WD; ++u) {
+        const int c = c0 + u;                    // the host only cuts the inputs into stretches of a multiple of WD chunks
+        // the chunk WD after this one (past the end the last chunk is fetched once more instead of branching:
+        // loads in this loop stay unconditional, so the waits stay exact)
+        const int cn = ahead(c + WD);
+        // the rows of x for a block are asked from LDS before the matrix instructions of the block before it are
+        // issued (two sets of registers), so that they arrive while those run and while this wavefront waits for
+        // the block's weights
+        uint4 xr[2][MF];
+#pragma unroll
+        for (int f = 0; f < MF; ++f) xr[0][f] = xat(buf, 0, f);
+#pragma unroll
+        for (int i = 0; i < C; ++i) {
+          if (i + 1 < C) {
+#pragma unroll
+            for (int f = 0; f < MF; ++f) xr[(i + 1) & 1][f] = xat(buf, i + 1, f);
+          }
+          const uint4 w = wbuf[u][i];
+#pragma unroll
+          for (int f = 0; f < MF; ++f) acc[f] = mfma32(xr[i & 1][f], w, acc[f]);
+          __builtin_amdgcn_sched_barrier(0);
+          wbuf[u][i] = wp[((size_t)cn * C + i) * 64];
+          __builtin_amdgcn_sched_barrier(0);
+        }
+        buf = buf + 1 == NBUF ? 0 : buf + 1;
+        __syncthreads();
+      }
     }
   }
 
@@ -341,25 +368,44 @@ __global__ __launch_bounds__((NW + 1) * 64) __attribute__((amdgpu_waves_per_eu(2
       for (int r = 0; r < 4; ++r) tile[(f * 16 + 4 * (lane >> 4) + r) * kTileCols + wave * 16 + (lane & 15)] = acc[f][r];
   }
   __syncthreads();
+  // eight neighbouring features of a row per thread (feature counts and segment widths are multiples of 16, so
+  // a group of eight never straddles a segment and every access below is one aligned 16-byte piece)
   const int n0 = group * kTileCols;
+  constexpr int VPR = kTileCols / 8;
   if (a.splits > 1 || a.to_shares) {                   // this cut's share; a second kernel adds them up
     float *mine = a.shares + (size_t)cut * a.m * a.n_out;
-    for (int o = tid; o < a.m * kTileCols; o += kFastThreads) {
-      const int mrow = o / kTileCols, n = n0 + o % kTileCols;
-      if (n < a.n_out) mine[(size_t)mrow * a.n_out + n] = tile[o];
+    for (int o = tid; o < a.m * VPR; o += kFastThreads) {
+      const int mrow = o / VPR, n = n0 + 8 * (o % VPR);
+      if (n >= a.n_out) continue;
+      const float4 *t = reinterpret_cast<const float4 *>(tile + mrow * kTileCols + 8 * (o % VPR));
+      float4 *dst = reinterpret_cast<float4 *>(mine + (size_t)mrow * a.n_out + n);
+      dst[0] = t[0];
+      dst[1] = t[1];
     }
     return;
   }
-  for (int o = tid; o < a.m * kTileCols; o += kFastThreads) {
-    const int mrow = o / kTileCols, n = n0 + o % kTileCols;
+  for (int o = tid; o < a.m * VPR; o += kFastThreads) {
+    const int mrow = o / VPR, n = n0 + 8 * (o % VPR);
     if (n >= a.n_out) continue;
-    float v = tile[o];
-    if (a.bias) v += (float)a.bias[n];
-    if (a.relu) v = fmaxf(v, 0.f);
+    const float4 *t = reinterpret_cast<const float4 *>(tile + mrow * kTileCols + 8 * (o % VPR));
+    const float4 t0 = t[0], t1 = t[1];
+    float v[8] = {t0.x, t0.y, t0.z, t0.w, t1.x, t1.y, t1.z, t1.w};
     const int seg = n / a.seg_cols, col = n - seg * a.seg_cols;
     const size_t at = (size_t)mrow * a.seg_cols + col;
-    if (a.residual) v += (float)a.residual[at];
-    a.out[seg][at] = (_Float16)v;
+    uint4 bb = make_uint4(0u, 0u, 0u, 0u), rb = bb;
+    if (a.bias) bb = *reinterpret_cast<const uint4 *>(a.bias + n);
+    if (a.residual) rb = *reinterpret_cast<const uint4 *>(a.residual + at);
+    const _Float16 *bp = reinterpret_cast<const _Float16 *>(&bb), *rp = reinterpret_cast<const _Float16 *>(&rb);
+    uint4 yo;
+    _Float16 *yp = reinterpret_cast<_Float16 *>(&yo);
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      float y = v[e] + (float)bp[e];
+      if (a.relu) y = fmaxf(y, 0.f);
+      y += (float)rp[e];
+      yp[e] = (_Float16)y;
+    }
+    *reinterpret_cast<uint4 *>(a.out[seg] + at) = yo;
   }
 }
 
@@ -575,8 +621,8 @@ template <int MF>
 hipError_t launch_linear_mf(const LinearArgs &args, int n_tiles, bool fast, int fast_waves, hipStream_t stream) {
   if (fast) {
     dim3 grid((n_tiles + fast_waves - 1) / fast_waves, args.splits);
-    if (fast_waves == 3) hipLaunchKernelGGL((linear_lds_kernel<MF, 3>), grid, dim3(4 * 64), 0, stream, args);
-    else hipLaunchKernelGGL((linear_lds_kernel<MF, 4>), grid, dim3(5 * 64), 0, stream, args);
+    if (fast_waves == 3) hipLaunchKernelGGL((linear_lds_kernel<MF, 3>), grid, dim3((3 + lin_stagers(MF)) * 64), 0, stream, args);
+    else hipLaunchKernelGGL((linear_lds_kernel<MF, 4>), grid, dim3((4 + lin_stagers(MF)) * 64), 0, stream, args);
     if (args.splits > 1 || args.to_shares) {
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
@@ -599,13 +645,13 @@ hipError_t launch_linear_mf(const LinearArgs &args, int n_tiles, bool fast, int 
 // for one per compute unit, as long as every cut keeps at least two chunks, and only cuts that divide the chunks
 // evenly.  0: not a shape for the fast kernel.
 int linear_splits(int32_t m, int32_t n_out, int32_t n_in, int32_t n_cus, int waves) {
-  const int chunk = lin_chunk((m + 15) / 16);
-  if (n_in % (32 * chunk)) return 0;
+  const int chunk = lin_chunk((m + 15) / 16), pace = lin_weight_lead((m + 15) / 16);
+  if (n_in % (32 * chunk * pace)) return 0;
   const int chunks = n_in / (32 * chunk);
   const int groups = (n_out / 16 + waves - 1) / waves;
   int best = 1;
   for (int s = 1; s <= chunks; ++s) {
-    if (chunks % s) continue;
+    if (chunks % (s * pace)) continue;                         // the kernel takes `pace` chunks at a time
     if (s > 1 && chunks / s < 2) break;
     best = s;
     if ((int64_t)groups * s >= OKV_LIN_WG_PER_CU * (int64_t)n_cus) break;
