@@ -227,7 +227,11 @@ int64_t count_items(const int32_t *ctx, int32_t B, int32_t S) {
 // round in which each of them runs at what U mod W wavefronts can pull (1536 units of
 // 2048 keys on 1024 wavefronts take as long as 2048 of them; cut in two they take three
 // rounds of half the length).  Fewer, longer items save per-item cost and the merge pass;
-// equal items avoid a tail; a unit count that fills the rounds avoids idle wavefronts.
+// equal items avoid a tail; a unit count that fills the rounds avoids idle wavefronts.  Units of
+// mixed sizes do not move in rounds (the queue hands the next unit to whichever wavefront is free), so
+// the term only counts when the smallest unit is within a tenth of the largest; the tail term speaks
+// for the others (batch 64 of 512..4096 keys, 32 heads: the rounds term chose 256-key units, 420 us a
+// layer, where 512 take 404).
 // The constants are measured on MI355X with this kernel (d = 128 rows).
 constexpr double kLaunchBytesPerUs = 6.3e6;      // what the split kernel sustains, bytes per microsecond
 constexpr double kWaveBytesPerUs = 6.5e3;        // one wavefront with 8 KiB in flight
@@ -268,8 +272,11 @@ double launch_cost_us(const okv_ctx *ctx, const std::vector<int32_t> &lens, int3
   const int64_t W = std::max<int64_t>(1, ctx->max_waves);
   const double unit_bytes = bytes / (double)units + kItemOverheadBytes;
   const int64_t left = units % W;
-  double rounds = (double)(units / W) * unit_bytes * (double)W / kLaunchBytesPerUs;
-  if (left) rounds += unit_bytes / std::min(kWaveBytesPerUs, kLaunchBytesPerUs / (double)left);
+  double rounds = 0;
+  if (sizes.back().first * 10 >= sizes[0].first * 9) {             // units of (nearly) one size move in step
+    rounds = (double)(units / W) * unit_bytes * (double)W / kLaunchBytesPerUs;
+    if (left) rounds += unit_bytes / std::min(kWaveBytesPerUs, kLaunchBytesPerUs / (double)left);
+  }
   return std::max({stream + 0.5 * tail, longest / kWaveBytesPerUs, rounds});
 }
 
