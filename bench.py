@@ -468,7 +468,7 @@ def run_layers(args):
     linear product alone."""
     import torch
     from paper_2504_11816_amd import binding, synth
-    from paper_2504_11816_amd.harness import LayerScratch, LayerWeights, Stack, decode_step_with_layers
+    from paper_2504_11816_amd.harness import BoundLayers, LayerScratch, LayerWeights, Stack
     w = dict(synth.WORKLOADS["cfg2"])
     L, H, G, d, B = w["L"], w["H"], w["G"], w["d"], w["B"]
     if args.layers:
@@ -484,10 +484,12 @@ def run_layers(args):
     x0 = synth.randn_f16_torch((B, h1), synth.stream_seed(args.seed, synth.TENSOR_Q), st.device)
     x = x0.clone()
 
+    bound = BoundLayers(st, weights, scratch)      # one call into the library per step (okv_decoder_step)
+
     def run(n):
         for _ in range(n):
             x.copy_(x0)                    # keep the activations at the scale of the inputs (random weights amplify)
-            decode_step_with_layers(st, weights, scratch, x)
+            bound.step(x)
     st.set_batch(ctx0, None)
     with torch.cuda.stream(st.compute_stream):
         run(warmup)
@@ -533,7 +535,7 @@ def run_layers(args):
         f"{res['hbm_gbps']:.0f} GB/s of weights + KV ({100 * res['hbm_frac']:.1f}% of HBM peak); products alone: "
         + ", ".join(f"{k} {v['us']:.1f} us = {v['weight_gbps']:.0f} GB/s" for k, v in alone.items()))
     st.close()
-    del st, weights, scratch
+    del st, weights, scratch, bound
     torch.cuda.empty_cache()
     return res
 

@@ -26,6 +26,8 @@ extern "C" {
 
 #define OKV_LINEAR_MAX_ROWS 128
 
+struct okv_ctx;   /* okv.h */
+
 /* Rearranges a weight matrix for okv_linear.
  *   src  fp16 [n_out][n_in] row-major (the layout of a framework's linear layer:
  *        out = x * src^T)
@@ -87,6 +89,42 @@ int64_t okv_linear_workspace_bytes(int32_t m, int32_t n_out, int32_t n_in);
  * h must be a multiple of 8 and at most 16384. */
 int okv_layernorm(const void *x, const void *gamma, const void *beta, void *out, int32_t m,
                   int32_t h, float eps, void *stream);
+
+/* One decoder layer's parameters for okv_decoder_step: matrices as okv_pack_linear_weight leaves
+ * them, biases and layer-norm vectors fp16.  w_qkv stacks the query, key and value projections
+ * ([3 h1][h1] before packing, h1 = n_q_heads * head_dim; needs n_kv_heads = n_q_heads), w_o is
+ * [h1][h1], w_ff1 [h2][h1], w_ff2 [h1][h2]. */
+typedef struct {
+  const void *ln1_gamma, *ln1_beta;   /* [h1]: the norm before the attention           */
+  const void *w_qkv, *b_qkv;          /* [3 h1 x h1] packed, [3 h1]                     */
+  const void *w_o, *b_o;              /* [h1 x h1] packed, [h1]                         */
+  const void *ln2_gamma, *ln2_beta;   /* [h1]: the norm before the feed-forward block   */
+  const void *w_ff1, *b_ff1;          /* [h2 x h1] packed, [h2]                         */
+  const void *w_ff2, *b_ff2;          /* [h1 x h2] packed, [h1]                         */
+} okv_decoder_layer;
+
+/* Bytes of scratch that okv_decoder_step needs for a batch of m rows: the layer's intermediate
+ * tensors (normed input, q, k, v, attention output, two residual streams, feed-forward hidden). */
+int64_t okv_decoder_scratch_bytes(const struct okv_ctx *ctx, int32_t m, int32_t h2);
+
+/* One decode step through n_layers = the context's layers of whole decoder layers (paper §IV-D:
+ * per token and layer the attention over the cache plus 8 h1^2 + 4 h1 h2 flops of linear layers),
+ * issued from inside the library on the context's compute stream: okv_step_begin, then per layer
+ *   a = LayerNorm1(x); q, k, v = a W_qkv^T + b; kv_append(k, v); t = decode_attn(q);
+ *   y = x + t W_o^T + b_o;  z = LayerNorm2(y);  u = relu(z W_ff1^T + b_ff1);  x = y + u W_ff2^T + b_ff2
+ * and okv_step_end.  The same launches, in the same order, as the calls one by one; what this
+ * saves is the caller's time per call (a Python caller spends longer on the six calls of a layer
+ * than a small layer runs on the GPU).
+ *   layers     HOST array [n_layers]
+ *   x          fp16 [B][h1], B = the batch of okv_set_batch (<= OKV_LINEAR_MAX_ROWS); overwritten
+ *              with the output of the last layer
+ *   scratch    >= okv_decoder_scratch_bytes(ctx, B, h2) bytes, 256-byte aligned
+ *   workspace  >= the largest okv_linear_workspace_bytes of the four products
+ *   eps        of both layer norms
+ * Errors as the calls it stands for; OKV_EINVAL also when n_kv_heads != n_q_heads or the context's
+ * out_dtype is not fp16. */
+int okv_decoder_step(struct okv_ctx *ctx, const okv_decoder_layer *layers, int32_t n_layers, int32_t h2, void *x,
+                     float eps, void *scratch, int64_t scratch_bytes, void *workspace, int64_t workspace_bytes);
 
 #ifdef __cplusplus
 }

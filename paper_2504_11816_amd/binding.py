@@ -28,7 +28,14 @@ EXPORTS = [
 
 
 # every symbol include/okv_layer.h declares (same library)
-LAYER_EXPORTS = ["okv_pack_linear_weight", "okv_linear", "okv_linear_layernorm", "okv_linear_workspace_bytes", "okv_layernorm"]
+LAYER_EXPORTS = ["okv_pack_linear_weight", "okv_linear", "okv_linear_layernorm", "okv_linear_workspace_bytes", "okv_layernorm",
+                 "okv_decoder_scratch_bytes", "okv_decoder_step"]
+
+
+class OkvDecoderLayer(ctypes.Structure):
+    """okv_decoder_layer of include/okv_layer.h: twelve device pointers."""
+    FIELDS = ("ln1_gamma", "ln1_beta", "w_qkv", "b_qkv", "w_o", "b_o", "ln2_gamma", "ln2_beta", "w_ff1", "b_ff1", "w_ff2", "b_ff2")
+    _fields_ = [(name, ctypes.c_void_p) for name in FIELDS]
 
 
 class OkvError(RuntimeError):
@@ -105,6 +112,8 @@ def lib():
             "okv_linear_workspace_bytes": (I64, [I32, I32, I32]),
             "okv_linear_layernorm": (ctypes.c_int, [P, P, P, P, P, P, P, ctypes.c_float, P, I32, I32, I32, I32, P, I64, P]),
             "okv_layernorm": (ctypes.c_int, [P, P, P, P, I32, I32, ctypes.c_float, P]),
+            "okv_decoder_scratch_bytes": (I64, [P, I32, I32]),
+            "okv_decoder_step": (ctypes.c_int, [P, P, I32, I32, P, ctypes.c_float, P, I64, P, I64]),
             "okv_probe_read": (ctypes.c_int, [P, I64, P, P]),
         }
         for name, (res, args) in sig.items():
@@ -337,6 +346,28 @@ class Context:
         if not (len(q) == len(k) == len(v) == len(o) == self.cfg.n_layers):
             raise ValueError("one pointer per layer in each array")
         self._c(lib().okv_decode_step(self._h, q, k, v, o))
+
+    @staticmethod
+    def decoder_layers(layers):
+        """The HOST array of okv_decoder_layer that okv_decoder_step takes, from one dict per layer
+        (keys: OkvDecoderLayer.FIELDS; values: device tensors or addresses, None for an absent bias).
+        Build it once; the caller keeps the tensors alive."""
+        arr = (OkvDecoderLayer * len(layers))()
+        for i, d in enumerate(layers):
+            for name in OkvDecoderLayer.FIELDS:
+                setattr(arr[i], name, _ptr(d.get(name)).value)
+        return arr
+
+    def okv_decoder_scratch_bytes(self, m, h2):
+        r = lib().okv_decoder_scratch_bytes(self._h, m, h2)
+        if r < 0:
+            _check(int(r))
+        return int(r)
+
+    def okv_decoder_step(self, layers, h2, x, scratch, scratch_bytes, workspace, workspace_bytes, eps=1e-5):
+        """layers: what decoder_layers returned."""
+        self._c(lib().okv_decoder_step(self._h, layers, len(layers), h2, _ptr(x), eps, _ptr(scratch), scratch_bytes,
+                                       _ptr(workspace), workspace_bytes))
 
     def okv_prefill_begin(self, n_new):
         n_new = np.ascontiguousarray(n_new, dtype=np.int32)

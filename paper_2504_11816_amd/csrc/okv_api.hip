@@ -1481,6 +1481,80 @@ int okv_layernorm(const void *x, const void *gamma, const void *beta, void *out,
   return OKV_OK;
 }
 
+namespace {
+// the intermediate tensors of a decoder layer inside the scratch buffer, each rounded up to 256 bytes
+struct DecoderScratch {
+  char *a, *q, *k, *v, *t, *y, *z, *u;
+  int64_t bytes;
+};
+DecoderScratch decoder_scratch(void *base, int32_t m, int32_t h1, int32_t h2) {
+  DecoderScratch d;
+  int64_t at = 0;
+  auto take = [&](int64_t cols) {
+    char *p = static_cast<char *>(base) + at;
+    at += ((int64_t)m * cols * 2 + 255) / 256 * 256;
+    return p;
+  };
+  d.a = take(h1), d.q = take(h1), d.k = take(h1), d.v = take(h1), d.t = take(h1), d.y = take(h1), d.z = take(h1), d.u = take(h2);
+  d.bytes = at;
+  return d;
+}
+}  // namespace
+
+int64_t okv_decoder_scratch_bytes(const okv_ctx *ctx, int32_t m, int32_t h2) {
+  if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
+  if (m < 1 || m > OKV_LINEAR_MAX_ROWS || h2 < 32 || h2 % 32) return fail(nullptr, OKV_EINVAL, "okv_decoder_scratch_bytes: bad shape");
+  return decoder_scratch(nullptr, m, ctx->cfg.n_q_heads * ctx->cfg.head_dim, h2).bytes;
+}
+
+int okv_decoder_step(okv_ctx *ctx, const okv_decoder_layer *layers, int32_t n_layers, int32_t h2, void *x, float eps,
+                     void *scratch, int64_t scratch_bytes, void *workspace, int64_t workspace_bytes) {
+  if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
+  if (!layers || !x || !scratch) return fail(ctx, OKV_EINVAL, "okv_decoder_step: NULL pointer");
+  if (n_layers != ctx->cfg.n_layers) return fail(ctx, OKV_EINVAL, "okv_decoder_step: %d layers, the context has %d", n_layers, ctx->cfg.n_layers);
+  if (ctx->cfg.n_kv_heads != ctx->cfg.n_q_heads)
+    return fail(ctx, OKV_EINVAL, "okv_decoder_step: the stacked q/k/v projection needs as many KV heads as query heads");
+  if (ctx->cfg.out_dtype != 0) return fail(ctx, OKV_EINVAL, "okv_decoder_step: the attention output must be fp16 (out_dtype 0)");
+  if (!ctx->batch_set) return fail(ctx, OKV_ESTATE, "okv_decoder_step before okv_set_batch");
+  const int32_t m = ctx->B, h1 = ctx->cfg.n_q_heads * ctx->cfg.head_dim;
+  if (m < 1 || m > OKV_LINEAR_MAX_ROWS) return fail(ctx, OKV_EINVAL, "okv_decoder_step: batch %d outside [1, %d]", m, OKV_LINEAR_MAX_ROWS);
+  if (h2 < 32 || h2 % 32 || h2 > 16384 * 8) return fail(ctx, OKV_EINVAL, "okv_decoder_step: bad feed-forward width %d", h2);
+  if (((uintptr_t)scratch & 255) || !aligned16(x)) return fail(ctx, OKV_EINVAL, "okv_decoder_step: scratch or x misaligned");
+  const DecoderScratch d = decoder_scratch(scratch, m, h1, h2);
+  if (scratch_bytes < d.bytes) return fail(ctx, OKV_ENOSPC, "okv_decoder_step: scratch holds %lld bytes, %lld needed", (long long)scratch_bytes, (long long)d.bytes);
+  for (int32_t l = 0; l < n_layers; ++l) {
+    const okv_decoder_layer &w = layers[l];
+    if (!w.ln1_gamma || !w.ln1_beta || !w.w_qkv || !w.w_o || !w.ln2_gamma || !w.ln2_beta || !w.w_ff1 || !w.w_ff2)
+      return fail(ctx, OKV_EINVAL, "okv_decoder_step: layer %d has a NULL matrix or norm vector", l);
+  }
+  void *stream = ctx->compute;
+  int rc = okv_step_begin(ctx);
+  if (rc != OKV_OK) return rc;
+  // from here on a failure leaves the step open, as it does when the calls are made one by one
+  rc = okv_layernorm(x, layers[0].ln1_gamma, layers[0].ln1_beta, d.a, m, h1, eps, stream);
+  for (int32_t l = 0; rc == OKV_OK && l < n_layers; ++l) {
+    const okv_decoder_layer &w = layers[l];
+    void *qkv[3] = {d.q, d.k, d.v};
+    rc = okv_linear(d.a, w.w_qkv, w.b_qkv, nullptr, qkv, 3, m, 3 * h1, h1, 0, workspace, workspace_bytes, stream);
+    if (rc == OKV_OK) rc = kv_append(ctx, l, d.k, d.v);
+    if (rc == OKV_OK) rc = decode_attn(ctx, l, d.q, d.t);
+    // output projection + residual, and the second norm of its result on the same share reduction
+    if (rc == OKV_OK)
+      rc = okv_linear_layernorm(d.t, w.w_o, w.b_o, x, d.y, w.ln2_gamma, w.ln2_beta, eps, d.z, m, h1, h1, 0, workspace, workspace_bytes, stream);
+    void *hidden[1] = {d.u};
+    if (rc == OKV_OK) rc = okv_linear(d.z, w.w_ff1, w.b_ff1, nullptr, hidden, 1, m, h2, h1, 1, workspace, workspace_bytes, stream);
+    if (rc != OKV_OK) break;
+    if (l + 1 < n_layers) {                                // the next layer's first norm rides on the feed-forward block
+      rc = okv_linear_layernorm(d.u, w.w_ff2, w.b_ff2, d.y, x, layers[l + 1].ln1_gamma, layers[l + 1].ln1_beta, eps, d.a, m, h1, h2, 0,
+                                workspace, workspace_bytes, stream);
+    } else {
+      void *outs[1] = {x};
+      rc = okv_linear(d.u, w.w_ff2, w.b_ff2, d.y, outs, 1, m, h1, h2, 0, workspace, workspace_bytes, stream);
+    }
+  }
+  return rc == OKV_OK ? okv_step_end(ctx) : rc;
+}
+
 int okv_probe_copy(void *dst, const void *src, int64_t bytes, void *stream) {
   if (!dst || !src || bytes < 0 || bytes % 16 || !aligned16(dst) || !aligned16(src))
     return fail(nullptr, OKV_EINVAL, "okv_probe_copy: bad argument");

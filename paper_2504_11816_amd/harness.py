@@ -306,6 +306,26 @@ class LayerScratch:
         self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
 
 
+class BoundLayers:
+    """The stack's decoder layers handed to the library once: the array of okv_decoder_layer and the
+    scratch that okv_decoder_step works in.  step(x) is then one call per decode step."""
+
+    def __init__(self, st, weights, scratch):
+        self.st, self.weights, self.ws = st, weights, scratch          # keeps the tensors alive
+        self.h2 = weights[0].h2
+        self.layers = binding.Context.decoder_layers([
+            dict(ln1_gamma=w.t["ln1_g"], ln1_beta=w.t["ln1_b"], w_qkv=w.packed["wqkv"], b_qkv=w.bqkv, w_o=w.packed["wo"], b_o=w.t["bo"],
+                 ln2_gamma=w.t["ln2_g"], ln2_beta=w.t["ln2_b"], w_ff1=w.packed["w1"], b_ff1=w.t["b1"], w_ff2=w.packed["w2"],
+                 b_ff2=w.t["b2"]) for w in weights])
+        self.scratch_bytes = st.ctx.okv_decoder_scratch_bytes(st.B, self.h2)
+        self.scratch = torch.empty(self.scratch_bytes, dtype=torch.uint8, device=scratch.ws.device)
+
+    def step(self, x):
+        self.st.ctx.okv_decoder_step(self.layers, self.h2, x, self.scratch, self.scratch_bytes, self.ws.ws, self.ws.ws_bytes)
+        if self.st.ctx_lens is not None:
+            self.st.ctx_lens += 1
+
+
 def decode_step_with_layers(st, weights, scratch, x):
     """One decode step of whole decoder layers: for every layer, layer norm, the stacked
     query/key/value projection, kv_append + decode_attn, output projection with residual,

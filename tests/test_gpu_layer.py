@@ -15,7 +15,7 @@ from oracle import attention as oa
 from oracle import decode_layer as dl
 from oracle import kv_layout
 from paper_2504_11816_amd import binding, synth
-from paper_2504_11816_amd.harness import LayerScratch, LayerWeights, decode_step_with_layers
+from paper_2504_11816_amd.harness import BoundLayers, LayerScratch, LayerWeights, decode_step_with_layers
 
 from gpu_util import build_stack
 
@@ -251,4 +251,60 @@ def test_whole_decoder_layers_against_the_oracle(T, on_host):
         for l in range(L):
             got = st.read_pool(l).astype(np.float64)
             assert np.abs(got - pools[l].astype(np.float64)).max() < 2e-2
+    st.close()
+
+
+@pytest.mark.parametrize("T", [0, 16])
+def test_decoder_step_in_one_call_equals_the_calls_one_by_one(T):
+    # okv_decoder_step issues the same launches as the six calls per layer: same bits in x and in the cache
+    say(f"decoder step in one call T={T}")
+    L, H, d, B = 3, 4, 64, 6
+    h1, h2 = H * d, 4 * H * d
+    ctx = [3, 40, 100, 17, 64, 1]
+    results = []
+    for one_call in (False, True):
+        st = build_stack(L=L, H=H, G=H, d=d, T=T, ctx_before=ctx, cap_tokens=128, seed=371)
+        weights = [LayerWeights(h1, h2, 373, l, st.device) for l in range(L)]
+        scratch = LayerScratch(B, h1, h2, H, d, st.device)
+        bound = BoundLayers(st, weights, scratch) if one_call else None
+        xs = []
+        for step in range(3):
+            x = synth.randn_f16_torch((B, h1), synth.stream_seed(375, 1, 0, step), st.device)
+            if one_call:
+                bound.step(x)
+            else:
+                decode_step_with_layers(st, weights, scratch, x)
+            st.synchronize()
+            xs.append(x.cpu().numpy().view(np.uint16).copy())
+        results.append((xs, [st.read_pool(l).view(np.uint16).copy() for l in range(L)], st.ctx_lens.copy()))
+        st.close()
+    for a, b in zip(results[0][0], results[1][0]):
+        np.testing.assert_array_equal(a, b)
+    for a, b in zip(results[0][1], results[1][1]):
+        np.testing.assert_array_equal(a, b)
+    np.testing.assert_array_equal(results[0][2], results[1][2])
+
+
+def test_decoder_step_rejects_what_it_cannot_run():
+    say("decoder step errors")
+    L, H, d, B = 2, 4, 64, 2
+    h1, h2 = H * d, 4 * H * d
+    st = build_stack(L=L, H=H, G=H, d=d, T=0, ctx_before=[5, 9], cap_tokens=64, seed=381)
+    weights = [LayerWeights(h1, h2, 383, l, st.device) for l in range(L)]
+    scratch = LayerScratch(B, h1, h2, H, d, st.device)
+    bound = BoundLayers(st, weights, scratch)
+    x = synth.randn_f16_torch((B, h1), synth.stream_seed(385, 1), st.device)
+    with pytest.raises(binding.OkvError):                     # scratch too small
+        st.ctx.okv_decoder_step(bound.layers, h2, x, bound.scratch, bound.scratch_bytes - 256, scratch.ws, scratch.ws_bytes)
+    short = binding.Context.decoder_layers([{}])               # one layer of NULL pointers for a two-layer context
+    with pytest.raises(binding.OkvError):
+        st.ctx.okv_decoder_step(short, h2, x, bound.scratch, bound.scratch_bytes, scratch.ws, scratch.ws_bytes)
+    bound.step(x)                                              # and the context is still usable afterwards
+    st.synchronize()
+    assert torch.isfinite(x.float()).all()
+    st.close()
+    # grouped heads: the stacked projection has no place for narrower keys and values
+    st = build_stack(L=1, H=4, G=2, d=64, T=0, ctx_before=[5, 9], cap_tokens=64, seed=387)
+    with pytest.raises(binding.OkvError):
+        st.ctx.okv_decoder_step(binding.Context.decoder_layers([{}]), h2, x, bound.scratch, bound.scratch_bytes, scratch.ws, scratch.ws_bytes)
     st.close()
