@@ -64,6 +64,17 @@ int okv_linear(const void *x, const void *w_packed, const void *bias, const void
                void *const *out, int32_t n_seg, int32_t m, int32_t n_out, int32_t n_in,
                int32_t relu, void *workspace, int64_t workspace_bytes, void *stream);
 
+/* The stacked query / key / value projection of a layer with grouped heads: okv_linear with
+ * three output tensors of which the first is q_cols wide and the other two kv_cols
+ * (W is [q_cols + 2 kv_cols][n_in] before packing, rows in the order q, k, v; no ReLU, no
+ * residual).  With q_cols = kv_cols this is okv_linear with n_seg = 3.
+ *   q  fp16 [m][q_cols];  k, v  fp16 [m][kv_cols]   (the shapes kv_append / decode_attn take:
+ *      q_cols = n_q_heads * head_dim, kv_cols = n_kv_heads * head_dim)
+ * Workspace as for okv_linear(m, q_cols + 2 kv_cols, n_in). */
+int okv_linear_qkv(const void *x, const void *w_packed, const void *bias, void *q, void *k, void *v,
+                   int32_t m, int32_t q_cols, int32_t kv_cols, int32_t n_in, void *workspace,
+                   int64_t workspace_bytes, void *stream);
+
 /* okv_linear (one output tensor) followed by okv_layernorm of its result:
  *   out      = act(x * W^T + bias) + residual          fp16 [m][n_out]
  *   out_norm = LayerNorm(out) with gamma, beta, eps    fp16 [m][n_out], a buffer other than out
@@ -92,11 +103,11 @@ int okv_layernorm(const void *x, const void *gamma, const void *beta, void *out,
 
 /* One decoder layer's parameters for okv_decoder_step: matrices as okv_pack_linear_weight leaves
  * them, biases and layer-norm vectors fp16.  w_qkv stacks the query, key and value projections
- * ([3 h1][h1] before packing, h1 = n_q_heads * head_dim; needs n_kv_heads = n_q_heads), w_o is
+ * ([h1 + 2 kv][h1] before packing, h1 = n_q_heads * head_dim, kv = n_kv_heads * head_dim), w_o is
  * [h1][h1], w_ff1 [h2][h1], w_ff2 [h1][h2]. */
 typedef struct {
   const void *ln1_gamma, *ln1_beta;   /* [h1]: the norm before the attention           */
-  const void *w_qkv, *b_qkv;          /* [3 h1 x h1] packed, [3 h1]                     */
+  const void *w_qkv, *b_qkv;          /* [(h1 + 2 kv) x h1] packed, [h1 + 2 kv]         */
   const void *w_o, *b_o;              /* [h1 x h1] packed, [h1]                         */
   const void *ln2_gamma, *ln2_beta;   /* [h1]: the norm before the feed-forward block   */
   const void *w_ff1, *b_ff1;          /* [h2 x h1] packed, [h2]                         */
@@ -121,8 +132,7 @@ int64_t okv_decoder_scratch_bytes(const struct okv_ctx *ctx, int32_t m, int32_t 
  *   scratch    >= okv_decoder_scratch_bytes(ctx, B, h2) bytes, 256-byte aligned
  *   workspace  >= the largest okv_linear_workspace_bytes of the four products
  *   eps        of both layer norms
- * Errors as the calls it stands for; OKV_EINVAL also when n_kv_heads != n_q_heads or the context's
- * out_dtype is not fp16. */
+ * Errors as the calls it stands for; OKV_EINVAL also when the context's out_dtype is not fp16. */
 int okv_decoder_step(struct okv_ctx *ctx, const okv_decoder_layer *layers, int32_t n_layers, int32_t h2, void *x,
                      float eps, void *scratch, int64_t scratch_bytes, void *workspace, int64_t workspace_bytes);
 

@@ -28,7 +28,7 @@ EXPORTS = [
 
 
 # every symbol include/okv_layer.h declares (same library)
-LAYER_EXPORTS = ["okv_pack_linear_weight", "okv_linear", "okv_linear_layernorm", "okv_linear_workspace_bytes", "okv_layernorm",
+LAYER_EXPORTS = ["okv_pack_linear_weight", "okv_linear", "okv_linear_qkv", "okv_linear_layernorm", "okv_linear_workspace_bytes", "okv_layernorm",
                  "okv_decoder_scratch_bytes", "okv_decoder_step"]
 
 
@@ -110,6 +110,7 @@ def lib():
             "okv_pack_linear_weight": (ctypes.c_int, [P, P, I32, I32, P]),
             "okv_linear": (ctypes.c_int, [P, P, P, P, ctypes.POINTER(P), I32, I32, I32, I32, I32, P, I64, P]),
             "okv_linear_workspace_bytes": (I64, [I32, I32, I32]),
+            "okv_linear_qkv": (ctypes.c_int, [P, P, P, P, P, P, I32, I32, I32, I32, P, I64, P]),
             "okv_linear_layernorm": (ctypes.c_int, [P, P, P, P, P, P, P, ctypes.c_float, P, I32, I32, I32, I32, P, I64, P]),
             "okv_layernorm": (ctypes.c_int, [P, P, P, P, I32, I32, ctypes.c_float, P]),
             "okv_decoder_scratch_bytes": (I64, [P, I32, I32]),
@@ -251,6 +252,11 @@ def okv_linear(x, w_packed, bias, residual, out, m, n_out, n_in, relu=False, str
     arr = (ctypes.c_void_p * len(outs))(*[_ptr(o) for o in outs])
     _check(lib().okv_linear(_ptr(x), _ptr(w_packed), _ptr(bias), _ptr(residual), arr, len(outs), m, n_out, n_in,
                             1 if relu else 0, _ptr(workspace), workspace_bytes, _ptr(stream)))
+
+
+def okv_linear_qkv(x, w_packed, bias, q, k, v, m, q_cols, kv_cols, n_in, stream=0, workspace=None, workspace_bytes=0):
+    _check(lib().okv_linear_qkv(_ptr(x), _ptr(w_packed), _ptr(bias), _ptr(q), _ptr(k), _ptr(v), m, q_cols, kv_cols, n_in,
+                                _ptr(workspace), workspace_bytes, _ptr(stream)))
 
 
 def okv_linear_layernorm(x, w_packed, bias, residual, out, gamma, beta, out_norm, m, n_out, n_in, eps=1e-5, relu=False,

@@ -1429,13 +1429,16 @@ int64_t okv_linear_workspace_bytes(int32_t m, int32_t n_out, int32_t n_in) {
 namespace {
 int linear_impl(const void *x, const void *w_packed, const void *bias, const void *residual, void *const *out, int32_t n_seg,
                 int32_t m, int32_t n_out, int32_t n_in, int32_t relu, void *workspace, int64_t workspace_bytes,
-                const void *ln_gamma, const void *ln_beta, void *ln_out, float ln_eps, void *stream) {
+                const void *ln_gamma, const void *ln_beta, void *ln_out, float ln_eps, void *stream, int32_t first_cols = 0) {
   if (!x || !w_packed || !out || !aligned16(x) || !aligned16(w_packed)) return fail(nullptr, OKV_EINVAL, "okv_linear: NULL or misaligned pointer");
   if (m < 1 || m > OKV_LINEAR_MAX_ROWS) return fail(nullptr, OKV_EINVAL, "okv_linear: m = %d outside [1, %d]", m, OKV_LINEAR_MAX_ROWS);
   if (n_out < 16 || n_out % 16 || n_in < 32 || n_in % 32 || n_in > (1 << 20))
     return fail(nullptr, OKV_EINVAL, "okv_linear: n_out must be a multiple of 16 and n_in of 32");
-  if (n_seg < 1 || n_seg > 3 || n_out % (16 * n_seg)) return fail(nullptr, OKV_EINVAL, "okv_linear: n_seg must be 1..3 and divide n_out / 16");
+  if (n_seg < 1 || n_seg > 3 || (!first_cols && n_out % (16 * n_seg)))
+    return fail(nullptr, OKV_EINVAL, "okv_linear: n_seg must be 1..3 and divide n_out / 16");
   if (residual && n_seg != 1) return fail(nullptr, OKV_EINVAL, "okv_linear: a residual needs n_seg = 1");
+  if (first_cols && (n_seg < 2 || first_cols < 16 || first_cols % 16 || first_cols >= n_out || (n_out - first_cols) % (16 * (n_seg - 1))))
+    return fail(nullptr, OKV_EINVAL, "okv_linear: widths of the output tensors must be multiples of 16 that add up to n_out");
   if (!aligned16(bias) || !aligned16(residual)) return fail(nullptr, OKV_EINVAL, "okv_linear: bias / residual misaligned");
   if (relu != 0 && relu != 1) return fail(nullptr, OKV_EINVAL, "okv_linear: relu must be 0 or 1");
   okv::LinearLaunch l;
@@ -1445,6 +1448,7 @@ int linear_impl(const void *x, const void *w_packed, const void *bias, const voi
     if (s < n_seg && (!out[s] || !aligned16(out[s]))) return fail(nullptr, OKV_EINVAL, "okv_linear: out[%d] is NULL or misaligned", s);
   }
   l.n_seg = n_seg, l.m = m, l.n_out = n_out, l.n_in = n_in, l.relu = relu;
+  l.first_cols = first_cols;
   if (workspace && (!aligned16(workspace) || workspace_bytes < 0)) return fail(nullptr, OKV_EINVAL, "okv_linear: workspace misaligned");
   l.workspace = workspace;
   l.workspace_bytes = workspace_bytes;
@@ -1459,6 +1463,14 @@ int okv_linear(const void *x, const void *w_packed, const void *bias, const void
                int32_t m, int32_t n_out, int32_t n_in, int32_t relu, void *workspace, int64_t workspace_bytes, void *stream) {
   return linear_impl(x, w_packed, bias, residual, out, n_seg, m, n_out, n_in, relu, workspace, workspace_bytes, nullptr, nullptr,
                      nullptr, 0.f, stream);
+}
+
+int okv_linear_qkv(const void *x, const void *w_packed, const void *bias, void *q, void *k, void *v, int32_t m, int32_t q_cols,
+                   int32_t kv_cols, int32_t n_in, void *workspace, int64_t workspace_bytes, void *stream) {
+  if (q_cols < 16 || kv_cols < 16 || q_cols % 16 || kv_cols % 16) return fail(nullptr, OKV_EINVAL, "okv_linear_qkv: widths must be multiples of 16");
+  void *outs[3] = {q, k, v};
+  return linear_impl(x, w_packed, bias, nullptr, outs, 3, m, q_cols + 2 * kv_cols, n_in, 0, workspace, workspace_bytes, nullptr, nullptr,
+                     nullptr, 0.f, stream, q_cols == kv_cols ? 0 : q_cols);
 }
 
 int okv_linear_layernorm(const void *x, const void *w_packed, const void *bias, const void *residual, void *out, const void *gamma,
@@ -1487,7 +1499,7 @@ struct DecoderScratch {
   char *a, *q, *k, *v, *t, *y, *z, *u;
   int64_t bytes;
 };
-DecoderScratch decoder_scratch(void *base, int32_t m, int32_t h1, int32_t h2) {
+DecoderScratch decoder_scratch(void *base, int32_t m, int32_t h1, int32_t kvw, int32_t h2) {
   DecoderScratch d;
   int64_t at = 0;
   auto take = [&](int64_t cols) {
@@ -1495,7 +1507,7 @@ DecoderScratch decoder_scratch(void *base, int32_t m, int32_t h1, int32_t h2) {
     at += ((int64_t)m * cols * 2 + 255) / 256 * 256;
     return p;
   };
-  d.a = take(h1), d.q = take(h1), d.k = take(h1), d.v = take(h1), d.t = take(h1), d.y = take(h1), d.z = take(h1), d.u = take(h2);
+  d.a = take(h1), d.q = take(h1), d.k = take(kvw), d.v = take(kvw), d.t = take(h1), d.y = take(h1), d.z = take(h1), d.u = take(h2);
   d.bytes = at;
   return d;
 }
@@ -1504,7 +1516,7 @@ DecoderScratch decoder_scratch(void *base, int32_t m, int32_t h1, int32_t h2) {
 int64_t okv_decoder_scratch_bytes(const okv_ctx *ctx, int32_t m, int32_t h2) {
   if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
   if (m < 1 || m > OKV_LINEAR_MAX_ROWS || h2 < 32 || h2 % 32) return fail(nullptr, OKV_EINVAL, "okv_decoder_scratch_bytes: bad shape");
-  return decoder_scratch(nullptr, m, ctx->cfg.n_q_heads * ctx->cfg.head_dim, h2).bytes;
+  return decoder_scratch(nullptr, m, ctx->cfg.n_q_heads * ctx->cfg.head_dim, ctx->cfg.n_kv_heads * ctx->cfg.head_dim, h2).bytes;
 }
 
 int okv_decoder_step(okv_ctx *ctx, const okv_decoder_layer *layers, int32_t n_layers, int32_t h2, void *x, float eps,
@@ -1512,15 +1524,13 @@ int okv_decoder_step(okv_ctx *ctx, const okv_decoder_layer *layers, int32_t n_la
   if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
   if (!layers || !x || !scratch) return fail(ctx, OKV_EINVAL, "okv_decoder_step: NULL pointer");
   if (n_layers != ctx->cfg.n_layers) return fail(ctx, OKV_EINVAL, "okv_decoder_step: %d layers, the context has %d", n_layers, ctx->cfg.n_layers);
-  if (ctx->cfg.n_kv_heads != ctx->cfg.n_q_heads)
-    return fail(ctx, OKV_EINVAL, "okv_decoder_step: the stacked q/k/v projection needs as many KV heads as query heads");
   if (ctx->cfg.out_dtype != 0) return fail(ctx, OKV_EINVAL, "okv_decoder_step: the attention output must be fp16 (out_dtype 0)");
   if (!ctx->batch_set) return fail(ctx, OKV_ESTATE, "okv_decoder_step before okv_set_batch");
-  const int32_t m = ctx->B, h1 = ctx->cfg.n_q_heads * ctx->cfg.head_dim;
+  const int32_t m = ctx->B, h1 = ctx->cfg.n_q_heads * ctx->cfg.head_dim, kvw = ctx->cfg.n_kv_heads * ctx->cfg.head_dim;
   if (m < 1 || m > OKV_LINEAR_MAX_ROWS) return fail(ctx, OKV_EINVAL, "okv_decoder_step: batch %d outside [1, %d]", m, OKV_LINEAR_MAX_ROWS);
   if (h2 < 32 || h2 % 32 || h2 > 16384 * 8) return fail(ctx, OKV_EINVAL, "okv_decoder_step: bad feed-forward width %d", h2);
   if (((uintptr_t)scratch & 255) || !aligned16(x)) return fail(ctx, OKV_EINVAL, "okv_decoder_step: scratch or x misaligned");
-  const DecoderScratch d = decoder_scratch(scratch, m, h1, h2);
+  const DecoderScratch d = decoder_scratch(scratch, m, h1, kvw, h2);
   if (scratch_bytes < d.bytes) return fail(ctx, OKV_ENOSPC, "okv_decoder_step: scratch holds %lld bytes, %lld needed", (long long)scratch_bytes, (long long)d.bytes);
   for (int32_t l = 0; l < n_layers; ++l) {
     const okv_decoder_layer &w = layers[l];
@@ -1534,8 +1544,7 @@ int okv_decoder_step(okv_ctx *ctx, const okv_decoder_layer *layers, int32_t n_la
   rc = okv_layernorm(x, layers[0].ln1_gamma, layers[0].ln1_beta, d.a, m, h1, eps, stream);
   for (int32_t l = 0; rc == OKV_OK && l < n_layers; ++l) {
     const okv_decoder_layer &w = layers[l];
-    void *qkv[3] = {d.q, d.k, d.v};
-    rc = okv_linear(d.a, w.w_qkv, w.b_qkv, nullptr, qkv, 3, m, 3 * h1, h1, 0, workspace, workspace_bytes, stream);
+    rc = okv_linear_qkv(d.a, w.w_qkv, w.b_qkv, d.q, d.k, d.v, m, h1, kvw, h1, workspace, workspace_bytes, stream);
     if (rc == OKV_OK) rc = kv_append(ctx, l, d.k, d.v);
     if (rc == OKV_OK) rc = decode_attn(ctx, l, d.q, d.t);
     // output projection + residual, and the second norm of its result on the same share reduction

@@ -102,6 +102,7 @@ struct LinearLaunch {
   const void *x, *w_packed, *bias, *residual;
   void *out[3];
   int32_t n_seg, m, n_out, n_in, relu;
+  int32_t first_cols = 0;      // width of out[0] when it differs from the others' (n_out - first_cols) / (n_seg - 1); 0: all equal
   void *workspace;             // fp32 shares of the cuts of the input dimension, or NULL
   int64_t workspace_bytes;
   const void *ln_gamma, *ln_beta;   // with ln_out: layer norm of the result (n_seg = 1) written there as well

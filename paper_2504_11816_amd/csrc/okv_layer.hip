@@ -74,7 +74,8 @@ struct LinearArgs {
   const uint4 *w;          // packed weights
   const _Float16 *bias, *residual;
   _Float16 *out[3];
-  int32_t m, n_in, n_kb, seg_cols, relu;
+  int32_t m, n_in, n_kb, relu;
+  int32_t seg0_cols, seg_cols;      // width of the first output tensor, of the others (multiples of 16)
   int32_t n_tiles, n_out, splits;   // fast path: 16-feature tiles, cuts of the input dimension
   float *shares;                    // fast path, splits > 1 or a layer norm to follow: [splits][m][n_out] fp32
   int32_t to_shares;                // fast path: write the share even when there is a single cut
@@ -82,6 +83,18 @@ struct LinearArgs {
   _Float16 *ln_out;                 // layer norm of the result, or NULL
   float ln_eps;
 };
+
+// Feature n of row mrow lands in output tensor `seg` at element `at` (the tensors are [m][their width]).
+__device__ __forceinline__ void seg_of(const LinearArgs &a, int mrow, int n, int &seg, size_t &at) {
+  if (n < a.seg0_cols) {
+    seg = 0;
+    at = (size_t)mrow * a.seg0_cols + n;
+  } else {
+    const int r = n - a.seg0_cols;
+    seg = 1 + r / a.seg_cols;
+    at = (size_t)mrow * a.seg_cols + (r - (seg - 1) * a.seg_cols);
+  }
+}
 
 __device__ __forceinline__ floatx4 mfma16(const uint2 a, const uint2 b, floatx4 c) {
   return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(half4, a), __builtin_bit_cast(half4, b), c, 0, 0, 0);
@@ -186,8 +199,9 @@ __global__ __launch_bounds__(kLinWaves * 64) void linear_kernel(const LinearArgs
     const int n = ntile * 16 + j;
     if (a.bias) v += (float)a.bias[n];
     if (a.relu) v = fmaxf(v, 0.f);
-    const int seg = n / a.seg_cols, col = n - seg * a.seg_cols;
-    const size_t at = (size_t)mrow * a.seg_cols + col;
+    int seg;
+    size_t at;
+    seg_of(a, mrow, n, seg, at);
     if (a.residual) v += (float)a.residual[at];
     a.out[seg][at] = (_Float16)v;
   }
@@ -390,8 +404,9 @@ __global__ __launch_bounds__((NW + lin_stagers(MF)) * 64) __attribute__((amdgpu_
     const float4 *t = reinterpret_cast<const float4 *>(tile + mrow * kTileCols + 8 * (o % VPR));
     const float4 t0 = t[0], t1 = t[1];
     float v[8] = {t0.x, t0.y, t0.z, t0.w, t1.x, t1.y, t1.z, t1.w};
-    const int seg = n / a.seg_cols, col = n - seg * a.seg_cols;
-    const size_t at = (size_t)mrow * a.seg_cols + col;
+    int seg;
+    size_t at;
+    seg_of(a, mrow, n, seg, at);
     uint4 bb = make_uint4(0u, 0u, 0u, 0u), rb = bb;
     if (a.bias) bb = *reinterpret_cast<const uint4 *>(a.bias + n);
     if (a.residual) rb = *reinterpret_cast<const uint4 *>(a.residual + at);
@@ -433,8 +448,9 @@ __global__ __launch_bounds__(256) void reduce_epilogue_kernel(const LinearArgs a
       v.x += w * part[j].x, v.y += w * part[j].y, v.z += w * part[j].z, v.w += w * part[j].w;
     }
   }
-  const int seg = n / a.seg_cols, col = n - seg * a.seg_cols;         // a segment is a multiple of 16 features wide
-  const size_t at = (size_t)mrow * a.seg_cols + col;
+  int seg;                                                             // a segment is a multiple of 16 features wide
+  size_t at;
+  seg_of(a, mrow, n, seg, at);
   float y[4] = {v.x, v.y, v.z, v.w};
   if (a.bias) {
     const uint2 b = *reinterpret_cast<const uint2 *>(a.bias + n);
@@ -687,7 +703,8 @@ hipError_t launch_linear(const LinearLaunch &l, hipStream_t stream) {
   a.m = l.m;
   a.n_in = l.n_in;
   a.n_kb = l.n_in / 32;
-  a.seg_cols = l.n_out / l.n_seg;
+  a.seg0_cols = l.first_cols ? l.first_cols : l.n_out / l.n_seg;
+  a.seg_cols = l.n_seg > 1 ? (l.n_out - a.seg0_cols) / (l.n_seg - 1) : l.n_out;
   a.relu = l.relu;
   const int n_tiles = l.n_out / 16;
   a.n_tiles = n_tiles;

@@ -256,23 +256,25 @@ class Stack:
 class LayerWeights:
     """The matrices and vectors of one decoder layer (fp16 on the device), row-major as a
     framework holds them, plus the rearranged copies okv_linear reads.  The query, key and
-    value projections are stacked into one [3 h1][h1] matrix so that one product serves all
-    three."""
+    value projections are stacked into one [h1 + 2 kv_cols][h1] matrix so that one product serves
+    all three."""
 
     NAMES = ("ln1_g", "ln1_b", "wq", "bq", "wk", "bk", "wv", "bv", "wo", "bo", "ln2_g", "ln2_b", "w1", "b1", "w2", "b2")
 
-    def __init__(self, h1, h2, seed, layer, device):
+    def __init__(self, h1, h2, seed, layer, device, kv_cols=None):
+        """kv_cols: width of the key and value projections (n_kv_heads * head_dim); h1 when the heads are not grouped."""
         self.h1, self.h2 = h1, h2
+        self.kv_cols = kv = h1 if kv_cols is None else kv_cols
         t = {}
         for i, name in enumerate(self.NAMES):
             sd = synth.stream_seed(seed, 100 + i, layer)
             if name.startswith("w"):
-                n_out, n_in = (h2, h1) if name == "w1" else (h1, h2) if name == "w2" else (h1, h1)
+                n_out, n_in = (h2, h1) if name == "w1" else (h1, h2) if name == "w2" else (kv, h1) if name in ("wk", "wv") else (h1, h1)
                 t[name] = (synth.randn_f16_torch((n_out, n_in), sd, device).float() / n_in ** 0.5).to(torch.float16)
             elif name.endswith("_g"):
                 t[name] = (1.0 + 0.1 * synth.randn_f16_torch((h1,), sd, device).float()).to(torch.float16)
             else:
-                n = h2 if name == "b1" else h1
+                n = h2 if name == "b1" else kv if name in ("bk", "bv") else h1
                 t[name] = (0.1 * synth.randn_f16_torch((n,), sd, device).float()).to(torch.float16)
         self.t = t
         self.wqkv = torch.cat([t["wq"], t["wk"], t["wv"]], dim=0).contiguous()
@@ -302,7 +304,7 @@ class LayerScratch:
         self.t, self.y, self.z, self.u = buf(B, h1), buf(B, h1), buf(B, h1), buf(B, h2)
         # one workspace for the four products of a layer (they follow one another on one stream)
         self.ws_bytes = max(16, max(binding.okv_linear_workspace_bytes(B, n_out, n_in)
-                                    for n_out, n_in in ((3 * h1, h1), (h1, h1), (h2, h1), (h1, h2))))
+                                    for n_out, n_in in ((h1 + 2 * G * d, h1), (h1, h1), (h2, h1), (h1, h2))))
         self.ws = torch.empty(self.ws_bytes, dtype=torch.uint8, device=device)
 
 
@@ -338,7 +340,7 @@ def decode_step_with_layers(st, weights, scratch, x):
     c.okv_step_begin()
     binding.okv_layernorm(x, weights[0].t["ln1_g"], weights[0].t["ln1_b"], s.a, B, h1, 1e-5, cs)
     for l, w in enumerate(weights):
-        binding.okv_linear(s.a, w.packed["wqkv"], w.bqkv, None, [s.q, s.k, s.v], B, 3 * h1, h1, False, cs, s.ws, s.ws_bytes)
+        binding.okv_linear_qkv(s.a, w.packed["wqkv"], w.bqkv, s.q, s.k, s.v, B, h1, w.kv_cols, h1, cs, s.ws, s.ws_bytes)
         c.kv_append(l, s.k, s.v)
         c.decode_attn(l, s.q, s.t)
         # output projection + residual, and the second norm of its result in the same pass

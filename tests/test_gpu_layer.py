@@ -221,15 +221,15 @@ def test_layernorm(m, h):
     assert torch.equal(x, out)
 
 
-@pytest.mark.parametrize("T,on_host", [(0, None), (16, [0, 1])])
-def test_whole_decoder_layers_against_the_oracle(T, on_host):
-    say(f"decoder layers T={T} on_host={on_host}")
+@pytest.mark.parametrize("T,on_host,G", [(0, None, 4), (16, [0, 1], 4), (16, None, 2), (0, None, 1)])
+def test_whole_decoder_layers_against_the_oracle(T, on_host, G):
+    say(f"decoder layers T={T} on_host={on_host} G={G}")
     L, H, d, B = 2, 4, 64, 5
     h1, h2 = H * d, 4 * H * d
     ctx = [3, 40, 100, 17, 64]
-    st = build_stack(L=L, H=H, G=H, d=d, T=T, ctx_before=ctx, cap_tokens=128, on_host=on_host, seed=361)
-    weights = [LayerWeights(h1, h2, 363, l, st.device) for l in range(L)]
-    scratch = LayerScratch(B, h1, h2, H, d, st.device)
+    st = build_stack(L=L, H=H, G=G, d=d, T=T, ctx_before=ctx, cap_tokens=128, on_host=on_host, seed=361)
+    weights = [LayerWeights(h1, h2, 363, l, st.device, kv_cols=G * d) for l in range(L)]
+    scratch = LayerScratch(B, h1, h2, G, d, st.device)
     layout = st.layout()
     pools = [st.read_pool(l).copy() for l in range(L)]
     n = np.array(ctx, dtype=np.int32)
@@ -242,7 +242,7 @@ def test_whole_decoder_layers_against_the_oracle(T, on_host):
         for l in range(L):
             p = weights[l].numpy()
             q, k, v = dl.qkv(x_ref, p, fp16_between=True)
-            kv_layout.append_scatter(pools[l], layout, n, k.astype(np.float16).reshape(B, H, d), v.astype(np.float16).reshape(B, H, d))
+            kv_layout.append_scatter(pools[l], layout, n, k.astype(np.float16).reshape(B, G, d), v.astype(np.float16).reshape(B, G, d))
             t = oa.decode_attn(q.reshape(B, H, d), pools[l], layout, n, H)
             t = dl.round16(np.asarray(t).reshape(B, h1))
             x_ref = dl.after_attention(x_ref, t, p, fp16_between=True)
@@ -254,18 +254,18 @@ def test_whole_decoder_layers_against_the_oracle(T, on_host):
     st.close()
 
 
-@pytest.mark.parametrize("T", [0, 16])
-def test_decoder_step_in_one_call_equals_the_calls_one_by_one(T):
+@pytest.mark.parametrize("T,G", [(0, 4), (16, 4), (16, 2)])
+def test_decoder_step_in_one_call_equals_the_calls_one_by_one(T, G):
     # okv_decoder_step issues the same launches as the six calls per layer: same bits in x and in the cache
-    say(f"decoder step in one call T={T}")
+    say(f"decoder step in one call T={T} G={G}")
     L, H, d, B = 3, 4, 64, 6
     h1, h2 = H * d, 4 * H * d
     ctx = [3, 40, 100, 17, 64, 1]
     results = []
     for one_call in (False, True):
-        st = build_stack(L=L, H=H, G=H, d=d, T=T, ctx_before=ctx, cap_tokens=128, seed=371)
-        weights = [LayerWeights(h1, h2, 373, l, st.device) for l in range(L)]
-        scratch = LayerScratch(B, h1, h2, H, d, st.device)
+        st = build_stack(L=L, H=H, G=G, d=d, T=T, ctx_before=ctx, cap_tokens=128, seed=371)
+        weights = [LayerWeights(h1, h2, 373, l, st.device, kv_cols=G * d) for l in range(L)]
+        scratch = LayerScratch(B, h1, h2, G, d, st.device)
         bound = BoundLayers(st, weights, scratch) if one_call else None
         xs = []
         for step in range(3):
@@ -303,8 +303,32 @@ def test_decoder_step_rejects_what_it_cannot_run():
     st.synchronize()
     assert torch.isfinite(x.float()).all()
     st.close()
-    # grouped heads: the stacked projection has no place for narrower keys and values
-    st = build_stack(L=1, H=4, G=2, d=64, T=0, ctx_before=[5, 9], cap_tokens=64, seed=387)
+    # a context that writes fp32 attention outputs cannot feed the output projection
+    st = build_stack(L=1, H=4, G=4, d=64, T=0, ctx_before=[5, 9], cap_tokens=64, seed=387, out_dtype=1)
     with pytest.raises(binding.OkvError):
-        st.ctx.okv_decoder_step(binding.Context.decoder_layers([{}]), h2, x, bound.scratch, bound.scratch_bytes, scratch.ws, scratch.ws_bytes)
+        BoundLayers(st, weights[:1], scratch).step(x)
     st.close()
+
+
+def test_linear_qkv_widths():
+    # the stacked projection with narrower keys and values, against three separate products
+    say("linear qkv")
+    m, h1, kv, n_in = 24, 512, 128, 512
+    x = synth.randn_f16_torch((m, n_in), synth.stream_seed(391, 1), DEV)
+    w = (synth.randn_f16_torch((h1 + 2 * kv, n_in), synth.stream_seed(391, 2), DEV).float() / n_in ** 0.5).to(torch.float16)
+    b = synth.randn_f16_torch((h1 + 2 * kv,), synth.stream_seed(391, 3), DEV)
+    wp = torch.empty_like(w)
+    binding.okv_pack_linear_weight(wp, w, h1 + 2 * kv, n_in)
+    q = torch.full((m, h1), float("nan"), dtype=torch.float16, device=DEV)
+    k = torch.full((m, kv), float("nan"), dtype=torch.float16, device=DEV)
+    v = torch.full((m, kv), float("nan"), dtype=torch.float16, device=DEV)
+    for mm in (m, 5):                                          # the staged kernel and the one for few rows
+        ws = workspace(binding.okv_linear_workspace_bytes(mm, h1 + 2 * kv, n_in))
+        binding.okv_linear_qkv(x, wp, b, q, k, v, mm, h1, kv, n_in, 0, ws, ws.numel())
+        torch.cuda.synchronize()
+        want = dl.linear(x[:mm].double().cpu().numpy(), w.double().cpu().numpy(), b.double().cpu().numpy())
+        close(q[:mm].float().cpu().numpy(), want[:, :h1], what="q")
+        close(k[:mm].float().cpu().numpy(), want[:, h1:h1 + kv], what="k")
+        close(v[:mm].float().cpu().numpy(), want[:, h1 + kv:], what="v")
+    with pytest.raises(binding.OkvError):
+        binding.okv_linear_qkv(x, wp, b, q, k, v, m, h1, 24, n_in)          # widths are multiples of 16
