@@ -469,17 +469,24 @@ def run_layers(args):
     import torch
     from paper_2504_11816_amd import binding, synth
     from paper_2504_11816_amd.harness import BoundLayers, LayerScratch, LayerWeights, Stack
-    w = dict(synth.WORKLOADS["cfg2"])
-    L, H, G, d, B = w["L"], w["H"], w["G"], w["d"], w["B"]
+    w = dict(synth.WORKLOADS[args.decoder_workload])
+    L, H, G, d, B, T = w["L"], w["H"], w["G"], w["d"], w["B"], w["T"]
     if args.layers:
         L = min(L, args.layers)
     h1, h2 = H * d, 4 * H * d
     steps, warmup = args.layer_steps, 4
-    ctx0 = np.full(B, w["ctx"] - 1, dtype=np.int32)
-    st = Stack(L=L, H=H, G=G, d=d, B=B, T=0, cap_tokens=int(ctx0.max()) + steps + warmup + 1, out_dtype=0)
+    if w["ragged"]:
+        ctx0 = synth.ragged_ctx_lens(B, w["ragged"][0], w["ragged"][1], args.seed) - 1
+    else:
+        ctx0 = np.full(B, w["ctx"] - 1, dtype=np.int32)
+    st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=int(ctx0.max()) + steps + warmup + 1, out_dtype=0)
     for l in range(L):
         st.fill_pool(l, synth.stream_seed(args.seed, synth.TENSOR_POOL, l))
-    weights = [LayerWeights(h1, h2, args.seed, l, st.device) for l in range(L)]
+    table = None
+    if T:
+        table = synth.shuffled_block_table([st.cap_tokens] * B, T, st.blocks_per_layer, args.seed + 1,
+                                           max_blocks_per_seq=st.max_blocks)
+    weights = [LayerWeights(h1, h2, args.seed, l, st.device, kv_cols=G * d) for l in range(L)]
     scratch = LayerScratch(B, h1, h2, G, d, st.device)
     x0 = synth.randn_f16_torch((B, h1), synth.stream_seed(args.seed, synth.TENSOR_Q), st.device)
     x = x0.clone()
@@ -490,11 +497,11 @@ def run_layers(args):
         for _ in range(n):
             x.copy_(x0)                    # keep the activations at the scale of the inputs (random weights amplify)
             bound.step(x)
-    st.set_batch(ctx0, None)
+    st.set_batch(ctx0, table)
     with torch.cuda.stream(st.compute_stream):
         run(warmup)
         st.synchronize()
-        st.set_batch(ctx0, None)
+        st.set_batch(ctx0, table)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         run(steps)
@@ -508,7 +515,7 @@ def run_layers(args):
     cs = st.compute_stream
     alone = {}
     for name, fn, nbytes in (
-            ("qkv 12288x4096", lambda wt: binding.okv_linear(scratch.a, wt.packed["wqkv"], wt.bqkv, None, [scratch.q, scratch.k, scratch.v], B, 3 * h1, h1, False, cs.cuda_stream, scratch.ws, scratch.ws_bytes), 3 * h1 * h1 * 2),
+            (f"qkv {h1 + 2 * G * d}x{h1}", lambda wt: binding.okv_linear_qkv(scratch.a, wt.packed["wqkv"], wt.bqkv, scratch.q, scratch.k, scratch.v, B, h1, G * d, h1, cs.cuda_stream, scratch.ws, scratch.ws_bytes), (h1 + 2 * G * d) * h1 * 2),
             ("out 4096x4096", lambda wt: binding.okv_linear(scratch.t, wt.packed["wo"], wt.t["bo"], scratch.z, scratch.y, B, h1, h1, False, cs.cuda_stream, scratch.ws, scratch.ws_bytes), h1 * h1 * 2),
             ("ffn1 16384x4096", lambda wt: binding.okv_linear(scratch.z, wt.packed["w1"], wt.t["b1"], None, scratch.u, B, h2, h1, True, cs.cuda_stream, scratch.ws, scratch.ws_bytes), h1 * h2 * 2),
             ("ffn2 4096x16384", lambda wt: binding.okv_linear(scratch.u, wt.packed["w2"], wt.t["b2"], scratch.z, scratch.y, B, h1, h2, False, cs.cuda_stream, scratch.ws, scratch.ws_bytes), h1 * h2 * 2)):
@@ -525,7 +532,9 @@ def run_layers(args):
         us = e0.elapsed_time(e1) / (2 * len(weights)) * 1e3
         alone[name] = {"us": us, "weight_gbps": nbytes / us / 1e3}
     res = {
-        "workload": f"{L} decoder layers, hidden {h1}, feed-forward {h2}, batch {B}, context {w['ctx']}..{w['ctx'] + steps - 1}, random weights",
+        "workload": f"{L} decoder layers ({args.decoder_workload} shape: {H} query / {G} KV heads x {d}), hidden {h1}, feed-forward {h2}, batch {B}, "
+                    + (f"context {w['ctx']}..{w['ctx'] + steps - 1}" if not w["ragged"] else
+                       f"ragged contexts {int(ctx0.min()) + 1}..{int(ctx0.max()) + 1} (+1 per step)") + ", random weights",
         "steps": steps, "tokens_per_s": B * steps / dt, "ms_per_step": dt / steps * 1e3,
         "weight_gb_per_step": w_bytes / steps / 1e9, "kv_gb_per_step": kv_bytes / steps / 1e9,
         "hbm_gbps": (w_bytes + kv_bytes) / dt / 1e9, "hbm_frac": (w_bytes + kv_bytes) / dt / 1e9 / HBM_PEAK_GBPS,
@@ -632,6 +641,8 @@ def main():
     ap.add_argument("--no-model", action="store_true", help="skip the prediction-model leg")
     ap.add_argument("--no-decoder", action="store_true", help="skip the whole-decoder-layer leg")
     ap.add_argument("--layer-steps", type=int, default=32, help="decoder-layer leg: decode steps to time")
+    ap.add_argument("--decoder-workload", default="cfg2", choices=["cfg2", "cfg3_resident", "cfg4", "gqa8"],
+                    help="decoder-layer leg: the stack and batch it runs on (all resident)")
     ap.add_argument("--no-prefill", action="store_true", help="skip the prefill-side store leg")
     ap.add_argument("--prefill-table", default="ordered", choices=["ordered", "shuffled"],
                     help="prefill leg: how the block table hands out blocks")

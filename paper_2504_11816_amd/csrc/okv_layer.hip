@@ -657,33 +657,45 @@ hipError_t launch_linear_mf(const LinearArgs &args, int n_tiles, bool fast, int 
 
 }  // namespace
 
-// How many ways the input dimension is cut, with workgroups of `waves` streaming wavefronts: enough workgroups
-// for one per compute unit, as long as every cut keeps at least two chunks, and only cuts that divide the chunks
-// evenly.  0: not a shape for the fast kernel.
-int linear_splits(int32_t m, int32_t n_out, int32_t n_in, int32_t n_cus, int waves) {
-  const int chunk = lin_chunk((m + 15) / 16), pace = lin_weight_lead((m + 15) / 16);
-  if (n_in % (32 * chunk * pace)) return 0;
-  const int chunks = n_in / (32 * chunk);
-  const int groups = (n_out / 16 + waves - 1) / waves;
-  int best = 1;
-  for (int s = 1; s <= chunks; ++s) {
-    if (chunks % (s * pace)) continue;                         // the kernel takes `pace` chunks at a time
-    if (s > 1 && chunks / s < 2) break;
-    best = s;
-    if ((int64_t)groups * s >= OKV_LIN_WG_PER_CU * (int64_t)n_cus) break;
-  }
-  return best;
-}
-
-// Streaming wavefronts per workgroup and cuts: 4 wavefronts; 3 and no cut where 4 would need a cut and 3 fill the
-// compute units (at least nine in ten, none twice) without one.  Cuts 0: not a shape for the fast kernel.
+// Streaming wavefronts per workgroup (4 or 3) and cuts of the input dimension for the fast kernel, by a small
+// model of the launch, in microseconds:
+//   max(weights / 6.0 MB/us, (weights + rows of x fetched) / 10 MB/us) / fill + second kernel
+// -- the weights come from HBM, they and the rows of x (every workgroup fetches the rows of its stretch:
+// m x n_in x 2 bytes per group of 64 or 48 features) come through the L2s, `fill` is the share of
+// workgroup slots in use when the workgroups are dealt to the compute units in rounds, and a cut costs the
+// kernel that adds the shares up (a dependent launch and the shares written and read).  The rates are
+// measured on MI355X (16384 x 4096: 27 us at 32 rows, 41 at 128).  Cuts divide the chunks evenly, leave every
+// cut at least two chunks, and the kernel takes the chunks `pace` at a time.  A launch with more than two
+// workgroups per compute unit is not considered (longer-lived workgroups measured faster than more of them).
+// Examples on 256 compute units: 12288 x 4096 -> 3 wavefronts, no cut (256 workgroups); 6144 x 4096 -> 3
+// wavefronts, 2 cuts; 4096 x 4096 and 4096 x 16384 -> 4 wavefronts, 4 cuts; 16384 x 4096 -> 4, none.
+// Cuts 0: not a shape for the fast kernel.
 void linear_plan(int32_t m, int32_t n_out, int32_t n_in, int32_t n_cus, int *waves, int *cuts) {
   *waves = 4;
-  *cuts = linear_splits(m, n_out, n_in, n_cus, 4);
-  const int groups3 = (n_out / 16 + 2) / 3;
-  if (*cuts > 1 && groups3 <= n_cus && groups3 * 10 >= n_cus * 9) {
-    *waves = 3;
-    *cuts = 1;
+  *cuts = 0;
+  const int chunk = lin_chunk((m + 15) / 16), pace = lin_weight_lead((m + 15) / 16);
+  if (n_in % (32 * chunk * pace)) return;
+  const int chunks = n_in / (32 * chunk);
+  const double weight_mb = (double)n_out * n_in * 2 / 1e6;
+  double best = 0;
+  for (int w : {4, 3}) {
+    const int groups = (n_out / 16 + w - 1) / w;
+    const double x_mb = (double)groups * m * n_in * 2 / 1e6;
+    for (int s = 1; s <= chunks; ++s) {
+      if (chunks % (s * pace)) continue;
+      if (s > 1 && chunks / s < 2) break;
+      const int64_t wgs = (int64_t)groups * s;
+      if (s > 1 && wgs > 2 * (int64_t)n_cus) break;
+      const int64_t rounds = (wgs + n_cus - 1) / n_cus;
+      const double fill = (double)wgs / (double)(rounds * n_cus);
+      double t = std::max(weight_mb / 6.0, (weight_mb + x_mb) / 10.0) / fill;
+      if (s > 1) t += 4.5 + 2.0 * s * m * n_out * 4 / 1e6 / 3.0;
+      if (*cuts == 0 || t < best * 0.98) {                      // on a near tie the first one found: 4 wavefronts, fewer cuts
+        best = t;
+        *waves = w;
+        *cuts = s;
+      }
+    }
   }
 }
 
