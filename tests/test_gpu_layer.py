@@ -332,3 +332,24 @@ def test_linear_qkv_widths():
         close(v[:mm].float().cpu().numpy(), want[:, h1 + kv:], what="v")
     with pytest.raises(binding.OkvError):
         binding.okv_linear_qkv(x, wp, b, q, k, v, m, h1, 24, n_in)          # widths are multiples of 16
+
+
+def test_linear_random_shapes_against_the_oracle():
+    # every row-fragment count (1..8 fragments of 16 rows), both workgroup forms, cuts or none, the kernel for few
+    # rows and for input sizes the staged kernel does not take, with a random epilogue
+    say("linear random shapes")
+    rng = np.random.Generator(np.random.PCG64(20250427))
+    cases = []
+    for m in (9, 16, 17, 32, 33, 48, 49, 64, 65, 80, 81, 96, 97, 112, 113, 128):      # each fragment count at both ends
+        n_in = int(rng.choice([256, 512, 768, 1024, 2048, 2560]))
+        n_out = 16 * int(rng.integers(1, 129))
+        cases.append((m, n_out, n_in))
+    for m in (24, 72, 128):                                   # wide products: three streaming wavefronts per workgroup
+        cases.append((m, 16 * int(rng.integers(700, 769)), 512 * int(rng.integers(2, 5))))
+        cases.append((m, 6144, 1024))
+    for _ in range(8):                                        # anything else
+        cases.append((int(rng.integers(1, 129)), 16 * int(rng.integers(1, 200)), 32 * int(rng.integers(1, 100))))
+    for i, (m, n_out, n_in) in enumerate(cases):
+        say(f"  m={m} {n_out}x{n_in}")
+        run_linear(m, n_out, n_in, 500 + i, bias=bool(rng.integers(0, 2)), relu=bool(rng.integers(0, 2)),
+                   residual=bool(rng.integers(0, 2)))
