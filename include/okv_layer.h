@@ -32,8 +32,8 @@ struct okv_ctx;   /* okv.h */
  *   src  fp16 [n_out][n_in] row-major (the layout of a framework's linear layer:
  *        out = x * src^T)
  *   dst  fp16, n_out * n_in elements: 16 output features x 32 inputs at a time, stored as
- *        the 64 x 16-byte pieces a wavefront loads with one instruction and feeds to two
- *        matrix-core instructions: piece (lane) of block (n / 16, k / 32) holds
+ *        the 64 x 16-byte pieces a wavefront loads with one instruction and feeds to the
+ *        matrix cores: piece (lane) of block (n / 16, k / 32) holds
  *        src[16 * (n / 16) + lane % 16][32 * (k / 32) + 8 * (lane / 16) .. + 7]
  * n_out must be a multiple of 16 and n_in of 32.  dst and src must not overlap. */
 int okv_pack_linear_weight(void *dst, const void *src, int32_t n_out, int32_t n_in, void *stream);
@@ -52,12 +52,13 @@ int okv_pack_linear_weight(void *dst, const void *src, int32_t n_out, int32_t n_
  *   workspace DEVICE scratch memory of at least okv_linear_workspace_bytes(m, n_out, n_in)
  *             bytes (workspace_bytes says how much there is); its contents before and
  *             after the call mean nothing.  Calls that may run at the same time (different
- *             streams) need workspaces of their own.  When n_in is a multiple of 512 the
- *             fast kernel runs: the input dimension is cut across workgroups, their fp32
- *             shares go through the workspace and a second small kernel adds them in a
- *             fixed order (results do not vary from run to run).  With another n_in, or
- *             when a cut is wanted and the workspace is NULL or too small, a simpler,
- *             slower kernel runs that needs no workspace.
+ *             streams) need workspaces of their own.  With more than 8 rows and n_in a
+ *             multiple of 256 the fast kernel runs: where that fills the GPU better the
+ *             input dimension is cut across workgroups, their fp32 shares go through the
+ *             workspace and a second small kernel adds them in a fixed order (results do
+ *             not vary from run to run).  With fewer rows or another n_in, or when a cut
+ *             is wanted and the workspace is NULL or too small, a simpler kernel runs that
+ *             needs no workspace.
  * Products accumulate in fp32 on the matrix cores; the result is rounded to fp16 once.
  * residual may alias out[0] (each element is read before it is written, by the same lane). */
 int okv_linear(const void *x, const void *w_packed, const void *bias, const void *residual,
