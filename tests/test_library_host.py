@@ -54,6 +54,29 @@ def test_layer_header_symbols_are_exported():
         binding.okv_pack_linear_weight(16, 32, 100, 64)         # n_out not a multiple of 16
 
 
+def test_cuts_of_the_product_kernels_follow_the_launch_model():
+    # okv_linear_workspace_bytes = cuts * m * n_out * 4 (0: the kernel for few rows or odd input sizes); without a
+    # GPU the library assumes the 256 compute units of the GPU it is written for
+    def cuts(m, n_out, n_in):
+        nbytes = binding.okv_linear_workspace_bytes(m, n_out, n_in)
+        assert nbytes % (m * n_out * 4) == 0
+        return nbytes // (m * n_out * 4)
+    assert cuts(32, 12288, 4096) == 1          # 256 workgroups of three 16-feature tiles: no second kernel
+    assert cuts(32, 16384, 4096) == 1          # 256 workgroups of four
+    assert cuts(32, 4096, 4096) == 4           # 64 groups of four tiles, four cuts: 256 workgroups
+    assert cuts(32, 4096, 16384) == 4
+    assert cuts(32, 6144, 4096) == 2           # 128 groups of three tiles, two cuts
+    assert cuts(128, 6144, 4096) == 2
+    assert cuts(8, 4096, 4096) == 0            # up to 8 rows: the kernel that needs no workspace
+    assert cuts(32, 4096, 4000) == 0           # inputs not a multiple of 256
+    assert cuts(128, 4096, 4096 + 128) == 0    # from 112 rows on the kernel takes two 128-input chunks at a time
+    for m in (9, 33, 65, 97, 128):
+        for n_out, n_in in ((16, 256), (48, 512), (2560, 2560), (5120, 13824), (28672, 8192)):
+            c = cuts(m, n_out, n_in)
+            chunk = 256 if m <= 96 else 128
+            assert c >= 1 and (n_in // chunk) % c == 0 and (c == 1 or n_in // chunk // c >= 2)
+
+
 def test_plan_matches_oracle_brute_force():
     for L in range(1, 65):
         for den in range(1, 33):
