@@ -50,9 +50,6 @@ typedef float floatx4 __attribute__((ext_vector_type(4)));
 #ifndef OKV_LIN_DEPTH
 #define OKV_LIN_DEPTH 8
 #endif
-#ifndef OKV_LIN_WG_PER_CU
-#define OKV_LIN_WG_PER_CU 1
-#endif
 // Up to this many rows the simple kernel is the faster one (its gather of x costs in proportion to the rows, and it
 // has more, shorter-lived workgroups and needs no second kernel); measured with the weights coming from HBM, 16384 x
 // 4096: 26.6 us against 27.0 at 8 rows, 27.8 against 26.9 at 10, 34.3 against 27.4 at 16.
@@ -227,10 +224,11 @@ constexpr int lin_weight_lead(int mf) { return 8 / lin_chunk(mf) > 1 ? 8 / lin_c
 // s_waitcnt operand that waits until at most n vector memory loads are outstanding and for nothing else
 constexpr int vmcnt_only(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
 
-// waves_per_eu: without the hint the compiler aims at the occupancy that the LDS footprint would allow and
-// caps the kernel at 64 registers.
+// waves_per_eu: a workgroup has one or two wavefronts per SIMD and a compute unit holds one workgroup (LDS), so
+// up to 128 registers cost nothing; without the hint the compiler aimed at the occupancy the launch bounds allow
+// and capped the kernel at 64.
 template <int MF, int NW>
-__global__ __launch_bounds__((NW + lin_stagers(MF)) * 64) __attribute__((amdgpu_waves_per_eu(2, 4))) void linear_lds_kernel(const LinearArgs a) {
+__global__ __launch_bounds__((NW + lin_stagers(MF)) * 64) __attribute__((amdgpu_waves_per_eu(1, 4))) void linear_lds_kernel(const LinearArgs a) {
   constexpr int NS = lin_stagers(MF);
   constexpr int kFastThreads = (NW + NS) * 64, kTileCols = NW * 16;      // kTileCols: output features of a workgroup
   constexpr int C = lin_chunk(MF), LEAD = lin_lead(MF), NBUF = LEAD + 1, PER = C * MF, MINE = PER / NS;
@@ -531,7 +529,7 @@ __global__ __launch_bounds__(kLnMaxThreads) void layernorm_kernel(const uint4 *x
   float q = 0.f;
 #pragma unroll
   for (int i = 0; i < PPT; ++i)
-    if ((int)threadIdx.x + i * blockDim.x < pieces) {
+    if ((int)(threadIdx.x + i * blockDim.x) < pieces) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) q += (v[i][e] - mean) * (v[i][e] - mean);
     }
@@ -614,7 +612,7 @@ __global__ __launch_bounds__(kLnMaxThreads) void reduce_layernorm_kernel(const L
   float q = 0.f;
 #pragma unroll
   for (int i = 0; i < PPT; ++i)
-    if ((int)threadIdx.x + i * blockDim.x < pieces) {
+    if ((int)(threadIdx.x + i * blockDim.x) < pieces) {
 #pragma unroll
       for (int e = 0; e < 8; ++e) q += (v[i][e] - mean) * (v[i][e] - mean);
     }
