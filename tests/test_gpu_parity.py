@@ -460,3 +460,44 @@ def test_whole_step_in_one_call_is_the_same_step():
     assert e.value.code == binding.OKV_ESTATE
     for st in sts:
         st.close()
+
+
+def test_two_contexts_side_by_side_do_not_disturb_each_other():
+    # two contexts of different shapes, each on streams of its own, issue their steps alternately without waiting
+    # for one another: every output equals what the same context gives alone, bit for bit, and the oracle's
+    say("two contexts side by side")
+    shapes = [dict(L=2, H=8, G=2, d=64, T=16, ctx_before=[30, 200, 77, 5], seed=601, on_host=[0, 1]),
+              dict(L=3, H=4, G=4, d=128, T=0, ctx_before=[100, 101, 99], seed=602, on_host=None)]
+    n_steps = 3
+
+    def run(which, interleaved):
+        stacks = [build_stack(cap_tokens=256, **shapes[i]) for i in which]
+        outs = [[] for _ in stacks]
+        ins = [[make_inputs(st, 610 + i, step, st.device) for step in range(n_steps)] for i, st in zip(which, stacks)]
+        for step in range(n_steps):
+            for j, st in enumerate(stacks):
+                q, k, v, out = ins[j][step]
+                st.step(q, k, v, out)                        # no synchronisation between the two contexts
+                if not interleaved:
+                    st.synchronize()
+        for j, st in enumerate(stacks):
+            st.synchronize()
+            outs[j] = [[o.cpu().numpy().view(np.uint16).copy() for o in ins[j][step][3]] for step in range(n_steps)]
+        last = [(st, ins[j][n_steps - 1]) for j, st in enumerate(stacks)]
+        return stacks, outs, last
+
+    stacks, both, last = run([0, 1], interleaved=True)
+    for st, (q, k, v, out) in last:                           # the last step against the oracle
+        pairs = [(b, h) for b in range(st.B) for h in range(st.H)]
+        for l in range(st.L):
+            ref = oracle_pairs(st, l, q[l].cpu().numpy(), st.ctx_lens.copy(), pairs)
+            got = np.stack([out[l].float().cpu().numpy()[b, h] for (b, h) in pairs])
+            assert_close(got, np.stack([ref[p] for p in pairs]), f"layer {l}")
+    for st in stacks:
+        st.close()
+    for i in (0, 1):
+        stacks, alone, _ = run([i], interleaved=False)
+        for step in range(n_steps):
+            for a, b in zip(alone[0][step], both[i][step]):
+                np.testing.assert_array_equal(a, b)
+        stacks[0].close()
