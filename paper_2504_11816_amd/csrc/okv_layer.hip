@@ -204,9 +204,10 @@ __global__ __launch_bounds__(kLinWaves * 64) void linear_kernel(const LinearArgs
   }
 }
 
-// Fast path: NW wavefronts x 16 features, x staged in LDS by one more wavefront, input
-// dimension cut across workgroups.  NW = 4, or 3 where that gives one workgroup per compute unit without a cut
-// (12288 features on 256 units), which saves the kernel that adds up the shares.
+// Fast path: NW wavefronts x 16 features, x staged in LDS by one or two more wavefronts, input
+// dimension cut across workgroups.  NW = 4 or 3 and the number of cuts: whatever linear_plan's model of the
+// launch prefers (3 and no cut for 12288 features on 256 compute units, which saves the kernel that adds up
+// the shares).
 // 32-input blocks per staged chunk of x: 8 (256 inputs), 4 from 112 rows on.  A chunk takes chunk x MF KiB of LDS
 // and there are lead + 1 of them: 128 KiB at most (4 x 32 at 64 and at 128 rows), 144 at 96 rows (3 x 48).
 constexpr int lin_chunk(int mf) { return mf <= 6 ? 8 : 4; }
