@@ -24,7 +24,8 @@
 extern "C" {
 #endif
 
-#define OKV_LINEAR_MAX_ROWS 128
+#define OKV_LINEAR_MAX_ROWS 128     /* rows that one launch of the product kernels takes                    */
+#define OKV_LINEAR_MAX_BATCH 4096   /* rows per call: beyond OKV_LINEAR_MAX_ROWS a call issues several launches */
 
 struct okv_ctx;   /* okv.h */
 
@@ -38,8 +39,10 @@ struct okv_ctx;   /* okv.h */
  * n_out must be a multiple of 16 and n_in of 32.  dst and src must not overlap. */
 int okv_pack_linear_weight(void *dst, const void *src, int32_t n_out, int32_t n_in, void *stream);
 
-/* out = act(x * W^T + bias) + residual for a batch of m <= OKV_LINEAR_MAX_ROWS rows
- * (paper §IV-D: the linear layers of the decode stage, 2 n_out n_in flops per row).
+/* out = act(x * W^T + bias) + residual for a batch of m <= OKV_LINEAR_MAX_BATCH rows
+ * (paper §IV-D: the linear layers of the decode stage, 2 n_out n_in flops per row).  Up to
+ * OKV_LINEAR_MAX_ROWS rows are one launch, in which every weight is read once; more rows are
+ * cut into the fewest launches of nearly equal size, each of which reads the weights again.
  *   x         fp16 [m][n_in]
  *   w_packed  fp16, as okv_pack_linear_weight leaves it
  *   bias      fp16 [n_out] or NULL
@@ -128,7 +131,7 @@ int64_t okv_decoder_scratch_bytes(const struct okv_ctx *ctx, int32_t m, int32_t 
  * saves is the caller's time per call (a Python caller spends longer on the six calls of a layer
  * than a small layer runs on the GPU).
  *   layers     HOST array [n_layers]
- *   x          fp16 [B][h1], B = the batch of okv_set_batch (<= OKV_LINEAR_MAX_ROWS); overwritten
+ *   x          fp16 [B][h1], B = the batch of okv_set_batch (<= OKV_LINEAR_MAX_BATCH); overwritten
  *              with the output of the last layer
  *   scratch    >= okv_decoder_scratch_bytes(ctx, B, h2) bytes, 256-byte aligned
  *   workspace  >= the largest okv_linear_workspace_bytes of the four products

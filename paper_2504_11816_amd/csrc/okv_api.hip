@@ -1420,10 +1420,21 @@ int device_cus() {
 }
 }  // namespace
 
+namespace {
+// Rows per launch for a batch of m rows: one launch up to OKV_LINEAR_MAX_ROWS, else the fewest launches of
+// (nearly) equal size, a multiple of 16 rows each but the last.
+int32_t rows_per_launch(int32_t m) {
+  if (m <= OKV_LINEAR_MAX_ROWS) return m;
+  const int32_t launches = (m + OKV_LINEAR_MAX_ROWS - 1) / OKV_LINEAR_MAX_ROWS;
+  return ((m + launches - 1) / launches + 15) / 16 * 16;
+}
+}  // namespace
+
 int64_t okv_linear_workspace_bytes(int32_t m, int32_t n_out, int32_t n_in) {
-  if (m < 1 || m > OKV_LINEAR_MAX_ROWS || n_out < 16 || n_out % 16 || n_in < 32 || n_in % 32)
+  if (m < 1 || m > OKV_LINEAR_MAX_BATCH || n_out < 16 || n_out % 16 || n_in < 32 || n_in % 32)
     return fail(nullptr, OKV_EINVAL, "okv_linear_workspace_bytes: bad shape");
-  return okv::linear_workspace_bytes(m, n_out, n_in, device_cus());
+  const int32_t rows = rows_per_launch(m), last = m % rows ? m % rows : rows;
+  return std::max(okv::linear_workspace_bytes(rows, n_out, n_in, device_cus()), okv::linear_workspace_bytes(last, n_out, n_in, device_cus()));
 }
 
 namespace {
@@ -1431,7 +1442,7 @@ int linear_impl(const void *x, const void *w_packed, const void *bias, const voi
                 int32_t m, int32_t n_out, int32_t n_in, int32_t relu, void *workspace, int64_t workspace_bytes,
                 const void *ln_gamma, const void *ln_beta, void *ln_out, float ln_eps, void *stream, int32_t first_cols = 0) {
   if (!x || !w_packed || !out || !aligned16(x) || !aligned16(w_packed)) return fail(nullptr, OKV_EINVAL, "okv_linear: NULL or misaligned pointer");
-  if (m < 1 || m > OKV_LINEAR_MAX_ROWS) return fail(nullptr, OKV_EINVAL, "okv_linear: m = %d outside [1, %d]", m, OKV_LINEAR_MAX_ROWS);
+  if (m < 1 || m > OKV_LINEAR_MAX_BATCH) return fail(nullptr, OKV_EINVAL, "okv_linear: m = %d outside [1, %d]", m, OKV_LINEAR_MAX_BATCH);
   if (n_out < 16 || n_out % 16 || n_in < 32 || n_in % 32 || n_in > (1 << 20))
     return fail(nullptr, OKV_EINVAL, "okv_linear: n_out must be a multiple of 16 and n_in of 32");
   if (n_seg < 1 || n_seg > 3 || (!first_cols && n_out % (16 * n_seg)))
@@ -1454,7 +1465,20 @@ int linear_impl(const void *x, const void *w_packed, const void *bias, const voi
   l.workspace_bytes = workspace_bytes;
   l.n_cus = device_cus();
   l.ln_gamma = ln_gamma, l.ln_beta = ln_beta, l.ln_out = ln_out, l.ln_eps = ln_eps;
-  OKV_HIP(nullptr, okv::launch_linear(l, static_cast<hipStream_t>(stream)));
+  // more rows than one launch takes: launches of (nearly) equal size, one after the other on the stream (they
+  // share the workspace); each reads the weights again
+  const int32_t rows = rows_per_launch(m);
+  const int64_t seg0 = first_cols ? first_cols : n_out / n_seg, seg = n_seg > 1 ? (n_out - seg0) / (n_seg - 1) : n_out;
+  auto at = [](const void *p, int64_t halves) -> const void * { return p ? static_cast<const char *>(p) + halves * 2 : nullptr; };
+  for (int32_t r0 = 0; r0 < m; r0 += rows) {
+    okv::LinearLaunch part = l;
+    part.m = std::min(rows, m - r0);
+    part.x = at(x, (int64_t)r0 * n_in);
+    part.residual = at(residual, (int64_t)r0 * n_out);
+    part.ln_out = const_cast<void *>(at(ln_out, (int64_t)r0 * n_out));
+    for (int s2 = 0; s2 < n_seg; ++s2) part.out[s2] = const_cast<void *>(at(out[s2], (int64_t)r0 * (s2 == 0 ? seg0 : seg)));
+    OKV_HIP(nullptr, okv::launch_linear(part, static_cast<hipStream_t>(stream)));
+  }
   return OKV_OK;
 }
 }  // namespace
@@ -1515,7 +1539,7 @@ DecoderScratch decoder_scratch(void *base, int32_t m, int32_t h1, int32_t kvw, i
 
 int64_t okv_decoder_scratch_bytes(const okv_ctx *ctx, int32_t m, int32_t h2) {
   if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
-  if (m < 1 || m > OKV_LINEAR_MAX_ROWS || h2 < 32 || h2 % 32) return fail(nullptr, OKV_EINVAL, "okv_decoder_scratch_bytes: bad shape");
+  if (m < 1 || m > OKV_LINEAR_MAX_BATCH || h2 < 32 || h2 % 32) return fail(nullptr, OKV_EINVAL, "okv_decoder_scratch_bytes: bad shape");
   return decoder_scratch(nullptr, m, ctx->cfg.n_q_heads * ctx->cfg.head_dim, ctx->cfg.n_kv_heads * ctx->cfg.head_dim, h2).bytes;
 }
 
@@ -1527,7 +1551,7 @@ int okv_decoder_step(okv_ctx *ctx, const okv_decoder_layer *layers, int32_t n_la
   if (ctx->cfg.out_dtype != 0) return fail(ctx, OKV_EINVAL, "okv_decoder_step: the attention output must be fp16 (out_dtype 0)");
   if (!ctx->batch_set) return fail(ctx, OKV_ESTATE, "okv_decoder_step before okv_set_batch");
   const int32_t m = ctx->B, h1 = ctx->cfg.n_q_heads * ctx->cfg.head_dim, kvw = ctx->cfg.n_kv_heads * ctx->cfg.head_dim;
-  if (m < 1 || m > OKV_LINEAR_MAX_ROWS) return fail(ctx, OKV_EINVAL, "okv_decoder_step: batch %d outside [1, %d]", m, OKV_LINEAR_MAX_ROWS);
+  if (m < 1 || m > OKV_LINEAR_MAX_BATCH) return fail(ctx, OKV_EINVAL, "okv_decoder_step: batch %d outside [1, %d]", m, OKV_LINEAR_MAX_BATCH);
   if (h2 < 32 || h2 % 32 || h2 > 16384 * 8) return fail(ctx, OKV_EINVAL, "okv_decoder_step: bad feed-forward width %d", h2);
   if (((uintptr_t)scratch & 255) || !aligned16(x)) return fail(ctx, OKV_EINVAL, "okv_decoder_step: scratch or x misaligned");
   const DecoderScratch d = decoder_scratch(scratch, m, h1, kvw, h2);

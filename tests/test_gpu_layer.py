@@ -353,3 +353,48 @@ def test_linear_random_shapes_against_the_oracle():
         say(f"  m={m} {n_out}x{n_in}")
         run_linear(m, n_out, n_in, 500 + i, bias=bool(rng.integers(0, 2)), relu=bool(rng.integers(0, 2)),
                    residual=bool(rng.integers(0, 2)))
+
+
+@pytest.mark.parametrize("m", [129, 192, 300])
+def test_linear_more_rows_than_one_launch_takes(m):
+    # beyond 128 rows a call issues several launches of nearly equal size; same contract
+    say(f"linear m={m}")
+    run_linear(m, 320, 512, 700 + m, relu=True, residual=True)
+    run_linear(m, 96, 1024, 710 + m, n_seg=3)
+    run_linear(m, 64, 96, 720 + m)                            # the kernel for odd input sizes
+
+
+def test_decoder_step_with_a_batch_of_more_than_128():
+    say("decoder step batch 160")
+    L, H, G, d, B = 2, 4, 2, 64, 160
+    h1, h2 = H * d, 4 * H * d
+    ctx = list(np.random.Generator(np.random.PCG64(5)).integers(1, 60, size=B))
+    results = []
+    for one_call in (False, True):
+        st = build_stack(L=L, H=H, G=G, d=d, T=16, ctx_before=ctx, cap_tokens=64, seed=731)
+        weights = [LayerWeights(h1, h2, 733, l, st.device, kv_cols=G * d) for l in range(L)]
+        scratch = LayerScratch(B, h1, h2, G, d, st.device)
+        x = synth.randn_f16_torch((B, h1), synth.stream_seed(735, 1), st.device)
+        x_ref = x.double().cpu().numpy()
+        if one_call:
+            BoundLayers(st, weights, scratch).step(x)
+        else:
+            decode_step_with_layers(st, weights, scratch, x)
+        st.synchronize()
+        results.append(x.cpu().numpy().view(np.uint16).copy())
+        if not one_call:                                      # against the oracle once
+            layout = st.layout()
+            n = np.array(ctx, dtype=np.int32) + 1
+            pools = None
+            st2 = build_stack(L=L, H=H, G=G, d=d, T=16, ctx_before=ctx, cap_tokens=64, seed=731)
+            pools = [st2.read_pool(l).copy() for l in range(L)]
+            st2.close()
+            for l in range(L):
+                p = weights[l].numpy()
+                q, k, v = dl.qkv(x_ref, p, fp16_between=True)
+                kv_layout.append_scatter(pools[l], layout, n, k.astype(np.float16).reshape(B, G, d), v.astype(np.float16).reshape(B, G, d))
+                t = oa.decode_attn(q.reshape(B, H, d), pools[l], layout, n, H)
+                x_ref = dl.after_attention(x_ref, dl.round16(np.asarray(t).reshape(B, h1)), p, fp16_between=True)
+            close(x.float().cpu().numpy(), x_ref, atol=1.5e-2, rtol=1.5e-2, what="batch 160")
+        st.close()
+    np.testing.assert_array_equal(results[0], results[1])

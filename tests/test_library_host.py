@@ -39,7 +39,7 @@ def test_layer_header_symbols_are_exported():
         assert hasattr(lib, name), name
     assert decl == sorted(binding.LAYER_EXPORTS)
     # argument checks need no GPU
-    for bad in (dict(m=0), dict(m=129), dict(n_out=24), dict(n_in=48), dict(n_seg=4), dict(n_seg=3, n_out=64)):
+    for bad in (dict(m=0), dict(m=4097), dict(n_out=24), dict(n_in=48), dict(n_seg=4), dict(n_seg=3, n_out=64)):
         kw = dict(m=4, n_out=96, n_in=64, n_seg=1)
         kw.update(bad)
         with pytest.raises(binding.OkvError) as e:
