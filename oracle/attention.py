@@ -84,14 +84,6 @@ def decode_attn(q, pool_flat, layout, ctx_lens, H, sample=None):
     return out
 
 
-def attention_weights(q_vec, k_rows):
-    """The softmax weights alone (sum to 1), for invariant checks."""
-    k_rows = np.asarray(k_rows, dtype=np.float64)
-    s = (k_rows @ np.asarray(q_vec, dtype=np.float64)) / math.sqrt(k_rows.shape[1])
-    w = np.exp(s - s.max())
-    return w / w.sum()
-
-
 def merge_partials(ms, ls, os):
     """Combine per-split (max, sum, weighted-sum) triples into one output.
 
