@@ -170,6 +170,21 @@ int okv_plan_from_bytes(int32_t n_layers, int64_t layer_bytes, int64_t mem_avail
 int okv_plan_block_split(int64_t n_blocks, int64_t coff_num, int64_t coff_den,
                          int64_t *resident_blocks, int64_t *host_blocks);
 
+/* How the keys of a batch are shared out over the wavefronts of a launch when no split size is
+ * fixed (split_tokens == 0): the 16-key tiles of all sequences, laid end to end in sequence order, are
+ * cut into n = min(max_groups, max(1, tiles / 8)) stretches of ceil(tiles / n) tiles, and a sequence is
+ * cut wherever a stretch ends inside it.  Every wavefront of a launch streams at the same rate, so
+ * equal shares end together (this is the split-K work list of a3 in §IV-D's terms: bookkeeping only,
+ * any partition of the keys merges to the same softmax).  Pure host function.
+ *   ctx_lens     HOST int32 [B], keys per sequence (>= 0)
+ *   max_groups   wavefronts per KV head (a context uses 4 per compute unit / n_kv_heads)
+ *   items        HOST int32 [max_items][3]: (sequence, first key, one past the last key), in order
+ *   group_first  HOST int32 [max_groups + 1]: first item of every stretch, then the item count
+ *   n_groups, span_tiles  HOST out: stretches in use, tiles per stretch
+ * OKV_ENOSPC if max_items is too small (*n_items still receives the count). */
+int okv_equal_stretches(const int32_t *ctx_lens, int32_t B, int32_t max_groups, int32_t *items, int64_t max_items,
+                        int64_t *n_items, int32_t *group_first, int32_t *n_groups, int64_t *span_tiles);
+
 /* The order of operations the copy pipeline enqueues, without a GPU (the runtime
  * walks the same scheduler).
  *   host_chunks   HOST int32 [n_layers]: streamed chunks of each layer (whole-layer

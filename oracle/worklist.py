@@ -11,6 +11,18 @@ the sequence contributes the items [c*size, min((c+1)*size, n_b)) for
 c = 0, 1, ... while they are non-empty.  Items are listed sequence by
 sequence, in order, and each item is processed once per KV head.
 
+When no split size is fixed the library shares the keys of a launch out in
+equal stretches instead, so that wavefronts that stream at one rate end
+together.  The contract: the 16-key tiles of all sequences are laid end to
+end in sequence order (a sequence with n keys has ceil(n / 16) tiles, the
+last one possibly partial); with T tiles in all, at most `max_groups`
+stretches and a shortest stretch of 8 tiles, there are
+g = min(max_groups, max(1, T // 8)) stretches of span = ceil(T / g) tiles:
+tile number p of the stream belongs to stretch p // span.  An item is a
+maximal run of consecutive tiles of ONE sequence inside ONE stretch; items
+are listed in stream order; the items that start in stretch j form group j.
+expected_items_equal_stretches below walks the stream tile by tile.
+
 Block-granular offload (paper §IV-C: a share C_off of the cache lives in host
 memory) adds one more cut.  Block ids below `resident_blocks` are in HBM
 (class 0); the others are in the host pool, which is streamed in chunks of
@@ -50,6 +62,37 @@ def expected_items(ctx_lens, split_tokens):
             items.append((b, start, stop))
             start = stop
     return items
+
+
+def expected_items_equal_stretches(ctx_lens, max_groups, min_span_tiles=8):
+    """(items, group_first, span): the stream of tiles walked one tile at a time.
+
+    items        [(b, tok_begin, tok_end)] in stream order
+    group_first  index of the first item of every stretch, then len(items)
+    span         tiles per stretch
+    """
+    stream = []                                   # (sequence, tile of the sequence) for every tile, in order
+    for b, n in enumerate(ctx_lens):
+        n = int(n)
+        for t in range(-(-n // 16)):
+            stream.append((b, t))
+    total = len(stream)
+    groups = min(max_groups, max(1, total // min_span_tiles))
+    span = max(1, -(-total // groups))
+    items, group_first = [], []
+    prev = None                                   # (sequence, stretch) of the previous tile
+    for p, (b, t) in enumerate(stream):
+        stretch = p // span
+        n = int(ctx_lens[b])
+        if prev != (b, stretch):
+            if prev is None or prev[1] != stretch:
+                group_first.append(len(items))
+            items.append([b, 16 * t, min(n, 16 * t + 16)])
+        else:
+            items[-1][2] = min(n, 16 * t + 16)
+        prev = (b, stretch)
+    group_first.append(len(items))
+    return [tuple(i) for i in items], group_first, span
 
 
 def check_tiling(items, ctx_lens):

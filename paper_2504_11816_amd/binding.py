@@ -23,7 +23,7 @@ EXPORTS = [
     "okv_worklist_classes", "okv_prefill_begin", "kv_append_bulk", "okv_prefill_release", "okv_prefill_end", "okv_prefill_plan",
     "okv_measure_d2h",
     "okv_profile_enable", "okv_profile_read", "okv_measure_h2d", "okv_time_copies", "okv_probe_copy",
-    "okv_probe_read",
+    "okv_probe_read", "okv_equal_stretches",
 ]
 
 
@@ -116,6 +116,8 @@ def lib():
             "okv_decoder_scratch_bytes": (I64, [P, I32, I32]),
             "okv_decoder_step": (ctypes.c_int, [P, P, I32, I32, P, ctypes.c_float, P, I64, P, I64]),
             "okv_probe_read": (ctypes.c_int, [P, I64, P, P]),
+            "okv_equal_stretches": (ctypes.c_int, [P, I32, I32, P, I64, ctypes.POINTER(I64), P, ctypes.POINTER(I32),
+                                                   ctypes.POINTER(I64)]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)
@@ -182,6 +184,19 @@ def okv_schedule_trace(host_chunks, n_staging, n_steps, has_resident=None):
     _check(lib().okv_schedule_trace(L, _ptr(host_chunks), _ptr(has_resident), n_staging, n_steps, _ptr(ops),
                                     max_ops, ctypes.byref(n)))
     return [tuple(int(v) for v in row) for row in ops[:n.value]]
+
+
+def okv_equal_stretches(ctx_lens, max_groups):
+    """-> (items int32 [n][3], group_first int32 [n_groups + 1], span_tiles)"""
+    ctx_lens = np.ascontiguousarray(ctx_lens, dtype=np.int32)
+    B = len(ctx_lens)
+    max_items = B + max_groups + 1
+    items = np.zeros((max_items, 3), dtype=np.int32)
+    first = np.zeros(max_groups + 1, dtype=np.int32)
+    n, groups, span = ctypes.c_int64(0), ctypes.c_int32(0), ctypes.c_int64(0)
+    _check(lib().okv_equal_stretches(_ptr(ctx_lens), B, max_groups, _ptr(items), max_items, ctypes.byref(n), _ptr(first),
+                                     ctypes.byref(groups), ctypes.byref(span)))
+    return items[:n.value].copy(), first[:groups.value + 1].copy(), span.value
 
 
 def make_config(**kw):

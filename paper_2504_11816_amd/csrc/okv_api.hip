@@ -35,7 +35,8 @@ constexpr int kEventRing = 8;            // > copies in flight (at most OKV_MAX_
 #ifndef OKV_WAVES_PER_CU_MFMA
 #define OKV_WAVES_PER_CU_MFMA 4
 #endif
-constexpr int32_t kMinAutoSplit = 128;   // smallest split size the library picks by itself
+constexpr int32_t kMinAutoSplit = 128;   // smallest stretch of keys the library cuts a launch into by itself
+constexpr int32_t kMinSpanTiles = kMinAutoSplit / 16;
 constexpr int32_t kClassSplit = 512;     // split size with block classes unless the caller sets one
 constexpr int64_t kMaxClasses = 4096;
 // Workgroups of a bulk store that writes into host memory: the link, not the GPU, sets its
@@ -82,7 +83,9 @@ struct okv_ctx {
 
   int32_t *d_block_table = nullptr, *d_ctx_lens = nullptr, *d_chunk_prefix = nullptr;
   int4 *d_item_desc = nullptr;
-  uint32_t *d_queues = nullptr;          // one ticket counter per layer and class, zeroed at every step
+  int32_t *d_group_first = nullptr;      // equal stretches: first item of every stretch (+ 1 entry)
+  int32_t *d_plan = nullptr;             // equal stretches: (stretches in use, items, tiles per stretch x 2)
+  int32_t max_groups = 1;                // wavefronts of a launch per KV head
   int32_t *d_items_dump = nullptr;
   int32_t max_waves = 0;                 // wavefronts of the persistent attention launch
   int64_t max_items = 0;
@@ -91,7 +94,9 @@ struct okv_ctx {
   std::vector<int32_t> h_block_table, h_ctx_lens;
   int32_t B = 0, split = 0, split_override = 0, n_items = 0;
   bool need_merge = false;
-  bool even_units = false;               // every sequence of the batch has (within a tile) the same length
+  bool spans = false;                    // the work list is cut into equal stretches (no split size given)
+  int32_t n_groups = 0;                  // stretches in use
+  int64_t span_tiles = 0;                // tiles per stretch
   int64_t copy_bytes = 0;
 
   // bulk store of prompts (prefill side)
@@ -215,89 +220,9 @@ int64_t count_items(const int32_t *ctx, int32_t B, int32_t S) {
   return n;
 }
 
-// Split size by a small cost model of one launch, evaluated for S = 128, 256, 512, ...
-//   time(S) = max( (bytes + units * kItemOverheadBytes) / kLaunchBytesPerUs + tail / 2,
-//                  longest item / kWaveBytesPerUs,
-//                  rounds(S) )
-// A wavefront alone pulls at most kWaveBytesPerUs, so about kSaturatingWaves of them
-// are needed to keep HBM busy; `tail` is the time the longest item keeps running after
-// fewer than that many items are left (they all start together and finish by size).
-// rounds(S): the launch has W persistent wavefronts, so U units of the mean size take
-// floor(U / W) full rounds at the launch's rate and, if units are left over, one more
-// round in which each of them runs at what U mod W wavefronts can pull (1536 units of
-// 2048 keys on 1024 wavefronts take as long as 2048 of them; cut in two they take three
-// rounds of half the length).  Fewer, longer items save per-item cost and the merge pass;
-// equal items avoid a tail; a unit count that fills the rounds avoids idle wavefronts.  Units of
-// mixed sizes do not move in rounds (the queue hands the next unit to whichever wavefront is free), so
-// the term only counts when the smallest unit is within a tenth of the largest; the tail term speaks
-// for the others (batch 64 of 512..4096 keys, 32 heads: the rounds term chose 256-key units, 420 us a
-// layer, where 512 take 404).
-// The constants are measured on MI355X with this kernel (d = 128 rows).
-constexpr double kLaunchBytesPerUs = 6.3e6;      // what the split kernel sustains, bytes per microsecond
-constexpr double kWaveBytesPerUs = 6.5e3;        // one wavefront with 8 KiB in flight
-constexpr double kItemOverheadBytes = 10240;     // prologue, epilogue, partial result, merge share
-constexpr int64_t kSaturatingWaves = 970;        // kLaunchBytesPerUs / kWaveBytesPerUs
-
-double launch_cost_us(const okv_ctx *ctx, const std::vector<int32_t> &lens, int32_t S, int64_t *n_items) {
-  const int32_t G = ctx->cfg.n_kv_heads;
-  const double row_bytes = 2.0 * ctx->cfg.head_dim * 2;            // K row + V row of one KV head
-  std::vector<std::pair<int32_t, int64_t>> sizes;                  // (keys per item, wavefront items)
-  double bytes = 0;
-  int64_t items = 0, units = 0;
-  for (int32_t b = 0; b < ctx->B; ++b) {
-    int32_t cnt, sz;
-    okv::seq_chunks(lens[b], S, &cnt, &sz);
-    if (cnt == 0) continue;
-    const int32_t longest_piece = cnt == 1 ? lens[b] : sz;
-    sizes.emplace_back(longest_piece, (int64_t)cnt * G);
-    bytes += (double)lens[b] * G * row_bytes;
-    items += cnt;
-    units += (int64_t)cnt * G;
-  }
-  *n_items = items;
-  if (sizes.empty()) return 0;
-  std::sort(sizes.begin(), sizes.end(), [](const auto &x, const auto &y) { return x.first > y.first; });
-  const double longest = sizes[0].first * row_bytes;
-  double at_saturation = 0;                                        // size of the kSaturatingWaves-th largest item
-  int64_t seen = 0;
-  for (const auto &p : sizes) {
-    seen += p.second;
-    if (seen >= kSaturatingWaves) {
-      at_saturation = p.first * row_bytes;
-      break;
-    }
-  }
-  const double tail = (longest - at_saturation) / kWaveBytesPerUs;
-  const double stream = (bytes + (double)units * kItemOverheadBytes) / kLaunchBytesPerUs;
-  const int64_t W = std::max<int64_t>(1, ctx->max_waves);
-  const double unit_bytes = bytes / (double)units + kItemOverheadBytes;
-  const int64_t left = units % W;
-  double rounds = 0;
-  if (sizes.back().first * 10 >= sizes[0].first * 9) {             // units of (nearly) one size move in step
-    rounds = (double)(units / W) * unit_bytes * (double)W / kLaunchBytesPerUs;
-    if (left) rounds += unit_bytes / std::min(kWaveBytesPerUs, kLaunchBytesPerUs / (double)left);
-  }
-  return std::max({stream + 0.5 * tail, longest / kWaveBytesPerUs, rounds});
-}
-
-int32_t choose_split(const okv_ctx *ctx, const std::vector<int32_t> &lens) {
-  if (ctx->split_override) return ctx->split_override;
-  if (ctx->cfg.split_tokens) return ctx->cfg.split_tokens;
-  int32_t longest = 1;
-  for (int32_t b = 0; b < ctx->B; ++b) longest = std::max(longest, lens[b]);
-  int32_t best = 0;
-  double best_cost = 0;
-  for (int64_t S = kMinAutoSplit; ; S *= 2) {
-    int64_t n_items = 0;
-    const double cost = launch_cost_us(ctx, lens, (int32_t)S, &n_items);
-    if (n_items <= ctx->max_items && (best == 0 || cost < best_cost * 0.999)) {
-      best = (int32_t)S;
-      best_cost = cost;
-    }
-    if (S >= longest) break;
-  }
-  return best ? best : kMinAutoSplit;
-}
+// The split size the caller fixed (okv_set_split_tokens, else cfg.split_tokens), or 0: the library
+// shares the launch's keys out in equal stretches.
+int32_t fixed_split(const okv_ctx *ctx) { return ctx->split_override ? ctx->split_override : ctx->cfg.split_tokens; }
 
 hipStream_t copy_stream(okv_ctx *ctx, int buf) { return (buf & 1) && ctx->h2d_odd ? ctx->h2d_odd : ctx->h2d; }
 
@@ -315,8 +240,10 @@ okv::AttnLaunch base_launch(okv_ctx *ctx) {
   a.part_ml = ctx->part_ml;
   a.out_fp32 = ctx->cfg.out_dtype;
   a.need_merge = ctx->need_merge;
-  a.even_units = ctx->even_units ? 1 : 0;
-  a.queue = nullptr;
+  if (ctx->spans) {
+    a.group_first = ctx->d_group_first;
+    a.n_groups = ctx->n_groups;
+  }
   a.max_waves = ctx->max_waves;
   a.item_first = 0;
   a.item_count = ctx->n_items;
@@ -347,8 +274,8 @@ int exec_op(okv_ctx *ctx, const Op &op, const void *a0, const void *a1, void *ou
     case okv::OP_ATTN: {
       if (op.wait_idx >= 0) OKV_HIP(ctx, hipStreamWaitEvent(ctx->compute, ctx->ready_ev[op.wait_idx % kEventRing], 0));
       okv::AttnLaunch a = base_launch(ctx);
-      int32_t cls = 0;
       if (ctx->by_class) {
+        int32_t cls = 0;
         if (op.chunk >= 0) {
           const int32_t chunk = ctx->active_chunks[op.chunk];
           cls = 1 + chunk;
@@ -359,7 +286,6 @@ int exec_op(okv_ctx *ctx, const Op &op, const void *a0, const void *a1, void *ou
         a.item_count = ctx->cls_count[cls];
       }
       if (a.item_count == 0) return OKV_OK;              // no key of the batch lies in this class at this step
-      a.queue = ctx->d_queues + (size_t)op.layer * ctx->n_cls + cls;
       a.q = a0;
       a.pool = op.buf >= 0 ? ctx->cfg.staging[op.buf] : ctx->dev_pool[op.layer];
       a.k_new = ctx->pending_k;
@@ -437,32 +363,56 @@ int rebuild_worklist(okv_ctx *ctx, int32_t inc, bool upload_lens = false) {
     ctx->cls_first.assign(ctx->n_cls + 1, 0);
     for (int32_t c = 0; c < ctx->n_cls; ++c) ctx->cls_first[c + 1] = ctx->cls_first[c] + ctx->cls_count[c];
     ctx->need_merge = false;
-    ctx->even_units = false;                             // stretches of blocks differ from sequence to sequence
+    ctx->spans = false;
     for (int32_t b = 0; b < ctx->B; ++b) ctx->need_merge |= per_seq[b] > 1;
     OKV_HIP(ctx, okv::launch_step_advance_classes(ctx->d_ctx_lens, ctx->d_runs, ctx->d_pair_first, ctx->d_chunk_prefix,
-                                                  ctx->d_item_desc, ctx->d_seq_total, ctx->d_queues,
-                                                  ctx->cfg.n_layers * ctx->n_cls, ctx->B, ctx->n_cls, ctx->split, inc,
+                                                  ctx->d_item_desc, ctx->d_seq_total, ctx->B, ctx->n_cls, ctx->split, inc,
                                                   ctx->compute));
     return OKV_OK;
   }
-  ctx->split = choose_split(ctx, ctx->h_ctx_lens);
-  int64_t n = count_items(ctx->h_ctx_lens.data(), ctx->B, ctx->split);
-  if (n > ctx->max_items)
-    return fail(ctx, OKV_ENOSPC, "split size %d needs %lld work items, workspace holds %lld", ctx->split,
-                (long long)n, (long long)ctx->max_items);
-  ctx->n_items = (int32_t)n;
-  ctx->need_merge = false;
-  int32_t shortest = ctx->B ? ctx->h_ctx_lens[0] : 0, longest = shortest;
-  for (int32_t b = 0; b < ctx->B; ++b) {
-    int32_t cnt, sz;
-    okv::seq_chunks(ctx->h_ctx_lens[b], ctx->split, &cnt, &sz);
-    if (cnt > 1) ctx->need_merge = true;
-    shortest = std::min(shortest, ctx->h_ctx_lens[b]);
-    longest = std::max(longest, ctx->h_ctx_lens[b]);
+  if (const int32_t S = fixed_split(ctx)) {
+    // a split size fixed by the caller: every sequence in equal pieces of at most S keys
+    int64_t n = count_items(ctx->h_ctx_lens.data(), ctx->B, S);
+    if (n > ctx->max_items)
+      return fail(ctx, OKV_ENOSPC, "split size %d needs %lld work items, workspace holds %lld", S, (long long)n,
+                  (long long)ctx->max_items);
+    ctx->split = S;
+    ctx->spans = false;
+    ctx->n_items = (int32_t)n;
+    ctx->need_merge = false;
+    for (int32_t b = 0; b < ctx->B; ++b) {
+      int32_t cnt, sz;
+      okv::seq_chunks(ctx->h_ctx_lens[b], S, &cnt, &sz);
+      if (cnt > 1) ctx->need_merge = true;
+    }
+    OKV_HIP(ctx, okv::launch_step_advance(ctx->d_ctx_lens, ctx->d_chunk_prefix, ctx->d_item_desc, ctx->B, S, inc,
+                                          ctx->compute));
+    return OKV_OK;
   }
-  ctx->even_units = longest - shortest < 16;
-  OKV_HIP(ctx, okv::launch_step_advance(ctx->d_ctx_lens, ctx->d_chunk_prefix, ctx->d_item_desc, ctx->d_queues,
-                                        ctx->cfg.n_layers, ctx->B, ctx->split, inc, ctx->compute));
+  // equal stretches: the host walks the same arithmetic as the kernel for the counts it needs
+  int64_t total = 0;
+  for (int32_t b = 0; b < ctx->B; ++b) total += (ctx->h_ctx_lens[b] + 15) >> 4;
+  const okv::SpanPlan plan = okv::span_plan(total, ctx->max_groups, kMinSpanTiles);
+  int64_t n = 0, first = 0;
+  bool merge = false;
+  for (int32_t b = 0; b < ctx->B; ++b) {
+    const int64_t tiles = (ctx->h_ctx_lens[b] + 15) >> 4;
+    int64_t k0;
+    const int32_t cnt = okv::span_pieces(first, tiles, plan.span, &k0);
+    merge |= cnt > 1;
+    n += cnt;
+    first += tiles;
+  }
+  if (n > ctx->max_items)
+    return fail(ctx, OKV_ENOSPC, "the batch needs %lld work items, workspace holds %lld", (long long)n, (long long)ctx->max_items);
+  ctx->spans = true;
+  ctx->n_groups = plan.n_groups;
+  ctx->span_tiles = plan.span;
+  ctx->split = (int32_t)std::min<int64_t>(plan.span * 16, 0x7fffffff);
+  ctx->n_items = (int32_t)n;
+  ctx->need_merge = merge;
+  OKV_HIP(ctx, okv::launch_step_advance_spans(ctx->d_ctx_lens, ctx->d_chunk_prefix, ctx->d_item_desc, ctx->d_group_first,
+                                              ctx->d_plan, ctx->B, ctx->max_groups, kMinSpanTiles, inc, ctx->compute));
   return OKV_OK;
 }
 
@@ -502,7 +452,9 @@ int64_t okv_workspace_bytes(const okv_config *cfg) {
   // with block classes a sequence has at least one item per class it has blocks in; the
   // figure assumes one run per class (an allocator that keeps a sequence's blocks of a
   // class together); a batch that needs more is refused by okv_set_batch
-  int64_t items = (int64_t)cfg->max_batch * ((cap + S - 1) / S + (max_classes_of(cfg) - 1));
+  // (equal stretches cut a batch into at most one item per sequence plus one per stretch, and a stretch
+  // is at least kMinAutoSplit keys unless the batch is a single one: one more item per sequence covers it)
+  int64_t items = (int64_t)cfg->max_batch * ((cap + S - 1) / S + (cfg->chunk_blocks > 0 ? 0 : 1) + (max_classes_of(cfg) - 1));
   return items * bytes_per_item(cfg);
 }
 
@@ -578,6 +530,36 @@ int okv_plan_block_split(int64_t n_blocks, int64_t coff_num, int64_t coff_den, i
   const int64_t host = (int64_t)((x + coff_den - 1) / coff_den);
   *host_blocks = host;
   *resident_blocks = n_blocks - host;
+  return OKV_OK;
+}
+
+int okv_equal_stretches(const int32_t *ctx_lens, int32_t B, int32_t max_groups, int32_t *items, int64_t max_items,
+                        int64_t *n_items, int32_t *group_first, int32_t *n_groups, int64_t *span_tiles) {
+  if (!ctx_lens || B < 1 || max_groups < 1 || !items || !n_items || !group_first || !n_groups || !span_tiles)
+    return fail(nullptr, OKV_EINVAL, "okv_equal_stretches: bad argument");
+  int64_t total = 0;
+  for (int32_t b = 0; b < B; ++b) {
+    if (ctx_lens[b] < 0) return fail(nullptr, OKV_EINVAL, "okv_equal_stretches: ctx_lens[%d] < 0", b);
+    total += (ctx_lens[b] + 15) >> 4;
+  }
+  const okv::SpanPlan plan = okv::span_plan(total, max_groups, kMinSpanTiles);
+  *span_tiles = plan.span;
+  *n_groups = plan.n_groups;
+  int64_t it = 0, first = 0;
+  for (int32_t b = 0; b < B; ++b) {
+    const int64_t tiles = (ctx_lens[b] + 15) >> 4;
+    int64_t k0, group;
+    const int32_t cnt = okv::span_pieces(first, tiles, plan.span, &k0);
+    for (int32_t c = 0; c < cnt; ++c, ++it) {
+      const okv::ItemRange r = okv::span_piece(b, c, ctx_lens[b], first, tiles, plan.span, k0, &group);
+      if (it < max_items) items[it * 3 + 0] = r.b, items[it * 3 + 1] = r.lo, items[it * 3 + 2] = r.hi;
+      if (c > 0 || first % plan.span == 0) group_first[group] = (int32_t)it;
+    }
+    first += tiles;
+  }
+  group_first[plan.n_groups] = (int32_t)it;
+  *n_items = it;
+  if (it > max_items) return fail(nullptr, OKV_ENOSPC, "okv_equal_stretches: %lld items", (long long)it);
   return OKV_OK;
 }
 
@@ -692,15 +674,17 @@ int okv_create(const okv_config *cfg, okv_ctx **out) {
     OKV_TRY_CREATE(hipMalloc(&ctx->d_seq_total, (size_t)cfg->max_batch * sizeof(int32_t)));
   }
   OKV_TRY_CREATE(hipMalloc(&ctx->d_item_desc, (size_t)std::max<int64_t>(1, max_items) * sizeof(int4)));
-  OKV_TRY_CREATE(hipMalloc(&ctx->d_queues, (size_t)L * ctx->n_cls * sizeof(uint32_t)));
-  OKV_TRY_CREATE(hipMemset(ctx->d_queues, 0, (size_t)L * ctx->n_cls * sizeof(uint32_t)));
   {
     int dev = 0, cus = 0;
     OKV_TRY_CREATE(hipGetDevice(&dev));
     OKV_TRY_CREATE(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
     const int group = cfg->n_q_heads / cfg->n_kv_heads;
     ctx->max_waves = std::max(1, cus) * (group == 1 ? OKV_WAVES_PER_CU_MHA : group < 8 ? OKV_WAVES_PER_CU_GQA : OKV_WAVES_PER_CU_MFMA);
+    ctx->max_groups = std::max(1, ctx->max_waves / cfg->n_kv_heads);
   }
+  OKV_TRY_CREATE(hipMalloc(&ctx->d_group_first, ((size_t)ctx->max_groups + 1) * sizeof(int32_t)));
+  OKV_TRY_CREATE(hipMemset(ctx->d_group_first, 0, ((size_t)ctx->max_groups + 1) * sizeof(int32_t)));
+  OKV_TRY_CREATE(hipMalloc(&ctx->d_plan, 4 * sizeof(int32_t)));
   if (n_staging >= 2) OKV_TRY_CREATE(hipStreamCreateWithFlags(&ctx->h2d_odd, hipStreamNonBlocking));
   for (int i = 0; i < kEventRing; ++i) {
     OKV_TRY_CREATE(hipEventCreateWithFlags(&ctx->ready_ev[i], hipEventDisableTiming));
@@ -723,7 +707,8 @@ int okv_destroy(okv_ctx *ctx) {
   (void)hipFree(ctx->d_ctx_lens);
   (void)hipFree(ctx->d_chunk_prefix);
   (void)hipFree(ctx->d_item_desc);
-  (void)hipFree(ctx->d_queues);
+  (void)hipFree(ctx->d_group_first);
+  (void)hipFree(ctx->d_plan);
   (void)hipFree(ctx->d_items_dump);
   if (ctx->d2h) {
     (void)hipStreamSynchronize(ctx->d2h);
@@ -1228,6 +1213,21 @@ int okv_worklist(okv_ctx *ctx, int32_t from_device, int32_t *items, int64_t max_
       for (int32_t c = 0; c < cnt; ++c, ++it) {
         items[it * 3 + 0] = r.b, items[it * 3 + 1] = r.lo + c * sz, items[it * 3 + 2] = std::min(r.lo + (c + 1) * sz, end);
       }
+    }
+    return OKV_OK;
+  }
+  if (ctx->spans) {
+    int64_t first = 0;
+    for (int32_t b = 0; b < ctx->B; ++b) {
+      const int32_t n = ctx->h_ctx_lens[b];
+      const int64_t tiles = (n + 15) >> 4;
+      int64_t k0, group;
+      const int32_t cnt = okv::span_pieces(first, tiles, ctx->span_tiles, &k0);
+      for (int32_t c = 0; c < cnt; ++c, ++it) {
+        okv::ItemRange r = okv::span_piece(b, c, n, first, tiles, ctx->span_tiles, k0, &group);
+        items[it * 3 + 0] = r.b, items[it * 3 + 1] = r.lo, items[it * 3 + 2] = r.hi;
+      }
+      first += tiles;
     }
     return OKV_OK;
   }

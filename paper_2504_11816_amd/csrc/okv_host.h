@@ -151,6 +151,55 @@ __host__ __device__ inline ItemRange chunk_range(int32_t b, int32_t c, int32_t s
   return r;
 }
 
+// ---- equal stretches -----------------------------------------------------------
+//
+// Unless the caller fixes a split size, the keys of a launch are shared out evenly: the 16-key tiles of
+// all sequences, laid end to end in sequence order, are cut into stretches of `span` tiles, one stretch
+// per wavefront and KV head, and a sequence is cut wherever a stretch ends inside it.  The items (pieces
+// of sequences) that start in stretch j form group j.  There are at most max_groups stretches and none
+// is shorter than min_span tiles unless the whole launch is.  The same arithmetic runs on the host (item
+// count, checks) and in the kernel that builds the item list.
+struct SpanPlan {
+  int64_t span;        // tiles per stretch (>= 1)
+  int32_t n_groups;    // stretches that hold at least one tile
+};
+
+__host__ __device__ inline SpanPlan span_plan(int64_t total_tiles, int32_t max_groups, int32_t min_span) {
+  int64_t g = total_tiles / (min_span > 0 ? min_span : 1);
+  if (g > max_groups) g = max_groups;
+  if (g < 1) g = 1;
+  SpanPlan p;
+  p.span = (total_tiles + g - 1) / g;
+  if (p.span < 1) p.span = 1;
+  p.n_groups = (int32_t)((total_tiles + p.span - 1) / p.span);
+  return p;
+}
+
+// Pieces of a sequence whose tiles are [first, first + tiles) of the stream: it is cut at the multiples
+// of span strictly inside that range.  *k0 receives the first such multiple's index, so that piece c >= 1
+// starts at tile (k0 + c - 1) * span of the stream and piece c ends where piece c + 1 starts.
+__host__ __device__ inline int32_t span_pieces(int64_t first, int64_t tiles, int64_t span, int64_t *k0) {
+  *k0 = first / span + 1;
+  if (tiles <= 0) return 0;
+  const int64_t k_last = (first + tiles - 1) / span;
+  return 1 + (k_last >= *k0 ? (int32_t)(k_last - *k0 + 1) : 0);
+}
+
+// Piece c of a sequence with n keys: keys [lo, hi) and the stretch it starts in.
+__host__ __device__ inline ItemRange span_piece(int32_t b, int32_t c, int32_t n, int64_t first, int64_t tiles,
+                                                int64_t span, int64_t k0, int64_t *group) {
+  const int64_t s = c == 0 ? first : (k0 + c - 1) * span;
+  int64_t e = (k0 + c) * span;
+  if (e > first + tiles) e = first + tiles;
+  *group = s / span;
+  ItemRange r;
+  r.b = b;
+  r.lo = (int32_t)((s - first) << 4);
+  const int64_t hi = (e - first) << 4;
+  r.hi = hi < n ? (int32_t)hi : n;
+  return r;
+}
+
 // ---- block classes (paper §IV-C: a share C_off of the cache lives in host memory) ----
 //
 // With block-granular offload, block ids below `resident` are in HBM (class 0); the others

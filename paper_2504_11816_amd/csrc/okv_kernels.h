@@ -41,8 +41,12 @@ struct AttnLaunch {
   float *part_ml;          // [n_items * H][2]  (max in log2 units, sum)
   int32_t out_fp32;
   int32_t need_merge;      // some sequence has more than one item
-  uint32_t *queue;         // this launch's ticket counter (zeroed by launch_step_advance)
-  int32_t even_units;      // all units are of (nearly) one length: deal them out in fixed rotation, no counter
+  // How the launch's items are shared out: group j = items group_first[j] .. group_first[j + 1] - 1
+  // (relative to item_first), one wavefront per (group, KV head); NULL: every item is a group of its own.
+  const int32_t *group_first = nullptr;   // device, [n_groups + 1]
+  int32_t n_groups = 0;
+  const int32_t *n_groups_dev = nullptr;  // device: the number of groups when the host does not know it
+                           // (the grid is then max_waves wavefronts)
   int32_t max_waves;       // wavefronts of the persistent launch (a multiple of 4)
   // The launch covers items [item_first, item_first + item_count) of the list: all of them, or
   // those of one block class.  `pool` then holds the blocks with ids from id_base on, and
@@ -59,11 +63,17 @@ hipError_t launch_decode_attn(const AttnLaunch &a, hipStream_t stream,
 // shape, batch, out, part_o, part_ml, out_fp32 of `a`).
 hipError_t launch_merge(const AttnLaunch &a, hipStream_t stream);
 
-// ctx_lens[b] += inc; rebuilds chunk_prefix and the item list for split size S; zeroes the
-// n_queues ticket counters.
-hipError_t launch_step_advance(int32_t *ctx_lens, int32_t *chunk_prefix, int4 *item_desc,
-                               uint32_t *queues, int32_t n_queues, int32_t B, int32_t S,
+// ctx_lens[b] += inc; rebuilds chunk_prefix and the item list for split size S (every sequence cut
+// into equal pieces of at most S keys).
+hipError_t launch_step_advance(int32_t *ctx_lens, int32_t *chunk_prefix, int4 *item_desc, int32_t B, int32_t S,
                                int32_t inc, hipStream_t stream);
+
+// The same with the keys of the batch shared out in equal stretches (okv_host.h: span_plan): at most
+// max_groups stretches of at least min_span tiles; group_first[j] = first item of stretch j (one more
+// entry closes the last); plan_out[0..3] = stretches in use, items, tiles per stretch (low 31 bits, rest).
+hipError_t launch_step_advance_spans(int32_t *ctx_lens, int32_t *chunk_prefix, int4 *item_desc, int32_t *group_first,
+                                     int32_t *plan_out, int32_t B, int32_t max_groups, int32_t min_span, int32_t inc,
+                                     hipStream_t stream);
 
 // The same for block classes: runs[r] = (sequence, first position, one past the last position
 // the run can hold, class), sorted by (class, sequence, position); pair_first[cls * B + b] is the
@@ -71,9 +81,8 @@ hipError_t launch_step_advance(int32_t *ctx_lens, int32_t *chunk_prefix, int4 *i
 // counts the items before those of (class, sequence).  seq_total[b] receives the sequence's
 // item count.
 hipError_t launch_step_advance_classes(int32_t *ctx_lens, const int4 *runs, const int32_t *pair_first,
-                                       int32_t *chunk_prefix, int4 *item_desc, int32_t *seq_total,
-                                       uint32_t *queues, int32_t n_queues, int32_t B, int32_t n_cls,
-                                       int32_t S, int32_t inc, hipStream_t stream);
+                                       int32_t *chunk_prefix, int4 *item_desc, int32_t *seq_total, int32_t B,
+                                       int32_t n_cls, int32_t S, int32_t inc, hipStream_t stream);
 
 // Bulk store of new K/V rows (a prompt).  tiles[i] = (sequence, 16-position tile, first slot of
 // the tile to store | one past the last << 8, destination block); the row of position p of

@@ -34,6 +34,7 @@ typedef const int32_t __attribute__((address_space(4))) *const_i32_ptr;   // nev
 #ifndef OKV_WAVES_PER_BLOCK
 #define OKV_WAVES_PER_BLOCK 4
 #endif
+
 constexpr int kWavesPerBlock = OKV_WAVES_PER_BLOCK;   // independent work items per workgroup
 constexpr float kNegBig = -1.0e30f;   // "no key seen yet"; finite so that differences stay finite
 constexpr int kItemLast = 1, kItemWhole = 2;   // flags of a work item (item_desc.w)
@@ -84,9 +85,11 @@ struct AttnArgs {
   float *part_ml;
   const int32_t *block_table, *chunk_prefix;
   const int4 *item_desc;           // [n_items] (sequence, first key, one past last key, flags)
-  uint32_t *queue;                 // ticket counter of this launch, zero when the kernel starts
-  int32_t even_units;              // units are of one length: wavefront w takes units w, w + n_waves, ... instead
-  int32_t H, G, log2_T, tcap, max_blocks, n_units, out_fp32;
+  const int32_t *group_first;      // [n_groups + 1] first item of each group of the launch (relative to item_first), or
+                                   // NULL: group j is item j
+  const int32_t *n_groups_dev;     // NULL, or where the number of groups is to be read (n_groups is then ignored)
+  int32_t n_groups;
+  int32_t H, G, log2_T, tcap, max_blocks, out_fp32;
   int32_t gg;                      // KV heads per group inside a tile slab
   int32_t item_first;              // the launch's first item in item_desc (and in the partial slots)
   int32_t id_base;                 // `pool` holds the blocks with ids id_base, id_base + 1, ...
@@ -128,27 +131,42 @@ constexpr int lds_tile_bytes() {
   return 16 * lds_row_bytes<D>();
 }
 
-// Online-softmax update of one wavefront with one 16-token tile (tok_tile = its first token).
-// MASKED: tokens outside [lo, hi) get score -inf (weight exactly 0; the running maximum stays finite
-// because it starts at kNegBig) and their V rows are read as zero, since unused slots may hold NaN bit
-// patterns.  Only an item's last tiles can need it; the steady-state loop uses the unmasked form.
-template <int D, bool MASKED>
-__device__ __forceinline__ void tile_update_mfma(const Tile<D / 32> &t, const half8_t (&qb)[D / 32], float &m,
-                                                 float &l, floatx4_t (&o)[D / 16], char *ks, char *vs,
-                                                 const int lane, const int tok_tile, const int lo,
-                                                 const int hi, const float scale) {
+// A tile on its way from the load registers (row-major, as loaded) into the wavefront's LDS.  masked
+// (wavefront-uniform; only an item's last tiles need it): V rows of tokens outside [lo, hi) are stored
+// as zeros, since unused slots may hold NaN bit patterns and a weight of zero would not remove those.
+// There is one copy of this code and of tile_update_mfma in the kernel, masks applied by selects: what a
+// launch pays for at its start and end is fetching instructions it runs once, so code size counts, and
+// the selects cost nothing measurable (a wavefront waits for its loads, not for its arithmetic).
+template <int D>
+__device__ __forceinline__ void tile_stage(const Tile<D / 32> &t, char *ks, char *vs, const int lane,
+                                           const int tok_tile, const int lo, const int hi, const bool masked) {
   constexpr int LPR = D / 8, RPL = 64 / LPR, LPT = D / 32, S = lds_row_bytes<D>();
   const int row = lane / LPR, col = lane % LPR;
-  const int quarter = lane >> 4, rho = lane & 15;
-  // the tile as loaded (row-major) into LDS; V rows outside [lo, hi) as zeros, since unused
-  // slots may hold NaN bit patterns and a weight of zero would not remove those
 #pragma unroll
   for (int j = 0; j < LPT; ++j) {
     const int r = row + j * RPL;
-    const bool valid = !MASKED || (tok_tile + r >= lo && tok_tile + r < hi);
     *reinterpret_cast<uint4 *>(ks + r * S + col * 16) = t.k[j];
-    *reinterpret_cast<uint4 *>(vs + r * S + col * 16) = valid ? t.v[j] : make_uint4(0u, 0u, 0u, 0u);
+    *reinterpret_cast<uint4 *>(vs + r * S + col * 16) = t.v[j];
   }
+  if (masked) {                                          // zeros over the V rows that are not the item's
+#pragma unroll
+    for (int j = 0; j < LPT; ++j) {
+      const int r = row + j * RPL;
+      if (tok_tile + r < lo || tok_tile + r >= hi) *reinterpret_cast<uint4 *>(vs + r * S + col * 16) = make_uint4(0u, 0u, 0u, 0u);
+    }
+  }
+}
+
+// Online-softmax update of one wavefront with the 16-token tile that tile_stage put into LDS
+// (tok_tile = its first token).  masked: tokens outside [lo, hi) get score -inf (weight exactly 0; the
+// running maximum stays finite because it starts at kNegBig).
+template <int D>
+__device__ __forceinline__ void tile_update_mfma(const half8_t (&qb)[D / 32], float &m,
+                                                 float &l, floatx4_t (&o)[D / 16], const char *ks, const char *vs,
+                                                 const int lane, const int tok_tile, const int lo,
+                                                 const int hi, const float scale, const bool masked) {
+  constexpr int S = lds_row_bytes<D>();
+  const int quarter = lane >> 4, rho = lane & 15;
   // scores: A = K, lane (quarter, rho) supplies key rho, dims 32 c + 8 quarter .. + 7, as q does
   floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -160,7 +178,7 @@ __device__ __forceinline__ void tile_update_mfma(const Tile<D / 32> &t, const ha
 #pragma unroll
   for (int r = 0; r < 4; ++r) {
     const int tok = tok_tile + 4 * quarter + r;
-    s[r] = (!MASKED || (tok >= lo && tok < hi)) ? acc[r] * scale : -__builtin_inff();
+    s[r] = (!masked || (tok >= lo && tok < hi)) ? acc[r] * scale : -__builtin_inff();
   }
   float mx = fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3]));
   mx = fmaxf(mx, __shfl_xor(mx, 16));
@@ -198,65 +216,69 @@ __device__ __forceinline__ void tile_update_mfma(const Tile<D / 32> &t, const ha
   }
 }
 
-// One work item (a run of keys of one sequence) for one KV head and its R query heads, by one
-// wavefront; `lds` is the wavefront's own 2 * lds_tile_bytes<D>() bytes.
+// A work unit as a wavefront sees it: an item (a run of keys of one sequence) for one KV head.  All
+// fields are wavefront-uniform and come through the scalar cache (constant address space: nothing
+// writes the item list or the block table while this kernel runs).
+template <int PIPE>
+struct Unit {
+  int it, g;                 // item (index in item_desc and in the partial slots), KV head
+  int b, lo, hi, flags;      // sequence, keys [lo, hi) with lo a multiple of 16, kItemLast / kItemWhole
+  int blk0[PIPE];            // pool slices of the first PIPE tiles (clamped to the last tile)
+};
+
+// Persistent wavefronts, each with a share of the launch that was fixed before it started.  The host
+// (or the bookkeeping kernel) cuts the launch's keys, all sequences laid end to end, into as many equal
+// stretches as there are wavefronts per KV head; a stretch is a group of consecutive items (the pieces
+// of the sequences it covers: group j = items group_first[j] .. group_first[j + 1] - 1, or just item j
+// when there is no such table), and the wavefront for (group, head), pair p = group * G + head,
+// reduces them one after the other; wavefront w takes the pairs w, w + n_waves, ...  Every wavefront
+// streams at the same rate (each is bound by the round trip of its own loads: measured within 1.3 % of
+// each other over all compute units, where wavefronts that keep a load in flight all the time differed
+// by 8 % from XCD to XCD and were no faster on average), so equal shares end together; nothing is drawn
+// from a counter and nothing waits.
+//
+// A wavefront treats its items as ONE stream of tiles: PIPE tile buffers in registers, each refilled
+// right after the tile in it has been reduced, and when the current item has no tile left to ask for,
+// the refill is the first tile of the next one.  So the loads of the next item are in flight while the
+// results of this one are written, and a wavefront's stream does not stop at an item boundary.  For
+// that the next item is looked up a whole item ahead (descriptor and first block ids, scalar loads).
+//
+// The body is one loop with one copy of everything -- [A] ask for the next item's first tiles and q,
+// [B] write the current item's results, [C] switch to the next item and reduce its tiles -- entered at
+// [A] for the first item: a launch fetches every instruction it runs from a cold instruction cache
+// (about 0.1 us per 64 bytes), which at 50 us a launch is worth keeping short.
 template <int D, bool PAGED, int PIPE>
-__device__ __forceinline__ void attend_item(const AttnArgs &a, const int it, const int g, const int R,
-                                            const int lane, char *lds) {
+__global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(const AttnArgs a) {
+  __shared__ __attribute__((aligned(16))) char lds_all[kWavesPerBlock][2 * lds_tile_bytes<D>()];
   constexpr int LPR = D / 8, RPL = 64 / LPR, LPT = D / 32;
+  const int lane = threadIdx.x & 63;
+  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+  const uint32_t n_waves = gridDim.x * kWavesPerBlock;
+  const int R = a.H / a.G;
+  // the number of groups is a launch argument, or (for callers that do not know the batch's lengths on
+  // the host) what the bookkeeping kernel left in device memory
+  const const_i32_ptr gf = (const_i32_ptr)(uintptr_t)a.group_first;
+  const uint32_t n_groups = a.n_groups_dev ? (uint32_t)((const_i32_ptr)(uintptr_t)a.n_groups_dev)[0] : (uint32_t)a.n_groups;
+  const uint32_t n_pairs = n_groups * (uint32_t)a.G;
+  uint32_t pair = blockIdx.x * kWavesPerBlock + wave;    // of the unit N below
+  if (pair >= n_pairs) return;
+
   const int row = lane / LPR, col = lane % LPR;
   const int quarter = lane >> 4, rho = lane & 15;
-  char *ks = lds, *vs = lds + lds_tile_bytes<D>();
-  // the item's descriptor, like the block table below, comes through the scalar cache (constant address
-  // space: nothing writes it while this kernel runs), which is a shorter round trip than a vector load
-  const const_i32_ptr dp = (const_i32_ptr)(uintptr_t)(a.item_desc + it);
-  const int b = dp[0], lo = dp[1], hi = dp[2], flags = dp[3];
-  const bool seq_last = (flags & kItemLast) != 0;         // the item ends at the sequence's last key
-  const bool seq_whole = (flags & kItemWhole) != 0;       // and is the sequence's only item
+  char *ks = lds_all[wave], *vs = ks + lds_tile_bytes<D>();
 
-  // The item that ends at the sequence's last key also stores this step's K/V rows
-  // (paper §II-A: keys and values of every processed token are kept).  The rows are
-  // patched into the tile in registers, so the attention below does not depend on
-  // reading its own store back; the store itself is issued after the reduction.
-  const int pos = hi - 1;
-  const bool appending = a.k_new != nullptr && seq_last;
-  uint4 k_row = make_uint4(0u, 0u, 0u, 0u), v_row = k_row;
-  if (appending) {
-    const size_t at = ((size_t)b * a.G + g) * LPR + col;
-    k_row = reinterpret_cast<const uint4 *>(a.k_new)[at];
-    v_row = reinterpret_cast<const uint4 *>(a.v_new)[at];
-  }
-
-  // q as the B operand of the score product: lane (quarter, rho) holds head rho, dims 32 c + 8 quarter .. + 7;
-  // columns past the group's heads are zero and never stored
-  half8_t qb[D / 32];
-#pragma unroll
-  for (int c = 0; c < D / 32; ++c) {
-    uint4 x = make_uint4(0u, 0u, 0u, 0u);
-    if (rho < R)
-      x = *reinterpret_cast<const uint4 *>(a.q + ((size_t)b * a.H + (size_t)g * R + rho) * D + 32 * c + 8 * quarter);
-    qb[c] = __builtin_bit_cast(half8_t, x);
-  }
-  float m = kNegBig, l = 0.f;
-  floatx4_t o[D / 16];
-#pragma unroll
-  for (int i = 0; i < D / 16; ++i) o[i] = floatx4_t{0.f, 0.f, 0.f, 0.f};
-
-  const int t0 = lo >> 4, t1 = (hi + 15) >> 4;               // 16-token tiles; lo is a multiple of 16
-  const TileAddr ta = tile_addr<D>(a.G, a.gg, a.tcap, g);
-  // Block id of a tile: a wavefront-uniform (scalar) load from the block table.  The index
-  // is clamped so that look-ahead past the item's last tile stays inside the table.
-  // The table is read through the constant address space: the kernel also stores (outputs,
-  // appended rows) and without that promise the compiler would turn these look-ups into
-  // vector loads, which share the tile loads' counter and would drain the pipeline.
-  const const_i32_ptr tbl_row = (const_i32_ptr)(uintptr_t)(a.block_table + (size_t)b * a.max_blocks);
-  auto blk_of = [&](int tile) -> int {
+  // Block id of a tile: a wavefront-uniform (scalar) load from the block table.  The table is read
+  // through the constant address space: the kernel also stores (outputs, appended rows) and without
+  // that promise the compiler would turn these look-ups into vector loads, which share the tile loads'
+  // counter and would drain the pipeline.
+  auto blk_of = [&](int b, int tile) -> int {
     if (!PAGED) return b;
+    const const_i32_ptr tbl = (const_i32_ptr)(uintptr_t)(a.block_table + (size_t)b * a.max_blocks);
     int bi = (tile << 4) >> a.log2_T;
     bi = bi < a.max_blocks ? bi : a.max_blocks - 1;
-    return tbl_row[bi] - a.id_base;
+    return tbl[bi] - a.id_base;
   };
-  auto load_tile = [&](Tile<LPT> &t, int tile, int blk) {
+  auto load_tile = [&](Tile<LPT> &t, const TileAddr &ta, int tile, int blk) {
     const int64_t base = slab_base<PAGED>(ta, blk, tile);
     const uint4 *kp = reinterpret_cast<const uint4 *>(a.pool + base + ta.head_k) + lane;
     const uint4 *vp = reinterpret_cast<const uint4 *>(a.pool + base + ta.head_v) + lane;
@@ -265,151 +287,178 @@ __device__ __forceinline__ void attend_item(const AttnArgs &a, const int it, con
 #pragma unroll
     for (int j = 0; j < LPT; ++j) t.v[j] = vp[j * 64];
   };
-  // Steady state: every tile is full (only the item's last tile can stick out of [lo, hi)
-  // or hold the appended row, and the last tile is always reduced in the drain below).
-  auto update = [&](const Tile<LPT> &t, int tile) {
-    tile_update_mfma<D, false>(t, qb, m, l, o, ks, vs, lane, tile << 4, lo, hi, a.scale_log2e);
-  };
-  // Drain: masked form for every tile (at most 2 * PIPE - 1 of them); the appended row
-  // replaces whatever the slot held.
-  auto update_last = [&](Tile<LPT> &t, int tile) {
-    if (appending && tile == (pos >> 4)) {
-#pragma unroll
-      for (int j = 0; j < LPT; ++j)
-        if ((tile << 4) + row + j * RPL == pos) {
-          t.k[j] = k_row;
-          t.v[j] = v_row;
-        }
-    }
-    tile_update_mfma<D, true>(t, qb, m, l, o, ks, vs, lane, tile << 4, lo, hi, a.scale_log2e);
-  };
 
-  // PIPE tiles are in flight ahead of the one being reduced.  The steady-state loop has no
-  // conditional loads, so each wait covers exactly the tile it needs and the younger loads
-  // stay in flight; block ids are fetched one refill ahead through the scalar cache, which
-  // has its own counter.
+  // the items of the pair: item .. item_end - 1 (relative to the launch's first item)
+  int item = gf ? gf[pair / (uint32_t)a.G] : (int)(pair / (uint32_t)a.G);
+  int item_end = gf ? gf[pair / (uint32_t)a.G + 1] : item + 1;
+  bool has_next = true;                                  // N is a unit (else the wavefront's share is done)
+  Unit<PIPE> N, C;                                       // the unit whose first tiles are asked for next; the one being reduced
+  bool live = false;                                     // C holds a unit whose results are still to be written
+  TileAddr ta = tile_addr<D>(a.G, a.gg, a.tcap, 0);
   Tile<LPT> buf[PIPE];
-  int t = t0;
-  if (t1 - t0 >= 2 * PIPE) {
+  uint4 q_next[D / 32];                                  // q of N: the B operand of the score product, lane (quarter, rho) holds
+                                                         // head rho, dims 32 c + 8 quarter .. + 7; columns past the group's heads are zero
+  float m = kNegBig, l = 0.f;
+  floatx4_t o[D / 16];
+  uint4 k_row = make_uint4(0u, 0u, 0u, 0u), v_row = k_row;
+  C.it = C.g = C.b = C.lo = C.hi = C.flags = 0;
+
+  for (;;) {
+    // N's descriptor and first block ids: for the first unit waited for here; for the others asked for
+    // a whole item earlier ([C] below)
+    if (!live) {
+      N.g = (int)(pair % (uint32_t)a.G);
+      N.it = a.item_first + item;
+      const const_i32_ptr dp = (const_i32_ptr)(uintptr_t)(a.item_desc + N.it);
+      N.b = dp[0], N.lo = dp[1], N.hi = dp[2], N.flags = dp[3];
+#pragma unroll
+      for (int i = 0; i < PIPE; ++i) N.blk0[i] = blk_of(N.b, min((N.lo >> 4) + i, (N.hi - 1) >> 4));
+    }
+    // [A] the next unit's first tiles and its q
+    const TileAddr ta_next = tile_addr<D>(a.G, a.gg, a.tcap, N.g);
+    if (has_next) {
+#pragma unroll
+      for (int i = 0; i < PIPE; ++i) load_tile(buf[i], ta_next, min((N.lo >> 4) + i, (N.hi - 1) >> 4), N.blk0[i]);
+#pragma unroll
+      for (int c = 0; c < D / 32; ++c) {
+        q_next[c] = make_uint4(0u, 0u, 0u, 0u);
+        if (rho < R)
+          q_next[c] = *reinterpret_cast<const uint4 *>(a.q + ((size_t)N.b * a.H + (size_t)N.g * R + rho) * D + 32 * c + 8 * quarter);
+      }
+    }
+    __builtin_amdgcn_sched_barrier(0);
+
+    // [B] the results of C.  The four quarters of the wavefront saw different keys of every tile: their
+    // sums add up (the maximum is common to them already).  Lane (quarter, rho) holds, of head rho, the
+    // dims 32 u + 8 quarter .. + 7 for every u: dim 32 u + 8 quarter + 2 r + par sits in o[2 u + par][r].
+    // A sequence that is a single item is normalised and written to `out`; otherwise the item's sums,
+    // maximum and weight go to its slot of the partial results, as floats.
+    if (live) {
+      const bool seq_whole = (C.flags & kItemWhole) != 0;
+      float lt = l;
+      lt += __shfl_xor(lt, 16);
+      lt += __shfl_xor(lt, 32);
+      if (rho < R) {
+        const int h = C.g * R + rho;
+        const float inv = seq_whole ? 1.0f / lt : 1.0f;
+        const bool as_float = !seq_whole || a.out_fp32;
+        float *fdst = seq_whole ? reinterpret_cast<float *>(a.out) + ((size_t)C.b * a.H + h) * D
+                                : a.part_o + ((size_t)C.it * a.H + h) * D;
+        uint16_t *hdst = reinterpret_cast<uint16_t *>(a.out) + ((size_t)C.b * a.H + h) * D;
+#pragma unroll
+        for (int u = 0; u < D / 32; ++u) {
+          float ot[8];
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            ot[2 * r] = o[2 * u][r] * inv;
+            ot[2 * r + 1] = o[2 * u + 1][r] * inv;
+          }
+          const int dim0 = 32 * u + 8 * quarter;
+          if (as_float) {
+            float4 *dst = reinterpret_cast<float4 *>(fdst + dim0);
+            dst[0] = make_float4(ot[0], ot[1], ot[2], ot[3]);
+            dst[1] = make_float4(ot[4], ot[5], ot[6], ot[7]);
+          } else {
+            half2_t h0 = {(_Float16)ot[0], (_Float16)ot[1]};
+            half2_t h1 = {(_Float16)ot[2], (_Float16)ot[3]};
+            half2_t h2 = {(_Float16)ot[4], (_Float16)ot[5]};
+            half2_t h3 = {(_Float16)ot[6], (_Float16)ot[7]};
+            *reinterpret_cast<uint4 *>(hdst + dim0) = make_uint4(__builtin_bit_cast(uint32_t, h0), __builtin_bit_cast(uint32_t, h1),
+                                                                 __builtin_bit_cast(uint32_t, h2), __builtin_bit_cast(uint32_t, h3));
+          }
+        }
+        if (!seq_whole && quarter == 0)
+          *reinterpret_cast<float2 *>(a.part_ml + ((size_t)C.it * a.H + h) * 2) = make_float2(m, lt);
+      }
+      // The item that ends at the sequence's last key also stores this step's K/V rows (paper §II-A: keys
+      // and values of every processed token are kept): row 0 of the load layout stores the K row, row 1 the V row.
+      const int pos = C.hi - 1;
+      if (a.k_new != nullptr && (C.flags & kItemLast) && row < 2) {
+        const int blk = blk_of(C.b, pos >> 4);
+        const int64_t in_slab = (row == 0 ? ta.head_k : ta.head_v) + (int64_t)(pos & 15) * D + col * 8;
+        const uint4 val = row == 0 ? k_row : v_row;
+        *reinterpret_cast<uint4 *>(a.pool_store + slab_base<PAGED>(ta, blk, pos >> 4) + in_slab) = val;
+        if (a.pool_mirror)
+          *reinterpret_cast<uint4 *>(a.pool_mirror + slab_base<PAGED>(ta, blk + (PAGED ? a.mirror_shift : 0), pos >> 4) + in_slab) = val;
+      }
+    }
+    if (!has_next) break;
+
+    // [C] N becomes the unit being reduced; the unit after it is looked up now, a whole item before its
+    // first tile is asked for: the next item of the pair, else the first item of the wavefront's next pair
+    C = N;
+    ta = ta_next;
+    live = true;
+    if (item + 1 < item_end) {
+      ++item;
+    } else {
+      pair += n_waves;
+      has_next = pair < n_pairs;
+      if (has_next) {
+        item = gf ? gf[pair / (uint32_t)a.G] : (int)(pair / (uint32_t)a.G);
+        item_end = gf ? gf[pair / (uint32_t)a.G + 1] : item + 1;
+      }
+    }
+    if (has_next) {
+      N.g = (int)(pair % (uint32_t)a.G);
+      N.it = a.item_first + item;
+      const const_i32_ptr dp = (const_i32_ptr)(uintptr_t)(a.item_desc + N.it);
+      N.b = dp[0], N.lo = dp[1], N.hi = dp[2], N.flags = dp[3];
+#pragma unroll
+      for (int i = 0; i < PIPE; ++i) N.blk0[i] = blk_of(N.b, min((N.lo >> 4) + i, (N.hi - 1) >> 4));
+    }
+    const int b = C.b, lo = C.lo, hi = C.hi;
+    // The rows to append are patched into the tile in registers, so the attention does not depend on
+    // reading its own store back; the store itself is issued with the results ([B]).
+    const int pos = hi - 1;
+    const bool appending = a.k_new != nullptr && (C.flags & kItemLast) != 0;
+    if (appending) {
+      const size_t at = ((size_t)b * a.G + C.g) * LPR + col;
+      k_row = reinterpret_cast<const uint4 *>(a.k_new)[at];
+      v_row = reinterpret_cast<const uint4 *>(a.v_new)[at];
+    }
+    half8_t qb[D / 32];
+#pragma unroll
+    for (int c = 0; c < D / 32; ++c) qb[c] = __builtin_bit_cast(half8_t, q_next[c]);
+    m = kNegBig, l = 0.f;
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) o[i] = floatx4_t{0.f, 0.f, 0.f, 0.f};
+
+    // Tiles go through the buffers in groups of PIPE (tile t0 + k sits in buffer k % PIPE).  Every group
+    // but the last holds full tiles only (an item starts on a tile boundary, so only its last tile can
+    // stick out of [lo, hi) or hold the appended row) and refills its buffers from the item itself: each
+    // wait covers exactly the tile it needs and the younger loads stay in flight; block ids are fetched
+    // one refill ahead through the scalar cache, which has its own counter.  A refill past the item's
+    // last tile (only when the tile count is not a multiple of PIPE) asks for the last tile again.  The
+    // last group's buffers are refilled at [A], from the next item.
+    const int t1 = (hi + 15) >> 4, last_tile = t1 - 1;
     int next_blk[PIPE];
 #pragma unroll
-    for (int i = 0; i < PIPE; ++i) load_tile(buf[i], t0 + i, blk_of(t0 + i));
-#pragma unroll
-    for (int i = 0; i < PIPE; ++i) next_blk[i] = blk_of(t0 + i + PIPE);
-    for (; t + 2 * PIPE <= t1; t += PIPE) {
+    for (int i = 0; i < PIPE; ++i) next_blk[i] = blk_of(b, min((lo >> 4) + PIPE + i, last_tile));
+    for (int t = lo >> 4; t < t1; t += PIPE) {
+      const bool last = t + PIPE >= t1;
 #pragma unroll
       for (int i = 0; i < PIPE; ++i) {
-        update(buf[i], t + i);
+        if (i == 0 || t + i < t1) {                      // else a second request for the last tile: skipped
+          if (last && appending && t + i == (pos >> 4)) {
+#pragma unroll
+            for (int j = 0; j < LPT; ++j)
+              if (((t + i) << 4) + row + j * RPL == pos) {
+                buf[i].k[j] = k_row;
+                buf[i].v[j] = v_row;
+              }
+          }
+          tile_stage<D>(buf[i], ks, vs, lane, (t + i) << 4, lo, hi, last);
+          tile_update_mfma<D>(qb, m, l, o, ks, vs, lane, (t + i) << 4, lo, hi, a.scale_log2e, last);
+        }
         __builtin_amdgcn_sched_barrier(0);    // keep the refill behind the reduce that frees it,
-        load_tile(buf[i], t + i + PIPE, next_blk[i]);
-        next_blk[i] = blk_of(t + i + 2 * PIPE);
+        if (!last) {
+          load_tile(buf[i], ta, min(t + i + PIPE, last_tile), next_blk[i]);
+          next_blk[i] = blk_of(b, min(t + i + 2 * PIPE, last_tile));
+        }
         __builtin_amdgcn_sched_barrier(0);    // and ahead of the next tile's reduce
       }
     }
-  } else {
-#pragma unroll
-    for (int i = 0; i < PIPE; ++i)
-      if (t0 + i < t1) load_tile(buf[i], t0 + i, blk_of(t0 + i));
-  }
-  // drain: at most 2 * PIPE - 1 tiles are left, the first PIPE of them in flight
-#pragma unroll
-  for (int i = 0; i < PIPE; ++i)
-    if (t + i < t1) {
-      update_last(buf[i], t + i);
-      if (t + i + PIPE < t1) load_tile(buf[i], t + i + PIPE, blk_of(t + i + PIPE));
-    }
-#pragma unroll
-  for (int i = 0; i < PIPE; ++i)
-    if (t + PIPE + i < t1) update_last(buf[i], t + PIPE + i);
-
-  // the four quarters of the wavefront saw different keys of every tile: their sums add up (the
-  // maximum is common to them already).  Lane (quarter, rho) holds, of head rho, the dims
-  // 32 u + 8 quarter .. + 7 for every u: dim 32 u + 8 quarter + 2 r + par sits in o[2 u + par][r].
-  float lt = l;
-  lt += __shfl_xor(lt, 16);
-  lt += __shfl_xor(lt, 32);
-  if (rho < R) {
-    const int h = g * R + rho;
-    const float inv = 1.0f / lt;
-#pragma unroll
-    for (int u = 0; u < D / 32; ++u) {
-      float ot[8];
-#pragma unroll
-      for (int r = 0; r < 4; ++r) {
-        ot[2 * r] = o[2 * u][r];
-        ot[2 * r + 1] = o[2 * u + 1][r];
-      }
-      const int dim0 = 32 * u + 8 * quarter;
-      if (seq_whole) {
-        const size_t at = ((size_t)b * a.H + h) * D + dim0;
-        if (a.out_fp32) {
-          float4 *dst = reinterpret_cast<float4 *>(reinterpret_cast<float *>(a.out) + at);
-          dst[0] = make_float4(ot[0] * inv, ot[1] * inv, ot[2] * inv, ot[3] * inv);
-          dst[1] = make_float4(ot[4] * inv, ot[5] * inv, ot[6] * inv, ot[7] * inv);
-        } else {
-          half2_t h0 = {(_Float16)(ot[0] * inv), (_Float16)(ot[1] * inv)};
-          half2_t h1 = {(_Float16)(ot[2] * inv), (_Float16)(ot[3] * inv)};
-          half2_t h2 = {(_Float16)(ot[4] * inv), (_Float16)(ot[5] * inv)};
-          half2_t h3 = {(_Float16)(ot[6] * inv), (_Float16)(ot[7] * inv)};
-          uint4 pk = make_uint4(__builtin_bit_cast(uint32_t, h0), __builtin_bit_cast(uint32_t, h1),
-                                __builtin_bit_cast(uint32_t, h2), __builtin_bit_cast(uint32_t, h3));
-          *reinterpret_cast<uint4 *>(reinterpret_cast<uint16_t *>(a.out) + at) = pk;
-        }
-      } else {
-        const size_t slot = (size_t)it * a.H + h;
-        float4 *dst = reinterpret_cast<float4 *>(a.part_o + slot * D + dim0);
-        dst[0] = make_float4(ot[0], ot[1], ot[2], ot[3]);
-        dst[1] = make_float4(ot[4], ot[5], ot[6], ot[7]);
-      }
-    }
-    if (!seq_whole && quarter == 0)
-      *reinterpret_cast<float2 *>(a.part_ml + ((size_t)it * a.H + h) * 2) = make_float2(m, lt);
-  }
-
-  if (appending && row < 2) {                          // row 0 stores the K row, row 1 the V row
-    const int blk = blk_of(pos >> 4);
-    const int64_t in_slab = (row == 0 ? ta.head_k : ta.head_v) + (int64_t)(pos & 15) * D + col * 8;
-    const uint4 val = row == 0 ? k_row : v_row;
-    *reinterpret_cast<uint4 *>(a.pool_store + slab_base<PAGED>(ta, blk, pos >> 4) + in_slab) = val;
-    if (a.pool_mirror)
-      *reinterpret_cast<uint4 *>(a.pool_mirror + slab_base<PAGED>(ta, blk + (PAGED ? a.mirror_shift : 0), pos >> 4) + in_slab) = val;
-  }
-}
-
-// Persistent wavefronts: each one starts on the unit (item, KV head) with its own number
-// and then draws further units from a ticket counter until none are left, so a faster
-// compute unit or XCD simply takes more of them (workgroups are dealt to the eight XCDs in
-// fixed rotation, which a static split cannot correct).  A launch that has no more units
-// than wavefronts never touches the counter: same-address atomics are served one at a
-// time, and a burst of them at the start would cost more than it balances.  Every
-// wavefront leaves as soon as its ticket is past the end; nothing ever waits.  When all units are
-// of one length (a batch of equal sequences) there is nothing to balance but the compute units' own
-// small differences, and the draw's round trip with nothing in flight costs more than that: such
-// launches deal the units out in fixed rotation (4096 units of 512 keys: 181 against 192-199 us; the
-// same rotation on a ragged batch: 434 against 414).  (Eight counters
-// in cache lines of their own, each dealing runs of eight neighbouring units, measured the same
-// within 2 % either way as this single one on launches of 2048 to 8192 units: what a draw costs
-// a wavefront is the round trip, not the queueing behind other draws.)
-template <int D, bool PAGED, int PIPE>
-__global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(const AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) char lds[kWavesPerBlock][2 * lds_tile_bytes<D>()];
-  const int lane = threadIdx.x & 63;
-  const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const uint32_t n_waves = gridDim.x * kWavesPerBlock;
-  const int R = a.H / a.G;
-  uint32_t ticket = blockIdx.x * kWavesPerBlock + wave;
-  while (ticket < (uint32_t)a.n_units) {
-    const int it = (int)(ticket / (uint32_t)a.G);
-    const int g = (int)(ticket - (uint32_t)it * (uint32_t)a.G);
-    attend_item<D, PAGED, PIPE>(a, a.item_first + it, g, R, lane, lds[wave]);
-    if (n_waves >= (uint32_t)a.n_units) break;           // every unit had its own wavefront
-    if (a.even_units) {                                  // nothing to balance: skip the draw's round trip
-      ticket += n_waves;
-      continue;
-    }
-    uint32_t drawn = 0;
-    if (lane == 0) drawn = atomicAdd(a.queue, 1u);
-    ticket = n_waves + __builtin_amdgcn_readfirstlane(drawn);
   }
 }
 
@@ -491,29 +540,22 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(const AttnArgs a) {
 
 // Tiles in flight per wavefront.  What counts is bytes: about 8 KiB per wavefront (one tile at d = 128,
 // two at d = 64) times a thousand wavefronts is where the memory system runs best (6.4-6.6 TB/s); twice
-// that measured 5.9-6.0, half of it (one tile at d = 64) 4.4.  When wavefronts work through many units
-// each (more than two per wavefront: ragged or very large batches cut into short items) they spend part
-// of their time between units with nothing in flight (the ticket draw), and twice the depth measured
-// 3-7 % faster there.
+// that measured 5.9-6.0, half of it (one tile at d = 64) 4.4.
+#ifndef OKV_PIPE_MULT
+#define OKV_PIPE_MULT 1
+#endif
 template <int D>
 constexpr int base_depth() {
-  return D == 64 ? 2 : 1;
-}
-
-template <int D, bool PAGED>
-hipError_t launch_split_depth(const AttnArgs &args, bool deep, dim3 grid, hipStream_t stream) {
-  if (deep)
-    hipLaunchKernelGGL((attn_split_mfma_kernel<D, PAGED, 2 * base_depth<D>()>), grid, dim3(kWavesPerBlock * 64), 0, stream, args);
-  else
-    hipLaunchKernelGGL((attn_split_mfma_kernel<D, PAGED, base_depth<D>()>), grid, dim3(kWavesPerBlock * 64), 0, stream, args);
-  return hipGetLastError();
+  return (D == 64 ? 2 : 1) * OKV_PIPE_MULT;
 }
 
 template <int D>
 hipError_t launch_split(const AttnArgs &args, bool paged, dim3 grid, hipStream_t stream) {
-  const int64_t n_waves = (int64_t)grid.x * kWavesPerBlock;
-  const bool deep = !args.even_units && args.n_units > 2 * n_waves;   // units in fixed rotation leave no gaps to cover
-  return paged ? launch_split_depth<D, true>(args, deep, grid, stream) : launch_split_depth<D, false>(args, deep, grid, stream);
+  if (paged)
+    hipLaunchKernelGGL((attn_split_mfma_kernel<D, true, base_depth<D>()>), grid, dim3(kWavesPerBlock * 64), 0, stream, args);
+  else
+    hipLaunchKernelGGL((attn_split_mfma_kernel<D, false, base_depth<D>()>), grid, dim3(kWavesPerBlock * 64), 0, stream, args);
+  return hipGetLastError();
 }
 
 }  // namespace
@@ -535,15 +577,15 @@ AttnArgs make_args(const AttnLaunch &a) {
   args.block_table = a.batch.block_table;
   args.chunk_prefix = a.batch.chunk_prefix;
   args.item_desc = a.batch.item_desc;
-  args.queue = a.queue;
-  args.even_units = a.even_units;
+  args.group_first = a.group_first;
+  args.n_groups_dev = a.n_groups_dev;
+  args.n_groups = a.group_first ? a.n_groups : a.item_count;
   args.H = s.H;
   args.G = s.G;
   args.log2_T = s.log2_T;
   args.tcap = s.tcap;
   args.gg = s.gg;
   args.max_blocks = s.max_blocks;
-  args.n_units = a.item_count * s.G;
   args.out_fp32 = a.out_fp32;
   args.item_first = a.item_first;
   args.id_base = a.id_base;
@@ -564,10 +606,10 @@ hipError_t launch_decode_attn(const AttnLaunch &a, hipStream_t stream, hipEvent_
     return hipErrorInvalidValue;
   const AttnArgs args = make_args(a);
   const int R = s.H / s.G;
-  // persistent launch: no more wavefronts than there are units, no more than a.max_waves
-  const int64_t want = ((int64_t)args.n_units + kWavesPerBlock - 1) / kWavesPerBlock;
+  // persistent launch: no more wavefronts than there are (group, KV head) pairs, no more than a.max_waves
+  const int64_t want = ((int64_t)args.n_groups * s.G + kWavesPerBlock - 1) / kWavesPerBlock;
   const int64_t cap = std::max<int64_t>(1, a.max_waves / kWavesPerBlock);
-  dim3 grid((unsigned)std::min(want, cap));
+  dim3 grid((unsigned)(a.n_groups_dev ? cap : std::min(want, cap)));
   hipError_t e;
   if (ev_begin && (e = hipEventRecord(ev_begin, stream)) != hipSuccess) return e;
   if (R < 1 || R > 16 || R * s.G != s.H)
@@ -604,12 +646,10 @@ constexpr int kStepThreads = 256;
 
 __global__ __launch_bounds__(kStepThreads) void step_advance_kernel(int32_t *ctx_lens,
                                                                    int32_t *chunk_prefix,
-                                                                   int4 *item_desc, uint32_t *queues,
-                                                                   int32_t n_queues, int32_t B,
+                                                                   int4 *item_desc, int32_t B,
                                                                    int32_t S, int32_t inc) {
   __shared__ int32_t part[kStepThreads];
   const int tid = threadIdx.x;
-  for (int i = tid; i < n_queues; i += kStepThreads) queues[i] = 0u;   // one ticket counter per layer
   const int per = (B + kStepThreads - 1) / kStepThreads;     // consecutive sequences per thread
   const int b0 = tid * per, b1 = min(B, b0 + per);
   int32_t mine = 0;
@@ -644,16 +684,89 @@ __global__ __launch_bounds__(kStepThreads) void step_advance_kernel(int32_t *ctx
   if (tid == kStepThreads - 1) chunk_prefix[B] = part[tid];
 }
 
+// The bookkeeping for equal stretches: lengths advance, the tiles of all sequences are counted and
+// laid end to end, cut into stretches (span_plan), every sequence into the pieces the cuts leave
+// (span_pieces), and the first item of every stretch is noted in group_first.  plan_out receives
+// (number of stretches in use, number of items, tiles per stretch as two halves).
+__global__ __launch_bounds__(kStepThreads) void step_advance_spans_kernel(int32_t *ctx_lens, int32_t *chunk_prefix,
+                                                                         int4 *item_desc, int32_t *group_first,
+                                                                         int32_t *plan_out, int32_t B,
+                                                                         int32_t max_groups, int32_t min_span,
+                                                                         int32_t inc) {
+  __shared__ int64_t part[kStepThreads];
+  const int tid = threadIdx.x;
+  const int per = (B + kStepThreads - 1) / kStepThreads;     // consecutive sequences per thread
+  const int b0 = min(B, tid * per), b1 = min(B, b0 + per);
+  int64_t mine = 0;
+  for (int b = b0; b < b1; ++b) {
+    const int32_t n = ctx_lens[b] + inc;
+    if (inc) ctx_lens[b] = n;                                  // inc == 0: the lengths are only read
+    mine += (n + 15) >> 4;
+  }
+  part[tid] = mine;
+  __syncthreads();
+  for (int off = 1; off < kStepThreads; off <<= 1) {           // inclusive scan: tiles up to and including this thread's
+    const int64_t add = tid >= off ? part[tid - off] : 0;
+    __syncthreads();
+    part[tid] += add;
+    __syncthreads();
+  }
+  const int64_t tile_first = part[tid] - mine;
+  const SpanPlan plan = span_plan(part[kStepThreads - 1], max_groups, min_span);
+  __syncthreads();
+  int64_t items_mine = 0, first = tile_first;
+  for (int b = b0; b < b1; ++b) {
+    const int64_t tiles = (ctx_lens[b] + 15) >> 4;
+    int64_t k0;
+    items_mine += span_pieces(first, tiles, plan.span, &k0);
+    first += tiles;
+  }
+  part[tid] = items_mine;
+  __syncthreads();
+  for (int off = 1; off < kStepThreads; off <<= 1) {
+    const int64_t add = tid >= off ? part[tid - off] : 0;
+    __syncthreads();
+    part[tid] += add;
+    __syncthreads();
+  }
+  int32_t at = (int32_t)(part[tid] - items_mine);
+  first = tile_first;
+  for (int b = b0; b < b1; ++b) {
+    chunk_prefix[b] = at;
+    const int32_t n = ctx_lens[b];
+    const int64_t tiles = (n + 15) >> 4;
+    int64_t k0;
+    const int32_t cnt = span_pieces(first, tiles, plan.span, &k0);
+    for (int32_t c = 0; c < cnt; ++c) {
+      int64_t group;
+      const ItemRange r = span_piece(b, c, n, first, tiles, plan.span, k0, &group);
+      const int32_t flags = (c == cnt - 1 ? kItemLast : 0) | (cnt == 1 ? kItemWhole : 0);
+      item_desc[at + c] = make_int4(r.b, r.lo, r.hi, flags);
+      if (c > 0 || first % plan.span == 0) group_first[group] = at + c;   // the item opens its stretch
+    }
+    at += cnt;
+    first += tiles;
+  }
+  if (tid == kStepThreads - 1) {
+    const int32_t n_items = (int32_t)part[tid];
+    chunk_prefix[B] = n_items;
+    group_first[plan.n_groups] = n_items;
+    plan_out[0] = plan.n_groups;
+    plan_out[1] = n_items;
+    plan_out[2] = (int32_t)(plan.span & 0x7fffffff);
+    plan_out[3] = (int32_t)(plan.span >> 31);
+  }
+}
+
 // The same bookkeeping when a sequence is cut into runs of one block class each.  Pairs
 // (class, sequence) take the place of sequences: thread t owns a stretch of consecutive
 // pairs, counts their items, the counts are scanned, and the items are written class by
 // class.  chunk_prefix doubles as the store of the per-pair counts between the passes.
 __global__ __launch_bounds__(kStepThreads) void step_advance_classes_kernel(
     int32_t *ctx_lens, const int4 *runs, const int32_t *pair_first, int32_t *chunk_prefix, int4 *item_desc,
-    int32_t *seq_total, uint32_t *queues, int32_t n_queues, int32_t B, int32_t n_cls, int32_t S, int32_t inc) {
+    int32_t *seq_total, int32_t B, int32_t n_cls, int32_t S, int32_t inc) {
   __shared__ int32_t part[kStepThreads];
   const int tid = threadIdx.x;
-  for (int i = tid; i < n_queues; i += kStepThreads) queues[i] = 0u;
   for (int b = tid; b < B; b += kStepThreads) ctx_lens[b] += inc;
   __syncthreads();
   const int P = n_cls * B;
@@ -784,20 +897,26 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const uint4 *src, int64
 
 }  // namespace
 
-hipError_t launch_step_advance(int32_t *ctx_lens, int32_t *chunk_prefix, int4 *item_desc,
-                               uint32_t *queues, int32_t n_queues, int32_t B, int32_t S,
+hipError_t launch_step_advance(int32_t *ctx_lens, int32_t *chunk_prefix, int4 *item_desc, int32_t B, int32_t S,
                                int32_t inc, hipStream_t stream) {
-  hipLaunchKernelGGL(step_advance_kernel, dim3(1), dim3(kStepThreads), 0, stream, ctx_lens,
-                     chunk_prefix, item_desc, queues, n_queues, B, S, inc);
+  hipLaunchKernelGGL(step_advance_kernel, dim3(1), dim3(kStepThreads), 0, stream, ctx_lens, chunk_prefix, item_desc,
+                     B, S, inc);
+  return hipGetLastError();
+}
+
+hipError_t launch_step_advance_spans(int32_t *ctx_lens, int32_t *chunk_prefix, int4 *item_desc, int32_t *group_first,
+                                     int32_t *plan_out, int32_t B, int32_t max_groups, int32_t min_span, int32_t inc,
+                                     hipStream_t stream) {
+  hipLaunchKernelGGL(step_advance_spans_kernel, dim3(1), dim3(kStepThreads), 0, stream, ctx_lens, chunk_prefix,
+                     item_desc, group_first, plan_out, B, max_groups, min_span, inc);
   return hipGetLastError();
 }
 
 hipError_t launch_step_advance_classes(int32_t *ctx_lens, const int4 *runs, const int32_t *pair_first,
-                                       int32_t *chunk_prefix, int4 *item_desc, int32_t *seq_total,
-                                       uint32_t *queues, int32_t n_queues, int32_t B, int32_t n_cls,
-                                       int32_t S, int32_t inc, hipStream_t stream) {
+                                       int32_t *chunk_prefix, int4 *item_desc, int32_t *seq_total, int32_t B,
+                                       int32_t n_cls, int32_t S, int32_t inc, hipStream_t stream) {
   hipLaunchKernelGGL(step_advance_classes_kernel, dim3(1), dim3(kStepThreads), 0, stream, ctx_lens, runs,
-                     pair_first, chunk_prefix, item_desc, seq_total, queues, n_queues, B, n_cls, S, inc);
+                     pair_first, chunk_prefix, item_desc, seq_total, B, n_cls, S, inc);
   return hipGetLastError();
 }
 

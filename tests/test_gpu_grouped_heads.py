@@ -172,7 +172,7 @@ def test_streamed_layers_are_bit_identical_to_resident_ones():
 
 
 def test_more_work_units_than_wavefronts_all_outputs():
-    say("grouped heads: ticket queue")
+    say("grouped heads: more pairs than wavefronts")
     ctx = synth.ragged_ctx_lens(48, 200, 420, 261)
     st = build_stack(L=1, H=64, G=8, d=128, T=16, ctx_before=ctx, cap_tokens=448, out_dtype=1, seed=263,
                      split_tokens=16)

@@ -68,9 +68,9 @@ def test_result_does_not_depend_on_the_split_size(split):
 
 @pytest.mark.parametrize("H,G,d", [(8, 4, 64), (16, 16, 128)])
 def test_more_work_units_than_wavefronts_all_outputs(H, G, d):
-    # Thousands of 16-key items: most units are drawn from the ticket counter by
-    # wavefronts that have already finished one, and every sequence needs the merge.
-    say(f"ticket queue H={H} G={G} d={d}")
+    # Thousands of 16-key items, each a group of its own: every wavefront works through several
+    # (item, KV head) pairs in fixed rotation, and every sequence needs the merge.
+    say(f"more pairs than wavefronts H={H} G={G} d={d}")
     ctx = synth.ragged_ctx_lens(48, 200, 420, 77)
     st = build_stack(L=1, H=H, G=G, d=d, T=16, ctx_before=ctx, cap_tokens=448, out_dtype=1, seed=79,
                      split_tokens=16)
@@ -82,8 +82,8 @@ def test_more_work_units_than_wavefronts_all_outputs(H, G, d):
 
 @pytest.mark.parametrize("H,G,d,T", [(8, 4, 64, 16), (16, 16, 128, 0), (16, 2, 128, 16)])
 def test_equal_sequences_more_work_units_than_wavefronts(H, G, d, T):
-    # a batch of equal sequences cut into thousands of 16-key items: the units are dealt to the wavefronts in
-    # fixed rotation (no ticket counter); a second batch one key off per sequence takes the same path
+    # a batch of equal sequences cut into thousands of 16-key items, dealt to the wavefronts in fixed rotation;
+    # a second batch one key off per sequence takes the same path
     say(f"fixed rotation H={H} G={G} d={d} T={T}")
     for ctx in ([333] * 40, [320 + (b % 2) * 15 for b in range(40)]):
         st = build_stack(L=1, H=H, G=G, d=d, T=T, ctx_before=ctx, cap_tokens=352, out_dtype=1, seed=83,
@@ -196,6 +196,11 @@ def test_unused_slots_full_of_nan_do_not_leak():
 
 # ---- integer work: bit-exact --------------------------------------------------------------
 
+def wavefronts_per_kv_head(G):
+    """What a context shares a launch out over: 4 wavefronts per compute unit, divided by the KV heads."""
+    return max(1, 4 * torch.cuda.get_device_properties(0).multi_processor_count // G)
+
+
 def test_worklist_on_device_matches_host_and_oracle():
     say("work list")
     ctx = synth.ragged_ctx_lens(37, 1, 900, 51)
@@ -205,6 +210,7 @@ def test_worklist_on_device_matches_host_and_oracle():
         S = st.ctx.okv_get_split_tokens()
         host = st.ctx.okv_worklist(from_device=False)
         dev = st.ctx.okv_worklist(from_device=True)
+        assert S == (split or 1)                         # 0 = back to the size the context was created with
         want = np.array(worklist.expected_items(ctx, S), dtype=np.int32)
         np.testing.assert_array_equal(host, want)
         np.testing.assert_array_equal(dev, want)
@@ -216,6 +222,27 @@ def test_worklist_on_device_matches_host_and_oracle():
     np.testing.assert_array_equal(st.ctx.okv_get_ctx_lens(), ctx + 1)
     dev = st.ctx.okv_worklist(from_device=True)
     np.testing.assert_array_equal(dev, np.array(worklist.expected_items(ctx + 1, 100), dtype=np.int32))
+    st.close()
+
+
+@pytest.mark.parametrize("H,G,d,T,B,lo,hi", [(32, 8, 128, 16, 40, 300, 2500), (12, 12, 64, 16, 30, 1, 1500),
+                                               (4, 1, 128, 0, 3, 2000, 6000), (16, 16, 128, 32, 70, 16, 900)])
+def test_equal_stretches_on_the_device_and_every_output(H, G, d, T, B, lo, hi):
+    # no split size fixed: the batch's keys are shared out in equal stretches; wavefronts run several items one
+    # after the other (the next item's first tile is asked for before this one's results are written), stretches
+    # begin and end in the middle of sequences, some sequences are cut several times, and with 12 or 1 KV heads
+    # the wavefronts do not divide evenly.  Work list against the oracle's walk, every output against the oracle.
+    say(f"equal stretches H={H} G={G} d={d} T={T} B={B}")
+    ctx = synth.ragged_ctx_lens(B, lo, hi, 401 + B)
+    st = build_stack(L=1, H=H, G=G, d=d, T=T, ctx_before=ctx, cap_tokens=hi + 24, out_dtype=1, seed=403)
+    want, first, span = worklist.expected_items_equal_stretches(ctx, wavefronts_per_kv_head(G))
+    np.testing.assert_array_equal(st.ctx.okv_worklist(from_device=True), np.array(want, dtype=np.int32))
+    np.testing.assert_array_equal(st.ctx.okv_worklist(from_device=False), np.array(want, dtype=np.int32))
+    assert worklist.check_tiling(want, ctx)
+    pairs = [(b, h) for b in range(B) for h in range(0, H, max(1, H // 4))]
+    run_and_check(st, n_steps=2, seed=405, pairs=pairs)
+    want2, _, _ = worklist.expected_items_equal_stretches(ctx + 2, wavefronts_per_kv_head(G))
+    np.testing.assert_array_equal(st.ctx.okv_worklist(from_device=True), np.array(want2, dtype=np.int32))
     st.close()
 
 

@@ -196,7 +196,7 @@ def test_size_queries_and_shape_errors():
     cfg = binding.make_config(n_layers=32, n_q_heads=32, n_kv_heads=32, head_dim=128, block_tokens=0,
                               max_batch=32, max_ctx=1024)
     assert binding.okv_layer_pool_bytes(cfg) == 512 << 20
-    assert binding.okv_workspace_bytes(cfg) == 32 * 8 * 32 * 130 * 4
+    assert binding.okv_workspace_bytes(cfg) == 32 * (8 + 1) * 32 * 130 * 4   # one item per 128 keys and one more per sequence
     assert binding.okv_block_bytes(cfg) == 2 * 32 * 1024 * 128 * 2      # one sequence's slice
     cfg = binding.make_config(n_layers=2, n_q_heads=8, n_kv_heads=8, head_dim=64, block_tokens=16,
                               max_batch=4, max_blocks_per_seq=16, blocks_per_layer=64,
@@ -225,3 +225,27 @@ def test_size_queries_and_shape_errors():
         with pytest.raises(binding.OkvError) as e:
             binding.okv_layer_pool_bytes(binding.make_config(**kw))
         assert e.value.code == binding.OKV_EINVAL
+
+
+def test_equal_stretches_match_the_oracle_walk():
+    # the library's closed-form cutting against the oracle's tile-by-tile walk, bit for bit
+    from oracle import worklist
+    rng = np.random.default_rng(11)
+    for case in range(80):
+        B = int(rng.integers(1, 60))
+        lens = rng.integers(0, 5000, size=B).astype(np.int32)
+        if case % 5 == 0:
+            lens[:] = int(rng.integers(1, 4100))
+        if case % 9 == 0:
+            lens[rng.integers(0, B)] = 0
+        max_groups = int(rng.choice([1, 3, 32, 85, 128, 1024]))
+        if lens.sum() == 0:
+            lens[0] = 1
+        items, first, span = binding.okv_equal_stretches(lens, max_groups)
+        want_items, want_first, want_span = worklist.expected_items_equal_stretches(lens, max_groups)
+        assert span == want_span
+        assert [tuple(int(v) for v in r) for r in items] == want_items
+        assert first.tolist() == want_first
+    with pytest.raises(binding.OkvError) as e:
+        binding.okv_equal_stretches(np.array([-1], dtype=np.int32), 4)
+    assert e.value.code == binding.OKV_EINVAL

@@ -393,3 +393,47 @@ def test_items_by_class_reduces_to_the_plain_list():
         plain = worklist.expected_items(lens, S)
         assert worklist.expected_items_by_class(lens, table, T, 200, 8, S, 1)[0] == plain
         assert worklist.expected_items_by_class(lens, table, T, 0, 200, S, 2) == [[], plain]
+
+
+# ---- equal stretches (the work list when no split size is fixed) ---------------------------------
+
+def test_equal_stretches_hand_cases():
+    # one sequence of 40 tiles, 4 wavefronts per KV head: four stretches of 10 tiles = 160 keys
+    items, first, span = worklist.expected_items_equal_stretches([640], 4)
+    assert span == 10 and first == [0, 1, 2, 3, 4]
+    assert items == [(0, 0, 160), (0, 160, 320), (0, 320, 480), (0, 480, 640)]
+    # two sequences of 24 and 8 tiles, 2 stretches of 16 tiles: the first sequence is cut, the second shares a stretch
+    items, first, span = worklist.expected_items_equal_stretches([384, 120], 2)
+    assert span == 16 and items == [(0, 0, 256), (0, 256, 384), (1, 0, 120)] and first == [0, 1, 3]
+    # a short batch is not cut below 8 tiles a stretch: 20 tiles -> 2 stretches although 64 are allowed
+    items, first, span = worklist.expected_items_equal_stretches([100, 100, 100], 64)
+    assert span == 11 and len(first) == 3
+    assert items == [(0, 0, 100), (1, 0, 64), (1, 64, 100), (2, 0, 100)]
+    # empty sequences contribute nothing; fewer than 8 tiles in all: one stretch
+    items, first, span = worklist.expected_items_equal_stretches([0, 5, 0, 33], 8)
+    assert items == [(1, 0, 5), (3, 0, 33)] and first == [0, 2] and span == 4
+
+
+def test_equal_stretches_tile_exactly_and_evenly():
+    rng = np.random.default_rng(7)
+    for case in range(60):
+        B = int(rng.integers(1, 40))
+        lens = rng.integers(0, 3000, size=B)
+        if case % 7 == 0:
+            lens[:] = int(rng.integers(1, 2000))             # a batch of equal sequences
+        G = int(rng.choice([1, 2, 8, 32]))
+        max_groups = max(1, 1024 // G)
+        items, first, span = worklist.expected_items_equal_stretches(lens, max_groups)
+        assert worklist.check_tiling(items, lens)
+        assert len(first) - 1 <= max_groups and first[0] == 0 and first[-1] == len(items)
+        assert all(a < b for a, b in zip(first, first[1:]))   # every stretch in use opens with an item
+        assert all(lo % 16 == 0 for (_, lo, _) in items)
+        tiles = [sum(-(-(hi - lo) // 16) for (_, lo, hi) in items[a:b]) for a, b in zip(first, first[1:])]
+        if tiles:
+            assert all(t == span for t in tiles[:-1]) and 1 <= tiles[-1] <= span
+        total = sum(-(-int(n) // 16) for n in lens)
+        assert sum(tiles) == total
+        if total >= 16:
+            assert span >= 8                                   # no stretch shorter than 8 tiles unless the batch is
+        # a sequence is cut only where a stretch ends: at most one item per sequence and stretch
+        assert len(items) <= int((lens > 0).sum()) + len(first) - 2 + 1
