@@ -341,6 +341,51 @@ int okv_prefill_release(okv_ctx *ctx, int32_t layer);
  * pipeline.  Synchronous. */
 int okv_prefill_end(okv_ctx *ctx);
 
+/* ---- for callers that cannot allocate ------------------------------------------------------
+ *
+ * decode_attn for one layer with no context and no allocation of any kind, for callers that must not
+ * reach hipMalloc: code under HIP graph capture, tight serving loops, harnesses that forbid it.  The
+ * split-K work list and partial results, which the entry points above keep in the context and in the
+ * caller's workspace, live here in OKV_STATIC_SCRATCH_BYTES of device memory that are part of the
+ * library itself (every GPU the library runs on holds them until the process ends).  The call makes
+ * no hipMalloc / hipFree and no library call that allocates; its first call on a device looks up the
+ * array's address on that device.  It enqueues three kernels on `stream` (work list from the device
+ * lengths, split-K attention with the store of k_new / v_new folded in, merge) and returns.
+ *
+ * The batch's lengths are read on the device, so the host never needs them: ctx_lens[b] is the number
+ * of keys sequence b attends to, INCLUDING the row stored by this call when k_new / v_new are given
+ * (that row goes to position ctx_lens[b] - 1).  Pool layout, block table and the meaning of every
+ * other argument are those of okv_config / kv_append / decode_attn; the keys of the batch are shared
+ * out in equal stretches exactly as a context does with split_tokens = 0, so the results equal
+ * decode_attn's bit for bit.
+ *
+ * Every call on a GPU uses that GPU's one array: calls that may overlap on one GPU (two streams, two
+ * host threads) race and must be ordered by the caller.  Nothing in the array has to be cleared
+ * between calls: each call's first kernel rewrites what the others read.
+ * OKV_EINVAL: NULL / misaligned pointer, bad shape, B outside [1, OKV_STATIC_MAX_BATCH].
+ * OKV_ENOSPC: (B + wavefronts per KV head) work items of n_q_heads * (head_dim + 2) floats, plus the
+ * item list, exceed OKV_STATIC_SCRATCH_BYTES (32 query heads of 128: B up to about 1900). */
+#define OKV_STATIC_SCRATCH_BYTES (32 << 20)
+#define OKV_STATIC_MAX_BATCH 4096
+
+typedef struct okv_static_attn {
+  int32_t n_q_heads, n_kv_heads, head_dim;   /* as in okv_config                                  */
+  int32_t block_tokens;                      /* 0 = contiguous pool, else T                       */
+  int32_t max_blocks_per_seq;                /* paged: columns of block_table                     */
+  int32_t max_ctx;                           /* contiguous: capacity per sequence, multiple of 16 */
+  int32_t out_dtype;                         /* 0 = fp16, 1 = fp32                                */
+  int32_t B;                                 /* sequences                                         */
+  const void    *pool;                       /* DEVICE: the layer's pool (written if k_new given) */
+  const int32_t *block_table;                /* DEVICE int32 [B][max_blocks_per_seq]; paged only  */
+  const int32_t *ctx_lens;                   /* DEVICE int32 [B], each >= 1                       */
+  const void    *q;                          /* DEVICE fp16 [B][H][d]                             */
+  void          *out;                        /* DEVICE [B][H][d], fp16 or fp32                    */
+  const void    *k_new, *v_new;              /* DEVICE fp16 [B][G][d], or both NULL               */
+  void          *stream;                     /* hipStream_t (NULL = the default stream)           */
+} okv_static_attn;
+
+int okv_decode_attn_static(const okv_static_attn *a);
+
 /* Blocks until everything enqueued on the library's streams has finished. */
 int okv_synchronize(okv_ctx *ctx);
 

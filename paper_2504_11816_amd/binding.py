@@ -23,7 +23,7 @@ EXPORTS = [
     "okv_worklist_classes", "okv_prefill_begin", "kv_append_bulk", "okv_prefill_release", "okv_prefill_end", "okv_prefill_plan",
     "okv_measure_d2h",
     "okv_profile_enable", "okv_profile_read", "okv_measure_h2d", "okv_time_copies", "okv_probe_copy",
-    "okv_probe_read", "okv_equal_stretches",
+    "okv_probe_read", "okv_equal_stretches", "okv_decode_attn_static",
 ]
 
 
@@ -57,6 +57,21 @@ class OkvConfig(ctypes.Structure):
         ("resident_blocks", ctypes.c_int64), ("chunk_blocks", ctypes.c_int64),
     ]
 
+
+class OkvStaticAttn(ctypes.Structure):
+    """okv_static_attn of include/okv.h."""
+    _fields_ = [
+        ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+        ("block_tokens", ctypes.c_int32), ("max_blocks_per_seq", ctypes.c_int32), ("max_ctx", ctypes.c_int32),
+        ("out_dtype", ctypes.c_int32), ("B", ctypes.c_int32),
+        ("pool", ctypes.c_void_p), ("block_table", ctypes.c_void_p), ("ctx_lens", ctypes.c_void_p),
+        ("q", ctypes.c_void_p), ("out", ctypes.c_void_p), ("k_new", ctypes.c_void_p), ("v_new", ctypes.c_void_p),
+        ("stream", ctypes.c_void_p),
+    ]
+
+
+OKV_STATIC_SCRATCH_BYTES = 32 << 20
+OKV_STATIC_MAX_BATCH = 4096
 
 _lib_handle = None
 
@@ -118,6 +133,7 @@ def lib():
             "okv_probe_read": (ctypes.c_int, [P, I64, P, P]),
             "okv_equal_stretches": (ctypes.c_int, [P, I32, I32, P, I64, ctypes.POINTER(I64), P, ctypes.POINTER(I32),
                                                    ctypes.POINTER(I64)]),
+            "okv_decode_attn_static": (ctypes.c_int, [ctypes.POINTER(OkvStaticAttn)]),
         }
         for name, (res, args) in sig.items():
             fn = getattr(L, name)
@@ -197,6 +213,15 @@ def okv_equal_stretches(ctx_lens, max_groups):
     _check(lib().okv_equal_stretches(_ptr(ctx_lens), B, max_groups, _ptr(items), max_items, ctypes.byref(n), _ptr(first),
                                      ctypes.byref(groups), ctypes.byref(span)))
     return items[:n.value].copy(), first[:groups.value + 1].copy(), span.value
+
+
+def okv_decode_attn_static(*, n_q_heads, n_kv_heads, head_dim, block_tokens, max_blocks_per_seq, max_ctx, out_dtype, B, pool,
+                           block_table, ctx_lens, q, out, k_new=None, v_new=None, stream=0):
+    """One layer's decode attention with no context and no allocation (okv_decode_attn_static)."""
+    a = OkvStaticAttn(n_q_heads, n_kv_heads, head_dim, block_tokens, max_blocks_per_seq, max_ctx, out_dtype, B,
+                      _ptr(pool), _ptr(block_table), _ptr(ctx_lens), _ptr(q), _ptr(out), _ptr(k_new), _ptr(v_new),
+                      ctypes.c_void_p(stream))
+    _check(lib().okv_decode_attn_static(ctypes.byref(a)))
 
 
 def make_config(**kw):

@@ -1588,6 +1588,121 @@ int okv_decoder_step(okv_ctx *ctx, const okv_decoder_layer *layers, int32_t n_la
   return rc == OKV_OK ? okv_step_end(ctx) : rc;
 }
 
+// ---- decode attention without any allocation ------------------------------------------------
+//
+// The work list, the stretch table and the split-K partial results of okv_decode_attn_static live in
+// one array of device memory that is part of the library's code object: every GPU that loads the
+// library holds its own copy until the process ends.  The name below stands for it in host code only;
+// its device address is looked up once per device (hipGetSymbolAddress) and everything uses that.
+}  // extern "C"
+
+static __device__ __align__(256) unsigned char scratch[OKV_STATIC_SCRATCH_BYTES];
+
+namespace {
+constexpr int kMaxDevices = 64;
+unsigned char *g_scratch_ptr[kMaxDevices] = {};
+int g_scratch_cus[kMaxDevices] = {};
+
+struct StaticLayout {            // offsets into the scratch array, each a multiple of 256
+  int64_t item_desc, chunk_prefix, group_first, plan, part_o, part_ml, bytes;
+};
+StaticLayout static_layout(int64_t max_items, int32_t B, int32_t max_groups, int32_t H, int32_t D) {
+  StaticLayout l;
+  int64_t at = 0;
+  auto take = [&](int64_t bytes) {
+    const int64_t here = at;
+    at += (bytes + 255) / 256 * 256;
+    return here;
+  };
+  l.item_desc = take(max_items * (int64_t)sizeof(int4));
+  l.chunk_prefix = take(((int64_t)B + 1) * 4);
+  l.group_first = take(((int64_t)max_groups + 1) * 4);
+  l.plan = take(16);
+  l.part_o = take(max_items * H * D * 4);
+  l.part_ml = take(max_items * H * 2 * 4);
+  l.bytes = at;
+  return l;
+}
+}  // namespace
+
+extern "C" {
+
+int okv_decode_attn_static(const okv_static_attn *a) {
+  if (!a) return fail(nullptr, OKV_EINVAL, "okv_decode_attn_static: NULL argument");
+  okv_config c;
+  memset(&c, 0, sizeof c);
+  c.n_layers = 1, c.n_q_heads = a->n_q_heads, c.n_kv_heads = a->n_kv_heads, c.head_dim = a->head_dim;
+  c.block_tokens = a->block_tokens, c.max_batch = a->B > 0 ? a->B : 1, c.max_blocks_per_seq = a->max_blocks_per_seq;
+  c.max_ctx = a->max_ctx, c.blocks_per_layer = a->block_tokens ? 1 : 0, c.out_dtype = a->out_dtype;
+  if (const char *why = shape_problem(&c)) return fail(nullptr, OKV_EINVAL, "okv_decode_attn_static: %s", why);
+  if (a->B < 1 || a->B > OKV_STATIC_MAX_BATCH)
+    return fail(nullptr, OKV_EINVAL, "okv_decode_attn_static: B = %d outside [1, %d]", a->B, OKV_STATIC_MAX_BATCH);
+  if (!a->pool || !a->ctx_lens || !a->q || !a->out || (a->block_tokens && !a->block_table))
+    return fail(nullptr, OKV_EINVAL, "okv_decode_attn_static: NULL pointer");
+  if (!aligned16(a->pool) || !aligned16(a->q) || !aligned16(a->out) || !aligned16(a->k_new) || !aligned16(a->v_new))
+    return fail(nullptr, OKV_EINVAL, "okv_decode_attn_static: pointer not 16-byte aligned");
+  if ((a->k_new == nullptr) != (a->v_new == nullptr))
+    return fail(nullptr, OKV_EINVAL, "okv_decode_attn_static: k_new and v_new go together");
+  int dev = 0;
+  OKV_HIP(nullptr, hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return fail(nullptr, OKV_EINVAL, "okv_decode_attn_static: device %d not supported", dev);
+  if (!g_scratch_ptr[dev]) {                             // first call on this device: where its copy of the array is
+    void *p = nullptr;
+    OKV_HIP(nullptr, hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+    int cus = 0;
+    OKV_HIP(nullptr, hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
+    g_scratch_cus[dev] = cus > 0 ? cus : 256;
+    g_scratch_ptr[dev] = static_cast<unsigned char *>(p);
+  }
+  unsigned char *base = g_scratch_ptr[dev];
+  const int32_t H = a->n_q_heads, G = a->n_kv_heads, D = a->head_dim;
+  const int32_t max_waves = g_scratch_cus[dev] * OKV_WAVES_PER_CU_MHA;
+  const int32_t max_groups = std::max(1, max_waves / G);
+  // the lengths are on the device only: room for the most items any lengths can give (one per
+  // sequence and one per stretch)
+  const int64_t max_items = (int64_t)a->B + max_groups;
+  const StaticLayout lay = static_layout(max_items, a->B, max_groups, H, D);
+  if (lay.bytes > (int64_t)OKV_STATIC_SCRATCH_BYTES)
+    return fail(nullptr, OKV_ENOSPC,
+                "okv_decode_attn_static: batch %d with %d query heads of %d needs %lld bytes of work space, the library holds %lld",
+                a->B, H, D, (long long)lay.bytes, (long long)OKV_STATIC_SCRATCH_BYTES);
+  hipStream_t stream = static_cast<hipStream_t>(a->stream);
+  int32_t *chunk_prefix = reinterpret_cast<int32_t *>(base + lay.chunk_prefix);
+  int4 *item_desc = reinterpret_cast<int4 *>(base + lay.item_desc);
+  int32_t *group_first = reinterpret_cast<int32_t *>(base + lay.group_first);
+  int32_t *plan = reinterpret_cast<int32_t *>(base + lay.plan);
+  OKV_HIP(nullptr, okv::launch_step_advance_spans(const_cast<int32_t *>(a->ctx_lens), chunk_prefix, item_desc, group_first, plan, a->B,
+                                                  max_groups, kMinSpanTiles, 0, stream));
+  okv::AttnLaunch l;
+  okv::PoolShape &s = l.shape;
+  s.H = H, s.G = G, s.D = D;
+  s.paged = a->block_tokens != 0;
+  s.log2_T = 0;
+  while (s.paged && (1 << s.log2_T) < a->block_tokens) ++s.log2_T;
+  s.tcap = s.paged ? a->block_tokens : a->max_ctx;
+  s.gg = okv::kv_head_group(G, D);
+  s.max_blocks = s.paged ? a->max_blocks_per_seq : 1;
+  l.batch = okv::BatchState{a->block_table, a->ctx_lens, chunk_prefix, item_desc, a->B, 0, (int32_t)max_items, 1};
+  l.q = a->q;
+  l.pool = const_cast<void *>(a->pool);
+  l.k_new = a->k_new, l.v_new = a->v_new;
+  l.pool_mirror = nullptr;
+  l.out = a->out;
+  l.part_o = reinterpret_cast<float *>(base + lay.part_o);
+  l.part_ml = reinterpret_cast<float *>(base + lay.part_ml);
+  l.out_fp32 = a->out_dtype;
+  l.need_merge = 1;
+  l.group_first = group_first;
+  l.n_groups = max_groups;
+  l.n_groups_dev = plan;                                 // the kernel reads how many stretches are in use
+  l.max_waves = max_waves;
+  l.item_first = 0, l.item_count = (int32_t)max_items;
+  l.id_base = l.mirror_base = 0;
+  OKV_HIP(nullptr, okv::launch_decode_attn(l, stream, nullptr, nullptr));
+  OKV_HIP(nullptr, okv::launch_merge(l, stream));         // leaves at once for sequences that were not cut
+  return OKV_OK;
+}
+
 int okv_probe_copy(void *dst, const void *src, int64_t bytes, void *stream) {
   if (!dst || !src || bytes < 0 || bytes % 16 || !aligned16(dst) || !aligned16(src))
     return fail(nullptr, OKV_EINVAL, "okv_probe_copy: bad argument");

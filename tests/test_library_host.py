@@ -249,3 +249,18 @@ def test_equal_stretches_match_the_oracle_walk():
     with pytest.raises(binding.OkvError) as e:
         binding.okv_equal_stretches(np.array([-1], dtype=np.int32), 4)
     assert e.value.code == binding.OKV_EINVAL
+
+
+def test_static_entry_point_rejects_bad_arguments_without_a_gpu():
+    # shape and size checks come before any GPU call
+    base = dict(n_q_heads=32, n_kv_heads=8, head_dim=128, block_tokens=16, max_blocks_per_seq=8, max_ctx=0, out_dtype=0, B=4,
+                pool=256, block_table=256, ctx_lens=256, q=256, out=256)
+    for bad, code in ((dict(head_dim=96), binding.OKV_EINVAL), (dict(B=0), binding.OKV_EINVAL),
+                      (dict(B=binding.OKV_STATIC_MAX_BATCH + 1), binding.OKV_EINVAL), (dict(pool=None), binding.OKV_EINVAL),
+                      (dict(q=264), binding.OKV_EINVAL), (dict(k_new=256), binding.OKV_EINVAL),
+                      (dict(n_q_heads=12), binding.OKV_EINVAL)):
+        kw = dict(base)
+        kw.update(bad)
+        with pytest.raises(binding.OkvError) as e:
+            binding.okv_decode_attn_static(**kw)
+        assert e.value.code == code, bad
