@@ -28,21 +28,23 @@ import numpy as np  # noqa: E402
 HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published peak
 PCIE5_X16_GBPS = 64.0       # nominal, one direction
 
-# HBM traffic of one launch of the split kernel, from two rocprofv3 --pmc runs of this
-# file's default workload (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch averaged over the
-# timed launches), each scaled by what the same counter read for the plain copy kernel of
-# known size in the same run.  Valid only for the kernel source it was taken on: if
-# okv_kernels.hip has changed since, `traffic` is reported as null.
+# HBM traffic of the split kernel, from two rocprofv3 --pmc runs of this file's headline workload
+# (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch summed over the timed launches), each scaled by what the
+# same counter read for the plain copy kernel of known size in the same run, and divided by the
+# algorithmic KV bytes of the same launches: HBM bytes moved per algorithmic byte.  The ratio is a
+# property of the kernel (it re-reads nothing; what exceeds 1 is q, the block table, partial results and
+# the rows appended), so it carries over to any number of steps of the workload; it is valid only for the
+# kernel source it was taken on: if okv_kernels.hip has changed since, `traffic` is reported as null.
 TRAFFIC_RECORD = {
-    "workload": "cfg2", "steps": 512,
-    "kernel_sha256": "5f7ae3e703292c3097a3b865f97a54078bd2c14c6649f1ca24ded28bd0359ae1",
-    "fetch_kib": 199056.5, "fetch_scale": 2.0000,
-    "write_kib": 768.0, "write_scale": 1.0000,
+    "workload": "cfg2",
+    "kernel_sha256": "",
+    "fetch_ratio": 0.0, "fetch_scale": 2.0000,
+    "write_ratio": 0.0, "write_scale": 1.0000,
 }
 
 
-def recorded_traffic(workload, steps):
-    """HBM bytes per launch from the recorded counters, or None if they do not apply."""
+def recorded_traffic(workload, bytes_per_launch):
+    """HBM bytes per launch from the recorded counter ratios, or None if they do not apply."""
     import hashlib
     rec = TRAFFIC_RECORD
     src = os.path.join(ROOT, "paper_2504_11816_amd", "csrc", "okv_kernels.hip")
@@ -50,9 +52,9 @@ def recorded_traffic(workload, steps):
         sha = hashlib.sha256(open(src, "rb").read()).hexdigest()
     except OSError:
         return None
-    if not rec["kernel_sha256"] or sha != rec["kernel_sha256"] or workload != rec["workload"] or steps != rec["steps"]:
+    if not rec["kernel_sha256"] or sha != rec["kernel_sha256"] or workload != rec["workload"]:
         return None
-    return (rec["fetch_kib"] * rec["fetch_scale"] + rec["write_kib"] * rec["write_scale"]) * 1024.0
+    return (rec["fetch_ratio"] + rec["write_ratio"]) * bytes_per_launch
 
 
 def log(msg):
@@ -117,61 +119,79 @@ def kernel_time(st, ctx0, table, inputs, steps, per_step=False):
     return ms * 1e-3, n
 
 
-def cpu_baseline(st, ctx_now, q_layers, budget_s=15.0):
-    """The fp64 oracle, as it stands, on this host: (b, h) pairs of the same
-    workload, layer after layer, until the time budget is used."""
-    from threadpoolctl import threadpool_limits
+_CPU_JOB = {}
+
+
+def _cpu_pairs(pairs):
+    """Worker of cpu_baseline: the oracle on a run of (sequence, head) pairs of the layer in _CPU_JOB."""
     from oracle import attention as oa
+    j = _CPU_JOB
+    for (b, h) in pairs:
+        oa.decode_attn(j["q"], j["pool"], j["layout"], j["ctx"], j["H"], sample=[(b, h)])
+    return len(pairs)
+
+
+def cpu_baseline(st, ctx_now, q_layers, budget_s=15.0):
+    """The fp64 oracle, as it stands, on this host's cores: the (b, h) pairs of the same workload, layer
+    after layer, shared out over one worker process per core of the affinity mask (each worker runs the
+    oracle single-threaded), until the time budget is used."""
+    import multiprocessing as mp
+    from threadpoolctl import threadpool_limits
+    cores = len(os.sched_getaffinity(0))
     layout = st.layout()
     pairs = [(b, h) for b in range(st.B) for h in range(st.H)]
+    per_task = max(1, len(pairs) // (cores * 8))
+    tasks = [pairs[i:i + per_task] for i in range(0, len(pairs), per_task)]
     done, tokens, dt, layers = 0, 0, 0.0, 0
     with threadpool_limits(limits=1):
         for layer in range(st.L):
-            pool = st.read_pool(layer)                       # not timed: the oracle starts from host memory
-            qn = q_layers[layer].cpu().numpy()
-            layers += 1
-            t0 = time.perf_counter()
-            for (b, h) in pairs:
-                oa.decode_attn(qn, pool, layout, ctx_now, st.H, sample=[(b, h)])
-                done += 1
-                tokens += int(ctx_now[b])
-                if dt + time.perf_counter() - t0 > budget_s:
-                    break
-            dt += time.perf_counter() - t0
+            # not timed: the oracle starts from host memory; the workers are forked after the layer's data is
+            # in place and inherit it (they never touch the GPU and leave without running exit handlers)
+            _CPU_JOB.update(q=q_layers[layer].cpu().numpy(), pool=st.read_pool(layer), layout=layout, ctx=ctx_now, H=st.H)
+            with mp.get_context("fork").Pool(cores) as pool:
+                layers += 1
+                t0 = time.perf_counter()
+                for n in pool.imap_unordered(_cpu_pairs, tasks):
+                    done += n
+                dt += time.perf_counter() - t0
+            tokens += int(sum(int(ctx_now[b]) for (b, h) in pairs))
             if dt > budget_s:
                 break
+    _CPU_JOB.clear()
     # one (b, h) pair of one layer is 1 / (H * L) of a generated token's attention
     tok_rate = done / dt / (st.H * st.L)
     kv_gbps = tokens * 2 * st.d * 2 * (st.G / st.H) / dt / 1e9
-    return {"value": tok_rate, "unit": "tokens/s", "cores": 1, "kind": "oracle",
+    return {"value": tok_rate, "unit": "tokens/s", "cores": cores, "kind": "oracle",
             "kv_gbps": kv_gbps,
-            "sample": f"{done} (sequence, head) pairs over {layers} layer(s) at context {int(np.mean(ctx_now))}, "
-                      f"{dt:.1f} s of single-thread numpy fp64, scaled to {st.H} heads x {st.L} layers"}
+            "sample": f"{done} (sequence, head) pairs = {layers} whole layer(s) at context {int(np.mean(ctx_now))}, "
+                      f"{dt:.1f} s of numpy fp64 on {cores} worker processes (one per core, single-threaded each), "
+                      f"scaled to {st.H} heads x {st.L} layers"}
 
 
-def run_resident(args):
+def run_resident(args, workload=None, steps=None, warmup=None, with_cpu=None, layers=None):
+    """An all-resident workload of synth.WORKLOADS: `steps` decode steps of the whole stack, timed end to
+    end, then once more with the split-K launches of every step bracketed by HIP events."""
     import torch
     from paper_2504_11816_amd import synth
     from paper_2504_11816_amd.harness import Stack
-    w = dict(synth.WORKLOADS[args.workload])
-    steps = args.steps if args.steps else w["steps"]
+    workload = workload or args.workload
+    w = dict(synth.WORKLOADS[workload])
+    steps = steps if steps else (args.steps if args.steps else w["steps"])
+    warmup = args.warmup if warmup is None else warmup
+    with_cpu = (not args.no_cpu) if with_cpu is None else with_cpu
     L, H, G, d, B, T = w["L"], w["H"], w["G"], w["d"], w["B"], w["T"]
-    if args.layers:
-        L = min(L, args.layers)
+    layers = args.layers if layers is None else layers
+    if layers:
+        L = min(L, layers)
     if w["ragged"]:
         ctx_first = synth.ragged_ctx_lens(B, w["ragged"][0], w["ragged"][1], args.seed)
     else:
         ctx_first = np.full(B, w["ctx"], dtype=np.int32)
     ctx0 = ctx_first - 1                                   # stored before the first timed step
-    cap = int(ctx0.max()) + max(steps, args.warmup) + 1
-    on_host = None
-    if w["c_off"][0]:
-        from paper_2504_11816_amd import binding
-        on_host = binding.kv_offload_plan(L, w["c_off"][0], w["c_off"][1])[0]
-    log(f"[bench] {args.workload}: L={L} H={H} G={G} d={d} B={B} T={T} ctx {int(ctx_first.min())}..{int(ctx_first.max())} "
+    cap = int(ctx0.max()) + max(steps, warmup) + 1
+    log(f"[bench] {workload}: L={L} H={H} G={G} d={d} B={B} T={T} ctx {int(ctx_first.min())}..{int(ctx_first.max())} "
         f"steps={steps} capacity={cap}")
-    st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=cap, on_host=on_host, out_dtype=0,
-               split_tokens=args.split_tokens)
+    st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=cap, out_dtype=0, split_tokens=args.split_tokens)
     for l in range(L):
         st.fill_pool(l, synth.stream_seed(args.seed, synth.TENSOR_POOL, l))
     table = None
@@ -180,23 +200,30 @@ def run_resident(args):
                                            max_blocks_per_seq=st.max_blocks)
     inputs = fixed_inputs(st, args.seed)
     log("[bench] pools filled; timing")
-    dt = timed_steps(st, ctx0, table, inputs, steps, args.warmup)
+    dt = timed_steps(st, ctx0, table, inputs, steps, warmup)
     split = st.ctx.okv_get_split_tokens()
+    n_items = len(st.ctx.okv_worklist(from_device=False))
     kv_bytes = kv_bytes_of_steps(ctx0, steps, G, d, L)
     log(f"[bench] {steps} steps in {dt * 1e3:.1f} ms, split {split}")
     k_s, k_n = kernel_time(st, ctx0, table, inputs, steps, per_step=True)
     log(f"[bench] split-K kernel: {k_n} launches, {k_s / max(k_n, 1) * 1e6:.1f} us average")
     res = {
+        "workload": workload,
         "tokens_per_s": B * steps / dt, "ms_per_step": dt / steps * 1e3, "kv_gbps": kv_bytes / dt / 1e9,
-        "kernel_gbps": kv_bytes / k_s / 1e9, "kernel_avg_us": k_s / max(k_n, 1) * 1e6, "kernel_launches": k_n,
-        "kv_bytes_per_launch": kv_bytes / max(k_n, 1), "split_tokens": split, "steps": steps,
+        "hbm_frac": kv_bytes / dt / 1e9 / HBM_PEAK_GBPS,
+        "kernel_gbps": kv_bytes / k_s / 1e9, "kernel_frac": kv_bytes / k_s / 1e9 / HBM_PEAK_GBPS,
+        "kernel_avg_us": k_s / max(k_n, 1) * 1e6, "kernel_launches": k_n,
+        "kernel_time_includes_merge_pass": n_items > B,
+        "kv_bytes_per_launch": kv_bytes / max(k_n, 1), "split_tokens": split, "work_items": n_items, "steps": steps,
         "B": B, "L": L, "H": H, "G": G, "d": d, "T": T,
         "ctx_desc": (f"{int(ctx_first.max())}..{int(ctx_first.max()) + steps - 1}" if not w["ragged"] else
                      f"ragged {int(ctx_first.min())}..{int(ctx_first.max())} at the first step (mean "
-                     f"{float(ctx_first.mean()):.0f}), +1 per step"),
+                     f"{float(ctx_first.mean()):.0f}, sum {int(ctx_first.sum())}), +1 per step"),
     }
+    log(f"[bench] {workload}: {res['tokens_per_s']:.0f} tokens/s, {res['kv_gbps']:.0f} GB/s of KV end to end "
+        f"({100 * res['hbm_frac']:.1f}% of HBM peak), kernels alone {100 * res['kernel_frac']:.1f}%")
     cpu = None
-    if not args.no_cpu:
+    if with_cpu:
         log("[bench] timing the CPU oracle on a sample")
         mid = ctx0 + steps                                  # lengths as the run left them
         cpu = cpu_baseline(st, mid, inputs[0], args.cpu_seconds)
@@ -204,6 +231,50 @@ def run_resident(args):
     del st
     torch.cuda.empty_cache()
     return res, cpu
+
+
+def run_latency(args, reps=200):
+    """The small single-layer workload (8 heads x 64, batch 4, context 256: 2 MiB of KV, which sits in
+    cache): latency only.  Every step is issued and waited for on its own; the median over `reps` steps is
+    reported, for contiguous and for paged pools, with the time the step's kernels take on the GPU beside
+    it (HIP events around the launches of a step: the rest is what the host spends issuing them)."""
+    import torch
+    from paper_2504_11816_amd import synth
+    from paper_2504_11816_amd.harness import Stack
+    w = dict(synth.WORKLOADS["cfg1"])
+    L, H, G, d, B = w["L"], w["H"], w["G"], w["d"], w["B"]
+    out = {"workload": f"cfg1: {L} layer, {H} heads x {d}, batch {B}, context {w['ctx']}", "reps": reps}
+    for name, T in (("contiguous", 0), ("paged", 16)):
+        ctx0 = np.full(B, w["ctx"] - 1, dtype=np.int32)
+        st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=w["ctx"] + 16, out_dtype=0)
+        st.fill_pool(0, synth.stream_seed(args.seed, synth.TENSOR_POOL, 0))
+        table = synth.shuffled_block_table([st.cap_tokens] * B, T, st.blocks_per_layer, args.seed + 1,
+                                           max_blocks_per_seq=st.max_blocks) if T else None
+        inputs = fixed_inputs(st, args.seed)
+        bound = st.bind_step(*inputs)
+        lat, gpu = [], []
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        for i in range(reps + 20):
+            st.set_batch(ctx0, table)                      # every repetition is the same step: 256 keys attended
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            e0.record(st.compute_stream)
+            st.step_bound(bound)
+            e1.record(st.compute_stream)
+            st.synchronize()
+            t1 = time.perf_counter()
+            if i >= 20:
+                lat.append((t1 - t0) * 1e6)
+                gpu.append(e0.elapsed_time(e1) * 1e3)
+        out[name] = {"step_latency_us_median": float(np.median(lat)), "step_latency_us_p10": float(np.percentile(lat, 10)),
+                     "step_latency_us_p90": float(np.percentile(lat, 90)), "gpu_time_us_median": float(np.median(gpu)),
+                     "work_items": len(st.ctx.okv_worklist(from_device=False)), "kernels_per_step": 3 if len(st.ctx.okv_worklist(from_device=False)) > B else 2}
+        log(f"[bench] cfg1 {name}: step latency {out[name]['step_latency_us_median']:.1f} us median "
+            f"({out[name]['step_latency_us_p10']:.1f}..{out[name]['step_latency_us_p90']:.1f}), on the GPU {out[name]['gpu_time_us_median']:.1f} us")
+        st.close()
+        del st
+    torch.cuda.empty_cache()
+    return out
 
 
 def run_probe(nbytes=1 << 30, reps=5):
@@ -239,16 +310,78 @@ def run_probe(nbytes=1 << 30, reps=5):
 OFFLOAD_DEFAULT_BATCH = {"cfg3": 64, "cfg5": 48}
 
 
-def run_offload(args):
+def overlap_figures(res, t_step_ms, t_copy_plain_ms, t_copy_pipelined_ms, t_compute_ms):
+    """overlap = 1 - (t_step - t_copy_only) / t_compute_only with the two halves measured alone: 1 when a
+    step costs no more than its copies, 0 when the attention adds to them in full (Eq. 6 of the paper's
+    model), below 0 when a step loses more than its whole attention time to something else.  Given twice:
+    against the copies run back to back on one stream with nothing between them, and against the copy half
+    issued as the pipeline issues it (two copy streams, a wait for the buffer's release before and a record
+    after every copy), which is the half a step really contains."""
+    res["t_step_ms"] = t_step_ms
+    res["t_compute_only_ms"] = t_compute_ms
+    res["t_copy_only_ms"] = t_copy_pipelined_ms
+    res["t_copy_back_to_back_ms"] = t_copy_plain_ms
+    res["overlap"] = 1.0 - (t_step_ms - t_copy_pipelined_ms) / max(t_compute_ms, 1e-9)
+    res["overlap_vs_back_to_back_copies"] = 1.0 - (t_step_ms - t_copy_plain_ms) / max(t_compute_ms, 1e-9)
+    res["copy_protocol_cost_ms"] = t_copy_pipelined_ms - t_copy_plain_ms
+    return res
+
+
+def host_memory_gib():
+    """(MemTotal, MemAvailable) of this box in GiB."""
+    vals = {}
+    with open("/proc/meminfo") as f:
+        for line in f:
+            k, v = line.split(":")
+            if k in ("MemTotal", "MemAvailable"):
+                vals[k] = int(v.split()[0]) / 2 ** 20
+    return vals.get("MemTotal", 0.0), vals.get("MemAvailable", 0.0)
+
+
+def pinnable_gib(want_gib, step_gib=4):
+    """How much pinned, device-mapped host memory this process can get, up to want_gib: hipHostMalloc in
+    pieces of step_gib until it is refused, then everything is given back.  (On the benchmark boxes the
+    refusal comes at about 70 GiB whatever the 288 GiB of RAM: a limit of the container, not of the host.)"""
+    from paper_2504_11816_amd.harness import PinnedHalfBuffer
+    got, bufs = 0, []
+    try:
+        while got + step_gib <= want_gib:
+            bufs.append(PinnedHalfBuffer(step_gib << 29))
+            got += step_gib
+    except MemoryError:
+        pass
+    for b in bufs:
+        b.free()
+    return float(got)
+
+
+def cfg5_batch():
+    """The batch the offline workload (batch 192, context 4096, 20 of 32 layers on the host) is run at: its own
+    if the host share (241 GiB at batch 192) can be pinned, else the largest multiple of 8 whose host share
+    fits 95 % of what this process can pin (measured just before the leg)."""
+    from paper_2504_11816_amd import synth
+    w = synth.WORKLOADS["cfg5"]
+    total, avail = host_memory_gib()
+    n_off = -(-w["c_off"][0] * w["L"] // w["c_off"][1])
+    per_seq_gib = n_off * synth.blocks_needed(w["ctx"] + 8, w["T"]) * w["T"] * 2 * w["G"] * w["d"] * 2 / 2 ** 30
+    full = w["B"] * per_seq_gib
+    can_pin = pinnable_gib(min(full + 4, 0.8 * avail))
+    B = min(w["B"], int(0.95 * can_pin / per_seq_gib) // 8 * 8)
+    return max(8, B), {"host_ram_gib": total, "host_ram_available_gib": avail, "pinnable_gib_measured": can_pin,
+                      "full_batch": w["B"], "full_batch_pinned_gib": full}
+
+
+def run_offload(args, name=None, B=None, steps=None, warmup=None):
     """Paged KV, part of the layers in pinned host memory, streamed per layer."""
     import torch
     from paper_2504_11816_amd import binding, synth
     from paper_2504_11816_amd.harness import Stack
-    name = args.offload_workload
+    name = name or args.offload_workload
     w = dict(synth.WORKLOADS[name])
     L, H, G, d, T = w["L"], w["H"], w["G"], w["d"], w["T"]
-    B = args.offload_batch or OFFLOAD_DEFAULT_BATCH[name]
-    steps, warmup = args.offload_steps or (6 if name == "cfg3" else 3), (2 if name == "cfg3" else 1)
+    B = B or args.offload_batch or OFFLOAD_DEFAULT_BATCH[name]
+    steps = steps or args.offload_steps or (6 if name == "cfg3" else 3)
+    warmup = (2 if name == "cfg3" else 1) if warmup is None else warmup
     ctx0 = np.full(B, w["ctx"] - 1, dtype=np.int32)
     cap = w["ctx"] + steps + warmup
     on_host, n_off = binding.kv_offload_plan(L, w["c_off"][0], w["c_off"][1])
@@ -271,7 +404,8 @@ def run_offload(args):
     # the two halves alone: every layer's attention kernels (one step), and one step's copies
     k_s, k_n = kernel_time(st, ctx0, table, inputs, 1)
     st.set_batch(ctx0, table)
-    copy_ms = st.ctx.okv_time_copies()
+    copy_ms = st.ctx.okv_time_copies(False, 1)
+    copy_pipe_ms = st.ctx.okv_time_copies(True, steps)      # as many steps as were timed: both then hold the same prefetch for the step after the last
     res = {
         "workload": name, "B": B, "ctx": w["ctx"], "host_layers": int(n_off), "layers": L, "steps": steps,
         "tokens_per_s": B * steps / dt, "ms_per_step": dt / steps * 1e3, "kv_gbps": kv_bytes / dt / 1e9,
@@ -286,10 +420,11 @@ def run_offload(args):
     # below 1 means compute is (partly) hidden; the per-copy dependency latency of the two-stream
     # protocol (~0.8 ms per layer copy in the copy trace) is in this figure too.
     res["step_minus_copies_ms"] = res["ms_per_step"] - copy_ms
-    res["exposed_over_attn"] = res["step_minus_copies_ms"] / max(res["attn_kernel_ms_per_step"], 1e-9)
+    overlap_figures(res, res["ms_per_step"], copy_ms, copy_pipe_ms, res["attn_kernel_ms_per_step"])
     log(f"[bench] offload leg {name}: {res['ms_per_step']:.1f} ms/step, link {res['link_gbps_achieved']:.1f} GB/s "
-        f"= {100 * res['link_frac']:.1f}% of measured; copies alone {copy_ms:.1f} ms, attention kernels alone "
-        f"{res['attn_kernel_ms_per_step']:.1f} ms/step ({res['attn_kernel_gbps']:.0f} GB/s)")
+        f"= {100 * res['link_frac']:.1f}% of measured; copies alone {copy_ms:.1f} ms back to back, {copy_pipe_ms:.1f} ms "
+        f"as the pipeline issues them; attention kernels alone {res['attn_kernel_ms_per_step']:.1f} ms/step "
+        f"({res['attn_kernel_gbps']:.0f} GB/s); overlap {res['overlap']:.2f} ({res['overlap_vs_back_to_back_copies']:.2f} against back-to-back copies)")
     st.close()
     del st
     torch.cuda.empty_cache()
@@ -338,7 +473,8 @@ def run_offload_blocks(args):
     kv_bytes = kv_bytes_of_steps(ctx0, steps, G, d, L)
     k_s, k_n = kernel_time(st, ctx0, table, inputs, 1)
     st.set_batch(ctx0, table)
-    copy_ms = st.ctx.okv_time_copies()
+    copy_ms = st.ctx.okv_time_copies(False, 1)
+    copy_pipe_ms = st.ctx.okv_time_copies(True, steps)      # as many steps as were timed: both then hold the same prefetch for the step after the last
     res = {
         "workload": name, "placement": args.placement, "B": B, "ctx": w["ctx"], "layers": L, "steps": steps,
         "host_blocks_per_layer": int(n_host), "blocks_per_layer": int(need),
@@ -353,9 +489,11 @@ def run_offload_blocks(args):
         "staging_buffers": args.staging, "staging_gib": args.staging * st.staging_bytes / 2 ** 30,
         "split_tokens": st.ctx.okv_get_split_tokens(),
     }
+    overlap_figures(res, res["ms_per_step"], copy_ms, copy_pipe_ms, res["attn_kernel_ms_per_step"])
     log(f"[bench] block-granular leg {name}: {res['ms_per_step']:.1f} ms/step, link {res['link_gbps_achieved']:.1f} GB/s "
-        f"= {100 * res['link_frac']:.1f}% of measured; copies alone {copy_ms:.1f} ms; attention alone "
-        f"{res['attn_kernel_ms_per_step']:.1f} ms/step in {k_n} launches; staging {res['staging_gib']:.2f} GiB")
+        f"= {100 * res['link_frac']:.1f}% of measured; copies alone {copy_ms:.1f} ms back to back, {copy_pipe_ms:.1f} ms as the "
+        f"pipeline issues them; attention alone {res['attn_kernel_ms_per_step']:.1f} ms/step in {k_n} launches; "
+        f"overlap {res['overlap']:.2f}; staging {res['staging_gib']:.2f} GiB")
     st.close()
     del st
     torch.cuda.empty_cache()
@@ -511,26 +649,40 @@ def run_layers(args):
     kv_bytes = kv_bytes_of_steps(ctx0, steps, G, d, L)
     w_bytes = sum(wt.bytes_read_per_step() for wt in weights) * steps
     # each product alone, back to back over the layers' own matrices in turn (two rounds): with L layers the
-    # weights come from HBM as they do in a step, not from the memory-side cache a single matrix would sit in
+    # weights come from HBM as they do in a step, not from the memory-side cache a single matrix would sit in;
+    # at the leg's own batch and at 32, 64, 128 and 192 rows (more than 128 rows take two launches, each reading
+    # the weights again: the rate below counts the matrix once)
     cs = st.compute_stream
-    alone = {}
-    for name, fn, nbytes in (
-            (f"qkv {h1 + 2 * G * d}x{h1}", lambda wt: binding.okv_linear_qkv(scratch.a, wt.packed["wqkv"], wt.bqkv, scratch.q, scratch.k, scratch.v, B, h1, G * d, h1, cs.cuda_stream, scratch.ws, scratch.ws_bytes), (h1 + 2 * G * d) * h1 * 2),
-            ("out 4096x4096", lambda wt: binding.okv_linear(scratch.t, wt.packed["wo"], wt.t["bo"], scratch.z, scratch.y, B, h1, h1, False, cs.cuda_stream, scratch.ws, scratch.ws_bytes), h1 * h1 * 2),
-            ("ffn1 16384x4096", lambda wt: binding.okv_linear(scratch.z, wt.packed["w1"], wt.t["b1"], None, scratch.u, B, h2, h1, True, cs.cuda_stream, scratch.ws, scratch.ws_bytes), h1 * h2 * 2),
-            ("ffn2 4096x16384", lambda wt: binding.okv_linear(scratch.u, wt.packed["w2"], wt.t["b2"], scratch.z, scratch.y, B, h1, h2, False, cs.cuda_stream, scratch.ws, scratch.ws_bytes), h1 * h2 * 2)):
-        for wt in weights:
-            fn(wt)
-        cs.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record(cs)
-        for _ in range(2):
+
+    def products_alone(m, sc):
+        out = {}
+        for name, fn, nbytes in (
+                (f"qkv {h1 + 2 * G * d}x{h1}", lambda wt: binding.okv_linear_qkv(sc.a, wt.packed["wqkv"], wt.bqkv, sc.q, sc.k, sc.v, m, h1, G * d, h1, cs.cuda_stream, sc.ws, sc.ws_bytes), (h1 + 2 * G * d) * h1 * 2),
+                ("out 4096x4096", lambda wt: binding.okv_linear(sc.t, wt.packed["wo"], wt.t["bo"], sc.z, sc.y, m, h1, h1, False, cs.cuda_stream, sc.ws, sc.ws_bytes), h1 * h1 * 2),
+                ("ffn1 16384x4096", lambda wt: binding.okv_linear(sc.z, wt.packed["w1"], wt.t["b1"], None, sc.u, m, h2, h1, True, cs.cuda_stream, sc.ws, sc.ws_bytes), h1 * h2 * 2),
+                ("ffn2 4096x16384", lambda wt: binding.okv_linear(sc.u, wt.packed["w2"], wt.t["b2"], sc.z, sc.y, m, h1, h2, False, cs.cuda_stream, sc.ws, sc.ws_bytes), h1 * h2 * 2)):
             for wt in weights:
                 fn(wt)
-        e1.record(cs)
-        cs.synchronize()
-        us = e0.elapsed_time(e1) / (2 * len(weights)) * 1e3
-        alone[name] = {"us": us, "weight_gbps": nbytes / us / 1e3}
+            cs.synchronize()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record(cs)
+            for _ in range(2):
+                for wt in weights:
+                    fn(wt)
+            e1.record(cs)
+            cs.synchronize()
+            us = e0.elapsed_time(e1) / (2 * len(weights)) * 1e3
+            out[name] = {"us": us, "weight_gbps": nbytes / us / 1e3, "hbm_frac": nbytes / us / 1e3 / HBM_PEAK_GBPS}
+        return out
+
+    alone = products_alone(B, scratch)
+    by_rows = {}
+    for m in (32, 64, 128, 192):
+        sc = scratch if m == B else LayerScratch(m, h1, h2, G, d, st.device)
+        for t in (sc.a, sc.t, sc.z, sc.u):
+            t.normal_()
+        by_rows[str(m)] = alone if m == B else products_alone(m, sc)
+        del sc
     res = {
         "workload": f"{L} decoder layers ({args.decoder_workload} shape: {H} query / {G} KV heads x {d}), hidden {h1}, feed-forward {h2}, batch {B}, "
                     + (f"context {w['ctx']}..{w['ctx'] + steps - 1}" if not w["ragged"] else
@@ -539,6 +691,7 @@ def run_layers(args):
         "weight_gb_per_step": w_bytes / steps / 1e9, "kv_gb_per_step": kv_bytes / steps / 1e9,
         "hbm_gbps": (w_bytes + kv_bytes) / dt / 1e9, "hbm_frac": (w_bytes + kv_bytes) / dt / 1e9 / HBM_PEAK_GBPS,
         "linear_alone": alone,
+        "linear_alone_by_rows": by_rows,
     }
     log(f"[bench] decoder layers: {res['ms_per_step']:.2f} ms/step, {res['tokens_per_s']:.0f} tokens/s, "
         f"{res['hbm_gbps']:.0f} GB/s of weights + KV ({100 * res['hbm_frac']:.1f}% of HBM peak); products alone: "
@@ -638,6 +791,9 @@ def main():
     ap.add_argument("--offload-batch", type=int, default=0)
     ap.add_argument("--staging", type=int, default=2, help="staging buffers for host layers (1..4)")
     ap.add_argument("--no-blocks", action="store_true", help="skip the block-granular offloaded leg")
+    ap.add_argument("--no-configs", action="store_true",
+                    help="skip the legs of the other named workloads (cfg2 in full, cfg4, cfg1)")
+    ap.add_argument("--no-cfg5", action="store_true", help="skip the offline large-batch offloaded leg")
     ap.add_argument("--no-model", action="store_true", help="skip the prediction-model leg")
     ap.add_argument("--no-decoder", action="store_true", help="skip the whole-decoder-layer leg")
     ap.add_argument("--layer-steps", type=int, default=32, help="decoder-layer leg: decode steps to time")
@@ -661,17 +817,34 @@ def main():
         sys.exit("bench.py needs a GPU")
     res, cpu = run_resident(args)
     probe = run_probe() if args.probe else None
+    # the other named workloads, each at its own size whatever --steps says
+    extra = {}
+    if not args.no_configs:
+        if not (args.workload == "cfg2" and res["steps"] == 512 and not args.layers):
+            extra["cfg2_full"], _ = run_resident(args, "cfg2", steps=512, with_cpu=False, layers=0)
+        extra["cfg4"], _ = run_resident(args, "cfg4", steps=20, with_cpu=False, layers=0)
+        extra["cfg1"] = run_latency(args)
     off = None if (args.no_offload or args.no_layers) else run_offload(args)
     off_blocks = None if (args.no_offload or args.no_blocks) else run_offload_blocks(args)
+    if not (args.no_offload or args.no_cfg5):
+        B5, why = cfg5_batch()
+        leg = run_offload(args, "cfg5", B=B5, steps=2, warmup=1)
+        leg.update(why)
+        leg["note"] = (f"batch {B5} of the workload's {why['full_batch']}: at the full batch the host share is "
+                       f"{why['full_batch_pinned_gib']:.0f} GiB of pinned memory; this box has {why['host_ram_gib']:.0f} GiB of RAM "
+                       f"but hipHostMalloc is refused beyond {why['pinnable_gib_measured']:.0f} GiB (measured just before the leg); "
+                       f"the per-sequence shape, the plan (20 of 32 layers on the host) and the depth are the workload's own")
+        extra["cfg5_shape"] = leg
     prefill = None if (args.no_offload or args.no_prefill) else run_prefill(args)
     model = None if args.no_model else run_model(args, off)
     layers = None if args.no_decoder else run_layers(args)
+    part = "" if res["steps"] == 512 else f" (the first {res['steps']} of its 512 steps: the shortest contexts)"
     line = {
         "metric": "decode_attn_tokens_per_s", "value": res["tokens_per_s"], "unit": "tokens/s",
         "n_gpus": 1, "steps": res["steps"], "warmup": args.warmup, "ms_per_step": res["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16",
         "data": "synthetic",
-        "config": {"workload": f"{args.workload}: {res['L']} layers, {res['H']} q heads / {res['G']} kv heads x {res['d']}, "
+        "config": {"workload": f"{args.workload}{part}: {res['L']} layers, {res['H']} q heads / {res['G']} kv heads x {res['d']}, "
                                f"batch {res['B']}, context {res['ctx_desc']}, fp16 KV "
                                f"{'paged T=%d' % res['T'] if res['T'] else 'contiguous'}, all resident",
                    "split_tokens": res["split_tokens"],
@@ -679,7 +852,7 @@ def main():
         "kv_gbps": res["kv_gbps"], "hbm_frac": res["kv_gbps"] / HBM_PEAK_GBPS,
         "roofline": {"bound": "hbm", "achieved": res["kernel_gbps"], "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": res["kernel_gbps"] / HBM_PEAK_GBPS,
-                     "traffic": recorded_traffic(args.workload, res["steps"]),
+                     "traffic": recorded_traffic(args.workload, res["kv_bytes_per_launch"]),
                      "kernel": "attn_split_mfma_kernel",
                      "avg_us": res["kernel_avg_us"],
                      "launches": res["kernel_launches"], "bytes_per_launch": res["kv_bytes_per_launch"]},
@@ -690,6 +863,7 @@ def main():
         "model": model,
         "decoder_layers": layers,
     }
+    line.update(extra)
     if probe:
         line["probe"] = probe
     print(json.dumps(line), flush=True)

@@ -159,7 +159,14 @@ int kv_offload_plan(int32_t n_layers, int64_t coff_num, int64_t coff_den,
  *   otherwise Case 3: staging buffers (two if two layers fit, else one) come out
  *   of mem_avail_bytes, the layers that still fit stay resident, the rest go to
  *   the host, placed as kv_offload_plan places them.  The share moved is never
- *   below 1 - mem_avail / (n_layers * layer_bytes).
+ *   below 1 - mem_avail / (n_layers * layer_bytes).  Two buffers are preferred to a
+ *   resident layer: when exactly two layers fit, both become staging buffers and
+ *   every layer is streamed, although one resident layer beside one buffer would
+ *   move one layer less per step.  With one buffer a copy cannot start before the
+ *   attention over the previous one has ended, so the link idles during every
+ *   attention launch and the attention during every copy; with two the copies run
+ *   back to back, which is worth more than a layer's bytes unless there are very
+ *   few layers.
  *   n_staging HOST out: 0, 1 or 2 (may be NULL). */
 int okv_plan_from_bytes(int32_t n_layers, int64_t layer_bytes, int64_t mem_avail_bytes,
                         uint8_t *on_host, int32_t *n_off, int32_t *n_staging);
@@ -240,11 +247,20 @@ int okv_set_batch(okv_ctx *ctx, int32_t B, const int32_t *block_table, const int
  * fills), the split-K work list is rebuilt on the device, and for host layers
  * the first copies are enqueued if none are in flight.
  * OKV_ENOSPC if a sequence would outgrow its capacity or reach an unallocated
- * block (nothing is changed then). */
+ * block (nothing is changed then).  After any other failure (OKV_EHIP) the state on the
+ * device is unknown and the batch has to be described again with okv_set_batch; until then
+ * the calls of a step return OKV_ESTATE. */
 int okv_step_begin(okv_ctx *ctx);
 
 /* Closes the step.  OKV_ESTATE unless every layer had its decode_attn. */
 int okv_step_end(okv_ctx *ctx);
+
+/* Gives up an open step (after a call inside it failed, say, and the remaining layers cannot be
+ * supplied): waits for everything enqueued, closes the step and forgets the batch.  The layers visited
+ * so far hold the step's rows and the lengths have advanced on the device, which cannot be taken back,
+ * so the next call must be okv_set_batch with the lengths the caller wants to go on from.
+ * OKV_ESTATE outside a step. */
+int okv_step_abort(okv_ctx *ctx);
 
 /* Stores this step's key and value rows of `layer` at position ctx_len - 1 of each
  * sequence (paper §II-A: K/V of every processed token are kept for the following
@@ -266,6 +282,13 @@ int kv_append(okv_ctx *ctx, int32_t layer, const void *k_new, const void *v_new)
  * query head h reading KV head h / (H / G).
  *   q    DEVICE fp16 [B][H][d]
  *   out  DEVICE [B][H][d], fp16 or fp32 as cfg.out_dtype says
+ * Arithmetic: q, K and V enter the matrix cores as the fp16 numbers they are stored as, both
+ * products accumulate in fp32, the softmax (maximum, exponentials, their sum) is fp32, and
+ * the weights 2^(s - max), which lie in [0, 1], are rounded to fp16 on their way into the
+ * second product (the normalising sum keeps them in fp32).  That rounding is relative to
+ * the running maximum of the work item a key falls in, so results depend on how the keys
+ * are cut into items at the 1e-4 level (relative); against an fp64 evaluation the error is
+ * about 3e-4 relative per output vector.
  * For a host layer the call first makes the compute stream wait for the layer's
  * copy, and afterwards hands the staging buffer back and enqueues the next copy.
  * With block-granular offload it launches once over the keys in HBM and once per
@@ -446,11 +469,19 @@ int okv_measure_h2d(void *dst, const void *src, int64_t bytes, int32_t reps, voi
 int okv_measure_d2h(void *dst, const void *src, int64_t bytes, int32_t reps, void *stream,
                     double *gbps_median);
 
-/* The copies of one decode step alone: every host layer's pool (every streamed chunk of
- * every layer) is copied into the staging buffers (alternating), back to back on the h2d stream, nothing else running; *ms receives
- * the elapsed time.  The yardstick for how well a real step hides its compute behind the
- * copies.  Needs a batch (okv_set_batch), must not be called inside a step.  Synchronous. */
-int okv_time_copies(okv_ctx *ctx, double *ms);
+/* The copy half of n_steps decode steps alone, nothing else running: every host layer's pool (every
+ * streamed chunk of every layer) is copied into the staging buffers; *ms receives the time per step.
+ * The yardstick for how well real steps hide their compute behind the copies (paper §IV-D: a decode
+ * layer costs compute plus transfer, Eq. 6; here the two overlap).
+ *   as_pipelined = 0  the copies back to back on the h2d stream, alternating over the staging buffers,
+ *                     timed with events: what the link gives when nothing orders the copies
+ *   as_pipelined = 1  issued exactly as real steps issue them: the same copy streams, every copy waiting
+ *                     for the release of its staging buffer and followed by its record, the compute
+ *                     stream waiting for each copy and handing the buffer back where a step would
+ *                     launch attention; timed on the host between two synchronisations, as real steps
+ *                     are (the copies prefetched for the step after the last are inside it too)
+ * Needs a batch (okv_set_batch), must not be called inside a step.  Synchronous; restarts the pipeline. */
+int okv_time_copies(okv_ctx *ctx, int32_t as_pipelined, int32_t n_steps, double *ms);
 
 /* A plain device-to-device copy kernel (16 bytes per lane, grid-stride), the
  * yardstick the attention kernel's HBM traffic and rate are compared with.

@@ -18,7 +18,7 @@ _CODE_NAMES = {0: "OKV_OK", -1: "OKV_EINVAL", -2: "OKV_ENOSPC", -3: "OKV_ESTATE"
 EXPORTS = [
     "okv_layer_pool_bytes", "okv_block_bytes", "okv_kv_head_group", "okv_workspace_bytes", "kv_offload_plan", "okv_plan_from_bytes",
     "okv_plan_block_split", "okv_schedule_trace", "okv_create", "okv_destroy", "okv_last_error", "okv_set_batch",
-    "okv_step_begin", "okv_step_end", "kv_append", "decode_attn", "okv_decode_step", "okv_synchronize",
+    "okv_step_begin", "okv_step_end", "okv_step_abort", "kv_append", "decode_attn", "okv_decode_step", "okv_synchronize",
     "okv_set_split_tokens", "okv_get_split_tokens", "okv_get_ctx_lens", "okv_worklist",
     "okv_worklist_classes", "okv_prefill_begin", "kv_append_bulk", "okv_prefill_release", "okv_prefill_end", "okv_prefill_plan",
     "okv_measure_d2h",
@@ -103,6 +103,7 @@ def lib():
             "okv_set_batch": (ctypes.c_int, [P, I32, P, P]),
             "okv_step_begin": (ctypes.c_int, [P]),
             "okv_step_end": (ctypes.c_int, [P]),
+            "okv_step_abort": (ctypes.c_int, [P]),
             "kv_append": (ctypes.c_int, [P, I32, P, P]),
             "decode_attn": (ctypes.c_int, [P, I32, P, P]),
             "okv_decode_step": (ctypes.c_int, [P, P, P, P, P]),
@@ -120,7 +121,7 @@ def lib():
             "okv_prefill_release": (ctypes.c_int, [P, I32]),
             "okv_prefill_end": (ctypes.c_int, [P]),
             "okv_prefill_plan": (ctypes.c_int, [P] + [ctypes.POINTER(I64)] * 4),
-            "okv_time_copies": (ctypes.c_int, [P, ctypes.POINTER(ctypes.c_double)]),
+            "okv_time_copies": (ctypes.c_int, [P, I32, I32, ctypes.POINTER(ctypes.c_double)]),
             "okv_probe_copy": (ctypes.c_int, [P, P, I64, P]),
             "okv_pack_linear_weight": (ctypes.c_int, [P, P, I32, I32, P]),
             "okv_linear": (ctypes.c_int, [P, P, P, P, ctypes.POINTER(P), I32, I32, I32, I32, I32, P, I64, P]),
@@ -374,6 +375,9 @@ class Context:
     def okv_step_end(self):
         self._c(lib().okv_step_end(self._h))
 
+    def okv_step_abort(self):
+        self._c(lib().okv_step_abort(self._h))
+
     def kv_append(self, layer, k_new, v_new):
         self._c(lib().kv_append(self._h, layer, _ptr(k_new), _ptr(v_new)))
 
@@ -462,9 +466,10 @@ class Context:
         self._c(lib().okv_worklist_classes(self._h, 1 if from_device else 0, _ptr(first), max_classes, ctypes.byref(n)))
         return first[:n.value + 1].copy()
 
-    def okv_time_copies(self):
+    def okv_time_copies(self, as_pipelined=False, n_steps=1):
+        """ms per step of the copy half alone (back to back, or issued as the pipeline issues it)."""
         ms = ctypes.c_double(0)
-        self._c(lib().okv_time_copies(self._h, ctypes.byref(ms)))
+        self._c(lib().okv_time_copies(self._h, 1 if as_pipelined else 0, n_steps, ctypes.byref(ms)))
         return ms.value
 
     def okv_profile_enable(self, on):

@@ -7,6 +7,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <chrono>
 #include <string>
 #include <utility>
 #include <vector>
@@ -852,22 +853,43 @@ int okv_step_begin(okv_ctx *ctx) {
     if (s.paged && ctx->h_block_table[(size_t)b * s.max_blocks + (n >> s.log2_T)] < 0)
       return fail(ctx, OKV_ENOSPC, "sequence %d has no block allocated for token %d", b, n);
   }
-  for (int32_t b = 0; b < ctx->B; ++b) ctx->h_ctx_lens[b] += 1;
-  int rc = rebuild_worklist(ctx, 1);
-  if (rc) {
-    for (int32_t b = 0; b < ctx->B; ++b) ctx->h_ctx_lens[b] -= 1;
-    return rc;
-  }
+  // The first copies go out before anything is advanced: a failure here leaves the lengths as they were.
+  // What it does leave is a copy pipeline in an unknown state, so the batch has to be described again.
   if (ctx->sched.n_units() > 0 && !ctx->sched.primed()) {
     std::vector<Op> ops;
     ctx->sched.prime(ops);
-    rc = exec_ops(ctx, ops, nullptr, nullptr, nullptr);
-    if (rc) return rc;
+    const int rc = exec_ops(ctx, ops, nullptr, nullptr, nullptr);
+    if (rc) {
+      ctx->batch_set = false;
+      return rc;
+    }
+  }
+  for (int32_t b = 0; b < ctx->B; ++b) ctx->h_ctx_lens[b] += 1;
+  const int rc = rebuild_worklist(ctx, 1);
+  if (rc) {
+    for (int32_t b = 0; b < ctx->B; ++b) ctx->h_ctx_lens[b] -= 1;
+    // OKV_ENOSPC is found on the host before anything is enqueued; any other failure may have left the
+    // device lengths advanced, and only okv_set_batch uploads them again
+    if (rc != OKV_ENOSPC) ctx->batch_set = false;
+    return rc;
   }
   ctx->in_step = true;
   ctx->next_layer = 0;
   ctx->appended = false;
   return OKV_OK;
+}
+
+int okv_step_abort(okv_ctx *ctx) {
+  if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
+  if (!ctx->in_step) return fail(ctx, OKV_ESTATE, "okv_step_abort outside a step");
+  // the layers visited so far hold this step's rows, the others do not, and the lengths have advanced:
+  // nothing of that can be taken back, so the batch counts as not described
+  ctx->in_step = false;
+  ctx->appended = false;
+  ctx->pending_k = ctx->pending_v = nullptr;
+  ctx->prof_open = false;
+  ctx->batch_set = false;
+  return okv_synchronize(ctx);
 }
 
 int okv_step_end(okv_ctx *ctx) {
@@ -1365,8 +1387,9 @@ int okv_measure_d2h(void *dst, const void *src, int64_t bytes, int32_t reps, voi
   return OKV_OK;
 }
 
-int okv_time_copies(okv_ctx *ctx, double *ms) {
+int okv_time_copies(okv_ctx *ctx, int32_t as_pipelined, int32_t n_steps, double *ms) {
   if (!ctx || !ms) return fail(ctx, OKV_EINVAL, "NULL argument");
+  if (n_steps < 1) return fail(ctx, OKV_EINVAL, "okv_time_copies: n_steps < 1");
   if (!ctx->batch_set) return fail(ctx, OKV_ESTATE, "no batch set");
   if (ctx->in_step) return fail(ctx, OKV_ESTATE, "okv_time_copies inside a step");
   *ms = 0;
@@ -1376,27 +1399,55 @@ int okv_time_copies(okv_ctx *ctx, double *ms) {
   hipEvent_t e0, e1;
   OKV_HIP(ctx, hipEventCreate(&e0));
   OKV_HIP(ctx, hipEventCreate(&e1));
-  hipError_t e = hipEventRecord(e0, ctx->h2d);
-  int buf = 0;
-  for (int32_t l = 0; l < ctx->cfg.n_layers && e == hipSuccess; ++l) {
-    if (!ctx->host_pool[l]) continue;
-    for (size_t u = 0; u < ctx->unit_bytes.size() && e == hipSuccess; ++u) {
-      const char *src = static_cast<const char *>(ctx->host_pool[l]) + ctx->unit_offset[u];
-      e = hipMemcpyAsync(ctx->cfg.staging[buf], src, (size_t)ctx->unit_bytes[u], hipMemcpyHostToDevice, ctx->h2d);
-      buf = (buf + 1) % ctx->n_staging;
-    }
-  }
-  if (e == hipSuccess) e = hipEventRecord(e1, ctx->h2d);
-  if (e == hipSuccess) e = hipEventSynchronize(e1);
+  hipError_t e = hipSuccess;
   float t = 0;
-  if (e == hipSuccess) e = hipEventElapsedTime(&t, e0, e1);
+  if (!as_pipelined) {
+    e = hipEventRecord(e0, ctx->h2d);
+    int buf = 0;
+    for (int32_t step = 0; step < n_steps; ++step)
+      for (int32_t l = 0; l < ctx->cfg.n_layers && e == hipSuccess; ++l) {
+        if (!ctx->host_pool[l]) continue;
+        for (size_t u = 0; u < ctx->unit_bytes.size() && e == hipSuccess; ++u) {
+          const char *src = static_cast<const char *>(ctx->host_pool[l]) + ctx->unit_offset[u];
+          e = hipMemcpyAsync(ctx->cfg.staging[buf], src, (size_t)ctx->unit_bytes[u], hipMemcpyHostToDevice, ctx->h2d);
+          buf = (buf + 1) % ctx->n_staging;
+        }
+      }
+    if (e == hipSuccess) e = hipEventRecord(e1, ctx->h2d);
+    if (e == hipSuccess) e = hipEventSynchronize(e1);
+    if (e == hipSuccess) e = hipEventElapsedTime(&t, e0, e1);
+  } else {
+    // the copy half of the steps exactly as the pipeline issues it: same streams, same waits for a buffer's
+    // release and same records after every copy; where a step launches attention, the compute stream only
+    // waits for the copy and hands the buffer back.  Timed on the host between two synchronisations, as a
+    // benchmark times real steps (the copies prefetched for the step after the last are inside it too).
+    reset_schedule(ctx);
+    std::vector<Op> ops;
+    const auto t0 = std::chrono::steady_clock::now();
+    ctx->sched.prime(ops);
+    for (int32_t step = 0; step < n_steps; ++step)
+      for (int32_t l = 0; l < ctx->cfg.n_layers; ++l) ctx->sched.on_attn(step, l, ops);
+    for (const Op &op : ops) {
+      if (e != hipSuccess) break;
+      if (op.kind == okv::OP_COPY) {
+        if (exec_op(ctx, op, nullptr, nullptr, nullptr) != OKV_OK) e = hipErrorUnknown;
+      } else if (op.kind == okv::OP_ATTN && op.wait_idx >= 0) {
+        e = hipStreamWaitEvent(ctx->compute, ctx->ready_ev[op.wait_idx % kEventRing], 0);
+      } else if (op.kind == okv::OP_RELEASE) {
+        e = hipEventRecord(ctx->consumed_ev[op.copy_idx % kEventRing], ctx->compute);
+      }
+    }
+    if (e == hipSuccess && okv_synchronize(ctx) != OKV_OK) e = hipErrorUnknown;
+    t = (float)std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();
+  }
   (void)hipEventDestroy(e0);
   (void)hipEventDestroy(e1);
   if (e != hipSuccess) return fail(ctx, OKV_EHIP, "okv_time_copies: %s", hipGetErrorString(e));
-  *ms = t;
+  *ms = t / n_steps;
   // the staging buffers no longer hold what the pipeline had prefetched: start it afresh
+  rc = okv_synchronize(ctx);
   reset_schedule(ctx);
-  return OKV_OK;
+  return rc;
 }
 
 // ---- linear layers ---------------------------------------------------------------------------

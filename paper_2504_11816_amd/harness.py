@@ -22,6 +22,8 @@ def _hip_runtime():
         _hip.hipHostMalloc.restype = ctypes.c_int
         _hip.hipHostFree.argtypes = [ctypes.c_void_p]
         _hip.hipHostFree.restype = ctypes.c_int
+        _hip.hipGetLastError.argtypes = []
+        _hip.hipGetLastError.restype = ctypes.c_int
     return _hip
 
 
@@ -35,6 +37,9 @@ class PinnedHalfBuffer:
         p = ctypes.c_void_p(0)
         rc = _hip_runtime().hipHostMalloc(ctypes.byref(p), self.nbytes, 0)
         if rc != 0 or not p.value:
+            # the runtime keeps the refusal as its "last error", and the next library that looks (torch after
+            # any call of its own) would report it as its own failure: read it, which clears it
+            _hip_runtime().hipGetLastError()
             raise MemoryError(f"hipHostMalloc({self.nbytes}) failed with {rc}")
         self.ptr = p.value
         raw = (ctypes.c_char * self.nbytes).from_address(self.ptr)
@@ -90,29 +95,14 @@ class Stack:
         self.resident_blocks, self.chunk_blocks = resident_blocks, chunk_blocks
         self.pools, self._pinned = [], []
         self.dev_part, self.host_part = [None] * L, [None] * L
-        if self.by_class:
-            self.block_elems = binding.okv_block_bytes(shape) // 2
-            self.split_at = resident_blocks * self.block_elems      # first element of the host part
-            host_el = n_el - self.split_at
-            for l in range(L):
-                if self.split_at:
-                    self.dev_part[l] = torch.empty(self.split_at, dtype=torch.float16, device=self.device)
-                if host_el:
-                    self._pinned.append(PinnedHalfBuffer(host_el))
-                    self.host_part[l] = self._pinned[-1].tensor
-            any_host = host_el > 0
-            staging_el = min(chunk_blocks, self.blocks_per_layer - resident_blocks) * self.block_elems
-        else:
-            for l in range(L):
-                if self.on_host[l]:
-                    self._pinned.append(PinnedHalfBuffer(n_el))
-                    self.pools.append(self._pinned[-1].tensor)
-                    self.host_part[l] = self.pools[-1]
-                else:
-                    self.pools.append(torch.empty(n_el, dtype=torch.float16, device=self.device))
-                    self.dev_part[l] = self.pools[-1]
-            any_host = bool(self.on_host.any())
-            staging_el = n_el
+        try:
+            self._allocate_pools(L, n_el, resident_blocks, chunk_blocks, shape)
+        except MemoryError:
+            for p in self._pinned:                       # what was pinned before the refusal goes back at once
+                p.free()
+            self._pinned = []
+            raise
+        any_host, staging_el = self._any_host, self._staging_el
         self.staging_bytes = staging_el * 2 if any_host else 0
         self.staging = [torch.empty(staging_el, dtype=torch.float16, device=self.device) if any_host and i < n_staging
                         else None for i in range(4)]
@@ -131,6 +121,31 @@ class Stack:
             compute_stream=self.compute_stream.cuda_stream, h2d_stream=self.h2d_stream.cuda_stream)
         self.block_table = None
         self.ctx_lens = None
+
+    def _allocate_pools(self, L, n_el, resident_blocks, chunk_blocks, shape):
+        if self.by_class:
+            self.block_elems = binding.okv_block_bytes(shape) // 2
+            self.split_at = resident_blocks * self.block_elems      # first element of the host part
+            host_el = n_el - self.split_at
+            for l in range(L):
+                if self.split_at:
+                    self.dev_part[l] = torch.empty(self.split_at, dtype=torch.float16, device=self.device)
+                if host_el:
+                    self._pinned.append(PinnedHalfBuffer(host_el))
+                    self.host_part[l] = self._pinned[-1].tensor
+            self._any_host = host_el > 0
+            self._staging_el = min(chunk_blocks, self.blocks_per_layer - resident_blocks) * self.block_elems
+        else:
+            for l in range(L):
+                if self.on_host[l]:
+                    self._pinned.append(PinnedHalfBuffer(n_el))
+                    self.pools.append(self._pinned[-1].tensor)
+                    self.host_part[l] = self.pools[-1]
+                else:
+                    self.pools.append(torch.empty(n_el, dtype=torch.float16, device=self.device))
+                    self.dev_part[l] = self.pools[-1]
+            self._any_host = bool(self.on_host.any())
+            self._staging_el = n_el
 
     # ---- batch ------------------------------------------------------------------
     def set_batch(self, ctx_lens, block_table=None):

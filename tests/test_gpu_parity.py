@@ -325,6 +325,16 @@ def test_error_paths():
         c.kv_append(l, k[l], v[l])
         c.decode_attn(l, q[l], out[l])
     c.okv_step_end()
+    # a step given up half way: the batch has to be described again before anything else
+    assert code(c.okv_step_abort) == binding.OKV_ESTATE                       # no step open
+    c.okv_step_begin()
+    c.kv_append(0, k[0], v[0])
+    assert code(c.kv_append, 0, k[0], v[0]) == binding.OKV_ESTATE             # the failure a caller gives up after
+    assert code(st.set_batch, [10, 20], st.block_table) == binding.OKV_ESTATE # still inside the step
+    c.okv_step_abort()
+    assert code(c.okv_step_begin) == binding.OKV_ESTATE                       # no batch
+    st.set_batch([10, 20], st.block_table)
+    run_and_check(st, n_steps=1, seed=87)                                     # and the context works as before
     # capacity: 32 tokens; 20 + 1 stored, 11 more fit
     st.set_batch([10, 32], st.block_table)
     assert code(c.okv_step_begin) == binding.OKV_ENOSPC
@@ -370,51 +380,6 @@ def test_probe_kernels_and_link_measurement():
     gbps = binding.okv_measure_h2d(dst, host, n, 3, s.cuda_stream)
     assert gbps > 1.0
     assert torch.equal(dst, src)
-
-
-# ---- the benchmark shapes at full size, sampled -----------------------------------------------------
-
-def _sampled_full_size(name, B, H, G, T, ctx_before, cap, on_host, pairs, steps=2, L=2):
-    say(f"full size {name}")
-    st = Stack(L=L, H=H, G=G, d=128, B=B, T=T, cap_tokens=cap, on_host=on_host, out_dtype=0)
-    for l in range(L):
-        st.fill_pool(l, synth.stream_seed(91, synth.TENSOR_POOL, l))
-    table = None
-    if T:
-        table = synth.shuffled_block_table([st.cap_tokens] * B, T, st.blocks_per_layer, 93,
-                                           max_blocks_per_seq=st.max_blocks)
-    st.set_batch(ctx_before, table)
-    say(f"  split {st.ctx.okv_get_split_tokens()}")
-    run_and_check(st, n_steps=steps, seed=95, pairs=pairs)
-    st.close()
-
-
-def test_full_size_cfg2_contiguous_mha_sampled():
-    # 32 heads x 128, batch 32, contexts 513 and 514 of capacity 1024; two of the 32 layers
-    _sampled_full_size("cfg2", 32, 32, 32, 0, [512] * 32, 1024, None, [(0, 0), (13, 7), (31, 31), (5, 18)])
-
-
-def test_full_size_cfg2_last_steps_sampled():
-    _sampled_full_size("cfg2 end", 32, 32, 32, 0, [1022] * 32, 1024, None, [(0, 31), (31, 0), (17, 9)])
-
-
-def test_full_size_cfg3_paged_half_offloaded_sampled():
-    # batch 64, context 2048, 16-token blocks, one resident and one host layer (2 GiB each)
-    _sampled_full_size("cfg3", 64, 32, 32, 16, [2047] * 64, 2064, [0, 1], [(0, 0), (63, 31), (20, 11)])
-
-
-def test_full_size_cfg5_shape_reduced_batch_sampled():
-    # context 4096, 16-token blocks, 3 of 5 layers on the host (60 %); batch 16 of the 192
-    on_host = binding.kv_offload_plan(5, 3, 5)[0]
-    assert on_host.tolist() == [0, 1, 0, 1, 1]
-    _sampled_full_size("cfg5 shape", 16, 32, 32, 16, [4094] * 16, 4112, on_host, [(0, 0), (15, 31), (7, 16)],
-                       steps=2, L=5)
-
-
-def test_full_size_cfg4_gqa_ragged_sampled():
-    ctx = synth.ragged_ctx_lens(128, 512, 4096, 97) - 1
-    lo, hi = int(np.argmin(ctx)), int(np.argmax(ctx))
-    _sampled_full_size("cfg4", 128, 32, 8, 16, ctx, 4112, None, [(lo, 0), (hi, 31), (64, 13), (1, 20)])
 
 
 def test_kernel_timing_modes_count_every_launch():
