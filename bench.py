@@ -29,22 +29,23 @@ HBM_PEAK_GBPS = 8000.0      # MI355X HBM3E, published peak
 PCIE5_X16_GBPS = 64.0       # nominal, one direction
 
 # HBM traffic of the split kernel, from two rocprofv3 --pmc runs of this file's headline workload
-# (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch summed over the timed launches), each scaled by what the
-# same counter read for the plain copy kernel of known size in the same run, and divided by the
-# algorithmic KV bytes of the same launches: HBM bytes moved per algorithmic byte.  The ratio is a
-# property of the kernel (it re-reads nothing; what exceeds 1 is q, the block table, partial results and
-# the rows appended), so it carries over to any number of steps of the workload; it is valid only for the
-# kernel source it was taken on: if okv_kernels.hip has changed since, `traffic` is reported as null.
+# (FETCH_SIZE, then WRITE_SIZE; KiB per dispatch, mean over the timed launches), each scaled by what the
+# same counter read for the plain copy kernel of known size in the same run.  Reads are kept as a ratio to
+# the algorithmic KV bytes of the same launches: the kernel re-reads nothing, and what exceeds 1 is the
+# rounding of every sequence to whole 16-key tiles plus q, so the ratio carries over to any number of steps
+# of the workload.  Writes (outputs, partial results, the appended rows) are a fixed number of bytes per
+# launch of that batch.  Both are valid only for the kernel source they were taken on: if okv_kernels.hip
+# has changed since, `traffic` is reported as null.
 TRAFFIC_RECORD = {
     "workload": "cfg2",
-    "kernel_sha256": "",
-    "fetch_ratio": 0.0, "fetch_scale": 2.0000,
-    "write_ratio": 0.0, "write_scale": 1.0000,
+    "kernel_sha256": "9500f39fdf5f2222d9ef9305504f7ab699d1e898b20464f9d821b8483125016c",
+    "fetch_kib": 141752.5, "fetch_scale": 2.0000, "algorithmic_bytes": 285474816,   # context 513..576
+    "write_kib": 768.0, "write_scale": 1.0000,
 }
 
 
 def recorded_traffic(workload, bytes_per_launch):
-    """HBM bytes per launch from the recorded counter ratios, or None if they do not apply."""
+    """HBM bytes per launch from the recorded counters, or None if they do not apply."""
     import hashlib
     rec = TRAFFIC_RECORD
     src = os.path.join(ROOT, "paper_2504_11816_amd", "csrc", "okv_kernels.hip")
@@ -54,7 +55,8 @@ def recorded_traffic(workload, bytes_per_launch):
         return None
     if not rec["kernel_sha256"] or sha != rec["kernel_sha256"] or workload != rec["workload"]:
         return None
-    return (rec["fetch_ratio"] + rec["write_ratio"]) * bytes_per_launch
+    fetch_ratio = rec["fetch_kib"] * 1024 * rec["fetch_scale"] / rec["algorithmic_bytes"]
+    return fetch_ratio * bytes_per_launch + rec["write_kib"] * 1024 * rec["write_scale"]
 
 
 def log(msg):
@@ -85,15 +87,20 @@ def kv_bytes_of_steps(ctx0, steps, G, d, L):
     return total
 
 
-def timed_steps(st, ctx0, table, inputs, steps, warmup):
-    """W untimed steps, state reset, then exactly K timed steps."""
+def timed_steps(st, ctx0, table, inputs, steps, warmup, running=False):
+    """W untimed steps, state reset, then exactly K timed steps.  running: the K steps follow the warm-up
+    steps as later steps of one generation follow earlier ones (the warm-up starts W tokens earlier, so the
+    timed steps see the same contexts); the copy pipeline is then in its running state on both sides of
+    the timed region: the first step finds its first copies done, the last one leaves those of the step
+    after it in flight, and K steps move exactly K times the offloaded bytes."""
     import torch
     bound = st.bind_step(*inputs)          # every layer of a step goes out in one call (okv_decode_step)
-    st.set_batch(ctx0, table)
+    st.set_batch(ctx0 - warmup if running else ctx0, table)
     for _ in range(warmup):
         st.step_bound(bound)
     st.synchronize()
-    st.set_batch(ctx0, table)
+    if not running:
+        st.set_batch(ctx0, table)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
@@ -385,9 +392,13 @@ def run_offload(args, name=None, B=None, steps=None, warmup=None):
     ctx0 = np.full(B, w["ctx"] - 1, dtype=np.int32)
     cap = w["ctx"] + steps + warmup
     on_host, n_off = binding.kv_offload_plan(L, w["c_off"][0], w["c_off"][1])
-    log(f"[bench] offload leg {name}: B={B} ctx={w['ctx']} T={T} host layers {n_off}/{L} steps={steps}")
+    # Whole layers: four staging buffers.  With two, the two copies in flight share the link, end together
+    # and leave it idle while the first of them is attended (0.7 ms per pair in the copy trace); with four the
+    # two copy streams drift apart and one copy is always running.  8.6 GiB of HBM at this shape.
+    n_staging = args.staging or 4
+    log(f"[bench] offload leg {name}: B={B} ctx={w['ctx']} T={T} host layers {n_off}/{L} steps={steps} staging buffers {n_staging}")
     st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=cap, on_host=on_host, out_dtype=0,
-               n_staging=args.staging)
+               n_staging=n_staging)
     for l in range(L):
         st.fill_pool(l, synth.stream_seed(args.seed, synth.TENSOR_POOL, l))
     table = synth.shuffled_block_table([st.cap_tokens] * B, T, st.blocks_per_layer, args.seed + 1,
@@ -397,7 +408,7 @@ def run_offload(args, name=None, B=None, steps=None, warmup=None):
     link = binding.okv_measure_h2d(st.staging[0], st.pools[host_layer], min(st.pool_bytes, 2 << 30), 10,
                                    st.h2d_stream.cuda_stream)
     log(f"[bench] host-to-device link: {link:.1f} GB/s (plain hipMemcpyAsync, pinned, median of 10)")
-    dt = timed_steps(st, ctx0, table, inputs, steps, warmup)
+    dt = timed_steps(st, ctx0, table, inputs, steps, warmup, running=True)
     per_tok = 2 * G * d * 2
     link_bytes = sum(int((ctx0 + s).sum()) * per_tok * n_off for s in range(1, steps + 1))
     kv_bytes = kv_bytes_of_steps(ctx0, steps, G, d, L)
@@ -405,7 +416,7 @@ def run_offload(args, name=None, B=None, steps=None, warmup=None):
     k_s, k_n = kernel_time(st, ctx0, table, inputs, 1)
     st.set_batch(ctx0, table)
     copy_ms = st.ctx.okv_time_copies(False, 1)
-    copy_pipe_ms = st.ctx.okv_time_copies(True, steps)      # as many steps as were timed: both then hold the same prefetch for the step after the last
+    copy_pipe_ms = st.ctx.okv_time_copies(True, steps)
     res = {
         "workload": name, "B": B, "ctx": w["ctx"], "host_layers": int(n_off), "layers": L, "steps": steps,
         "tokens_per_s": B * steps / dt, "ms_per_step": dt / steps * 1e3, "kv_gbps": kv_bytes / dt / 1e9,
@@ -413,8 +424,8 @@ def run_offload(args, name=None, B=None, steps=None, warmup=None):
         "link_gbps_achieved": link_bytes / dt / 1e9, "link_frac": link_bytes / dt / 1e9 / link,
         "attn_kernel_ms_per_step": k_s * 1e3, "attn_kernel_gbps": kv_bytes / steps / k_s / 1e9,
         "copy_only_ms_per_step": copy_ms,
-        "pinned_gib": n_off * st.pool_bytes / 2 ** 30, "staging_buffers": args.staging,
-        "staging_gib": args.staging * st.pool_bytes / 2 ** 30,
+        "pinned_gib": n_off * st.pool_bytes / 2 ** 30, "staging_buffers": n_staging,
+        "staging_gib": n_staging * st.pool_bytes / 2 ** 30,
     }
     # What a step costs beyond its copies run back to back, set against the attention it contains:
     # below 1 means compute is (partly) hidden; the per-copy dependency latency of the two-stream
@@ -451,9 +462,10 @@ def run_offload_blocks(args):
                                 max_blocks_per_seq=synth.blocks_needed(cap, T), blocks_per_layer=need)
     block_bytes = binding.okv_block_bytes(shape)
     chunk_blocks = max(1, (args.chunk_mib << 20) // block_bytes)
+    n_staging = args.staging or 2
     log(f"[bench] block-granular leg {name}: B={B} ctx={w['ctx']} T={T} host blocks {n_host}/{need} per layer, "
-        f"chunks of {chunk_blocks} blocks ({chunk_blocks * block_bytes / 2 ** 20:.0f} MiB), {args.staging} staging buffers")
-    st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=cap, out_dtype=0, n_staging=args.staging,
+        f"chunks of {chunk_blocks} blocks ({chunk_blocks * block_bytes / 2 ** 20:.0f} MiB), {n_staging} staging buffers")
+    st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=cap, out_dtype=0, n_staging=n_staging,
                blocks_per_layer=need, resident_blocks=n_res, chunk_blocks=chunk_blocks)
     # link rate first (it overwrites the start of layer 0's HBM part, which is filled afterwards)
     probe_bytes = min(st.dev_part[0].numel() * 2, st.host_part[0].numel() * 2, 2 << 30)
@@ -464,7 +476,7 @@ def run_offload_blocks(args):
     table = synth.classed_block_table([st.cap_tokens] * B, T, n_res, n_host, n_host, args.placement, args.seed + 1,
                                       max_blocks_per_seq=st.max_blocks)
     inputs = fixed_inputs(st, args.seed)
-    dt = timed_steps(st, ctx0, table, inputs, steps, warmup)
+    dt = timed_steps(st, ctx0, table, inputs, steps, warmup, running=True)
     # what crosses the link per step: every host block of every layer (all of them hold keys:
     # the oldest blocks of a sequence are full)
     host_tokens = int(((table >= n_res).sum(axis=1) * T).sum())
@@ -474,7 +486,7 @@ def run_offload_blocks(args):
     k_s, k_n = kernel_time(st, ctx0, table, inputs, 1)
     st.set_batch(ctx0, table)
     copy_ms = st.ctx.okv_time_copies(False, 1)
-    copy_pipe_ms = st.ctx.okv_time_copies(True, steps)      # as many steps as were timed: both then hold the same prefetch for the step after the last
+    copy_pipe_ms = st.ctx.okv_time_copies(True, steps)
     res = {
         "workload": name, "placement": args.placement, "B": B, "ctx": w["ctx"], "layers": L, "steps": steps,
         "host_blocks_per_layer": int(n_host), "blocks_per_layer": int(need),
@@ -486,7 +498,7 @@ def run_offload_blocks(args):
         "attn_kernel_ms_per_step": k_s * 1e3, "attn_launches_per_step": k_n,
         "copy_only_ms_per_step": copy_ms, "step_minus_copies_ms": dt / steps * 1e3 - copy_ms,
         "pinned_gib": L * st.host_part[0].numel() * 2 / 2 ** 30,
-        "staging_buffers": args.staging, "staging_gib": args.staging * st.staging_bytes / 2 ** 30,
+        "staging_buffers": n_staging, "staging_gib": n_staging * st.staging_bytes / 2 ** 30,
         "split_tokens": st.ctx.okv_get_split_tokens(),
     }
     overlap_figures(res, res["ms_per_step"], copy_ms, copy_pipe_ms, res["attn_kernel_ms_per_step"])
@@ -516,7 +528,7 @@ def run_prefill(args):
     P = w["ctx"]
     on_host, n_off = binding.kv_offload_plan(L, w["c_off"][0], w["c_off"][1])
     log(f"[bench] prefill leg {name}: B={B} prompt={P} T={T} host layers {n_off}/{L}")
-    st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=P + 16, on_host=on_host, out_dtype=0, n_staging=args.staging)
+    st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=P + 16, on_host=on_host, out_dtype=0, n_staging=args.staging or 2)
     if args.prefill_table == "ordered":                  # a sequence's blocks are neighbours in the pool
         table = synth.identity_block_table([st.cap_tokens] * B, T, max_blocks_per_seq=st.max_blocks)
     else:
@@ -789,7 +801,7 @@ def main():
     ap.add_argument("--offload-workload", default="cfg3", choices=["cfg3", "cfg5"])
     ap.add_argument("--offload-steps", type=int, default=0)
     ap.add_argument("--offload-batch", type=int, default=0)
-    ap.add_argument("--staging", type=int, default=2, help="staging buffers for host layers (1..4)")
+    ap.add_argument("--staging", type=int, default=0, help="staging buffers (1..4); 0 = 4 for whole layers, 2 for chunks")
     ap.add_argument("--no-blocks", action="store_true", help="skip the block-granular offloaded leg")
     ap.add_argument("--no-configs", action="store_true",
                     help="skip the legs of the other named workloads (cfg2 in full, cfg4, cfg1)")

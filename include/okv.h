@@ -478,8 +478,10 @@ int okv_measure_d2h(void *dst, const void *src, int64_t bytes, int32_t reps, voi
  *   as_pipelined = 1  issued exactly as real steps issue them: the same copy streams, every copy waiting
  *                     for the release of its staging buffer and followed by its record, the compute
  *                     stream waiting for each copy and handing the buffer back where a step would
- *                     launch attention; timed on the host between two synchronisations, as real steps
- *                     are (the copies prefetched for the step after the last are inside it too)
+ *                     launch attention; timed on the host between two synchronisations, from the
+ *                     pipeline's running state (the first copies are done before the clock starts, the
+ *                     copies prefetched for the step after the last are inside it), so that n_steps steps
+ *                     move exactly n_steps times the offloaded bytes
  * Needs a batch (okv_set_batch), must not be called inside a step.  Synchronous; restarts the pipeline. */
 int okv_time_copies(okv_ctx *ctx, int32_t as_pipelined, int32_t n_steps, double *ms);
 

@@ -1419,12 +1419,17 @@ int okv_time_copies(okv_ctx *ctx, int32_t as_pipelined, int32_t n_steps, double 
   } else {
     // the copy half of the steps exactly as the pipeline issues it: same streams, same waits for a buffer's
     // release and same records after every copy; where a step launches attention, the compute stream only
-    // waits for the copy and hands the buffer back.  Timed on the host between two synchronisations, as a
-    // benchmark times real steps (the copies prefetched for the step after the last are inside it too).
+    // waits for the copy and hands the buffer back.  Like a step in the middle of a generation, the first one
+    // finds its first copies done and the last one leaves those of the step after it in flight, so n_steps
+    // steps move exactly n_steps times the offloaded bytes between the two synchronisations that bracket them.
     reset_schedule(ctx);
     std::vector<Op> ops;
-    const auto t0 = std::chrono::steady_clock::now();
     ctx->sched.prime(ops);
+    for (const Op &op : ops)
+      if (e == hipSuccess && op.kind == okv::OP_COPY && exec_op(ctx, op, nullptr, nullptr, nullptr) != OKV_OK) e = hipErrorUnknown;
+    if (e == hipSuccess && okv_synchronize(ctx) != OKV_OK) e = hipErrorUnknown;
+    ops.clear();
+    const auto t0 = std::chrono::steady_clock::now();
     for (int32_t step = 0; step < n_steps; ++step)
       for (int32_t l = 0; l < ctx->cfg.n_layers; ++l) ctx->sched.on_attn(step, l, ops);
     for (const Op &op : ops) {
