@@ -466,7 +466,7 @@ def run_offload_blocks(args):
     log(f"[bench] block-granular leg {name}: B={B} ctx={w['ctx']} T={T} host blocks {n_host}/{need} per layer, "
         f"chunks of {chunk_blocks} blocks ({chunk_blocks * block_bytes / 2 ** 20:.0f} MiB), {n_staging} staging buffers")
     st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=cap, out_dtype=0, n_staging=n_staging,
-               blocks_per_layer=need, resident_blocks=n_res, chunk_blocks=chunk_blocks)
+               blocks_per_layer=need, resident_blocks=n_res, chunk_blocks=chunk_blocks, hot_tails=not args.no_tails)
     # link rate first (it overwrites the start of layer 0's HBM part, which is filled afterwards)
     probe_bytes = min(st.dev_part[0].numel() * 2, st.host_part[0].numel() * 2, 2 << 30)
     link = binding.okv_measure_h2d(st.dev_part[0], st.host_part[0], probe_bytes, 10, st.h2d_stream.cuda_stream)
@@ -803,6 +803,9 @@ def main():
     ap.add_argument("--offload-batch", type=int, default=0)
     ap.add_argument("--staging", type=int, default=0, help="staging buffers (1..4); 0 = 4 for whole layers, 2 for chunks")
     ap.add_argument("--no-blocks", action="store_true", help="skip the block-granular offloaded leg")
+    ap.add_argument("--no-tails", action="store_true",
+                    help="block-granular leg: store every appended row through the mapped pointer instead of keeping "
+                         "the newest blocks in HBM")
     ap.add_argument("--no-configs", action="store_true",
                     help="skip the legs of the other named workloads (cfg2 in full, cfg4, cfg1)")
     ap.add_argument("--no-cfg5", action="store_true", help="skip the offline large-batch offloaded leg")

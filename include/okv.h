@@ -93,8 +93,10 @@ typedef struct okv_config {
   void   *staging[OKV_MAX_STAGING]; /* DEVICE: buffers host layers are copied into, each at least
                                   okv_layer_pool_bytes.  The leading non-NULL entries are used:
                                   one = no overlap of copy and compute; two = the copy of the next
-                                  host layer runs during this one's attention (more than two
-                                  measured no faster).  All NULL if no layer is on the host      */
+                                  host layer runs during this one's attention; with four, one copy
+                                  is running at any time (two copies in flight end together and
+                                  leave the link idle while the first is attended: 1-2 % of a
+                                  step).  All NULL if no layer is on the host                   */
   int64_t staging_bytes;       /* size of each staging buffer                                */
   void   *workspace;           /* DEVICE: split-K partial results                            */
   int64_t workspace_bytes;     /* at least okv_workspace_bytes(cfg)                          */
@@ -118,6 +120,16 @@ typedef struct okv_config {
    * fewer work items. */
   int64_t resident_blocks;
   int64_t chunk_blocks;
+  /* Block-granular offload only, optional (paper §IV-C Case 3 keeps what does not fit in host
+   * memory; which rows travel when is left open).  DEVICE memory of okv_tail_bytes(cfg) bytes: two
+   * block-sized slots per sequence and layer.  With it, the rows that decode steps append to a
+   * block of the HOST pool are kept in a slot in HBM and the block is written to the host pool
+   * once, when it is full (after the step that fills it; okv_flush_tails, okv_set_batch and
+   * okv_prefill_begin write out what is left).  Until then the host pool lacks those rows: read it
+   * only after okv_flush_tails.  NULL: every appended row is stored through the mapped pointer of
+   * the host pool in the step that appends it, and the host pool is complete after every step. */
+  void   *tail_blocks;
+  int64_t tail_bytes;
 } okv_config;
 
 /* ---- sizes ------------------------------------------------------------------ */
@@ -139,6 +151,10 @@ int32_t okv_kv_head_group(int32_t n_kv_heads, int32_t head_dim);
  * sequence at full capacity, the smallest split size the library would choose or
  * cfg->split_tokens if set); < 0 on a bad cfg. */
 int64_t okv_workspace_bytes(const okv_config *cfg);
+
+/* Bytes that cfg->tail_blocks has to hold (n_layers * 2 * max_batch * okv_block_bytes), 0 if
+ * cfg->chunk_blocks == 0; < 0 on a bad cfg.  Only the shape fields are read. */
+int64_t okv_tail_bytes(const okv_config *cfg);
 
 /* ---- offload plan (pure host functions, no GPU, no context) ------------------- */
 
@@ -245,15 +261,27 @@ int okv_set_batch(okv_ctx *ctx, int32_t B, const int32_t *block_table, const int
 
 /* Opens a decode step: every sequence's length grows by one (the slot kv_append
  * fills), the split-K work list is rebuilt on the device, and for host layers
- * the first copies are enqueued if none are in flight.
+ * the first copies are enqueued if none are in flight.  With block-granular offload
+ * (chunk_blocks > 0, blocks on the host) the call first waits until the previous step's
+ * kernels have finished: letting the host enqueue several steps ahead made those steps
+ * up to 10 % slower and erratic, and the compute stream waits for copies most of the
+ * time anyway.
  * OKV_ENOSPC if a sequence would outgrow its capacity or reach an unallocated
  * block (nothing is changed then).  After any other failure (OKV_EHIP) the state on the
  * device is unknown and the batch has to be described again with okv_set_batch; until then
  * the calls of a step return OKV_ESTATE. */
 int okv_step_begin(okv_ctx *ctx);
 
-/* Closes the step.  OKV_ESTATE unless every layer had its decode_attn. */
+/* Closes the step.  OKV_ESTATE unless every layer had its decode_attn.  With cfg->tail_blocks, the
+ * blocks of the host pools that this step filled are written out (one kernel on the compute stream,
+ * after the step's attention; copies of the host pools enqueued later wait for it). */
 int okv_step_end(okv_ctx *ctx);
+
+/* Writes every appended row that is still only in a slot of cfg->tail_blocks to the host pools, so
+ * that they are complete; waits for it, and restarts the copy pipeline (copies made before lack
+ * those rows).  Without tail_blocks it only synchronises.  Needs a batch; not inside a step or a
+ * prefill (OKV_ESTATE). */
+int okv_flush_tails(okv_ctx *ctx);
 
 /* Gives up an open step (after a call inside it failed, say, and the remaining layers cannot be
  * supplied): waits for everything enqueued, closes the step and forgets the batch.  The layers visited

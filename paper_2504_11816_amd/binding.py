@@ -16,9 +16,9 @@ _CODE_NAMES = {0: "OKV_OK", -1: "OKV_EINVAL", -2: "OKV_ENOSPC", -3: "OKV_ESTATE"
 
 # every symbol include/okv.h declares
 EXPORTS = [
-    "okv_layer_pool_bytes", "okv_block_bytes", "okv_kv_head_group", "okv_workspace_bytes", "kv_offload_plan", "okv_plan_from_bytes",
+    "okv_layer_pool_bytes", "okv_block_bytes", "okv_kv_head_group", "okv_workspace_bytes", "okv_tail_bytes", "kv_offload_plan", "okv_plan_from_bytes",
     "okv_plan_block_split", "okv_schedule_trace", "okv_create", "okv_destroy", "okv_last_error", "okv_set_batch",
-    "okv_step_begin", "okv_step_end", "okv_step_abort", "kv_append", "decode_attn", "okv_decode_step", "okv_synchronize",
+    "okv_step_begin", "okv_step_end", "okv_step_abort", "okv_flush_tails", "kv_append", "decode_attn", "okv_decode_step", "okv_synchronize",
     "okv_set_split_tokens", "okv_get_split_tokens", "okv_get_ctx_lens", "okv_worklist",
     "okv_worklist_classes", "okv_prefill_begin", "kv_append_bulk", "okv_prefill_release", "okv_prefill_end", "okv_prefill_plan",
     "okv_measure_d2h",
@@ -55,6 +55,7 @@ class OkvConfig(ctypes.Structure):
         ("workspace", ctypes.c_void_p), ("workspace_bytes", ctypes.c_int64),
         ("compute_stream", ctypes.c_void_p), ("h2d_stream", ctypes.c_void_p),
         ("resident_blocks", ctypes.c_int64), ("chunk_blocks", ctypes.c_int64),
+        ("tail_blocks", ctypes.c_void_p), ("tail_bytes", ctypes.c_int64),
     ]
 
 
@@ -92,6 +93,7 @@ def lib():
             "okv_block_bytes": (I64, [cfgp]),
             "okv_kv_head_group": (I32, [I32, I32]),
             "okv_workspace_bytes": (I64, [cfgp]),
+            "okv_tail_bytes": (I64, [cfgp]),
             "okv_plan_block_split": (ctypes.c_int, [I64, I64, I64, ctypes.POINTER(I64), ctypes.POINTER(I64)]),
             "okv_worklist_classes": (ctypes.c_int, [P, I32, P, I32, ctypes.POINTER(I32)]),
             "kv_offload_plan": (ctypes.c_int, [I32, I64, I64, P, ctypes.POINTER(I32)]),
@@ -104,6 +106,7 @@ def lib():
             "okv_step_begin": (ctypes.c_int, [P]),
             "okv_step_end": (ctypes.c_int, [P]),
             "okv_step_abort": (ctypes.c_int, [P]),
+            "okv_flush_tails": (ctypes.c_int, [P]),
             "kv_append": (ctypes.c_int, [P, I32, P, P]),
             "decode_attn": (ctypes.c_int, [P, I32, P, P]),
             "okv_decode_step": (ctypes.c_int, [P, P, P, P, P]),
@@ -260,6 +263,13 @@ def okv_workspace_bytes(cfg):
     return int(r)
 
 
+def okv_tail_bytes(cfg):
+    r = lib().okv_tail_bytes(ctypes.byref(cfg))
+    if r < 0:
+        _check(int(r))
+    return int(r)
+
+
 def okv_measure_h2d(dst, src, nbytes, reps, stream):
     g = ctypes.c_double(0)
     _check(lib().okv_measure_h2d(_ptr(dst), _ptr(src), nbytes, reps, _ptr(stream), ctypes.byref(g)))
@@ -327,7 +337,8 @@ class Context:
     def __init__(self, *, n_layers, n_q_heads, n_kv_heads, head_dim, block_tokens, max_batch,
                  max_blocks_per_seq=0, max_ctx=0, blocks_per_layer=0, out_dtype=0, split_tokens=0,
                  dev_pool, host_pool=None, staging=(None, None), staging_bytes=0,
-                 workspace, workspace_bytes, compute_stream=0, h2d_stream=0, resident_blocks=0, chunk_blocks=0):
+                 workspace, workspace_bytes, compute_stream=0, h2d_stream=0, resident_blocks=0, chunk_blocks=0,
+                 tail_blocks=None, tail_bytes=0):
         L = n_layers
         self._dev = (ctypes.c_void_p * L)(*[_ptr(p) for p in dev_pool])
         self._host = (ctypes.c_void_p * L)(*[_ptr(p) for p in (host_pool or [None] * L)])
@@ -343,6 +354,7 @@ class Context:
         cfg.workspace, cfg.workspace_bytes = _ptr(workspace), workspace_bytes
         cfg.compute_stream, cfg.h2d_stream = _ptr(compute_stream), _ptr(h2d_stream)
         cfg.resident_blocks, cfg.chunk_blocks = resident_blocks, chunk_blocks
+        cfg.tail_blocks, cfg.tail_bytes = _ptr(tail_blocks), tail_bytes
         self.cfg = cfg
         self.B = 0
         self._h = ctypes.c_void_p(0)
@@ -377,6 +389,9 @@ class Context:
 
     def okv_step_abort(self):
         self._c(lib().okv_step_abort(self._h))
+
+    def okv_flush_tails(self):
+        self._c(lib().okv_flush_tails(self._h))
 
     def kv_append(self, layer, k_new, v_new):
         self._c(lib().kv_append(self._h, layer, _ptr(k_new), _ptr(v_new)))

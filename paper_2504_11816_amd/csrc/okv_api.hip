@@ -48,6 +48,15 @@ constexpr int64_t kMaxClasses = 4096;
 #ifndef OKV_HOST_WRITE_WORKGROUPS
 #define OKV_HOST_WRITE_WORKGROUPS 64
 #endif
+// With a share of every layer's blocks on the host, how many steps the host may have enqueued that the
+// compute stream has not finished when a new one begins (0 = no limit).  Steps enqueued several deep made the
+// chunked copy pipeline slower and erratic (cfg3 shape in 256 MiB chunks: 608.7 ms a step in every process
+// with 1, 610 with 2, 615 without a limit on a quiet machine and 624-695 from process to process on others);
+// the compute stream waits for copies most of the time anyway.  Whole layers on the host are the other way
+// round (606.9 ms a step without a limit, 608.5 with 2, 610.8 with 1) and never were erratic: no limit there.
+#ifndef OKV_STEPS_AHEAD
+#define OKV_STEPS_AHEAD 1
+#endif
 // Blocks bound for the host are gathered in a staging buffer and moved by hipMemcpyAsync when, on
 // average, at least this many bytes of them are adjacent in the host pool; below that the per-copy
 // cost is too high and the rows are written by a kernel through the mapped pointer instead.
@@ -81,6 +90,22 @@ struct okv_ctx {
   int4 *d_runs = nullptr;
   int32_t *d_pair_first = nullptr, *d_seq_total = nullptr;
   int64_t runs_cap = 0;
+
+  // The sequences' newest blocks kept in HBM (cfg.tail_blocks): positions from tail_from[b] on were
+  // appended through this context and, where their block belongs to the host pool, reach it only when
+  // the block is full (or on okv_flush_tails).
+  bool tail_on = false;
+  bool tail_dirty = false;               // some appended row may not have reached the host pool yet
+  int64_t tail_layer_stride = 0;         // numbers between two layers' slots
+  int32_t *d_tail_from = nullptr;
+  void **d_host_ptrs = nullptr;          // device array [L] of the host pools' device-visible addresses
+  std::vector<int32_t> h_tail_from;
+  std::vector<uint8_t> patch_chunk;      // per active chunk: a newest or second-newest block of the batch lies in it
+  hipEvent_t flush_ev = nullptr;
+  bool flush_recorded = false;
+  // host layers or blocks: the ends of the last steps on the compute stream (a ring)
+  hipEvent_t step_done_ev[OKV_STEPS_AHEAD > 0 ? OKV_STEPS_AHEAD : 1] = {};
+  int64_t steps_recorded = 0;
 
   int32_t *d_block_table = nullptr, *d_ctx_lens = nullptr, *d_chunk_prefix = nullptr;
   int4 *d_item_desc = nullptr;
@@ -252,6 +277,87 @@ okv::AttnLaunch base_launch(okv_ctx *ctx) {
   return a;
 }
 
+void reset_schedule(okv_ctx *ctx);
+
+// The host's lead over the compute stream, in steps (OKV_STEPS_AHEAD): the step about to be enqueued may
+// not begin before the one that many steps back has finished.
+int wait_for_earlier_steps(okv_ctx *ctx) {
+  constexpr int64_t kAhead = OKV_STEPS_AHEAD;
+  if (kAhead <= 0 || !ctx->step_done_ev[0] || ctx->steps_recorded < kAhead) return OKV_OK;
+  OKV_HIP(ctx, hipEventSynchronize(ctx->step_done_ev[ctx->steps_recorded % kAhead]));   // the oldest of the ring
+  return OKV_OK;
+}
+
+int mark_step_done(okv_ctx *ctx) {
+  constexpr int64_t kAhead = OKV_STEPS_AHEAD;
+  if (kAhead <= 0 || !ctx->step_done_ev[0]) return OKV_OK;
+  OKV_HIP(ctx, hipEventRecord(ctx->step_done_ev[ctx->steps_recorded % kAhead], ctx->compute));
+  ctx->steps_recorded += 1;
+  return OKV_OK;
+}
+
+okv::TailLaunch tail_launch(okv_ctx *ctx, int32_t mode) {
+  okv::TailLaunch t;
+  t.staged = nullptr;
+  t.host_pools = ctx->d_host_ptrs;
+  t.tail = ctx->cfg.tail_blocks;
+  t.block_table = ctx->d_block_table;
+  t.ctx_lens = ctx->d_ctx_lens;
+  t.tail_from = ctx->d_tail_from;
+  t.block_elems = ctx->block_bytes / 2;
+  t.layer_stride = ctx->tail_layer_stride;
+  t.B = ctx->B;
+  t.n_layers = ctx->cfg.n_layers;
+  t.max_blocks = ctx->shape.max_blocks;
+  t.log2_T = ctx->shape.log2_T;
+  t.D = ctx->shape.D;
+  t.id_lo = (int32_t)ctx->resident_blocks;
+  t.id_hi = (int32_t)ctx->cfg.blocks_per_layer;
+  t.mode = mode;
+  return t;
+}
+
+// Positions from the current lengths on are the ones whose rows the slots will hold.
+int tail_restart(okv_ctx *ctx) {
+  if (!ctx->tail_on) return OKV_OK;
+  ctx->h_tail_from.assign(ctx->h_ctx_lens.begin(), ctx->h_ctx_lens.begin() + ctx->B);
+  OKV_HIP(ctx, hipMemcpy(ctx->d_tail_from, ctx->h_tail_from.data(), (size_t)ctx->B * sizeof(int32_t), hipMemcpyHostToDevice));
+  ctx->tail_dirty = false;
+  return OKV_OK;
+}
+
+// Every row still only in a slot goes to the host pool; afterwards the pools are complete, the copies
+// already made of them are not, so the pipeline starts afresh.  Synchronous.
+int tail_flush_all(okv_ctx *ctx) {
+  if (!ctx->tail_on || !ctx->tail_dirty || !ctx->batch_set) return OKV_OK;
+  int rc = okv_synchronize(ctx);
+  if (rc) return rc;
+  OKV_HIP(ctx, okv::launch_tail_rows(tail_launch(ctx, 2), ctx->compute));
+  rc = okv_synchronize(ctx);
+  if (rc) return rc;
+  rc = tail_restart(ctx);
+  reset_schedule(ctx);
+  return rc;
+}
+
+// Chunks in which some sequence's newest or second-newest block lies at the lengths the host holds.
+void tail_mark_chunks(okv_ctx *ctx) {
+  ctx->patch_chunk.assign(ctx->active_chunks.size(), 0);
+  const okv::PoolShape &s = ctx->shape;
+  for (int32_t b = 0; b < ctx->B; ++b) {
+    const int32_t n = ctx->h_ctx_lens[b];
+    const int32_t jn = (n - 1) >> s.log2_T;
+    for (int32_t j = std::max(0, jn - 1); j <= jn; ++j) {
+      if (((j + 1) << s.log2_T) <= ctx->h_tail_from[b]) continue;          // all of it was in the pool from the start
+      const int64_t id = ctx->h_block_table[(size_t)b * s.max_blocks + j];
+      if (id < ctx->resident_blocks) continue;
+      const int32_t chunk = (int32_t)((id - ctx->resident_blocks) / ctx->chunk_blocks);
+      for (size_t u = 0; u < ctx->active_chunks.size(); ++u)
+        if (ctx->active_chunks[u] == chunk) ctx->patch_chunk[u] = 1;
+    }
+  }
+}
+
 int exec_op(okv_ctx *ctx, const Op &op, const void *a0, const void *a1, void *out) {
   switch (op.kind) {
     case okv::OP_COPY: {
@@ -260,6 +366,8 @@ int exec_op(okv_ctx *ctx, const Op &op, const void *a0, const void *a1, void *ou
       // about 2 % of the copy time) then overlaps with the next copy instead of delaying it.
       hipStream_t cs = copy_stream(ctx, op.buf);
       if (op.wait_idx >= 0) OKV_HIP(ctx, hipStreamWaitEvent(cs, ctx->consumed_ev[op.wait_idx % kEventRing], 0));
+      // a block written out to the host pool at the end of a step is in every copy enqueued after that
+      if (ctx->flush_recorded) OKV_HIP(ctx, hipStreamWaitEvent(cs, ctx->flush_ev, 0));
       const char *src = static_cast<const char *>(ctx->host_pool[op.layer]) + ctx->unit_offset[op.chunk];
       OKV_HIP(ctx, hipMemcpyAsync(ctx->cfg.staging[op.buf], src, (size_t)ctx->unit_bytes[op.chunk],
                                   hipMemcpyHostToDevice, cs));
@@ -292,6 +400,21 @@ int exec_op(okv_ctx *ctx, const Op &op, const void *a0, const void *a1, void *ou
       a.k_new = ctx->pending_k;
       a.v_new = ctx->pending_v;
       a.pool_mirror = op.buf >= 0 ? ctx->host_pool[op.layer] : nullptr;
+      if (ctx->tail_on && op.buf >= 0 && op.chunk >= 0) {
+        // rows appended to blocks of this chunk live in the layer's slots: the new ones go there, and
+        // those of earlier steps are put into the staged chunk before it is attended
+        uint16_t *slots = static_cast<uint16_t *>(ctx->cfg.tail_blocks) + (int64_t)op.layer * ctx->tail_layer_stride;
+        a.pool_mirror = slots;
+        a.mirror_is_tail = 1;
+        if (ctx->patch_chunk[op.chunk]) {
+          okv::TailLaunch t = tail_launch(ctx, 0);
+          t.staged = ctx->cfg.staging[op.buf];
+          t.tail = slots;
+          t.id_lo = a.id_base;
+          t.id_hi = (int32_t)std::min<int64_t>((int64_t)a.id_base + ctx->chunk_blocks, ctx->cfg.blocks_per_layer);
+          OKV_HIP(ctx, okv::launch_tail_rows(t, ctx->compute));
+        }
+      }
       a.out = out;
       hipEvent_t e0 = nullptr, e1 = nullptr;
       if (ctx->profile == 1 || (ctx->profile == 2 && !ctx->prof_open)) {
@@ -459,6 +582,12 @@ int64_t okv_workspace_bytes(const okv_config *cfg) {
   return items * bytes_per_item(cfg);
 }
 
+int64_t okv_tail_bytes(const okv_config *cfg) {
+  if (const char *why = shape_problem(cfg)) return fail(nullptr, OKV_EINVAL, "%s", why);
+  if (cfg->chunk_blocks <= 0) return 0;
+  return (int64_t)cfg->n_layers * 2 * cfg->max_batch * block_bytes_of(cfg);
+}
+
 int kv_offload_plan(int32_t n_layers, int64_t coff_num, int64_t coff_den, uint8_t *on_host, int32_t *n_off) {
   if (n_layers < 1 || !on_host) return fail(nullptr, OKV_EINVAL, "kv_offload_plan: n_layers < 1 or on_host NULL");
   if (coff_den <= 0 || coff_num < 0 || coff_num > coff_den)
@@ -609,6 +738,14 @@ int okv_create(const okv_config *cfg, okv_ctx **out) {
     if (cfg->h2d_stream == cfg->compute_stream) return fail(nullptr, OKV_EINVAL, "okv_create: h2d_stream must differ from compute_stream");
     while (n_staging < OKV_MAX_STAGING && cfg->staging[n_staging]) ++n_staging;
   }
+  if (cfg->tail_blocks) {
+    if (!by_class || host_blocks == 0)
+      return fail(nullptr, OKV_EINVAL, "okv_create: tail_blocks is for block-granular offload (chunk_blocks > 0, blocks on the host)");
+    if (!aligned16(cfg->tail_blocks)) return fail(nullptr, OKV_EINVAL, "okv_create: tail_blocks not 16-byte aligned");
+    const int64_t need_tail = okv_tail_bytes(cfg);
+    if (cfg->tail_bytes < need_tail)
+      return fail(nullptr, OKV_ENOSPC, "okv_create: tail_bytes %lld < %lld", (long long)cfg->tail_bytes, (long long)need_tail);
+  }
   const int64_t need_ws = okv_workspace_bytes(cfg);
   if (!cfg->workspace || !aligned16(cfg->workspace)) return fail(nullptr, OKV_EINVAL, "okv_create: workspace NULL or misaligned");
   if (cfg->workspace_bytes < need_ws)
@@ -675,6 +812,14 @@ int okv_create(const okv_config *cfg, okv_ctx **out) {
     OKV_TRY_CREATE(hipMalloc(&ctx->d_seq_total, (size_t)cfg->max_batch * sizeof(int32_t)));
   }
   OKV_TRY_CREATE(hipMalloc(&ctx->d_item_desc, (size_t)std::max<int64_t>(1, max_items) * sizeof(int4)));
+  if (cfg->tail_blocks) {
+    ctx->tail_on = true;
+    ctx->tail_layer_stride = (int64_t)2 * cfg->max_batch * (ctx->block_bytes / 2);
+    OKV_TRY_CREATE(hipMalloc(&ctx->d_tail_from, (size_t)cfg->max_batch * sizeof(int32_t)));
+    OKV_TRY_CREATE(hipMalloc(&ctx->d_host_ptrs, (size_t)L * sizeof(void *)));
+    OKV_TRY_CREATE(hipMemcpy(ctx->d_host_ptrs, ctx->host_pool.data(), (size_t)L * sizeof(void *), hipMemcpyHostToDevice));
+    OKV_TRY_CREATE(hipEventCreateWithFlags(&ctx->flush_ev, hipEventDisableTiming));
+  }
   {
     int dev = 0, cus = 0;
     OKV_TRY_CREATE(hipGetDevice(&dev));
@@ -687,6 +832,8 @@ int okv_create(const okv_config *cfg, okv_ctx **out) {
   OKV_TRY_CREATE(hipMemset(ctx->d_group_first, 0, ((size_t)ctx->max_groups + 1) * sizeof(int32_t)));
   OKV_TRY_CREATE(hipMalloc(&ctx->d_plan, 4 * sizeof(int32_t)));
   if (n_staging >= 2) OKV_TRY_CREATE(hipStreamCreateWithFlags(&ctx->h2d_odd, hipStreamNonBlocking));
+  if (by_class && any_host && OKV_STEPS_AHEAD > 0)
+    for (hipEvent_t &e : ctx->step_done_ev) OKV_TRY_CREATE(hipEventCreateWithFlags(&e, hipEventDisableTiming));
   for (int i = 0; i < kEventRing; ++i) {
     OKV_TRY_CREATE(hipEventCreateWithFlags(&ctx->ready_ev[i], hipEventDisableTiming));
     OKV_TRY_CREATE(hipEventCreateWithFlags(&ctx->consumed_ev[i], hipEventDisableTiming));
@@ -704,6 +851,11 @@ int okv_destroy(okv_ctx *ctx) {
     (void)hipStreamDestroy(ctx->h2d_odd);
   }
   (void)hipStreamSynchronize(ctx->compute);
+  (void)hipFree(ctx->d_tail_from);
+  (void)hipFree(ctx->d_host_ptrs);
+  if (ctx->flush_ev) (void)hipEventDestroy(ctx->flush_ev);
+  for (hipEvent_t e : ctx->step_done_ev)
+    if (e) (void)hipEventDestroy(e);
   (void)hipFree(ctx->d_block_table);
   (void)hipFree(ctx->d_ctx_lens);
   (void)hipFree(ctx->d_chunk_prefix);
@@ -782,7 +934,9 @@ int okv_set_batch(okv_ctx *ctx, int32_t B, const int32_t *block_table, const int
           return fail(ctx, OKV_EINVAL, "sequence %d holds %d tokens but block %d is not allocated", b, ctx_lens[b], i);
     }
   }
-  int rc = okv_synchronize(ctx);
+  int rc = tail_flush_all(ctx);                          // rows of the batch that is being replaced
+  if (rc) return rc;
+  rc = okv_synchronize(ctx);
   if (rc) return rc;
   ctx->batch_set = false;
   ctx->B = B;
@@ -836,6 +990,8 @@ int okv_set_batch(okv_ctx *ctx, int32_t B, const int32_t *block_table, const int
   reset_schedule(ctx);
   ctx->next_layer = 0;
   ctx->appended = false;
+  rc = tail_restart(ctx);
+  if (rc) return rc;
   ctx->batch_set = true;
   rc = rebuild_worklist(ctx, 0);
   if (rc) { ctx->batch_set = false; return rc; }
@@ -853,6 +1009,7 @@ int okv_step_begin(okv_ctx *ctx) {
     if (s.paged && ctx->h_block_table[(size_t)b * s.max_blocks + (n >> s.log2_T)] < 0)
       return fail(ctx, OKV_ENOSPC, "sequence %d has no block allocated for token %d", b, n);
   }
+  if (int rc = wait_for_earlier_steps(ctx)) return rc;
   // The first copies go out before anything is advanced: a failure here leaves the lengths as they were.
   // What it does leave is a copy pipeline in an unknown state, so the batch has to be described again.
   if (ctx->sched.n_units() > 0 && !ctx->sched.primed()) {
@@ -872,6 +1029,10 @@ int okv_step_begin(okv_ctx *ctx) {
     // device lengths advanced, and only okv_set_batch uploads them again
     if (rc != OKV_ENOSPC) ctx->batch_set = false;
     return rc;
+  }
+  if (ctx->tail_on) {
+    tail_mark_chunks(ctx);
+    ctx->tail_dirty = true;
   }
   ctx->in_step = true;
   ctx->next_layer = 0;
@@ -902,9 +1063,35 @@ int okv_step_end(okv_ctx *ctx) {
     ++ctx->prof_used;
     ctx->prof_open = false;
   }
+  if (ctx->tail_on) {
+    const okv::PoolShape &s = ctx->shape;
+    bool filled = false;
+    for (int32_t b = 0; b < ctx->B && !filled; ++b) {
+      const int32_t n = ctx->h_ctx_lens[b];
+      if ((n & (ctx->cfg.block_tokens - 1)) || ctx->h_tail_from[b] >= n) continue;
+      filled = ctx->h_block_table[(size_t)b * s.max_blocks + (n >> s.log2_T) - 1] >= ctx->resident_blocks;
+    }
+    if (filled) {
+      // after every layer's attention of this step (same stream); copies of the host pools enqueued
+      // from now on wait for it, those already enqueued are made good from the slots
+      OKV_HIP(ctx, okv::launch_tail_rows(tail_launch(ctx, 1), ctx->compute));
+      OKV_HIP(ctx, hipEventRecord(ctx->flush_ev, ctx->compute));
+      ctx->flush_recorded = true;
+    }
+  }
+  if (int rc = mark_step_done(ctx)) return rc;
   ctx->in_step = false;
   ctx->step += 1;
   return OKV_OK;
+}
+
+int okv_flush_tails(okv_ctx *ctx) {
+  if (!ctx) return fail(nullptr, OKV_EINVAL, "ctx is NULL");
+  if (ctx->in_step || ctx->in_prefill) return fail(ctx, OKV_ESTATE, "okv_flush_tails inside a step or a prefill");
+  if (!ctx->batch_set) return fail(ctx, OKV_ESTATE, "okv_flush_tails: no batch set");
+  if (!ctx->tail_on) return okv_synchronize(ctx);
+  if (!ctx->tail_dirty) return okv_synchronize(ctx);
+  return tail_flush_all(ctx);
 }
 
 int kv_append(okv_ctx *ctx, int32_t layer, const void *k_new, const void *v_new) {
@@ -970,7 +1157,9 @@ int okv_prefill_begin(okv_ctx *ctx, const int32_t *n_new) {
         if (ctx->h_block_table[(size_t)b * s.max_blocks + i] < 0)
           return fail(ctx, OKV_ENOSPC, "sequence %d has no block allocated for token %d", b, i << s.log2_T);
   }
-  int rc = okv_synchronize(ctx);                        // a change of phase: nothing of a decode step is left in flight
+  int rc = tail_flush_all(ctx);                         // the prompt's rows go to the pools, past what decode steps left in the slots
+  if (rc) return rc;
+  rc = okv_synchronize(ctx);                            // a change of phase: nothing of a decode step is left in flight
   if (rc) return rc;
   // 16-position tiles that receive rows.  A tile is (sequence, tile, first and last position
   // inside it, destination block relative to the pool the launch writes into).
@@ -1180,6 +1369,7 @@ int okv_prefill_end(okv_ctx *ctx) {
   for (int32_t b = 0; b < ctx->B; ++b) ctx->h_ctx_lens[b] += ctx->h_n_new[b];
   ctx->in_prefill = false;
   reset_schedule(ctx);
+  if (int rc = tail_restart(ctx)) return rc;
   return rebuild_worklist(ctx, 0, /*upload_lens=*/true);
 }
 
@@ -1430,17 +1620,21 @@ int okv_time_copies(okv_ctx *ctx, int32_t as_pipelined, int32_t n_steps, double 
     if (e == hipSuccess && okv_synchronize(ctx) != OKV_OK) e = hipErrorUnknown;
     ops.clear();
     const auto t0 = std::chrono::steady_clock::now();
-    for (int32_t step = 0; step < n_steps; ++step)
+    for (int32_t step = 0; step < n_steps && e == hipSuccess; ++step) {
+      if (wait_for_earlier_steps(ctx) != OKV_OK) e = hipErrorUnknown;   // the host leads by as much as in real steps
+      ops.clear();
       for (int32_t l = 0; l < ctx->cfg.n_layers; ++l) ctx->sched.on_attn(step, l, ops);
-    for (const Op &op : ops) {
-      if (e != hipSuccess) break;
-      if (op.kind == okv::OP_COPY) {
-        if (exec_op(ctx, op, nullptr, nullptr, nullptr) != OKV_OK) e = hipErrorUnknown;
-      } else if (op.kind == okv::OP_ATTN && op.wait_idx >= 0) {
-        e = hipStreamWaitEvent(ctx->compute, ctx->ready_ev[op.wait_idx % kEventRing], 0);
-      } else if (op.kind == okv::OP_RELEASE) {
-        e = hipEventRecord(ctx->consumed_ev[op.copy_idx % kEventRing], ctx->compute);
+      for (const Op &op : ops) {
+        if (e != hipSuccess) break;
+        if (op.kind == okv::OP_COPY) {
+          if (exec_op(ctx, op, nullptr, nullptr, nullptr) != OKV_OK) e = hipErrorUnknown;
+        } else if (op.kind == okv::OP_ATTN && op.wait_idx >= 0) {
+          e = hipStreamWaitEvent(ctx->compute, ctx->ready_ev[op.wait_idx % kEventRing], 0);
+        } else if (op.kind == okv::OP_RELEASE) {
+          e = hipEventRecord(ctx->consumed_ev[op.copy_idx % kEventRing], ctx->compute);
+        }
       }
+      if (e == hipSuccess && mark_step_done(ctx) != OKV_OK) e = hipErrorUnknown;
     }
     if (e == hipSuccess && okv_synchronize(ctx) != OKV_OK) e = hipErrorUnknown;
     t = (float)std::chrono::duration<double, std::milli>(std::chrono::steady_clock::now() - t0).count();

@@ -53,6 +53,9 @@ struct AttnLaunch {
   // `pool_mirror` those from mirror_base on.
   int32_t item_first, item_count;
   int32_t id_base, mirror_base;
+  // pool_mirror holds the layer's tail slots instead (two blocks per sequence: block j of sequence b
+  // in slot 2 b + (j & 1)); the appended rows go there and not across the link.
+  int32_t mirror_is_tail = 0;
 };
 
 // Store of the step's K/V rows and split-K partial attention over the launch's items.
@@ -102,6 +105,26 @@ struct BulkLaunch {
   int32_t throttle;
 };
 hipError_t launch_bulk_append(const BulkLaunch &a, hipStream_t stream);
+
+// Rows of the sequences' newest blocks between their slots in HBM and where they are read or kept.
+// mode 0: for every sequence, the rows [tail_from[b], ctx_lens[b] - 1) that lie in the block of position
+//         ctx_lens[b] - 1 or in the block before it go from the slots to `staged` (which holds the blocks
+//         with ids id_lo .. id_hi - 1), if the block's id is in that range.
+// mode 1: for every sequence whose length is a multiple of the block size, the rows from tail_from[b]
+//         on of the block just filled go to the host pool of every layer (ids id_lo .. id_hi - 1 = the
+//         host pool's blocks).
+// mode 2: the same for the newest block of every sequence, as far as it is filled.
+struct TailLaunch {
+  void *staged;
+  void *const *host_pools;       // device array [n_layers]
+  const void *tail;              // mode 0: the layer's slots; else layer 0's
+  const int32_t *block_table, *ctx_lens, *tail_from;
+  int64_t block_elems, layer_stride;
+  int32_t B, n_layers, max_blocks, log2_T, D;
+  int32_t id_lo, id_hi;
+  int32_t mode;
+};
+hipError_t launch_tail_rows(const TailLaunch &t, hipStream_t stream);
 
 // items[it] = (b, lo, hi) decoded on the device.
 hipError_t launch_worklist_dump(const BatchState &batch, int32_t *items, hipStream_t stream);

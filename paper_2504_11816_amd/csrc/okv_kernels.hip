@@ -94,6 +94,7 @@ struct AttnArgs {
   int32_t item_first;              // the launch's first item in item_desc (and in the partial slots)
   int32_t id_base;                 // `pool` holds the blocks with ids id_base, id_base + 1, ...
   int32_t mirror_shift;            // id_base minus the id of the first block of pool_mirror
+  int32_t mirror_is_tail;          // pool_mirror is the layer's tail slots: block (2 b + (block index & 1)) of it
   int32_t B, n_cls;                // merge: chunk_prefix is [n_cls][B] (+ 1)
   float scale_log2e;
 };
@@ -378,8 +379,10 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(co
         const int64_t in_slab = (row == 0 ? ta.head_k : ta.head_v) + (int64_t)(pos & 15) * D + col * 8;
         const uint4 val = row == 0 ? k_row : v_row;
         *reinterpret_cast<uint4 *>(a.pool_store + slab_base<PAGED>(ta, blk, pos >> 4) + in_slab) = val;
-        if (a.pool_mirror)
-          *reinterpret_cast<uint4 *>(a.pool_mirror + slab_base<PAGED>(ta, blk + (PAGED ? a.mirror_shift : 0), pos >> 4) + in_slab) = val;
+        if (a.pool_mirror) {
+          const int mblk = PAGED && a.mirror_is_tail ? 2 * C.b + ((pos >> a.log2_T) & 1) : blk + (PAGED ? a.mirror_shift : 0);
+          *reinterpret_cast<uint4 *>(a.pool_mirror + slab_base<PAGED>(ta, mblk, pos >> 4) + in_slab) = val;
+        }
       }
     }
     if (!has_next) break;
@@ -590,6 +593,7 @@ AttnArgs make_args(const AttnLaunch &a) {
   args.item_first = a.item_first;
   args.id_base = a.id_base;
   args.mirror_shift = a.id_base - a.mirror_base;
+  args.mirror_is_tail = a.mirror_is_tail;
   args.B = a.batch.B;
   args.n_cls = a.batch.n_cls;
   // exp(x) = 2^(x log2 e): the 1/sqrt(d) scale and log2 e are folded into one factor
@@ -871,6 +875,64 @@ __global__ __launch_bounds__(256) void bulk_append_kernel(const BulkArgs a) {
   }
 }
 
+// ---- the newest blocks of the sequences, kept in HBM (block-granular offload) ------------------
+//
+// Rows that a decode step appends to a block of the host pool are not stored across the link one by
+// one: they go into a slot in HBM (two per sequence and layer, block j of a sequence uses slot j & 1)
+// and the block is written to the host pool once, when it is full.  Until a copy of the host pool that
+// was started after that write arrives, the staged chunk lacks those rows; this kernel puts them there
+// (mode 0, before the chunk is attended) or writes them out (modes 1 and 2).  A block is
+// tiles x [G / Gg][K|V][Gg][16 slots][D]; thread p moves the 16-byte piece p of the block if the
+// piece's position lies in the range of rows wanted.
+struct TailArgs {
+  uint16_t *staged;                  // mode 0: the staged chunk (blocks id_lo .. id_hi - 1)
+  uint16_t *const *host_pools;       // modes 1, 2: [layers] device-visible pointers to the host pools (block id_lo first)
+  const uint16_t *tail;              // slots of the layer (mode 0) or of layer 0 (modes 1, 2)
+  const int32_t *block_table, *ctx_lens, *tail_from;
+  int64_t block_elems, layer_stride; // numbers per block; numbers between two layers' slots
+  int32_t max_blocks, log2_T, d8;    // d8 = 16-byte pieces per row
+  int32_t id_lo, id_hi;
+  int32_t mode;                      // 0: blocks j and j - 1 of the newest position, rows before it, into the staged chunk
+                                     // 1: the block that this step filled, to the host pool
+                                     // 2: the newest block as far as it is filled, to the host pool
+};
+
+__global__ __launch_bounds__(256) void tail_rows_kernel(TailArgs a) {
+  const int b = blockIdx.y;
+  const int n = a.ctx_lens[b];
+  const int T = 1 << a.log2_T;
+  int j, hi;
+  if (a.mode == 0) {
+    j = ((n - 1) >> a.log2_T) - (int)blockIdx.z;
+    hi = min((j + 1) << a.log2_T, n - 1);
+  } else if (a.mode == 1) {
+    if (n & (T - 1)) return;
+    j = (n >> a.log2_T) - 1;
+    hi = n;
+  } else {
+    j = (n - 1) >> a.log2_T;
+    hi = n;
+  }
+  if (j < 0) return;
+  const int lo = max(j << a.log2_T, a.tail_from[b]);
+  if (lo >= hi) return;
+  const int id = a.block_table[(size_t)b * a.max_blocks + j];
+  if (id < a.id_lo || id >= a.id_hi) return;
+  const int layer = a.mode == 0 ? 0 : (int)blockIdx.z;
+  const uint4 *src = reinterpret_cast<const uint4 *>(a.tail + layer * a.layer_stride + (int64_t)(2 * b + (j & 1)) * a.block_elems);
+  uint16_t *dst_pool = a.mode == 0 ? a.staged : a.host_pools[layer];
+  uint4 *dst = reinterpret_cast<uint4 *>(dst_pool + (int64_t)(id - a.id_lo) * a.block_elems);
+  const int lo_in = lo - (j << a.log2_T), hi_in = hi - (j << a.log2_T);
+  const int pieces = (int)(a.block_elems >> 3);
+  const int slab_pieces = pieces >> (a.log2_T - 4);
+  for (int p = blockIdx.x * blockDim.x + threadIdx.x; p < pieces; p += gridDim.x * blockDim.x) {
+    const int slab = p / slab_pieces;
+    const int slot = ((p - slab * slab_pieces) / a.d8) & 15;
+    const int pos = slab * 16 + slot;
+    if (pos >= lo_in && pos < hi_in) dst[p] = src[p];
+  }
+}
+
 __global__ void worklist_dump_kernel(BatchState bs, int32_t *items) {
   const int it = blockIdx.x * blockDim.x + threadIdx.x;
   if (it >= bs.n_items) return;
@@ -949,6 +1011,29 @@ hipError_t launch_bulk_append(const BulkLaunch &a, hipStream_t stream) {
   } else {
     return hipErrorInvalidValue;
   }
+  return hipGetLastError();
+}
+
+hipError_t launch_tail_rows(const TailLaunch &t, hipStream_t stream) {
+  if (t.B <= 0) return hipSuccess;
+  TailArgs a;
+  a.staged = static_cast<uint16_t *>(t.staged);
+  a.host_pools = reinterpret_cast<uint16_t *const *>(t.host_pools);
+  a.tail = static_cast<const uint16_t *>(t.tail);
+  a.block_table = t.block_table;
+  a.ctx_lens = t.ctx_lens;
+  a.tail_from = t.tail_from;
+  a.block_elems = t.block_elems;
+  a.layer_stride = t.layer_stride;
+  a.max_blocks = t.max_blocks;
+  a.log2_T = t.log2_T;
+  a.d8 = t.D / 8;
+  a.id_lo = t.id_lo;
+  a.id_hi = t.id_hi;
+  a.mode = t.mode;
+  const int64_t pieces = t.block_elems / 8;
+  const unsigned gx = (unsigned)std::max<int64_t>(1, std::min<int64_t>((pieces + 255) / 256, 64));
+  hipLaunchKernelGGL(tail_rows_kernel, dim3(gx, t.B, t.mode == 0 ? 2 : t.n_layers), dim3(256), 0, stream, a);
   return hipGetLastError();
 }
 

@@ -63,7 +63,7 @@ class Stack:
 
     def __init__(self, *, L, H, G, d, B, T, cap_tokens, on_host=None, out_dtype=0, split_tokens=0,
                  blocks_per_layer=None, n_staging=2, device="cuda:0", resident_blocks=0, chunk_blocks=0,
-                 workspace_items=None):
+                 workspace_items=None, hot_tails=None):
         if not torch.cuda.is_available():
             raise RuntimeError("the okv library needs a GPU; there is no CPU path")
         self.L, self.H, self.G, self.d, self.B, self.T = L, H, G, d, B, T
@@ -107,6 +107,11 @@ class Stack:
         self.staging = [torch.empty(staging_el, dtype=torch.float16, device=self.device) if any_host and i < n_staging
                         else None for i in range(4)]
         self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=self.device)
+        # block-granular offload: rows appended to host blocks stay in HBM slots until their block is full
+        # (hot_tails=False: every row is stored through the mapped pointer in its own step)
+        self.hot_tails = bool(self.by_class and any_host and (hot_tails is None or hot_tails))
+        self.tail_bytes = binding.okv_tail_bytes(shape) if self.hot_tails else 0
+        self.tail_blocks = torch.empty(self.tail_bytes, dtype=torch.uint8, device=self.device) if self.hot_tails else None
         self.compute_stream = torch.cuda.Stream(device=self.device)
         self.h2d_stream = torch.cuda.Stream(device=self.device)
         self.out_torch_dtype = torch.float32 if out_dtype else torch.float16
@@ -118,6 +123,7 @@ class Stack:
             staging=tuple(self.staging), staging_bytes=self.staging_bytes,
             resident_blocks=resident_blocks, chunk_blocks=chunk_blocks,
             workspace=self.workspace, workspace_bytes=self.workspace_bytes,
+            tail_blocks=self.tail_blocks, tail_bytes=self.tail_bytes,
             compute_stream=self.compute_stream.cuda_stream, h2d_stream=self.h2d_stream.cuda_stream)
         self.block_table = None
         self.ctx_lens = None
@@ -186,14 +192,19 @@ class Stack:
                 at += part.numel()
         return out
 
-    def read_pool(self, layer):
+    def read_pool(self, layer, flush=True):
         """A host numpy copy (fp16, flat) of the layer's pool as it is stored
-        (HBM part first, then the host part)."""
+        (HBM part first, then the host part).  Rows still held in HBM slots are written out first
+        unless flush is False."""
+        if flush and self.hot_tails and self.ctx_lens is not None:
+            self.ctx.okv_flush_tails()
         torch.cuda.synchronize(self.device)
         return np.concatenate([p.cpu().numpy() for _, p in self._parts(layer)])
 
     def read_rows(self, layer, row_offsets):
         """Rows of d fp16 numbers at the given element offsets -> [n][d] numpy."""
+        if self.hot_tails and self.ctx_lens is not None:
+            self.ctx.okv_flush_tails()
         torch.cuda.synchronize(self.device)
         idx = torch.as_tensor(np.asarray(row_offsets, dtype=np.int64))
         cols = torch.arange(self.d, dtype=torch.int64)

@@ -23,7 +23,7 @@ def say(msg):
 
 
 def classed_stack(*, L, H, G, d, T, ctx_before, cap_tokens, c_off, chunk_blocks, policy, seed, n_staging=2,
-                  split_tokens=0, workspace_items=None, spare_resident=2, spare_host=3, out_dtype=0):
+                  split_tokens=0, workspace_items=None, spare_resident=2, spare_host=3, out_dtype=0, hot_tails=None):
     """A Stack in block-class mode: of the blocks the batch can grow into, the share c_off
     (a Fraction) is taken from the host part of the pool by `policy`."""
     ctx_before = np.asarray(ctx_before, dtype=np.int32)
@@ -35,7 +35,7 @@ def classed_stack(*, L, H, G, d, T, ctx_before, cap_tokens, c_off, chunk_blocks,
     host_blocks = n_host + (spare_host if n_host else 0)
     st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=cap_tokens, blocks_per_layer=R + host_blocks,
                n_staging=n_staging, resident_blocks=R, chunk_blocks=chunk_blocks, split_tokens=split_tokens,
-               workspace_items=workspace_items, out_dtype=out_dtype)
+               workspace_items=workspace_items, out_dtype=out_dtype, hot_tails=hot_tails)
     for l in range(L):
         st.fill_pool(l, synth.stream_seed(seed, synth.TENSOR_POOL, l))
     table = synth.classed_block_table([st.cap_tokens] * B, T, R, host_blocks, n_host, policy, seed + 1,
@@ -169,6 +169,106 @@ def test_appended_rows_land_in_the_right_part_bit_exact(policy):
     for l in range(2):
         np.testing.assert_array_equal(st.read_pool(l).view(np.uint16), want[l].view(np.uint16))
     st.close()
+
+
+def oracle_outputs(pool, layout, q_np, n_now, H, G):
+    """decode attention of every (sequence, head) on a flat pool that the oracle keeps itself."""
+    from oracle import attention as oa
+    d = q_np.shape[-1]
+    out = np.zeros(q_np.shape, dtype=np.float64)
+    for b in range(q_np.shape[0]):
+        n = int(n_now[b])
+        for g in range(G):
+            K = np.stack([pool[o:o + d] for o in (kv_layout.token_row_offset(layout, b, 0, g, i) for i in range(n))])
+            V = np.stack([pool[o:o + d] for o in (kv_layout.token_row_offset(layout, b, 1, g, i) for i in range(n))])
+            for h in range(g * (H // G), (g + 1) * (H // G)):
+                out[b, h] = oa.attend_one(oa.as_f64(q_np[b, h]), oa.as_f64(K), oa.as_f64(V))
+    return out
+
+
+def full_block_rows(layout, ctx, T, G, d):
+    """Element offsets of every row that lies in a block its sequence has filled."""
+    rows = []
+    for b, n in enumerate(ctx):
+        for i in range((int(n) // T) * T):
+            for kv in (0, 1):
+                for g in range(G):
+                    rows.append(kv_layout.token_row_offset(layout, b, kv, g, i))
+    at = np.asarray(rows, dtype=np.int64)
+    return (at[:, None] + np.arange(d)[None, :]).reshape(-1)
+
+
+@pytest.mark.parametrize("n_staging", [2, 4])
+@pytest.mark.parametrize("policy", ["prefix", "sequence", "scatter"])
+def test_newest_blocks_kept_in_hbm_across_block_boundaries(policy, n_staging):
+    # rows appended to host blocks live in HBM slots until their block is full: 36 steps take every sequence
+    # across two block boundaries, at different steps; the oracle keeps its own pool (append_scatter) and
+    # every output of every step is checked against it; without an explicit flush the host pool must hold
+    # every filled block bit for bit, after the flush everything
+    say(f"classes: tails policy={policy} staging={n_staging}")
+    from gpu_util import assert_close
+    ctx = np.array([0, 15, 16, 31, 47, 60, 5], dtype=np.int32)
+    L, H, G, d, T = 2, 4, 2, 64, 16
+    st = classed_stack(L=L, H=H, G=G, d=d, T=T, ctx_before=ctx, cap_tokens=112, c_off=Fraction(3, 5), chunk_blocks=4,
+                       policy=policy, seed=171, n_staging=n_staging, workspace_items=7 * 16)
+    assert st.hot_tails
+    st.tail_blocks.fill_(0xFF)                            # fp16 NaNs: a row read from a slot it was never put in shows
+    poison_staging(st)
+    want = [st.read_pool(l) for l in range(L)]
+    layout = st.layout()
+    n = ctx.copy()
+    for step in range(36):
+        q, k, v, out = make_inputs(st, 173, step, st.device)
+        st.step(q, k, v, out)
+        st.synchronize()
+        n += 1
+        for l in range(L):
+            kv_layout.append_scatter(want[l], layout, n, k[l].cpu().numpy(), v[l].cpu().numpy())
+            ref = oracle_outputs(want[l], layout, q[l].cpu().numpy(), n, H, G)
+            assert_close(out[l].float().cpu().numpy().reshape(-1, d), ref.reshape(-1, d), f"step {step} layer {l}")
+    done = full_block_rows(layout, n, T, G, d)
+    for l in range(L):
+        got = st.read_pool(l, flush=False)
+        np.testing.assert_array_equal(got.view(np.uint16)[done], want[l].view(np.uint16)[done])
+    for l in range(L):
+        np.testing.assert_array_equal(st.read_pool(l).view(np.uint16), want[l].view(np.uint16))
+    # and on from there: the flush restarted the slots
+    for step in range(36, 40):
+        q, k, v, out = make_inputs(st, 173, step, st.device)
+        st.step(q, k, v, out)
+        st.synchronize()
+        n += 1
+        for l in range(L):
+            kv_layout.append_scatter(want[l], layout, n, k[l].cpu().numpy(), v[l].cpu().numpy())
+            ref = oracle_outputs(want[l], layout, q[l].cpu().numpy(), n, H, G)
+            assert_close(out[l].float().cpu().numpy().reshape(-1, d), ref.reshape(-1, d), f"step {step} layer {l}")
+    # a new description of the batch writes out what the old one left in the slots
+    st.set_batch(n, st.block_table)
+    for l in range(L):
+        np.testing.assert_array_equal(st.read_pool(l, flush=False).view(np.uint16), want[l].view(np.uint16))
+    st.close()
+
+
+def test_tail_slots_and_the_mapped_pointer_give_the_same_pools_and_outputs():
+    say("classes: tails on / off")
+    ctx = np.array([3, 40, 64, 77], dtype=np.int32)
+    res = {}
+    for hot in (True, False):
+        st = classed_stack(L=2, H=8, G=2, d=128, T=32, ctx_before=ctx, cap_tokens=160, c_off=Fraction(1, 2), chunk_blocks=3,
+                           policy="scatter", seed=181, workspace_items=4 * 12, hot_tails=hot)
+        assert st.hot_tails == hot
+        outs = []
+        for step in range(40):
+            q, k, v, out = make_inputs(st, 183, step, st.device)
+            st.step(q, k, v, out)
+            outs.append([o.cpu().numpy().copy() for o in out])
+        res[hot] = (outs, [st.read_pool(l) for l in range(2)])
+        st.close()
+    for l in range(2):
+        np.testing.assert_array_equal(res[True][1][l].view(np.uint16), res[False][1][l].view(np.uint16))
+    for a, b in zip(res[True][0], res[False][0]):
+        for x, y in zip(a, b):
+            np.testing.assert_array_equal(x.view(np.uint16), y.view(np.uint16))
 
 
 def test_class_mode_error_paths():

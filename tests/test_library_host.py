@@ -202,6 +202,10 @@ def test_size_queries_and_shape_errors():
                               max_batch=4, max_blocks_per_seq=16, blocks_per_layer=64,
                               resident_blocks=24, chunk_blocks=8)
     assert binding.okv_block_bytes(cfg) == 2 * 8 * 16 * 64 * 2
+    # two block-sized slots per sequence and layer for the newest blocks; none without block-granular offload
+    assert binding.okv_tail_bytes(cfg) == 2 * 2 * 4 * (2 * 8 * 16 * 64 * 2)
+    assert binding.okv_tail_bytes(binding.make_config(n_layers=2, n_q_heads=8, n_kv_heads=8, head_dim=64, block_tokens=16,
+                                                      max_batch=4, max_blocks_per_seq=16, blocks_per_layer=64)) == 0
     # KV heads per group of the pool layout: the library's rule against the oracle's statement of it
     from oracle import kv_layout
     for G in list(range(1, 41)) + [48, 64, 96, 128]:
