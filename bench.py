@@ -155,12 +155,18 @@ def cpu_baseline(st, ctx_now, q_layers, budget_s=15.0):
             # not timed: the oracle starts from host memory; the workers are forked after the layer's data is
             # in place and inherit it (they never touch the GPU and leave without running exit handlers)
             _CPU_JOB.update(q=q_layers[layer].cpu().numpy(), pool=st.read_pool(layer), layout=layout, ctx=ctx_now, H=st.H)
-            with mp.get_context("fork").Pool(cores) as pool:
+            pool = mp.get_context("fork").Pool(cores)
+            try:
                 layers += 1
                 t0 = time.perf_counter()
                 for n in pool.imap_unordered(_cpu_pairs, tasks):
                     done += n
                 dt += time.perf_counter() - t0
+            finally:
+                # the workers end by themselves once the queue is closed; terminate() would signal them, and a
+                # signal handler that a profiler has installed in the parent is inherited by them
+                pool.close()
+                pool.join()
             tokens += int(sum(int(ctx_now[b]) for (b, h) in pairs))
             if dt > budget_s:
                 break
@@ -293,7 +299,7 @@ def run_probe(nbytes=1 << 30, reps=5):
     src = torch.empty(nbytes, dtype=torch.uint8, device=dev).random_(0, 255)
     dst = torch.empty(nbytes, dtype=torch.uint8, device=dev)
     sink = torch.zeros(4, dtype=torch.int32, device=dev)
-    st = torch.cuda.Stream()
+    st = torch.cuda.current_stream()               # no stream of torch's pool: see harness.new_stream
     torch.cuda.synchronize()
     out = {"bytes": nbytes}
     for name, fn, moved in (("copy", lambda: binding.okv_probe_copy(dst, src, nbytes, st.cuda_stream), 2 * nbytes),

@@ -105,7 +105,15 @@ typedef struct okv_config {
                                   compute_stream when any layer is on the host.  With two or
                                   more staging buffers the library creates one more copy
                                   stream of its own (default priority) for the odd-numbered
-                                  buffers; okv_synchronize waits for it as well.             */
+                                  buffers; okv_synchronize waits for it as well.
+                                  The two streams should not share a hardware queue: the
+                                  runtime spreads ordinary streams over a few queues and works
+                                  each through in order, and kernels queued behind a copy's
+                                  completion marker wait for that copy (measured: no overlap
+                                  of attention and copies, 2-3 % of a step).  A stream made
+                                  with hipExtStreamCreateWithCUMask and a mask of all compute
+                                  units has a queue to itself; the library's own streams are
+                                  made that way.                                             */
   /* Block-granular offload (paper §IV-C: C_off is a share of the cache, not a number of
    * layers).  chunk_blocks == 0: off, whole layers are resident or on the host as
    * described above.  chunk_blocks > 0 (paged pools only): in EVERY layer the blocks with

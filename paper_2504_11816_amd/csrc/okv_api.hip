@@ -279,6 +279,21 @@ okv::AttnLaunch base_launch(okv_ctx *ctx) {
 
 void reset_schedule(okv_ctx *ctx);
 
+// A stream whose hardware queue no other stream of the process uses.  The runtime spreads ordinary streams
+// over a few hardware queues (4 by default) and works each queue through in order, so a copy stream that
+// happens to share a queue with the compute stream holds the attention kernels back behind the marker of
+// every copy (seen in the copy trace: kernels that waited for nothing started only when the other stream's
+// 2 GiB copy had finished).  A stream created with a compute-unit mask is given a queue of its own; the mask
+// names every compute unit.  Default priority.
+hipError_t own_queue_stream(hipStream_t *out) {
+  int dev = 0, cus = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
+  if (e != hipSuccess) return e;
+  std::vector<uint32_t> mask((size_t)(std::max(cus, 1) + 31) / 32, 0xFFFFFFFFu);
+  return hipExtStreamCreateWithCUMask(out, (uint32_t)mask.size(), mask.data());
+}
+
 // The host's lead over the compute stream, in steps (OKV_STEPS_AHEAD): the step about to be enqueued may
 // not begin before the one that many steps back has finished.
 int wait_for_earlier_steps(okv_ctx *ctx) {
@@ -831,7 +846,7 @@ int okv_create(const okv_config *cfg, okv_ctx **out) {
   OKV_TRY_CREATE(hipMalloc(&ctx->d_group_first, ((size_t)ctx->max_groups + 1) * sizeof(int32_t)));
   OKV_TRY_CREATE(hipMemset(ctx->d_group_first, 0, ((size_t)ctx->max_groups + 1) * sizeof(int32_t)));
   OKV_TRY_CREATE(hipMalloc(&ctx->d_plan, 4 * sizeof(int32_t)));
-  if (n_staging >= 2) OKV_TRY_CREATE(hipStreamCreateWithFlags(&ctx->h2d_odd, hipStreamNonBlocking));
+  if (n_staging >= 2) OKV_TRY_CREATE(own_queue_stream(&ctx->h2d_odd));
   if (by_class && any_host && OKV_STEPS_AHEAD > 0)
     for (hipEvent_t &e : ctx->step_done_ev) OKV_TRY_CREATE(hipEventCreateWithFlags(&e, hipEventDisableTiming));
   for (int i = 0; i < kEventRing; ++i) {
@@ -1258,7 +1273,7 @@ int okv_prefill_begin(okv_ctx *ctx, const int32_t *n_new) {
   if (n_tiles) OKV_HIP(ctx, hipMemcpy(ctx->d_tiles, flat.data(), (size_t)n_tiles * sizeof(int4), hipMemcpyHostToDevice));
   OKV_HIP(ctx, hipMemcpy(ctx->d_row_base, row_base.data(), (size_t)B * sizeof(int32_t), hipMemcpyHostToDevice));
   if (!ctx->d2h) {
-    OKV_HIP(ctx, hipStreamCreateWithFlags(&ctx->d2h, hipStreamNonBlocking));
+    OKV_HIP(ctx, own_queue_stream(&ctx->d2h));
     OKV_HIP(ctx, hipEventCreateWithFlags(&ctx->rows_ready_ev, hipEventDisableTiming));
     OKV_HIP(ctx, hipEventCreateWithFlags(&ctx->prefill_done_ev, hipEventDisableTiming));
     for (int i = 0; i < kEventRing; ++i) {

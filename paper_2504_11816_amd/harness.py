@@ -24,7 +24,32 @@ def _hip_runtime():
         _hip.hipHostFree.restype = ctypes.c_int
         _hip.hipGetLastError.argtypes = []
         _hip.hipGetLastError.restype = ctypes.c_int
+        _hip.hipExtStreamCreateWithCUMask.argtypes = [ctypes.POINTER(ctypes.c_void_p), ctypes.c_uint32,
+                                                      ctypes.POINTER(ctypes.c_uint32)]
+        _hip.hipExtStreamCreateWithCUMask.restype = ctypes.c_int
+        _hip.hipStreamDestroy.argtypes = [ctypes.c_void_p]
+        _hip.hipStreamDestroy.restype = ctypes.c_int
     return _hip
+
+
+def new_stream(device):
+    """A HIP stream with a hardware queue of its own (default priority), wrapped for torch.
+
+    The runtime spreads the streams of a process over a handful of hardware queues (4 here) and a queue is
+    worked through in order.  When the compute stream shares a queue with a copy stream, its kernels wait
+    behind the marker that follows every copy: in the copy trace no attention kernel started before the copy
+    stream's current 2 GiB copy had finished, and which streams share depends on how many were created before
+    (torch alone makes 32 at its first torch.cuda.Stream()).  A stream created with a compute-unit mask gets a
+    queue that no other stream uses; the mask names every compute unit, so nothing is masked.
+    """
+    hip = _hip_runtime()
+    words = (torch.cuda.get_device_properties(device).multi_processor_count + 31) // 32
+    mask = (ctypes.c_uint32 * words)(*([0xFFFFFFFF] * words))
+    raw = ctypes.c_void_p(0)
+    rc = hip.hipExtStreamCreateWithCUMask(ctypes.byref(raw), words, mask)
+    if rc != 0 or not raw.value:
+        raise RuntimeError(f"hipExtStreamCreateWithCUMask failed with {rc}")
+    return raw.value, torch.cuda.ExternalStream(raw.value, device=device)
 
 
 class PinnedHalfBuffer:
@@ -112,8 +137,11 @@ class Stack:
         self.hot_tails = bool(self.by_class and any_host and (hot_tails is None or hot_tails))
         self.tail_bytes = binding.okv_tail_bytes(shape) if self.hot_tails else 0
         self.tail_blocks = torch.empty(self.tail_bytes, dtype=torch.uint8, device=self.device) if self.hot_tails else None
-        self.compute_stream = torch.cuda.Stream(device=self.device)
-        self.h2d_stream = torch.cuda.Stream(device=self.device)
+        self._raw_streams = []
+        for name in ("compute_stream", "h2d_stream"):
+            raw, wrapped = new_stream(self.device)
+            self._raw_streams.append(raw)
+            setattr(self, name, wrapped)
         self.out_torch_dtype = torch.float32 if out_dtype else torch.float16
         self.ctx = binding.Context(
             n_layers=L, n_q_heads=H, n_kv_heads=G, head_dim=d, block_tokens=T, max_batch=B,
@@ -273,6 +301,9 @@ class Stack:
 
     def close(self):
         self.ctx.close()
+        for raw in self._raw_streams:
+            _hip_runtime().hipStreamDestroy(ctypes.c_void_p(raw))
+        self._raw_streams = []
         self.pools, self.dev_part, self.host_part = [], [], []
         for p in self._pinned:
             p.free()
