@@ -38,8 +38,8 @@ PCIE5_X16_GBPS = 64.0       # nominal, one direction
 # has changed since, `traffic` is reported as null.
 TRAFFIC_RECORD = {
     "workload": "cfg2",
-    "kernel_sha256": "9500f39fdf5f2222d9ef9305504f7ab699d1e898b20464f9d821b8483125016c",
-    "fetch_kib": 141752.5, "fetch_scale": 2.0000, "algorithmic_bytes": 285474816,   # context 513..576
+    "kernel_sha256": "e608ec559966436867b3c94a053fc4d0a1cb87752d42a40bbf0ac8afc6b120d4",
+    "fetch_kib": 141752.5, "fetch_scale": 1.9999, "algorithmic_bytes": 285474816,   # context 513..576
     "write_kib": 768.0, "write_scale": 1.0000,
 }
 
@@ -398,10 +398,7 @@ def run_offload(args, name=None, B=None, steps=None, warmup=None):
     ctx0 = np.full(B, w["ctx"] - 1, dtype=np.int32)
     cap = w["ctx"] + steps + warmup
     on_host, n_off = binding.kv_offload_plan(L, w["c_off"][0], w["c_off"][1])
-    # Whole layers: four staging buffers.  With two, the two copies in flight share the link, end together
-    # and leave it idle while the first of them is attended (0.7 ms per pair in the copy trace); with four the
-    # two copy streams drift apart and one copy is always running.  8.6 GiB of HBM at this shape.
-    n_staging = args.staging or 4
+    n_staging = args.staging or 2
     log(f"[bench] offload leg {name}: B={B} ctx={w['ctx']} T={T} host layers {n_off}/{L} steps={steps} staging buffers {n_staging}")
     st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=cap, on_host=on_host, out_dtype=0,
                n_staging=n_staging)
@@ -807,7 +804,7 @@ def main():
     ap.add_argument("--offload-workload", default="cfg3", choices=["cfg3", "cfg5"])
     ap.add_argument("--offload-steps", type=int, default=0)
     ap.add_argument("--offload-batch", type=int, default=0)
-    ap.add_argument("--staging", type=int, default=0, help="staging buffers (1..4); 0 = 4 for whole layers, 2 for chunks")
+    ap.add_argument("--staging", type=int, default=0, help="staging buffers (1..4); 0 = 2")
     ap.add_argument("--no-blocks", action="store_true", help="skip the block-granular offloaded leg")
     ap.add_argument("--no-tails", action="store_true",
                     help="block-granular leg: store every appended row through the mapped pointer instead of keeping "

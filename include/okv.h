@@ -93,10 +93,8 @@ typedef struct okv_config {
   void   *staging[OKV_MAX_STAGING]; /* DEVICE: buffers host layers are copied into, each at least
                                   okv_layer_pool_bytes.  The leading non-NULL entries are used:
                                   one = no overlap of copy and compute; two = the copy of the next
-                                  host layer runs during this one's attention; with four, one copy
-                                  is running at any time (two copies in flight end together and
-                                  leave the link idle while the first is attended: 1-2 % of a
-                                  step).  All NULL if no layer is on the host                   */
+                                  host layer runs during this one's attention (more than two
+                                  measured no faster).  All NULL if no layer is on the host      */
   int64_t staging_bytes;       /* size of each staging buffer                                */
   void   *workspace;           /* DEVICE: split-K partial results                            */
   int64_t workspace_bytes;     /* at least okv_workspace_bytes(cfg)                          */
