@@ -10,9 +10,6 @@ SOURCES = ["okv_kernels.hip", "okv_layer.hip", "okv_api.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno-gpu-rdc",
          # keep the compiler from forming packed-fp32 instructions
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-         # a ticket draw by one lane stays one plain atomic whose result is read a unit later (the
-         # wave-aggregating rewrite reads the result at once and so waits for the whole round trip)
-         "-mllvm", "-amdgpu-atomic-optimizer-strategy=None",
          # matrix-core results stay in ordinary vector registers: the kernels here run one or two
          # wavefronts per SIMD and have registers to spare, and the accumulator-register form cost the
          # attention loop a copy of all 32 accumulators in and out per tile
