@@ -77,3 +77,70 @@ def test_cfg5_shape_all_layers_reduced_batch():
     run_and_check(st, n_steps=2, seed=542, pairs=[(0, 0), (15, 31)])
     st.close()
     torch.cuda.empty_cache()
+
+
+def test_cfg3_share_of_every_layer_on_the_host_newest_blocks_in_hbm_across_a_block_boundary():
+    # batch 64, 16-token blocks, half of every layer's blocks in pinned host memory, whole sequences at a time
+    # ("sequence" placement: the newest block of half of the sequences is a host block), streamed in 256 MiB
+    # chunks.  18 steps from context 2041 to 2058 cross the block boundary at 2048: the rows appended on the way
+    # live in HBM slots, the block is written to the host pool after step 8.  The oracle keeps the keys and values
+    # of the sampled (layer, sequence, KV head) triples itself, so nothing is read back (and nothing flushed) on
+    # the way; sampled outputs at four steps, the host pool's filled block bit for bit at the end.
+    from fractions import Fraction
+    from oracle import attention as oa, kv_layout
+    from gpu_util import assert_close, make_inputs
+    L, B, H, G, d, T = 32, 64, 32, 32, 128, 16
+    cap = 2064
+    need = B * synth.blocks_needed(cap, T)
+    n_res, n_host = binding.okv_plan_block_split(need, 1, 2)
+    shape = binding.make_config(n_layers=L, n_q_heads=H, n_kv_heads=G, head_dim=d, block_tokens=T, max_batch=B,
+                                max_blocks_per_seq=synth.blocks_needed(cap, T), blocks_per_layer=need)
+    chunk_blocks = (256 << 20) // binding.okv_block_bytes(shape)
+    say(f"cfg3 blocks: building {L} layers, {n_host} of {need} blocks per layer on the host")
+    st = Stack(L=L, H=H, G=G, d=d, B=B, T=T, cap_tokens=cap, out_dtype=0, blocks_per_layer=need,
+               resident_blocks=n_res, chunk_blocks=chunk_blocks)
+    assert st.hot_tails
+    for l in range(L):
+        st.fill_pool(l, synth.stream_seed(550, synth.TENSOR_POOL, l))
+    table = synth.classed_block_table([st.cap_tokens] * B, T, n_res, n_host, n_host, "sequence", 551,
+                                      max_blocks_per_seq=st.max_blocks)
+    on_host = [b for b in range(B) if table[b, 2040 // T] >= n_res]
+    in_hbm = [b for b in range(B) if table[b, 2040 // T] < n_res]
+    assert on_host and in_hbm
+    st.set_batch([2040] * B, table)
+    layout = st.layout()
+    pairs = [(on_host[0], 0), (on_host[-1], 31), (in_hbm[0], 17)]
+    kept = {}                                              # (layer, b, g) -> [K rows, V rows] as the oracle holds them
+    for l in range(L):
+        for (b, h) in pairs:
+            rows = [[kv_layout.token_row_offset(layout, b, kv, h, i) for i in range(2040)] for kv in (0, 1)]
+            kept[(l, b, h)] = [st.read_rows(l, rows[0]), st.read_rows(l, rows[1])]
+    for step in range(18):
+        q, k, v, out = make_inputs(st, 553, step, st.device)
+        st.step(q, k, v, out)
+        for l in range(L):
+            kl, vl = k[l].cpu().numpy(), v[l].cpu().numpy()
+            for (b, h) in pairs:
+                kept[(l, b, h)][0] = np.concatenate([kept[(l, b, h)][0], kl[b, h][None]])
+                kept[(l, b, h)][1] = np.concatenate([kept[(l, b, h)][1], vl[b, h][None]])
+        if step in (0, 7, 8, 17):
+            st.synchronize()
+            say(f"  step {step + 1}: context {2041 + step}")
+            for l in range(L):
+                got = out[l].float().cpu().numpy()
+                ql = q[l].cpu().numpy()
+                for (b, h) in pairs:
+                    K, V = kept[(l, b, h)]
+                    ref = oa.attend_one(oa.as_f64(ql[b, h]), oa.as_f64(K), oa.as_f64(V))
+                    assert_close(got[b, h][None], ref[None], f"step {step} layer {l} pair {(b, h)}")
+    # the block that step 8 filled is in the host pool although nothing asked for a flush
+    st.synchronize()
+    for l in (0, 31):
+        host = st.host_part[l].numpy()
+        for (b, h) in pairs[:2]:
+            for kv in (0, 1):
+                for i in (2040, 2047):
+                    at = kv_layout.token_row_offset(layout, b, kv, h, i) - st.split_at
+                    np.testing.assert_array_equal(host[at:at + d].view(np.uint16), kept[(l, b, h)][kv][i].view(np.uint16))
+    st.close()
+    torch.cuda.empty_cache()
