@@ -63,6 +63,34 @@ def log(msg):
     print(msg, file=sys.stderr, flush=True)
 
 
+_SETTLE = {"big_release": False, "seconds": 6.0}
+
+
+def settle(leg, seconds=None):
+    """A pause before a leg's timed region when the process has given tens of GiB of device memory back since
+    it last paused (closing the previous leg's buffers): for several seconds after such a release steps with
+    copies in them run 2-3 % slower (the same leg, in the same process: 618-624 ms a step right away, 607 from
+    the sixth second on or after a pause of 8 s) -- something is still busy with the memory.  A serving process
+    does not do that; the headline leg runs first and never waits."""
+    import torch
+    torch.cuda.synchronize()
+    seconds = _SETTLE["seconds"] if seconds is None else min(seconds, _SETTLE["seconds"])
+    waited = 0.0
+    if _SETTLE["big_release"] and seconds > 0:
+        log(f"[bench] {leg}: waiting {seconds:.0f} s for the device to settle after the previous leg's release")
+        time.sleep(seconds)
+        waited = seconds
+    _SETTLE["big_release"] = False
+    return waited
+
+
+def released():
+    """Called when a leg has closed its buffers."""
+    import torch
+    torch.cuda.empty_cache()
+    _SETTLE["big_release"] = True
+
+
 def fixed_inputs(st, seed):
     """q / k_new / v_new per layer, drawn once and reused every step, plus outputs."""
     import torch
@@ -213,6 +241,7 @@ def run_resident(args, workload=None, steps=None, warmup=None, with_cpu=None, la
                                            max_blocks_per_seq=st.max_blocks)
     inputs = fixed_inputs(st, args.seed)
     log("[bench] pools filled; timing")
+    settled = settle(workload, 2.0)                      # no copies in these steps: the effect is under 1 % here
     dt = timed_steps(st, ctx0, table, inputs, steps, warmup)
     split = st.ctx.okv_get_split_tokens()
     n_items = len(st.ctx.okv_worklist(from_device=False))
@@ -226,7 +255,7 @@ def run_resident(args, workload=None, steps=None, warmup=None, with_cpu=None, la
         "hbm_frac": kv_bytes / dt / 1e9 / HBM_PEAK_GBPS,
         "kernel_gbps": kv_bytes / k_s / 1e9, "kernel_frac": kv_bytes / k_s / 1e9 / HBM_PEAK_GBPS,
         "kernel_avg_us": k_s / max(k_n, 1) * 1e6, "kernel_launches": k_n,
-        "kernel_time_includes_merge_pass": n_items > B,
+        "kernel_time_includes_merge_pass": n_items > B, "settle_s": settled,
         "kv_bytes_per_launch": kv_bytes / max(k_n, 1), "split_tokens": split, "work_items": n_items, "steps": steps,
         "B": B, "L": L, "H": H, "G": G, "d": d, "T": T,
         "ctx_desc": (f"{int(ctx_first.max())}..{int(ctx_first.max()) + steps - 1}" if not w["ragged"] else
@@ -242,7 +271,7 @@ def run_resident(args, workload=None, steps=None, warmup=None, with_cpu=None, la
         cpu = cpu_baseline(st, mid, inputs[0], args.cpu_seconds)
     st.close()
     del st
-    torch.cuda.empty_cache()
+    released()
     return res, cpu
 
 
@@ -286,7 +315,7 @@ def run_latency(args, reps=200):
             f"({out[name]['step_latency_us_p10']:.1f}..{out[name]['step_latency_us_p90']:.1f}), on the GPU {out[name]['gpu_time_us_median']:.1f} us")
         st.close()
         del st
-    torch.cuda.empty_cache()
+    released()
     return out
 
 
@@ -411,6 +440,7 @@ def run_offload(args, name=None, B=None, steps=None, warmup=None):
     link = binding.okv_measure_h2d(st.staging[0], st.pools[host_layer], min(st.pool_bytes, 2 << 30), 10,
                                    st.h2d_stream.cuda_stream)
     log(f"[bench] host-to-device link: {link:.1f} GB/s (plain hipMemcpyAsync, pinned, median of 10)")
+    settle(f"offload leg {name}")
     dt = timed_steps(st, ctx0, table, inputs, steps, warmup, running=True)
     per_tok = 2 * G * d * 2
     link_bytes = sum(int((ctx0 + s).sum()) * per_tok * n_off for s in range(1, steps + 1))
@@ -441,7 +471,7 @@ def run_offload(args, name=None, B=None, steps=None, warmup=None):
         f"({res['attn_kernel_gbps']:.0f} GB/s); overlap {res['overlap']:.2f} ({res['overlap_vs_back_to_back_copies']:.2f} against back-to-back copies)")
     st.close()
     del st
-    torch.cuda.empty_cache()
+    released()
     return res
 
 
@@ -479,6 +509,7 @@ def run_offload_blocks(args):
     table = synth.classed_block_table([st.cap_tokens] * B, T, n_res, n_host, n_host, args.placement, args.seed + 1,
                                       max_blocks_per_seq=st.max_blocks)
     inputs = fixed_inputs(st, args.seed)
+    settle(f"block-granular leg {name}")
     dt = timed_steps(st, ctx0, table, inputs, steps, warmup, running=True)
     # what crosses the link per step: every host block of every layer (all of them hold keys:
     # the oldest blocks of a sequence are full)
@@ -511,7 +542,7 @@ def run_offload_blocks(args):
         f"overlap {res['overlap']:.2f}; staging {res['staging_gib']:.2f} GiB")
     st.close()
     del st
-    torch.cuda.empty_cache()
+    released()
     return res
 
 
@@ -565,6 +596,7 @@ def run_prefill(args):
     reads_per_layer = max(1, int(round(want_ms / read_ms)))
 
     plan = {}
+    settle("prefill leg")
 
     def one_pass(with_compute):
         st.set_batch([0] * B, table)
@@ -610,7 +642,7 @@ def run_prefill(args):
         f"route: {res['route']}, {res['copies_per_host_layer']} copies per host layer")
     st.close()
     del st, bufs, scratch
-    torch.cuda.empty_cache()
+    released()
     return res
 
 
@@ -650,6 +682,7 @@ def run_layers(args):
         for _ in range(n):
             x.copy_(x0)                    # keep the activations at the scale of the inputs (random weights amplify)
             bound.step(x)
+    settle("decoder layers", 2.0)
     st.set_batch(ctx0, table)
     with torch.cuda.stream(st.compute_stream):
         run(warmup)
@@ -713,7 +746,7 @@ def run_layers(args):
         + ", ".join(f"{k} {v['us']:.1f} us = {v['weight_gbps']:.0f} GB/s" for k, v in alone.items()))
     st.close()
     del st, weights, scratch, bound
-    torch.cuda.empty_cache()
+    released()
     return res
 
 
@@ -747,7 +780,7 @@ def run_model(args, off):
         times[B] = k_s / k_n                                  # seconds per layer and step
         st.close()
         del st
-        torch.cuda.empty_cache()
+        released()
     theory = {B: isv.isv_attention_flops_decode(B, ctx + (steps - 1) / 2, h1) / flops for B in times}
     alpha, beta, fit_err = isv.isv_ctcf_fit([theory[B] for B in fit_b], [times[B] for B in fit_b])
     hold_err = float(np.mean([abs(alpha * theory[B] + beta - times[B]) / times[B] for B in hold_b]))
@@ -790,7 +823,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=0, help="decode steps to time (0 = the workload's own count)")
     ap.add_argument("--warmup", type=int, default=8)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3_resident", "cfg4", "gqa8", "gqa16"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg1", "cfg2", "cfg3_resident", "cfg4", "gqa8", "gqa16", "kv8", "kv4", "kv2"])
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--split-tokens", type=int, default=0,
                     help="resident leg: upper bound on the keys of one work item (0 = the library chooses)")
@@ -812,6 +845,9 @@ def main():
     ap.add_argument("--no-configs", action="store_true",
                     help="skip the legs of the other named workloads (cfg2 in full, cfg4, cfg1)")
     ap.add_argument("--no-cfg5", action="store_true", help="skip the offline large-batch offloaded leg")
+    ap.add_argument("--settle", type=float, default=6.0,
+                    help="seconds a leg with copies waits before its timed region when the leg before it has just "
+                         "released its buffers (legs without copies wait 2 s at most); 0 = never")
     ap.add_argument("--no-model", action="store_true", help="skip the prediction-model leg")
     ap.add_argument("--no-decoder", action="store_true", help="skip the whole-decoder-layer leg")
     ap.add_argument("--layer-steps", type=int, default=32, help="decoder-layer leg: decode steps to time")
@@ -833,6 +869,7 @@ def main():
     import torch
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
+    _SETTLE["seconds"] = args.settle
     res, cpu = run_resident(args)
     probe = run_probe() if args.probe else None
     # the other named workloads, each at its own size whatever --steps says
@@ -842,6 +879,8 @@ def main():
             extra["cfg2_full"], _ = run_resident(args, "cfg2", steps=512, with_cpu=False, layers=0)
         extra["cfg4"], _ = run_resident(args, "cfg4", steps=20, with_cpu=False, layers=0)
         extra["cfg1"] = run_latency(args)
+        # 8, 4 and 2 KV heads at the same KV bytes per layer: what the pool layout's slabs of several tiles buy
+        extra["few_kv_heads"] = {w: run_resident(args, w, steps=8, with_cpu=False, layers=0)[0] for w in ("kv8", "kv4", "kv2")}
     off = None if (args.no_offload or args.no_layers) else run_offload(args)
     off_blocks = None if (args.no_offload or args.no_blocks) else run_offload_blocks(args)
     if not (args.no_offload or args.no_cfg5):

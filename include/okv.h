@@ -31,23 +31,27 @@
  *   - A context is not thread-safe: one host thread drives it.
  *
  * KV pool layouts (fp16; kv = 0 keys, kv = 1 values; G = n_kv_heads, d = head_dim).
- * A pool is a row of TILE SLABS.  A slab holds the K and V rows of 16 consecutive
- * tokens for all G KV heads, the heads taken in groups of Gg consecutive heads, each
- * group as its K rows and then its V rows, row-major:
- *   slab[g / Gg][kv][g % Gg][slot][d]      slot < 16;  2 * G * 16 * d * 2 bytes
- * Gg is the largest divisor of G with Gg * d <= 1024, i.e. the K rows of a group (and
- * its V rows) are one run of at most 32 KiB: 8 heads at d = 128, 16 at d = 64, all G
- * heads when there are fewer (okv_kv_head_group returns it).  The K rows (and the V
- * rows) of 16 consecutive tokens of one KV head are one contiguous run of 16 * d * 2
- * bytes, which is what a wavefront reads at a time; with this grouping the K run and
- * the V run it reads together are 32 KiB apart and those of neighbouring heads adjoin,
- * which measured 8-10 % faster on MI355X than keeping all K rows of a block before all
- * its V rows.
- *   contiguous (block_tokens == 0):  sequence b < max_batch owns the max_ctx / 16 slabs
- *     from b * (max_ctx / 16) on; token i is in slab i / 16 of them, slot i % 16.
- *   paged (block_tokens == T):  block blk < blocks_per_layer is the T / 16 slabs from
- *     blk * (T / 16) on; token i of sequence b is in block block_table[b][i / T], slab
- *     (i % T) / 16 of it, slot i % 16.
+ * A pool is a row of SLABS.  A slab holds the K and V rows of 16 * St consecutive tokens
+ * (St tiles of 16) for all G KV heads, the heads taken in groups of Gg consecutive heads,
+ * each group as its K rows and then its V rows, tile after tile, row-major:
+ *   slab[g / Gg][kv][tile in slab][g % Gg][slot][d]    slot < 16;  2 * G * 16 * St * d * 2 bytes
+ * Gg is the largest divisor of G with Gg * d <= 1024 (8 heads at d = 128, 16 at d = 64, all
+ * G heads when there are fewer; okv_kv_head_group returns it).  St is the largest power of
+ * two with St * Gg * d <= 1024 that divides the number of 16-token tiles of a pool slice (a
+ * block, or a sequence's slice of a contiguous pool; okv_slab_tiles returns it): 1 for 8 or
+ * more KV heads at d = 128, else as many tiles as it takes to make the K rows of a group one
+ * run of 32 KiB, if the slice has them.  The K rows (and the V rows) of 16 consecutive tokens
+ * of one KV head are one contiguous run of 16 * d * 2 bytes, which is what a wavefront reads
+ * at a time; with this grouping the K run and the V run it reads together are 32 KiB apart and
+ * those of neighbouring heads adjoin, which measured 8-10 % faster on MI355X than keeping all
+ * K rows of a block before all its V rows, and with fewer than 8 KV heads 10 % faster than
+ * slabs of a single tile (their K and V runs are 4-16 KiB apart).
+ *   contiguous (block_tokens == 0):  sequence b < max_batch owns the max_ctx / (16 St) slabs
+ *     from b * (max_ctx / (16 St)) on; token i is in slab i / (16 St) of them, tile
+ *     (i / 16) % St of it, slot i % 16.
+ *   paged (block_tokens == T):  block blk < blocks_per_layer is the T / (16 St) slabs from
+ *     blk * (T / (16 St)) on; token i of sequence b is in block block_table[b][i / T], at
+ *     token i % T of it: slab (i % T) / (16 St), tile ((i % T) / 16) % St, slot i % 16.
  */
 #ifndef OKV_H
 #define OKV_H
@@ -152,6 +156,11 @@ int64_t okv_block_bytes(const okv_config *cfg);
 /* Gg of the pool layout above for n_kv_heads KV heads of head_dim numbers; < 0 unless
  * n_kv_heads >= 1 and head_dim is 64 or 128.  Pure host function. */
 int32_t okv_kv_head_group(int32_t n_kv_heads, int32_t head_dim);
+
+/* St of the pool layout above for a pool slice of slice_tokens tokens (block_tokens, or max_ctx
+ * of a contiguous pool); < 0 unless n_kv_heads >= 1, head_dim is 64 or 128 and slice_tokens is a
+ * positive multiple of 16.  Pure host function. */
+int32_t okv_slab_tiles(int32_t n_kv_heads, int32_t head_dim, int32_t slice_tokens);
 
 /* Bytes of workspace the split-K partials need in the worst case under cfg (every
  * sequence at full capacity, the smallest split size the library would choose or

@@ -6,22 +6,26 @@ The KV cache holds, per layer, one key row and one value row of `d` fp16
 numbers per sequence, per token, per KV head (paper §II-A: keys and values of
 every processed token are kept for reuse by the decode stage).  The library
 fixes two pool layouts, written here from their description.  Both are made of
-TILE SLABS: the K and V rows of 16 consecutive tokens for all G KV heads,
-row-major as
+SLABS: the K and V rows of 16 * St consecutive tokens (St tiles of 16) for all G
+KV heads, row-major as
 
-  slab[group][kv][head in group][slot][d]   group < G / Gg, head in group < Gg, slot < 16
+  slab[group][kv][tile in slab][head in group][slot][d]
+      group < G / Gg, tile in slab < St, head in group < Gg, slot < 16
 
 where the KV heads are taken in groups of Gg consecutive heads, Gg being the
-largest divisor of G with Gg * d <= 1024 (so that the K rows of a group, and
-its V rows, are one run of at most 32 KiB), kv = 0 selects keys and kv = 1
-values.
+largest divisor of G with Gg * d <= 1024, kv = 0 selects keys and kv = 1
+values, and St is the largest power of two with St * Gg * d <= 1024 that divides
+the number of 16-token tiles of a pool slice (so that the K rows of a group, and
+its V rows, are one run of at most 32 KiB, and of exactly 32 KiB wherever the
+slice is long enough; St = 1 when a single tile of a group already is).
 
-  contiguous  sequence b owns the C / 16 consecutive slabs from b * C / 16 on
-              (C = capacity in tokens, a multiple of 16); token tok is in slab
-              tok // 16 of them, slot tok % 16
-  paged       block blk is the T / 16 consecutive slabs from blk * T / 16 on;
-              token i of sequence b lives in block block_table[b][i // T], at
-              token (i % T) of that block: slab (i % T) // 16, slot i % 16
+  contiguous  sequence b owns the C / (16 St) consecutive slabs from
+              b * C / (16 St) on (C = capacity in tokens, a multiple of 16);
+              token tok is in slab tok // (16 St) of them, tile
+              (tok // 16) % St of it, slot tok % 16
+  paged       block blk is the T / (16 St) consecutive slabs from
+              blk * T / (16 St) on; token i of sequence b lives in block
+              block_table[b][i // T], at token (i % T) of that block
 
 Offsets are in ELEMENTS (fp16), not bytes.
 """
@@ -37,23 +41,35 @@ def head_group(G, d):
     return best
 
 
-def slab_row_offset(kv, g, slot, G, d):
-    """Element offset of row (kv, g, slot) inside one tile slab."""
-    assert 0 <= kv < 2 and 0 <= g < G and 0 <= slot < 16
+def slab_tiles(G, d, slice_tokens):
+    """St: 16-token tiles per slab for a pool slice (block or sequence) of slice_tokens tokens."""
+    assert slice_tokens % 16 == 0
+    Gg = head_group(G, d)
+    St = 1
+    while 2 * St * Gg * d <= 1024 and (slice_tokens // 16) % (2 * St) == 0:
+        St *= 2
+    return St
+
+
+def slab_row_offset(kv, g, tok, G, d, St):
+    """Element offset of row (kv, g, tok) inside one slab (tok < 16 * St counts the slab's tokens)."""
+    assert 0 <= kv < 2 and 0 <= g < G and 0 <= tok < 16 * St
     Gg = head_group(G, d)
     group, within = divmod(g, Gg)
-    return (((group * 2 + kv) * Gg + within) * 16 + slot) * d
+    tile, slot = divmod(tok, 16)
+    return (((((group * 2 + kv) * St + tile) * Gg + within) * 16) + slot) * d
 
 
-def slab_elems(G, d):
-    return 2 * G * 16 * d
+def slab_elems(G, d, St):
+    return 2 * G * 16 * St * d
 
 
 def contiguous_row_offset(b, kv, g, tok, G, C, d):
     """Element offset of row (b, kv, g, tok) in a contiguous pool."""
     assert C % 16 == 0 and 0 <= tok < C
-    slab = b * (C // 16) + tok // 16
-    return slab * slab_elems(G, d) + slab_row_offset(kv, g, tok % 16, G, d)
+    St = slab_tiles(G, d, C)
+    slab = b * (C // (16 * St)) + tok // (16 * St)
+    return slab * slab_elems(G, d, St) + slab_row_offset(kv, g, tok % (16 * St), G, d, St)
 
 
 def paged_row_offset(blk, kv, g, slot, G, T, d):
@@ -61,8 +77,9 @@ def paged_row_offset(blk, kv, g, slot, G, T, d):
     tokens inside the block)."""
     assert blk >= 0, "token maps to an unallocated block"
     assert T % 16 == 0 and 0 <= slot < T
-    slab = blk * (T // 16) + slot // 16
-    return slab * slab_elems(G, d) + slab_row_offset(kv, g, slot % 16, G, d)
+    St = slab_tiles(G, d, T)
+    slab = blk * (T // (16 * St)) + slot // (16 * St)
+    return slab * slab_elems(G, d, St) + slab_row_offset(kv, g, slot % (16 * St), G, d, St)
 
 
 def token_row_offset(layout, b, kv, g, tok):

@@ -16,7 +16,7 @@ _CODE_NAMES = {0: "OKV_OK", -1: "OKV_EINVAL", -2: "OKV_ENOSPC", -3: "OKV_ESTATE"
 
 # every symbol include/okv.h declares
 EXPORTS = [
-    "okv_layer_pool_bytes", "okv_block_bytes", "okv_kv_head_group", "okv_workspace_bytes", "okv_tail_bytes", "kv_offload_plan", "okv_plan_from_bytes",
+    "okv_layer_pool_bytes", "okv_block_bytes", "okv_kv_head_group", "okv_slab_tiles", "okv_workspace_bytes", "okv_tail_bytes", "kv_offload_plan", "okv_plan_from_bytes",
     "okv_plan_block_split", "okv_schedule_trace", "okv_create", "okv_destroy", "okv_last_error", "okv_set_batch",
     "okv_step_begin", "okv_step_end", "okv_step_abort", "okv_flush_tails", "kv_append", "decode_attn", "okv_decode_step", "okv_synchronize",
     "okv_set_split_tokens", "okv_get_split_tokens", "okv_get_ctx_lens", "okv_worklist",
@@ -92,6 +92,7 @@ def lib():
             "okv_layer_pool_bytes": (I64, [cfgp]),
             "okv_block_bytes": (I64, [cfgp]),
             "okv_kv_head_group": (I32, [I32, I32]),
+            "okv_slab_tiles": (I32, [I32, I32, I32]),
             "okv_workspace_bytes": (I64, [cfgp]),
             "okv_tail_bytes": (I64, [cfgp]),
             "okv_plan_block_split": (ctypes.c_int, [I64, I64, I64, ctypes.POINTER(I64), ctypes.POINTER(I64)]),
@@ -251,6 +252,13 @@ def okv_block_bytes(cfg):
 
 def okv_kv_head_group(n_kv_heads, head_dim):
     r = lib().okv_kv_head_group(n_kv_heads, head_dim)
+    if r < 0:
+        _check(int(r))
+    return int(r)
+
+
+def okv_slab_tiles(n_kv_heads, head_dim, slice_tokens):
+    r = lib().okv_slab_tiles(n_kv_heads, head_dim, slice_tokens)
     if r < 0:
         _check(int(r))
     return int(r)

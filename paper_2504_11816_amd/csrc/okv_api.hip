@@ -57,6 +57,11 @@ constexpr int64_t kMaxClasses = 4096;
 #ifndef OKV_STEPS_AHEAD
 #define OKV_STEPS_AHEAD 1
 #endif
+#ifndef OKV_STEPS_AHEAD_LAYERS
+#define OKV_STEPS_AHEAD_LAYERS 0
+#endif
+constexpr int kAheadRing = (OKV_STEPS_AHEAD > OKV_STEPS_AHEAD_LAYERS ? OKV_STEPS_AHEAD : OKV_STEPS_AHEAD_LAYERS) > 0
+                               ? (OKV_STEPS_AHEAD > OKV_STEPS_AHEAD_LAYERS ? OKV_STEPS_AHEAD : OKV_STEPS_AHEAD_LAYERS) : 1;
 // Blocks bound for the host are gathered in a staging buffer and moved by hipMemcpyAsync when, on
 // average, at least this many bytes of them are adjacent in the host pool; below that the per-copy
 // cost is too high and the rows are written by a kernel through the mapped pointer instead.
@@ -104,8 +109,9 @@ struct okv_ctx {
   hipEvent_t flush_ev = nullptr;
   bool flush_recorded = false;
   // host layers or blocks: the ends of the last steps on the compute stream (a ring)
-  hipEvent_t step_done_ev[OKV_STEPS_AHEAD > 0 ? OKV_STEPS_AHEAD : 1] = {};
+  hipEvent_t step_done_ev[kAheadRing] = {};
   int64_t steps_recorded = 0;
+  int32_t steps_ahead = 0;               // the limit that applies to this context's kind of offload (0 = none)
 
   int32_t *d_block_table = nullptr, *d_ctx_lens = nullptr, *d_chunk_prefix = nullptr;
   int4 *d_item_desc = nullptr;
@@ -297,14 +303,14 @@ hipError_t own_queue_stream(hipStream_t *out) {
 // The host's lead over the compute stream, in steps (OKV_STEPS_AHEAD): the step about to be enqueued may
 // not begin before the one that many steps back has finished.
 int wait_for_earlier_steps(okv_ctx *ctx) {
-  constexpr int64_t kAhead = OKV_STEPS_AHEAD;
+  const int64_t kAhead = ctx->steps_ahead;
   if (kAhead <= 0 || !ctx->step_done_ev[0] || ctx->steps_recorded < kAhead) return OKV_OK;
   OKV_HIP(ctx, hipEventSynchronize(ctx->step_done_ev[ctx->steps_recorded % kAhead]));   // the oldest of the ring
   return OKV_OK;
 }
 
 int mark_step_done(okv_ctx *ctx) {
-  constexpr int64_t kAhead = OKV_STEPS_AHEAD;
+  const int64_t kAhead = ctx->steps_ahead;
   if (kAhead <= 0 || !ctx->step_done_ev[0]) return OKV_OK;
   OKV_HIP(ctx, hipEventRecord(ctx->step_done_ev[ctx->steps_recorded % kAhead], ctx->compute));
   ctx->steps_recorded += 1;
@@ -326,6 +332,8 @@ okv::TailLaunch tail_launch(okv_ctx *ctx, int32_t mode) {
   t.max_blocks = ctx->shape.max_blocks;
   t.log2_T = ctx->shape.log2_T;
   t.D = ctx->shape.D;
+  t.gg = ctx->shape.gg;
+  t.st_log2 = ctx->shape.st_log2;
   t.id_lo = (int32_t)ctx->resident_blocks;
   t.id_hi = (int32_t)ctx->cfg.blocks_per_layer;
   t.mode = mode;
@@ -708,6 +716,12 @@ int okv_equal_stretches(const int32_t *ctx_lens, int32_t B, int32_t max_groups, 
   return OKV_OK;
 }
 
+int32_t okv_slab_tiles(int32_t n_kv_heads, int32_t head_dim, int32_t slice_tokens) {
+  if (n_kv_heads < 1 || (head_dim != 64 && head_dim != 128) || slice_tokens < 16 || slice_tokens % 16)
+    return fail(nullptr, OKV_EINVAL, "okv_slab_tiles: bad argument");
+  return 1 << okv::slab_tiles_log2(n_kv_heads, head_dim, slice_tokens);
+}
+
 int32_t okv_kv_head_group(int32_t n_kv_heads, int32_t head_dim) {
   if (n_kv_heads < 1 || (head_dim != 64 && head_dim != 128)) return OKV_EINVAL;
   return okv::kv_head_group(n_kv_heads, head_dim);
@@ -787,6 +801,7 @@ int okv_create(const okv_config *cfg, okv_ctx **out) {
   while (s.paged && (1 << s.log2_T) < cfg->block_tokens) ++s.log2_T;
   s.tcap = s.paged ? cfg->block_tokens : cfg->max_ctx;
   s.gg = okv::kv_head_group(s.G, s.D);
+  s.st_log2 = okv::slab_tiles_log2(s.G, s.D, s.tcap);
   s.max_blocks = s.paged ? cfg->max_blocks_per_seq : 1;
   ctx->block_bytes = (int64_t)2 * s.G * s.tcap * s.D * 2;
   ctx->by_class = by_class;
@@ -847,7 +862,8 @@ int okv_create(const okv_config *cfg, okv_ctx **out) {
   OKV_TRY_CREATE(hipMemset(ctx->d_group_first, 0, ((size_t)ctx->max_groups + 1) * sizeof(int32_t)));
   OKV_TRY_CREATE(hipMalloc(&ctx->d_plan, 4 * sizeof(int32_t)));
   if (n_staging >= 2) OKV_TRY_CREATE(own_queue_stream(&ctx->h2d_odd));
-  if (by_class && any_host && OKV_STEPS_AHEAD > 0)
+  ctx->steps_ahead = !any_host ? 0 : by_class ? OKV_STEPS_AHEAD : OKV_STEPS_AHEAD_LAYERS;
+  if (ctx->steps_ahead > 0)
     for (hipEvent_t &e : ctx->step_done_ev) OKV_TRY_CREATE(hipEventCreateWithFlags(&e, hipEventDisableTiming));
   for (int i = 0; i < kEventRing; ++i) {
     OKV_TRY_CREATE(hipEventCreateWithFlags(&ctx->ready_ev[i], hipEventDisableTiming));
@@ -1946,6 +1962,7 @@ int okv_decode_attn_static(const okv_static_attn *a) {
   while (s.paged && (1 << s.log2_T) < a->block_tokens) ++s.log2_T;
   s.tcap = s.paged ? a->block_tokens : a->max_ctx;
   s.gg = okv::kv_head_group(G, D);
+  s.st_log2 = okv::slab_tiles_log2(G, D, s.tcap);
   s.max_blocks = s.paged ? a->max_blocks_per_seq : 1;
   l.batch = okv::BatchState{a->block_table, a->ctx_lens, chunk_prefix, item_desc, a->B, 0, (int32_t)max_items, 1};
   l.q = a->q;

@@ -218,6 +218,19 @@ inline int32_t kv_head_group(int32_t G, int32_t d) {
   return gg;
 }
 
+// 16-token tiles per slab, St: the largest power of two for which the K rows of a head group of St tiles
+// (St * gg * 16 * d * 2 bytes) fit in 32 KiB and St divides the tiles of a pool slice (a block, or a
+// sequence's slice of a contiguous pool).  With fewer than 8 KV heads at d = 128 the K rows of one tile are
+// less than 32 KiB, the K tile and the V tile a wavefront reads together would lie 4-16 KiB apart, and the
+// kernel ran at 71-72 % of the HBM peak where 8 KV heads reach 81 %; taking St tiles together puts them
+// 32 KiB apart again wherever the block size allows it.
+inline int32_t slab_tiles_log2(int32_t G, int32_t d, int32_t slice_tokens) {
+  const int32_t gg = kv_head_group(G, d);
+  int32_t lg = 0;
+  while ((int64_t)(2 << lg) * gg * d <= 1024 && (slice_tokens >> 4) % (2 << lg) == 0) ++lg;
+  return lg;
+}
+
 inline int32_t block_class(int64_t id, int64_t resident, int64_t chunk) {
   return id < resident ? 0 : 1 + (int32_t)((id - resident) / chunk);
 }

@@ -13,7 +13,8 @@ struct PoolShape {
   int32_t paged;           // 1: block table lookup, 0: sequence b owns slice b
   int32_t log2_T;          // paged: log2(block tokens)
   int32_t tcap;            // tokens per pool slice: T (paged) or max_ctx (contiguous); a multiple of 16
-  int32_t gg;              // KV heads per group inside a 16-token tile slab (divides G)
+  int32_t gg;              // KV heads per group inside a slab (divides G)
+  int32_t st_log2;         // log2 of the 16-token tiles per slab (okv_host.h: slab_tiles); tcap / 16 is a multiple
   int32_t max_blocks;      // paged: columns of the block table
 };
 
@@ -121,6 +122,7 @@ struct TailLaunch {
   const int32_t *block_table, *ctx_lens, *tail_from;
   int64_t block_elems, layer_stride;
   int32_t B, n_layers, max_blocks, log2_T, D;
+  int32_t gg, st_log2;           // of the pools' layout (PoolShape)
   int32_t id_lo, id_hi;
   int32_t mode;
 };

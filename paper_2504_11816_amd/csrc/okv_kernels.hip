@@ -39,33 +39,40 @@ constexpr int kWavesPerBlock = OKV_WAVES_PER_BLOCK;   // independent work items 
 constexpr float kNegBig = -1.0e30f;   // "no key seen yet"; finite so that differences stay finite
 constexpr int kItemLast = 1, kItemWhole = 2;   // flags of a work item (item_desc.w)
 
-// Where the rows of a 16-token tile live.  A pool is a sequence of tile slabs: the K and V rows of 16
-// consecutive tokens for every KV head, 2 * G * 16 * D elements.  Block blk of a paged pool is the
-// tcap / 16 slabs from blk * (tcap / 16) on; sequence b of a contiguous pool owns the tcap / 16 slabs
-// from b * (tcap / 16) on.  Inside a slab the KV heads come in groups of gg: the K rows of the group's
-// heads (16 * D elements each), then their V rows.
+// Where the rows of a 16-token tile live.  A pool is a sequence of slabs: the K and V rows of 16 * St
+// consecutive tokens for every KV head, 2 * G * 16 * St * D elements.  Block blk of a paged pool is the
+// tcap / (16 St) slabs from blk * (tcap / (16 St)) on; sequence b of a contiguous pool owns as many from
+// b * (tcap / (16 St)) on.  Inside a slab the KV heads come in groups of gg: the K rows of the group (for each
+// of the slab's St tiles in turn, the 16 * D elements of each of its heads), then its V rows likewise.
+// St = 1 << st_log2 is 1 when a group's K rows of one tile already fill 32 KiB.
 struct TileAddr {
   int64_t slab_elems;    // elements of one slab
-  int64_t head_k;        // offset of this KV head's K rows inside a slab
+  int64_t head_k;        // offset of this KV head's K rows of the slab's first tile inside a slab
   int64_t head_v;        // and of its V rows
-  int32_t tiles;         // slabs per block (paged) or per sequence (contiguous)
+  int32_t tile_stride;   // elements between a head's rows of one tile of a slab and of the next
+  int32_t tiles;         // 16-token tiles per block (paged) or per sequence (contiguous): a multiple of St
+  int32_t st_log2;
 };
 
 template <int D>
-__device__ __forceinline__ TileAddr tile_addr(int G, int gg, int tcap, int g) {
+__device__ __forceinline__ TileAddr tile_addr(int G, int gg, int tcap, int st_log2, int g) {
   TileAddr t;
-  t.slab_elems = (int64_t)2 * G * 16 * D;
+  t.slab_elems = ((int64_t)2 * G * 16 * D) << st_log2;
+  t.tile_stride = gg * (16 * D);
   const int grp = g / gg;
-  t.head_k = ((int64_t)grp * 2 * gg + (g - grp * gg)) * (16 * D);
-  t.head_v = t.head_k + (int64_t)gg * (16 * D);
+  t.head_k = (((int64_t)grp * 2 * gg) << st_log2) * (16 * D) + (int64_t)(g - grp * gg) * (16 * D);
+  t.head_v = t.head_k + ((int64_t)t.tile_stride << st_log2);
   t.tiles = tcap >> 4;
+  t.st_log2 = st_log2;
   return t;
 }
 
-// First element of the slab of 16-token tile `tile` in pool slice `blk` (a block, or a sequence's slice).
+// First element of 16-token tile `tile` of pool slice `blk` (a block, or a sequence's slice), before the
+// head's offset: the slab the tile lies in, and the tile's place among the slab's St.
 template <bool PAGED>
 __device__ __forceinline__ int64_t slab_base(const TileAddr &t, int blk, int tile) {
-  return ((int64_t)blk * t.tiles + (PAGED ? tile & (t.tiles - 1) : tile)) * t.slab_elems;
+  const int64_t lin = (int64_t)blk * t.tiles + (PAGED ? tile & (t.tiles - 1) : tile);
+  return (lin >> t.st_log2) * t.slab_elems + (int64_t)((int)lin & ((1 << t.st_log2) - 1)) * t.tile_stride;
 }
 
 template <int LPT>
@@ -90,7 +97,8 @@ struct AttnArgs {
   const int32_t *n_groups_dev;     // NULL, or where the number of groups is to be read (n_groups is then ignored)
   int32_t n_groups;
   int32_t H, G, log2_T, tcap, max_blocks, out_fp32;
-  int32_t gg;                      // KV heads per group inside a tile slab
+  int32_t gg;                      // KV heads per group inside a slab
+  int32_t st_log2;                 // log2 of the 16-token tiles per slab
   int32_t item_first;              // the launch's first item in item_desc (and in the partial slots)
   int32_t id_base;                 // `pool` holds the blocks with ids id_base, id_base + 1, ...
   int32_t mirror_shift;            // id_base minus the id of the first block of pool_mirror
@@ -295,7 +303,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(co
   bool has_next = true;                                  // N is a unit (else the wavefront's share is done)
   Unit<PIPE> N, C;                                       // the unit whose first tiles are asked for next; the one being reduced
   bool live = false;                                     // C holds a unit whose results are still to be written
-  TileAddr ta = tile_addr<D>(a.G, a.gg, a.tcap, 0);
+  TileAddr ta = tile_addr<D>(a.G, a.gg, a.tcap, a.st_log2, 0);
   Tile<LPT> buf[PIPE];
   uint4 q_next[D / 32];                                  // q of N: the B operand of the score product, lane (quarter, rho) holds
                                                          // head rho, dims 32 c + 8 quarter .. + 7; columns past the group's heads are zero
@@ -316,7 +324,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(co
       for (int i = 0; i < PIPE; ++i) N.blk0[i] = blk_of(N.b, min((N.lo >> 4) + i, (N.hi - 1) >> 4));
     }
     // [A] the next unit's first tiles and its q
-    const TileAddr ta_next = tile_addr<D>(a.G, a.gg, a.tcap, N.g);
+    const TileAddr ta_next = tile_addr<D>(a.G, a.gg, a.tcap, a.st_log2, N.g);
     if (has_next) {
 #pragma unroll
       for (int i = 0; i < PIPE; ++i) load_tile(buf[i], ta_next, min((N.lo >> 4) + i, (N.hi - 1) >> 4), N.blk0[i]);
@@ -588,6 +596,7 @@ AttnArgs make_args(const AttnLaunch &a) {
   args.log2_T = s.log2_T;
   args.tcap = s.tcap;
   args.gg = s.gg;
+  args.st_log2 = s.st_log2;
   args.max_blocks = s.max_blocks;
   args.out_fp32 = a.out_fp32;
   args.item_first = a.item_first;
@@ -832,7 +841,7 @@ struct BulkArgs {
   uint16_t *pool;
   const int4 *tiles;
   const int32_t *row_base;
-  int32_t G, gg, tcap, n_units;
+  int32_t G, gg, tcap, st_log2, n_units;
   int32_t drain_each_tile;   // wait for a tile's stores before starting the next one
 };
 
@@ -850,7 +859,7 @@ __global__ __launch_bounds__(256) void bulk_append_kernel(const BulkArgs a) {
     const int b = tile.x, pos0 = tile.y << 4;
     const int first = tile.z & 0xff, last = tile.z >> 8;      // slots of the tile to store: [first, last)
     const int blk = tile.w;
-    const TileAddr ta = tile_addr<D>(a.G, a.gg, a.tcap, g);
+    const TileAddr ta = tile_addr<D>(a.G, a.gg, a.tcap, a.st_log2, g);
     const uint16_t *src = (kv ? a.v_rows : a.k_rows) + (size_t)g * D + col * 8;
     uint16_t *dst = a.pool + slab_base<PAGED>(ta, blk, tile.y) + (kv ? ta.head_v : ta.head_k) + col * 8;
     const int64_t base_row = (int64_t)a.row_base[b] + pos0;
@@ -891,6 +900,7 @@ struct TailArgs {
   const int32_t *block_table, *ctx_lens, *tail_from;
   int64_t block_elems, layer_stride; // numbers per block; numbers between two layers' slots
   int32_t max_blocks, log2_T, d8;    // d8 = 16-byte pieces per row
+  int32_t gg, st_log2;               // KV heads per group and log2 of the tiles per slab (see TileAddr)
   int32_t id_lo, id_hi;
   int32_t mode;                      // 0: blocks j and j - 1 of the newest position, rows before it, into the staged chunk
                                      // 1: the block that this step filled, to the host pool
@@ -924,11 +934,11 @@ __global__ __launch_bounds__(256) void tail_rows_kernel(TailArgs a) {
   uint4 *dst = reinterpret_cast<uint4 *>(dst_pool + (int64_t)(id - a.id_lo) * a.block_elems);
   const int lo_in = lo - (j << a.log2_T), hi_in = hi - (j << a.log2_T);
   const int pieces = (int)(a.block_elems >> 3);
-  const int slab_pieces = pieces >> (a.log2_T - 4);
+  const int slab_pieces = pieces >> (a.log2_T - 4 - a.st_log2);
   for (int p = blockIdx.x * blockDim.x + threadIdx.x; p < pieces; p += gridDim.x * blockDim.x) {
     const int slab = p / slab_pieces;
-    const int slot = ((p - slab * slab_pieces) / a.d8) & 15;
-    const int pos = slab * 16 + slot;
+    const int row = (p - slab * slab_pieces) / a.d8;                  // ((group, kv), tile in slab, head in group, slot)
+    const int pos = (((slab << a.st_log2) + ((row / (16 * a.gg)) & ((1 << a.st_log2) - 1))) << 4) + (row & 15);
     if (pos >= lo_in && pos < hi_in) dst[p] = src[p];
   }
 }
@@ -993,6 +1003,7 @@ hipError_t launch_bulk_append(const BulkLaunch &a, hipStream_t stream) {
   args.row_base = a.row_base;
   args.G = s.G;
   args.gg = s.gg;
+  args.st_log2 = s.st_log2;
   args.tcap = s.tcap;
   const int64_t units = (int64_t)a.n_tiles * 2 * s.G;
   if (units > 0x7fffffff) return hipErrorInvalidValue;
@@ -1028,6 +1039,8 @@ hipError_t launch_tail_rows(const TailLaunch &t, hipStream_t stream) {
   a.max_blocks = t.max_blocks;
   a.log2_T = t.log2_T;
   a.d8 = t.D / 8;
+  a.gg = t.gg;
+  a.st_log2 = t.st_log2;
   a.id_lo = t.id_lo;
   a.id_hi = t.id_hi;
   a.mode = t.mode;

@@ -103,7 +103,10 @@ class Stack:
             self.max_ctx = 0
         else:
             self.max_blocks = 0
-            self.max_ctx = (cap_tokens + 15) // 16 * 16
+            # a multiple of the tokens of a full slab (16 with 8 or more KV heads at d = 128), so that the layout
+            # can keep a head's K and V tiles 32 KiB apart
+            unit = 16 * binding.okv_slab_tiles(G, d, 1 << 20)
+            self.max_ctx = (cap_tokens + unit - 1) // unit * unit
             self.cap_tokens = self.max_ctx
             self.blocks_per_layer = 0
         shape = binding.make_config(n_layers=L, n_q_heads=H, n_kv_heads=G, head_dim=d, block_tokens=T,

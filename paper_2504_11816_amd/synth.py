@@ -187,4 +187,12 @@ WORKLOADS = {
                  note="GQA 64/8, context 2048, paged, resident"),
     "gqa16": dict(L=32, H=128, G=8, d=128, B=128, ctx=2048, steps=20, T=16, c_off=(0, 1), ragged=None,
                   note="GQA 128/8, context 2048, paged, resident"),
+    # fewer than 8 KV heads (a model's KV heads divided over several GPUs), again 1 GiB of KV per layer; blocks
+    # of 64 tokens, which the pool layout needs to keep a head's K and V tiles 32 KiB apart
+    "kv8": dict(L=8, H=32, G=8, d=128, B=128, ctx=2048, steps=8, T=64, c_off=(0, 1), ragged=None,
+                note="32 query / 8 KV heads, context 2048, 64-token blocks, resident"),
+    "kv4": dict(L=8, H=32, G=4, d=128, B=256, ctx=2048, steps=8, T=64, c_off=(0, 1), ragged=None,
+                note="32 query / 4 KV heads, context 2048, 64-token blocks, resident"),
+    "kv2": dict(L=8, H=32, G=2, d=128, B=512, ctx=2048, steps=8, T=64, c_off=(0, 1), ragged=None,
+                note="32 query / 2 KV heads, context 2048, 64-token blocks, resident"),
 }

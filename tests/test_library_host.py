@@ -212,6 +212,14 @@ def test_size_queries_and_shape_errors():
         for d in (64, 128):
             assert binding.okv_kv_head_group(G, d) == kv_layout.head_group(G, d)
     assert binding.okv_kv_head_group(32, 128) == 8 and binding.okv_kv_head_group(32, 64) == 16
+    # 16-token tiles per slab: the same for the oracle's statement of the rule
+    for G in (1, 2, 3, 4, 6, 8, 12, 16, 32, 40):
+        for d in (64, 128):
+            for tokens in (16, 32, 48, 64, 80, 96, 128, 256, 1024, 4096, 4112):
+                assert binding.okv_slab_tiles(G, d, tokens) == kv_layout.slab_tiles(G, d, tokens), (G, d, tokens)
+    assert binding.okv_slab_tiles(32, 128, 4096) == 1 and binding.okv_slab_tiles(4, 128, 64) == 2 and binding.okv_slab_tiles(1, 128, 16) == 1
+    with pytest.raises(binding.OkvError):
+        binding.okv_slab_tiles(8, 128, 24)
     with pytest.raises(binding.OkvError):
         binding.okv_kv_head_group(8, 96)
     # 16 blocks of 16 tokens at the default split of 512 -> 1 item, plus one per chunk of the host pool (5)

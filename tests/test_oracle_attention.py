@@ -314,28 +314,48 @@ def test_append_scatter_then_attend_sees_the_new_token():
 def test_layout_offsets_address_probe():
     # Every (coordinate) -> offset map is a bijection onto the pool and row
     # major in the stated order: number the elements of a pool shaped as the
-    # description reads ([slabs][group][kv][head in group][slot][d]) and look
-    # every row up.
-    for G, d, Gg in ((16, 128, 8), (32, 64, 16), (3, 64, 3), (12, 128, 6)):
+    # description reads ([slabs][group][kv][tile in slab][head in group][slot][d])
+    # and look every row up.  St (tiles per slab) is written out per case from the rule's
+    # wording: the largest power of two with St * Gg * d <= 1024 that divides the slice's tiles.
+    for G, d, Gg, T, St_T, C, St_C in ((16, 128, 8, 32, 1, 48, 1), (32, 64, 16, 32, 1, 48, 1), (3, 64, 3, 32, 2, 48, 1),
+                                       (12, 128, 6, 32, 1, 48, 1), (4, 128, 4, 32, 2, 64, 2), (2, 128, 2, 64, 4, 96, 2),
+                                       (1, 128, 1, 128, 8, 128, 8), (1, 64, 1, 256, 16, 16, 1), (4, 128, 4, 16, 1, 32, 2),
+                                       (8, 64, 8, 64, 2, 80, 1)):
         assert kv_layout.head_group(G, d) == Gg
-        T, nblk = 32, 3
-        ref = np.arange(nblk * (T // 16) * 2 * G * 16 * d).reshape(nblk, T // 16, G // Gg, 2, Gg, 16, d)
+        assert kv_layout.slab_tiles(G, d, T) == St_T and kv_layout.slab_tiles(G, d, C) == St_C
+        nblk, St = 3, St_T
+        ref = np.arange(nblk * T * 2 * G * d).reshape(nblk, T // (16 * St), G // Gg, 2, St, Gg, 16, d)
         seen = set()
         for blk in range(nblk):
             for kv in range(2):
                 for g in range(G):
                     for s in range(T):
                         off = kv_layout.paged_row_offset(blk, kv, g, s, G, T, d)
-                        assert off == ref[blk, s // 16, g // Gg, kv, g % Gg, s % 16, 0]
+                        assert off == ref[blk, s // (16 * St), g // Gg, kv, (s // 16) % St, g % Gg, s % 16, 0]
                         seen.add(off)
         assert len(seen) == nblk * 2 * G * T and max(seen) == ref.size - d
-        B, C = 3, 48
-        ref = np.arange(B * (C // 16) * 2 * G * 16 * d).reshape(B, C // 16, G // Gg, 2, Gg, 16, d)
+        B, St = 3, St_C
+        ref = np.arange(B * C * 2 * G * d).reshape(B, C // (16 * St), G // Gg, 2, St, Gg, 16, d)
         for b in range(B):
             for kv in range(2):
                 for g in range(G):
                     for t in range(C):
-                        assert kv_layout.contiguous_row_offset(b, kv, g, t, G, C, d) == ref[b, t // 16, g // Gg, kv, g % Gg, t % 16, 0]
+                        assert kv_layout.contiguous_row_offset(b, kv, g, t, G, C, d) == \
+                            ref[b, t // (16 * St), g // Gg, kv, (t // 16) % St, g % Gg, t % 16, 0]
+
+
+def test_slab_tiles_rule_puts_k_and_v_of_a_tile_32_kib_apart_where_the_slice_allows():
+    # distance between a head's K rows and its V rows of the same tile = St * Gg * 16 * d * 2 bytes
+    for G, d, slice_tokens, apart in ((32, 128, 16, 32768), (8, 128, 16, 32768), (4, 128, 16, 16384), (4, 128, 32, 32768),
+                                      (4, 128, 4096, 32768), (2, 128, 64, 32768), (2, 128, 32, 16384), (1, 128, 128, 32768),
+                                      (1, 128, 1024, 32768), (1, 128, 48, 4096), (8, 64, 32, 32768), (16, 64, 16, 32768),
+                                      (12, 128, 64, 24576), (3, 64, 64, 24576)):
+        St, Gg = kv_layout.slab_tiles(G, d, slice_tokens), kv_layout.head_group(G, d)
+        assert St * Gg * 16 * d * 2 == apart, (G, d, slice_tokens)
+        assert (slice_tokens // 16) % St == 0 and St & (St - 1) == 0
+        k0 = kv_layout.paged_row_offset(0, 0, 0, 0, G, slice_tokens, d)
+        v0 = kv_layout.paged_row_offset(0, 1, 0, 0, G, slice_tokens, d)
+        assert (v0 - k0) * 2 == apart
 
 
 def test_head_group_rule():
