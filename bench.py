@@ -38,8 +38,8 @@ PCIE5_X16_GBPS = 64.0       # nominal, one direction
 # has changed since, `traffic` is reported as null.
 TRAFFIC_RECORD = {
     "workload": "cfg2",
-    "kernel_sha256": "e608ec559966436867b3c94a053fc4d0a1cb87752d42a40bbf0ac8afc6b120d4",
-    "fetch_kib": 141752.5, "fetch_scale": 1.9999, "algorithmic_bytes": 285474816,   # context 513..576
+    "kernel_sha256": "72e438ed2577a739f04c6c21d4c27bdbdfe4ebb2d6007fb540e7e9630d907133",
+    "fetch_kib": 141754.5, "fetch_scale": 1.9999, "algorithmic_bytes": 285474816,   # context 513..576
     "write_kib": 768.0, "write_scale": 1.0000,
 }
 
