@@ -297,7 +297,10 @@ hipError_t own_queue_stream(hipStream_t *out) {
   if (e == hipSuccess) e = hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
   if (e != hipSuccess) return e;
   std::vector<uint32_t> mask((size_t)(std::max(cus, 1) + 31) / 32, 0xFFFFFFFFu);
-  return hipExtStreamCreateWithCUMask(out, (uint32_t)mask.size(), mask.data());
+  e = hipExtStreamCreateWithCUMask(out, (uint32_t)mask.size(), mask.data());
+  if (e == hipSuccess) return e;
+  (void)hipGetLastError();                               // an ordinary stream still works, it may only share a queue
+  return hipStreamCreateWithFlags(out, hipStreamNonBlocking);
 }
 
 // The host's lead over the compute stream, in steps (OKV_STEPS_AHEAD): the step about to be enqueued may
