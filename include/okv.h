@@ -86,7 +86,9 @@ typedef struct okv_config {
   int32_t out_dtype;           /* 0 = fp16 (round to nearest even), 1 = fp32                 */
   int32_t split_tokens;        /* upper bound on the keys of one split-K work item (a sequence
                                   of n keys is cut into ceil(n / split_tokens) equal pieces,
-                                  rounded up to multiples of 16); 0 lets the library choose  */
+                                  rounded up to multiples of 16); 0 lets the library share the
+                                  keys of every launch out in equal stretches over its
+                                  wavefronts (okv_equal_stretches), which is what to use      */
   void  **dev_pool;            /* HOST array [L] of DEVICE pointers: the pool of each layer
                                   that stays in HBM, NULL for a layer kept on the host       */
   void  **host_pool;           /* HOST array [L] of HOST pointers to PINNED, device-mapped
@@ -462,7 +464,8 @@ int okv_synchronize(okv_ctx *ctx);
  * is too small for it. */
 int okv_set_split_tokens(okv_ctx *ctx, int32_t split_tokens);
 
-/* The split size in use (after the last okv_step_begin / okv_set_batch). */
+/* The split size in use (after the last okv_step_begin / okv_set_batch); when the library shares the
+ * keys out in equal stretches (no split size given), the length of a stretch in keys. */
 int32_t okv_get_split_tokens(const okv_ctx *ctx);
 
 /* Copies the device-side sequence lengths back.  out: HOST int32 [B].  Synchronous. */
