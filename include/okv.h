@@ -173,6 +173,21 @@ int64_t okv_workspace_bytes(const okv_config *cfg);
  * cfg->chunk_blocks == 0; < 0 on a bad cfg.  Only the shape fields are read. */
 int64_t okv_tail_bytes(const okv_config *cfg);
 
+/* What keeping the newest blocks in HBM (cfg->tail_blocks) asks of a decode step, as a pure host
+ * function (the context runs the same code; tests replay it against a model of the pools).
+ * ctx_lens_after[b] = keys sequence b holds once the step's row is stored; tail_from[b] = the length
+ * it had when the batch was described (okv_set_batch, okv_prefill_end, okv_flush_tails).
+ *   patch_chunk[c] (HOST, [n_chunks]) = 1 if, before chunk c of the host pool (blocks resident_blocks +
+ *     c * chunk_blocks ..) is attended in this step, rows have to be copied into its staged copy from the
+ *     slots: the newest block of some sequence, or the one before it, lies in the chunk and holds a
+ *     position >= tail_from[b];
+ *   fills_block[b] (HOST, [B]) = 1 if the step fills a block of sequence b that belongs to the host pool
+ *     and holds such positions: the block is written to the host pool after the step.
+ * OKV_EINVAL on NULL pointers, a block size that is not a power of two >= 16, or lengths outside the table. */
+int okv_tail_plan(int32_t B, const int32_t *block_table, int32_t max_blocks_per_seq, int32_t block_tokens,
+                  const int32_t *ctx_lens_after, const int32_t *tail_from, int64_t resident_blocks, int64_t chunk_blocks,
+                  int32_t n_chunks, uint8_t *patch_chunk, uint8_t *fills_block);
+
 /* ---- offload plan (pure host functions, no GPU, no context) ------------------- */
 
 /* Which layers live on the host for an offload ratio C_off = coff_num / coff_den

@@ -15,6 +15,7 @@ Modules
   kv_bytes      the paper's size / flop / transfer-time formulas
   worklist      the tiling a split-K work list has to satisfy
   pipeline_sim  replay of a copy/attend op trace on a fake copy engine
+  tail_sim      replay of "newest blocks stay in HBM" on sets of row positions
 
 Every function here is pinned by a CPU test (tests/test_oracle_*.py) to a
 closed form, an invariant, a library routine on a special case or brute

@@ -16,7 +16,7 @@ _CODE_NAMES = {0: "OKV_OK", -1: "OKV_EINVAL", -2: "OKV_ENOSPC", -3: "OKV_ESTATE"
 
 # every symbol include/okv.h declares
 EXPORTS = [
-    "okv_layer_pool_bytes", "okv_block_bytes", "okv_kv_head_group", "okv_slab_tiles", "okv_workspace_bytes", "okv_tail_bytes", "kv_offload_plan", "okv_plan_from_bytes",
+    "okv_layer_pool_bytes", "okv_block_bytes", "okv_kv_head_group", "okv_slab_tiles", "okv_workspace_bytes", "okv_tail_bytes", "okv_tail_plan", "kv_offload_plan", "okv_plan_from_bytes",
     "okv_plan_block_split", "okv_schedule_trace", "okv_create", "okv_destroy", "okv_last_error", "okv_set_batch",
     "okv_step_begin", "okv_step_end", "okv_step_abort", "okv_flush_tails", "kv_append", "decode_attn", "okv_decode_step", "okv_synchronize",
     "okv_set_split_tokens", "okv_get_split_tokens", "okv_get_ctx_lens", "okv_worklist",
@@ -95,6 +95,7 @@ def lib():
             "okv_slab_tiles": (I32, [I32, I32, I32]),
             "okv_workspace_bytes": (I64, [cfgp]),
             "okv_tail_bytes": (I64, [cfgp]),
+            "okv_tail_plan": (ctypes.c_int, [I32, P, I32, I32, P, P, I64, I64, I32, P, P]),
             "okv_plan_block_split": (ctypes.c_int, [I64, I64, I64, ctypes.POINTER(I64), ctypes.POINTER(I64)]),
             "okv_worklist_classes": (ctypes.c_int, [P, I32, P, I32, ctypes.POINTER(I32)]),
             "kv_offload_plan": (ctypes.c_int, [I32, I64, I64, P, ctypes.POINTER(I32)]),
@@ -269,6 +270,19 @@ def okv_workspace_bytes(cfg):
     if r < 0:
         _check(int(r))
     return int(r)
+
+
+def okv_tail_plan(block_table, block_tokens, ctx_lens_after, tail_from, resident_blocks, chunk_blocks, n_chunks):
+    """(patch_chunk [n_chunks], fills_block [B]) as uint8 arrays."""
+    table = np.ascontiguousarray(block_table, dtype=np.int32)
+    n = np.ascontiguousarray(ctx_lens_after, dtype=np.int32)
+    t0 = np.ascontiguousarray(tail_from, dtype=np.int32)
+    B = len(n)
+    patch = np.zeros(max(n_chunks, 1), dtype=np.uint8)
+    fills = np.zeros(B, dtype=np.uint8)
+    _check(lib().okv_tail_plan(B, _ptr(table), table.shape[1], block_tokens, _ptr(n), _ptr(t0), resident_blocks, chunk_blocks,
+                               n_chunks, _ptr(patch), _ptr(fills)))
+    return patch[:n_chunks], fills
 
 
 def okv_tail_bytes(cfg):

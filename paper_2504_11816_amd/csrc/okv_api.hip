@@ -368,20 +368,12 @@ int tail_flush_all(okv_ctx *ctx) {
 
 // Chunks in which some sequence's newest or second-newest block lies at the lengths the host holds.
 void tail_mark_chunks(okv_ctx *ctx) {
-  ctx->patch_chunk.assign(ctx->active_chunks.size(), 0);
   const okv::PoolShape &s = ctx->shape;
-  for (int32_t b = 0; b < ctx->B; ++b) {
-    const int32_t n = ctx->h_ctx_lens[b];
-    const int32_t jn = (n - 1) >> s.log2_T;
-    for (int32_t j = std::max(0, jn - 1); j <= jn; ++j) {
-      if (((j + 1) << s.log2_T) <= ctx->h_tail_from[b]) continue;          // all of it was in the pool from the start
-      const int64_t id = ctx->h_block_table[(size_t)b * s.max_blocks + j];
-      if (id < ctx->resident_blocks) continue;
-      const int32_t chunk = (int32_t)((id - ctx->resident_blocks) / ctx->chunk_blocks);
-      for (size_t u = 0; u < ctx->active_chunks.size(); ++u)
-        if (ctx->active_chunks[u] == chunk) ctx->patch_chunk[u] = 1;
-    }
-  }
+  std::vector<uint8_t> by_chunk((size_t)std::max(0, ctx->n_cls - 1), 0);
+  okv::tail_patch_chunks(ctx->h_block_table.data(), ctx->B, s.max_blocks, s.log2_T, ctx->h_ctx_lens.data(),
+                         ctx->h_tail_from.data(), ctx->resident_blocks, ctx->chunk_blocks, by_chunk);
+  ctx->patch_chunk.assign(ctx->active_chunks.size(), 0);
+  for (size_t u = 0; u < ctx->active_chunks.size(); ++u) ctx->patch_chunk[u] = by_chunk[(size_t)ctx->active_chunks[u]];
 }
 
 int exec_op(okv_ctx *ctx, const Op &op, const void *a0, const void *a1, void *out) {
@@ -612,6 +604,28 @@ int64_t okv_tail_bytes(const okv_config *cfg) {
   if (const char *why = shape_problem(cfg)) return fail(nullptr, OKV_EINVAL, "%s", why);
   if (cfg->chunk_blocks <= 0) return 0;
   return (int64_t)cfg->n_layers * 2 * cfg->max_batch * block_bytes_of(cfg);
+}
+
+int okv_tail_plan(int32_t B, const int32_t *block_table, int32_t max_blocks_per_seq, int32_t block_tokens,
+                  const int32_t *ctx_lens_after, const int32_t *tail_from, int64_t resident_blocks, int64_t chunk_blocks,
+                  int32_t n_chunks, uint8_t *patch_chunk, uint8_t *fills_block) {
+  if (B < 1 || !block_table || !ctx_lens_after || !tail_from || !patch_chunk || !fills_block)
+    return fail(nullptr, OKV_EINVAL, "okv_tail_plan: NULL argument or B < 1");
+  if (max_blocks_per_seq < 1 || block_tokens < 16 || (block_tokens & (block_tokens - 1)) || resident_blocks < 0 || chunk_blocks < 1 ||
+      n_chunks < 0)
+    return fail(nullptr, OKV_EINVAL, "okv_tail_plan: bad shape");
+  int32_t log2_T = 0;
+  while ((1 << log2_T) < block_tokens) ++log2_T;
+  for (int32_t b = 0; b < B; ++b)
+    if (ctx_lens_after[b] < 1 || ctx_lens_after[b] > (int64_t)max_blocks_per_seq * block_tokens || tail_from[b] < 0)
+      return fail(nullptr, OKV_EINVAL, "okv_tail_plan: sequence %d: length %d outside [1, %lld] or tail_from < 0", b, ctx_lens_after[b],
+                  (long long)max_blocks_per_seq * block_tokens);
+  std::vector<uint8_t> patch((size_t)n_chunks, 0);
+  okv::tail_patch_chunks(block_table, B, max_blocks_per_seq, log2_T, ctx_lens_after, tail_from, resident_blocks, chunk_blocks, patch);
+  for (int32_t c = 0; c < n_chunks; ++c) patch_chunk[c] = patch[(size_t)c];
+  for (int32_t b = 0; b < B; ++b)
+    fills_block[b] = okv::tail_fills(block_table, b, max_blocks_per_seq, log2_T, ctx_lens_after[b], tail_from[b], resident_blocks);
+  return OKV_OK;
 }
 
 int kv_offload_plan(int32_t n_layers, int64_t coff_num, int64_t coff_den, uint8_t *on_host, int32_t *n_off) {
@@ -1100,11 +1114,9 @@ int okv_step_end(okv_ctx *ctx) {
   if (ctx->tail_on) {
     const okv::PoolShape &s = ctx->shape;
     bool filled = false;
-    for (int32_t b = 0; b < ctx->B && !filled; ++b) {
-      const int32_t n = ctx->h_ctx_lens[b];
-      if ((n & (ctx->cfg.block_tokens - 1)) || ctx->h_tail_from[b] >= n) continue;
-      filled = ctx->h_block_table[(size_t)b * s.max_blocks + (n >> s.log2_T) - 1] >= ctx->resident_blocks;
-    }
+    for (int32_t b = 0; b < ctx->B && !filled; ++b)
+      filled = okv::tail_fills(ctx->h_block_table.data(), b, s.max_blocks, s.log2_T, ctx->h_ctx_lens[b], ctx->h_tail_from[b],
+                               ctx->resident_blocks);
     if (filled) {
       // after every layer's attention of this step (same stream); copies of the host pools enqueued
       // from now on wait for it, those already enqueued are made good from the slots

@@ -272,4 +272,34 @@ __host__ __device__ inline int32_t run_items(int32_t lo, int32_t hi_cap, int32_t
   return cnt;
 }
 
+// ---- the newest blocks kept in HBM (block-granular offload) ----------------------------------------
+//
+// Rows appended to a block of the host pool stay in a slot in HBM until the block is full.  For a step
+// after which sequence b holds n[b] keys (from[b] = the length it had when the batch was described:
+// rows before that are in the pools already):
+//   tail_patch_chunks: host chunk c (blocks resident + c * chunk .. ) gets patch[c] = 1 if the newest
+//     block of some sequence (that of position n[b] - 1) or the one before it lies in the chunk and holds
+//     a position >= from[b]: before the chunk is attended those rows are copied into it from the slots;
+//   tail_fills: the step fills a block of sequence b that belongs to the host pool and holds rows from
+//     from[b] on: after the step the block is written out.
+inline void tail_patch_chunks(const int32_t *table, int32_t B, int32_t max_blocks, int32_t log2_T, const int32_t *n,
+                              const int32_t *from, int64_t resident, int64_t chunk, std::vector<uint8_t> &patch) {
+  for (int32_t b = 0; b < B; ++b) {
+    const int32_t jn = (n[b] - 1) >> log2_T;
+    for (int32_t j = jn > 0 ? jn - 1 : 0; j <= jn; ++j) {
+      if (((j + 1) << log2_T) <= from[b]) continue;          // all of it was in the pool from the start
+      const int64_t id = table[(size_t)b * max_blocks + j];
+      if (id < resident) continue;
+      const int64_t c = (id - resident) / chunk;
+      if (c < (int64_t)patch.size()) patch[(size_t)c] = 1;
+    }
+  }
+}
+
+inline bool tail_fills(const int32_t *table, int32_t b, int32_t max_blocks, int32_t log2_T, int32_t n, int32_t from,
+                       int64_t resident) {
+  if (n <= 0 || (n & ((1 << log2_T) - 1)) || from >= n) return false;
+  return table[(size_t)b * max_blocks + (n >> log2_T) - 1] >= resident;
+}
+
 }  // namespace okv

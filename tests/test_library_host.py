@@ -276,3 +276,33 @@ def test_static_entry_point_rejects_bad_arguments_without_a_gpu():
         with pytest.raises(binding.OkvError) as e:
             binding.okv_decode_attn_static(**kw)
         assert e.value.code == code, bad
+
+
+def test_tail_plan_matches_the_oracle_and_serves_every_chunk_in_the_model():
+    # which chunks get rows from the slots and which blocks are written out, per step: the library's host code
+    # against the rule as oracle/tail_sim.py states it, then the library's decisions drive the model of the pools
+    from oracle import tail_sim
+    from paper_2504_11816_amd import synth
+    rng = np.random.default_rng(7)
+    for seed, policy in enumerate(("prefix", "sequence", "scatter", "scatter", "sequence")):
+        T, B, cap, chunk = (16, 32)[seed % 2], 6, 192, 3
+        need = B * (cap // T)
+        n_host = need * 3 // 5
+        resident = need - n_host + 1
+        table = synth.classed_block_table([cap] * B, T, resident, n_host + 2, n_host, policy, 40 + seed, max_blocks_per_seq=cap // T)
+        n_chunks = -(-(n_host + 2) // chunk)
+        ctx = rng.integers(0, cap - 80, size=B).astype(np.int32)
+
+        def lib_plan(n, t0):
+            patch, fills = binding.okv_tail_plan(table, T, n, t0, resident, chunk, n_chunks)
+            want_patch, want_fills = tail_sim.expected_plan(table, T, n, t0, resident, chunk, n_chunks)
+            np.testing.assert_array_equal(patch, want_patch)
+            np.testing.assert_array_equal(fills, want_fills)
+            return patch, fills
+
+        for lag in (0, 1):
+            tail_sim.replay(table, T, ctx, resident, chunk, n_chunks, 75, lib_plan, lag)
+    with pytest.raises(binding.OkvError):
+        binding.okv_tail_plan(table, 24, ctx + 1, ctx, resident, chunk, n_chunks)
+    with pytest.raises(binding.OkvError):
+        binding.okv_tail_plan(table, T, ctx * 0, ctx, resident, chunk, n_chunks)
