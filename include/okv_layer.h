@@ -24,8 +24,9 @@
 extern "C" {
 #endif
 
-#define OKV_LINEAR_MAX_ROWS 128     /* rows that one launch of the product kernels takes                    */
-#define OKV_LINEAR_MAX_BATCH 4096   /* rows per call: beyond OKV_LINEAR_MAX_ROWS a call issues several launches */
+#define OKV_LINEAR_MAX_ROWS 128     /* rows that one launch of the product kernels takes whatever the shape   */
+#define OKV_LINEAR_MAX_ROWS_STAGED 192  /* ... and when n_in is a multiple of 256 and the workspace is there    */
+#define OKV_LINEAR_MAX_BATCH 4096   /* rows per call: beyond that a call issues several launches              */
 
 struct okv_ctx;   /* okv.h */
 
@@ -41,8 +42,10 @@ int okv_pack_linear_weight(void *dst, const void *src, int32_t n_out, int32_t n_
 
 /* out = act(x * W^T + bias) + residual for a batch of m <= OKV_LINEAR_MAX_BATCH rows
  * (paper §IV-D: the linear layers of the decode stage, 2 n_out n_in flops per row).  Up to
- * OKV_LINEAR_MAX_ROWS rows are one launch, in which every weight is read once; more rows are
- * cut into the fewest launches of nearly equal size, each of which reads the weights again.
+ * OKV_LINEAR_MAX_ROWS rows are one launch, in which every weight is read once, and up to
+ * OKV_LINEAR_MAX_ROWS_STAGED when the input width is a multiple of 256 (and the workspace of
+ * okv_linear_workspace_bytes is passed); more rows are cut into the fewest launches of nearly
+ * equal size, each of which reads the weights again.
  *   x         fp16 [m][n_in]
  *   w_packed  fp16, as okv_pack_linear_weight leaves it
  *   bias      fp16 [n_out] or NULL

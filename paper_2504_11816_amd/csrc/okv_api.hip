@@ -1717,19 +1717,31 @@ int device_cus() {
 }  // namespace
 
 namespace {
-// Rows per launch for a batch of m rows: one launch up to OKV_LINEAR_MAX_ROWS, else the fewest launches of
-// (nearly) equal size, a multiple of 16 rows each but the last.
-int32_t rows_per_launch(int32_t m) {
+// Rows per launch for a batch of m rows: the fewest launches of (nearly) equal size, a multiple of 16 rows each
+// but the last.  A launch takes OKV_LINEAR_MAX_ROWS_STAGED rows if the staged kernel takes the shape (with
+// the workspace at hand: unknown = as much as okv_linear_workspace_bytes would ask for), else OKV_LINEAR_MAX_ROWS.
+int32_t rows_per_launch(int32_t m, int32_t n_out, int32_t n_in, bool workspace_known, bool have_workspace, int64_t workspace_bytes) {
   if (m <= OKV_LINEAR_MAX_ROWS) return m;
-  const int32_t launches = (m + OKV_LINEAR_MAX_ROWS - 1) / OKV_LINEAR_MAX_ROWS;
-  return ((m + launches - 1) / launches + 15) / 16 * 16;
+  for (int32_t cap : {OKV_LINEAR_MAX_ROWS_STAGED, OKV_LINEAR_MAX_ROWS}) {
+    const int32_t launches = (m + cap - 1) / cap;
+    const int32_t rows = std::min(m, ((m + launches - 1) / launches + 15) / 16 * 16);
+    const int32_t last = m % rows ? m % rows : rows;
+    if (cap == OKV_LINEAR_MAX_ROWS) return rows;
+    auto takes = [&](int32_t r) {
+      return r <= OKV_LINEAR_MAX_ROWS ||
+             okv::linear_staged_takes(r, n_out, n_in, device_cus(), workspace_known ? have_workspace : true,
+                                      workspace_known ? workspace_bytes : INT64_MAX);
+    };
+    if (takes(rows) && takes(last)) return rows;
+  }
+  return m;
 }
 }  // namespace
 
 int64_t okv_linear_workspace_bytes(int32_t m, int32_t n_out, int32_t n_in) {
   if (m < 1 || m > OKV_LINEAR_MAX_BATCH || n_out < 16 || n_out % 16 || n_in < 32 || n_in % 32)
     return fail(nullptr, OKV_EINVAL, "okv_linear_workspace_bytes: bad shape");
-  const int32_t rows = rows_per_launch(m), last = m % rows ? m % rows : rows;
+  const int32_t rows = rows_per_launch(m, n_out, n_in, false, false, 0), last = m % rows ? m % rows : rows;
   return std::max(okv::linear_workspace_bytes(rows, n_out, n_in, device_cus()), okv::linear_workspace_bytes(last, n_out, n_in, device_cus()));
 }
 
@@ -1763,7 +1775,7 @@ int linear_impl(const void *x, const void *w_packed, const void *bias, const voi
   l.ln_gamma = ln_gamma, l.ln_beta = ln_beta, l.ln_out = ln_out, l.ln_eps = ln_eps;
   // more rows than one launch takes: launches of (nearly) equal size, one after the other on the stream (they
   // share the workspace); each reads the weights again
-  const int32_t rows = rows_per_launch(m);
+  const int32_t rows = rows_per_launch(m, n_out, n_in, true, workspace != nullptr, workspace_bytes);
   const int64_t seg0 = first_cols ? first_cols : n_out / n_seg, seg = n_seg > 1 ? (n_out - seg0) / (n_seg - 1) : n_out;
   auto at = [](const void *p, int64_t halves) -> const void * { return p ? static_cast<const char *>(p) + halves * 2 : nullptr; };
   for (int32_t r0 = 0; r0 < m; r0 += rows) {

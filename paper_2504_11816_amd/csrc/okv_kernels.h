@@ -146,6 +146,7 @@ struct LinearLaunch {
 };
 hipError_t launch_linear(const LinearLaunch &l, hipStream_t stream);
 int64_t linear_workspace_bytes(int32_t m, int32_t n_out, int32_t n_in, int32_t n_cus);
+bool linear_staged_takes(int32_t m, int32_t n_out, int32_t n_in, int32_t n_cus, bool have_workspace, int64_t workspace_bytes);
 hipError_t launch_pack_weight(void *dst, const void *src, int32_t n_out, int32_t n_in, hipStream_t stream);
 hipError_t launch_layernorm(const void *x, const void *gamma, const void *beta, void *out, int32_t m, int32_t h, float eps,
                             hipStream_t stream);

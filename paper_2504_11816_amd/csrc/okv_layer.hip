@@ -36,6 +36,7 @@
 //     of 256), run the simple kernel: a workgroup per 16 features, its wavefronts split the
 //     inputs and add up through LDS, x by gather.
 #include "okv_kernels.h"
+#include "okv_layer.h"
 
 #include <algorithm>
 
@@ -209,12 +210,13 @@ __global__ __launch_bounds__(kLinWaves * 64) void linear_kernel(const LinearArgs
 // launch prefers (3 and no cut for 12288 features on 256 compute units, which saves the kernel that adds up
 // the shares).
 // 32-input blocks per staged chunk of x: 8 (256 inputs), 4 from 112 rows on.  A chunk takes chunk x MF KiB of LDS
-// and there are lead + 1 of them: 128 KiB at most (4 x 32 at 64 and at 128 rows), 144 at 96 rows (3 x 48).
+// and there are lead + 1 of them: 128 KiB at most up to 128 rows (4 x 32 at 64 and at 128 rows), 144 at 96 rows
+// (3 x 48) and from 129 to 192 rows (9 to 12 fragments of 16 rows: 3 x 36 .. 3 x 48).
 constexpr int lin_chunk(int mf) { return mf <= 6 ? 8 : 4; }
 // How many chunks of x the staging wavefronts are ahead of the others (one LDS buffer more than that).  Bounded by
 // LDS and by the counter of loads in flight, which stops at 63: the wait for a chunk leaves the loads of the
 // lead - 1 chunks after it outstanding.
-constexpr int lin_lead(int mf) { return mf == 5 || mf == 6 ? 2 : 3; }
+constexpr int lin_lead(int mf) { return mf == 5 || mf == 6 || mf > 8 ? 2 : 3; }
 // Staging wavefronts per workgroup: two from 64 rows on, each taking every other instruction of a chunk.  (At 128
 // rows the rows of x that the workgroups fetch from L2 are twice the bytes of the weights, and that traffic is
 // what the time then follows: 16384 x 4096 takes 40 us, 31 with the staging switched off, whether one wavefront
@@ -226,10 +228,11 @@ constexpr int lin_weight_lead(int mf) { return 8 / lin_chunk(mf) > 1 ? 8 / lin_c
 constexpr int vmcnt_only(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
 
 // waves_per_eu: a workgroup has one or two wavefronts per SIMD and a compute unit holds one workgroup (LDS), so
-// up to 128 registers cost nothing; without the hint the compiler aimed at the occupancy the launch bounds allow
-// and capped the kernel at 64.
+// up to 128 registers cost nothing (256 with more than 8 row fragments, whose accumulators and operand registers
+// need them: a SIMD holds two of the workgroup's six wavefronts at most); without the hint the compiler aimed
+// at the occupancy the launch bounds allow and capped the kernel at 64.
 template <int MF, int NW>
-__global__ __launch_bounds__((NW + lin_stagers(MF)) * 64) __attribute__((amdgpu_waves_per_eu(1, 4))) void linear_lds_kernel(const LinearArgs a) {
+__global__ __launch_bounds__((NW + lin_stagers(MF)) * 64) __attribute__((amdgpu_waves_per_eu(1, MF > 8 ? 2 : 4))) void linear_lds_kernel(const LinearArgs a) {
   constexpr int NS = lin_stagers(MF);
   constexpr int kFastThreads = (NW + NS) * 64, kTileCols = NW * 16;      // kTileCols: output features of a workgroup
   constexpr int C = lin_chunk(MF), LEAD = lin_lead(MF), NBUF = LEAD + 1, PER = C * MF, MINE = PER / NS;
@@ -648,8 +651,10 @@ hipError_t launch_linear_mf(const LinearArgs &args, int n_tiles, bool fast, int 
       else
         hipLaunchKernelGGL(reduce_epilogue_kernel, dim3((args.n_out + 1023) / 1024, args.m), dim3(256), 0, stream, args);
     }
-  } else {
+  } else if constexpr (MF <= OKV_LINEAR_MAX_ROWS / 16) {
     hipLaunchKernelGGL(linear_kernel<MF>, dim3(n_tiles), dim3(kLinWaves * 64), 0, stream, args);
+  } else {
+    return hipErrorInvalidValue;                       // more than OKV_LINEAR_MAX_ROWS rows: the staged kernel only
   }
   return hipGetLastError();
 }
@@ -704,6 +709,16 @@ int64_t linear_workspace_bytes(int32_t m, int32_t n_out, int32_t n_in, int32_t n
   return s < 1 ? 0 : (int64_t)s * m * n_out * 4;        // a single cut still goes through a share when a layer norm follows
 }
 
+// Whether one launch of the staged kernel takes m rows of this product with the workspace at hand (the only
+// kernel there is for more than OKV_LINEAR_MAX_ROWS rows).
+bool linear_staged_takes(int32_t m, int32_t n_out, int32_t n_in, int32_t n_cus, bool have_workspace, int64_t workspace_bytes) {
+  if (m <= OKV_LIN_SIMPLE_ROWS || m > OKV_LINEAR_MAX_ROWS_STAGED) return false;
+  int waves = 4, s = 0;
+  linear_plan(m, n_out, n_in, n_cus, &waves, &s);
+  if (s < 1) return false;
+  return s == 1 || (have_workspace && workspace_bytes >= (int64_t)s * m * n_out * 4);
+}
+
 hipError_t launch_linear(const LinearLaunch &l, hipStream_t stream) {
   LinearArgs a;
   a.x = static_cast<const uint4 *>(l.x);
@@ -752,6 +767,10 @@ hipError_t launch_linear(const LinearLaunch &l, hipStream_t stream) {
     case 6: e = launch_linear_mf<6>(a, n_tiles, fast, fast_waves, stream); break;
     case 7: e = launch_linear_mf<7>(a, n_tiles, fast, fast_waves, stream); break;
     case 8: e = launch_linear_mf<8>(a, n_tiles, fast, fast_waves, stream); break;
+    case 9: e = launch_linear_mf<9>(a, n_tiles, fast, fast_waves, stream); break;
+    case 10: e = launch_linear_mf<10>(a, n_tiles, fast, fast_waves, stream); break;
+    case 11: e = launch_linear_mf<11>(a, n_tiles, fast, fast_waves, stream); break;
+    case 12: e = launch_linear_mf<12>(a, n_tiles, fast, fast_waves, stream); break;
   }
   if (e != hipSuccess || !l.ln_out || fuse_ln) return e;
   return launch_layernorm(l.out[0], l.ln_gamma, l.ln_beta, l.ln_out, l.m, l.n_out, l.ln_eps, stream);   // the same in two steps

@@ -111,7 +111,8 @@ def test_linear_shapes(n_out, n_in):
 
 
 @pytest.mark.parametrize("m,n_out,n_in,relu", [(32, 4096, 4096, False), (20, 256, 512, True), (64, 2560, 2560, False),
-                                               (8, 256, 512, False), (32, 192, 320, False), (33, 16384, 256, False)])
+                                               (8, 256, 512, False), (32, 192, 320, False), (33, 16384, 256, False),
+                                               (192, 1024, 2048, True), (150, 4096, 1024, False)])
 def test_linear_followed_by_layernorm_in_one_call(m, n_out, n_in, relu):
     # fast path (the norm rides on the share reduction), few rows and odd input sizes (two kernels): same contract
     say(f"linear+layernorm m={m} {n_out}x{n_in}")
@@ -355,9 +356,21 @@ def test_linear_random_shapes_against_the_oracle():
                    residual=bool(rng.integers(0, 2)))
 
 
-@pytest.mark.parametrize("m", [129, 192, 300])
+@pytest.mark.parametrize("m", [129, 144, 145, 160, 161, 176, 177, 192])
+def test_linear_129_to_192_rows_in_one_launch(m):
+    # 9 to 12 fragments of 16 rows: one launch of the staged kernel when the input width is a multiple of 256,
+    # both workgroup forms, with cuts (and the norm on the share reduction) or without
+    say(f"linear one launch m={m}")
+    run_linear(m, 12288 // 8, 512, 800 + m, n_seg=3)                       # three streaming wavefronts, no cut
+    run_linear(m, 1024, 1024, 810 + m, bias=True, relu=True, residual=True)
+    run_linear(m, 256, 2048, 820 + m, residual=True)
+    run_linear(m, 2048, 256, 830 + m, relu=True)
+
+
+@pytest.mark.parametrize("m", [129, 192, 193, 300, 400])
 def test_linear_more_rows_than_one_launch_takes(m):
-    # beyond 128 rows a call issues several launches of nearly equal size; same contract
+    # beyond what one launch takes (192 rows for the staged kernel, 128 otherwise) a call issues several launches
+    # of nearly equal size; same contract
     say(f"linear m={m}")
     run_linear(m, 320, 512, 700 + m, relu=True, residual=True)
     run_linear(m, 96, 1024, 710 + m, n_seg=3)
