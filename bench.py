@@ -682,7 +682,7 @@ def run_layers(args):
         for _ in range(n):
             x.copy_(x0)                    # keep the activations at the scale of the inputs (random weights amplify)
             bound.step(x)
-    settle("decoder layers", 2.0)
+    settle("decoder layers")
     st.set_batch(ctx0, table)
     with torch.cuda.stream(st.compute_stream):
         run(warmup)
