@@ -318,8 +318,9 @@ int okv_flush_tails(okv_ctx *ctx);
 /* Gives up an open step (after a call inside it failed, say, and the remaining layers cannot be
  * supplied): waits for everything enqueued, closes the step and forgets the batch.  The layers visited
  * so far hold the step's rows and the lengths have advanced on the device, which cannot be taken back,
- * so the next call must be okv_set_batch with the lengths the caller wants to go on from.
- * OKV_ESTATE outside a step. */
+ * so the next call must be okv_set_batch with the lengths the caller wants to go on from.  With
+ * cfg->tail_blocks, rows appended since the last block was written out and still only in the slots are
+ * not written to the host pools.  OKV_ESTATE outside a step. */
 int okv_step_abort(okv_ctx *ctx);
 
 /* Stores this step's key and value rows of `layer` at position ctx_len - 1 of each

@@ -146,6 +146,46 @@ def test_decode_then_prefill_then_decode():
     st.close()
 
 
+def test_decode_then_prefill_then_decode_with_the_newest_blocks_in_hbm():
+    # block-granular offload with the slots that keep appended rows in HBM: a prefill must first write out what
+    # the decode steps left there (the prompt continues in the middle of those blocks), and the steps after it
+    # start the slots afresh.  Nothing is read back on the way: the oracle keeps its own pools.
+    say("prefill between decode steps, newest blocks in HBM")
+    from gpu_util import assert_close, make_inputs
+    from test_gpu_block_classes import oracle_outputs
+    ctx = np.array([50, 9, 31], dtype=np.int32)
+    st = classed_stack(L=2, H=4, G=2, d=64, T=16, ctx_before=ctx, cap_tokens=320, c_off=Fraction(3, 5), chunk_blocks=5,
+                       policy="scatter", seed=231, workspace_items=3 * 24)
+    assert st.hot_tails
+    layout = st.layout()
+    want = [st.read_pool(l) for l in range(2)]
+    n = ctx.copy()
+
+    def decode(steps, seed):
+        for step in range(steps):
+            q, k, v, out = make_inputs(st, seed, step, st.device)
+            st.step(q, k, v, out)
+            st.synchronize()
+            n[:] = n + 1
+            for l in range(2):
+                kv_layout.append_scatter(want[l], layout, n, k[l].cpu().numpy(), v[l].cpu().numpy())
+                ref = oracle_outputs(want[l], layout, q[l].cpu().numpy(), n, 4, 2)
+                assert_close(out[l].float().cpu().numpy().reshape(-1, 64), ref.reshape(-1, 64), f"seed {seed} step {step} layer {l}")
+
+    decode(5, 233)
+    n_new = np.array([40, 70, 20], dtype=np.int32)
+    k, v = prompt_rows(st, n_new, 235)
+    st.prefill(n_new, k, v)
+    for l in range(2):
+        kv_layout.bulk_append_scatter(want[l], layout, n, n_new, k[l].cpu().numpy(), v[l].cpu().numpy())
+    n[:] = n + n_new
+    decode(20, 237)
+    care = ~unused_slots(st, n)
+    for l in range(2):
+        np.testing.assert_array_equal(st.read_pool(l).view(np.uint16)[care], want[l].view(np.uint16)[care])
+    st.close()
+
+
 def test_prefill_error_paths():
     say("prefill errors")
     st = build_stack(L=2, H=4, G=2, d=64, T=16, ctx_before=[10, 20], cap_tokens=64, seed=231)
