@@ -39,7 +39,7 @@ PCIE5_X16_GBPS = 64.0       # nominal, one direction
 TRAFFIC_RECORD = {
     "workload": "cfg2",
     "kernel_sha256": "72e438ed2577a739f04c6c21d4c27bdbdfe4ebb2d6007fb540e7e9630d907133",
-    "fetch_kib": 141754.5, "fetch_scale": 1.9999, "algorithmic_bytes": 285474816,   # context 513..576
+    "fetch_kib": 199098.5, "fetch_scale": 1.9999, "algorithmic_bytes": 402915328,   # context 737..800
     "write_kib": 768.0, "write_scale": 1.0000,
 }
 
