@@ -80,3 +80,62 @@ def test_static_entry_point_refuses_what_does_not_fit():
     with pytest.raises(binding.OkvError) as e:
         binding.okv_decode_attn_static(B=binding.OKV_STATIC_MAX_BATCH + 1, **kw)
     assert e.value.code == binding.OKV_EINVAL
+
+
+def test_static_entry_point_in_a_captured_graph_replays_like_the_eager_calls():
+    # what the entry point is for: a caller that captures a decode step into a HIP graph.  The graph holds a
+    # length bump and the call; it is replayed several times with eager work and synchronisations in between,
+    # and every replay is compared with the same steps made by eager calls on a second, identically filled pool.
+    say("graph capture")
+    from paper_2504_11816_amd.harness import new_stream
+    shape = dict(H=8, G=2, d=128, T=16, cap_tokens=600, out_dtype=0)
+    ctx_before = [300, 17, 129, 511]
+    stacks, pools = [], []
+    for _ in range(2):
+        st = build_stack(L=1, ctx_before=ctx_before, seed=930, **shape)
+        stacks.append(st)
+    st = stacks[0]
+    dev, B = st.device, len(ctx_before)
+    q, k, v, _ = make_inputs(st, 931, 0, dev)
+    q, k, v = q[0], k[0], v[0]
+    table = torch.tensor(st.block_table, dtype=torch.int32, device=dev)
+    raw, stream = new_stream(dev)
+
+    def call(pool, lens, out):
+        binding.okv_decode_attn_static(n_q_heads=st.H, n_kv_heads=st.G, head_dim=st.d, block_tokens=st.T,
+                                       max_blocks_per_seq=st.max_blocks, max_ctx=st.max_ctx, out_dtype=0, B=B, pool=pool,
+                                       block_table=table, ctx_lens=lens, q=q, out=out, k_new=k, v_new=v, stream=stream.cuda_stream)
+
+    lens_g = torch.tensor(ctx_before, dtype=torch.int32, device=dev)
+    lens_e = lens_g.clone()
+    out_g = torch.zeros((B, st.H, st.d), dtype=torch.float16, device=dev)
+    out_e = torch.zeros_like(out_g)
+    warm = torch.zeros_like(out_g)
+    call(stacks[1].dev_part[0], lens_e + 0, warm)               # first call on the device, outside any capture
+    stream.synchronize()
+    torch.cuda.synchronize()
+    # (that warm call stored rows at positions ctx_before - 1 of the second pool: positions below every length,
+    # overwritten identically in both pools below, since both get the same k / v at the same positions)
+    call(stacks[0].dev_part[0], lens_g + 0, warm)
+    stream.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g, stream=stream):
+        lens_g.add_(1)
+        call(stacks[0].dev_part[0], lens_g, out_g)
+    torch.cuda.synchronize()
+    lens_g.copy_(torch.tensor(ctx_before, dtype=torch.int32))   # the capture ran nothing, but start from a known state
+    for step in range(6):
+        g.replay()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(stream):
+            lens_e.add_(1)
+        call(stacks[1].dev_part[0], lens_e, out_e)
+        stream.synchronize()
+        junk = torch.randn(1 << 16, device=dev).sum().item()   # eager work of the program's own between replays
+        assert np.isfinite(junk)
+        assert torch.equal(lens_g, lens_e), step
+        assert torch.equal(out_g.view(torch.int16), out_e.view(torch.int16)), step
+        out_g.zero_()
+    np.testing.assert_array_equal(stacks[0].read_pool(0).view(np.uint16), stacks[1].read_pool(0).view(np.uint16))
+    for s in stacks:
+        s.close()
