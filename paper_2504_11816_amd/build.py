@@ -14,6 +14,9 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared", "-fno
          # wavefronts per SIMD and have registers to spare, and the accumulator-register form cost the
          # attention loop a copy of all 32 accumulators in and out per tile
          "-mllvm", "-amdgpu-mfma-vgpr-form",
+         # the leading scalar and pointer arguments of a kernel arrive in scalar registers with the wavefront
+         # instead of through a first round trip to the argument segment
+         "-mllvm", "-amdgpu-kernarg-preload-count=14",
          "-Wall", "-Wno-unused-command-line-argument"]
 
 

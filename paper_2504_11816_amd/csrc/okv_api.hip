@@ -38,6 +38,9 @@ constexpr int kEventRing = 8;            // > copies in flight (at most OKV_MAX_
 #endif
 constexpr int32_t kMinAutoSplit = 128;   // smallest stretch of keys the library cuts a launch into by itself
 constexpr int32_t kMinSpanTiles = kMinAutoSplit / 16;
+// Records of the per-pair look-up table an attention launch with max_waves wavefronts may read: its grid is
+// whole workgroups of four.
+inline int32_t max_pairs(int32_t max_waves) { return std::max(max_waves, 4); }
 constexpr int32_t kClassSplit = 512;     // split size with block classes unless the caller sets one
 constexpr int64_t kMaxClasses = 4096;
 // Workgroups of a bulk store that writes into host memory: the link, not the GPU, sets its
@@ -116,6 +119,7 @@ struct okv_ctx {
   int32_t *d_block_table = nullptr, *d_ctx_lens = nullptr, *d_chunk_prefix = nullptr;
   int4 *d_item_desc = nullptr;
   int32_t *d_group_first = nullptr;      // equal stretches: first item of every stretch (+ 1 entry)
+  void *d_pair_head = nullptr;           // equal stretches: what every (stretch, KV head) pair starts with
   int32_t *d_plan = nullptr;             // equal stretches: (stretches in use, items, tiles per stretch x 2)
   int32_t max_groups = 1;                // wavefronts of a launch per KV head
   int32_t *d_items_dump = nullptr;
@@ -274,6 +278,7 @@ okv::AttnLaunch base_launch(okv_ctx *ctx) {
   a.need_merge = ctx->need_merge;
   if (ctx->spans) {
     a.group_first = ctx->d_group_first;
+    a.pair_head = ctx->d_pair_head;
     a.n_groups = ctx->n_groups;
   }
   a.max_waves = ctx->max_waves;
@@ -554,7 +559,9 @@ int rebuild_worklist(okv_ctx *ctx, int32_t inc, bool upload_lens = false) {
   ctx->n_items = (int32_t)n;
   ctx->need_merge = merge;
   OKV_HIP(ctx, okv::launch_step_advance_spans(ctx->d_ctx_lens, ctx->d_chunk_prefix, ctx->d_item_desc, ctx->d_group_first,
-                                              ctx->d_plan, ctx->B, ctx->max_groups, kMinSpanTiles, inc, ctx->compute));
+                                              ctx->d_plan, ctx->B, ctx->max_groups, kMinSpanTiles, inc, ctx->d_pair_head,
+                                              okv::head_geom(ctx->shape, ctx->d_block_table, max_pairs(ctx->max_waves)),
+                                              ctx->compute));
   return OKV_OK;
 }
 
@@ -877,6 +884,10 @@ int okv_create(const okv_config *cfg, okv_ctx **out) {
   }
   OKV_TRY_CREATE(hipMalloc(&ctx->d_group_first, ((size_t)ctx->max_groups + 1) * sizeof(int32_t)));
   OKV_TRY_CREATE(hipMemset(ctx->d_group_first, 0, ((size_t)ctx->max_groups + 1) * sizeof(int32_t)));
+  if (ctx->max_groups <= okv::kHeadGroupsMax) {
+    OKV_TRY_CREATE(hipMalloc(&ctx->d_pair_head, (size_t)max_pairs(ctx->max_waves) * okv::kPairHeadBytes));
+    OKV_TRY_CREATE(hipMemset(ctx->d_pair_head, 0, (size_t)max_pairs(ctx->max_waves) * okv::kPairHeadBytes));
+  }
   OKV_TRY_CREATE(hipMalloc(&ctx->d_plan, 4 * sizeof(int32_t)));
   if (n_staging >= 2) OKV_TRY_CREATE(own_queue_stream(&ctx->h2d_odd));
   ctx->steps_ahead = !any_host ? 0 : by_class ? OKV_STEPS_AHEAD : OKV_STEPS_AHEAD_LAYERS;
@@ -909,6 +920,7 @@ int okv_destroy(okv_ctx *ctx) {
   (void)hipFree(ctx->d_chunk_prefix);
   (void)hipFree(ctx->d_item_desc);
   (void)hipFree(ctx->d_group_first);
+  (void)hipFree(ctx->d_pair_head);
   (void)hipFree(ctx->d_plan);
   (void)hipFree(ctx->d_items_dump);
   if (ctx->d2h) {
@@ -1912,9 +1924,9 @@ unsigned char *g_scratch_ptr[kMaxDevices] = {};
 int g_scratch_cus[kMaxDevices] = {};
 
 struct StaticLayout {            // offsets into the scratch array, each a multiple of 256
-  int64_t item_desc, chunk_prefix, group_first, plan, part_o, part_ml, bytes;
+  int64_t item_desc, chunk_prefix, group_first, pair_head, plan, part_o, part_ml, bytes;
 };
-StaticLayout static_layout(int64_t max_items, int32_t B, int32_t max_groups, int32_t H, int32_t D) {
+StaticLayout static_layout(int64_t max_items, int32_t B, int32_t max_groups, int32_t max_waves, int32_t H, int32_t D) {
   StaticLayout l;
   int64_t at = 0;
   auto take = [&](int64_t bytes) {
@@ -1925,6 +1937,7 @@ StaticLayout static_layout(int64_t max_items, int32_t B, int32_t max_groups, int
   l.item_desc = take(max_items * (int64_t)sizeof(int4));
   l.chunk_prefix = take(((int64_t)B + 1) * 4);
   l.group_first = take(((int64_t)max_groups + 1) * 4);
+  l.pair_head = take((int64_t)max_pairs(max_waves) * okv::kPairHeadBytes);
   l.plan = take(16);
   l.part_o = take(max_items * H * D * 4);
   l.part_ml = take(max_items * H * 2 * 4);
@@ -1969,7 +1982,7 @@ int okv_decode_attn_static(const okv_static_attn *a) {
   // the lengths are on the device only: room for the most items any lengths can give (one per
   // sequence and one per stretch)
   const int64_t max_items = (int64_t)a->B + max_groups;
-  const StaticLayout lay = static_layout(max_items, a->B, max_groups, H, D);
+  const StaticLayout lay = static_layout(max_items, a->B, max_groups, max_waves, H, D);
   if (lay.bytes > (int64_t)OKV_STATIC_SCRATCH_BYTES)
     return fail(nullptr, OKV_ENOSPC,
                 "okv_decode_attn_static: batch %d with %d query heads of %d needs %lld bytes of work space, the library holds %lld",
@@ -1979,8 +1992,7 @@ int okv_decode_attn_static(const okv_static_attn *a) {
   int4 *item_desc = reinterpret_cast<int4 *>(base + lay.item_desc);
   int32_t *group_first = reinterpret_cast<int32_t *>(base + lay.group_first);
   int32_t *plan = reinterpret_cast<int32_t *>(base + lay.plan);
-  OKV_HIP(nullptr, okv::launch_step_advance_spans(const_cast<int32_t *>(a->ctx_lens), chunk_prefix, item_desc, group_first, plan, a->B,
-                                                  max_groups, kMinSpanTiles, 0, stream));
+  void *pair_head = max_groups <= okv::kHeadGroupsMax ? base + lay.pair_head : nullptr;
   okv::AttnLaunch l;
   okv::PoolShape &s = l.shape;
   s.H = H, s.G = G, s.D = D;
@@ -1991,6 +2003,9 @@ int okv_decode_attn_static(const okv_static_attn *a) {
   s.gg = okv::kv_head_group(G, D);
   s.st_log2 = okv::slab_tiles_log2(G, D, s.tcap);
   s.max_blocks = s.paged ? a->max_blocks_per_seq : 1;
+  OKV_HIP(nullptr, okv::launch_step_advance_spans(const_cast<int32_t *>(a->ctx_lens), chunk_prefix, item_desc, group_first, plan, a->B,
+                                                  max_groups, kMinSpanTiles, 0, pair_head,
+                                                  okv::head_geom(s, a->block_table, max_pairs(max_waves)), stream));
   l.batch = okv::BatchState{a->block_table, a->ctx_lens, chunk_prefix, item_desc, a->B, 0, (int32_t)max_items, 1};
   l.q = a->q;
   l.pool = const_cast<void *>(a->pool);
@@ -2002,6 +2017,7 @@ int okv_decode_attn_static(const okv_static_attn *a) {
   l.out_fp32 = a->out_dtype;
   l.need_merge = 1;
   l.group_first = group_first;
+  l.pair_head = pair_head;
   l.n_groups = max_groups;
   l.n_groups_dev = plan;                                 // the kernel reads how many stretches are in use
   l.max_waves = max_waves;

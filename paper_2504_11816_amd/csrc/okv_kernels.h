@@ -48,6 +48,8 @@ struct AttnLaunch {
   int32_t n_groups = 0;
   const int32_t *n_groups_dev = nullptr;  // device: the number of groups when the host does not know it
                            // (the grid is then max_waves wavefronts)
+  const void *pair_head = nullptr;        // device: the records launch_step_advance_spans wrote for pools of this
+                           // shape; with them every (stretch, KV head) pair starts from one look-up (used when id_base is 0)
   int32_t max_waves;       // wavefronts of the persistent launch (a multiple of 4)
   // The launch covers items [item_first, item_first + item_count) of the list: all of them, or
   // those of one block class.  `pool` then holds the blocks with ids from id_base on, and
@@ -75,9 +77,31 @@ hipError_t launch_step_advance(int32_t *ctx_lens, int32_t *chunk_prefix, int4 *i
 // The same with the keys of the batch shared out in equal stretches (okv_host.h: span_plan): at most
 // max_groups stretches of at least min_span tiles; group_first[j] = first item of stretch j (one more
 // entry closes the last); plan_out[0..3] = stretches in use, items, tiles per stretch (low 31 bits, rest).
+// pair_head (may be NULL): [geom.max_pairs] records of kPairHeadBytes, one per (stretch, KV head) pair, pair =
+// stretch * G + head, written for the stretches the step has: the stretch's first item and how many it has,
+// that item's descriptor, and where the head's K rows of its first two tiles lie in a pool of the geometry
+// given (the same for every layer).  An attention launch with max_waves wavefronts looks at the records of
+// the pairs below max(max_waves, 4) (and ignores those past the last stretch): geom.max_pairs is at least that.
+// The bookkeeping kernel keeps what opens each stretch in LDS: a table is written only for at most
+// kHeadGroupsMax stretches (callers with more pass NULL, to it and to the attention launches alike).
+constexpr int kPairHeadBytes = 32, kHeadGroupsMax = 1024;
+struct HeadGeom {
+  const int32_t *block_table = nullptr;   // device; NULL: contiguous pools (a sequence's slice is its block)
+  int32_t max_blocks = 1, log2_T = 0;
+  int32_t tiles = 1;                      // 16-token tiles of a pool slice (tcap / 16)
+  int32_t st_log2 = 0, G = 1, gg = 1;     // slab geometry, as in PoolShape
+  int32_t max_pairs = 0;                  // records to write
+};
+inline HeadGeom head_geom(const PoolShape &s, const int32_t *block_table, int32_t max_pairs) {
+  HeadGeom g;
+  g.block_table = s.paged ? block_table : nullptr;
+  g.max_blocks = s.max_blocks, g.log2_T = s.log2_T, g.tiles = s.tcap >> 4;
+  g.st_log2 = s.st_log2, g.G = s.G, g.gg = s.gg, g.max_pairs = max_pairs;
+  return g;
+}
 hipError_t launch_step_advance_spans(int32_t *ctx_lens, int32_t *chunk_prefix, int4 *item_desc, int32_t *group_first,
                                      int32_t *plan_out, int32_t B, int32_t max_groups, int32_t min_span, int32_t inc,
-                                     hipStream_t stream);
+                                     void *pair_head, const HeadGeom &geom, hipStream_t stream);
 
 // The same for block classes: runs[r] = (sequence, first position, one past the last position
 // the run can hold, class), sorted by (class, sequence, position); pair_first[cls * B + b] is the

@@ -75,6 +75,23 @@ __device__ __forceinline__ int64_t slab_base(const TileAddr &t, int blk, int til
   return (lin >> t.st_log2) * t.slab_elems + (int64_t)((int)lin & ((1 << t.st_log2) - 1)) * t.tile_stride;
 }
 
+// What a wavefront needs to know to ask for its first tiles, in one aligned 32-byte record per (stretch, KV
+// head) pair: the bookkeeping kernel writes the records once per step, for all layers, and the attention
+// kernel fetches its own with a single scalar load instead of walking group_first -> item descriptor ->
+// block table and working out the tile's place in the pool, all of it while nothing is in flight yet and
+// from an instruction cache that every launch finds cold.
+struct alignas(32) PairHead {
+  int32_t item;              // the stretch's first item (relative to the launch's first)
+  int32_t count;             // items of the stretch (0: none, which only a batch without keys has)
+  int32_t b, lo, hi;         // that item's sequence and keys
+  int32_t flags_g;           // its flags, and the KV head in the bits from 8 up
+  int32_t base0, base1;      // where the head's K rows of the item's first two tiles begin (the second clamped to the
+                             // item's last tile), in units of 16 * D elements from the pool's start, block ids as the
+                             // table has them
+};
+typedef int32_t int32x8_t __attribute__((ext_vector_type(8)));
+typedef const int32x8_t __attribute__((address_space(4))) *const_head_ptr;   // a record as one scalar load
+
 template <int LPT>
 struct Tile {
   uint4 k[LPT];
@@ -95,8 +112,10 @@ struct AttnArgs {
   const int32_t *group_first;      // [n_groups + 1] first item of each group of the launch (relative to item_first), or
                                    // NULL: group j is item j
   const int32_t *n_groups_dev;     // NULL, or where the number of groups is to be read (n_groups is then ignored)
+  const PairHead *pair_head;       // NULL, or what every (stretch, KV head) pair starts with: pair p is wavefront p's
+                                   // (then neither n_groups nor group_first is looked at; needs id_base == 0)
   int32_t n_groups;
-  int32_t H, G, log2_T, tcap, max_blocks, out_fp32;
+  int32_t H, G, R, log2_T, tcap, max_blocks, out_fp32;   // R = H / G
   int32_t gg;                      // KV heads per group inside a slab
   int32_t st_log2;                 // log2 of the 16-token tiles per slab
   int32_t item_first;              // the launch's first item in item_desc (and in the partial slots)
@@ -255,22 +274,47 @@ struct Unit {
 // The body is one loop with one copy of everything -- [A] ask for the next item's first tiles and q,
 // [B] write the current item's results, [C] switch to the next item and reduce its tiles -- entered at
 // [A] for the first item: a launch fetches every instruction it runs from a cold instruction cache
-// (about 0.1 us per 64 bytes), which at 50 us a launch is worth keeping short.
-template <int D, bool PAGED, int PIPE>
-__global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(const AttnArgs a) {
+// (about 0.1 us per 64 bytes where the fetch does not run straight on), which at 50 us a launch is worth
+// keeping short.
+//
+// The start of a launch is the other fixed cost: until a wavefront's first tile arrives nothing hides the
+// round trips in front of it (a scalar load right after the launch takes 1-2 us).  With HEADS the
+// wavefront's own (stretch, KV head) pair comes from a table the bookkeeping kernel wrote (PairHead): one
+// look-up, whose address needs only arguments that arrive in registers, then the first tile loads, and
+// everything else (the other arguments, the LDS addresses, the zeroed sums) is set up behind them.  Without
+// it (a split size fixed by the caller, block classes, more pairs than wavefronts) pairs are dealt out
+// round robin and the first item is found through group_first, the item list and the block table.
+template <int D, bool PAGED, int PIPE, bool HEADS>
+__global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(
+    const PairHead *pair_head, const uint16_t *pool, const uint16_t *q, const int32_t *n_groups_dev, const int32_t n_groups,
+    const int32_t G, const int32_t H, const int32_t R, const int32_t v_tiles, const AttnArgs a) {
   __shared__ __attribute__((aligned(16))) char lds_all[kWavesPerBlock][2 * lds_tile_bytes<D>()];
   constexpr int LPR = D / 8, RPL = 64 / LPR, LPT = D / 32;
   const int lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t n_waves = gridDim.x * kWavesPerBlock;
-  const int R = a.H / a.G;
-  // the number of groups is a launch argument, or (for callers that do not know the batch's lengths on
-  // the host) what the bookkeeping kernel left in device memory
   const const_i32_ptr gf = (const_i32_ptr)(uintptr_t)a.group_first;
-  const uint32_t n_groups = a.n_groups_dev ? (uint32_t)((const_i32_ptr)(uintptr_t)a.n_groups_dev)[0] : (uint32_t)a.n_groups;
-  const uint32_t n_pairs = n_groups * (uint32_t)a.G;
   uint32_t pair = blockIdx.x * kWavesPerBlock + wave;    // of the unit N below
+  // With a table of heads every (stretch, KV head) pair has a wavefront of its own and its head says what
+  // the pair starts with; otherwise pairs are dealt out round robin.  The number of groups is a launch
+  // argument, or (for callers that do not know the batch's lengths on the host) what the bookkeeping kernel
+  // left in device memory.
+  //
+  // The parameters in front of `a` are the ones the first loads need: the build asks for the leading kernel
+  // arguments to be in scalar registers when a wavefront starts, so the pair's record can be asked for at
+  // once, and the first tiles as soon as it is there.
+  constexpr bool by_head = HEADS;                        // (pair_head is not NULL then)
+  int32x8_t w = {0, 0, 0, 0, 0, 0, 0, 0};
+  if (by_head) w = *(const_head_ptr)(uintptr_t)(pair_head + pair);
+  const uint32_t n_pairs = (n_groups_dev ? (uint32_t)((const_i32_ptr)(uintptr_t)n_groups_dev)[0] : (uint32_t)n_groups) * (uint32_t)G;
+  asm volatile("" ::"s"(w[0]), "s"(n_pairs));           // (both asked for before either is waited for)
   if (pair >= n_pairs) return;
+  PairHead head = {};
+  if (by_head) {
+    head.item = w[0], head.count = w[1], head.b = w[2], head.lo = w[3], head.hi = w[4], head.flags_g = w[5];
+    head.base0 = w[6], head.base1 = w[7];
+    if (head.count <= 0) return;                         // (records past the last pair are not written)
+  }
 
   const int row = lane / LPR, col = lane % LPR;
   const int quarter = lane >> 4, rho = lane & 15;
@@ -289,8 +333,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(co
   };
   auto load_tile = [&](Tile<LPT> &t, const TileAddr &ta, int tile, int blk) {
     const int64_t base = slab_base<PAGED>(ta, blk, tile);
-    const uint4 *kp = reinterpret_cast<const uint4 *>(a.pool + base + ta.head_k) + lane;
-    const uint4 *vp = reinterpret_cast<const uint4 *>(a.pool + base + ta.head_v) + lane;
+    const uint4 *kp = reinterpret_cast<const uint4 *>(pool + base + ta.head_k) + lane;
+    const uint4 *vp = reinterpret_cast<const uint4 *>(pool + base + ta.head_v) + lane;
 #pragma unroll
     for (int j = 0; j < LPT; ++j) t.k[j] = kp[j * 64];
 #pragma unroll
@@ -298,15 +342,46 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(co
   };
 
   // the items of the pair: item .. item_end - 1 (relative to the launch's first item)
-  int item = gf ? gf[pair / (uint32_t)a.G] : (int)(pair / (uint32_t)a.G);
-  int item_end = gf ? gf[pair / (uint32_t)a.G + 1] : item + 1;
+  int item, item_end;
+  if (by_head) {
+    item = head.item, item_end = head.item + head.count;
+  } else {
+    item = gf ? gf[pair / (uint32_t)G] : (int)(pair / (uint32_t)G);
+    item_end = gf ? gf[pair / (uint32_t)G + 1] : item + 1;
+  }
   bool has_next = true;                                  // N is a unit (else the wavefront's share is done)
   Unit<PIPE> N, C;                                       // the unit whose first tiles are asked for next; the one being reduced
   bool live = false;                                     // C holds a unit whose results are still to be written
-  TileAddr ta = tile_addr<D>(a.G, a.gg, a.tcap, a.st_log2, 0);
+  TileAddr ta = tile_addr<D>(G, a.gg, a.tcap, a.st_log2, 0);
   Tile<LPT> buf[PIPE];
   uint4 q_next[D / 32];                                  // q of N: the B operand of the score product, lane (quarter, rho) holds
                                                          // head rho, dims 32 c + 8 quarter .. + 7; columns past the group's heads are zero
+  if (by_head) {
+    // the first unit's first tiles and its q straight from the head, before anything else is set up
+#pragma unroll
+    for (int i = 0; i < PIPE; ++i) {
+      const uint4 *kp = reinterpret_cast<const uint4 *>(pool + (size_t)(uint32_t)(i ? head.base1 : head.base0) * (16 * D)) + lane;
+      const uint4 *vp = kp + ((size_t)v_tiles * (16 * D) * 2 / 16);
+#pragma unroll
+      for (int j = 0; j < LPT; ++j) buf[i].k[j] = kp[j * 64];
+#pragma unroll
+      for (int j = 0; j < LPT; ++j) buf[i].v[j] = vp[j * 64];
+    }
+#pragma unroll
+    for (int c = 0; c < D / 32; ++c) {
+      q_next[c] = make_uint4(0u, 0u, 0u, 0u);
+      if (rho < R)
+        q_next[c] = *reinterpret_cast<const uint4 *>(q + ((size_t)head.b * H + (size_t)(head.flags_g >> 8) * R + rho) * D + 32 * c + 8 * quarter);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+  }
+  // All the other launch arguments are asked for here, in one batch of scalar loads (with a table of heads:
+  // behind the first tile loads).  Left to itself the compiler fetches each where it is first used, which
+  // makes three or four dependent round trips to the argument segment of them.
+  asm volatile("" ::"s"(gridDim.x), "s"(a.gg), "s"(a.st_log2), "s"(a.k_new), "s"(a.v_new), "s"(a.pool_store),
+               "s"(a.pool_mirror), "s"(a.out), "s"(a.part_o), "s"(a.part_ml), "s"(a.block_table), "s"(a.item_desc),
+               "s"(a.group_first), "s"(a.log2_T), "s"(a.tcap), "s"(a.max_blocks), "s"(a.out_fp32), "s"(a.item_first),
+               "s"(a.id_base), "s"(a.mirror_shift), "s"(a.mirror_is_tail), "s"(a.scale_log2e));
   float m = kNegBig, l = 0.f;
   floatx4_t o[D / 16];
   uint4 k_row = make_uint4(0u, 0u, 0u, 0u), v_row = k_row;
@@ -316,23 +391,30 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(co
     // N's descriptor and first block ids: for the first unit waited for here; for the others asked for
     // a whole item earlier ([C] below)
     if (!live) {
-      N.g = (int)(pair % (uint32_t)a.G);
       N.it = a.item_first + item;
-      const const_i32_ptr dp = (const_i32_ptr)(uintptr_t)(a.item_desc + N.it);
-      N.b = dp[0], N.lo = dp[1], N.hi = dp[2], N.flags = dp[3];
+      if (by_head) {                                     // its first tiles are on their way already
+        N.g = head.flags_g >> 8;
+        N.b = head.b, N.lo = head.lo, N.hi = head.hi, N.flags = head.flags_g & 0xff;
 #pragma unroll
-      for (int i = 0; i < PIPE; ++i) N.blk0[i] = blk_of(N.b, min((N.lo >> 4) + i, (N.hi - 1) >> 4));
+        for (int i = 0; i < PIPE; ++i) N.blk0[i] = 0;
+      } else {
+        N.g = (int)(pair % (uint32_t)G);
+        const const_i32_ptr dp = (const_i32_ptr)(uintptr_t)(a.item_desc + N.it);
+        N.b = dp[0], N.lo = dp[1], N.hi = dp[2], N.flags = dp[3];
+#pragma unroll
+        for (int i = 0; i < PIPE; ++i) N.blk0[i] = blk_of(N.b, min((N.lo >> 4) + i, (N.hi - 1) >> 4));
+      }
     }
     // [A] the next unit's first tiles and its q
-    const TileAddr ta_next = tile_addr<D>(a.G, a.gg, a.tcap, a.st_log2, N.g);
-    if (has_next) {
+    const TileAddr ta_next = tile_addr<D>(G, a.gg, a.tcap, a.st_log2, N.g);
+    if (has_next && (live || !by_head)) {
 #pragma unroll
       for (int i = 0; i < PIPE; ++i) load_tile(buf[i], ta_next, min((N.lo >> 4) + i, (N.hi - 1) >> 4), N.blk0[i]);
 #pragma unroll
       for (int c = 0; c < D / 32; ++c) {
         q_next[c] = make_uint4(0u, 0u, 0u, 0u);
         if (rho < R)
-          q_next[c] = *reinterpret_cast<const uint4 *>(a.q + ((size_t)N.b * a.H + (size_t)N.g * R + rho) * D + 32 * c + 8 * quarter);
+          q_next[c] = *reinterpret_cast<const uint4 *>(q + ((size_t)N.b * H + (size_t)N.g * R + rho) * D + 32 * c + 8 * quarter);
       }
     }
     __builtin_amdgcn_sched_barrier(0);
@@ -351,9 +433,9 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(co
         const int h = C.g * R + rho;
         const float inv = seq_whole ? 1.0f / lt : 1.0f;
         const bool as_float = !seq_whole || a.out_fp32;
-        float *fdst = seq_whole ? reinterpret_cast<float *>(a.out) + ((size_t)C.b * a.H + h) * D
-                                : a.part_o + ((size_t)C.it * a.H + h) * D;
-        uint16_t *hdst = reinterpret_cast<uint16_t *>(a.out) + ((size_t)C.b * a.H + h) * D;
+        float *fdst = seq_whole ? reinterpret_cast<float *>(a.out) + ((size_t)C.b * H + h) * D
+                                : a.part_o + ((size_t)C.it * H + h) * D;
+        uint16_t *hdst = reinterpret_cast<uint16_t *>(a.out) + ((size_t)C.b * H + h) * D;
 #pragma unroll
         for (int u = 0; u < D / 32; ++u) {
           float ot[8];
@@ -377,7 +459,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(co
           }
         }
         if (!seq_whole && quarter == 0)
-          *reinterpret_cast<float2 *>(a.part_ml + ((size_t)C.it * a.H + h) * 2) = make_float2(m, lt);
+          *reinterpret_cast<float2 *>(a.part_ml + ((size_t)C.it * H + h) * 2) = make_float2(m, lt);
       }
       // The item that ends at the sequence's last key also stores this step's K/V rows (paper §II-A: keys
       // and values of every processed token are kept): row 0 of the load layout stores the K row, row 1 the V row.
@@ -404,14 +486,14 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(co
       ++item;
     } else {
       pair += n_waves;
-      has_next = pair < n_pairs;
+      has_next = !by_head && pair < n_pairs;             // by head: the wavefront's own stretch is all it has
       if (has_next) {
-        item = gf ? gf[pair / (uint32_t)a.G] : (int)(pair / (uint32_t)a.G);
-        item_end = gf ? gf[pair / (uint32_t)a.G + 1] : item + 1;
+        item = gf ? gf[pair / (uint32_t)G] : (int)(pair / (uint32_t)G);
+        item_end = gf ? gf[pair / (uint32_t)G + 1] : item + 1;
       }
     }
     if (has_next) {
-      N.g = (int)(pair % (uint32_t)a.G);
+      N.g = by_head ? C.g : (int)(pair % (uint32_t)G);
       N.it = a.item_first + item;
       const const_i32_ptr dp = (const_i32_ptr)(uintptr_t)(a.item_desc + N.it);
       N.b = dp[0], N.lo = dp[1], N.hi = dp[2], N.flags = dp[3];
@@ -424,7 +506,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(co
     const int pos = hi - 1;
     const bool appending = a.k_new != nullptr && (C.flags & kItemLast) != 0;
     if (appending) {
-      const size_t at = ((size_t)b * a.G + C.g) * LPR + col;
+      const size_t at = ((size_t)b * G + C.g) * LPR + col;
       k_row = reinterpret_cast<const uint4 *>(a.k_new)[at];
       v_row = reinterpret_cast<const uint4 *>(a.v_new)[at];
     }
@@ -560,12 +642,20 @@ constexpr int base_depth() {
   return (D == 64 ? 2 : 1) * OKV_PIPE_MULT;
 }
 
+template <int D, bool PAGED, bool HEADS>
+void launch_split_as(const AttnArgs &args, dim3 grid, hipStream_t stream) {
+  hipLaunchKernelGGL((attn_split_mfma_kernel<D, PAGED, base_depth<D>(), HEADS>), grid, dim3(kWavesPerBlock * 64), 0, stream,
+                     args.pair_head, args.pool, args.q, args.n_groups_dev, args.n_groups, args.G, args.H, args.R,
+                     args.gg << args.st_log2, args);
+}
+
 template <int D>
 hipError_t launch_split(const AttnArgs &args, bool paged, dim3 grid, hipStream_t stream) {
+  const bool heads = args.pair_head != nullptr;
   if (paged)
-    hipLaunchKernelGGL((attn_split_mfma_kernel<D, true, base_depth<D>()>), grid, dim3(kWavesPerBlock * 64), 0, stream, args);
+    heads ? launch_split_as<D, true, true>(args, grid, stream) : launch_split_as<D, true, false>(args, grid, stream);
   else
-    hipLaunchKernelGGL((attn_split_mfma_kernel<D, false, base_depth<D>()>), grid, dim3(kWavesPerBlock * 64), 0, stream, args);
+    heads ? launch_split_as<D, false, true>(args, grid, stream) : launch_split_as<D, false, false>(args, grid, stream);
   return hipGetLastError();
 }
 
@@ -590,9 +680,11 @@ AttnArgs make_args(const AttnLaunch &a) {
   args.item_desc = a.batch.item_desc;
   args.group_first = a.group_first;
   args.n_groups_dev = a.n_groups_dev;
+  args.pair_head = a.id_base == 0 ? static_cast<const PairHead *>(a.pair_head) : nullptr;
   args.n_groups = a.group_first ? a.n_groups : a.item_count;
   args.H = s.H;
   args.G = s.G;
+  args.R = s.H / s.G;
   args.log2_T = s.log2_T;
   args.tcap = s.tcap;
   args.gg = s.gg;
@@ -617,12 +709,13 @@ hipError_t launch_decode_attn(const AttnLaunch &a, hipStream_t stream, hipEvent_
   const PoolShape &s = a.shape;
   if (a.item_count <= 0 || a.item_first < 0 || a.item_first + a.item_count > a.batch.n_items)
     return hipErrorInvalidValue;
-  const AttnArgs args = make_args(a);
+  AttnArgs args = make_args(a);
   const int R = s.H / s.G;
   // persistent launch: no more wavefronts than there are (group, KV head) pairs, no more than a.max_waves
   const int64_t want = ((int64_t)args.n_groups * s.G + kWavesPerBlock - 1) / kWavesPerBlock;
   const int64_t cap = std::max<int64_t>(1, a.max_waves / kWavesPerBlock);
   dim3 grid((unsigned)(a.n_groups_dev ? cap : std::min(want, cap)));
+  if (want > cap) args.pair_head = nullptr;              // heads need a wavefront per (stretch, KV head) pair
   hipError_t e;
   if (ev_begin && (e = hipEventRecord(ev_begin, stream)) != hipSuccess) return e;
   if (R < 1 || R > 16 || R * s.G != s.H)
@@ -705,9 +798,17 @@ __global__ __launch_bounds__(kStepThreads) void step_advance_spans_kernel(int32_
                                                                          int4 *item_desc, int32_t *group_first,
                                                                          int32_t *plan_out, int32_t B,
                                                                          int32_t max_groups, int32_t min_span,
-                                                                         int32_t inc) {
+                                                                         int32_t inc, PairHead *pair_head,
+                                                                         const HeadGeom hg) {
   __shared__ int64_t part[kStepThreads];
+  // what opens each stretch, for the per-pair records: its first item, that item's descriptor and the block
+  // ids of the item's first two tiles (the second clamped to the item's last tile)
+  __shared__ int32_t open_item[kHeadGroupsMax + 1];
+  __shared__ int4 open_desc[kHeadGroupsMax];
+  __shared__ int2 open_blk[kHeadGroupsMax];
   const int tid = threadIdx.x;
+  if (pair_head)
+    for (int j = tid; j <= kHeadGroupsMax; j += kStepThreads) open_item[j] = -1;
   const int per = (B + kStepThreads - 1) / kStepThreads;     // consecutive sequences per thread
   const int b0 = min(B, tid * per), b1 = min(B, b0 + per);
   int64_t mine = 0;
@@ -755,15 +856,62 @@ __global__ __launch_bounds__(kStepThreads) void step_advance_spans_kernel(int32_
       const ItemRange r = span_piece(b, c, n, first, tiles, plan.span, k0, &group);
       const int32_t flags = (c == cnt - 1 ? kItemLast : 0) | (cnt == 1 ? kItemWhole : 0);
       item_desc[at + c] = make_int4(r.b, r.lo, r.hi, flags);
-      if (c > 0 || first % plan.span == 0) group_first[group] = at + c;   // the item opens its stretch
+      if (c > 0 || first % plan.span == 0) {                               // the item opens its stretch
+        group_first[group] = at + c;
+        if (pair_head && group < kHeadGroupsMax) {
+          open_item[group] = at + c;
+          open_desc[group] = make_int4(r.b, r.lo, r.hi, flags);
+          int2 blk = make_int2(b, b);
+          if (hg.block_table) {
+            const int32_t t0 = r.lo >> 4, t1 = min(t0 + 1, (r.hi - 1) >> 4);
+            const int32_t *row = hg.block_table + (size_t)b * hg.max_blocks;
+            blk.x = row[min((t0 << 4) >> hg.log2_T, hg.max_blocks - 1)];
+            blk.y = row[min((t1 << 4) >> hg.log2_T, hg.max_blocks - 1)];
+          }
+          open_blk[group] = blk;
+        }
+      }
     }
     at += cnt;
     first += tiles;
   }
   if (tid == kStepThreads - 1) {
+    group_first[plan.n_groups] = (int32_t)part[tid];
+    if (pair_head && plan.n_groups <= kHeadGroupsMax) open_item[plan.n_groups] = (int32_t)part[tid];
+  }
+  if (pair_head) {
+    // One record per (stretch, KV head) pair: the stretch's first item and where that head's rows of the
+    // item's first two tiles lie.  Nothing is written for pairs past the last stretch: the attention kernel
+    // knows how many stretches there are.
+    __syncthreads();
+    const int32_t St_mask = (1 << hg.st_log2) - 1;
+    const int32_t n_pairs = (int32_t)min((int64_t)plan.n_groups * hg.G, (int64_t)hg.max_pairs);
+    for (int p = tid; p < n_pairs; p += kStepThreads) {
+      const int32_t group = p / hg.G, g = p - group * hg.G;
+      PairHead h = {};
+      const int32_t it = group < plan.n_groups && group < kHeadGroupsMax ? open_item[group] : -1;
+      const int32_t n = it >= 0 ? open_item[group + 1] - it : 0;
+      if (n > 0) {                                       // (a batch with no keys at all has one stretch and no item)
+        h.item = it, h.count = n;
+        const int4 d = open_desc[group];
+        h.b = d.x, h.lo = d.y, h.hi = d.z, h.flags_g = d.w | (g << 8);
+        const int32_t grp = g / hg.gg;
+        const int32_t head_k = ((grp * 2 * hg.gg) << hg.st_log2) + (g - grp * hg.gg);
+        const int32_t t0 = d.y >> 4, t_last = (d.z - 1) >> 4;
+        for (int i = 0; i < 2; ++i) {
+          const int32_t t = min(t0 + i, t_last);
+          const int32_t blk = i ? open_blk[group].y : open_blk[group].x;
+          const int64_t lin = (int64_t)blk * hg.tiles + (hg.block_table ? t & (hg.tiles - 1) : t);
+          const int64_t base = (lin >> hg.st_log2) * ((int64_t)(2 * hg.G) << hg.st_log2) + (lin & St_mask) * hg.gg + head_k;
+          (i ? h.base1 : h.base0) = (int32_t)base;
+        }
+      }
+      pair_head[p] = h;
+    }
+  }
+  if (tid == kStepThreads - 1) {
     const int32_t n_items = (int32_t)part[tid];
     chunk_prefix[B] = n_items;
-    group_first[plan.n_groups] = n_items;
     plan_out[0] = plan.n_groups;
     plan_out[1] = n_items;
     plan_out[2] = (int32_t)(plan.span & 0x7fffffff);
@@ -978,9 +1126,10 @@ hipError_t launch_step_advance(int32_t *ctx_lens, int32_t *chunk_prefix, int4 *i
 
 hipError_t launch_step_advance_spans(int32_t *ctx_lens, int32_t *chunk_prefix, int4 *item_desc, int32_t *group_first,
                                      int32_t *plan_out, int32_t B, int32_t max_groups, int32_t min_span, int32_t inc,
-                                     hipStream_t stream) {
+                                     void *pair_head, const HeadGeom &geom, hipStream_t stream) {
   hipLaunchKernelGGL(step_advance_spans_kernel, dim3(1), dim3(kStepThreads), 0, stream, ctx_lens, chunk_prefix,
-                     item_desc, group_first, plan_out, B, max_groups, min_span, inc);
+                     item_desc, group_first, plan_out, B, max_groups, min_span, inc, static_cast<PairHead *>(pair_head),
+                     geom);
   return hipGetLastError();
 }
 
