@@ -277,7 +277,6 @@ okv::AttnLaunch base_launch(okv_ctx *ctx) {
   a.out_fp32 = ctx->cfg.out_dtype;
   a.need_merge = ctx->need_merge;
   if (ctx->spans) {
-    a.group_first = ctx->d_group_first;
     a.pair_head = ctx->d_pair_head;
     a.n_groups = ctx->n_groups;
   }
@@ -880,14 +879,12 @@ int okv_create(const okv_config *cfg, okv_ctx **out) {
     OKV_TRY_CREATE(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev));
     const int group = cfg->n_q_heads / cfg->n_kv_heads;
     ctx->max_waves = std::max(1, cus) * (group == 1 ? OKV_WAVES_PER_CU_MHA : group < 8 ? OKV_WAVES_PER_CU_GQA : OKV_WAVES_PER_CU_MFMA);
-    ctx->max_groups = std::max(1, ctx->max_waves / cfg->n_kv_heads);
+    ctx->max_groups = std::min(std::max(1, ctx->max_waves / cfg->n_kv_heads), okv::kHeadGroupsMax);
   }
   OKV_TRY_CREATE(hipMalloc(&ctx->d_group_first, ((size_t)ctx->max_groups + 1) * sizeof(int32_t)));
   OKV_TRY_CREATE(hipMemset(ctx->d_group_first, 0, ((size_t)ctx->max_groups + 1) * sizeof(int32_t)));
-  if (ctx->max_groups <= okv::kHeadGroupsMax) {
-    OKV_TRY_CREATE(hipMalloc(&ctx->d_pair_head, (size_t)max_pairs(ctx->max_waves) * okv::kPairHeadBytes));
-    OKV_TRY_CREATE(hipMemset(ctx->d_pair_head, 0, (size_t)max_pairs(ctx->max_waves) * okv::kPairHeadBytes));
-  }
+  OKV_TRY_CREATE(hipMalloc(&ctx->d_pair_head, (size_t)max_pairs(ctx->max_waves) * okv::kPairHeadBytes));
+  OKV_TRY_CREATE(hipMemset(ctx->d_pair_head, 0, (size_t)max_pairs(ctx->max_waves) * okv::kPairHeadBytes));
   OKV_TRY_CREATE(hipMalloc(&ctx->d_plan, 4 * sizeof(int32_t)));
   if (n_staging >= 2) OKV_TRY_CREATE(own_queue_stream(&ctx->h2d_odd));
   ctx->steps_ahead = !any_host ? 0 : by_class ? OKV_STEPS_AHEAD : OKV_STEPS_AHEAD_LAYERS;
@@ -1978,7 +1975,7 @@ int okv_decode_attn_static(const okv_static_attn *a) {
   unsigned char *base = g_scratch_ptr[dev];
   const int32_t H = a->n_q_heads, G = a->n_kv_heads, D = a->head_dim;
   const int32_t max_waves = g_scratch_cus[dev] * OKV_WAVES_PER_CU_MHA;
-  const int32_t max_groups = std::max(1, max_waves / G);
+  const int32_t max_groups = std::min(std::max(1, max_waves / G), okv::kHeadGroupsMax);
   // the lengths are on the device only: room for the most items any lengths can give (one per
   // sequence and one per stretch)
   const int64_t max_items = (int64_t)a->B + max_groups;
@@ -1992,7 +1989,7 @@ int okv_decode_attn_static(const okv_static_attn *a) {
   int4 *item_desc = reinterpret_cast<int4 *>(base + lay.item_desc);
   int32_t *group_first = reinterpret_cast<int32_t *>(base + lay.group_first);
   int32_t *plan = reinterpret_cast<int32_t *>(base + lay.plan);
-  void *pair_head = max_groups <= okv::kHeadGroupsMax ? base + lay.pair_head : nullptr;
+  void *pair_head = base + lay.pair_head;
   okv::AttnLaunch l;
   okv::PoolShape &s = l.shape;
   s.H = H, s.G = G, s.D = D;
@@ -2016,7 +2013,6 @@ int okv_decode_attn_static(const okv_static_attn *a) {
   l.part_ml = reinterpret_cast<float *>(base + lay.part_ml);
   l.out_fp32 = a->out_dtype;
   l.need_merge = 1;
-  l.group_first = group_first;
   l.pair_head = pair_head;
   l.n_groups = max_groups;
   l.n_groups_dev = plan;                                 // the kernel reads how many stretches are in use

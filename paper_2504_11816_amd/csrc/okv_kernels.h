@@ -42,14 +42,16 @@ struct AttnLaunch {
   float *part_ml;          // [n_items * H][2]  (max in log2 units, sum)
   int32_t out_fp32;
   int32_t need_merge;      // some sequence has more than one item
-  // How the launch's items are shared out: group j = items group_first[j] .. group_first[j + 1] - 1
-  // (relative to item_first), one wavefront per (group, KV head); NULL: every item is a group of its own.
-  const int32_t *group_first = nullptr;   // device, [n_groups + 1]
-  int32_t n_groups = 0;
-  const int32_t *n_groups_dev = nullptr;  // device: the number of groups when the host does not know it
-                           // (the grid is then max_waves wavefronts)
-  const void *pair_head = nullptr;        // device: the records launch_step_advance_spans wrote for pools of this
-                           // shape; with them every (stretch, KV head) pair starts from one look-up (used when id_base is 0)
+  // How the launch's items are shared out.  pair_head NULL: every item is a group of its own, and the (item, KV
+  // head) pairs are dealt out to the wavefronts round robin.  Else the records launch_step_advance_spans wrote
+  // for pools of this shape: stretch j is a group of consecutive items, record j * G + g says what the wavefront
+  // for KV head g of it starts with, and every pair has a wavefront of its own (n_groups * G <= max_waves); the
+  // launch must cover the whole list (item_first 0) from a pool that holds the blocks as the table numbers
+  // them (id_base 0).
+  const void *pair_head = nullptr;        // device
+  int32_t n_groups = 0;                   // stretches in use (with pair_head)
+  const int32_t *n_groups_dev = nullptr;  // device: the same number when the host does not know it (the grid is
+                           // then max_waves wavefronts)
   int32_t max_waves;       // wavefronts of the persistent launch (a multiple of 4)
   // The launch covers items [item_first, item_first + item_count) of the list: all of them, or
   // those of one block class.  `pool` then holds the blocks with ids from id_base on, and

@@ -109,11 +109,9 @@ struct AttnArgs {
   float *part_ml;
   const int32_t *block_table, *chunk_prefix;
   const int4 *item_desc;           // [n_items] (sequence, first key, one past last key, flags)
-  const int32_t *group_first;      // [n_groups + 1] first item of each group of the launch (relative to item_first), or
-                                   // NULL: group j is item j
   const int32_t *n_groups_dev;     // NULL, or where the number of groups is to be read (n_groups is then ignored)
-  const PairHead *pair_head;       // NULL, or what every (stretch, KV head) pair starts with: pair p is wavefront p's
-                                   // (then neither n_groups nor group_first is looked at; needs id_base == 0)
+  const PairHead *pair_head;       // what every (stretch, KV head) pair starts with: pair p is wavefront p's; or
+                                   // NULL: group j is item j of the launch
   int32_t n_groups;
   int32_t H, G, R, log2_T, tcap, max_blocks, out_fp32;   // R = H / G
   int32_t gg;                      // KV heads per group inside a slab
@@ -257,9 +255,9 @@ struct Unit {
 // Persistent wavefronts, each with a share of the launch that was fixed before it started.  The host
 // (or the bookkeeping kernel) cuts the launch's keys, all sequences laid end to end, into as many equal
 // stretches as there are wavefronts per KV head; a stretch is a group of consecutive items (the pieces
-// of the sequences it covers: group j = items group_first[j] .. group_first[j + 1] - 1, or just item j
-// when there is no such table), and the wavefront for (group, head), pair p = group * G + head,
-// reduces them one after the other; wavefront w takes the pairs w, w + n_waves, ...  Every wavefront
+// of the sequences it covers), and the wavefront for (group, head), pair p = group * G + head, reduces
+// them one after the other.  (Without stretches every item is a group and wavefront w takes the pairs w,
+// w + n_waves, ...)  Every wavefront
 // streams at the same rate (each is bound by the round trip of its own loads: measured within 1.3 % of
 // each other over all compute units, where wavefronts that keep a load in flight all the time differed
 // by 8 % from XCD to XCD and were no faster on average), so equal shares end together; nothing is drawn
@@ -293,7 +291,6 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(
   const int lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const uint32_t n_waves = gridDim.x * kWavesPerBlock;
-  const const_i32_ptr gf = (const_i32_ptr)(uintptr_t)a.group_first;
   uint32_t pair = blockIdx.x * kWavesPerBlock + wave;    // of the unit N below
   // With a table of heads every (stretch, KV head) pair has a wavefront of its own and its head says what
   // the pair starts with; otherwise pairs are dealt out round robin.  The number of groups is a launch
@@ -346,8 +343,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(
   if (by_head) {
     item = head.item, item_end = head.item + head.count;
   } else {
-    item = gf ? gf[pair / (uint32_t)G] : (int)(pair / (uint32_t)G);
-    item_end = gf ? gf[pair / (uint32_t)G + 1] : item + 1;
+    item = (int)(pair / (uint32_t)G), item_end = item + 1;
   }
   bool has_next = true;                                  // N is a unit (else the wavefront's share is done)
   Unit<PIPE> N, C;                                       // the unit whose first tiles are asked for next; the one being reduced
@@ -380,7 +376,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(
   // makes three or four dependent round trips to the argument segment of them.
   asm volatile("" ::"s"(gridDim.x), "s"(a.gg), "s"(a.st_log2), "s"(a.k_new), "s"(a.v_new), "s"(a.pool_store),
                "s"(a.pool_mirror), "s"(a.out), "s"(a.part_o), "s"(a.part_ml), "s"(a.block_table), "s"(a.item_desc),
-               "s"(a.group_first), "s"(a.log2_T), "s"(a.tcap), "s"(a.max_blocks), "s"(a.out_fp32), "s"(a.item_first),
+               "s"(a.log2_T), "s"(a.tcap), "s"(a.max_blocks), "s"(a.out_fp32), "s"(a.item_first),
                "s"(a.id_base), "s"(a.mirror_shift), "s"(a.mirror_is_tail), "s"(a.scale_log2e));
   float m = kNegBig, l = 0.f;
   floatx4_t o[D / 16];
@@ -488,8 +484,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(
       pair += n_waves;
       has_next = !by_head && pair < n_pairs;             // by head: the wavefront's own stretch is all it has
       if (has_next) {
-        item = gf ? gf[pair / (uint32_t)G] : (int)(pair / (uint32_t)G);
-        item_end = gf ? gf[pair / (uint32_t)G + 1] : item + 1;
+        item = (int)(pair / (uint32_t)G), item_end = item + 1;
       }
     }
     if (has_next) {
@@ -678,10 +673,9 @@ AttnArgs make_args(const AttnLaunch &a) {
   args.block_table = a.batch.block_table;
   args.chunk_prefix = a.batch.chunk_prefix;
   args.item_desc = a.batch.item_desc;
-  args.group_first = a.group_first;
   args.n_groups_dev = a.n_groups_dev;
-  args.pair_head = a.id_base == 0 ? static_cast<const PairHead *>(a.pair_head) : nullptr;
-  args.n_groups = a.group_first ? a.n_groups : a.item_count;
+  args.pair_head = static_cast<const PairHead *>(a.pair_head);
+  args.n_groups = a.pair_head ? a.n_groups : a.item_count;
   args.H = s.H;
   args.G = s.G;
   args.R = s.H / s.G;
@@ -715,7 +709,9 @@ hipError_t launch_decode_attn(const AttnLaunch &a, hipStream_t stream, hipEvent_
   const int64_t want = ((int64_t)args.n_groups * s.G + kWavesPerBlock - 1) / kWavesPerBlock;
   const int64_t cap = std::max<int64_t>(1, a.max_waves / kWavesPerBlock);
   dim3 grid((unsigned)(a.n_groups_dev ? cap : std::min(want, cap)));
-  if (want > cap) args.pair_head = nullptr;              // heads need a wavefront per (stretch, KV head) pair
+  // (stretches come with a table of heads, which needs a wavefront per (stretch, KV head) pair and a pool that
+  // holds the blocks as the table numbers them)
+  if (a.pair_head && (want > cap || a.id_base != 0 || a.item_first != 0)) return hipErrorInvalidValue;
   hipError_t e;
   if (ev_begin && (e = hipEventRecord(ev_begin, stream)) != hipSuccess) return e;
   if (R < 1 || R > 16 || R * s.G != s.H)
