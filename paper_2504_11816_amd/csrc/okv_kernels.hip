@@ -351,7 +351,8 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(
   TileAddr ta = tile_addr<D>(G, a.gg, a.tcap, a.st_log2, 0);
   Tile<LPT> buf[PIPE];
   uint4 q_next[D / 32];                                  // q of N: the B operand of the score product, lane (quarter, rho) holds
-                                                         // head rho, dims 32 c + 8 quarter .. + 7; columns past the group's heads are zero
+                                                         // head rho, dims 32 c + 8 quarter .. + 7 (columns past the group's heads:
+                                                         // head 0's, zeroed where the unit takes q over)
   if (by_head) {
     // the first unit's first tiles and its q straight from the head, before anything else is set up
 #pragma unroll
@@ -363,12 +364,9 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(
 #pragma unroll
       for (int j = 0; j < LPT; ++j) buf[i].v[j] = vp[j * 64];
     }
+    const uint4 *qp = reinterpret_cast<const uint4 *>(q + ((size_t)head.b * H + (size_t)(head.flags_g >> 8) * R + (rho < R ? rho : 0)) * D + 8 * quarter);
 #pragma unroll
-    for (int c = 0; c < D / 32; ++c) {
-      q_next[c] = make_uint4(0u, 0u, 0u, 0u);
-      if (rho < R)
-        q_next[c] = *reinterpret_cast<const uint4 *>(q + ((size_t)head.b * H + (size_t)(head.flags_g >> 8) * R + rho) * D + 32 * c + 8 * quarter);
-    }
+    for (int c = 0; c < D / 32; ++c) q_next[c] = qp[4 * c];
     __builtin_amdgcn_sched_barrier(0);
   }
   // All the other launch arguments are asked for here, in one batch of scalar loads (with a table of heads:
@@ -402,16 +400,16 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(
       }
     }
     // [A] the next unit's first tiles and its q
-    const TileAddr ta_next = tile_addr<D>(G, a.gg, a.tcap, a.st_log2, N.g);
+    // (with a table of heads a wavefront stays with one KV head: nothing to work out again)
+    const TileAddr ta_next = by_head && live ? ta : tile_addr<D>(G, a.gg, a.tcap, a.st_log2, N.g);
     if (has_next && (live || !by_head)) {
 #pragma unroll
       for (int i = 0; i < PIPE; ++i) load_tile(buf[i], ta_next, min((N.lo >> 4) + i, (N.hi - 1) >> 4), N.blk0[i]);
+      // (lanes past the group's heads read head 0's piece, which is dropped where q is taken over: no branch
+      // around each load)
+      const uint4 *qp = reinterpret_cast<const uint4 *>(q + ((size_t)N.b * H + (size_t)N.g * R + (rho < R ? rho : 0)) * D + 8 * quarter);
 #pragma unroll
-      for (int c = 0; c < D / 32; ++c) {
-        q_next[c] = make_uint4(0u, 0u, 0u, 0u);
-        if (rho < R)
-          q_next[c] = *reinterpret_cast<const uint4 *>(q + ((size_t)N.b * H + (size_t)N.g * R + rho) * D + 32 * c + 8 * quarter);
-      }
+      for (int c = 0; c < D / 32; ++c) q_next[c] = qp[4 * c];
     }
     __builtin_amdgcn_sched_barrier(0);
 
@@ -507,7 +505,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(
     }
     half8_t qb[D / 32];
 #pragma unroll
-    for (int c = 0; c < D / 32; ++c) qb[c] = __builtin_bit_cast(half8_t, q_next[c]);
+    for (int c = 0; c < D / 32; ++c) qb[c] = __builtin_bit_cast(half8_t, rho < R ? q_next[c] : make_uint4(0u, 0u, 0u, 0u));
     m = kNegBig, l = 0.f;
 #pragma unroll
     for (int i = 0; i < D / 16; ++i) o[i] = floatx4_t{0.f, 0.f, 0.f, 0.f};
