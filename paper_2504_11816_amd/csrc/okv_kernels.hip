@@ -554,18 +554,21 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(
 // 64 items are formed by wavefront reductions instead of a chain of dependent loads; the
 // weighted sums then stream the partial rows four items at a time.
 template <int D>
-__global__ __launch_bounds__(64) void attn_merge_kernel(const AttnArgs a) {
+__global__ __launch_bounds__(64) void attn_merge_kernel(const int32_t *chunk_prefix, const float *part_ml, const int32_t B,
+                                                         const int32_t n_cls, const int32_t H, const AttnArgs a) {
+  // (leading parameters: in scalar registers when the wavefront starts, so the first look-ups need no round trip
+  // to the argument segment; most wavefronts of a launch find a sequence in one piece and leave at once)
   constexpr int EPT = D / 64;
   const int b = blockIdx.y, h = blockIdx.x, lane = threadIdx.x;
   float M = kNegBig;
   int total = 0;
-  for (int cls = 0; cls < a.n_cls; ++cls) {
-    const int first = a.chunk_prefix[cls * a.B + b];
-    const int n_chunks = a.chunk_prefix[cls * a.B + b + 1] - first;
+  for (int cls = 0; cls < n_cls; ++cls) {
+    const int first = chunk_prefix[cls * B + b];
+    const int n_chunks = chunk_prefix[cls * B + b + 1] - first;
     total += n_chunks;
     for (int c0 = 0; c0 < n_chunks; c0 += 64) {
       const int c = c0 + lane;
-      float mc = c < n_chunks ? a.part_ml[((size_t)(first + c) * a.H + h) * 2] : kNegBig;
+      float mc = c < n_chunks ? part_ml[((size_t)(first + c) * H + h) * 2] : kNegBig;
 #pragma unroll
       for (int off = 32; off > 0; off >>= 1) mc = fmaxf(mc, __shfl_xor(mc, off));
       M = fmaxf(M, mc);
@@ -575,14 +578,14 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(const AttnArgs a) {
   float L = 0.f, acc[EPT];
 #pragma unroll
   for (int e = 0; e < EPT; ++e) acc[e] = 0.f;
-  for (int cls = 0; cls < a.n_cls; ++cls) {
-    const int first = a.chunk_prefix[cls * a.B + b];
-    const int n_chunks = a.chunk_prefix[cls * a.B + b + 1] - first;
+  for (int cls = 0; cls < n_cls; ++cls) {
+    const int first = chunk_prefix[cls * B + b];
+    const int n_chunks = chunk_prefix[cls * B + b + 1] - first;
     for (int c0 = 0; c0 < n_chunks; c0 += 64) {
       const int c = c0 + lane;
       float w = 0.f, lw = 0.f;
       if (c < n_chunks) {
-        const float2 ml = *reinterpret_cast<const float2 *>(a.part_ml + ((size_t)(first + c) * a.H + h) * 2);
+        const float2 ml = *reinterpret_cast<const float2 *>(part_ml + ((size_t)(first + c) * H + h) * 2);
         w = __builtin_amdgcn_exp2f(ml.x - M);
         lw = ml.y * w;
       }
@@ -597,7 +600,7 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(const AttnArgs a) {
         for (int k = 0; k < 4; ++k)
 #pragma unroll
           for (int e = 0; e < EPT; ++e)
-            x[k][e] = a.part_o[((size_t)(first + c0 + i + k) * a.H + h) * D + lane * EPT + e];
+            x[k][e] = a.part_o[((size_t)(first + c0 + i + k) * H + h) * D + lane * EPT + e];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
           const float wk = __shfl(w, i + k);
@@ -609,12 +612,12 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(const AttnArgs a) {
         const float wk = __shfl(w, i);
 #pragma unroll
         for (int e = 0; e < EPT; ++e)
-          acc[e] += a.part_o[((size_t)(first + c0 + i) * a.H + h) * D + lane * EPT + e] * wk;
+          acc[e] += a.part_o[((size_t)(first + c0 + i) * H + h) * D + lane * EPT + e] * wk;
       }
     }
   }
   const float inv = 1.0f / L;
-  const size_t at = ((size_t)b * a.H + h) * D + lane * EPT;
+  const size_t at = ((size_t)b * H + h) * D + lane * EPT;
 #pragma unroll
   for (int e = 0; e < EPT; ++e) {
     if (a.out_fp32)
@@ -730,9 +733,9 @@ hipError_t launch_merge(const AttnLaunch &a, hipStream_t stream) {
   const AttnArgs args = make_args(a);
   dim3 mgrid(s.H, a.batch.B);
   if (s.D == 128)
-    hipLaunchKernelGGL(attn_merge_kernel<128>, mgrid, dim3(64), 0, stream, args);
+    hipLaunchKernelGGL(attn_merge_kernel<128>, mgrid, dim3(64), 0, stream, args.chunk_prefix, args.part_ml, args.B, args.n_cls, args.H, args);
   else if (s.D == 64)
-    hipLaunchKernelGGL(attn_merge_kernel<64>, mgrid, dim3(64), 0, stream, args);
+    hipLaunchKernelGGL(attn_merge_kernel<64>, mgrid, dim3(64), 0, stream, args.chunk_prefix, args.part_ml, args.B, args.n_cls, args.H, args);
   else
     return hipErrorInvalidValue;
   return hipGetLastError();

@@ -232,7 +232,12 @@ constexpr int vmcnt_only(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >
 // need them: a SIMD holds two of the workgroup's six wavefronts at most); without the hint the compiler aimed
 // at the occupancy the launch bounds allow and capped the kernel at 64.
 template <int MF, int NW>
-__global__ __launch_bounds__((NW + lin_stagers(MF)) * 64) __attribute__((amdgpu_waves_per_eu(1, MF > 8 ? 2 : 4))) void linear_lds_kernel(const LinearArgs a) {
+__global__ __launch_bounds__((NW + lin_stagers(MF)) * 64) __attribute__((amdgpu_waves_per_eu(1, MF > 8 ? 2 : 4))) void linear_lds_kernel(
+    const uint4 *w, const uint4 *x, const int32_t n_kb, const int32_t splits, const int32_t n_in, const int32_t m,
+    const int32_t n_tiles, const LinearArgs a) {
+  // (the parameters in front of `a` are what the first loads need: the build has the leading kernel arguments
+  // arrive in scalar registers with the wavefront, so the weight stream starts without a round trip to the
+  // argument segment)
   constexpr int NS = lin_stagers(MF);
   constexpr int kFastThreads = (NW + NS) * 64, kTileCols = NW * 16;      // kTileCols: output features of a workgroup
   constexpr int C = lin_chunk(MF), LEAD = lin_lead(MF), NBUF = LEAD + 1, PER = C * MF, MINE = PER / NS;
@@ -255,7 +260,7 @@ __global__ __launch_bounds__((NW + lin_stagers(MF)) * 64) __attribute__((amdgpu_
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int group = blockIdx.x, cut = blockIdx.y;
-  const int nk = a.n_kb / a.splits, kb0 = cut * nk, n_chunks = nk / C;
+  const int nk = n_kb / splits, kb0 = cut * nk, n_chunks = nk / C;
   floatx4 acc[MF];
 #pragma unroll
   for (int f = 0; f < MF; ++f) acc[f] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -273,7 +278,7 @@ __global__ __launch_bounds__((NW + lin_stagers(MF)) * 64) __attribute__((amdgpu_
     // there.  An instruction brings whole rows of the chunk (2 x 512 or 4 x 256 contiguous bytes).  (Fetched in
     // the order the matrix core reads -- 16 rows x 64 bytes per instruction -- the same bytes took twice as
     // many half-used cache lines.)
-    const int row_pieces = a.n_in >> 3;
+    const int row_pieces = n_in >> 3;
     const int bank = lane & 15, ql = (lane >> 4) & 1, odd = lane >> 5;
     const int first = wave - NW;                   // this staging wavefront takes instructions first, first + NS, ...
     const uint4 *xg[MINE];
@@ -287,7 +292,7 @@ __global__ __launch_bounds__((NW + lin_stagers(MF)) * 64) __attribute__((amdgpu_
       const int v = C == 4 ? (d & 7) : d;                            // 2 i + q / 2
       const int piece = 4 * (v >> 1) + 2 * (v & 1) + ql;
       const int row = 16 * f + rr;                 // rows past the batch read row 0: they only reach result rows that are not stored
-      xg[k] = a.x + (size_t)(row < a.m ? row : 0) * row_pieces + (size_t)kb0 * 4 + piece;
+      xg[k] = x + (size_t)(row < m ? row : 0) * row_pieces + (size_t)kb0 * 4 + piece;
     }
     auto stage = [&](int chunk, int buf) {
 #pragma unroll
@@ -319,7 +324,7 @@ __global__ __launch_bounds__((NW + lin_stagers(MF)) * 64) __attribute__((amdgpu_
   } else {
     const int ntile = group * NW + wave;
     // a wavefront past the last tile streams tile 0 (valid memory) and never stores
-    const uint4 *wp = a.w + ((size_t)(ntile < a.n_tiles ? ntile : 0) * a.n_kb + kb0) * 64 + lane;
+    const uint4 *wp = w + ((size_t)(ntile < n_tiles ? ntile : 0) * n_kb + kb0) * 64 + lane;
     // where this lane's operand pieces sit in a chunk (see the layout above): rr = lane % 16, q = lane / 16
     const int rr = lane & 15, q = lane >> 4;
     const int xbase = 64 * (C == 8 ? rr >> 1 : (rr & 7) >> 1) + 16 * (2 * (rr & 1) + (q & 1));
@@ -388,9 +393,9 @@ __global__ __launch_bounds__((NW + lin_stagers(MF)) * 64) __attribute__((amdgpu_
   // a group of eight never straddles a segment and every access below is one aligned 16-byte piece)
   const int n0 = group * kTileCols;
   constexpr int VPR = kTileCols / 8;
-  if (a.splits > 1 || a.to_shares) {                   // this cut's share; a second kernel adds them up
-    float *mine = a.shares + (size_t)cut * a.m * a.n_out;
-    for (int o = tid; o < a.m * VPR; o += kFastThreads) {
+  if (splits > 1 || a.to_shares) {                   // this cut's share; a second kernel adds them up
+    float *mine = a.shares + (size_t)cut * m * a.n_out;
+    for (int o = tid; o < m * VPR; o += kFastThreads) {
       const int mrow = o / VPR, n = n0 + 8 * (o % VPR);
       if (n >= a.n_out) continue;
       const float4 *t = reinterpret_cast<const float4 *>(tile + mrow * kTileCols + 8 * (o % VPR));
@@ -400,7 +405,7 @@ __global__ __launch_bounds__((NW + lin_stagers(MF)) * 64) __attribute__((amdgpu_
     }
     return;
   }
-  for (int o = tid; o < a.m * VPR; o += kFastThreads) {
+  for (int o = tid; o < m * VPR; o += kFastThreads) {
     const int mrow = o / VPR, n = n0 + 8 * (o % VPR);
     if (n >= a.n_out) continue;
     const float4 *t = reinterpret_cast<const float4 *>(tile + mrow * kTileCols + 8 * (o % VPR));
@@ -559,9 +564,11 @@ __global__ __launch_bounds__(kLnMaxThreads) void layernorm_kernel(const uint4 *x
 // the row whenever a product feeds a layer norm (output projection -> second norm, feed-forward
 // -> the next layer's first norm).
 template <int PPT>
-__global__ __launch_bounds__(kLnMaxThreads) void reduce_layernorm_kernel(const LinearArgs a) {
+__global__ __launch_bounds__(kLnMaxThreads) void reduce_layernorm_kernel(const float *shares, const int32_t n_out, const int32_t splits,
+                                                                           const int32_t m, const LinearArgs a) {
+  // (leading parameters: in scalar registers when the wavefront starts, so the shares are asked for at once)
   __shared__ float scratch[kLnMaxThreads / 64];
-  const int h = a.n_out, pieces = h >> 3, mrow = blockIdx.x;
+  const int h = n_out, pieces = h >> 3, mrow = blockIdx.x;
   float v[PPT][8];
   float s = 0.f;
 #pragma unroll
@@ -571,17 +578,17 @@ __global__ __launch_bounds__(kLnMaxThreads) void reduce_layernorm_kernel(const L
       float acc[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e) acc[e] = 0.f;
-      for (int s2 = 0; s2 < a.splits; s2 += 4) {             // four cuts at a time, loads independent of one another
+      for (int s2 = 0; s2 < splits; s2 += 4) {             // four cuts at a time, loads independent of one another
         float4 lo[4], hi[4];
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          const int sj = s2 + j < a.splits ? s2 + j : a.splits - 1;      // past the last cut: the last again, weight 0
-          const float4 *sp = reinterpret_cast<const float4 *>(a.shares + ((size_t)sj * a.m + mrow) * h + p * 8);
+          const int sj = s2 + j < splits ? s2 + j : splits - 1;      // past the last cut: the last again, weight 0
+          const float4 *sp = reinterpret_cast<const float4 *>(shares + ((size_t)sj * m + mrow) * h + p * 8);
           lo[j] = sp[0], hi[j] = sp[1];
         }
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
-          const float w = s2 + j < a.splits ? 1.f : 0.f;
+          const float w = s2 + j < splits ? 1.f : 0.f;
           acc[0] += w * lo[j].x, acc[1] += w * lo[j].y, acc[2] += w * lo[j].z, acc[3] += w * lo[j].w;
           acc[4] += w * hi[j].x, acc[5] += w * hi[j].y, acc[6] += w * hi[j].z, acc[7] += w * hi[j].w;
         }
@@ -639,15 +646,19 @@ template <int MF>
 hipError_t launch_linear_mf(const LinearArgs &args, int n_tiles, bool fast, int fast_waves, hipStream_t stream) {
   if (fast) {
     dim3 grid((n_tiles + fast_waves - 1) / fast_waves, args.splits);
-    if (fast_waves == 3) hipLaunchKernelGGL((linear_lds_kernel<MF, 3>), grid, dim3((3 + lin_stagers(MF)) * 64), 0, stream, args);
-    else hipLaunchKernelGGL((linear_lds_kernel<MF, 4>), grid, dim3((4 + lin_stagers(MF)) * 64), 0, stream, args);
+    if (fast_waves == 3) hipLaunchKernelGGL((linear_lds_kernel<MF, 3>), grid, dim3((3 + lin_stagers(MF)) * 64), 0, stream, args.w, args.x, args.n_kb,
+                                           args.splits, args.n_in, args.m, args.n_tiles, args);
+    else hipLaunchKernelGGL((linear_lds_kernel<MF, 4>), grid, dim3((4 + lin_stagers(MF)) * 64), 0, stream, args.w, args.x, args.n_kb,
+                            args.splits, args.n_in, args.m, args.n_tiles, args);
     if (args.splits > 1 || args.to_shares) {
       hipError_t e = hipGetLastError();
       if (e != hipSuccess) return e;
       if (args.ln_out && (args.n_out >> 3) <= kLnMaxThreads)
-        hipLaunchKernelGGL(reduce_layernorm_kernel<1>, dim3(args.m), dim3(ln_threads(args.n_out)), 0, stream, args);
+        hipLaunchKernelGGL(reduce_layernorm_kernel<1>, dim3(args.m), dim3(ln_threads(args.n_out)), 0, stream, args.shares, args.n_out,
+                           args.splits, args.m, args);
       else if (args.ln_out)
-        hipLaunchKernelGGL(reduce_layernorm_kernel<2>, dim3(args.m), dim3(ln_threads(args.n_out)), 0, stream, args);
+        hipLaunchKernelGGL(reduce_layernorm_kernel<2>, dim3(args.m), dim3(ln_threads(args.n_out)), 0, stream, args.shares, args.n_out,
+                           args.splits, args.m, args);
       else
         hipLaunchKernelGGL(reduce_epilogue_kernel, dim3((args.n_out + 1023) / 1024, args.m), dim3(256), 0, stream, args);
     }
