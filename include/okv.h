@@ -75,7 +75,7 @@ typedef struct okv_ctx okv_ctx;   /* opaque */
 typedef struct okv_config {
   int32_t n_layers;            /* L >= 1                                                     */
   int32_t n_q_heads;           /* H; H % G == 0 and 1 <= H / G <= 16                         */
-  int32_t n_kv_heads;          /* G                                                          */
+  int32_t n_kv_heads;          /* G, at most 4 x the device's compute units (1024 here)      */
   int32_t head_dim;            /* d in {64, 128}                                             */
   int32_t block_tokens;        /* T: 0 = contiguous pools, else a power of two in [16, 1024] */
   int32_t max_batch;           /* largest B okv_set_batch will see                           */

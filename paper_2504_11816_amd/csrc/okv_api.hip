@@ -880,6 +880,10 @@ int okv_create(const okv_config *cfg, okv_ctx **out) {
     const int group = cfg->n_q_heads / cfg->n_kv_heads;
     ctx->max_waves = std::max(1, cus) * (group == 1 ? OKV_WAVES_PER_CU_MHA : group < 8 ? OKV_WAVES_PER_CU_GQA : OKV_WAVES_PER_CU_MFMA);
     ctx->max_groups = std::min(std::max(1, ctx->max_waves / cfg->n_kv_heads), okv::kHeadGroupsMax);
+    if (cfg->n_kv_heads > ctx->max_waves) {              // a stretch needs a wavefront per KV head
+      fail(ctx, OKV_EINVAL, "okv_create: %d KV heads, a launch on this device has %d wavefronts", cfg->n_kv_heads, ctx->max_waves);
+      return bail(OKV_EINVAL);
+    }
   }
   OKV_TRY_CREATE(hipMalloc(&ctx->d_group_first, ((size_t)ctx->max_groups + 1) * sizeof(int32_t)));
   OKV_TRY_CREATE(hipMemset(ctx->d_group_first, 0, ((size_t)ctx->max_groups + 1) * sizeof(int32_t)));
@@ -1975,6 +1979,8 @@ int okv_decode_attn_static(const okv_static_attn *a) {
   unsigned char *base = g_scratch_ptr[dev];
   const int32_t H = a->n_q_heads, G = a->n_kv_heads, D = a->head_dim;
   const int32_t max_waves = g_scratch_cus[dev] * OKV_WAVES_PER_CU_MHA;
+  if (G > max_waves)
+    return fail(nullptr, OKV_EINVAL, "okv_decode_attn_static: %d KV heads, a launch on this device has %d wavefronts", G, max_waves);
   const int32_t max_groups = std::min(std::max(1, max_waves / G), okv::kHeadGroupsMax);
   // the lengths are on the device only: room for the most items any lengths can give (one per
   // sequence and one per stretch)

@@ -357,6 +357,14 @@ def test_error_paths():
         binding.Context(n_layers=1, n_q_heads=4, n_kv_heads=2, head_dim=64, block_tokens=0, max_batch=2,
                         max_ctx=64, dev_pool=[pool], host_pool=[pool], workspace=ws, workspace_bytes=1 << 20)
     assert e.value.code == binding.OKV_EINVAL
+    # more KV heads than a launch has wavefronts (4 per compute unit): a stretch of keys could not have one each
+    with pytest.raises(binding.OkvError) as e:
+        heads = 4 * torch.cuda.get_device_properties(0).multi_processor_count + 64
+        ws = torch.empty(64 << 20, dtype=torch.uint8, device="cuda")
+        pool = torch.empty(2 * 2 * heads * 16 * 64, dtype=torch.float16, device="cuda")
+        binding.Context(n_layers=1, n_q_heads=heads, n_kv_heads=heads, head_dim=64, block_tokens=0, max_batch=2,
+                        max_ctx=16, dev_pool=[pool], host_pool=[None], workspace=ws, workspace_bytes=64 << 20)
+    assert e.value.code == binding.OKV_EINVAL and "KV heads" in str(e.value)
 
 
 def test_probe_kernels_and_link_measurement():
