@@ -499,6 +499,18 @@ int okv_get_ctx_lens(okv_ctx *ctx, int32_t *out);
 int okv_worklist(okv_ctx *ctx, int32_t from_device, int32_t *items, int64_t max_items,
                  int64_t *n_items);
 
+/* With equal stretches (no split size fixed), what the wavefronts of a launch start from: one record of
+ * eight int32 per (stretch, KV head) pair, pair = stretch * G + head, as the bookkeeping kernel of the last
+ * okv_step_begin / okv_set_batch wrote them on the device (synchronous copy):
+ *   [0] the stretch's first item (index into okv_worklist's list)   [1] items of the stretch
+ *   [2] that item's sequence   [3] its first key   [4] one past its last key
+ *   [5] bit 0: the item ends its sequence, bit 1: it is the whole sequence; the KV head in the bits from 8 up
+ *   [6], [7] where the head's K rows of the item's first and second 16-key tile begin in a layer's pool, in
+ *            units of 16 * head_dim elements (the second clamped to the item's last tile)
+ *   records  HOST int32 [max_records][8];  n_records HOST out (stretches in use * G).
+ * OKV_ESTATE when the work list is cut otherwise (a fixed split size, block classes). */
+int okv_pair_heads(okv_ctx *ctx, int32_t *records, int64_t max_records, int64_t *n_records);
+
 /* Where each class starts in that list: class_first[c] .. class_first[c + 1] are the
  * items of class c; *n_classes receives the number of classes (1 without
  * block-granular offload).  from_device = 1 reads the prefix the kernels use.

@@ -20,7 +20,7 @@ EXPORTS = [
     "okv_plan_block_split", "okv_schedule_trace", "okv_create", "okv_destroy", "okv_last_error", "okv_set_batch",
     "okv_step_begin", "okv_step_end", "okv_step_abort", "okv_flush_tails", "kv_append", "decode_attn", "okv_decode_step", "okv_synchronize",
     "okv_set_split_tokens", "okv_get_split_tokens", "okv_get_ctx_lens", "okv_worklist",
-    "okv_worklist_classes", "okv_prefill_begin", "kv_append_bulk", "okv_prefill_release", "okv_prefill_end", "okv_prefill_plan",
+    "okv_worklist_classes", "okv_pair_heads", "okv_prefill_begin", "kv_append_bulk", "okv_prefill_release", "okv_prefill_end", "okv_prefill_plan",
     "okv_measure_d2h",
     "okv_profile_enable", "okv_profile_read", "okv_measure_h2d", "okv_time_copies", "okv_probe_copy",
     "okv_probe_read", "okv_equal_stretches", "okv_decode_attn_static",
@@ -98,6 +98,7 @@ def lib():
             "okv_tail_plan": (ctypes.c_int, [I32, P, I32, I32, P, P, I64, I64, I32, P, P]),
             "okv_plan_block_split": (ctypes.c_int, [I64, I64, I64, ctypes.POINTER(I64), ctypes.POINTER(I64)]),
             "okv_worklist_classes": (ctypes.c_int, [P, I32, P, I32, ctypes.POINTER(I32)]),
+            "okv_pair_heads": (ctypes.c_int, [P, P, I64, ctypes.POINTER(I64)]),
             "kv_offload_plan": (ctypes.c_int, [I32, I64, I64, P, ctypes.POINTER(I32)]),
             "okv_plan_from_bytes": (ctypes.c_int, [I32, I64, I64, P, ctypes.POINTER(I32), ctypes.POINTER(I32)]),
             "okv_schedule_trace": (ctypes.c_int, [I32, P, P, I32, I32, P, I64, ctypes.POINTER(I64)]),
@@ -502,6 +503,13 @@ class Context:
         n = ctypes.c_int32(0)
         self._c(lib().okv_worklist_classes(self._h, 1 if from_device else 0, _ptr(first), max_classes, ctypes.byref(n)))
         return first[:n.value + 1].copy()
+
+    def okv_pair_heads(self, max_records=1 << 16):
+        """int32 [stretches in use * G][8]: what the wavefronts of a launch start from (okv_pair_heads)."""
+        rec = np.zeros((max_records, 8), dtype=np.int32)
+        n = ctypes.c_int64(0)
+        self._c(lib().okv_pair_heads(self._h, _ptr(rec), max_records, ctypes.byref(n)))
+        return rec[:n.value].copy()
 
     def okv_time_copies(self, as_pipelined=False, n_steps=1):
         """ms per step of the copy half alone (back to back, or issued as the pipeline issues it)."""

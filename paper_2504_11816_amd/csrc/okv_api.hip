@@ -1513,6 +1513,18 @@ int okv_worklist(okv_ctx *ctx, int32_t from_device, int32_t *items, int64_t max_
   return OKV_OK;
 }
 
+int okv_pair_heads(okv_ctx *ctx, int32_t *records, int64_t max_records, int64_t *n_records) {
+  if (!ctx || !records || !n_records) return fail(ctx, OKV_EINVAL, "NULL argument");
+  if (!ctx->batch_set) return fail(ctx, OKV_ESTATE, "no batch set");
+  if (!ctx->spans) return fail(ctx, OKV_ESTATE, "okv_pair_heads: the work list is not cut into equal stretches");
+  const int64_t n = std::min<int64_t>((int64_t)ctx->n_groups * ctx->shape.G, max_pairs(ctx->max_waves));
+  *n_records = n;
+  if (n > max_records) return fail(ctx, OKV_ENOSPC, "okv_pair_heads: %lld records", (long long)n);
+  OKV_HIP(ctx, hipStreamSynchronize(ctx->compute));
+  OKV_HIP(ctx, hipMemcpy(records, ctx->d_pair_head, (size_t)n * okv::kPairHeadBytes, hipMemcpyDeviceToHost));
+  return OKV_OK;
+}
+
 int okv_worklist_classes(okv_ctx *ctx, int32_t from_device, int32_t *class_first, int32_t max_classes, int32_t *n_classes) {
   if (!ctx || !class_first || !n_classes) return fail(ctx, OKV_EINVAL, "NULL argument");
   if (!ctx->batch_set) return fail(ctx, OKV_ESTATE, "no batch set");

@@ -222,6 +222,9 @@ def test_worklist_on_device_matches_host_and_oracle():
     np.testing.assert_array_equal(st.ctx.okv_get_ctx_lens(), ctx + 1)
     dev = st.ctx.okv_worklist(from_device=True)
     np.testing.assert_array_equal(dev, np.array(worklist.expected_items(ctx + 1, 100), dtype=np.int32))
+    with pytest.raises(binding.OkvError) as e:            # a fixed split size has no stretches, hence no such table
+        st.ctx.okv_pair_heads()
+    assert e.value.code == binding.OKV_ESTATE
     st.close()
 
 
@@ -239,6 +242,22 @@ def test_equal_stretches_on_the_device_and_every_output(H, G, d, T, B, lo, hi):
     np.testing.assert_array_equal(st.ctx.okv_worklist(from_device=True), np.array(want, dtype=np.int32))
     np.testing.assert_array_equal(st.ctx.okv_worklist(from_device=False), np.array(want, dtype=np.int32))
     assert worklist.check_tiling(want, ctx)
+    # what every wavefront starts from: the first item of its stretch, and where the oracle's layout puts the
+    # K rows of that item's first two tiles for the wavefront's KV head
+    heads = st.ctx.okv_pair_heads()
+    assert heads.shape == ((len(first) - 1) * G, 8)
+    layout = st.layout()
+    for p, rec in enumerate(heads):
+        stretch, g = divmod(p, G)
+        it = first[stretch]
+        b, lo, hi = want[it]
+        assert (rec[0], rec[1], rec[2], rec[3], rec[4]) == (it, first[stretch + 1] - it, b, lo, hi), (p, rec)
+        ends_sequence, whole = hi == ctx[b], (lo == 0 and hi == ctx[b])
+        assert rec[5] == (1 if ends_sequence else 0) | (2 if whole else 0) | (g << 8), (p, rec)
+        last_tile_tok = (hi - 1) // 16 * 16
+        for i in (0, 1):
+            tok = min(lo + 16 * i, last_tile_tok)
+            assert rec[6 + i] * 16 * d == kv_layout.token_row_offset(layout, b, 0, g, tok), (p, i, rec)
     pairs = [(b, h) for b in range(B) for h in range(0, H, max(1, H // 4))]
     run_and_check(st, n_steps=2, seed=405, pairs=pairs)
     want2, _, _ = worklist.expected_items_equal_stretches(ctx + 2, wavefronts_per_kv_head(G))
