@@ -105,24 +105,26 @@ __device__ __forceinline__ floatx4 mfma32(const uint4 a, const uint4 b, floatx4 
 }
 
 template <int MF>
-__global__ __launch_bounds__(kLinWaves * 64) void linear_kernel(const LinearArgs a) {
+__global__ __launch_bounds__(kLinWaves * 64) void linear_kernel(const uint4 *w, const uint4 *x, const int32_t n_kb,
+                                                                   const int32_t n_in, const int32_t m, const LinearArgs a) {
+  // (leading parameters: in scalar registers when the wavefront starts, see linear_lds_kernel)
   constexpr int D = lin_depth<MF>();
   __shared__ floatx4 part[kLinWaves][MF][64];
   const int lane = threadIdx.x & 63;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);      // uniform: the loops below are scalar loops
   const int ntile = blockIdx.x;
-  const int kb0 = (int)((int64_t)wave * a.n_kb / kLinWaves), kb1 = (int)((int64_t)(wave + 1) * a.n_kb / kLinWaves);
+  const int kb0 = (int)((int64_t)wave * n_kb / kLinWaves), kb1 = (int)((int64_t)(wave + 1) * n_kb / kLinWaves);
   const int nk = kb1 - kb0;
-  const uint4 *wp = a.w + ((size_t)ntile * a.n_kb + kb0) * 64 + lane;
+  const uint4 *wp = w + ((size_t)ntile * n_kb + kb0) * 64 + lane;
   // this lane's piece of x for k-block kb and row fragment f: row 16 f + lane % 16, inputs 32 kb + 8 (lane / 16) .. + 7
   const int row = lane & 15, kq = lane >> 4;
-  const int row_pieces = a.n_in >> 3;
+  const int row_pieces = n_in >> 3;
   // Rows past the batch read row 0 instead: a row of x only ever reaches the same row of the
   // result, and those rows are not stored.
   const uint4 *xp[MF];
 #pragma unroll
   for (int f = 0; f < MF; ++f)
-    xp[f] = a.x + (size_t)(f * 16 + row < a.m ? f * 16 + row : 0) * row_pieces + (size_t)kb0 * 4 + kq;
+    xp[f] = x + (size_t)(f * 16 + row < m ? f * 16 + row : 0) * row_pieces + (size_t)kb0 * 4 + kq;
   floatx4 acc[MF];
 #pragma unroll
   for (int f = 0; f < MF; ++f) acc[f] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -189,7 +191,7 @@ __global__ __launch_bounds__(kLinWaves * 64) void linear_kernel(const LinearArgs
   __syncthreads();
   for (int o = threadIdx.x; o < MF * 256; o += kLinWaves * 64) {
     const int mrow = o >> 4, j = o & 15;
-    if (mrow >= a.m) continue;
+    if (mrow >= m) continue;
     const int f = mrow >> 4, src_lane = j + 16 * ((mrow & 15) >> 2), r = mrow & 3;
     float v = 0.f;
 #pragma unroll
@@ -435,23 +437,24 @@ __global__ __launch_bounds__((NW + lin_stagers(MF)) * 64) __attribute__((amdgpu_
 // workgroup per 256 consecutive features of a row.  A launch of its own rather than a hand-over inside
 // the product kernel: a workgroup that reads what other workgroups wrote needs device-wide fences, and on
 // this GPU those write back and invalidate the L2 caches (measured: 75 us instead of 11 for a 32 MiB matrix).
-__global__ __launch_bounds__(256) void reduce_epilogue_kernel(const LinearArgs a) {
+__global__ __launch_bounds__(256) void reduce_epilogue_kernel(const float *shares, const int32_t n_out, const int32_t splits,
+                                                                 const int32_t m, const LinearArgs a) {
   // four neighbouring features per thread; the shares are fetched four cuts at a time with loads that do not
   // depend on one another (a cut past the last one re-reads the last with weight 0), so a thread waits for
   // one round trip, not for one per cut
   const int n = (blockIdx.x * 256 + threadIdx.x) * 4, mrow = blockIdx.y;
-  if (n >= a.n_out) return;
+  if (n >= n_out) return;
   float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int s2 = 0; s2 < a.splits; s2 += 4) {
+  for (int s2 = 0; s2 < splits; s2 += 4) {
     float4 part[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const int sj = s2 + j < a.splits ? s2 + j : a.splits - 1;
-      part[j] = *reinterpret_cast<const float4 *>(a.shares + ((size_t)sj * a.m + mrow) * a.n_out + n);
+      const int sj = s2 + j < splits ? s2 + j : splits - 1;
+      part[j] = *reinterpret_cast<const float4 *>(shares + ((size_t)sj * m + mrow) * n_out + n);
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const float w = s2 + j < a.splits ? 1.f : 0.f;
+      const float w = s2 + j < splits ? 1.f : 0.f;
       v.x += w * part[j].x, v.y += w * part[j].y, v.z += w * part[j].z, v.w += w * part[j].w;
     }
   }
@@ -660,10 +663,12 @@ hipError_t launch_linear_mf(const LinearArgs &args, int n_tiles, bool fast, int 
         hipLaunchKernelGGL(reduce_layernorm_kernel<2>, dim3(args.m), dim3(ln_threads(args.n_out)), 0, stream, args.shares, args.n_out,
                            args.splits, args.m, args);
       else
-        hipLaunchKernelGGL(reduce_epilogue_kernel, dim3((args.n_out + 1023) / 1024, args.m), dim3(256), 0, stream, args);
+        hipLaunchKernelGGL(reduce_epilogue_kernel, dim3((args.n_out + 1023) / 1024, args.m), dim3(256), 0, stream, args.shares,
+                           args.n_out, args.splits, args.m, args);
     }
   } else if constexpr (MF <= OKV_LINEAR_MAX_ROWS / 16) {
-    hipLaunchKernelGGL(linear_kernel<MF>, dim3(n_tiles), dim3(kLinWaves * 64), 0, stream, args);
+    hipLaunchKernelGGL(linear_kernel<MF>, dim3(n_tiles), dim3(kLinWaves * 64), 0, stream, args.w, args.x, args.n_kb, args.n_in,
+                       args.m, args);
   } else {
     return hipErrorInvalidValue;                       // more than OKV_LINEAR_MAX_ROWS rows: the staged kernel only
   }
