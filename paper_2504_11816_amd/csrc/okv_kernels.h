@@ -84,8 +84,8 @@ hipError_t launch_step_advance(int32_t *ctx_lens, int32_t *chunk_prefix, int4 *i
 // that item's descriptor, and where the head's K rows of its first two tiles lie in a pool of the geometry
 // given (the same for every layer).  An attention launch with max_waves wavefronts looks at the records of
 // the pairs below max(max_waves, 4) (and ignores those past the last stretch): geom.max_pairs is at least that.
-// The bookkeeping kernel keeps what opens each stretch in LDS: a table is written only for at most
-// kHeadGroupsMax stretches (callers with more pass NULL, to it and to the attention launches alike).
+// The bookkeeping kernel keeps what opens each stretch in LDS, for at most kHeadGroupsMax stretches: callers
+// keep max_groups at or below that.
 constexpr int kPairHeadBytes = 32, kHeadGroupsMax = 1024;
 struct HeadGeom {
   const int32_t *block_table = nullptr;   // device; NULL: contiguous pools (a sequence's slice is its block)
