@@ -356,13 +356,22 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(
   if (by_head) {
     // the first unit's first tiles and its q straight from the head, before anything else is set up
 #pragma unroll
-    for (int i = 0; i < PIPE; ++i) {
+    for (int i = 0; i < (PIPE < 2 ? PIPE : 2); ++i) {
       const uint4 *kp = reinterpret_cast<const uint4 *>(pool + (size_t)(uint32_t)(i ? head.base1 : head.base0) * (16 * D)) + lane;
       const uint4 *vp = kp + ((size_t)v_tiles * (16 * D) * 2 / 16);
 #pragma unroll
       for (int j = 0; j < LPT; ++j) buf[i].k[j] = kp[j * 64];
 #pragma unroll
       for (int j = 0; j < LPT; ++j) buf[i].v[j] = vp[j * 64];
+    }
+    if (PIPE > 2) {                                      // the record holds two places: the deeper buffers the long way
+      const int g0 = head.flags_g >> 8, last0 = (head.hi - 1) >> 4;
+      const TileAddr ta0 = tile_addr<D>(G, a.gg, a.tcap, a.st_log2, g0);
+#pragma unroll
+      for (int i = 2; i < PIPE; ++i) {
+        const int tile = min((head.lo >> 4) + i, last0);
+        load_tile(buf[i], ta0, tile, blk_of(head.b, tile));
+      }
     }
     const uint4 *qp = reinterpret_cast<const uint4 *>(q + ((size_t)head.b * H + (size_t)(head.flags_g >> 8) * R + (rho < R ? rho : 0)) * D + 8 * quarter);
 #pragma unroll
@@ -627,15 +636,19 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(const int32_t *chunk_pre
   }
 }
 
-// Tiles in flight per wavefront.  What counts is bytes: about 8 KiB per wavefront (one tile at d = 128,
-// two at d = 64) times a thousand wavefronts is where the memory system runs best (6.4-6.6 TB/s); twice
-// that measured 5.9-6.0, half of it (one tile at d = 64) 4.4.
+// Tiles in flight per wavefront.  At d = 128 what counts is bytes: about 8 KiB per wavefront (one tile) times
+// a thousand wavefronts is where the memory system runs best (6.4-6.7 TB/s); twice that measured 5.9-6.1.  At
+// d = 64 a tile is half the bytes for the same chain of waits (LDS round trip, scores, softmax, weighted sum),
+// and that chain, not the memory system, sets the pace: two tiles in flight (8 KiB) run at 5.3-5.4 TB/s
+// (32 x 64 heads, batch 64, context 2048), four at 5.9, six at 6.1, eight at 6.2; launches of a few dozen
+// microseconds gain less and the shortest lose to the longer loop body from six on (11.3 us with two, 11.7
+// with four, 12.6 with six, 13.9 with eight): four.
 #ifndef OKV_PIPE_MULT
 #define OKV_PIPE_MULT 1
 #endif
 template <int D>
 constexpr int base_depth() {
-  return (D == 64 ? 2 : 1) * OKV_PIPE_MULT;
+  return (D == 64 ? 4 : 1) * OKV_PIPE_MULT;
 }
 
 template <int D, bool PAGED, bool HEADS>
