@@ -8,9 +8,9 @@
 //     all H/G query heads that share the KV head, so K/V is read once per group;
 //   * a K or V tile of 16 tokens is one contiguous run of 16*d*2 bytes; every
 //     load instruction moves 16 bytes per lane, 1 KiB per wavefront;
-//   * tiles are loaded PIPE deep ahead of their use into registers, about 8 KiB in
-//     flight per wavefront, one wavefront per SIMD: a thousand such streams is
-//     where the memory system runs best;
+//   * tiles are loaded PIPE deep ahead of their use into registers, 8 KiB in flight
+//     per wavefront at d = 128 (16 KiB at d = 64, see base_depth), one wavefront per
+//     SIMD: a thousand such streams is where the memory system runs best;
 //   * the arithmetic of a tile (scores, online softmax, weighted sum of V rows) runs
 //     on the matrix cores, which takes it off the vector ALU; the tile passes through
 //     LDS that belongs to the wavefront alone to reach the operand layouts;
