@@ -804,13 +804,38 @@ __global__ __launch_bounds__(kStepThreads) void step_advance_kernel(int32_t *ctx
 // laid end to end, cut into stretches (span_plan), every sequence into the pieces the cuts leave
 // (span_pieces), and the first item of every stretch is noted in group_first.  plan_out receives
 // (number of stretches in use, number of items, tiles per stretch as two halves).
+// Inclusive scan of one value per thread over the workgroup's kStepThreads threads, and the sum of all of them:
+// a shuffle scan inside every wavefront and one hand-over of the wavefronts' sums through LDS (two barriers,
+// where a scan through shared memory needs two per doubling: the kernel runs once per step, in front of every
+// layer's attention, and a single-sequence step is short enough to see the difference).
+__device__ __forceinline__ int64_t block_scan(int64_t v, int64_t *wave_sums, int64_t *total) {
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const int64_t up = __shfl_up(v, off);
+    if (lane >= off) v += up;
+  }
+  if (lane == 63) wave_sums[wave] = v;
+  __syncthreads();
+  int64_t before = 0, all = 0;
+#pragma unroll
+  for (int w = 0; w < kStepThreads / 64; ++w) {
+    const int64_t sw = wave_sums[w];
+    before += w < wave ? sw : 0;
+    all += sw;
+  }
+  __syncthreads();                                       // wave_sums may be written again
+  *total = all;
+  return v + before;
+}
+
 __global__ __launch_bounds__(kStepThreads) void step_advance_spans_kernel(int32_t *ctx_lens, int32_t *chunk_prefix,
                                                                          int4 *item_desc, int32_t *group_first,
                                                                          int32_t *plan_out, int32_t B,
                                                                          int32_t max_groups, int32_t min_span,
                                                                          int32_t inc, PairHead *pair_head,
                                                                          const HeadGeom hg) {
-  __shared__ int64_t part[kStepThreads];
+  __shared__ int64_t wave_sums[kStepThreads / 64];
   // what opens each stretch, for the per-pair records: its first item, that item's descriptor and the block
   // ids of the item's first two tiles (the second clamped to the item's last tile)
   __shared__ int32_t open_item[kHeadGroupsMax + 1];
@@ -827,17 +852,9 @@ __global__ __launch_bounds__(kStepThreads) void step_advance_spans_kernel(int32_
     if (inc) ctx_lens[b] = n;                                  // inc == 0: the lengths are only read
     mine += (n + 15) >> 4;
   }
-  part[tid] = mine;
-  __syncthreads();
-  for (int off = 1; off < kStepThreads; off <<= 1) {           // inclusive scan: tiles up to and including this thread's
-    const int64_t add = tid >= off ? part[tid - off] : 0;
-    __syncthreads();
-    part[tid] += add;
-    __syncthreads();
-  }
-  const int64_t tile_first = part[tid] - mine;
-  const SpanPlan plan = span_plan(part[kStepThreads - 1], max_groups, min_span);
-  __syncthreads();
+  int64_t total_tiles;
+  const int64_t tile_first = block_scan(mine, wave_sums, &total_tiles) - mine;   // tiles before this thread's sequences
+  const SpanPlan plan = span_plan(total_tiles, max_groups, min_span);
   int64_t items_mine = 0, first = tile_first;
   for (int b = b0; b < b1; ++b) {
     const int64_t tiles = (ctx_lens[b] + 15) >> 4;
@@ -845,15 +862,8 @@ __global__ __launch_bounds__(kStepThreads) void step_advance_spans_kernel(int32_
     items_mine += span_pieces(first, tiles, plan.span, &k0);
     first += tiles;
   }
-  part[tid] = items_mine;
-  __syncthreads();
-  for (int off = 1; off < kStepThreads; off <<= 1) {
-    const int64_t add = tid >= off ? part[tid - off] : 0;
-    __syncthreads();
-    part[tid] += add;
-    __syncthreads();
-  }
-  int32_t at = (int32_t)(part[tid] - items_mine);
+  int64_t total_items;
+  int32_t at = (int32_t)(block_scan(items_mine, wave_sums, &total_items) - items_mine);
   first = tile_first;
   for (int b = b0; b < b1; ++b) {
     chunk_prefix[b] = at;
@@ -886,8 +896,8 @@ __global__ __launch_bounds__(kStepThreads) void step_advance_spans_kernel(int32_
     first += tiles;
   }
   if (tid == kStepThreads - 1) {
-    group_first[plan.n_groups] = (int32_t)part[tid];
-    if (pair_head && plan.n_groups <= kHeadGroupsMax) open_item[plan.n_groups] = (int32_t)part[tid];
+    group_first[plan.n_groups] = (int32_t)total_items;
+    if (pair_head && plan.n_groups <= kHeadGroupsMax) open_item[plan.n_groups] = (int32_t)total_items;
   }
   if (pair_head) {
     // One record per (stretch, KV head) pair: the stretch's first item and where that head's rows of the
@@ -920,7 +930,7 @@ __global__ __launch_bounds__(kStepThreads) void step_advance_spans_kernel(int32_
     }
   }
   if (tid == kStepThreads - 1) {
-    const int32_t n_items = (int32_t)part[tid];
+    const int32_t n_items = (int32_t)total_items;
     chunk_prefix[B] = n_items;
     plan_out[0] = plan.n_groups;
     plan_out[1] = n_items;
