@@ -760,50 +760,6 @@ namespace {
 
 constexpr int kStepThreads = 256;
 
-__global__ __launch_bounds__(kStepThreads) void step_advance_kernel(int32_t *ctx_lens,
-                                                                   int32_t *chunk_prefix,
-                                                                   int4 *item_desc, int32_t B,
-                                                                   int32_t S, int32_t inc) {
-  __shared__ int32_t part[kStepThreads];
-  const int tid = threadIdx.x;
-  const int per = (B + kStepThreads - 1) / kStepThreads;     // consecutive sequences per thread
-  const int b0 = tid * per, b1 = min(B, b0 + per);
-  int32_t mine = 0;
-  for (int b = b0; b < b1; ++b) {
-    const int32_t n = ctx_lens[b] + inc;
-    ctx_lens[b] = n;
-    int32_t cnt, sz;
-    seq_chunks(n, S, &cnt, &sz);
-    mine += cnt;
-  }
-  part[tid] = mine;
-  __syncthreads();
-  for (int off = 1; off < kStepThreads; off <<= 1) {           // inclusive scan of the thread sums
-    int32_t add = tid >= off ? part[tid - off] : 0;
-    __syncthreads();
-    part[tid] += add;
-    __syncthreads();
-  }
-  int32_t at = part[tid] - mine;                               // exclusive prefix of this thread
-  for (int b = b0; b < b1; ++b) {
-    chunk_prefix[b] = at;
-    const int32_t n = ctx_lens[b];
-    int32_t cnt, sz;
-    seq_chunks(n, S, &cnt, &sz);
-    for (int32_t c = 0; c < cnt; ++c) {
-      const ItemRange r = chunk_range(b, c, sz, n);
-      const int32_t flags = (c == cnt - 1 ? kItemLast : 0) | (cnt == 1 ? kItemWhole : 0);
-      item_desc[at + c] = make_int4(r.b, r.lo, r.hi, flags);
-    }
-    at += cnt;
-  }
-  if (tid == kStepThreads - 1) chunk_prefix[B] = part[tid];
-}
-
-// The bookkeeping for equal stretches: lengths advance, the tiles of all sequences are counted and
-// laid end to end, cut into stretches (span_plan), every sequence into the pieces the cuts leave
-// (span_pieces), and the first item of every stretch is noted in group_first.  plan_out receives
-// (number of stretches in use, number of items, tiles per stretch as two halves).
 // Inclusive scan of one value per thread over the workgroup's kStepThreads threads, and the sum of all of them:
 // a shuffle scan inside every wavefront and one hand-over of the wavefronts' sums through LDS (two barriers,
 // where a scan through shared memory needs two per doubling: the kernel runs once per step, in front of every
@@ -829,6 +785,43 @@ __device__ __forceinline__ int64_t block_scan(int64_t v, int64_t *wave_sums, int
   return v + before;
 }
 
+__global__ __launch_bounds__(kStepThreads) void step_advance_kernel(int32_t *ctx_lens,
+                                                                   int32_t *chunk_prefix,
+                                                                   int4 *item_desc, int32_t B,
+                                                                   int32_t S, int32_t inc) {
+  __shared__ int64_t wave_sums[kStepThreads / 64];
+  const int tid = threadIdx.x;
+  const int per = (B + kStepThreads - 1) / kStepThreads;     // consecutive sequences per thread
+  const int b0 = tid * per, b1 = min(B, b0 + per);
+  int32_t mine = 0;
+  for (int b = b0; b < b1; ++b) {
+    const int32_t n = ctx_lens[b] + inc;
+    ctx_lens[b] = n;
+    int32_t cnt, sz;
+    seq_chunks(n, S, &cnt, &sz);
+    mine += cnt;
+  }
+  int64_t total_items;
+  int32_t at = (int32_t)(block_scan(mine, wave_sums, &total_items) - mine);   // exclusive prefix of this thread
+  for (int b = b0; b < b1; ++b) {
+    chunk_prefix[b] = at;
+    const int32_t n = ctx_lens[b];
+    int32_t cnt, sz;
+    seq_chunks(n, S, &cnt, &sz);
+    for (int32_t c = 0; c < cnt; ++c) {
+      const ItemRange r = chunk_range(b, c, sz, n);
+      const int32_t flags = (c == cnt - 1 ? kItemLast : 0) | (cnt == 1 ? kItemWhole : 0);
+      item_desc[at + c] = make_int4(r.b, r.lo, r.hi, flags);
+    }
+    at += cnt;
+  }
+  if (tid == kStepThreads - 1) chunk_prefix[B] = (int32_t)total_items;
+}
+
+// The bookkeeping for equal stretches: lengths advance, the tiles of all sequences are counted and
+// laid end to end, cut into stretches (span_plan), every sequence into the pieces the cuts leave
+// (span_pieces), and the first item of every stretch is noted in group_first.  plan_out receives
+// (number of stretches in use, number of items, tiles per stretch as two halves).
 __global__ __launch_bounds__(kStepThreads) void step_advance_spans_kernel(int32_t *ctx_lens, int32_t *chunk_prefix,
                                                                          int4 *item_desc, int32_t *group_first,
                                                                          int32_t *plan_out, int32_t B,
