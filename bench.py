@@ -38,7 +38,7 @@ PCIE5_X16_GBPS = 64.0       # nominal, one direction
 # has changed since, `traffic` is reported as null.
 TRAFFIC_RECORD = {
     "workload": "cfg2",
-    "kernel_sha256": "dfe2abc84823b86dcfc691c5e9e242570e2d60b831382c58bdba2af72b4f27a0",
+    "kernel_sha256": "3a1a8b5917f21676835dc02e29303cf0ea5368b5129be17c03b0acdbd66f3aaa",
     "fetch_kib": 199121.0, "fetch_scale": 2.0000, "algorithmic_bytes": 402915328,   # context 737..800
     "write_kib": 768.0, "write_scale": 1.0000,
 }
