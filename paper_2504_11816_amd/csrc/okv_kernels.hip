@@ -156,6 +156,11 @@ template <int D>
 constexpr int lds_tile_bytes() {
   return 16 * lds_row_bytes<D>();
 }
+// 16-key tiles that are reduced together: two at d = 64 (see tile_update_pair), one at d = 128
+template <int D>
+constexpr int lds_tiles() {
+  return D == 64 ? 2 : 1;
+}
 
 // A tile on its way from the load registers (row-major, as loaded) into the wavefront's LDS.  masked
 // (wavefront-uniform; only an item's last tiles need it): V rows of tokens outside [lo, hi) are stored
@@ -242,6 +247,71 @@ __device__ __forceinline__ void tile_update_mfma(const half8_t (&qb)[D / 32], fl
   }
 }
 
+// Two 16-key tiles at once (d = 64, where a tile is half the bytes of one at d = 128 behind the same chain of
+// waits): the tiles sit in rows 0-15 and 16-31 of ks / vs; one maximum, one rescaling and one pass of weights
+// for the 32 keys, and the weighted sum as 16 x 16 x 32 products.  Lane (quarter, rho) holds, of head rho, the
+// scores of keys 4 quarter .. + 3 of either tile; taken in that order (first tile's four, then the second's) they
+// are the eight key slots 8 quarter .. + 7 of the B operand of the second product, and its A operand, V^T,
+// is gathered from the same rows in the same order.  valid1 = 0: the second tile is not the item's (its
+// buffer holds the last tile once more): every key of it is masked out.
+__device__ __forceinline__ void tile_update_pair(const half8_t (&qb)[2], float &m, float &l, floatx4_t (&o)[4],
+                                                 const char *ks, const char *vs, const int lane, const int tok_tile,
+                                                 const bool valid1, const int lo, const int hi, const float scale,
+                                                 const bool masked) {
+  constexpr int D = 64, S = lds_row_bytes<D>();
+  const int quarter = lane >> 4, rho = lane & 15;
+  float s[8];
+#pragma unroll
+  for (int h = 0; h < 2; ++h) {
+    floatx4_t acc = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int c = 0; c < D / 32; ++c) {
+      const half8_t ka = *reinterpret_cast<const half8_t *>(ks + (16 * h + rho) * S + c * 64 + quarter * 16);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_f16(ka, qb[c], acc, 0, 0, 0);
+    }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int tok = tok_tile + 16 * h + 4 * quarter + r;
+      const bool in = (!masked || (tok >= lo && tok < hi)) && (h == 0 || valid1);
+      s[4 * h + r] = in ? acc[r] * scale : -__builtin_inff();
+    }
+  }
+  float mx = fmaxf(fmaxf(fmaxf(s[0], s[1]), fmaxf(s[2], s[3])), fmaxf(fmaxf(s[4], s[5]), fmaxf(s[6], s[7])));
+  mx = fmaxf(mx, __shfl_xor(mx, 16));
+  mx = fmaxf(mx, __shfl_xor(mx, 32));
+  const float m_new = fmaxf(m, mx);
+  if (__any(m_new != m)) {
+    const float alpha = __builtin_amdgcn_exp2f(m - m_new);
+    l *= alpha;
+#pragma unroll
+    for (int i = 0; i < D / 16; ++i) o[i] *= alpha;
+    m = m_new;
+  }
+  float p[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    p[j] = __builtin_amdgcn_exp2f(s[j] - m);
+    l += p[j];
+  }
+  const half8_t pb = {(_Float16)p[0], (_Float16)p[1], (_Float16)p[2], (_Float16)p[3],
+                      (_Float16)p[4], (_Float16)p[5], (_Float16)p[6], (_Float16)p[7]};
+#pragma unroll
+  for (int u = 0; u < D / 32; ++u) {
+    uint32_t w[8];
+#pragma unroll
+    for (int h = 0; h < 2; ++h)
+#pragma unroll
+      for (int e = 0; e < 4; ++e)
+        w[4 * h + e] = *reinterpret_cast<const uint32_t *>(vs + (16 * h + 4 * quarter + e) * S + (16 * u + rho) * 4);
+    const uint4 even = make_uint4(__builtin_amdgcn_perm(w[1], w[0], 0x05040100u), __builtin_amdgcn_perm(w[3], w[2], 0x05040100u),
+                                  __builtin_amdgcn_perm(w[5], w[4], 0x05040100u), __builtin_amdgcn_perm(w[7], w[6], 0x05040100u));
+    const uint4 odd = make_uint4(__builtin_amdgcn_perm(w[1], w[0], 0x07060302u), __builtin_amdgcn_perm(w[3], w[2], 0x07060302u),
+                                 __builtin_amdgcn_perm(w[5], w[4], 0x07060302u), __builtin_amdgcn_perm(w[7], w[6], 0x07060302u));
+    o[2 * u] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, even), pb, o[2 * u], 0, 0, 0);
+    o[2 * u + 1] = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(half8_t, odd), pb, o[2 * u + 1], 0, 0, 0);
+  }
+}
+
 // A work unit as a wavefront sees it: an item (a run of keys of one sequence) for one KV head.  All
 // fields are wavefront-uniform and come through the scalar cache (constant address space: nothing
 // writes the item list or the block table while this kernel runs).
@@ -286,7 +356,7 @@ template <int D, bool PAGED, int PIPE, bool HEADS>
 __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(
     const PairHead *pair_head, const uint16_t *pool, const uint16_t *q, const int32_t *n_groups_dev, const int32_t n_groups,
     const int32_t G, const int32_t H, const int32_t R, const int32_t v_tiles, const AttnArgs a) {
-  __shared__ __attribute__((aligned(16))) char lds_all[kWavesPerBlock][2 * lds_tile_bytes<D>()];
+  __shared__ __attribute__((aligned(16))) char lds_all[kWavesPerBlock][2 * lds_tiles<D>() * lds_tile_bytes<D>()];
   constexpr int LPR = D / 8, RPL = 64 / LPR, LPT = D / 32;
   const int lane = threadIdx.x & 63;
   const uint32_t wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -315,7 +385,7 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(
 
   const int row = lane / LPR, col = lane % LPR;
   const int quarter = lane >> 4, rho = lane & 15;
-  char *ks = lds_all[wave], *vs = ks + lds_tile_bytes<D>();
+  char *ks = lds_all[wave], *vs = ks + lds_tiles<D>() * lds_tile_bytes<D>();
 
   // Block id of a tile: a wavefront-uniform (scalar) load from the block table.  The table is read
   // through the constant address space: the kernel also stores (outputs, appended rows) and without
@@ -534,7 +604,10 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(
       const bool last = t + PIPE >= t1;
 #pragma unroll
       for (int i = 0; i < PIPE; ++i) {
-        if (i == 0 || t + i < t1) {                      // else a second request for the last tile: skipped
+        // at d = 64 two tiles are reduced together: buffer i (even) is staged and waits for buffer i + 1
+        constexpr int PAIR = lds_tiles<D>();
+        char *const ks_i = ks + (i % PAIR) * lds_tile_bytes<D>(), *const vs_i = vs + (i % PAIR) * lds_tile_bytes<D>();
+        if (i - i % PAIR == 0 || t + (i - i % PAIR) < t1) {   // else a second request for the last tile: skipped
           if (last && appending && t + i == (pos >> 4)) {
 #pragma unroll
             for (int j = 0; j < LPT; ++j)
@@ -543,8 +616,12 @@ __global__ __launch_bounds__(kWavesPerBlock * 64) void attn_split_mfma_kernel(
                 buf[i].v[j] = v_row;
               }
           }
-          tile_stage<D>(buf[i], ks, vs, lane, (t + i) << 4, lo, hi, last);
-          tile_update_mfma<D>(qb, m, l, o, ks, vs, lane, (t + i) << 4, lo, hi, a.scale_log2e, last);
+          tile_stage<D>(buf[i], ks_i, vs_i, lane, (t + i) << 4, lo, hi, last);
+          if constexpr (PAIR == 1) {
+            tile_update_mfma<D>(qb, m, l, o, ks, vs, lane, (t + i) << 4, lo, hi, a.scale_log2e, last);
+          } else if (i % PAIR == PAIR - 1) {
+            tile_update_pair(qb, m, l, o, ks, vs, lane, (t + i - 1) << 4, t + i < t1, lo, hi, a.scale_log2e, last);
+          }
         }
         __builtin_amdgcn_sched_barrier(0);    // keep the refill behind the reduce that frees it,
         if (!last) {
@@ -639,10 +716,11 @@ __global__ __launch_bounds__(64) void attn_merge_kernel(const int32_t *chunk_pre
 // Tiles in flight per wavefront.  At d = 128 what counts is bytes: about 8 KiB per wavefront (one tile) times
 // a thousand wavefronts is where the memory system runs best (6.4-6.7 TB/s); twice that measured 5.9-6.1.  At
 // d = 64 a tile is half the bytes for the same chain of waits (LDS round trip, scores, softmax, weighted sum),
-// and that chain, not the memory system, sets the pace: two tiles in flight (8 KiB) run at 5.3-5.4 TB/s
-// (32 x 64 heads, batch 64, context 2048), four at 5.9, six at 6.1, eight at 6.2; launches of a few dozen
-// microseconds gain less and the shortest lose to the longer loop body from six on (11.3 us with two, 11.7
-// with four, 12.6 with six, 13.9 with eight): four.
+// and that chain, not the memory system, sets the pace: with every tile reduced on its own, two tiles in
+// flight (8 KiB) ran at 5.3-5.4 TB/s (32 x 64 heads, batch 64, context 2048), four at 5.9, six at 6.1, eight
+// at 6.2; launches of a few dozen microseconds gained less and the shortest lost to the longer loop body from
+// six on (11.3 us with two, 11.7 with four, 12.6 with six, 13.9 with eight): four, which tile_update_pair
+// reduces two at a time (6.25 TB/s).
 #ifndef OKV_PIPE_MULT
 #define OKV_PIPE_MULT 1
 #endif
