@@ -38,7 +38,7 @@ PCIE5_X16_GBPS = 64.0       # nominal, one direction
 # has changed since, `traffic` is reported as null.
 TRAFFIC_RECORD = {
     "workload": "cfg2",
-    "kernel_sha256": "3a1a8b5917f21676835dc02e29303cf0ea5368b5129be17c03b0acdbd66f3aaa",
+    "kernel_sha256": "5a1747b6fb410b0ef77cd8abb128a8735718c45a69c02285b23bd970a05856b3",
     "fetch_kib": 199121.0, "fetch_scale": 2.0000, "algorithmic_bytes": 402915328,   # context 737..800
     "write_kib": 768.0, "write_scale": 1.0000,
 }
